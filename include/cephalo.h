@@ -1,0 +1,148 @@
+/*
+ * cephalo.h -- C ABI of the MI355X (gfx950) library for one GPU's share of a sharded
+ * data-parallel transformer training step, after "Cephalo: Harnessing Heterogeneous GPU
+ * Clusters for Training Transformer Models" (arXiv 2411.01075).
+ *
+ * The paper decouples what a GPU computes from what it stores:
+ *   - Sec. 3.1 "Compute Partitioning" / Eq. 1: GPU i gets a batch share b_i and scales its
+ *     local gradient by N*b_i/B.
+ *   - Sec. 3.2: the share runs as l micro-batches of m samples, b = l*m, gradients
+ *     accumulated; with layered accumulation every micro-batch passes through a layer
+ *     before the next layer.
+ *   - Sec. 3.1 "Training State Partitioning": GPU i owns a ratio r_i (anything from none to
+ *     all, Sec. 1) of the flat parameter / gradient / Adam-moment buffers of an FSDP unit,
+ *     and only that slice is updated there.  Sec. 3.3: 4+4+8 bytes of state per parameter.
+ *
+ * Conventions common to every call
+ *   - Every pointer marked "device" is GPU memory owned by the caller; the library
+ *     allocates nothing, keeps no state between calls and frees nothing.
+ *   - `stream` is a hipStream_t passed as void* (NULL = the default stream).  Calls only
+ *     enqueue work on it and return; there is no hidden synchronisation.
+ *   - Return value: 0 on success, a negative CEPHALO_E* code otherwise.  Arguments are
+ *     validated on the host before anything is launched, so an error return means no
+ *     kernel ran.  cephalo_last_error() gives a text for the calling thread's last error.
+ *   - Device base pointers must be 16-byte aligned.
+ *
+ * Flat layout of one layer (an FSDP unit), element indices, no padding, matrices
+ * [out_features, in_features] row-major (y = x W^T + b):
+ *     ln1.gamma[H] ln1.beta[H] W_qkv[3H,H] b_qkv[3H] W_o[H,H] b_o[H]
+ *     ln2.gamma[H] ln2.beta[H] W_fc1[F,H] b_fc1[F] W_fc2[H,F] b_fc2[H]
+ * W_qkv rows [0,H) produce Q, [H,2H) K, [2H,3H) V; head a owns columns [a*d,(a+1)*d).
+ * The paper fixes no order inside a unit; this one is the library's contract.
+ */
+#ifndef CEPHALO_H
+#define CEPHALO_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+#define CEPHALO_OK            0
+#define CEPHALO_EINVAL       (-1)  /* bad size, range, null or misaligned pointer          */
+#define CEPHALO_EUNSUPPORTED (-2)  /* a shape the kernels do not cover (e.g. head dim)      */
+#define CEPHALO_EWORKSPACE   (-3)  /* save / scratch buffer smaller than the query reports  */
+#define CEPHALO_EHIP         (-4)  /* a HIP launch reported an error                        */
+
+#define CEPHALO_F32   0  /* activations, parameters and arithmetic in fp32                  */
+#define CEPHALO_BF16  1  /* bf16 activations and parameter copy, fp32 accumulation, fp32
+                            statistics / softmax / GELU / gradients                         */
+
+/* A transformer layer: pre-LayerNorm residual blocks, exact (erf) GELU, biases on every
+ * projection, scores scaled by 1/sqrt(d), optional causal mask, no dropout (Sec. 2.1 names
+ * only "self-attention and feed-forward"; this form is the library's reading). */
+typedef struct cephalo_layer_desc {
+  int32_t hidden;   /* H, a multiple of heads; head dim d = H/heads must be 64 or 128 in BF16 mode */
+  int32_t heads;    /* A */
+  int32_t mlp;      /* F */
+  int32_t seq;      /* S, tokens per sample */
+  int32_t causal;   /* 0 or 1 */
+  int32_t dtype;    /* CEPHALO_F32 or CEPHALO_BF16 */
+  float   ln_eps;   /* added to the biased variance inside the square root */
+} cephalo_layer_desc;
+
+/* Text of the calling thread's most recent error ("" if none). Host pointer, library-owned. */
+const char* cephalo_last_error(void);
+
+/* Number of elements P of one layer's flat buffer, 4H^2 + 2HF + 9H + F; negative on a bad desc. */
+int64_t cephalo_layer_param_count(const cephalo_layer_desc* desc);
+
+/* Element offset of each of the 12 tensors inside the flat buffer, in layout order, written
+ * to host array offsets[12]. */
+int cephalo_layer_param_offsets(const cephalo_layer_desc* desc, int64_t* offsets);
+
+/* Bytes of the per-micro-batch activation save area (written by layer_fwd, read by
+ * layer_bwd) and of the scratch area, for micro-batch size m.  Neither depends on the
+ * number of micro-batches l: compute memory is a function of m alone (Sec. 3.3, memory
+ * utilization model).  Host pointers out. */
+int cephalo_layer_workspace_bytes(const cephalo_layer_desc* desc, int32_t micro_batch,
+                                  size_t* save_bytes, size_t* scratch_bytes);
+
+/* Forward of one layer on one micro-batch of m samples (Sec. 3.2; the step timed as T_f(m)
+ * in Sec. 3.3).
+ *   flat_param  device, [P] in the compute dtype (fp32, or the bf16 copy of the fp32 master)
+ *   x, y        device, [m, S, H] in the compute dtype; y may not alias x
+ *   save        device, save_bytes; holds what the backward needs (x itself is not copied:
+ *               the caller keeps x alive and passes it to layer_bwd)
+ *   scratch     device, scratch_bytes; contents undefined afterwards */
+int cephalo_layer_fwd(const cephalo_layer_desc* desc, const void* flat_param,
+                      const void* x, void* y, int32_t micro_batch,
+                      void* save, size_t save_bytes,
+                      void* scratch, size_t scratch_bytes, void* stream);
+
+/* Backward of the same micro-batch (T_b(m) in Sec. 3.3) with the gradient accumulation of
+ * Sec. 3.2 folded in:   flat_grad <- (accumulate ? flat_grad : 0) + grad_scale * g_j
+ * where g_j is this micro-batch's parameter gradient summed over its tokens and grad_scale
+ * is the caller's factor (Eq. 1's N*b_i/B and any 1/b_i mean).  Every element of flat_grad
+ * is written by exactly one thread block in a fixed order, so results are reproducible.
+ *   x           device, the forward input of this micro-batch
+ *   dy, dx      device, [m, S, H] compute dtype; dx may not alias dy
+ *   flat_grad   device, [P] fp32 */
+int cephalo_layer_bwd(const cephalo_layer_desc* desc, const void* flat_param,
+                      const void* x, const void* dy, void* dx, int32_t micro_batch,
+                      const void* save, size_t save_bytes,
+                      float* flat_grad, float grad_scale, int32_t accumulate,
+                      void* scratch, size_t scratch_bytes, void* stream);
+
+/* Whole share of one layer, micro-batches in order j = 0..l-1 (Sec. 3.2, b = l*m): forward
+ * of every micro-batch, then backward of every micro-batch with accumulation into
+ * flat_grad (first micro-batch overwrites).  Fails with CEPHALO_EINVAL unless
+ * batch_share = l * micro_batch for a positive integer l.
+ *   x, y, dy, dx  device, [b, S, H];  save: l * save_bytes;  scratch: scratch_bytes */
+int cephalo_share_layer_step(const cephalo_layer_desc* desc, const void* flat_param,
+                             const void* x, void* y, const void* dy, void* dx,
+                             int32_t batch_share, int32_t micro_batch,
+                             void* save, size_t save_bytes_total,
+                             float* flat_grad, float grad_scale,
+                             void* scratch, size_t scratch_bytes, void* stream);
+
+/* acc[i] <- acc[i] + scale * g[i], i in [0, n): gradient accumulation across micro-batches
+ * (Sec. 3.2) as a stand-alone pass.  acc, g device fp32, n >= 0. */
+int cephalo_grad_accum(float* acc, const float* g, float scale, int64_t n, void* stream);
+
+/* Adam on this GPU's slice [offset, offset+len) of the flat training state (Sec. 3.1
+ * "Training State Partitioning"; fp32 parameter, gradient and two moments, Sec. 3.3).
+ *   m <- beta1 m + (1-beta1) g;  v <- beta2 v + (1-beta2) g^2
+ *   p <- p - lr * (m / (1-beta1^step)) / (sqrt(v / (1-beta2^step)) + eps)
+ * p, g, m, v are device pointers to element 0 of the flat buffers and are indexed globally;
+ * nothing outside the slice is read or written.  p_lowp, if not NULL, is a device bf16 [P]
+ * buffer whose slice receives the rounded (nearest-even) new parameters for the next
+ * step's compute.  len = 0 is a valid no-op; offset = 0, len = P is the unsharded update.
+ * step is 1-based.  Each element's arithmetic is the same instruction sequence wherever
+ * the slice starts, so updates over any partition of [0,P) concatenate to the unsharded
+ * update bit for bit. */
+int cephalo_shard_adam(float* p, const float* g, float* m, float* v, void* p_lowp,
+                       int64_t P, int64_t offset, int64_t len,
+                       float lr, float beta1, float beta2, float eps, int64_t step,
+                       void* stream);
+
+/* dst[i] <- bf16(src[i]) (nearest-even), i in [0, n): makes the compute copy of fp32 master
+ * parameters (the mixed-precision workloads' rule; the paper itself trains in fp32). */
+int cephalo_cast_bf16(void* dst_bf16, const float* src, int64_t n, void* stream);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* CEPHALO_H */

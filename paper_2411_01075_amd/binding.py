@@ -1,0 +1,152 @@
+"""ctypes binding of libcephalo.so: same names as include/cephalo.h, argument marshalling only.
+
+Tensors are torch CUDA(HIP) tensors used as plain device memory; every step of the path runs
+in the library's kernels.  There is no fallback: a missing library raises at first use.
+"""
+import ctypes
+import os
+
+import torch
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(_HERE, "libcephalo.so")
+
+F32 = 0
+BF16 = 1
+
+_lib = None
+
+
+class CephaloError(RuntimeError):
+    pass
+
+
+class LayerDesc(ctypes.Structure):
+    _fields_ = [("hidden", ctypes.c_int32), ("heads", ctypes.c_int32), ("mlp", ctypes.c_int32),
+                ("seq", ctypes.c_int32), ("causal", ctypes.c_int32), ("dtype", ctypes.c_int32),
+                ("ln_eps", ctypes.c_float)]
+
+
+def layer_desc(hidden, heads, mlp, seq, causal, dtype, ln_eps=1e-5):
+    return LayerDesc(int(hidden), int(heads), int(mlp), int(seq), int(bool(causal)), int(dtype), float(ln_eps))
+
+
+def desc_from_config(cfg):
+    return layer_desc(cfg.hidden, cfg.heads, cfg.mlp, cfg.seq, cfg.causal, F32 if cfg.dtype == "f32" else BF16)
+
+
+_vp, _i32, _i64, _f32, _sz = ctypes.c_void_p, ctypes.c_int32, ctypes.c_int64, ctypes.c_float, ctypes.c_size_t
+_dp = ctypes.POINTER(LayerDesc)
+
+# name -> (restype, argtypes); must list every symbol include/cephalo.h declares
+SIGNATURES = {
+    "cephalo_last_error": (ctypes.c_char_p, []),
+    "cephalo_layer_param_count": (_i64, [_dp]),
+    "cephalo_layer_param_offsets": (ctypes.c_int, [_dp, ctypes.POINTER(_i64)]),
+    "cephalo_layer_workspace_bytes": (ctypes.c_int, [_dp, _i32, ctypes.POINTER(_sz), ctypes.POINTER(_sz)]),
+    "cephalo_layer_fwd": (ctypes.c_int, [_dp, _vp, _vp, _vp, _i32, _vp, _sz, _vp, _sz, _vp]),
+    "cephalo_layer_bwd": (ctypes.c_int, [_dp, _vp, _vp, _vp, _vp, _i32, _vp, _sz, _vp, _f32, _i32, _vp, _sz, _vp]),
+    "cephalo_share_layer_step": (ctypes.c_int, [_dp, _vp, _vp, _vp, _vp, _vp, _i32, _i32, _vp, _sz, _vp, _f32,
+                                                _vp, _sz, _vp]),
+    "cephalo_grad_accum": (ctypes.c_int, [_vp, _vp, _f32, _i64, _vp]),
+    "cephalo_shard_adam": (ctypes.c_int, [_vp, _vp, _vp, _vp, _vp, _i64, _i64, _i64, _f32, _f32, _f32, _f32, _i64, _vp]),
+    "cephalo_cast_bf16": (ctypes.c_int, [_vp, _vp, _i64, _vp]),
+}
+
+
+def lib():
+    """The loaded library; raises if it has not been built (python -m paper_2411_01075_amd.build)."""
+    global _lib
+    if _lib is None:
+        if not os.path.exists(LIB_PATH):
+            raise CephaloError("libcephalo.so is missing at %s: build it with "
+                               "`python -m paper_2411_01075_amd.build`" % LIB_PATH)
+        L = ctypes.CDLL(LIB_PATH)
+        for name, (res, args) in SIGNATURES.items():
+            fn = getattr(L, name)
+            fn.restype = res
+            fn.argtypes = args
+        _lib = L
+    return _lib
+
+
+def _check(rc):
+    if rc != 0:
+        raise CephaloError("cephalo error %d: %s" % (rc, lib().cephalo_last_error().decode()))
+
+
+def _ptr(t):
+    if t is None:
+        return None
+    if not t.is_cuda:
+        raise CephaloError("expected a device tensor")
+    if not t.is_contiguous():
+        raise CephaloError("expected a contiguous tensor")
+    return t.data_ptr()
+
+
+def _stream(stream):
+    if stream is None:
+        stream = torch.cuda.current_stream()
+    return stream.cuda_stream
+
+
+def cephalo_last_error():
+    return lib().cephalo_last_error().decode()
+
+
+def cephalo_layer_param_count(desc):
+    n = lib().cephalo_layer_param_count(ctypes.byref(desc))
+    if n < 0:
+        _check(int(n))
+    return int(n)
+
+
+def cephalo_layer_param_offsets(desc):
+    out = (_i64 * 12)()
+    _check(lib().cephalo_layer_param_offsets(ctypes.byref(desc), out))
+    return list(out)
+
+
+def cephalo_layer_workspace_bytes(desc, micro_batch):
+    a, b = _sz(0), _sz(0)
+    _check(lib().cephalo_layer_workspace_bytes(ctypes.byref(desc), micro_batch, ctypes.byref(a), ctypes.byref(b)))
+    return a.value, b.value
+
+
+def cephalo_layer_fwd(desc, flat_param, x, y, micro_batch, save, scratch, stream=None):
+    _check(lib().cephalo_layer_fwd(ctypes.byref(desc), _ptr(flat_param), _ptr(x), _ptr(y), micro_batch,
+                                   _ptr(save), save.numel() * save.element_size(),
+                                   _ptr(scratch), scratch.numel() * scratch.element_size(), _stream(stream)))
+
+
+def cephalo_layer_bwd(desc, flat_param, x, dy, dx, micro_batch, save, flat_grad, grad_scale, accumulate,
+                      scratch, stream=None):
+    _check(lib().cephalo_layer_bwd(ctypes.byref(desc), _ptr(flat_param), _ptr(x), _ptr(dy), _ptr(dx), micro_batch,
+                                   _ptr(save), save.numel() * save.element_size(),
+                                   _ptr(flat_grad), grad_scale, int(accumulate),
+                                   _ptr(scratch), scratch.numel() * scratch.element_size(), _stream(stream)))
+
+
+def cephalo_share_layer_step(desc, flat_param, x, y, dy, dx, batch_share, micro_batch, save, flat_grad,
+                             grad_scale, scratch, stream=None):
+    _check(lib().cephalo_share_layer_step(ctypes.byref(desc), _ptr(flat_param), _ptr(x), _ptr(y), _ptr(dy), _ptr(dx),
+                                          batch_share, micro_batch,
+                                          _ptr(save), save.numel() * save.element_size(),
+                                          _ptr(flat_grad), grad_scale,
+                                          _ptr(scratch), scratch.numel() * scratch.element_size(), _stream(stream)))
+
+
+def cephalo_grad_accum(acc, g, scale, n=None, stream=None):
+    n = acc.numel() if n is None else n
+    _check(lib().cephalo_grad_accum(_ptr(acc), _ptr(g), scale, n, _stream(stream)))
+
+
+def cephalo_shard_adam(p, g, m, v, p_lowp, P, offset, length, lr, beta1, beta2, eps, step, stream=None):
+    _check(lib().cephalo_shard_adam(_ptr(p), _ptr(g), _ptr(m), _ptr(v), _ptr(p_lowp), P, offset, length,
+                                    lr, beta1, beta2, eps, step, _stream(stream)))
+
+
+def cephalo_cast_bf16(dst, src, n=None, stream=None):
+    n = src.numel() if n is None else n
+    _check(lib().cephalo_cast_bf16(_ptr(dst), _ptr(src), n, _stream(stream)))

@@ -1,0 +1,263 @@
+// LayerNorm forward/backward and column sums (bias gradients): HBM-bound row kernels.
+// One 64-lane wavefront owns a row; its lanes hold the row in registers as 16-byte
+// vectors, and row statistics are wavefront reductions (no LDS, no block barrier).
+#include "kernels.h"
+
+namespace cephalo {
+namespace {
+
+constexpr int kThreads = 256;
+constexpr int kWaves = kThreads / 64;
+
+template <typename T, int MAXV>
+__global__ void __launch_bounds__(kThreads)
+ln_fwd_kernel(const T* __restrict__ x, const T* __restrict__ gamma, const T* __restrict__ beta,
+              T* __restrict__ u, float* __restrict__ mean, float* __restrict__ rstd,
+              int rows, int H, float eps) {
+  constexpr int VN = Vec<T>::N;
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  const int nv = H / VN;
+  const float inv_h = 1.0f / (float)H;
+  for (int row = blockIdx.x * kWaves + wave; row < rows; row += gridDim.x * kWaves) {
+    const T* xr = x + (int64_t)row * H;
+    float vals[MAXV][VN];
+    float sum = 0.f;
+#pragma unroll
+    for (int j = 0; j < MAXV; ++j) {
+      const int v = lane + 64 * j;
+      if (v < nv) {
+        load_vec<T>(xr + v * VN, vals[j]);
+#pragma unroll
+        for (int i = 0; i < VN; ++i) sum += vals[j][i];
+      }
+    }
+    const float mu = wave_sum(sum) * inv_h;
+    float sq = 0.f;
+#pragma unroll
+    for (int j = 0; j < MAXV; ++j) {
+      if (lane + 64 * j < nv) {
+#pragma unroll
+        for (int i = 0; i < VN; ++i) { const float d = vals[j][i] - mu; sq += d * d; }
+      }
+    }
+    const float rs = 1.0f / sqrtf(wave_sum(sq) * inv_h + eps);
+    T* ur = u + (int64_t)row * H;
+#pragma unroll
+    for (int j = 0; j < MAXV; ++j) {
+      const int v = lane + 64 * j;
+      if (v < nv) {
+        float g[VN], b[VN], o[VN];
+        load_vec<T>(gamma + v * VN, g);
+        load_vec<T>(beta + v * VN, b);
+#pragma unroll
+        for (int i = 0; i < VN; ++i) o[i] = g[i] * ((vals[j][i] - mu) * rs) + b[i];
+        store_vec<T>(ur + v * VN, o);
+      }
+    }
+    if (lane == 0) { mean[row] = mu; rstd[row] = rs; }
+  }
+}
+
+constexpr int kLnBwdRowsPerBlock = 16;  // 4 rows per wavefront
+
+// out = resid + rstd * (g - mean(g) - xhat * mean(g*xhat)),  g = du * gamma
+// partials[0][blk][h] = sum over the block's rows of du*xhat, partials[1][blk][h] = sum of du
+template <typename T, int MAXV>
+__global__ void __launch_bounds__(kThreads)
+ln_bwd_kernel(const T* __restrict__ du, const T* __restrict__ x, const float* __restrict__ mean,
+              const float* __restrict__ rstd, const T* __restrict__ gamma, const T* __restrict__ resid,
+              T* __restrict__ out, float* __restrict__ partials, int rows, int H) {
+  constexpr int VN = Vec<T>::N;
+  __shared__ float red[2][kWaves][64 * VN];
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  const int nv = H / VN;
+  const float inv_h = 1.0f / (float)H;
+  float dg[MAXV][VN], db[MAXV][VN];
+#pragma unroll
+  for (int j = 0; j < MAXV; ++j)
+#pragma unroll
+    for (int i = 0; i < VN; ++i) { dg[j][i] = 0.f; db[j][i] = 0.f; }
+
+  const int row0 = blockIdx.x * kLnBwdRowsPerBlock;
+  for (int r = wave; r < kLnBwdRowsPerBlock; r += kWaves) {
+    const int row = row0 + r;
+    if (row >= rows) break;
+    const float mu = mean[row], rs = rstd[row];
+    float g[MAXV][VN], xh[MAXV][VN];
+    float s1 = 0.f, s2 = 0.f;
+#pragma unroll
+    for (int j = 0; j < MAXV; ++j) {
+      const int v = lane + 64 * j;
+      if (v < nv) {
+        float d[VN], xv[VN], gm[VN];
+        load_vec<T>(du + (int64_t)row * H + v * VN, d);
+        load_vec<T>(x + (int64_t)row * H + v * VN, xv);
+        load_vec<T>(gamma + v * VN, gm);
+#pragma unroll
+        for (int i = 0; i < VN; ++i) {
+          xh[j][i] = (xv[i] - mu) * rs;
+          g[j][i] = d[i] * gm[i];
+          s1 += g[j][i];
+          s2 += g[j][i] * xh[j][i];
+          dg[j][i] += d[i] * xh[j][i];
+          db[j][i] += d[i];
+        }
+      }
+    }
+    const float c1 = wave_sum(s1) * inv_h, c2 = wave_sum(s2) * inv_h;
+#pragma unroll
+    for (int j = 0; j < MAXV; ++j) {
+      const int v = lane + 64 * j;
+      if (v < nv) {
+        float rr[VN], o[VN];
+        load_vec<T>(resid + (int64_t)row * H + v * VN, rr);
+#pragma unroll
+        for (int i = 0; i < VN; ++i) o[i] = rr[i] + rs * (g[j][i] - c1 - xh[j][i] * c2);
+        store_vec<T>(out + (int64_t)row * H + v * VN, o);
+      }
+    }
+  }
+  // cross-wavefront sum of the column partials, one 64*VN-column slab at a time
+  float* pg = partials + (int64_t)blockIdx.x * H;
+  float* pb = partials + ((int64_t)gridDim.x + blockIdx.x) * H;
+#pragma unroll
+  for (int j = 0; j < MAXV; ++j) {
+    __syncthreads();
+#pragma unroll
+    for (int i = 0; i < VN; ++i) {
+      red[0][wave][lane * VN + i] = dg[j][i];
+      red[1][wave][lane * VN + i] = db[j][i];
+    }
+    __syncthreads();
+    for (int c = threadIdx.x; c < 64 * VN; c += kThreads) {
+      const int col = j * 64 * VN + c;
+      if (col < H) {
+        float a = 0.f, b = 0.f;
+#pragma unroll
+        for (int w = 0; w < kWaves; ++w) { a += red[0][w][c]; b += red[1][w][c]; }
+        pg[col] = a;
+        pb[col] = b;
+      }
+    }
+  }
+}
+
+// g[n] = (accumulate ? g[n] : 0) + scale * sum_{c < nchunks} partials[c][n], fixed order
+__global__ void __launch_bounds__(kThreads)
+reduce_partials_kernel(const float* __restrict__ partials, int nchunks, int N, float* __restrict__ g,
+                       float scale, int accumulate) {
+  const int n = blockIdx.x * kThreads + threadIdx.x;
+  if (n >= N) return;
+  float s = 0.f;
+  for (int c = 0; c < nchunks; ++c) s += partials[(int64_t)c * N + n];
+  g[n] = (accumulate ? g[n] : 0.f) + scale * s;
+}
+
+constexpr int kColsumRowsPerChunk = 64;
+
+template <typename T>
+__global__ void __launch_bounds__(kThreads)
+colsum_kernel(const T* __restrict__ dY, float* __restrict__ partials, int rows, int N) {
+  constexpr int VN = Vec<T>::N;
+  const int v = blockIdx.x * kThreads + threadIdx.x;  // vector column
+  if (v * VN >= N) return;
+  const int r0 = blockIdx.y * kColsumRowsPerChunk;
+  const int r1 = min(rows, r0 + kColsumRowsPerChunk);
+  float acc[VN];
+#pragma unroll
+  for (int i = 0; i < VN; ++i) acc[i] = 0.f;
+  for (int r = r0; r < r1; ++r) {
+    float d[VN];
+    load_vec<T>(dY + (int64_t)r * N + v * VN, d);
+#pragma unroll
+    for (int i = 0; i < VN; ++i) acc[i] += d[i];
+  }
+  float* p = partials + (int64_t)blockIdx.y * N + v * VN;
+#pragma unroll
+  for (int i = 0; i < VN; ++i) p[i] = acc[i];
+}
+
+template <typename T> int maxv_for(int H) {
+  const int nv = H / Vec<T>::N;
+  const int need = (nv + 63) / 64;
+  int m = 1;
+  while (m < need) m *= 2;
+  return m;
+}
+
+}  // namespace
+
+template <typename T>
+int launch_ln_fwd(const T* x, const T* gamma, const T* beta, T* u, float* mean, float* rstd,
+                  int rows, int H, float eps, hipStream_t s) {
+  const int grid = (rows + kWaves - 1) / kWaves;
+#define LN_FWD_CASE(MV)                                                                             \
+  case MV:                                                                                          \
+    ln_fwd_kernel<T, MV><<<grid, kThreads, 0, s>>>(x, gamma, beta, u, mean, rstd, rows, H, eps);    \
+    break;
+  switch (maxv_for<T>(H)) {
+    LN_FWD_CASE(1) LN_FWD_CASE(2) LN_FWD_CASE(4) LN_FWD_CASE(8) LN_FWD_CASE(16)
+    default: return fail(CEPHALO_EUNSUPPORTED, "layer norm: hidden width %d too large", H);
+  }
+#undef LN_FWD_CASE
+  CEPHALO_CHECK_LAUNCH("ln_fwd");
+  return CEPHALO_OK;
+}
+
+size_t ln_bwd_partial_bytes(int rows, int H) {
+  const size_t nblocks = (rows + kLnBwdRowsPerBlock - 1) / kLnBwdRowsPerBlock;
+  return 2 * nblocks * (size_t)H * sizeof(float);
+}
+
+template <typename T>
+int launch_ln_bwd(const T* du, const T* x, const float* mean, const float* rstd, const T* gamma,
+                  const T* resid, T* out, float* partials, size_t partial_bytes,
+                  float* g_gamma, float* g_beta, float scale, int accumulate,
+                  int rows, int H, hipStream_t s) {
+  if (partial_bytes < ln_bwd_partial_bytes(rows, H)) return fail(CEPHALO_EWORKSPACE, "ln_bwd: partial buffer too small");
+  const int nblocks = (rows + kLnBwdRowsPerBlock - 1) / kLnBwdRowsPerBlock;
+#define LN_BWD_CASE(MV)                                                                                      \
+  case MV:                                                                                                   \
+    ln_bwd_kernel<T, MV><<<nblocks, kThreads, 0, s>>>(du, x, mean, rstd, gamma, resid, out, partials, rows, H); \
+    break;
+  switch (maxv_for<T>(H)) {
+    LN_BWD_CASE(1) LN_BWD_CASE(2) LN_BWD_CASE(4) LN_BWD_CASE(8) LN_BWD_CASE(16)
+    default: return fail(CEPHALO_EUNSUPPORTED, "layer norm: hidden width %d too large", H);
+  }
+#undef LN_BWD_CASE
+  CEPHALO_CHECK_LAUNCH("ln_bwd");
+  const int rgrid = (H + kThreads - 1) / kThreads;
+  reduce_partials_kernel<<<rgrid, kThreads, 0, s>>>(partials, nblocks, H, g_gamma, scale, accumulate);
+  reduce_partials_kernel<<<rgrid, kThreads, 0, s>>>(partials + (int64_t)nblocks * H, nblocks, H, g_beta, scale, accumulate);
+  CEPHALO_CHECK_LAUNCH("ln_bwd reduce");
+  return CEPHALO_OK;
+}
+
+size_t colsum_partial_bytes(int rows, int N) {
+  const size_t nchunks = (rows + kColsumRowsPerChunk - 1) / kColsumRowsPerChunk;
+  return nchunks * (size_t)N * sizeof(float);
+}
+
+template <typename T>
+int launch_colsum(const T* dY, float* partials, size_t partial_bytes, float* g, float scale,
+                  int accumulate, int rows, int N, hipStream_t s) {
+  if (partial_bytes < colsum_partial_bytes(rows, N)) return fail(CEPHALO_EWORKSPACE, "colsum: partial buffer too small");
+  const int nchunks = (rows + kColsumRowsPerChunk - 1) / kColsumRowsPerChunk;
+  const int nvec = N / Vec<T>::N;
+  dim3 grid((nvec + kThreads - 1) / kThreads, nchunks);
+  colsum_kernel<T><<<grid, kThreads, 0, s>>>(dY, partials, rows, N);
+  reduce_partials_kernel<<<(N + kThreads - 1) / kThreads, kThreads, 0, s>>>(partials, nchunks, N, g, scale, accumulate);
+  CEPHALO_CHECK_LAUNCH("colsum");
+  return CEPHALO_OK;
+}
+
+#define INSTANTIATE(T)                                                                                         \
+  template int launch_ln_fwd<T>(const T*, const T*, const T*, T*, float*, float*, int, int, float, hipStream_t); \
+  template int launch_ln_bwd<T>(const T*, const T*, const float*, const float*, const T*, const T*, T*, float*, \
+                                size_t, float*, float*, float, int, int, int, hipStream_t);                     \
+  template int launch_colsum<T>(const T*, float*, size_t, float*, float, int, int, int, hipStream_t);
+INSTANTIATE(float)
+INSTANTIATE(bf16)
+#undef INSTANTIATE
+
+}  // namespace cephalo

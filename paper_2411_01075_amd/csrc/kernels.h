@@ -1,0 +1,121 @@
+// Internal launch interface between the layer driver and the kernel files.
+// Every function enqueues on `s` and returns; shapes were validated by the caller.
+#pragma once
+#include "common.h"
+
+namespace cephalo {
+
+// ---------------------------------------------------------------------------------------
+// Element type helpers: 16-byte vectors of the activation type, widened to float.
+template <typename T> struct Vec;
+template <> struct Vec<float> {
+  static constexpr int N = 4;
+  typedef float raw __attribute__((ext_vector_type(4)));
+};
+template <> struct Vec<bf16> {
+  static constexpr int N = 8;
+  typedef bf16 raw __attribute__((ext_vector_type(8)));
+};
+
+template <typename T>
+__device__ __forceinline__ void load_vec(const T* p, float (&out)[Vec<T>::N]) {
+  typename Vec<T>::raw r = *reinterpret_cast<const typename Vec<T>::raw*>(p);
+#pragma unroll
+  for (int i = 0; i < Vec<T>::N; ++i) out[i] = (float)r[i];
+}
+template <typename T>
+__device__ __forceinline__ void store_vec(T* p, const float (&in)[Vec<T>::N]) {
+  typename Vec<T>::raw r;
+#pragma unroll
+  for (int i = 0; i < Vec<T>::N; ++i) r[i] = (T)in[i];
+  *reinterpret_cast<typename Vec<T>::raw*>(p) = r;
+}
+
+__device__ __forceinline__ float wave_sum(float v) {
+#pragma unroll
+  for (int o = 32; o > 0; o >>= 1) v += __shfl_xor(v, o, 64);
+  return v;
+}
+__device__ __forceinline__ float wave_max(float v) {
+#pragma unroll
+  for (int o = 32; o > 0; o >>= 1) v = fmaxf(v, __shfl_xor(v, o, 64));
+  return v;
+}
+
+// exact GELU and its derivative, fp32
+__device__ __forceinline__ float gelu_f(float z) { return 0.5f * z * (1.0f + erff(z * 0.70710678118654752440f)); }
+__device__ __forceinline__ float gelu_grad_f(float z) {
+  const float cdf = 0.5f * (1.0f + erff(z * 0.70710678118654752440f));
+  const float pdf = 0.39894228040143267794f * __expf(-0.5f * z * z);
+  return cdf + z * pdf;
+}
+
+// ---------------------------------------------------------------------------------------
+// GEMM:  C[M,N] = sum_k A(m,k) * B(n,k)  followed by an epilogue.
+// Operand element (m,k) of A sits at A[m*a_rs + k*a_cs]; one of the two strides is 1.
+// Likewise B(n,k) at B[n*b_rs + k*b_cs].
+enum Epilogue {
+  EPI_NONE = 0,        // C = acc
+  EPI_BIAS = 1,        // C = acc + bias[n]
+  EPI_BIAS_RESID = 2,  // C = acc + bias[n] + R[m,n]
+  EPI_BIAS_GELU = 3,   // Z = acc + bias[n] ; C = gelu(Z)          (Z and C both stored)
+  EPI_DGELU = 4,       // C = acc * gelu'(Z[m,n])
+  EPI_GRAD = 5,        // G[m,n] = (accumulate ? G[m,n] : 0) + scale * acc     (G fp32)
+};
+
+template <typename T>
+struct GemmArgs {
+  const T* A; int64_t a_rs, a_cs;
+  const T* B; int64_t b_rs, b_cs;
+  int M, N, K;
+  int epi;
+  T* C;            // [M,N] row-major, ldc = N (unused for EPI_GRAD)
+  const T* bias;   // [N]
+  const T* R;      // [M,N] residual
+  T* Z;            // [M,N] pre-activation: written by EPI_BIAS_GELU, read by EPI_DGELU
+  float* G;        // [M,N] fp32 gradient (EPI_GRAD)
+  float scale;
+  int accumulate;
+};
+
+template <typename T> int launch_gemm_simple(const GemmArgs<T>& a, hipStream_t s);
+int launch_gemm_mfma(const GemmArgs<bf16>& a, hipStream_t s);  // bf16 operands, MFMA, fp32 accumulate
+
+// ---------------------------------------------------------------------------------------
+// LayerNorm over the last axis of x[rows, H].
+template <typename T>
+int launch_ln_fwd(const T* x, const T* gamma, const T* beta, T* u, float* mean, float* rstd,
+                  int rows, int H, float eps, hipStream_t s);
+
+// out = resid + LN-backward(du); per-block partial sums of dgamma/dbeta go to `partials`
+// ([2][nblocks][H] fp32) and are folded into g_gamma / g_beta (each [H] fp32, flat-gradient
+// slices) as  g = (accumulate ? g : 0) + scale * sum.
+template <typename T>
+int launch_ln_bwd(const T* du, const T* x, const float* mean, const float* rstd, const T* gamma,
+                  const T* resid, T* out, float* partials, size_t partial_bytes,
+                  float* g_gamma, float* g_beta, float scale, int accumulate,
+                  int rows, int H, hipStream_t s);
+size_t ln_bwd_partial_bytes(int rows, int H);
+
+// g[n] = (accumulate ? g[n] : 0) + scale * sum_t dY[t][n]   (bias gradient), dY [rows, N]
+template <typename T>
+int launch_colsum(const T* dY, float* partials, size_t partial_bytes, float* g, float scale,
+                  int accumulate, int rows, int N, hipStream_t s);
+size_t colsum_partial_bytes(int rows, int N);
+
+// ---------------------------------------------------------------------------------------
+// Attention on the packed projection qkv [m*S, 3H] (Q | K | V column blocks, head a in
+// columns [a*d,(a+1)*d) of each block).  O [m*S, H], lse [m, A, S] fp32 (log-sum-exp of the
+// scaled, masked scores of each query row).
+template <typename T>
+int launch_attn_fwd_simple(const T* qkv, T* O, float* lse, int m, int S, int H, int A, int causal, hipStream_t s);
+// dqkv [m*S, 3H]; dvec [m, A, S] fp32 scratch for rowsum(dO*O)
+template <typename T>
+int launch_attn_bwd_simple(const T* qkv, const T* O, const T* dO, const float* lse, float* dvec, T* dqkv,
+                           int m, int S, int H, int A, int causal, hipStream_t s);
+
+int launch_attn_fwd_mfma(const bf16* qkv, bf16* O, float* lse, int m, int S, int H, int A, int causal, hipStream_t s);
+int launch_attn_bwd_mfma(const bf16* qkv, const bf16* O, const bf16* dO, const float* lse, float* dvec, bf16* dqkv,
+                         int m, int S, int H, int A, int causal, hipStream_t s);
+
+}  // namespace cephalo

@@ -1,0 +1,105 @@
+"""Glue used by the GPU parity tests: moves seeded inputs to the device, calls the library
+through its binding, runs the oracle on the same inputs, and compares tensor by tensor."""
+import numpy as np
+import torch
+
+import paper_2411_01075_amd as C
+from oracle import layout as olayout
+from oracle import share as oshare
+from oracle.precision import round_to_bf16
+from workloads.generate import LAYER_TENSORS
+
+TENSOR_NAMES = [t[0] for t in LAYER_TENSORS]
+
+# tolerances (tensor-normalised): max|gpu-ref|/max|ref| and mean|gpu-ref|/mean|ref|
+TOL = {"f32": (1e-4, 1e-4), "bf16": (2e-2, 5e-3)}
+
+
+def tdtype(cfg):
+    return torch.float32 if cfg.dtype == "f32" else torch.bfloat16
+
+
+def gpu_flatten(desc, tensors):
+    """fp32 flat parameter vector in the library's own layout (offsets asked from the library)."""
+    P = C.cephalo_layer_param_count(desc)
+    offs = C.cephalo_layer_param_offsets(desc)
+    flat = np.empty(P, dtype=np.float32)
+    for name, o in zip(TENSOR_NAMES, offs):
+        t = tensors[name]
+        flat[o:o + t.size] = t.reshape(-1)
+    return flat
+
+
+def rel_errors(got, ref):
+    got = np.asarray(got, dtype=np.float64)
+    ref = np.asarray(ref, dtype=np.float64)
+    diff = np.abs(got - ref)
+    mx = diff.max() / max(np.abs(ref).max(), 1e-300)
+    mean = diff.mean() / max(np.abs(ref).mean(), 1e-300)
+    return mx, mean
+
+
+def assert_close(name, got, ref, dtype, scale=1.0):
+    mx, mean = rel_errors(got, ref)
+    tmax, tmean = TOL[dtype]
+    assert np.isfinite(np.asarray(got, dtype=np.float64)).all(), "%s has non-finite values" % name
+    assert mx <= tmax * scale and mean <= tmean * scale, "%s: max-rel %.3e (tol %.1e) mean-rel %.3e (tol %.1e)" % (
+        name, mx, tmax * scale, mean, tmean * scale)
+    return mx, mean
+
+
+def gpu_share_step(cfg, tensors, x, dy, grad_scale=1.0, via_share_call=True):
+    """Runs forward+backward of the whole share on the GPU.  Returns y, dx (float64 numpy) and G (float32)."""
+    desc = C.desc_from_config(cfg)
+    dt = tdtype(cfg)
+    flat32 = torch.from_numpy(gpu_flatten(desc, tensors)).cuda()
+    if cfg.dtype == "f32":
+        flat = flat32
+    else:
+        flat = torch.empty(flat32.numel(), dtype=torch.bfloat16, device="cuda")
+        C.cephalo_cast_bf16(flat, flat32)
+    xd = torch.from_numpy(x).cuda().to(dt).contiguous()
+    dyd = torch.from_numpy(dy).cuda().to(dt).contiguous()
+    b, m = x.shape[0], cfg.micro_batch
+    l = b // m
+    yd = torch.empty_like(xd)
+    dxd = torch.empty_like(xd)
+    save_b, scr_b = C.cephalo_layer_workspace_bytes(desc, m)
+    save = torch.empty(save_b * l, dtype=torch.uint8, device="cuda")
+    scratch = torch.empty(scr_b, dtype=torch.uint8, device="cuda")
+    G = torch.full((flat32.numel(),), float("nan"), dtype=torch.float32, device="cuda")   # first micro-batch must overwrite
+    if via_share_call:
+        C.cephalo_share_layer_step(desc, flat, xd, yd, dyd, dxd, b, m, save, G, grad_scale, scratch)
+    else:
+        per = m * cfg.seq * cfg.hidden
+        for j in range(l):
+            sl = slice(j * m, (j + 1) * m)
+            C.cephalo_layer_fwd(desc, flat, xd[sl], yd[sl], m, save[j * save_b:(j + 1) * save_b], scratch)
+        for j in range(l):
+            sl = slice(j * m, (j + 1) * m)
+            C.cephalo_layer_bwd(desc, flat, xd[sl], dyd[sl], dxd[sl], m, save[j * save_b:(j + 1) * save_b],
+                                G, grad_scale, j > 0, scratch)
+    torch.cuda.synchronize()
+    return yd.double().cpu().numpy(), dxd.double().cpu().numpy(), G.cpu().numpy()
+
+
+def oracle_share_step(cfg, tensors, x, dy, grad_scale=1.0):
+    """Oracle on the same inputs; bf16 workloads round parameters, x and dy to bf16 first."""
+    H, F = cfg.hidden, cfg.mlp
+    flat = olayout.flatten_layer(tensors, H, F, dtype=np.float64)
+    x64, dy64 = x.astype(np.float64), dy.astype(np.float64)
+    if cfg.dtype == "bf16":
+        flat = round_to_bf16(flat.astype(np.float32))
+        x64, dy64 = round_to_bf16(x), round_to_bf16(dy)
+    return oshare.share_layer_step(flat, x64, dy64, H, F, cfg.heads, cfg.causal, cfg.micro_batch, scale=grad_scale)
+
+
+def compare_share(cfg, got, ref, scale=1.0):
+    """Asserts y, dx and every parameter-gradient tensor against the oracle; returns a report dict."""
+    y, dx, G = got
+    ry, rdx, rG = ref
+    rep = {"y": assert_close("y", y, ry, cfg.dtype, scale), "dx": assert_close("dx", dx, rdx, cfg.dtype, scale)}
+    for name, (start, shape) in olayout.layer_offsets(cfg.hidden, cfg.mlp).items():
+        n = int(np.prod(shape))
+        rep[name] = assert_close("grad " + name, G[start:start + n], rG[start:start + n], cfg.dtype, scale)
+    return rep

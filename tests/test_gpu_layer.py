@@ -1,0 +1,95 @@
+"""GPU parity of the layer path (forward, backward, accumulation over micro-batches)
+against the CPU oracle, element by element, through the C ABI."""
+import dataclasses
+import numpy as np
+import pytest
+import torch
+
+import paper_2411_01075_amd as C
+from workloads import CONFIGS, draw_layer_params, draw_activations
+from tests import harness as Hn
+
+pytestmark = pytest.mark.gpu
+
+
+def small(cfg, **kw):
+    return dataclasses.replace(cfg, **kw)
+
+
+CASES = {
+    # the fp32 workload at its full size
+    "c1": CONFIGS["c1"],
+    # fp32, ragged everything: head dim 24, seq not a multiple of any tile, odd micro-batch count
+    "f32_ragged": small(CONFIGS["c1"], name="f32_ragged", hidden=72, heads=3, mlp=200, seq=37, micro_batch=1, n_micro=3),
+    "f32_noncausal": small(CONFIGS["c1"], name="f32_nc", hidden=128, heads=2, mlp=256, seq=70, causal=False, micro_batch=3, n_micro=1),
+    # bf16, reduced relatives of c2 / c3 / c4 that still span several tiles and a ragged tail
+    "bf16_c2_small": small(CONFIGS["c2"], name="bf16_c2s", hidden=256, heads=4, mlp=1024, seq=192, micro_batch=2, n_micro=2),
+    "bf16_c3_small": small(CONFIGS["c3"], name="bf16_c3s", hidden=320, heads=5, mlp=1280, seq=200, micro_batch=2, n_micro=3),
+    "bf16_c4_small": small(CONFIGS["c4"], name="bf16_c4s", hidden=512, heads=4, mlp=2048, seq=320, micro_batch=1, n_micro=2),
+}
+
+
+@pytest.mark.parametrize("case", list(CASES))
+@pytest.mark.parametrize("perturbed", [False, True])
+def test_share_step_matches_oracle(case, perturbed):
+    cfg = CASES[case]
+    print("case", case, "perturbed", perturbed, flush=True)
+    tensors = draw_layer_params(cfg, perturbed=perturbed)
+    x, dy = draw_activations(cfg)
+    got = Hn.gpu_share_step(cfg, tensors, x, dy)
+    ref = Hn.oracle_share_step(cfg, tensors, x, dy)
+    rep = Hn.compare_share(cfg, got, ref)
+    print({k: "%.1e/%.1e" % v for k, v in rep.items()}, flush=True)
+
+
+def test_per_microbatch_calls_equal_share_call_bitwise():
+    cfg = CASES["bf16_c2_small"]
+    tensors = draw_layer_params(cfg, perturbed=True)
+    x, dy = draw_activations(cfg)
+    a = Hn.gpu_share_step(cfg, tensors, x, dy, via_share_call=True)
+    b = Hn.gpu_share_step(cfg, tensors, x, dy, via_share_call=False)
+    for u, v in zip(a, b):
+        assert np.array_equal(u, v)
+
+
+def test_grad_scale_is_eq1_factor():
+    """Accumulating with scale s equals s times the unit-scale result (Eq. 1's factor enters linearly)."""
+    cfg = CASES["f32_ragged"]
+    tensors = draw_layer_params(cfg, perturbed=True)
+    x, dy = draw_activations(cfg)
+    s = 3 * 5 / 8.0          # N * b_i / B for N = 3, b_i = 5, B = 8
+    g1 = Hn.gpu_share_step(cfg, tensors, x, dy, grad_scale=1.0)[2]
+    gs = Hn.gpu_share_step(cfg, tensors, x, dy, grad_scale=s)[2]
+    ref = Hn.oracle_share_step(cfg, tensors, x, dy, grad_scale=s)[2]
+    assert Hn.rel_errors(gs, ref)[0] < 1e-4
+    assert Hn.rel_errors(gs, s * g1.astype(np.float64))[0] < 1e-5
+
+
+def test_results_are_reproducible_run_to_run():
+    cfg = CASES["bf16_c3_small"]
+    tensors = draw_layer_params(cfg)
+    x, dy = draw_activations(cfg)
+    a = Hn.gpu_share_step(cfg, tensors, x, dy)
+    b = Hn.gpu_share_step(cfg, tensors, x, dy)
+    for u, v in zip(a, b):
+        assert np.array_equal(u, v)
+
+
+def test_device_argument_errors_launch_nothing():
+    cfg = CASES["c1"]
+    desc = C.desc_from_config(cfg)
+    P = C.cephalo_layer_param_count(desc)
+    flat = torch.zeros(P, device="cuda")
+    x = torch.zeros(2, cfg.seq, cfg.hidden, device="cuda")
+    y = torch.empty_like(x)
+    save_b, scr_b = C.cephalo_layer_workspace_bytes(desc, 2)
+    small_save = torch.empty(save_b - 256, dtype=torch.uint8, device="cuda")
+    scratch = torch.empty(scr_b, dtype=torch.uint8, device="cuda")
+    with pytest.raises(C.CephaloError, match="error -3"):
+        C.cephalo_layer_fwd(desc, flat, x, y, 2, small_save, scratch)
+    save = torch.empty(save_b, dtype=torch.uint8, device="cuda")
+    with pytest.raises(C.CephaloError, match="alias"):
+        C.cephalo_layer_fwd(desc, flat, x, x, 2, save, scratch)
+    with pytest.raises(C.CephaloError, match="positive"):
+        C.cephalo_layer_fwd(desc, flat, x, y, 0, save, scratch)
+    torch.cuda.synchronize()
