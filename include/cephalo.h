@@ -142,6 +142,39 @@ int cephalo_shard_adam(float* p, const float* g, float* m, float* v, void* p_low
  * parameters (the mixed-precision workloads' rule; the paper itself trains in fp32). */
 int cephalo_cast_bf16(void* dst_bf16, const float* src, int64_t n, void* stream);
 
+/* ---------------------------------------------------------------------------------------
+ * Building blocks of the layer, exported so that each kernel family can be checked against
+ * the oracle and profiled on its own.  Same conventions as above.
+ */
+
+/* Epilogues of cephalo_op_gemm */
+#define CEPHALO_EPI_NONE        0  /* C = acc                                              */
+#define CEPHALO_EPI_BIAS        1  /* C = acc + bias[n]                                    */
+#define CEPHALO_EPI_BIAS_RESID  2  /* C = acc + bias[n] + R[m,n]                           */
+#define CEPHALO_EPI_BIAS_GELU   3  /* Z = acc + bias[n]; C = gelu(Z); both stored          */
+#define CEPHALO_EPI_DGELU       4  /* C = acc * gelu'(Z[m,n])                              */
+#define CEPHALO_EPI_GRAD        5  /* G = (accumulate ? G : 0) + scale * acc   (G fp32)    */
+
+/* C[M,N] = sum_k A(m,k) * B(n,k) with a fused epilogue; the contraction of a linear layer's
+ * forward (both operands k-contiguous), input gradient (B n-contiguous) and weight gradient
+ * (both operands contiguous along their own rows, strided along k = tokens).
+ * Element (m,k) of A is A[m*a_rs + k*a_cs], (n,k) of B is B[n*b_rs + k*b_cs]; one stride of
+ * each operand is 1.  dtype selects fp32 or bf16 operands/outputs (accumulation is fp32 either
+ * way).  C, R, Z are [M,N] row-major in dtype; bias [N] in dtype; G [M,N] fp32.  Unused
+ * pointers may be NULL.  All device memory. */
+int cephalo_op_gemm(int32_t dtype, const void* A, int64_t a_rs, int64_t a_cs,
+                    const void* B, int64_t b_rs, int64_t b_cs, int32_t M, int32_t N, int32_t K,
+                    int32_t epilogue, void* C, const void* bias, const void* R, void* Z,
+                    float* G, float scale, int32_t accumulate, void* stream);
+
+/* Attention of one micro-batch on the packed projection qkv [m*S, 3H] (column blocks Q | K | V).
+ * Forward writes O [m*S, H] (dtype) and lse [m, A, S] fp32, the log-sum-exp of each query row's
+ * scaled, masked scores.  Backward writes dqkv [m*S, 3H]; dvec [m, A, S] fp32 is scratch. */
+int cephalo_op_attention_fwd(const cephalo_layer_desc* desc, const void* qkv, void* O, float* lse,
+                             int32_t micro_batch, void* stream);
+int cephalo_op_attention_bwd(const cephalo_layer_desc* desc, const void* qkv, const void* O, const void* dO,
+                             const float* lse, float* dvec, void* dqkv, int32_t micro_batch, void* stream);
+
 #ifdef __cplusplus
 }
 #endif

@@ -51,6 +51,10 @@ SIGNATURES = {
     "cephalo_grad_accum": (ctypes.c_int, [_vp, _vp, _f32, _i64, _vp]),
     "cephalo_shard_adam": (ctypes.c_int, [_vp, _vp, _vp, _vp, _vp, _i64, _i64, _i64, _f32, _f32, _f32, _f32, _i64, _vp]),
     "cephalo_cast_bf16": (ctypes.c_int, [_vp, _vp, _i64, _vp]),
+    "cephalo_op_gemm": (ctypes.c_int, [_i32, _vp, _i64, _i64, _vp, _i64, _i64, _i32, _i32, _i32, _i32, _vp, _vp, _vp, _vp,
+                                       _vp, _f32, _i32, _vp]),
+    "cephalo_op_attention_fwd": (ctypes.c_int, [_dp, _vp, _vp, _vp, _i32, _vp]),
+    "cephalo_op_attention_bwd": (ctypes.c_int, [_dp, _vp, _vp, _vp, _vp, _vp, _vp, _i32, _vp]),
 }
 
 
@@ -150,3 +154,21 @@ def cephalo_shard_adam(p, g, m, v, p_lowp, P, offset, length, lr, beta1, beta2, 
 def cephalo_cast_bf16(dst, src, n=None, stream=None):
     n = src.numel() if n is None else n
     _check(lib().cephalo_cast_bf16(_ptr(dst), _ptr(src), n, _stream(stream)))
+
+
+EPI_NONE, EPI_BIAS, EPI_BIAS_RESID, EPI_BIAS_GELU, EPI_DGELU, EPI_GRAD = range(6)
+
+
+def cephalo_op_gemm(dtype, A, a_rs, a_cs, B, b_rs, b_cs, M, N, K, epilogue, C=None, bias=None, R=None, Z=None,
+                    G=None, scale=1.0, accumulate=0, stream=None):
+    _check(lib().cephalo_op_gemm(dtype, _ptr(A), a_rs, a_cs, _ptr(B), b_rs, b_cs, M, N, K, epilogue,
+                                 _ptr(C), _ptr(bias), _ptr(R), _ptr(Z), _ptr(G), scale, int(accumulate), _stream(stream)))
+
+
+def cephalo_op_attention_fwd(desc, qkv, O, lse, micro_batch, stream=None):
+    _check(lib().cephalo_op_attention_fwd(ctypes.byref(desc), _ptr(qkv), _ptr(O), _ptr(lse), micro_batch, _stream(stream)))
+
+
+def cephalo_op_attention_bwd(desc, qkv, O, dO, lse, dvec, dqkv, micro_batch, stream=None):
+    _check(lib().cephalo_op_attention_bwd(ctypes.byref(desc), _ptr(qkv), _ptr(O), _ptr(dO), _ptr(lse), _ptr(dvec),
+                                          _ptr(dqkv), micro_batch, _stream(stream)))

@@ -1,0 +1,87 @@
+"""GPU parity of the GEMM family (forward, input-gradient and weight-gradient contractions with
+their fused epilogues) against plain fp64 definitions evaluated by the oracle's pieces."""
+import numpy as np
+import pytest
+import torch
+
+import paper_2411_01075_amd as C
+from oracle import layer as olayer
+from oracle.precision import round_to_bf16
+from tests.harness import rel_errors
+
+pytestmark = pytest.mark.gpu
+
+
+def dev(a, bf16):
+    t = torch.from_numpy(np.ascontiguousarray(a, dtype=np.float32)).cuda()
+    return t.to(torch.bfloat16) if bf16 else t
+
+
+def host(t):
+    return t.double().cpu().numpy()
+
+
+SHAPES = [  # tokens T, out features N, in features K
+    (256, 384, 128),      # exact tiles
+    (200, 1600, 320),     # ragged rows, 12.5 tiles of 128 columns
+    (520, 328, 72),       # ragged in all three, k not a multiple of the 64-slab
+    (1024, 3072, 1024),   # the BERT-large-shaped QKV projection
+    (64, 64, 64),
+]
+
+
+@pytest.mark.parametrize("bf16", [False, True])
+@pytest.mark.parametrize("T,N,K", SHAPES)
+def test_linear_forward_epilogues(T, N, K, bf16):
+    print("fwd", T, N, K, "bf16" if bf16 else "f32", flush=True)
+    rng = np.random.default_rng(T + N + K)
+    X = rng.standard_normal((T, K)).astype(np.float32)
+    W = (rng.standard_normal((N, K)) * 0.05).astype(np.float32)
+    b = (rng.standard_normal(N) * 0.1).astype(np.float32)
+    R = rng.standard_normal((T, N)).astype(np.float32)
+    rnd = round_to_bf16 if bf16 else (lambda a: a.astype(np.float64))
+    Xr, Wr, br, Rr = rnd(X), rnd(W), rnd(b), rnd(R)
+    acc = Xr @ Wr.T
+    dt = C.BF16 if bf16 else C.F32
+    tol = 6e-3 if bf16 else 1e-5      # one bf16 rounding of the output: 2^-9 relative, tensor-normalised
+    dX, dW, db, dR = dev(X, bf16), dev(W, bf16), dev(b, bf16), dev(R, bf16)
+    out = torch.empty_like(dR)
+    Z = torch.empty_like(dR)
+    C.cephalo_op_gemm(dt, dX, K, 1, dW, K, 1, T, N, K, C.EPI_NONE, C=out)
+    assert rel_errors(host(out), acc)[0] < tol
+    C.cephalo_op_gemm(dt, dX, K, 1, dW, K, 1, T, N, K, C.EPI_BIAS, C=out, bias=db)
+    assert rel_errors(host(out), acc + br)[0] < tol
+    C.cephalo_op_gemm(dt, dX, K, 1, dW, K, 1, T, N, K, C.EPI_BIAS_RESID, C=out, bias=db, R=dR)
+    assert rel_errors(host(out), acc + br + Rr)[0] < tol
+    C.cephalo_op_gemm(dt, dX, K, 1, dW, K, 1, T, N, K, C.EPI_BIAS_GELU, C=out, bias=db, Z=Z)
+    assert rel_errors(host(Z), acc + br)[0] < tol
+    assert rel_errors(host(out), olayer.gelu(acc + br))[0] < tol
+
+
+@pytest.mark.parametrize("bf16", [False, True])
+@pytest.mark.parametrize("T,N,K", SHAPES)
+def test_linear_input_and_weight_gradients(T, N, K, bf16):
+    print("bwd", T, N, K, "bf16" if bf16 else "f32", flush=True)
+    rng = np.random.default_rng(T * 3 + N + K)
+    X = rng.standard_normal((T, K)).astype(np.float32)
+    W = (rng.standard_normal((N, K)) * 0.05).astype(np.float32)
+    dY = rng.standard_normal((T, N)).astype(np.float32)
+    Zp = rng.standard_normal((T, K)).astype(np.float32)
+    rnd = round_to_bf16 if bf16 else (lambda a: a.astype(np.float64))
+    Xr, Wr, dYr, Zr = rnd(X), rnd(W), rnd(dY), rnd(Zp)
+    dt = C.BF16 if bf16 else C.F32
+    tol = 6e-3 if bf16 else 1e-5
+    dX_, dW_, ddY, dZ = dev(X, bf16), dev(W, bf16), dev(dY, bf16), dev(Zp, bf16)
+    # input gradient: dX[T,K] = dY[T,N] W[N,K]
+    out = torch.empty_like(dX_)
+    C.cephalo_op_gemm(dt, ddY, N, 1, dW_, 1, K, T, K, N, C.EPI_NONE, C=out)
+    assert rel_errors(host(out), dYr @ Wr)[0] < tol
+    C.cephalo_op_gemm(dt, ddY, N, 1, dW_, 1, K, T, K, N, C.EPI_DGELU, C=out, Z=dZ)
+    assert rel_errors(host(out), (dYr @ Wr) * olayer.gelu_grad(Zr))[0] < tol
+    # weight gradient with accumulation: G = (acc ? G : 0) + s * dY^T X
+    G = torch.full((N, K), float("nan"), dtype=torch.float32, device="cuda")
+    C.cephalo_op_gemm(dt, ddY, 1, N, dX_, 1, K, N, K, T, C.EPI_GRAD, G=G, scale=0.5, accumulate=0)
+    ref = 0.5 * (dYr.T @ Xr)
+    assert rel_errors(host(G), ref)[0] < 1e-5
+    C.cephalo_op_gemm(dt, ddY, 1, N, dX_, 1, K, N, K, T, C.EPI_GRAD, G=G, scale=0.25, accumulate=1)
+    assert rel_errors(host(G), 1.5 * ref)[0] < 1e-5
