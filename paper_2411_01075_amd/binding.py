@@ -172,3 +172,19 @@ def cephalo_op_attention_fwd(desc, qkv, O, lse, micro_batch, stream=None):
 def cephalo_op_attention_bwd(desc, qkv, O, dO, lse, dvec, dqkv, micro_batch, stream=None):
     _check(lib().cephalo_op_attention_bwd(ctypes.byref(desc), _ptr(qkv), _ptr(O), _ptr(dO), _ptr(lse), _ptr(dvec),
                                           _ptr(dqkv), micro_batch, _stream(stream)))
+
+
+# Names of the 12 tensors of a layer in flat-layout order (see include/cephalo.h).
+LAYER_TENSOR_NAMES = ("ln1_g", "ln1_b", "w_qkv", "b_qkv", "w_o", "b_o", "ln2_g", "ln2_b", "w_fc1", "b_fc1", "w_fc2", "b_fc2")
+
+
+def flatten_layer_params(desc, tensors):
+    """Host-side marshalling: dict name -> float32 array to the fp32 flat vector, at the offsets the library reports."""
+    import numpy as np
+    P = cephalo_layer_param_count(desc)
+    offs = cephalo_layer_param_offsets(desc)
+    flat = np.empty(P, dtype=np.float32)
+    for name, o in zip(LAYER_TENSOR_NAMES, offs):
+        t = tensors[name]
+        flat[o:o + t.size] = t.reshape(-1)
+    return flat

@@ -21,13 +21,7 @@ def tdtype(cfg):
 
 def gpu_flatten(desc, tensors):
     """fp32 flat parameter vector in the library's own layout (offsets asked from the library)."""
-    P = C.cephalo_layer_param_count(desc)
-    offs = C.cephalo_layer_param_offsets(desc)
-    flat = np.empty(P, dtype=np.float32)
-    for name, o in zip(TENSOR_NAMES, offs):
-        t = tensors[name]
-        flat[o:o + t.size] = t.reshape(-1)
-    return flat
+    return C.flatten_layer_params(desc, tensors)
 
 
 def rel_errors(got, ref):
