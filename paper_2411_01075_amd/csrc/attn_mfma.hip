@@ -1,10 +1,505 @@
+// Tiled attention forward and backward on the gfx950 matrix cores (bf16 operands, fp32 softmax
+// and accumulation).  The S x S score matrix never reaches HBM: forward keeps a running row
+// maximum and row sum (online softmax) and stores only the per-row log-sum-exp; backward
+// recomputes the probabilities from Q, K and that log-sum-exp.
+//
+// Orientation.  v_mfma_f32_32x32x16_bf16 leaves each lane with ONE column of the 32x32 result
+// (column lane%32) and 16 of its rows.  Every product is arranged so that the column is the
+// index whose per-row statistics are needed and the rows are the index contracted next:
+//   forward / dQ : S^T[t][q] = K Q^T  -> lane owns query q: max, sum, lse[q], rowsum(dO*O)[q] are
+//                  lane scalars; the rows t feed the next product (O^T = V^T P^T, dQ^T = K^T dS^T)
+//                  straight from registers as its B operand.
+//   dK / dV      : S[q][t] = Q K^T    -> lane owns key t; rows q feed dV^T = dO^T P, dK^T = Q^T dS.
+// The other operand of those second products (V^T, K^T, dO^T, Q^T: d-major views of row-major
+// [token][d] tiles) is fetched from LDS with the transposing read ds_read_b64_tr_b16.
 #include "kernels.h"
+
 namespace cephalo {
-int launch_attn_fwd_mfma(const bf16* qkv, bf16* O, float* lse, int m, int S, int H, int A, int causal, hipStream_t s) {
-  return launch_attn_fwd_simple<bf16>(qkv, O, lse, m, S, H, A, causal, s);
+namespace {
+
+typedef bf16 bf16x8 __attribute__((ext_vector_type(8)));
+typedef bf16 bf16x4 __attribute__((ext_vector_type(4)));
+typedef float f32x16 __attribute__((ext_vector_type(16)));
+typedef float f32x4 __attribute__((ext_vector_type(4)));
+typedef short s16x4 __attribute__((ext_vector_type(4)));
+typedef __attribute__((address_space(3))) s16x4* lds_s16x4_ptr;
+
+constexpr int kThreads = 256;
+constexpr int TILE = 64;            // tokens per LDS tile
+constexpr float kLog2e = 1.44269504088896340736f;
+constexpr float kLn2 = 0.69314718055994530942f;
+
+template <int D> struct Tile {
+  static constexpr int LD = D + 8;                 // padded row, elements
+  static constexpr int ELEMS = TILE * LD;
+  static constexpr int PER_THREAD = TILE * D / 8 / kThreads;
+
+  // rows [row0, row0+64) of a [*, ld] matrix, columns [0, D); rows >= nrows read as zero
+  __device__ static void load_global(const bf16* __restrict__ g, int64_t ld, int row0, int nrows, bf16x8 (&reg)[PER_THREAD]) {
+#pragma unroll
+    for (int p = 0; p < PER_THREAD; ++p) {
+      const int v = threadIdx.x + kThreads * p;
+      const int row = v / (D / 8), c = (v % (D / 8)) * 8;
+      bf16x8 val = {0, 0, 0, 0, 0, 0, 0, 0};
+      if (row0 + row < nrows) val = *reinterpret_cast<const bf16x8*>(g + (int64_t)(row0 + row) * ld + c);
+      reg[p] = val;
+    }
+  }
+  __device__ static void store_lds(bf16* lds, const bf16x8 (&reg)[PER_THREAD]) {
+#pragma unroll
+    for (int p = 0; p < PER_THREAD; ++p) {
+      const int v = threadIdx.x + kThreads * p;
+      const int row = v / (D / 8), c = (v % (D / 8)) * 8;
+      *reinterpret_cast<bf16x8*>(lds + row * LD + c) = reg[p];
+    }
+  }
+  // operand with MFMA rows = tile rows [rb, rb+32), contraction over d in [kk, kk+16)
+  __device__ static bf16x8 frag_rows(const bf16* lds, int rb, int kk) {
+    const int lane = threadIdx.x & 63;
+    return *reinterpret_cast<const bf16x8*>(lds + (rb + (lane & 31)) * LD + kk + (lane >> 5) * 8);
+  }
+  // operand with MFMA rows = d in [db, db+32), contraction over 16 tile rows in the order the
+  // accumulator of a preceding 32x32 product holds them: slot 4c+i of half-wave h is tile row
+  // tb + 8c + 4h + i  (tb = first of the 16 rows)
+  __device__ static bf16x8 frag_cols(const bf16* lds, int db, int tb) {
+    const int lane = threadIdx.x & 63;
+    const int g = lane >> 4, i = lane & 15;
+    const bf16* p0 = lds + (tb + 4 * (g >> 1) + (i >> 2)) * LD + db + 16 * (g & 1) + 4 * (i & 3);
+    s16x4 lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s16x4_ptr)(p0));
+    s16x4 hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s16x4_ptr)(p0 + 8 * LD));
+    union { struct { s16x4 a, b; } s; bf16x8 v; } u;
+    u.s.a = lo; u.s.b = hi;
+    return u.v;
+  }
+};
+
+// fragment of 32 rows of a row-major [*, ld] matrix straight from global memory (rows = MFMA rows)
+template <int D>
+__device__ void load_row_frags(const bf16* __restrict__ g, int64_t ld, int row0, int nrows, bf16x8 (&f)[D / 16]) {
+  const int lane = threadIdx.x & 63;
+  const int row = row0 + (lane & 31);
+#pragma unroll
+  for (int kk = 0; kk < D / 16; ++kk) {
+    bf16x8 val = {0, 0, 0, 0, 0, 0, 0, 0};
+    if (row < nrows) val = *reinterpret_cast<const bf16x8*>(g + (int64_t)row * ld + kk * 16 + (lane >> 5) * 8);
+    f[kk] = val;
+  }
 }
+
+__device__ __forceinline__ bf16x8 pack8(const f32x16& v, int e0) {
+  bf16x8 r;
+#pragma unroll
+  for (int i = 0; i < 8; ++i) r[i] = (bf16)v[e0 + i];
+  return r;
+}
+
+// accumulator rows d (4 consecutive per group) of column token -> out[token][d0 + d], scaled
+template <int D>
+__device__ void store_transposed(const f32x16 (&acc)[D / 32], bf16* __restrict__ out, int64_t ld, int token, int ntokens, float mul) {
+  if (token >= ntokens) return;
+  const int h = (threadIdx.x & 63) >> 5;
+#pragma unroll
+  for (int dt = 0; dt < D / 32; ++dt)
+#pragma unroll
+    for (int j = 0; j < 4; ++j) {
+      bf16x4 v;
+#pragma unroll
+      for (int i = 0; i < 4; ++i) v[i] = (bf16)(acc[dt][4 * j + i] * mul);
+      *reinterpret_cast<bf16x4*>(out + (int64_t)token * ld + dt * 32 + 8 * j + 4 * h) = v;
+    }
+}
+
+// ------------------------------------------------------------------------------------ forward
+template <int D, bool CAUSAL>
+__global__ void __launch_bounds__(kThreads)
+attn_fwd_kernel(const bf16* __restrict__ qkv, bf16* __restrict__ O, float* __restrict__ lse, int S, int H, int A, float scale) {
+  typedef Tile<D> TL;
+  extern __shared__ __attribute__((aligned(16))) char smem_raw[];
+  bf16* smem = reinterpret_cast<bf16*>(smem_raw);
+  bf16* Ks[2] = {smem, smem + 2 * TL::ELEMS};
+  bf16* Vs[2] = {smem + TL::ELEMS, smem + 3 * TL::ELEMS};
+
+  const int qt = gridDim.x - 1 - blockIdx.x;       // heavy (late) causal tiles first
+  const int a = blockIdx.y, n = blockIdx.z;
+  const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63, h = lane >> 5;
+  const int64_t ld = 3 * (int64_t)H;
+  const bf16* base = qkv + (int64_t)n * S * ld + a * D;
+  const int q0 = qt * 128 + wave * 32;             // this wavefront's 32 query rows
+  const int q = q0 + (lane & 31);
+  const float c2 = scale * kLog2e;
+
+  bf16x8 qf[D / 16];
+  load_row_frags<D>(base, ld, q0, S, qf);
+
+  f32x16 o[D / 32];
+#pragma unroll
+  for (int dt = 0; dt < D / 32; ++dt)
+#pragma unroll
+    for (int e = 0; e < 16; ++e) o[dt][e] = 0.f;
+  float m_run = -INFINITY, l_run = 0.f;
+
+  const int kv_end = CAUSAL ? min(S, qt * 128 + 128) : S;
+  const int ntiles = (kv_end + TILE - 1) / TILE;
+  bf16x8 rk[TL::PER_THREAD], rv[TL::PER_THREAD];
+  TL::load_global(base + H, ld, 0, S, rk);
+  TL::load_global(base + 2 * H, ld, 0, S, rv);
+  TL::store_lds(Ks[0], rk);
+  TL::store_lds(Vs[0], rv);
+  __syncthreads();
+
+  for (int kt = 0; kt < ntiles; ++kt) {
+    const int cur = kt & 1, t0 = kt * TILE;
+    if (kt + 1 < ntiles) {
+      TL::load_global(base + H, ld, t0 + TILE, S, rk);
+      TL::load_global(base + 2 * H, ld, t0 + TILE, S, rv);
+    }
+    if (!CAUSAL || t0 <= q0 + 31) {
+      f32x16 s[2];
+#pragma unroll
+      for (int tb = 0; tb < 2; ++tb) {
+#pragma unroll
+        for (int e = 0; e < 16; ++e) s[tb][e] = 0.f;
+#pragma unroll
+        for (int kk = 0; kk < D / 16; ++kk)
+          s[tb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(TL::frag_rows(Ks[cur], tb * 32, kk * 16), qf[kk], s[tb], 0, 0, 0);
+      }
+      float mx = -INFINITY;
+#pragma unroll
+      for (int tb = 0; tb < 2; ++tb)
+#pragma unroll
+        for (int e = 0; e < 16; ++e) {
+          const int t = t0 + tb * 32 + 8 * (e >> 2) + 4 * h + (e & 3);
+          float v = s[tb][e] * c2;
+          if (t >= S || (CAUSAL && t > q)) v = -INFINITY;
+          s[tb][e] = v;
+          mx = fmaxf(mx, v);
+        }
+      mx = fmaxf(mx, __shfl_xor(mx, 32, 64));
+      const float m_new = fmaxf(m_run, mx);
+      const float m_use = (m_new == -INFINITY) ? 0.f : m_new;
+      const float alpha = __builtin_amdgcn_exp2f(m_run - m_use);
+      float psum = 0.f;
+#pragma unroll
+      for (int tb = 0; tb < 2; ++tb)
+#pragma unroll
+        for (int e = 0; e < 16; ++e) {
+          const float p = __builtin_amdgcn_exp2f(s[tb][e] - m_use);
+          s[tb][e] = p;
+          psum += p;
+        }
+      l_run = l_run * alpha + psum;
+      m_run = m_new;
+#pragma unroll
+      for (int dt = 0; dt < D / 32; ++dt)
+#pragma unroll
+        for (int e = 0; e < 16; ++e) o[dt][e] *= alpha;
+#pragma unroll
+      for (int tb = 0; tb < 2; ++tb)
+#pragma unroll
+        for (int jj = 0; jj < 2; ++jj) {
+          const bf16x8 pf = pack8(s[tb], 8 * jj);
+#pragma unroll
+          for (int dt = 0; dt < D / 32; ++dt)
+            o[dt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(TL::frag_cols(Vs[cur], dt * 32, tb * 32 + 16 * jj), pf, o[dt], 0, 0, 0);
+        }
+    }
+    if (kt + 1 < ntiles) {
+      TL::store_lds(Ks[cur ^ 1], rk);
+      TL::store_lds(Vs[cur ^ 1], rv);
+    }
+    __syncthreads();
+  }
+  const float l_tot = l_run + __shfl_xor(l_run, 32, 64);
+  const float inv = 1.0f / l_tot;
+  store_transposed<D>(o, O + (int64_t)n * S * H + a * D, H, q, S, inv);
+  if (h == 0 && q < S) lse[((int64_t)n * A + a) * S + q] = (m_run + __builtin_amdgcn_logf(l_tot)) * kLn2;
+}
+
+// ------------------------------------------------------------------------------------ rowsum(dO * O)
+// dvec[n, a, s] = sum_d dO[s, a*D + d] * O[s, a*D + d]; a head's D values sit in D/8 consecutive lanes
+template <int D>
+__global__ void __launch_bounds__(kThreads)
+attn_dvec_kernel(const bf16* __restrict__ O, const bf16* __restrict__ dO, float* __restrict__ dvec, int rows, int S, int H, int A) {
+  const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
+  const int row = blockIdx.x * 4 + wave;
+  if (row >= rows) return;
+  const int n = row / S, s = row % S;
+  for (int v = lane; v < H / 8; v += 64) {
+    float a8[8], b8[8];
+    load_vec<bf16>(O + (int64_t)row * H + v * 8, a8);
+    load_vec<bf16>(dO + (int64_t)row * H + v * 8, b8);
+    float acc = 0.f;
+#pragma unroll
+    for (int i = 0; i < 8; ++i) acc += a8[i] * b8[i];
+#pragma unroll
+    for (int o = 1; o < D / 8; o <<= 1) acc += __shfl_xor(acc, o, 64);
+    if ((lane & (D / 8 - 1)) == 0) dvec[((int64_t)n * A + (v * 8) / D) * S + s] = acc;
+  }
+}
+
+// ------------------------------------------------------------------------------------ dQ
+template <int D, bool CAUSAL>
+__global__ void __launch_bounds__(kThreads)
+attn_dq_kernel(const bf16* __restrict__ qkv, const bf16* __restrict__ dO, const float* __restrict__ lse,
+               const float* __restrict__ dvec, bf16* __restrict__ dqkv, int S, int H, int A, float scale) {
+  typedef Tile<D> TL;
+  extern __shared__ __attribute__((aligned(16))) char smem_raw[];
+  bf16* smem = reinterpret_cast<bf16*>(smem_raw);
+  bf16* Ks[2] = {smem, smem + 2 * TL::ELEMS};
+  bf16* Vs[2] = {smem + TL::ELEMS, smem + 3 * TL::ELEMS};
+
+  const int qt = gridDim.x - 1 - blockIdx.x;
+  const int a = blockIdx.y, n = blockIdx.z;
+  const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63, h = lane >> 5;
+  const int64_t ld = 3 * (int64_t)H;
+  const bf16* base = qkv + (int64_t)n * S * ld + a * D;
+  const int q0 = qt * 128 + wave * 32;
+  const int q = q0 + (lane & 31);
+  const float c2 = scale * kLog2e;
+
+  bf16x8 qf[D / 16], dof[D / 16];
+  load_row_frags<D>(base, ld, q0, S, qf);
+  load_row_frags<D>(dO + (int64_t)n * S * H + a * D, H, q0, S, dof);
+  const int64_t stat = ((int64_t)n * A + a) * S + q;
+  const float lse2 = (q < S) ? lse[stat] * kLog2e : 0.f;
+  const float dv = (q < S) ? dvec[stat] : 0.f;
+
+  f32x16 dq[D / 32];
+#pragma unroll
+  for (int dt = 0; dt < D / 32; ++dt)
+#pragma unroll
+    for (int e = 0; e < 16; ++e) dq[dt][e] = 0.f;
+
+  const int kv_end = CAUSAL ? min(S, qt * 128 + 128) : S;
+  const int ntiles = (kv_end + TILE - 1) / TILE;
+  bf16x8 rk[TL::PER_THREAD], rv[TL::PER_THREAD];
+  TL::load_global(base + H, ld, 0, S, rk);
+  TL::load_global(base + 2 * H, ld, 0, S, rv);
+  TL::store_lds(Ks[0], rk);
+  TL::store_lds(Vs[0], rv);
+  __syncthreads();
+
+  for (int kt = 0; kt < ntiles; ++kt) {
+    const int cur = kt & 1, t0 = kt * TILE;
+    if (kt + 1 < ntiles) {
+      TL::load_global(base + H, ld, t0 + TILE, S, rk);
+      TL::load_global(base + 2 * H, ld, t0 + TILE, S, rv);
+    }
+    if (!CAUSAL || t0 <= q0 + 31) {
+#pragma unroll
+      for (int tb = 0; tb < 2; ++tb) {
+        f32x16 s, dp;
+#pragma unroll
+        for (int e = 0; e < 16; ++e) { s[e] = 0.f; dp[e] = 0.f; }
+#pragma unroll
+        for (int kk = 0; kk < D / 16; ++kk) {
+          s = __builtin_amdgcn_mfma_f32_32x32x16_bf16(TL::frag_rows(Ks[cur], tb * 32, kk * 16), qf[kk], s, 0, 0, 0);
+          dp = __builtin_amdgcn_mfma_f32_32x32x16_bf16(TL::frag_rows(Vs[cur], tb * 32, kk * 16), dof[kk], dp, 0, 0, 0);
+        }
+#pragma unroll
+        for (int e = 0; e < 16; ++e) {
+          const int t = t0 + tb * 32 + 8 * (e >> 2) + 4 * h + (e & 3);
+          float p = __builtin_amdgcn_exp2f(s[e] * c2 - lse2);
+          if (t >= S || (CAUSAL && t > q)) p = 0.f;
+          s[e] = p * (dp[e] - dv);                // dS^T
+        }
+#pragma unroll
+        for (int jj = 0; jj < 2; ++jj) {
+          const bf16x8 df = pack8(s, 8 * jj);
+#pragma unroll
+          for (int dt = 0; dt < D / 32; ++dt)
+            dq[dt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(TL::frag_cols(Ks[cur], dt * 32, tb * 32 + 16 * jj), df, dq[dt], 0, 0, 0);
+        }
+      }
+    }
+    if (kt + 1 < ntiles) {
+      TL::store_lds(Ks[cur ^ 1], rk);
+      TL::store_lds(Vs[cur ^ 1], rv);
+    }
+    __syncthreads();
+  }
+  store_transposed<D>(dq, dqkv + (int64_t)n * S * ld + a * D, ld, q, S, scale);
+}
+
+// ------------------------------------------------------------------------------------ dK, dV
+template <int D, bool CAUSAL>
+__global__ void __launch_bounds__(kThreads)
+attn_dkv_kernel(const bf16* __restrict__ qkv, const bf16* __restrict__ dO, const float* __restrict__ lse,
+                const float* __restrict__ dvec, bf16* __restrict__ dqkv, int S, int H, int A, float scale) {
+  typedef Tile<D> TL;
+  extern __shared__ __attribute__((aligned(16))) char smem_raw[];
+  bf16* smem = reinterpret_cast<bf16*>(smem_raw);
+  bf16* Qs[2] = {smem, smem + 2 * TL::ELEMS};
+  bf16* dOs[2] = {smem + TL::ELEMS, smem + 3 * TL::ELEMS};
+  float* stats = reinterpret_cast<float*>(smem + 4 * TL::ELEMS);   // [2 buffers][lse2 | dvec][64]
+
+  const int tt = blockIdx.x;                       // key tile of 128 keys; early tiles are the heavy ones under a causal mask
+  const int a = blockIdx.y, n = blockIdx.z;
+  const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63, h = lane >> 5;
+  const int64_t ld = 3 * (int64_t)H;
+  const bf16* base = qkv + (int64_t)n * S * ld + a * D;
+  const bf16* dObase = dO + (int64_t)n * S * H + a * D;
+  const float* lse_base = lse + ((int64_t)n * A + a) * S;
+  const float* dv_base = dvec + ((int64_t)n * A + a) * S;
+  const int t0 = tt * 128 + wave * 32;             // this wavefront's 32 keys
+  const int t = t0 + (lane & 31);
+  const float c2 = scale * kLog2e;
+
+  bf16x8 kf[D / 16], vf[D / 16];
+  load_row_frags<D>(base + H, ld, t0, S, kf);
+  load_row_frags<D>(base + 2 * H, ld, t0, S, vf);
+
+  f32x16 dk[D / 32], dvv[D / 32];
+#pragma unroll
+  for (int dt = 0; dt < D / 32; ++dt)
+#pragma unroll
+    for (int e = 0; e < 16; ++e) { dk[dt][e] = 0.f; dvv[dt][e] = 0.f; }
+
+  const int first = CAUSAL ? (tt * 128) / TILE : 0;    // first query tile that can see these keys
+  const int ntiles = (S + TILE - 1) / TILE;
+  bf16x8 rq[TL::PER_THREAD], rdo[TL::PER_THREAD];
+  float rstat = 0.f;                                   // threads 0..63: lse2, 64..127: dvec
+  auto load_stats = [&](int row0) {
+    rstat = 0.f;
+    if (threadIdx.x < 128) {
+      const int r = row0 + (threadIdx.x & 63);
+      if (r < S) rstat = threadIdx.x < 64 ? lse_base[r] * kLog2e : dv_base[r];
+    }
+  };
+  TL::load_global(base, ld, first * TILE, S, rq);
+  TL::load_global(dObase, H, first * TILE, S, rdo);
+  load_stats(first * TILE);
+  TL::store_lds(Qs[0], rq);
+  TL::store_lds(dOs[0], rdo);
+  if (threadIdx.x < 128) stats[threadIdx.x] = rstat;
+  __syncthreads();
+
+  for (int it = first; it < ntiles; ++it) {
+    const int cur = (it - first) & 1, qb0 = it * TILE;
+    if (it + 1 < ntiles) {
+      TL::load_global(base, ld, qb0 + TILE, S, rq);
+      TL::load_global(dObase, H, qb0 + TILE, S, rdo);
+      load_stats(qb0 + TILE);
+    }
+    const float* st = stats + cur * 128;
+    if (!CAUSAL || qb0 + TILE - 1 >= t0) {
+#pragma unroll
+      for (int qb = 0; qb < 2; ++qb) {
+        f32x16 s, dp;
+#pragma unroll
+        for (int e = 0; e < 16; ++e) { s[e] = 0.f; dp[e] = 0.f; }
+#pragma unroll
+        for (int kk = 0; kk < D / 16; ++kk) {
+          s = __builtin_amdgcn_mfma_f32_32x32x16_bf16(TL::frag_rows(Qs[cur], qb * 32, kk * 16), kf[kk], s, 0, 0, 0);
+          dp = __builtin_amdgcn_mfma_f32_32x32x16_bf16(TL::frag_rows(dOs[cur], qb * 32, kk * 16), vf[kk], dp, 0, 0, 0);
+        }
+#pragma unroll
+        for (int j = 0; j < 4; ++j) {
+          const int r = qb * 32 + 8 * j + 4 * h;       // 4 consecutive query rows
+          const f32x4 l4 = *reinterpret_cast<const f32x4*>(st + r);
+          const f32x4 d4 = *reinterpret_cast<const f32x4*>(st + 64 + r);
+#pragma unroll
+          for (int i = 0; i < 4; ++i) {
+            const int e = 4 * j + i;
+            const int qq = qb0 + r + i;
+            float p = __builtin_amdgcn_exp2f(s[e] * c2 - l4[i]);
+            if (qq >= S || (CAUSAL && t > qq)) p = 0.f;
+            s[e] = p;                                  // P
+            dp[e] = p * (dp[e] - d4[i]);               // dS
+          }
+        }
+#pragma unroll
+        for (int jj = 0; jj < 2; ++jj) {
+          const bf16x8 pf = pack8(s, 8 * jj), df = pack8(dp, 8 * jj);
+#pragma unroll
+          for (int dt = 0; dt < D / 32; ++dt) {
+            dvv[dt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(TL::frag_cols(dOs[cur], dt * 32, qb * 32 + 16 * jj), pf, dvv[dt], 0, 0, 0);
+            dk[dt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(TL::frag_cols(Qs[cur], dt * 32, qb * 32 + 16 * jj), df, dk[dt], 0, 0, 0);
+          }
+        }
+      }
+    }
+    if (it + 1 < ntiles) {
+      TL::store_lds(Qs[cur ^ 1], rq);
+      TL::store_lds(dOs[cur ^ 1], rdo);
+      if (threadIdx.x < 128) stats[(cur ^ 1) * 128 + threadIdx.x] = rstat;
+    }
+    __syncthreads();
+  }
+  bf16* out = dqkv + (int64_t)n * S * ld + a * D;
+  store_transposed<D>(dk, out + H, ld, t, S, scale);
+  store_transposed<D>(dvv, out + 2 * H, ld, t, S, 1.0f);
+}
+
+template <typename K>
+int reserve_lds(K kern, size_t bytes) {
+  static bool done = false;       // one flag per kernel instantiation
+  if (done) return CEPHALO_OK;
+  done = true;
+  if (hipFuncSetAttribute(reinterpret_cast<const void*>(kern), hipFuncAttributeMaxDynamicSharedMemorySize, (int)bytes) != hipSuccess)
+    return fail(CEPHALO_EHIP, "attention: cannot reserve %zu B of LDS", bytes);
+  return CEPHALO_OK;
+}
+
+template <int D, bool CAUSAL>
+int fwd_cfg(const bf16* qkv, bf16* O, float* lse, int m, int S, int H, int A, hipStream_t s) {
+  const size_t lds = 4 * (size_t)Tile<D>::ELEMS * sizeof(bf16);
+  auto kern = attn_fwd_kernel<D, CAUSAL>;
+  int rc = reserve_lds(kern, lds);
+  if (rc != CEPHALO_OK) return rc;
+  dim3 grid((S + 127) / 128, A, m);
+  kern<<<grid, kThreads, lds, s>>>(qkv, O, lse, S, H, A, 1.0f / sqrtf((float)D));
+  CEPHALO_CHECK_LAUNCH("attn_fwd_mfma");
+  return CEPHALO_OK;
+}
+
+template <int D, bool CAUSAL>
+int bwd_cfg(const bf16* qkv, const bf16* O, const bf16* dO, const float* lse, float* dvec, bf16* dqkv,
+            int m, int S, int H, int A, hipStream_t s) {
+  const float scale = 1.0f / sqrtf((float)D);
+  const int rows = m * S;
+  attn_dvec_kernel<D><<<(rows + 3) / 4, kThreads, 0, s>>>(O, dO, dvec, rows, S, H, A);
+  dim3 grid((S + 127) / 128, A, m);
+  {
+    const size_t lds = 4 * (size_t)Tile<D>::ELEMS * sizeof(bf16);
+    auto kern = attn_dq_kernel<D, CAUSAL>;
+    int rc = reserve_lds(kern, lds);
+    if (rc != CEPHALO_OK) return rc;
+    kern<<<grid, kThreads, lds, s>>>(qkv, dO, lse, dvec, dqkv, S, H, A, scale);
+  }
+  {
+    const size_t lds = 4 * (size_t)Tile<D>::ELEMS * sizeof(bf16) + 2 * 128 * sizeof(float);
+    auto kern = attn_dkv_kernel<D, CAUSAL>;
+    int rc = reserve_lds(kern, lds);
+    if (rc != CEPHALO_OK) return rc;
+    kern<<<grid, kThreads, lds, s>>>(qkv, dO, lse, dvec, dqkv, S, H, A, scale);
+  }
+  CEPHALO_CHECK_LAUNCH("attn_bwd_mfma");
+  return CEPHALO_OK;
+}
+
+}  // namespace
+
+int launch_attn_fwd_mfma(const bf16* qkv, bf16* O, float* lse, int m, int S, int H, int A, int causal, hipStream_t s) {
+  const int D = H / A;
+  if (H % 8 != 0 || !aligned16(qkv) || !aligned16(O)) return fail(CEPHALO_EINVAL, "attention: rows must be 16-byte aligned");
+  if (D == 64) return causal ? fwd_cfg<64, true>(qkv, O, lse, m, S, H, A, s) : fwd_cfg<64, false>(qkv, O, lse, m, S, H, A, s);
+  if (D == 128) return causal ? fwd_cfg<128, true>(qkv, O, lse, m, S, H, A, s) : fwd_cfg<128, false>(qkv, O, lse, m, S, H, A, s);
+  return fail(CEPHALO_EUNSUPPORTED, "attention (matrix-core kernel): head dim %d is not 64 or 128", D);
+}
+
 int launch_attn_bwd_mfma(const bf16* qkv, const bf16* O, const bf16* dO, const float* lse, float* dvec, bf16* dqkv,
                          int m, int S, int H, int A, int causal, hipStream_t s) {
-  return launch_attn_bwd_simple<bf16>(qkv, O, dO, lse, dvec, dqkv, m, S, H, A, causal, s);
+  const int D = H / A;
+  if (H % 8 != 0 || !aligned16(qkv) || !aligned16(O) || !aligned16(dO) || !aligned16(dqkv))
+    return fail(CEPHALO_EINVAL, "attention: rows must be 16-byte aligned");
+  if (D == 64)
+    return causal ? bwd_cfg<64, true>(qkv, O, dO, lse, dvec, dqkv, m, S, H, A, s)
+                  : bwd_cfg<64, false>(qkv, O, dO, lse, dvec, dqkv, m, S, H, A, s);
+  if (D == 128)
+    return causal ? bwd_cfg<128, true>(qkv, O, dO, lse, dvec, dqkv, m, S, H, A, s)
+                  : bwd_cfg<128, false>(qkv, O, dO, lse, dvec, dqkv, m, S, H, A, s);
+  return fail(CEPHALO_EUNSUPPORTED, "attention (matrix-core kernel): head dim %d is not 64 or 128", D);
 }
-}
+
+}  // namespace cephalo
