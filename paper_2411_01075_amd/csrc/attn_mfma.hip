@@ -22,7 +22,8 @@ typedef bf16 bf16x4 __attribute__((ext_vector_type(4)));
 typedef float f32x16 __attribute__((ext_vector_type(16)));
 typedef float f32x4 __attribute__((ext_vector_type(4)));
 typedef short s16x4 __attribute__((ext_vector_type(4)));
-typedef __attribute__((address_space(3))) s16x4* lds_s16x4_ptr;
+#define LDS_AS __attribute__((address_space(3)))
+typedef LDS_AS bf16 lds_bf16;
 
 constexpr int kThreads = 256;
 constexpr int TILE = 64;            // tokens per LDS tile
@@ -45,28 +46,28 @@ template <int D> struct Tile {
       reg[p] = val;
     }
   }
-  __device__ static void store_lds(bf16* lds, const bf16x8 (&reg)[PER_THREAD]) {
+  __device__ static void store_lds(lds_bf16* lds, const bf16x8 (&reg)[PER_THREAD]) {
 #pragma unroll
     for (int p = 0; p < PER_THREAD; ++p) {
       const int v = threadIdx.x + kThreads * p;
       const int row = v / (D / 8), c = (v % (D / 8)) * 8;
-      *reinterpret_cast<bf16x8*>(lds + row * LD + c) = reg[p];
+      *reinterpret_cast<LDS_AS bf16x8*>(lds + row * LD + c) = reg[p];
     }
   }
   // operand with MFMA rows = tile rows [rb, rb+32), contraction over d in [kk, kk+16)
-  __device__ static bf16x8 frag_rows(const bf16* lds, int rb, int kk) {
+  __device__ static bf16x8 frag_rows(const lds_bf16* lds, int rb, int kk) {
     const int lane = threadIdx.x & 63;
-    return *reinterpret_cast<const bf16x8*>(lds + (rb + (lane & 31)) * LD + kk + (lane >> 5) * 8);
+    return *reinterpret_cast<const LDS_AS bf16x8*>(lds + (rb + (lane & 31)) * LD + kk + (lane >> 5) * 8);
   }
   // operand with MFMA rows = d in [db, db+32), contraction over 16 tile rows in the order the
   // accumulator of a preceding 32x32 product holds them: slot 4c+i of half-wave h is tile row
   // tb + 8c + 4h + i  (tb = first of the 16 rows)
-  __device__ static bf16x8 frag_cols(const bf16* lds, int db, int tb) {
+  __device__ static bf16x8 frag_cols(const lds_bf16* lds, int db, int tb) {
     const int lane = threadIdx.x & 63;
     const int g = lane >> 4, i = lane & 15;
-    const bf16* p0 = lds + (tb + 4 * (g >> 1) + (i >> 2)) * LD + db + 16 * (g & 1) + 4 * (i & 3);
-    s16x4 lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s16x4_ptr)(p0));
-    s16x4 hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s16x4_ptr)(p0 + 8 * LD));
+    const lds_bf16* p0 = lds + (tb + 4 * (g >> 1) + (i >> 2)) * LD + db + 16 * (g & 1) + 4 * (i & 3);
+    s16x4 lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16((LDS_AS s16x4*)(p0));
+    s16x4 hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16((LDS_AS s16x4*)(p0 + 8 * LD));
     union { struct { s16x4 a, b; } s; bf16x8 v; } u;
     u.s.a = lo; u.s.b = hi;
     return u.v;
@@ -115,9 +116,9 @@ __global__ void __launch_bounds__(kThreads)
 attn_fwd_kernel(const bf16* __restrict__ qkv, bf16* __restrict__ O, float* __restrict__ lse, int S, int H, int A, float scale) {
   typedef Tile<D> TL;
   extern __shared__ __attribute__((aligned(16))) char smem_raw[];
-  bf16* smem = reinterpret_cast<bf16*>(smem_raw);
-  bf16* Ks[2] = {smem, smem + 2 * TL::ELEMS};
-  bf16* Vs[2] = {smem + TL::ELEMS, smem + 3 * TL::ELEMS};
+  lds_bf16* smem = (lds_bf16*)smem_raw;
+  auto Ks = [&](int st) { return smem + st * 2 * TL::ELEMS; };
+  auto Vs = [&](int st) { return smem + st * 2 * TL::ELEMS + TL::ELEMS; };
 
   const int qt = gridDim.x - 1 - blockIdx.x;       // heavy (late) causal tiles first
   const int a = blockIdx.y, n = blockIdx.z;
@@ -143,8 +144,8 @@ attn_fwd_kernel(const bf16* __restrict__ qkv, bf16* __restrict__ O, float* __res
   bf16x8 rk[TL::PER_THREAD], rv[TL::PER_THREAD];
   TL::load_global(base + H, ld, 0, S, rk);
   TL::load_global(base + 2 * H, ld, 0, S, rv);
-  TL::store_lds(Ks[0], rk);
-  TL::store_lds(Vs[0], rv);
+  TL::store_lds(Ks(0), rk);
+  TL::store_lds(Vs(0), rv);
   __syncthreads();
 
   for (int kt = 0; kt < ntiles; ++kt) {
@@ -161,7 +162,7 @@ attn_fwd_kernel(const bf16* __restrict__ qkv, bf16* __restrict__ O, float* __res
         for (int e = 0; e < 16; ++e) s[tb][e] = 0.f;
 #pragma unroll
         for (int kk = 0; kk < D / 16; ++kk)
-          s[tb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(TL::frag_rows(Ks[cur], tb * 32, kk * 16), qf[kk], s[tb], 0, 0, 0);
+          s[tb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(TL::frag_rows(Ks(cur), tb * 32, kk * 16), qf[kk], s[tb], 0, 0, 0);
       }
       float mx = -INFINITY;
 #pragma unroll
@@ -200,12 +201,12 @@ attn_fwd_kernel(const bf16* __restrict__ qkv, bf16* __restrict__ O, float* __res
           const bf16x8 pf = pack8(s[tb], 8 * jj);
 #pragma unroll
           for (int dt = 0; dt < D / 32; ++dt)
-            o[dt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(TL::frag_cols(Vs[cur], dt * 32, tb * 32 + 16 * jj), pf, o[dt], 0, 0, 0);
+            o[dt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(TL::frag_cols(Vs(cur), dt * 32, tb * 32 + 16 * jj), pf, o[dt], 0, 0, 0);
         }
     }
     if (kt + 1 < ntiles) {
-      TL::store_lds(Ks[cur ^ 1], rk);
-      TL::store_lds(Vs[cur ^ 1], rv);
+      TL::store_lds(Ks(cur ^ 1), rk);
+      TL::store_lds(Vs(cur ^ 1), rv);
     }
     __syncthreads();
   }
@@ -244,9 +245,9 @@ attn_dq_kernel(const bf16* __restrict__ qkv, const bf16* __restrict__ dO, const 
                const float* __restrict__ dvec, bf16* __restrict__ dqkv, int S, int H, int A, float scale) {
   typedef Tile<D> TL;
   extern __shared__ __attribute__((aligned(16))) char smem_raw[];
-  bf16* smem = reinterpret_cast<bf16*>(smem_raw);
-  bf16* Ks[2] = {smem, smem + 2 * TL::ELEMS};
-  bf16* Vs[2] = {smem + TL::ELEMS, smem + 3 * TL::ELEMS};
+  lds_bf16* smem = (lds_bf16*)smem_raw;
+  auto Ks = [&](int st) { return smem + st * 2 * TL::ELEMS; };
+  auto Vs = [&](int st) { return smem + st * 2 * TL::ELEMS + TL::ELEMS; };
 
   const int qt = gridDim.x - 1 - blockIdx.x;
   const int a = blockIdx.y, n = blockIdx.z;
@@ -275,8 +276,8 @@ attn_dq_kernel(const bf16* __restrict__ qkv, const bf16* __restrict__ dO, const 
   bf16x8 rk[TL::PER_THREAD], rv[TL::PER_THREAD];
   TL::load_global(base + H, ld, 0, S, rk);
   TL::load_global(base + 2 * H, ld, 0, S, rv);
-  TL::store_lds(Ks[0], rk);
-  TL::store_lds(Vs[0], rv);
+  TL::store_lds(Ks(0), rk);
+  TL::store_lds(Vs(0), rv);
   __syncthreads();
 
   for (int kt = 0; kt < ntiles; ++kt) {
@@ -293,8 +294,8 @@ attn_dq_kernel(const bf16* __restrict__ qkv, const bf16* __restrict__ dO, const 
         for (int e = 0; e < 16; ++e) { s[e] = 0.f; dp[e] = 0.f; }
 #pragma unroll
         for (int kk = 0; kk < D / 16; ++kk) {
-          s = __builtin_amdgcn_mfma_f32_32x32x16_bf16(TL::frag_rows(Ks[cur], tb * 32, kk * 16), qf[kk], s, 0, 0, 0);
-          dp = __builtin_amdgcn_mfma_f32_32x32x16_bf16(TL::frag_rows(Vs[cur], tb * 32, kk * 16), dof[kk], dp, 0, 0, 0);
+          s = __builtin_amdgcn_mfma_f32_32x32x16_bf16(TL::frag_rows(Ks(cur), tb * 32, kk * 16), qf[kk], s, 0, 0, 0);
+          dp = __builtin_amdgcn_mfma_f32_32x32x16_bf16(TL::frag_rows(Vs(cur), tb * 32, kk * 16), dof[kk], dp, 0, 0, 0);
         }
 #pragma unroll
         for (int e = 0; e < 16; ++e) {
@@ -308,13 +309,13 @@ attn_dq_kernel(const bf16* __restrict__ qkv, const bf16* __restrict__ dO, const 
           const bf16x8 df = pack8(s, 8 * jj);
 #pragma unroll
           for (int dt = 0; dt < D / 32; ++dt)
-            dq[dt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(TL::frag_cols(Ks[cur], dt * 32, tb * 32 + 16 * jj), df, dq[dt], 0, 0, 0);
+            dq[dt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(TL::frag_cols(Ks(cur), dt * 32, tb * 32 + 16 * jj), df, dq[dt], 0, 0, 0);
         }
       }
     }
     if (kt + 1 < ntiles) {
-      TL::store_lds(Ks[cur ^ 1], rk);
-      TL::store_lds(Vs[cur ^ 1], rv);
+      TL::store_lds(Ks(cur ^ 1), rk);
+      TL::store_lds(Vs(cur ^ 1), rv);
     }
     __syncthreads();
   }
@@ -328,10 +329,10 @@ attn_dkv_kernel(const bf16* __restrict__ qkv, const bf16* __restrict__ dO, const
                 const float* __restrict__ dvec, bf16* __restrict__ dqkv, int S, int H, int A, float scale) {
   typedef Tile<D> TL;
   extern __shared__ __attribute__((aligned(16))) char smem_raw[];
-  bf16* smem = reinterpret_cast<bf16*>(smem_raw);
-  bf16* Qs[2] = {smem, smem + 2 * TL::ELEMS};
-  bf16* dOs[2] = {smem + TL::ELEMS, smem + 3 * TL::ELEMS};
-  float* stats = reinterpret_cast<float*>(smem + 4 * TL::ELEMS);   // [2 buffers][lse2 | dvec][64]
+  lds_bf16* smem = (lds_bf16*)smem_raw;
+  auto Qs = [&](int st) { return smem + st * 2 * TL::ELEMS; };
+  auto dOs = [&](int st) { return smem + st * 2 * TL::ELEMS + TL::ELEMS; };
+  LDS_AS float* stats = (LDS_AS float*)(smem + 4 * TL::ELEMS);   // [2 buffers][lse2 | dvec][64]
 
   const int tt = blockIdx.x;                       // key tile of 128 keys; early tiles are the heavy ones under a causal mask
   const int a = blockIdx.y, n = blockIdx.z;
@@ -369,8 +370,8 @@ attn_dkv_kernel(const bf16* __restrict__ qkv, const bf16* __restrict__ dO, const
   TL::load_global(base, ld, first * TILE, S, rq);
   TL::load_global(dObase, H, first * TILE, S, rdo);
   load_stats(first * TILE);
-  TL::store_lds(Qs[0], rq);
-  TL::store_lds(dOs[0], rdo);
+  TL::store_lds(Qs(0), rq);
+  TL::store_lds(dOs(0), rdo);
   if (threadIdx.x < 128) stats[threadIdx.x] = rstat;
   __syncthreads();
 
@@ -381,7 +382,7 @@ attn_dkv_kernel(const bf16* __restrict__ qkv, const bf16* __restrict__ dO, const
       TL::load_global(dObase, H, qb0 + TILE, S, rdo);
       load_stats(qb0 + TILE);
     }
-    const float* st = stats + cur * 128;
+    const LDS_AS float* st = stats + cur * 128;
     if (!CAUSAL || qb0 + TILE - 1 >= t0) {
 #pragma unroll
       for (int qb = 0; qb < 2; ++qb) {
@@ -390,14 +391,14 @@ attn_dkv_kernel(const bf16* __restrict__ qkv, const bf16* __restrict__ dO, const
         for (int e = 0; e < 16; ++e) { s[e] = 0.f; dp[e] = 0.f; }
 #pragma unroll
         for (int kk = 0; kk < D / 16; ++kk) {
-          s = __builtin_amdgcn_mfma_f32_32x32x16_bf16(TL::frag_rows(Qs[cur], qb * 32, kk * 16), kf[kk], s, 0, 0, 0);
-          dp = __builtin_amdgcn_mfma_f32_32x32x16_bf16(TL::frag_rows(dOs[cur], qb * 32, kk * 16), vf[kk], dp, 0, 0, 0);
+          s = __builtin_amdgcn_mfma_f32_32x32x16_bf16(TL::frag_rows(Qs(cur), qb * 32, kk * 16), kf[kk], s, 0, 0, 0);
+          dp = __builtin_amdgcn_mfma_f32_32x32x16_bf16(TL::frag_rows(dOs(cur), qb * 32, kk * 16), vf[kk], dp, 0, 0, 0);
         }
 #pragma unroll
         for (int j = 0; j < 4; ++j) {
           const int r = qb * 32 + 8 * j + 4 * h;       // 4 consecutive query rows
-          const f32x4 l4 = *reinterpret_cast<const f32x4*>(st + r);
-          const f32x4 d4 = *reinterpret_cast<const f32x4*>(st + 64 + r);
+          const f32x4 l4 = *reinterpret_cast<const LDS_AS f32x4*>(st + r);
+          const f32x4 d4 = *reinterpret_cast<const LDS_AS f32x4*>(st + 64 + r);
 #pragma unroll
           for (int i = 0; i < 4; ++i) {
             const int e = 4 * j + i;
@@ -413,15 +414,15 @@ attn_dkv_kernel(const bf16* __restrict__ qkv, const bf16* __restrict__ dO, const
           const bf16x8 pf = pack8(s, 8 * jj), df = pack8(dp, 8 * jj);
 #pragma unroll
           for (int dt = 0; dt < D / 32; ++dt) {
-            dvv[dt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(TL::frag_cols(dOs[cur], dt * 32, qb * 32 + 16 * jj), pf, dvv[dt], 0, 0, 0);
-            dk[dt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(TL::frag_cols(Qs[cur], dt * 32, qb * 32 + 16 * jj), df, dk[dt], 0, 0, 0);
+            dvv[dt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(TL::frag_cols(dOs(cur), dt * 32, qb * 32 + 16 * jj), pf, dvv[dt], 0, 0, 0);
+            dk[dt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(TL::frag_cols(Qs(cur), dt * 32, qb * 32 + 16 * jj), df, dk[dt], 0, 0, 0);
           }
         }
       }
     }
     if (it + 1 < ntiles) {
-      TL::store_lds(Qs[cur ^ 1], rq);
-      TL::store_lds(dOs[cur ^ 1], rdo);
+      TL::store_lds(Qs(cur ^ 1), rq);
+      TL::store_lds(dOs(cur ^ 1), rdo);
       if (threadIdx.x < 128) stats[(cur ^ 1) * 128 + threadIdx.x] = rstat;
     }
     __syncthreads();

@@ -20,62 +20,85 @@ namespace cephalo {
 namespace {
 
 typedef bf16 bf16x8 __attribute__((ext_vector_type(8)));
-typedef bf16 bf16x4 __attribute__((ext_vector_type(4)));
 typedef float f32x16 __attribute__((ext_vector_type(16)));
 typedef short s16x4 __attribute__((ext_vector_type(4)));
-typedef __attribute__((address_space(3))) s16x4* lds_s16x4_ptr;
+typedef unsigned int u32x4 __attribute__((ext_vector_type(4)));
+#define LDS_AS __attribute__((address_space(3)))
+typedef LDS_AS bf16 lds_bf16;
 
 constexpr int kThreads = 256;
 constexpr int BK = 64;    // k-slab
-constexpr int PAD = 8;    // elements of row padding in LDS (16 bytes)
+constexpr unsigned kOob = 0x80000000u;   // byte offset beyond any buffer: such a buffer load returns zero
+
+// Buffer descriptor over `bytes` bytes at p: loads at offsets >= bytes return 0 (hardware range check).
+__device__ __forceinline__ __amdgpu_buffer_rsrc_t make_rsrc(const void* p, unsigned bytes) {
+  return __builtin_amdgcn_make_buffer_rsrc(const_cast<void*>(p), 0, bytes, 0x00020000);
+}
 
 // One operand's tile: ROWS matrix rows (m or n) by BK k-values.
+//   KFAST  : LDS [row][k], row pitch BK+8 elements; the 16 lanes of a 16-byte read phase fall in 16 different
+//            16-byte bank groups (pitch 144 B = 9 * 16 B).
+//   !KFAST : LDS [k][row], row pitch ROWS+32 elements; the four k-rows a transposing read touches are 64 B apart
+//            modulo 256 B, so a 16-lane group covers the banks once.
 template <int ROWS, bool KFAST>
 struct OperandTile {
-  static constexpr int LD = KFAST ? (BK + PAD) : (ROWS + PAD);   // LDS row stride, elements
+  static constexpr int LD = KFAST ? (BK + 8) : (ROWS + 32);      // LDS row pitch, elements
   static constexpr int ELEMS = KFAST ? ROWS * LD : BK * LD;
   static constexpr int VECS = ROWS * BK / 8;                     // 16-byte vectors per tile
   static constexpr int PER_THREAD = VECS / kThreads;
   static_assert(VECS % kThreads == 0, "tile must split evenly over the threads");
 
-  // global -> registers; rows/k outside the matrix read as zero
-  __device__ static void load_global(const bf16* __restrict__ g, int64_t rs, int64_t cs, int row0, int k0,
-                                     int nrows, int K, bf16x8 (&reg)[PER_THREAD]) {
+  __device__ static void vec_coords(int p, int& row, int& k) {
+    const int v = threadIdx.x + kThreads * p;
+    if (KFAST) { row = v / (BK / 8); k = (v % (BK / 8)) * 8; }
+    else       { k = v / (ROWS / 8); row = (v % (ROWS / 8)) * 8; }
+  }
+  // byte offsets of this thread's vectors for k-slab 0; rows outside the matrix get the out-of-range mark
+  __device__ static void init_offsets(int64_t rs, int64_t cs, int row0, int nrows, unsigned (&off)[PER_THREAD]) {
 #pragma unroll
     for (int p = 0; p < PER_THREAD; ++p) {
-      const int v = threadIdx.x + kThreads * p;
       int row, k;
-      if (KFAST) { row = v / (BK / 8); k = (v % (BK / 8)) * 8; }
-      else       { k = v / (ROWS / 8); row = (v % (ROWS / 8)) * 8; }
-      bf16x8 val = {0, 0, 0, 0, 0, 0, 0, 0};
-      if (row0 + row < nrows && k0 + k < K)
-        val = *reinterpret_cast<const bf16x8*>(g + (int64_t)(row0 + row) * rs + (int64_t)(k0 + k) * cs);
-      reg[p] = val;
+      vec_coords(p, row, k);
+      const int64_t e = (int64_t)(row0 + row) * rs + (int64_t)k * cs;
+      off[p] = (row0 + row < nrows) ? (unsigned)(e * 2) : kOob;
     }
   }
-  __device__ static void store_lds(bf16* lds, const bf16x8 (&reg)[PER_THREAD]) {
+  // global -> registers for the slab starting at k0 (off[] already points at that slab)
+  __device__ static void load_global(__amdgpu_buffer_rsrc_t rsrc, const unsigned (&off)[PER_THREAD], int k0, int K,
+                                     u32x4 (&reg)[PER_THREAD]) {
 #pragma unroll
     for (int p = 0; p < PER_THREAD; ++p) {
-      const int v = threadIdx.x + kThreads * p;
       int row, k;
-      if (KFAST) { row = v / (BK / 8); k = (v % (BK / 8)) * 8; }
-      else       { k = v / (ROWS / 8); row = (v % (ROWS / 8)) * 8; }
-      bf16* dst = KFAST ? (lds + row * LD + k) : (lds + k * LD + row);
-      *reinterpret_cast<bf16x8*>(dst) = reg[p];
+      vec_coords(p, row, k);
+      const unsigned o = (k0 + k < K) ? off[p] : kOob;
+      reg[p] = __builtin_amdgcn_raw_buffer_load_b128(rsrc, o, 0, 0);
+    }
+  }
+  __device__ static void advance(unsigned (&off)[PER_THREAD], unsigned slab_bytes) {
+#pragma unroll
+    for (int p = 0; p < PER_THREAD; ++p) off[p] += slab_bytes;    // the mark stays out of range (no wrap below 2^31 steps)
+  }
+  __device__ static void store_lds(lds_bf16* lds, const u32x4 (&reg)[PER_THREAD]) {
+#pragma unroll
+    for (int p = 0; p < PER_THREAD; ++p) {
+      int row, k;
+      vec_coords(p, row, k);
+      lds_bf16* dst = KFAST ? (lds + row * LD + k) : (lds + k * LD + row);
+      *reinterpret_cast<LDS_AS u32x4*>(dst) = reg[p];
     }
   }
   // MFMA 32x32x16 operand fragment: rows [rb, rb+32), k-values [kk, kk+16) of the tile
-  __device__ static bf16x8 fragment(const bf16* lds, int rb, int kk) {
+  __device__ static bf16x8 fragment(const lds_bf16* lds, int rb, int kk) {
     const int lane = threadIdx.x & 63;
     if (KFAST) {
-      return *reinterpret_cast<const bf16x8*>(lds + (rb + (lane & 31)) * LD + kk + (lane >> 5) * 8);
+      return *reinterpret_cast<const LDS_AS bf16x8*>(lds + (rb + (lane & 31)) * LD + kk + (lane >> 5) * 8);
     } else {
       const int g = lane >> 4, i = lane & 15;
       const int r = rb + 16 * (g & 1) + 4 * (i & 3);
       const int k = kk + 8 * (g >> 1) + (i >> 2);
-      const bf16* p0 = lds + k * LD + r;
-      s16x4 lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s16x4_ptr)(p0));
-      s16x4 hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s16x4_ptr)(p0 + 4 * LD));
+      const lds_bf16* p0 = lds + k * LD + r;
+      s16x4 lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16((LDS_AS s16x4*)(p0));
+      s16x4 hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16((LDS_AS s16x4*)(p0 + 4 * LD));
       union { struct { s16x4 a, b; } s; bf16x8 v; } u;
       u.s.a = lo; u.s.b = hi;
       return u.v;
@@ -89,10 +112,9 @@ __global__ void __launch_bounds__(kThreads) gemm_mfma_kernel(GemmArgs<bf16> a, i
   typedef OperandTile<BN, BKF> TB;
   constexpr int WTM = BM / 2, WTN = BN / 2;     // wavefront tile (2x2 wavefronts)
   constexpr int MI = WTM / 32, NI = WTN / 32;
+  constexpr int STAGE = TA::ELEMS + TB::ELEMS;
   extern __shared__ __attribute__((aligned(16))) char smem_raw[];
-  bf16* smem = reinterpret_cast<bf16*>(smem_raw);
-  bf16* As[2] = {smem, smem + TA::ELEMS + TB::ELEMS};
-  bf16* Bs[2] = {smem + TA::ELEMS, smem + 2 * TA::ELEMS + TB::ELEMS};
+  lds_bf16* smem = (lds_bf16*)smem_raw;
 
   // Blocks are dealt round-robin to the 8 XCDs; give each XCD a contiguous run of tiles so
   // that neighbours in the tile order (which share operand panels) share an L2.
@@ -112,27 +134,39 @@ __global__ void __launch_bounds__(kThreads) gemm_mfma_kernel(GemmArgs<bf16> a, i
 #pragma unroll
       for (int e = 0; e < 16; ++e) acc[i][j][e] = 0.f;
 
-  bf16x8 ra[TA::PER_THREAD], rb[TB::PER_THREAD];
-  TA::load_global(a.A, a.a_rs, a.a_cs, m0, 0, a.M, a.K, ra);
-  TB::load_global(a.B, a.b_rs, a.b_cs, n0, 0, a.N, a.K, rb);
-  TA::store_lds(As[0], ra);
-  TB::store_lds(Bs[0], rb);
+  // operand extents in bytes (dense matrices: the strided pitch times the number of strided steps)
+  const unsigned a_bytes = (unsigned)(2 * (AK ? (int64_t)a.M * a.a_rs : (int64_t)a.K * a.a_cs));
+  const unsigned b_bytes = (unsigned)(2 * (BKF ? (int64_t)a.N * a.b_rs : (int64_t)a.K * a.b_cs));
+  const __amdgpu_buffer_rsrc_t ra_rsrc = make_rsrc(a.A, a_bytes), rb_rsrc = make_rsrc(a.B, b_bytes);
+  unsigned offa[TA::PER_THREAD], offb[TB::PER_THREAD];
+  TA::init_offsets(a.a_rs, a.a_cs, m0, a.M, offa);
+  TB::init_offsets(a.b_rs, a.b_cs, n0, a.N, offb);
+  const unsigned a_step = (unsigned)(2 * BK * a.a_cs), b_step = (unsigned)(2 * BK * a.b_cs);
+
+  u32x4 ra[TA::PER_THREAD], rb[TB::PER_THREAD];
+  TA::load_global(ra_rsrc, offa, 0, a.K, ra);
+  TB::load_global(rb_rsrc, offb, 0, a.K, rb);
+  TA::store_lds(smem, ra);
+  TB::store_lds(smem + TA::ELEMS, rb);
   __syncthreads();
 
   const int nk = (a.K + BK - 1) / BK;
   for (int kt = 0; kt < nk; ++kt) {
-    const int cur = kt & 1;
+    const lds_bf16* As = smem + (kt & 1) * STAGE;
+    const lds_bf16* Bs = As + TA::ELEMS;
     if (kt + 1 < nk) {
-      TA::load_global(a.A, a.a_rs, a.a_cs, m0, (kt + 1) * BK, a.M, a.K, ra);
-      TB::load_global(a.B, a.b_rs, a.b_cs, n0, (kt + 1) * BK, a.N, a.K, rb);
+      TA::advance(offa, a_step);
+      TB::advance(offb, b_step);
+      TA::load_global(ra_rsrc, offa, (kt + 1) * BK, a.K, ra);
+      TB::load_global(rb_rsrc, offb, (kt + 1) * BK, a.K, rb);
     }
 #pragma unroll
     for (int kk = 0; kk < BK; kk += 16) {
       bf16x8 fa[MI], fb[NI];
 #pragma unroll
-      for (int i = 0; i < MI; ++i) fa[i] = TA::fragment(As[cur], wm + 32 * i, kk);
+      for (int i = 0; i < MI; ++i) fa[i] = TA::fragment(As, wm + 32 * i, kk);
 #pragma unroll
-      for (int j = 0; j < NI; ++j) fb[j] = TB::fragment(Bs[cur], wn + 32 * j, kk);
+      for (int j = 0; j < NI; ++j) fb[j] = TB::fragment(Bs, wn + 32 * j, kk);
 #pragma unroll
       for (int i = 0; i < MI; ++i)
 #pragma unroll
@@ -140,8 +174,9 @@ __global__ void __launch_bounds__(kThreads) gemm_mfma_kernel(GemmArgs<bf16> a, i
           acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa[i], fb[j], acc[i][j], 0, 0, 0);
     }
     if (kt + 1 < nk) {
-      TA::store_lds(As[cur ^ 1], ra);
-      TB::store_lds(Bs[cur ^ 1], rb);
+      lds_bf16* An = smem + ((kt + 1) & 1) * STAGE;
+      TA::store_lds(An, ra);
+      TB::store_lds(An + TA::ELEMS, rb);
     }
     __syncthreads();
   }
@@ -212,7 +247,9 @@ int launch_gemm_mfma(const GemmArgs<bf16>& a, hipStream_t s) {
   // 16-byte vector loads need the contiguous extent and the strided pitch to be multiples of 8 elements.
   const bool ok_a = ak ? (a.K % 8 == 0 && a.a_rs % 8 == 0) : (a.a_rs == 1 && a.M % 8 == 0 && a.a_cs % 8 == 0);
   const bool ok_b = bk ? (a.K % 8 == 0 && a.b_rs % 8 == 0) : (a.b_rs == 1 && a.N % 8 == 0 && a.b_cs % 8 == 0);
-  if (!ok_a || !ok_b || !aligned16(a.A) || !aligned16(a.B)) return launch_gemm_simple<bf16>(a, s);
+  const int64_t ext_a = 2 * (ak ? (int64_t)a.M * a.a_rs : (int64_t)a.K * a.a_cs), ext_b = 2 * (bk ? (int64_t)a.N * a.b_rs : (int64_t)a.K * a.b_cs);
+  const bool small = ext_a < (int64_t)0x7fffffff && ext_b < (int64_t)0x7fffffff;   // 32-bit buffer extents and offsets
+  if (!ok_a || !ok_b || !small || !aligned16(a.A) || !aligned16(a.B)) return launch_gemm_simple<bf16>(a, s);
   // Only the layout/epilogue pairs a linear layer produces are instantiated.
   if (ak && bk) {          // forward: Y = X W^T
     switch (a.epi) {
