@@ -5,16 +5,27 @@
 //   forward   Y  = X W^T      A k-contiguous, B k-contiguous
 //   dgrad     dX = dY W       A k-contiguous, B n-contiguous (k strided)
 //   wgrad     dW = dY^T X     A m-contiguous, B n-contiguous (both strided along k = tokens)
-// A k-contiguous operand is staged in LDS as [row][k] and its MFMA fragment (8 consecutive k of
-// one row per lane) is one 16-byte LDS read.  A row-contiguous operand is staged as [k][row] and
-// its fragment is fetched with the transposing LDS read of gfx950 (ds_read_b64_tr_b16): within
-// each 16-lane group, lane i supplies the address of 4 consecutive rows at k-row (i/4) and
-// receives the 4 k-values of row i -- exactly the MFMA operand layout.
 //
-// Tiling: 256 threads = 4 wavefronts in a 2x2 grid; v_mfma_f32_32x32x16_bf16; k-slab 64;
-// global->register->LDS double buffering (next slab's global loads are in flight during the
-// current slab's MFMAs; one barrier per slab).
+// Data path.  The kernel is bound by LDS bandwidth before it is bound by the matrix cores, so
+// the tile is as large as the accumulators allow (256 x 256 per block, 128 x 128 per wavefront:
+// every LDS byte read feeds the most MFMAs) and operand slabs go from global memory straight
+// into LDS (buffer_load ... lds, 16 bytes per lane) without passing through registers.  Those
+// loads write 64 lanes x 16 B = 1 KiB of consecutive LDS per instruction, so rows cannot be
+// padded; bank conflicts are avoided by an XOR swizzle of the 16-byte chunk index, applied to
+// the global address each lane fetches and again when fragments are read:
+//   k-contiguous tile [row][64 k]  (128 B rows):  chunk' = chunk ^ ((row >> 1) & 7)
+//   row-contiguous tile [k][rows]                 chunk' = chunk ^ ((k & 3) << 2)
+// A k-contiguous operand's MFMA fragment (8 consecutive k of one row per lane) is one 16-byte
+// LDS read.  A row-contiguous operand's fragment is fetched with the transposing LDS read of
+// gfx950 (ds_read_b64_tr_b16): within each 16-lane group, lane i supplies the address of 4
+// consecutive rows at k-row (i/4) and receives the 4 k-values of row i -- the MFMA layout.
+// Rows or k-values outside the matrix are never read: their buffer offsets are out of the
+// descriptor's range and the hardware returns zeros.
+//
+// Pipeline: two LDS stages; the loads of slab kt+1 are in flight while slab kt is multiplied;
+// one barrier per slab.  256 threads = 4 wavefronts in a 2x2 grid; v_mfma_f32_32x32x16_bf16.
 #include "kernels.h"
+#include <cstdlib>
 
 namespace cephalo {
 namespace {
@@ -22,9 +33,7 @@ namespace {
 typedef bf16 bf16x8 __attribute__((ext_vector_type(8)));
 typedef float f32x16 __attribute__((ext_vector_type(16)));
 typedef short s16x4 __attribute__((ext_vector_type(4)));
-typedef unsigned int u32x4 __attribute__((ext_vector_type(4)));
 #define LDS_AS __attribute__((address_space(3)))
-typedef LDS_AS bf16 lds_bf16;
 
 constexpr int kThreads = 256;
 constexpr int BK = 64;    // k-slab
@@ -35,70 +44,92 @@ __device__ __forceinline__ __amdgpu_buffer_rsrc_t make_rsrc(const void* p, unsig
   return __builtin_amdgcn_make_buffer_rsrc(const_cast<void*>(p), 0, bytes, 0x00020000);
 }
 
-// One operand's tile: ROWS matrix rows (m or n) by BK k-values.
-//   KFAST  : LDS [row][k], row pitch BK+8 elements; the 16 lanes of a 16-byte read phase fall in 16 different
-//            16-byte bank groups (pitch 144 B = 9 * 16 B).
-//   !KFAST : LDS [k][row], row pitch ROWS+32 elements; the four k-rows a transposing read touches are 64 B apart
-//            modulo 256 B, so a 16-lane group covers the banks once.
+// One operand's tile: ROWS matrix rows (m or n) by BK k-values, ROWS*BK*2 bytes of LDS, unpadded.
 template <int ROWS, bool KFAST>
 struct OperandTile {
-  static constexpr int LD = KFAST ? (BK + 8) : (ROWS + 32);      // LDS row pitch, elements
-  static constexpr int ELEMS = KFAST ? ROWS * LD : BK * LD;
-  static constexpr int VECS = ROWS * BK / 8;                     // 16-byte vectors per tile
-  static constexpr int PER_THREAD = VECS / kThreads;
-  static_assert(VECS % kThreads == 0, "tile must split evenly over the threads");
+  static constexpr int BYTES = ROWS * BK * 2;
+  static constexpr int INSTR = BYTES / 1024;            // direct-to-LDS load instructions per tile (1 KiB each)
+  static constexpr int PER_WAVE = INSTR / 4;
+  static constexpr int PITCH = KFAST ? BK * 2 : ROWS * 2;   // bytes per LDS row
+  static constexpr int CHUNKS = PITCH / 16;                 // 16-byte chunks per LDS row
+  static_assert(INSTR % 4 == 0, "tile must split evenly over the 4 wavefronts");
+  static_assert(KFAST || ROWS >= 128, "row-contiguous tiles need at least 128 rows");
 
-  __device__ static void vec_coords(int p, int& row, int& k) {
-    const int v = threadIdx.x + kThreads * p;
-    if (KFAST) { row = v / (BK / 8); k = (v % (BK / 8)) * 8; }
-    else       { k = v / (ROWS / 8); row = (v % (ROWS / 8)) * 8; }
+  // LDS row / chunk slot that lane `lane` of load instruction `j` of this wavefront fills, and the
+  // (un-swizzled) chunk of the tile that belongs there
+  __device__ static void slot(int j, int& line, int& chunk) {
+    const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
+    const int s = (wave * PER_WAVE + j) * 64 + lane;    // 16-byte slot index within the tile
+    line = s / CHUNKS;
+    const int cs = s % CHUNKS;
+    chunk = KFAST ? (cs ^ ((line >> 1) & 7)) : (cs ^ ((line & 3) << 2));
   }
-  // byte offsets of this thread's vectors for k-slab 0; rows outside the matrix get the out-of-range mark
-  __device__ static void init_offsets(int64_t rs, int64_t cs, int row0, int nrows, unsigned (&off)[PER_THREAD]) {
+  // byte offsets into the operand for k-slab 0; rows outside the matrix get the out-of-range mark
+  __device__ static void init_offsets(int64_t rs, int64_t cs, int row0, int nrows, int K, unsigned (&off)[PER_WAVE]) {
 #pragma unroll
-    for (int p = 0; p < PER_THREAD; ++p) {
-      int row, k;
-      vec_coords(p, row, k);
-      const int64_t e = (int64_t)(row0 + row) * rs + (int64_t)k * cs;
-      off[p] = (row0 + row < nrows) ? (unsigned)(e * 2) : kOob;
+    for (int j = 0; j < PER_WAVE; ++j) {
+      int line, chunk;
+      slot(j, line, chunk);
+      if (KFAST) {      // line = tile row, chunk = 8 k-values
+        const int64_t e = (int64_t)(row0 + line) * rs + chunk * 8;
+        off[j] = (row0 + line < nrows) ? (unsigned)(e * 2) : kOob;
+      } else {          // line = k, chunk = 8 rows
+        const int64_t e = (int64_t)line * cs + row0 + chunk * 8;
+        off[j] = (row0 + chunk * 8 < nrows) ? (unsigned)(e * 2) : kOob;
+      }
+    }
+    (void)K;
+  }
+  // issue the loads of the slab starting at k0 into the LDS tile at `lds` (off[] already points at that slab)
+  __device__ static void load_slab(__amdgpu_buffer_rsrc_t rsrc, const unsigned (&off)[PER_WAVE], int k0, int K, LDS_AS char* lds) {
+    const int wave = threadIdx.x >> 6;
+#pragma unroll
+    for (int j = 0; j < PER_WAVE; ++j) {
+      unsigned o = off[j];
+      if (KFAST) {      // a ragged last slab: chunks past K must read as zero, not as the next row
+        int line, chunk;
+        slot(j, line, chunk);
+        if (k0 + chunk * 8 >= K) o = kOob;
+      }
+      __builtin_amdgcn_raw_ptr_buffer_load_lds(rsrc, (LDS_AS void*)(lds + (wave * PER_WAVE + j) * 1024), 16, o, 0, 0, 0);
     }
   }
-  // global -> registers for the slab starting at k0 (off[] already points at that slab)
-  __device__ static void load_global(__amdgpu_buffer_rsrc_t rsrc, const unsigned (&off)[PER_THREAD], int k0, int K,
-                                     u32x4 (&reg)[PER_THREAD]) {
+  __device__ static void advance(unsigned (&off)[PER_WAVE], unsigned slab_bytes) {
 #pragma unroll
-    for (int p = 0; p < PER_THREAD; ++p) {
-      int row, k;
-      vec_coords(p, row, k);
-      const unsigned o = (k0 + k < K) ? off[p] : kOob;
-      reg[p] = __builtin_amdgcn_raw_buffer_load_b128(rsrc, o, 0, 0);
-    }
+    for (int j = 0; j < PER_WAVE; ++j) off[j] += slab_bytes;    // the mark stays out of range (extents are < 2^31)
   }
-  __device__ static void advance(unsigned (&off)[PER_THREAD], unsigned slab_bytes) {
-#pragma unroll
-    for (int p = 0; p < PER_THREAD; ++p) off[p] += slab_bytes;    // the mark stays out of range (no wrap below 2^31 steps)
-  }
-  __device__ static void store_lds(lds_bf16* lds, const u32x4 (&reg)[PER_THREAD]) {
-#pragma unroll
-    for (int p = 0; p < PER_THREAD; ++p) {
-      int row, k;
-      vec_coords(p, row, k);
-      lds_bf16* dst = KFAST ? (lds + row * LD + k) : (lds + k * LD + row);
-      *reinterpret_cast<LDS_AS u32x4*>(dst) = reg[p];
-    }
-  }
-  // MFMA 32x32x16 operand fragment: rows [rb, rb+32), k-values [kk, kk+16) of the tile
-  __device__ static bf16x8 fragment(const lds_bf16* lds, int rb, int kk) {
+
+  // Per-lane constants of the fragment reads.
+  struct Frag {
+    int base;   // byte offset of the lane's row (KFAST) / of its k-row and in-chunk position (!KFAST)
+    int sw;     // swizzle term
+  };
+  __device__ static Frag frag_init(int rb0) {
     const int lane = threadIdx.x & 63;
+    Frag f;
     if (KFAST) {
-      return *reinterpret_cast<const LDS_AS bf16x8*>(lds + (rb + (lane & 31)) * LD + kk + (lane >> 5) * 8);
+      const int row = rb0 + (lane & 31);
+      f.base = row * PITCH;
+      f.sw = (row >> 1) & 7;
     } else {
       const int g = lane >> 4, i = lane & 15;
-      const int r = rb + 16 * (g & 1) + 4 * (i & 3);
-      const int k = kk + 8 * (g >> 1) + (i >> 2);
-      const lds_bf16* p0 = lds + k * LD + r;
+      f.base = (8 * (g >> 1) + (i >> 2)) * PITCH + 8 * (i & 1);
+      f.sw = (rb0 / 8 + 2 * (g & 1) + ((i & 3) >> 1)) | (((i >> 2) & 3) << 8);   // chunk of row block 0 | k&3
+    }
+    return f;
+  }
+  // MFMA 32x32x16 operand fragment: rows [rb0 + 32*blk, +32), k-values [kk, kk+16) of the tile at `lds`
+  __device__ static bf16x8 fragment(const LDS_AS char* lds, const Frag& f, int blk, int kk) {
+    if (KFAST) {
+      const int lane = threadIdx.x & 63;
+      const int c = (kk / 8 + (lane >> 5)) ^ f.sw;
+      return *reinterpret_cast<const LDS_AS bf16x8*>(lds + f.base + blk * 32 * PITCH + c * 16);
+    } else {
+      const int kq = f.sw >> 8;
+      const int c = ((f.sw & 0xff) + blk * 4) ^ (kq << 2);
+      const LDS_AS char* p0 = lds + f.base + kk * PITCH + c * 16;
       s16x4 lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16((LDS_AS s16x4*)(p0));
-      s16x4 hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16((LDS_AS s16x4*)(p0 + 4 * LD));
+      s16x4 hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16((LDS_AS s16x4*)(p0 + 4 * PITCH));
       union { struct { s16x4 a, b; } s; bf16x8 v; } u;
       u.s.a = lo; u.s.b = hi;
       return u.v;
@@ -107,20 +138,27 @@ struct OperandTile {
 };
 
 template <int BM, int BN, bool AK, bool BKF, int EPI>
-__global__ void __launch_bounds__(kThreads) gemm_mfma_kernel(GemmArgs<bf16> a, int tiles_n, int tiles_total) {
+__global__ void __launch_bounds__(kThreads) gemm_mfma_kernel(GemmArgs<bf16> a, int tiles_m, int tiles_n) {
   typedef OperandTile<BM, AK> TA;
   typedef OperandTile<BN, BKF> TB;
   constexpr int WTM = BM / 2, WTN = BN / 2;     // wavefront tile (2x2 wavefronts)
   constexpr int MI = WTM / 32, NI = WTN / 32;
-  constexpr int STAGE = TA::ELEMS + TB::ELEMS;
-  extern __shared__ __attribute__((aligned(16))) char smem_raw[];
-  lds_bf16* smem = (lds_bf16*)smem_raw;
+  constexpr int STAGE = TA::BYTES + TB::BYTES;
+  extern __shared__ __attribute__((aligned(1024))) char smem_raw[];
+  LDS_AS char* smem = (LDS_AS char*)smem_raw;
 
-  // Blocks are dealt round-robin to the 8 XCDs; give each XCD a contiguous run of tiles so
-  // that neighbours in the tile order (which share operand panels) share an L2.
+  // Tile order.  Blocks are dealt round-robin to the 8 XCDs (each with its own L2), so XCD x
+  // runs blocks x, x+8, ...: give it a contiguous run of the tile order, and make that order
+  // walk 4-row groups of the tile grid column by column, so that the tiles an XCD works on at
+  // the same time form a compact patch sharing A row-panels and B column-panels in its L2.
+  const int total = tiles_m * tiles_n;
   int pid = blockIdx.x;
-  if (tiles_total % 8 == 0) pid = (pid % 8) * (tiles_total / 8) + pid / 8;
-  const int tile_m = pid / tiles_n, tile_n = pid % tiles_n;
+  if (total % 8 == 0) pid = (pid % 8) * (total / 8) + pid / 8;
+  constexpr int GROUP = 4;
+  const int per_group = GROUP * tiles_n;
+  const int g0 = (pid / per_group) * GROUP;
+  const int gsz = min(tiles_m - g0, GROUP);
+  const int tile_m = g0 + (pid % per_group) % gsz, tile_n = (pid % per_group) / gsz;
   const int m0 = tile_m * BM, n0 = tile_n * BN;
 
   const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
@@ -138,47 +176,74 @@ __global__ void __launch_bounds__(kThreads) gemm_mfma_kernel(GemmArgs<bf16> a, i
   const unsigned a_bytes = (unsigned)(2 * (AK ? (int64_t)a.M * a.a_rs : (int64_t)a.K * a.a_cs));
   const unsigned b_bytes = (unsigned)(2 * (BKF ? (int64_t)a.N * a.b_rs : (int64_t)a.K * a.b_cs));
   const __amdgpu_buffer_rsrc_t ra_rsrc = make_rsrc(a.A, a_bytes), rb_rsrc = make_rsrc(a.B, b_bytes);
-  unsigned offa[TA::PER_THREAD], offb[TB::PER_THREAD];
-  TA::init_offsets(a.a_rs, a.a_cs, m0, a.M, offa);
-  TB::init_offsets(a.b_rs, a.b_cs, n0, a.N, offb);
+  unsigned offa[TA::PER_WAVE], offb[TB::PER_WAVE];
+  TA::init_offsets(a.a_rs, a.a_cs, m0, a.M, a.K, offa);
+  TB::init_offsets(a.b_rs, a.b_cs, n0, a.N, a.K, offb);
   const unsigned a_step = (unsigned)(2 * BK * a.a_cs), b_step = (unsigned)(2 * BK * a.b_cs);
+  const typename TA::Frag fra = TA::frag_init(wm);
+  const typename TB::Frag frb = TB::frag_init(wn);
 
-  u32x4 ra[TA::PER_THREAD], rb[TB::PER_THREAD];
-  TA::load_global(ra_rsrc, offa, 0, a.K, ra);
-  TB::load_global(rb_rsrc, offb, 0, a.K, rb);
-  TA::store_lds(smem, ra);
-  TB::store_lds(smem + TA::ELEMS, rb);
+  // Software pipeline over k-slabs of 64 (4 MFMA k-steps of 16 each):
+  //   - fragments of k-step s+1 are read from LDS while the MFMAs of k-step s run;
+  //   - between k-steps 2 and 3 of slab kt: wait until slab kt+1 has landed in the other stage, barrier
+  //     (every wavefront has finished reading this stage: its k-step-3 fragments are in registers), then
+  //     start the loads of slab kt+2 into this stage and read the first fragments of slab kt+1 during
+  //     the MFMAs of k-step 3.  One barrier per slab; no LDS or global latency is exposed.
+  const int nk = (a.K + BK - 1) / BK;
+  TA::load_slab(ra_rsrc, offa, 0, a.K, smem);
+  TB::load_slab(rb_rsrc, offb, 0, a.K, smem + TA::BYTES);
+  if (nk > 1) {
+    TA::advance(offa, a_step);
+    TB::advance(offb, b_step);
+    TA::load_slab(ra_rsrc, offa, BK, a.K, smem + STAGE);
+    TB::load_slab(rb_rsrc, offb, BK, a.K, smem + STAGE + TA::BYTES);
+    __builtin_amdgcn_s_waitcnt(0x0F70 | (TA::PER_WAVE + TB::PER_WAVE));   // vmcnt(loads of slab 1 may still fly)
+  } else {
+    __builtin_amdgcn_s_waitcnt(0x0F70);                                   // vmcnt(0)
+  }
   __syncthreads();
 
-  const int nk = (a.K + BK - 1) / BK;
+  bf16x8 fa[2][MI], fb[2][NI];
+#pragma unroll
+  for (int i = 0; i < MI; ++i) fa[0][i] = TA::fragment(smem, fra, i, 0);
+#pragma unroll
+  for (int j = 0; j < NI; ++j) fb[0][j] = TB::fragment(smem + TA::BYTES, frb, j, 0);
+
   for (int kt = 0; kt < nk; ++kt) {
-    const lds_bf16* As = smem + (kt & 1) * STAGE;
-    const lds_bf16* Bs = As + TA::ELEMS;
-    if (kt + 1 < nk) {
-      TA::advance(offa, a_step);
-      TB::advance(offb, b_step);
-      TA::load_global(ra_rsrc, offa, (kt + 1) * BK, a.K, ra);
-      TB::load_global(rb_rsrc, offb, (kt + 1) * BK, a.K, rb);
-    }
+    const LDS_AS char* As = smem + (kt & 1) * STAGE;
+    const LDS_AS char* Bs = As + TA::BYTES;
+    LDS_AS char* An = smem + ((kt + 1) & 1) * STAGE;     // stage of slab kt+1
 #pragma unroll
-    for (int kk = 0; kk < BK; kk += 16) {
-      bf16x8 fa[MI], fb[NI];
+    for (int step = 0; step < 4; ++step) {
+      const int cur = step & 1, nxt = cur ^ 1;
+      if (step < 3) {
 #pragma unroll
-      for (int i = 0; i < MI; ++i) fa[i] = TA::fragment(As, wm + 32 * i, kk);
+        for (int i = 0; i < MI; ++i) fa[nxt][i] = TA::fragment(As, fra, i, 16 * (step + 1));
 #pragma unroll
-      for (int j = 0; j < NI; ++j) fb[j] = TB::fragment(Bs, wn + 32 * j, kk);
+        for (int j = 0; j < NI; ++j) fb[nxt][j] = TB::fragment(Bs, frb, j, 16 * (step + 1));
+      } else {
+        // all LDS reads of this stage are done once lgkmcnt drains; slab kt+1 (issued one slab ago) has landed
+        __builtin_amdgcn_s_waitcnt(0x0070);              // vmcnt(0) lgkmcnt(0)
+        __syncthreads();
+        if (kt + 2 < nk) {
+          TA::advance(offa, a_step);
+          TB::advance(offb, b_step);
+          TA::load_slab(ra_rsrc, offa, (kt + 2) * BK, a.K, smem + (kt & 1) * STAGE);
+          TB::load_slab(rb_rsrc, offb, (kt + 2) * BK, a.K, smem + (kt & 1) * STAGE + TA::BYTES);
+        }
+        if (kt + 1 < nk) {
+#pragma unroll
+          for (int i = 0; i < MI; ++i) fa[nxt][i] = TA::fragment(An, fra, i, 0);
+#pragma unroll
+          for (int j = 0; j < NI; ++j) fb[nxt][j] = TB::fragment(An + TA::BYTES, frb, j, 0);
+        }
+      }
 #pragma unroll
       for (int i = 0; i < MI; ++i)
 #pragma unroll
         for (int j = 0; j < NI; ++j)
-          acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa[i], fb[j], acc[i][j], 0, 0, 0);
+          acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa[cur][i], fb[cur][j], acc[i][j], 0, 0, 0);
     }
-    if (kt + 1 < nk) {
-      lds_bf16* An = smem + ((kt + 1) & 1) * STAGE;
-      TA::store_lds(An, ra);
-      TB::store_lds(An + TA::ELEMS, rb);
-    }
-    __syncthreads();
   }
 
   // Epilogue.  Accumulator element e of a 32x32 tile: row 8*(e/4) + 4*(lane/32) + e%4, column lane%32.
@@ -215,7 +280,7 @@ template <int BM, int BN, bool AK, bool BKF, int EPI>
 int launch_cfg(const GemmArgs<bf16>& a, hipStream_t s) {
   typedef OperandTile<BM, AK> TA;
   typedef OperandTile<BN, BKF> TB;
-  const size_t lds = 2 * (size_t)(TA::ELEMS + TB::ELEMS) * sizeof(bf16);
+  const size_t lds = 2 * (size_t)(TA::BYTES + TB::BYTES);
   const int tm = (a.M + BM - 1) / BM, tn = (a.N + BN - 1) / BN;
   auto kern = gemm_mfma_kernel<BM, BN, AK, BKF, EPI>;
   static bool attr_set = false;   // per instantiation
@@ -224,19 +289,20 @@ int launch_cfg(const GemmArgs<bf16>& a, hipStream_t s) {
       return fail(CEPHALO_EHIP, "gemm_mfma: cannot reserve %zu B of LDS", lds);
     attr_set = true;
   }
-  kern<<<tm * tn, kThreads, lds, s>>>(a, tn, tm * tn);
+  kern<<<tm * tn, kThreads, lds, s>>>(a, tm, tn);
   CEPHALO_CHECK_LAUNCH("gemm_mfma");
   return CEPHALO_OK;
 }
 
 template <bool AK, bool BKF, int EPI>
 int launch_tiles(const GemmArgs<bf16>& a, hipStream_t s) {
-  // Largest tile that still yields about one block per compute unit.
-  const int64_t t256 = (int64_t)((a.M + 255) / 256) * ((a.N + 127) / 128);
-  if (t256 >= 200) return launch_cfg<256, 128, AK, BKF, EPI>(a, s);
-  const int64_t t128 = (int64_t)((a.M + 127) / 128) * ((a.N + 127) / 128);
-  if (t128 >= 200) return launch_cfg<128, 128, AK, BKF, EPI>(a, s);
-  return launch_cfg<128, 64, AK, BKF, EPI>(a, s);
+  // Largest tile that still yields at least one block per compute unit.
+  static const int force = getenv("CEPHALO_GEMM_TILE") ? atoi(getenv("CEPHALO_GEMM_TILE")) : 0;   // tuning aid
+  const int64_t t256 = (int64_t)((a.M + 255) / 256) * ((a.N + 255) / 256);
+  const int64_t t128 = (int64_t)((a.M + 255) / 256) * ((a.N + 127) / 128);
+  if (force == 256 || (force == 0 && t256 >= 256)) return launch_cfg<256, 256, AK, BKF, EPI>(a, s);
+  if (force == 128 || (force == 0 && t128 >= 200)) return launch_cfg<256, 128, AK, BKF, EPI>(a, s);
+  return launch_cfg<128, 128, AK, BKF, EPI>(a, s);
 }
 
 }  // namespace
