@@ -85,8 +85,8 @@ def main():
     var = torch.zeros(P, dtype=torch.float32, device="cuda")
     mom[off:off + ln] = torch.from_numpy(m_h).cuda()
     var[off:off + ln] = torch.from_numpy(v_h).cuda()
-    save_b, scr_b = C.cephalo_layer_workspace_bytes(desc, m)
-    save = torch.empty(save_b * l, dtype=torch.uint8, device="cuda")
+    save_b, scr_b = C.cephalo_share_workspace_bytes(desc, b, m)
+    save = torch.empty(save_b, dtype=torch.uint8, device="cuda")
     scratch = torch.empty(scr_b, dtype=torch.uint8, device="cuda")
     lr = float(np.float32(cfg.lr))
 

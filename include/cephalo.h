@@ -80,6 +80,13 @@ int cephalo_layer_param_offsets(const cephalo_layer_desc* desc, int64_t* offsets
 int cephalo_layer_workspace_bytes(const cephalo_layer_desc* desc, int32_t micro_batch,
                                   size_t* save_bytes, size_t* scratch_bytes);
 
+/* The same for cephalo_share_layer_step, which keeps every micro-batch's saved activations and
+ * weight-gradient operands until the share's single parameter-gradient pass (288 GB of HBM make
+ * keeping cheaper than the recomputation and host offload the paper needs on 12-24 GB GPUs, Sec. 3.2
+ * "Activation Checkpointing and Offloading").  batch_share must be a positive multiple of micro_batch. */
+int cephalo_share_workspace_bytes(const cephalo_layer_desc* desc, int32_t batch_share, int32_t micro_batch,
+                                  size_t* save_bytes_total, size_t* scratch_bytes);
+
 /* Forward of one layer on one micro-batch of m samples (Sec. 3.2; the step timed as T_f(m)
  * in Sec. 3.3).
  *   flat_param  device, [P] in the compute dtype (fp32, or the bf16 copy of the fp32 master)
@@ -106,11 +113,15 @@ int cephalo_layer_bwd(const cephalo_layer_desc* desc, const void* flat_param,
                       float* flat_grad, float grad_scale, int32_t accumulate,
                       void* scratch, size_t scratch_bytes, void* stream);
 
-/* Whole share of one layer, micro-batches in order j = 0..l-1 (Sec. 3.2, b = l*m): forward
- * of every micro-batch, then backward of every micro-batch with accumulation into
- * flat_grad (first micro-batch overwrites).  Fails with CEPHALO_EINVAL unless
- * batch_share = l * micro_batch for a positive integer l.
- *   x, y, dy, dx  device, [b, S, H];  save: l * save_bytes;  scratch: scratch_bytes */
+/* Whole share of one layer, micro-batches in order j = 0..l-1 (Sec. 3.2, b = l*m; the layered
+ * order of Sec. 3.2 "Layered Gradient Accumulation": every micro-batch passes through the layer
+ * before anything else runs): forward of every micro-batch, backward data path of every
+ * micro-batch, then one parameter-gradient pass over all b*S tokens, in which the sum over
+ * micro-batches is formed in the fp32 accumulators of the weight-gradient GEMMs and every element
+ * of flat_grad is written exactly once:  flat_grad <- grad_scale * sum_j g_j.
+ * Equal to l calls of layer_fwd and layer_bwd up to the order of the fp32 additions.
+ * Fails with CEPHALO_EINVAL unless batch_share = l * micro_batch for a positive integer l.
+ *   x, y, dy, dx  device, [b, S, H];  save, scratch: sizes from cephalo_share_workspace_bytes */
 int cephalo_share_layer_step(const cephalo_layer_desc* desc, const void* flat_param,
                              const void* x, void* y, const void* dy, void* dx,
                              int32_t batch_share, int32_t micro_batch,

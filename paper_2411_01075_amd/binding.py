@@ -44,6 +44,7 @@ SIGNATURES = {
     "cephalo_layer_param_count": (_i64, [_dp]),
     "cephalo_layer_param_offsets": (ctypes.c_int, [_dp, ctypes.POINTER(_i64)]),
     "cephalo_layer_workspace_bytes": (ctypes.c_int, [_dp, _i32, ctypes.POINTER(_sz), ctypes.POINTER(_sz)]),
+    "cephalo_share_workspace_bytes": (ctypes.c_int, [_dp, _i32, _i32, ctypes.POINTER(_sz), ctypes.POINTER(_sz)]),
     "cephalo_layer_fwd": (ctypes.c_int, [_dp, _vp, _vp, _vp, _i32, _vp, _sz, _vp, _sz, _vp]),
     "cephalo_layer_bwd": (ctypes.c_int, [_dp, _vp, _vp, _vp, _vp, _i32, _vp, _sz, _vp, _f32, _i32, _vp, _sz, _vp]),
     "cephalo_share_layer_step": (ctypes.c_int, [_dp, _vp, _vp, _vp, _vp, _vp, _i32, _i32, _vp, _sz, _vp, _f32,
@@ -115,6 +116,12 @@ def cephalo_layer_param_offsets(desc):
 def cephalo_layer_workspace_bytes(desc, micro_batch):
     a, b = _sz(0), _sz(0)
     _check(lib().cephalo_layer_workspace_bytes(ctypes.byref(desc), micro_batch, ctypes.byref(a), ctypes.byref(b)))
+    return a.value, b.value
+
+
+def cephalo_share_workspace_bytes(desc, batch_share, micro_batch):
+    a, b = _sz(0), _sz(0)
+    _check(lib().cephalo_share_workspace_bytes(ctypes.byref(desc), batch_share, micro_batch, ctypes.byref(a), ctypes.byref(b)))
     return a.value, b.value
 
 

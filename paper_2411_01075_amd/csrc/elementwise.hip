@@ -61,12 +61,12 @@ ln_fwd_kernel(const T* __restrict__ x, const T* __restrict__ gamma, const T* __r
 constexpr int kLnBwdRowsPerBlock = 16;  // 4 rows per wavefront
 
 // out = resid + rstd * (g - mean(g) - xhat * mean(g*xhat)),  g = du * gamma
-// partials[0][blk][h] = sum over the block's rows of du*xhat, partials[1][blk][h] = sum of du
+// part_g[blk][h] = sum over the block's rows of du*xhat, part_b[blk][h] = sum of du
 template <typename T, int MAXV>
 __global__ void __launch_bounds__(kThreads)
 ln_bwd_kernel(const T* __restrict__ du, const T* __restrict__ x, const float* __restrict__ mean,
               const float* __restrict__ rstd, const T* __restrict__ gamma, const T* __restrict__ resid,
-              T* __restrict__ out, float* __restrict__ partials, int rows, int H) {
+              T* __restrict__ out, float* __restrict__ part_g, float* __restrict__ part_b, int rows, int H) {
   constexpr int VN = Vec<T>::N;
   __shared__ float red[2][kWaves][64 * VN];
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
@@ -118,8 +118,8 @@ ln_bwd_kernel(const T* __restrict__ du, const T* __restrict__ x, const float* __
     }
   }
   // cross-wavefront sum of the column partials, one 64*VN-column slab at a time
-  float* pg = partials + (int64_t)blockIdx.x * H;
-  float* pb = partials + ((int64_t)gridDim.x + blockIdx.x) * H;
+  float* pg = part_g + (int64_t)blockIdx.x * H;
+  float* pb = part_b + (int64_t)blockIdx.x * H;
 #pragma unroll
   for (int j = 0; j < MAXV; ++j) {
     __syncthreads();
@@ -177,6 +177,36 @@ colsum_kernel(const T* __restrict__ dY, float* __restrict__ partials, int rows, 
   for (int i = 0; i < VN; ++i) p[i] = acc[i];
 }
 
+// 64x64 tile transposed through LDS: 16-byte global reads along the input rows, 16-byte global
+// writes along the output rows; the LDS tile is padded so that the column walk is conflict-free.
+__global__ void __launch_bounds__(kThreads)
+transpose_bf16_kernel(const bf16* __restrict__ in, bf16* __restrict__ out, int rows, int cols) {
+  __shared__ bf16 tile[64][64 + 2];
+  typedef bf16 bf16x8 __attribute__((ext_vector_type(8)));
+  const int r0 = blockIdx.y * 64, c0 = blockIdx.x * 64;
+#pragma unroll
+  for (int p = 0; p < 2; ++p) {
+    const int v = threadIdx.x + kThreads * p;
+    const int r = v >> 3, c = (v & 7) * 8;
+    bf16x8 val = {0, 0, 0, 0, 0, 0, 0, 0};
+    if (r0 + r < rows && c0 + c < cols) val = *reinterpret_cast<const bf16x8*>(in + (int64_t)(r0 + r) * cols + c0 + c);
+#pragma unroll
+    for (int i = 0; i < 8; ++i) tile[r][c + i] = val[i];
+  }
+  __syncthreads();
+#pragma unroll
+  for (int p = 0; p < 2; ++p) {
+    const int v = threadIdx.x + kThreads * p;
+    const int c = v >> 3, r = (v & 7) * 8;       // output row c, output columns r..r+7
+    if (c0 + c < cols && r0 + r < rows) {
+      bf16x8 val;
+#pragma unroll
+      for (int i = 0; i < 8; ++i) val[i] = tile[r + i][c];
+      *reinterpret_cast<bf16x8*>(out + (int64_t)(c0 + c) * rows + r0 + r) = val;
+    }
+  }
+}
+
 template <typename T> int maxv_for(int H) {
   const int nv = H / Vec<T>::N;
   const int need = (nv + 63) / 64;
@@ -204,21 +234,15 @@ int launch_ln_fwd(const T* x, const T* gamma, const T* beta, T* u, float* mean, 
   return CEPHALO_OK;
 }
 
-size_t ln_bwd_partial_bytes(int rows, int H) {
-  const size_t nblocks = (rows + kLnBwdRowsPerBlock - 1) / kLnBwdRowsPerBlock;
-  return 2 * nblocks * (size_t)H * sizeof(float);
-}
+int ln_bwd_blocks(int rows) { return (rows + kLnBwdRowsPerBlock - 1) / kLnBwdRowsPerBlock; }
 
 template <typename T>
 int launch_ln_bwd(const T* du, const T* x, const float* mean, const float* rstd, const T* gamma,
-                  const T* resid, T* out, float* partials, size_t partial_bytes,
-                  float* g_gamma, float* g_beta, float scale, int accumulate,
-                  int rows, int H, hipStream_t s) {
-  if (partial_bytes < ln_bwd_partial_bytes(rows, H)) return fail(CEPHALO_EWORKSPACE, "ln_bwd: partial buffer too small");
-  const int nblocks = (rows + kLnBwdRowsPerBlock - 1) / kLnBwdRowsPerBlock;
-#define LN_BWD_CASE(MV)                                                                                      \
-  case MV:                                                                                                   \
-    ln_bwd_kernel<T, MV><<<nblocks, kThreads, 0, s>>>(du, x, mean, rstd, gamma, resid, out, partials, rows, H); \
+                  const T* resid, T* out, float* part_g, float* part_b, int rows, int H, hipStream_t s) {
+  const int nblocks = ln_bwd_blocks(rows);
+#define LN_BWD_CASE(MV)                                                                                               \
+  case MV:                                                                                                            \
+    ln_bwd_kernel<T, MV><<<nblocks, kThreads, 0, s>>>(du, x, mean, rstd, gamma, resid, out, part_g, part_b, rows, H); \
     break;
   switch (maxv_for<T>(H)) {
     LN_BWD_CASE(1) LN_BWD_CASE(2) LN_BWD_CASE(4) LN_BWD_CASE(8) LN_BWD_CASE(16)
@@ -226,10 +250,12 @@ int launch_ln_bwd(const T* du, const T* x, const float* mean, const float* rstd,
   }
 #undef LN_BWD_CASE
   CEPHALO_CHECK_LAUNCH("ln_bwd");
-  const int rgrid = (H + kThreads - 1) / kThreads;
-  reduce_partials_kernel<<<rgrid, kThreads, 0, s>>>(partials, nblocks, H, g_gamma, scale, accumulate);
-  reduce_partials_kernel<<<rgrid, kThreads, 0, s>>>(partials + (int64_t)nblocks * H, nblocks, H, g_beta, scale, accumulate);
-  CEPHALO_CHECK_LAUNCH("ln_bwd reduce");
+  return CEPHALO_OK;
+}
+
+int launch_reduce_partials(const float* partials, int nchunks, int N, float* g, float scale, int accumulate, hipStream_t s) {
+  reduce_partials_kernel<<<(N + kThreads - 1) / kThreads, kThreads, 0, s>>>(partials, nchunks, N, g, scale, accumulate);
+  CEPHALO_CHECK_LAUNCH("reduce_partials");
   return CEPHALO_OK;
 }
 
@@ -251,10 +277,18 @@ int launch_colsum(const T* dY, float* partials, size_t partial_bytes, float* g, 
   return CEPHALO_OK;
 }
 
+int launch_transpose_bf16(const bf16* in, bf16* out, int rows, int cols, hipStream_t s) {
+  if (rows % 8 != 0 || cols % 8 != 0) return fail(CEPHALO_EINVAL, "transpose: %d x %d is not a multiple of 8 in both extents", rows, cols);
+  dim3 grid((cols + 63) / 64, (rows + 63) / 64);
+  transpose_bf16_kernel<<<grid, kThreads, 0, s>>>(in, out, rows, cols);
+  CEPHALO_CHECK_LAUNCH("transpose");
+  return CEPHALO_OK;
+}
+
 #define INSTANTIATE(T)                                                                                         \
   template int launch_ln_fwd<T>(const T*, const T*, const T*, T*, float*, float*, int, int, float, hipStream_t); \
   template int launch_ln_bwd<T>(const T*, const T*, const float*, const float*, const T*, const T*, T*, float*, \
-                                size_t, float*, float*, float, int, int, int, hipStream_t);                     \
+                                float*, int, int, hipStream_t);                                                  \
   template int launch_colsum<T>(const T*, float*, size_t, float*, float, int, int, int, hipStream_t);
 INSTANTIATE(float)
 INSTANTIATE(bf16)

@@ -267,9 +267,9 @@ __global__ void __launch_bounds__(kThreads) gemm_mfma_kernel(GemmArgs<bf16> a, i
         if (EPI == EPI_BIAS_GELU) {
           const float z = v + bias;
           a.Z[o] = (bf16)z;
-          a.C[o] = (bf16)gelu_f(z);
+          a.C[o] = (bf16)gelu_fast(z);
         }
-        if (EPI == EPI_DGELU) a.C[o] = (bf16)(v * gelu_grad_f((float)a.Z[o]));
+        if (EPI == EPI_DGELU) a.C[o] = (bf16)(v * gelu_grad_fast((float)a.Z[o]));
         if (EPI == EPI_GRAD) a.G[o] = (a.accumulate ? a.G[o] : 0.f) + a.scale * v;
       }
     }
@@ -328,9 +328,13 @@ int launch_gemm_mfma(const GemmArgs<bf16>& a, hipStream_t s) {
     switch (a.epi) {
       case EPI_NONE: return launch_tiles<true, false, EPI_NONE>(a, s);
       case EPI_DGELU: return launch_tiles<true, false, EPI_DGELU>(a, s);
+      default: break;
     }
+    if (a.epi == EPI_GRAD) return launch_tiles<true, false, EPI_GRAD>(a, s);   // wgrad with dY pre-transposed
   } else if (!ak && !bk) {  // wgrad: dW = dY^T X
     if (a.epi == EPI_GRAD) return launch_tiles<false, false, EPI_GRAD>(a, s);
+  } else {                  // wgrad with X pre-transposed
+    if (a.epi == EPI_GRAD) return launch_tiles<false, true, EPI_GRAD>(a, s);
   }
   return launch_gemm_simple<bf16>(a, s);
 }

@@ -50,6 +50,31 @@ __device__ __forceinline__ float gelu_grad_f(float z) {
   return cdf + z * pdf;
 }
 
+
+// Branch-free exact-form GELU for the bf16 epilogues.  erf(|x|) = 1 - (a1 t + ... + a5 t^5) exp(-x^2),
+// t = 1/(1 + p|x|)  (Abramowitz & Stegun 7.1.26, absolute error <= 1.5e-7: three orders of magnitude
+// below one bf16 rounding of the result).  With x = z/sqrt(2) the exponential exp(-z^2/2) is shared
+// between Phi(z) and the density phi(z) of the derivative.
+__device__ __forceinline__ void gelu_terms_fast(float z, float& cdf, float& pdf_unnorm) {
+  const float ax = fabsf(z) * 0.70710678118654752440f;
+  const float t = __builtin_amdgcn_rcpf(1.0f + 0.3275911f * ax);
+  const float e = __expf(-ax * ax);                   // exp(-z^2/2)
+  const float poly = t * (0.254829592f + t * (-0.284496736f + t * (1.421413741f + t * (-1.453152027f + t * 1.061405429f))));
+  const float erf_abs = 1.0f - poly * e;
+  cdf = 0.5f * (1.0f + copysignf(erf_abs, z));
+  pdf_unnorm = e;
+}
+__device__ __forceinline__ float gelu_fast(float z) {
+  float cdf, e;
+  gelu_terms_fast(z, cdf, e);
+  return z * cdf;
+}
+__device__ __forceinline__ float gelu_grad_fast(float z) {
+  float cdf, e;
+  gelu_terms_fast(z, cdf, e);
+  return cdf + z * (0.39894228040143267794f * e);
+}
+
 // ---------------------------------------------------------------------------------------
 // GEMM:  C[M,N] = sum_k A(m,k) * B(n,k)  followed by an epilogue.
 // Operand element (m,k) of A sits at A[m*a_rs + k*a_cs]; one of the two strides is 1.
@@ -87,21 +112,23 @@ template <typename T>
 int launch_ln_fwd(const T* x, const T* gamma, const T* beta, T* u, float* mean, float* rstd,
                   int rows, int H, float eps, hipStream_t s);
 
-// out = resid + LN-backward(du); per-block partial sums of dgamma/dbeta go to `partials`
-// ([2][nblocks][H] fp32) and are folded into g_gamma / g_beta (each [H] fp32, flat-gradient
-// slices) as  g = (accumulate ? g : 0) + scale * sum.
+// out = resid + LN-backward(du).  Each block of rows also writes its partial sums of dgamma (du * xhat) and
+// dbeta (du) to part_g / part_b ([ln_bwd_blocks(rows)][H] fp32 each); launch_reduce_partials folds any number
+// of such partial rows into a flat-gradient slice:  g = (accumulate ? g : 0) + scale * sum over chunks.
 template <typename T>
 int launch_ln_bwd(const T* du, const T* x, const float* mean, const float* rstd, const T* gamma,
-                  const T* resid, T* out, float* partials, size_t partial_bytes,
-                  float* g_gamma, float* g_beta, float scale, int accumulate,
-                  int rows, int H, hipStream_t s);
-size_t ln_bwd_partial_bytes(int rows, int H);
+                  const T* resid, T* out, float* part_g, float* part_b, int rows, int H, hipStream_t s);
+int ln_bwd_blocks(int rows);
+int launch_reduce_partials(const float* partials, int nchunks, int N, float* g, float scale, int accumulate, hipStream_t s);
 
 // g[n] = (accumulate ? g[n] : 0) + scale * sum_t dY[t][n]   (bias gradient), dY [rows, N]
 template <typename T>
 int launch_colsum(const T* dY, float* partials, size_t partial_bytes, float* g, float scale,
                   int accumulate, int rows, int N, hipStream_t s);
 size_t colsum_partial_bytes(int rows, int N);
+
+// out[c][r] = in[r][c] for a row-major bf16 matrix [rows, cols]; rows and cols multiples of 8
+int launch_transpose_bf16(const bf16* in, bf16* out, int rows, int cols, hipStream_t s);
 
 // ---------------------------------------------------------------------------------------
 // Attention on the packed projection qkv [m*S, 3H] (Q | K | V column blocks, head a in

@@ -4,6 +4,8 @@
 #include "kernels.h"
 #include <type_traits>
 
+#define TRY(expr) do { int rc__ = (expr); if (rc__ != CEPHALO_OK) return rc__; } while (0)
+
 namespace cephalo {
 namespace {
 
@@ -54,23 +56,28 @@ int check_desc(const cephalo_layer_desc* d) {
   return CEPHALO_OK;
 }
 
+// Saved activations of `n` samples, tensor-major: each tensor is one [n*S, width] matrix, so the
+// slice of a micro-batch is a row range and the whole share is one contiguous operand.
 struct SaveLayout {
   size_t mean1, rstd1, u, qkv, lse, O, x1, mean2, rstd2, u2, z, h, total;
 };
+// Backward work area.  dz, dx1 and dqkv (the dY operands of the weight gradients) are kept for `span`
+// samples; the rest is per micro-batch of m samples.
 struct ScratchLayout {
-  size_t dz, du2, dx1, dO, dqkv, du, dvec, partials, partial_bytes, total;
+  size_t dz, dx1, dqkv, du2, dO, du, dvec, tpose, ln_part, col_part, col_part_bytes, total;
+  size_t ln_rows;   // rows of each of the four LayerNorm partial arrays (ln2.gamma, ln2.beta, ln1.gamma, ln1.beta)
 };
 
-SaveLayout save_layout(const cephalo_layer_desc& d, int m) {
+SaveLayout save_layout(const cephalo_layer_desc& d, int n) {
   const size_t es = d.dtype == CEPHALO_F32 ? 4 : 2;
-  const size_t T = (size_t)m * d.seq, H = d.hidden, F = d.mlp;
+  const size_t T = (size_t)n * d.seq, H = d.hidden, F = d.mlp;
   SaveLayout L;
   size_t p = 0;
   auto take = [&](size_t bytes) { size_t at = p; p += align_up(bytes); return at; };
   L.mean1 = take(T * 4); L.rstd1 = take(T * 4);
   L.u = take(T * H * es);
   L.qkv = take(T * 3 * H * es);
-  L.lse = take((size_t)m * d.heads * d.seq * 4);
+  L.lse = take((size_t)n * d.heads * d.seq * 4);
   L.O = take(T * H * es);
   L.x1 = take(T * H * es);
   L.mean2 = take(T * 4); L.rstd2 = take(T * 4);
@@ -81,25 +88,25 @@ SaveLayout save_layout(const cephalo_layer_desc& d, int m) {
   return L;
 }
 
-ScratchLayout scratch_layout(const cephalo_layer_desc& d, int m) {
+ScratchLayout scratch_layout(const cephalo_layer_desc& d, int m, int span) {
   const size_t es = d.dtype == CEPHALO_F32 ? 4 : 2;
-  const size_t T = (size_t)m * d.seq, H = d.hidden, F = d.mlp;
+  const size_t Tm = (size_t)m * d.seq, Ts = (size_t)span * d.seq, H = d.hidden, F = d.mlp;
   ScratchLayout L;
   size_t p = 0;
   auto take = [&](size_t bytes) { size_t at = p; p += align_up(bytes); return at; };
-  L.dz = take(T * F * es);
-  L.du2 = take(T * H * es);
-  L.dx1 = take(T * H * es);
-  L.dO = take(T * H * es);
-  L.dqkv = take(T * 3 * H * es);
-  L.du = take(T * H * es);
+  L.dz = take(Ts * F * es);
+  L.dx1 = take(Ts * H * es);
+  L.dqkv = take(Ts * 3 * H * es);
+  L.du2 = take(Tm * H * es);
+  L.dO = take(Tm * H * es);
+  L.du = take(Tm * H * es);
   L.dvec = take((size_t)m * d.heads * d.seq * 4);
+  L.tpose = take(Ts * H * es);     // [H, tokens] token-minor copy of one activation for the weight-gradient GEMMs
+  L.ln_rows = (size_t)(span / m) * ln_bwd_blocks((int)Tm);
+  L.ln_part = take(4 * L.ln_rows * H * sizeof(float));
   const int widest = (int)(3 * H > F ? 3 * H : F);
-  size_t pb = ln_bwd_partial_bytes((int)T, (int)H);
-  const size_t cb = colsum_partial_bytes((int)T, widest);
-  if (cb > pb) pb = cb;
-  L.partial_bytes = pb;
-  L.partials = take(pb);
+  L.col_part_bytes = colsum_partial_bytes((int)Ts, widest);
+  L.col_part = take(L.col_part_bytes);
   L.total = p;
   return L;
 }
@@ -126,8 +133,6 @@ template <> int attn_bwd<bf16>(const bf16* qkv, const bf16* O, const bf16* dO, c
                                int m, int S, int H, int A, int causal, hipStream_t s) {
   return launch_attn_bwd_mfma(qkv, O, dO, lse, dvec, dqkv, m, S, H, A, causal, s);
 }
-
-#define TRY(expr) do { int rc__ = (expr); if (rc__ != CEPHALO_OK) return rc__; } while (0)
 
 template <typename T> T* at(void* base, size_t off) { return reinterpret_cast<T*>(static_cast<char*>(base) + off); }
 template <typename T> const T* at(const void* base, size_t off) { return reinterpret_cast<const T*>(static_cast<const char*>(base) + off); }
@@ -161,94 +166,193 @@ GemmArgs<T> linear_wgrad(const T* dY, const T* X, int Tn, int N, int K, float* G
   return a;
 }
 
+// Weight gradient of a linear layer, G[N,K] (+)= scale * dY[T,N]^T X[T,K].  Both operands are strided along
+// the contracted token axis.  In bf16 the narrower of the two is first copied token-minor ([N,T] or [K,T]):
+// its MFMA fragments then come from 16-byte LDS reads, which run at about three times the rate of the
+// transposing reads the other operand needs, for one extra pass over the small matrix.
 template <typename T>
-int layer_fwd_t(const cephalo_layer_desc& d, const T* P, const T* x, T* y, int m, void* save, hipStream_t s) {
-  const ParamOffsets o = param_offsets(d);
-  const SaveLayout L = save_layout(d, m);
-  const int Tn = m * d.seq, H = d.hidden, F = d.mlp;
-  T* u = at<T>(save, L.u); T* qkv = at<T>(save, L.qkv); T* O = at<T>(save, L.O); T* x1 = at<T>(save, L.x1);
-  T* u2 = at<T>(save, L.u2); T* z = at<T>(save, L.z); T* h = at<T>(save, L.h);
+int wgrad(const T* dY, const T* X, int Tn, int N, int K, float* G, float scale, int acc, T* tbuf, hipStream_t s);
+template <>
+int wgrad<float>(const float* dY, const float* X, int Tn, int N, int K, float* G, float scale, int acc, float*, hipStream_t s) {
+  return gemm<float>(linear_wgrad<float>(dY, X, Tn, N, K, G, scale, acc), s);
+}
+template <>
+int wgrad<bf16>(const bf16* dY, const bf16* X, int Tn, int N, int K, float* G, float scale, int acc, bf16* tbuf, hipStream_t s) {
+  GemmArgs<bf16> a = linear_wgrad<bf16>(dY, X, Tn, N, K, G, scale, acc);
+  if (Tn % 8 != 0) return gemm<bf16>(a, s);
+  if (N <= K) {   // dY^T [N, T] as the k-contiguous A operand
+    TRY(launch_transpose_bf16(dY, tbuf, Tn, N, s));
+    a.A = tbuf; a.a_rs = Tn; a.a_cs = 1;
+  } else {        // X^T [K, T] as the k-contiguous B operand
+    TRY(launch_transpose_bf16(X, tbuf, Tn, K, s));
+    a.B = tbuf; a.b_rs = Tn; a.b_cs = 1;
+  }
+  return gemm<bf16>(a, s);
+}
 
-  TRY(launch_ln_fwd<T>(x, P + o.ln1_g, P + o.ln1_b, u, at<float>(save, L.mean1), at<float>(save, L.rstd1), Tn, H, d.ln_eps, s));
+template <typename T> struct Saved {
+  float *mean1, *rstd1, *lse, *mean2, *rstd2;
+  T *u, *qkv, *O, *x1, *u2, *z, *h;
+};
+// pointers to the saved tensors of the samples starting at `sample0` inside a save area laid out by L
+template <typename T>
+Saved<T> saved_at(void* base, const SaveLayout& L, const cephalo_layer_desc& d, int sample0) {
+  const size_t t0 = (size_t)sample0 * d.seq, H = d.hidden, F = d.mlp;
+  Saved<T> s;
+  s.mean1 = at<float>(base, L.mean1) + t0; s.rstd1 = at<float>(base, L.rstd1) + t0;
+  s.mean2 = at<float>(base, L.mean2) + t0; s.rstd2 = at<float>(base, L.rstd2) + t0;
+  s.lse = at<float>(base, L.lse) + (size_t)sample0 * d.heads * d.seq;
+  s.u = at<T>(base, L.u) + t0 * H; s.qkv = at<T>(base, L.qkv) + t0 * 3 * H; s.O = at<T>(base, L.O) + t0 * H;
+  s.x1 = at<T>(base, L.x1) + t0 * H; s.u2 = at<T>(base, L.u2) + t0 * H;
+  s.z = at<T>(base, L.z) + t0 * F; s.h = at<T>(base, L.h) + t0 * F;
+  return s;
+}
+
+template <typename T> struct Work {
+  T *dz, *dx1, *dqkv;          // at the token offset of the current micro-batch (or of the span for the parameter pass)
+  T *du2, *dO, *du, *tbuf;
+  float *dvec;
+  float *ln2_g, *ln2_b, *ln1_g, *ln1_b;   // LayerNorm partial sums, at the row offset of the current micro-batch
+  float *col_part; size_t col_part_bytes;
+};
+template <typename T>
+Work<T> work_at(void* base, const ScratchLayout& W, const cephalo_layer_desc& d, int sample0, int mb_index, int m) {
+  const size_t t0 = (size_t)sample0 * d.seq, H = d.hidden, F = d.mlp;
+  Work<T> w;
+  w.dz = at<T>(base, W.dz) + t0 * F; w.dx1 = at<T>(base, W.dx1) + t0 * H; w.dqkv = at<T>(base, W.dqkv) + t0 * 3 * H;
+  w.du2 = at<T>(base, W.du2); w.dO = at<T>(base, W.dO); w.du = at<T>(base, W.du); w.tbuf = at<T>(base, W.tpose);
+  w.dvec = at<float>(base, W.dvec);
+  float* ln = at<float>(base, W.ln_part);
+  const size_t r0 = (size_t)mb_index * ln_bwd_blocks(m * d.seq) * H, arr = W.ln_rows * H;
+  w.ln2_g = ln + r0; w.ln2_b = ln + arr + r0; w.ln1_g = ln + 2 * arr + r0; w.ln1_b = ln + 3 * arr + r0;
+  w.col_part = at<float>(base, W.col_part); w.col_part_bytes = W.col_part_bytes;
+  return w;
+}
+
+// ---- forward of one micro-batch ----------------------------------------------------------------
+template <typename T>
+int layer_fwd_t(const cephalo_layer_desc& d, const T* P, const T* x, T* y, int m, const Saved<T>& sv, hipStream_t s) {
+  const ParamOffsets o = param_offsets(d);
+  const int Tn = m * d.seq, H = d.hidden, F = d.mlp;
+  TRY(launch_ln_fwd<T>(x, P + o.ln1_g, P + o.ln1_b, sv.u, sv.mean1, sv.rstd1, Tn, H, d.ln_eps, s));
   {
-    GemmArgs<T> a = linear_fwd<T>(u, P + o.w_qkv, Tn, 3 * H, H);
-    a.epi = EPI_BIAS; a.bias = P + o.b_qkv; a.C = qkv;
+    GemmArgs<T> a = linear_fwd<T>(sv.u, P + o.w_qkv, Tn, 3 * H, H);
+    a.epi = EPI_BIAS; a.bias = P + o.b_qkv; a.C = sv.qkv;
     TRY(gemm<T>(a, s));
   }
-  TRY(attn_fwd<T>(qkv, O, at<float>(save, L.lse), m, d.seq, H, d.heads, d.causal, s));
+  TRY(attn_fwd<T>(sv.qkv, sv.O, sv.lse, m, d.seq, H, d.heads, d.causal, s));
   {
-    GemmArgs<T> a = linear_fwd<T>(O, P + o.w_o, Tn, H, H);
-    a.epi = EPI_BIAS_RESID; a.bias = P + o.b_o; a.R = x; a.C = x1;
+    GemmArgs<T> a = linear_fwd<T>(sv.O, P + o.w_o, Tn, H, H);
+    a.epi = EPI_BIAS_RESID; a.bias = P + o.b_o; a.R = x; a.C = sv.x1;
     TRY(gemm<T>(a, s));
   }
-  TRY(launch_ln_fwd<T>(x1, P + o.ln2_g, P + o.ln2_b, u2, at<float>(save, L.mean2), at<float>(save, L.rstd2), Tn, H, d.ln_eps, s));
+  TRY(launch_ln_fwd<T>(sv.x1, P + o.ln2_g, P + o.ln2_b, sv.u2, sv.mean2, sv.rstd2, Tn, H, d.ln_eps, s));
   {
-    GemmArgs<T> a = linear_fwd<T>(u2, P + o.w_fc1, Tn, F, H);
-    a.epi = EPI_BIAS_GELU; a.bias = P + o.b_fc1; a.Z = z; a.C = h;
+    GemmArgs<T> a = linear_fwd<T>(sv.u2, P + o.w_fc1, Tn, F, H);
+    a.epi = EPI_BIAS_GELU; a.bias = P + o.b_fc1; a.Z = sv.z; a.C = sv.h;
     TRY(gemm<T>(a, s));
   }
   {
-    GemmArgs<T> a = linear_fwd<T>(h, P + o.w_fc2, Tn, H, F);
-    a.epi = EPI_BIAS_RESID; a.bias = P + o.b_fc2; a.R = x1; a.C = y;
+    GemmArgs<T> a = linear_fwd<T>(sv.h, P + o.w_fc2, Tn, H, F);
+    a.epi = EPI_BIAS_RESID; a.bias = P + o.b_fc2; a.R = sv.x1; a.C = y;
     TRY(gemm<T>(a, s));
   }
   return CEPHALO_OK;
 }
 
+// ---- backward, data path of one micro-batch: dx and the dY operands (dz, dx1, dqkv) of the weight gradients --------
 template <typename T>
-int layer_bwd_t(const cephalo_layer_desc& d, const T* P, const T* x, const T* dy, T* dx, int m, const void* save,
-                float* G, float scale, int acc, void* scratch, hipStream_t s) {
+int layer_bwd_data_t(const cephalo_layer_desc& d, const T* P, const T* x, const T* dy, T* dx, int m,
+                     const Saved<T>& sv, const Work<T>& w, hipStream_t s) {
   const ParamOffsets o = param_offsets(d);
-  const SaveLayout L = save_layout(d, m);
-  const ScratchLayout W = scratch_layout(d, m);
   const int Tn = m * d.seq, H = d.hidden, F = d.mlp;
-  const T* u = at<T>(save, L.u); const T* qkv = at<T>(save, L.qkv); const T* O = at<T>(save, L.O);
-  const T* x1 = at<T>(save, L.x1); const T* u2 = at<T>(save, L.u2); const T* z = at<T>(save, L.z); const T* h = at<T>(save, L.h);
-  T* dz = at<T>(scratch, W.dz); T* du2 = at<T>(scratch, W.du2); T* dx1 = at<T>(scratch, W.dx1);
-  T* dO = at<T>(scratch, W.dO); T* dqkv = at<T>(scratch, W.dqkv); T* du = at<T>(scratch, W.du);
-  float* dvec = at<float>(scratch, W.dvec);
-  float* part = at<float>(scratch, W.partials);
-
-  // y = x1 + h W2^T + b2
-  TRY(launch_colsum<T>(dy, part, W.partial_bytes, G + o.b_fc2, scale, acc, Tn, H, s));
-  TRY(gemm<T>(linear_wgrad<T>(dy, h, Tn, H, F, G + o.w_fc2, scale, acc), s));
   {
-    GemmArgs<T> a = linear_dgrad<T>(dy, P + o.w_fc2, Tn, H, F);   // dh, then dz = dh * gelu'(z)
-    a.epi = EPI_DGELU; a.Z = const_cast<T*>(z); a.C = dz;
+    GemmArgs<T> a = linear_dgrad<T>(dy, P + o.w_fc2, Tn, H, F);   // dh = dy W2, then dz = dh * gelu'(z)
+    a.epi = EPI_DGELU; a.Z = sv.z; a.C = w.dz;
     TRY(gemm<T>(a, s));
   }
-  // z = u2 W1^T + b1
-  TRY(launch_colsum<T>(dz, part, W.partial_bytes, G + o.b_fc1, scale, acc, Tn, F, s));
-  TRY(gemm<T>(linear_wgrad<T>(dz, u2, Tn, F, H, G + o.w_fc1, scale, acc), s));
   {
-    GemmArgs<T> a = linear_dgrad<T>(dz, P + o.w_fc1, Tn, F, H);
-    a.epi = EPI_NONE; a.C = du2;
+    GemmArgs<T> a = linear_dgrad<T>(w.dz, P + o.w_fc1, Tn, F, H);
+    a.epi = EPI_NONE; a.C = w.du2;
     TRY(gemm<T>(a, s));
   }
   // u2 = LN2(x1); dx1 = dy + LN2-backward(du2)
-  TRY(launch_ln_bwd<T>(du2, x1, at<float>(save, L.mean2), at<float>(save, L.rstd2), P + o.ln2_g, dy, dx1,
-                       part, W.partial_bytes, G + o.ln2_g, G + o.ln2_b, scale, acc, Tn, H, s));
-  // x1 = x + O Wo^T + bo
-  TRY(launch_colsum<T>(dx1, part, W.partial_bytes, G + o.b_o, scale, acc, Tn, H, s));
-  TRY(gemm<T>(linear_wgrad<T>(dx1, O, Tn, H, H, G + o.w_o, scale, acc), s));
+  TRY(launch_ln_bwd<T>(w.du2, sv.x1, sv.mean2, sv.rstd2, P + o.ln2_g, dy, w.dx1, w.ln2_g, w.ln2_b, Tn, H, s));
   {
-    GemmArgs<T> a = linear_dgrad<T>(dx1, P + o.w_o, Tn, H, H);
-    a.epi = EPI_NONE; a.C = dO;
+    GemmArgs<T> a = linear_dgrad<T>(w.dx1, P + o.w_o, Tn, H, H);
+    a.epi = EPI_NONE; a.C = w.dO;
     TRY(gemm<T>(a, s));
   }
-  TRY(attn_bwd<T>(qkv, O, dO, at<float>(save, L.lse), dvec, dqkv, m, d.seq, H, d.heads, d.causal, s));
-  // qkv = u Wqkv^T + bqkv
-  TRY(launch_colsum<T>(dqkv, part, W.partial_bytes, G + o.b_qkv, scale, acc, Tn, 3 * H, s));
-  TRY(gemm<T>(linear_wgrad<T>(dqkv, u, Tn, 3 * H, H, G + o.w_qkv, scale, acc), s));
+  TRY(attn_bwd<T>(sv.qkv, sv.O, w.dO, sv.lse, w.dvec, w.dqkv, m, d.seq, H, d.heads, d.causal, s));
   {
-    GemmArgs<T> a = linear_dgrad<T>(dqkv, P + o.w_qkv, Tn, 3 * H, H);
-    a.epi = EPI_NONE; a.C = du;
+    GemmArgs<T> a = linear_dgrad<T>(w.dqkv, P + o.w_qkv, Tn, 3 * H, H);
+    a.epi = EPI_NONE; a.C = w.du;
     TRY(gemm<T>(a, s));
   }
   // u = LN1(x); dx = dx1 + LN1-backward(du)
-  TRY(launch_ln_bwd<T>(du, x, at<float>(save, L.mean1), at<float>(save, L.rstd1), P + o.ln1_g, dx1, dx,
-                       part, W.partial_bytes, G + o.ln1_g, G + o.ln1_b, scale, acc, Tn, H, s));
+  TRY(launch_ln_bwd<T>(w.du, x, sv.mean1, sv.rstd1, P + o.ln1_g, w.dx1, dx, w.ln1_g, w.ln1_b, Tn, H, s));
   return CEPHALO_OK;
+}
+
+// ---- backward, parameter path over `tokens` tokens (one micro-batch, or the whole share at once) ---------------------
+// G <- (acc ? G : 0) + scale * (gradient summed over those tokens).  Over the whole share the sum over micro-batches
+// happens inside the fp32 MFMA accumulators and each gradient element is written exactly once.
+template <typename T>
+int layer_bwd_params_t(const cephalo_layer_desc& d, const T* dy, int tokens, int ln_chunks,
+                       const Saved<T>& sv, const Work<T>& w, float* G, float scale, int acc, hipStream_t s) {
+  const ParamOffsets o = param_offsets(d);
+  const int H = d.hidden, F = d.mlp;
+  TRY(launch_colsum<T>(dy, w.col_part, w.col_part_bytes, G + o.b_fc2, scale, acc, tokens, H, s));
+  TRY(wgrad<T>(dy, sv.h, tokens, H, F, G + o.w_fc2, scale, acc, w.tbuf, s));
+  TRY(launch_colsum<T>(w.dz, w.col_part, w.col_part_bytes, G + o.b_fc1, scale, acc, tokens, F, s));
+  TRY(wgrad<T>(w.dz, sv.u2, tokens, F, H, G + o.w_fc1, scale, acc, w.tbuf, s));
+  TRY(launch_reduce_partials(w.ln2_g, ln_chunks, H, G + o.ln2_g, scale, acc, s));
+  TRY(launch_reduce_partials(w.ln2_b, ln_chunks, H, G + o.ln2_b, scale, acc, s));
+  TRY(launch_colsum<T>(w.dx1, w.col_part, w.col_part_bytes, G + o.b_o, scale, acc, tokens, H, s));
+  TRY(wgrad<T>(w.dx1, sv.O, tokens, H, H, G + o.w_o, scale, acc, w.tbuf, s));
+  TRY(launch_colsum<T>(w.dqkv, w.col_part, w.col_part_bytes, G + o.b_qkv, scale, acc, tokens, 3 * H, s));
+  TRY(wgrad<T>(w.dqkv, sv.u, tokens, 3 * H, H, G + o.w_qkv, scale, acc, w.tbuf, s));
+  TRY(launch_reduce_partials(w.ln1_g, ln_chunks, H, G + o.ln1_g, scale, acc, s));
+  TRY(launch_reduce_partials(w.ln1_b, ln_chunks, H, G + o.ln1_b, scale, acc, s));
+  return CEPHALO_OK;
+}
+
+template <typename T>
+int run_fwd(const cephalo_layer_desc& d, const void* P, const void* x, void* y, int m, void* save, hipStream_t s) {
+  const SaveLayout L = save_layout(d, m);
+  return layer_fwd_t<T>(d, static_cast<const T*>(P), static_cast<const T*>(x), static_cast<T*>(y), m, saved_at<T>(save, L, d, 0), s);
+}
+
+template <typename T>
+int run_bwd(const cephalo_layer_desc& d, const void* P, const void* x, const void* dy, void* dx, int m, void* save,
+            float* G, float scale, int acc, void* scratch, hipStream_t s) {
+  const SaveLayout L = save_layout(d, m);
+  const ScratchLayout W = scratch_layout(d, m, m);
+  const Saved<T> sv = saved_at<T>(save, L, d, 0);
+  const Work<T> w = work_at<T>(scratch, W, d, 0, 0, m);
+  TRY(layer_bwd_data_t<T>(d, static_cast<const T*>(P), static_cast<const T*>(x), static_cast<const T*>(dy), static_cast<T*>(dx), m, sv, w, s));
+  return layer_bwd_params_t<T>(d, static_cast<const T*>(dy), m * d.seq, ln_bwd_blocks(m * d.seq), sv, w, G, scale, acc, s);
+}
+
+// Whole share: forward of every micro-batch, data-path backward of every micro-batch, then ONE parameter pass over
+// all b*S tokens (the dY operands and the saved activations of all micro-batches are contiguous by construction).
+template <typename T>
+int run_share(const cephalo_layer_desc& d, const void* Pv, const void* xv, void* yv, const void* dyv, void* dxv,
+              int b, int m, void* save, float* G, float scale, void* scratch, hipStream_t s) {
+  const T* P = static_cast<const T*>(Pv);
+  const T* x = static_cast<const T*>(xv); T* y = static_cast<T*>(yv);
+  const T* dy = static_cast<const T*>(dyv); T* dx = static_cast<T*>(dxv);
+  const SaveLayout L = save_layout(d, b);
+  const ScratchLayout W = scratch_layout(d, m, b);
+  const int l = b / m;
+  const size_t act = (size_t)m * d.seq * d.hidden;   // elements of one micro-batch of x / y / dy / dx
+  for (int j = 0; j < l; ++j)
+    TRY(layer_fwd_t<T>(d, P, x + j * act, y + j * act, m, saved_at<T>(save, L, d, j * m), s));
+  for (int j = 0; j < l; ++j)
+    TRY(layer_bwd_data_t<T>(d, P, x + j * act, dy + j * act, dx + j * act, m, saved_at<T>(save, L, d, j * m),
+                            work_at<T>(scratch, W, d, j * m, j, m), s));
+  return layer_bwd_params_t<T>(d, dy, b * d.seq, l * ln_bwd_blocks(m * d.seq), saved_at<T>(save, L, d, 0),
+                               work_at<T>(scratch, W, d, 0, 0, m), G, scale, 0, s);
 }
 
 int check_io(const char* who, const cephalo_layer_desc* d, int m, std::initializer_list<const void*> ptrs) {
@@ -288,7 +392,19 @@ extern "C" int cephalo_layer_workspace_bytes(const cephalo_layer_desc* desc, int
   if (micro_batch <= 0) return fail(CEPHALO_EINVAL, "workspace_bytes: micro-batch size m = %d must be positive", micro_batch);
   if (!save_bytes || !scratch_bytes) return fail(CEPHALO_EINVAL, "workspace_bytes: null output");
   *save_bytes = save_layout(*desc, micro_batch).total;
-  *scratch_bytes = scratch_layout(*desc, micro_batch).total;
+  *scratch_bytes = scratch_layout(*desc, micro_batch, micro_batch).total;
+  return CEPHALO_OK;
+}
+
+extern "C" int cephalo_share_workspace_bytes(const cephalo_layer_desc* desc, int32_t batch_share, int32_t micro_batch,
+                                             size_t* save_bytes_total, size_t* scratch_bytes) {
+  TRY(check_desc(desc));
+  if (micro_batch <= 0 || batch_share <= 0 || batch_share % micro_batch != 0)
+    return fail(CEPHALO_EINVAL, "share_workspace_bytes: batch share b = %d is not a positive multiple of micro-batch size m = %d",
+                batch_share, micro_batch);
+  if (!save_bytes_total || !scratch_bytes) return fail(CEPHALO_EINVAL, "share_workspace_bytes: null output");
+  *save_bytes_total = save_layout(*desc, batch_share).total;
+  *scratch_bytes = scratch_layout(*desc, micro_batch, batch_share).total;
   return CEPHALO_OK;
 }
 
@@ -302,11 +418,8 @@ extern "C" int cephalo_layer_fwd(const cephalo_layer_desc* desc, const void* fla
     return fail(CEPHALO_EWORKSPACE, "layer_fwd: save area %zu B < %zu B", save_bytes, save_layout(*desc, micro_batch).total);
   (void)scratch; (void)scratch_bytes;
   hipStream_t s = static_cast<hipStream_t>(stream);
-  if (desc->dtype == CEPHALO_F32)
-    return layer_fwd_t<float>(*desc, static_cast<const float*>(flat_param), static_cast<const float*>(x),
-                              static_cast<float*>(y), micro_batch, save, s);
-  return layer_fwd_t<bf16>(*desc, static_cast<const bf16*>(flat_param), static_cast<const bf16*>(x),
-                           static_cast<bf16*>(y), micro_batch, save, s);
+  if (desc->dtype == CEPHALO_F32) return run_fwd<float>(*desc, flat_param, x, y, micro_batch, save, s);
+  return run_fwd<bf16>(*desc, flat_param, x, y, micro_batch, save, s);
 }
 
 extern "C" int cephalo_layer_bwd(const cephalo_layer_desc* desc, const void* flat_param,
@@ -319,16 +432,13 @@ extern "C" int cephalo_layer_bwd(const cephalo_layer_desc* desc, const void* fla
   if (accumulate != 0 && accumulate != 1) return fail(CEPHALO_EINVAL, "layer_bwd: accumulate must be 0 or 1");
   if (save_bytes < save_layout(*desc, micro_batch).total)
     return fail(CEPHALO_EWORKSPACE, "layer_bwd: save area %zu B < %zu B", save_bytes, save_layout(*desc, micro_batch).total);
-  if (scratch_bytes < scratch_layout(*desc, micro_batch).total)
-    return fail(CEPHALO_EWORKSPACE, "layer_bwd: scratch %zu B < %zu B", scratch_bytes, scratch_layout(*desc, micro_batch).total);
+  const size_t need = scratch_layout(*desc, micro_batch, micro_batch).total;
+  if (scratch_bytes < need) return fail(CEPHALO_EWORKSPACE, "layer_bwd: scratch %zu B < %zu B", scratch_bytes, need);
   hipStream_t s = static_cast<hipStream_t>(stream);
+  void* sv = const_cast<void*>(save);
   if (desc->dtype == CEPHALO_F32)
-    return layer_bwd_t<float>(*desc, static_cast<const float*>(flat_param), static_cast<const float*>(x),
-                              static_cast<const float*>(dy), static_cast<float*>(dx), micro_batch, save,
-                              flat_grad, grad_scale, accumulate, scratch, s);
-  return layer_bwd_t<bf16>(*desc, static_cast<const bf16*>(flat_param), static_cast<const bf16*>(x),
-                           static_cast<const bf16*>(dy), static_cast<bf16*>(dx), micro_batch, save,
-                           flat_grad, grad_scale, accumulate, scratch, s);
+    return run_bwd<float>(*desc, flat_param, x, dy, dx, micro_batch, sv, flat_grad, grad_scale, accumulate, scratch, s);
+  return run_bwd<bf16>(*desc, flat_param, x, dy, dx, micro_batch, sv, flat_grad, grad_scale, accumulate, scratch, s);
 }
 
 extern "C" int cephalo_share_layer_step(const cephalo_layer_desc* desc, const void* flat_param,
@@ -341,18 +451,16 @@ extern "C" int cephalo_share_layer_step(const cephalo_layer_desc* desc, const vo
   if (batch_share <= 0 || batch_share % micro_batch != 0)
     return fail(CEPHALO_EINVAL, "share_layer_step: batch share b = %d is not a positive multiple of micro-batch size m = %d",
                 batch_share, micro_batch);
-  const int l = batch_share / micro_batch;
-  const size_t per = save_layout(*desc, micro_batch).total;
-  if (save_bytes_total < per * (size_t)l)
-    return fail(CEPHALO_EWORKSPACE, "share_layer_step: save area %zu B < %d micro-batches x %zu B", save_bytes_total, l, per);
-  const size_t es = desc->dtype == CEPHALO_F32 ? 4 : 2;
-  const size_t act = (size_t)micro_batch * desc->seq * desc->hidden * es;  // bytes of one micro-batch of x / y
-  for (int j = 0; j < l; ++j)
-    TRY(cephalo_layer_fwd(desc, flat_param, static_cast<const char*>(x) + j * act, static_cast<char*>(y) + j * act,
-                          micro_batch, static_cast<char*>(save) + j * per, per, scratch, scratch_bytes, stream));
-  for (int j = 0; j < l; ++j)
-    TRY(cephalo_layer_bwd(desc, flat_param, static_cast<const char*>(x) + j * act, static_cast<const char*>(dy) + j * act,
-                          static_cast<char*>(dx) + j * act, micro_batch, static_cast<char*>(save) + j * per, per,
-                          flat_grad, grad_scale, j > 0, scratch, scratch_bytes, stream));
-  return CEPHALO_OK;
+  if ((int64_t)batch_share * desc->seq > (1 << 24))
+    return fail(CEPHALO_EUNSUPPORTED, "share_layer_step: b*S = %lld tokens is too many", (long long)batch_share * desc->seq);
+  if (x == y || dx == dy) return fail(CEPHALO_EINVAL, "share_layer_step: outputs may not alias inputs");
+  const size_t need_save = save_layout(*desc, batch_share).total;
+  if (save_bytes_total < need_save)
+    return fail(CEPHALO_EWORKSPACE, "share_layer_step: save area %zu B < %zu B", save_bytes_total, need_save);
+  const size_t need = scratch_layout(*desc, micro_batch, batch_share).total;
+  if (scratch_bytes < need) return fail(CEPHALO_EWORKSPACE, "share_layer_step: scratch %zu B < %zu B", scratch_bytes, need);
+  hipStream_t s = static_cast<hipStream_t>(stream);
+  if (desc->dtype == CEPHALO_F32)
+    return run_share<float>(*desc, flat_param, x, y, dy, dx, batch_share, micro_batch, save, flat_grad, grad_scale, scratch, s);
+  return run_share<bf16>(*desc, flat_param, x, y, dy, dx, batch_share, micro_batch, save, flat_grad, grad_scale, scratch, s);
 }

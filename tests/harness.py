@@ -58,13 +58,16 @@ def gpu_share_step(cfg, tensors, x, dy, grad_scale=1.0, via_share_call=True):
     l = b // m
     yd = torch.empty_like(xd)
     dxd = torch.empty_like(xd)
-    save_b, scr_b = C.cephalo_layer_workspace_bytes(desc, m)
-    save = torch.empty(save_b * l, dtype=torch.uint8, device="cuda")
-    scratch = torch.empty(scr_b, dtype=torch.uint8, device="cuda")
     G = torch.full((flat32.numel(),), float("nan"), dtype=torch.float32, device="cuda")   # first micro-batch must overwrite
     if via_share_call:
+        save_b, scr_b = C.cephalo_share_workspace_bytes(desc, b, m)
+        save = torch.empty(save_b, dtype=torch.uint8, device="cuda")
+        scratch = torch.empty(scr_b, dtype=torch.uint8, device="cuda")
         C.cephalo_share_layer_step(desc, flat, xd, yd, dyd, dxd, b, m, save, G, grad_scale, scratch)
     else:
+        save_b, scr_b = C.cephalo_layer_workspace_bytes(desc, m)
+        save = torch.empty(save_b * l, dtype=torch.uint8, device="cuda")
+        scratch = torch.empty(scr_b, dtype=torch.uint8, device="cuda")
         per = m * cfg.seq * cfg.hidden
         for j in range(l):
             sl = slice(j * m, (j + 1) * m)

@@ -90,3 +90,8 @@ def test_host_validation_of_slices_and_shares():
     # workspace too small
     a = list(args(4, 2)); a[9] = 16
     assert lib.cephalo_share_layer_step(*a) == -3
+    with pytest.raises(C.CephaloError):
+        C.cephalo_share_workspace_bytes(d, 5, 2)
+    s_share, w_share = C.cephalo_share_workspace_bytes(d, 4, 2)
+    s_mb, w_mb = C.cephalo_layer_workspace_bytes(d, 2)
+    assert s_share <= 2 * s_mb and w_share >= w_mb
