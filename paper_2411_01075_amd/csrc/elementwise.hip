@@ -142,15 +142,32 @@ ln_bwd_kernel(const T* __restrict__ du, const T* __restrict__ x, const float* __
   }
 }
 
-// g[n] = (accumulate ? g[n] : 0) + scale * sum_{c < nchunks} partials[c][n], fixed order
+// g[n] = (accumulate ? g[n] : 0) + scale * sum_{c < nchunks} partials[c][n].  A block owns 64 columns; its four
+// wavefronts take chunks c = w, w+4, ... and their sums are combined in a fixed order, so the result does not
+// depend on scheduling.
 __global__ void __launch_bounds__(kThreads)
 reduce_partials_kernel(const float* __restrict__ partials, int nchunks, int N, float* __restrict__ g,
                        float scale, int accumulate) {
-  const int n = blockIdx.x * kThreads + threadIdx.x;
-  if (n >= N) return;
-  float s = 0.f;
-  for (int c = 0; c < nchunks; ++c) s += partials[(int64_t)c * N + n];
-  g[n] = (accumulate ? g[n] : 0.f) + scale * s;
+  __shared__ float red[kWaves][64];
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  const int n = blockIdx.x * 64 + lane;
+  float s0 = 0.f, s1 = 0.f, s2 = 0.f, s3 = 0.f;
+  if (n < N) {
+    int c = wave;
+    for (; c + 3 * kWaves < nchunks; c += 4 * kWaves) {
+      s0 += partials[(int64_t)c * N + n];
+      s1 += partials[(int64_t)(c + kWaves) * N + n];
+      s2 += partials[(int64_t)(c + 2 * kWaves) * N + n];
+      s3 += partials[(int64_t)(c + 3 * kWaves) * N + n];
+    }
+    for (; c < nchunks; c += kWaves) s0 += partials[(int64_t)c * N + n];
+  }
+  red[wave][lane] = (s0 + s1) + (s2 + s3);
+  __syncthreads();
+  if (wave == 0 && n < N) {
+    const float s = (red[0][lane] + red[1][lane]) + (red[2][lane] + red[3][lane]);
+    g[n] = (accumulate ? g[n] : 0.f) + scale * s;
+  }
 }
 
 constexpr int kColsumRowsPerChunk = 64;
@@ -254,7 +271,7 @@ int launch_ln_bwd(const T* du, const T* x, const float* mean, const float* rstd,
 }
 
 int launch_reduce_partials(const float* partials, int nchunks, int N, float* g, float scale, int accumulate, hipStream_t s) {
-  reduce_partials_kernel<<<(N + kThreads - 1) / kThreads, kThreads, 0, s>>>(partials, nchunks, N, g, scale, accumulate);
+  reduce_partials_kernel<<<(N + 63) / 64, kThreads, 0, s>>>(partials, nchunks, N, g, scale, accumulate);
   CEPHALO_CHECK_LAUNCH("reduce_partials");
   return CEPHALO_OK;
 }
@@ -272,7 +289,7 @@ int launch_colsum(const T* dY, float* partials, size_t partial_bytes, float* g, 
   const int nvec = N / Vec<T>::N;
   dim3 grid((nvec + kThreads - 1) / kThreads, nchunks);
   colsum_kernel<T><<<grid, kThreads, 0, s>>>(dY, partials, rows, N);
-  reduce_partials_kernel<<<(N + kThreads - 1) / kThreads, kThreads, 0, s>>>(partials, nchunks, N, g, scale, accumulate);
+  reduce_partials_kernel<<<(N + 63) / 64, kThreads, 0, s>>>(partials, nchunks, N, g, scale, accumulate);
   CEPHALO_CHECK_LAUNCH("colsum");
   return CEPHALO_OK;
 }

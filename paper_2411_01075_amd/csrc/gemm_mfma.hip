@@ -33,6 +33,7 @@ namespace {
 typedef bf16 bf16x8 __attribute__((ext_vector_type(8)));
 typedef float f32x16 __attribute__((ext_vector_type(16)));
 typedef short s16x4 __attribute__((ext_vector_type(4)));
+typedef float f32x4 __attribute__((ext_vector_type(4)));
 #define LDS_AS __attribute__((address_space(3)))
 
 constexpr int kThreads = 256;
@@ -242,36 +243,92 @@ __global__ void __launch_bounds__(kThreads) gemm_mfma_kernel(GemmArgs<bf16> a, i
       for (int i = 0; i < MI; ++i)
 #pragma unroll
         for (int j = 0; j < NI; ++j)
-          acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa[cur][i], fb[cur][j], acc[i][j], 0, 0, 0);
+          acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fb[cur][j], fa[cur][i], acc[i][j], 0, 0, 0);
     }
   }
 
-  // Epilogue.  Accumulator element e of a 32x32 tile: row 8*(e/4) + 4*(lane/32) + e%4, column lane%32.
+  // Epilogue.  The MFMAs above were issued with the operands exchanged, so each 32x32 accumulator block holds
+  // C^T: lane l owns output row m = l%32 and, for e = 0..15, the columns n = 8*(e/4) + 4*(l/32) + e%4, i.e. four
+  // groups of four consecutive columns.
+  const int h = lane >> 5;
+  if (EPI == EPI_GRAD) {
+    // fp32 gradient tile: 16-byte read-modify-write per lane
+#pragma unroll
+    for (int i = 0; i < MI; ++i) {
+      const int m = m0 + wm + 32 * i + (lane & 31);
+      if (m >= a.M) continue;
+#pragma unroll
+      for (int j = 0; j < NI; ++j)
+#pragma unroll
+        for (int q = 0; q < 4; ++q) {
+          const int n = n0 + wn + 32 * j + 8 * q + 4 * h;
+          if (n >= a.N) continue;                       // N is a multiple of 8: the group of 4 is inside or outside
+          f32x4* gp = reinterpret_cast<f32x4*>(a.G + (int64_t)m * a.N + n);
+          f32x4 v;
+#pragma unroll
+          for (int r = 0; r < 4; ++r) v[r] = a.scale * acc[i][j][4 * q + r];
+          if (a.accumulate) v += *gp;
+          *gp = v;
+        }
+    }
+    return;
+  }
+  // bf16 outputs: each wavefront passes its tile through its own LDS region, 32 rows at a time, to turn the
+  // accumulator layout into row-major 16-byte vectors; bias, residual and pre-activation are then read, and the
+  // results written, as coalesced 16-byte accesses.  (All wavefronts are past the last barrier of the main loop
+  // and hold their fragments in registers, so the operand stages are free.)
+  constexpr int SP = WTN + 4;                           // staging pitch in floats (16 bytes of padding per row)
+  constexpr int LPR = WTN / 8;                          // lanes per row when reading back 8 columns per lane
+  constexpr int RPS = 64 / LPR;                         // rows per read step
+  static_assert(4 * 32 * SP * 4 <= 2 * STAGE, "staging regions must fit in the operand stages");
+  LDS_AS float* stage = (LDS_AS float*)(smem + wave * (32 * SP * 4));
 #pragma unroll
   for (int i = 0; i < MI; ++i) {
 #pragma unroll
-    for (int j = 0; j < NI; ++j) {
-      const int n = n0 + wn + 32 * j + (lane & 31);
-      if (n >= a.N) continue;
-      float bias = 0.f;
-      if (EPI == EPI_BIAS || EPI == EPI_BIAS_RESID || EPI == EPI_BIAS_GELU) bias = (float)a.bias[n];
+    for (int j = 0; j < NI; ++j)
 #pragma unroll
-      for (int e = 0; e < 16; ++e) {
-        const int m = m0 + wm + 32 * i + 8 * (e >> 2) + 4 * (lane >> 5) + (e & 3);
-        if (m >= a.M) continue;
-        const int64_t o = (int64_t)m * a.N + n;
-        const float v = acc[i][j][e];
-        if (EPI == EPI_NONE) a.C[o] = (bf16)v;
-        if (EPI == EPI_BIAS) a.C[o] = (bf16)(v + bias);
-        if (EPI == EPI_BIAS_RESID) a.C[o] = (bf16)(v + bias + (float)a.R[o]);
-        if (EPI == EPI_BIAS_GELU) {
-          const float z = v + bias;
-          a.Z[o] = (bf16)z;
-          a.C[o] = (bf16)gelu_fast(z);
-        }
-        if (EPI == EPI_DGELU) a.C[o] = (bf16)(v * gelu_grad_fast((float)a.Z[o]));
-        if (EPI == EPI_GRAD) a.G[o] = (a.accumulate ? a.G[o] : 0.f) + a.scale * v;
+      for (int q = 0; q < 4; ++q) {
+        f32x4 v;
+#pragma unroll
+        for (int r = 0; r < 4; ++r) v[r] = acc[i][j][4 * q + r];
+        *reinterpret_cast<LDS_AS f32x4*>(stage + (lane & 31) * SP + 32 * j + 8 * q + 4 * h) = v;
       }
+    const int c = (lane % LPR) * 8;
+    const int n = n0 + wn + c;
+#pragma unroll
+    for (int r = lane / LPR; r < 32; r += RPS) {
+      const f32x4 v0 = *reinterpret_cast<const LDS_AS f32x4*>(stage + r * SP + c);
+      const f32x4 v1 = *reinterpret_cast<const LDS_AS f32x4*>(stage + r * SP + c + 4);
+      const int m = m0 + wm + 32 * i + r;
+      if (m >= a.M || n >= a.N) continue;
+      const int64_t o = (int64_t)m * a.N + n;
+      float v[8];
+#pragma unroll
+      for (int t = 0; t < 4; ++t) { v[t] = v0[t]; v[4 + t] = v1[t]; }
+      if (EPI == EPI_BIAS || EPI == EPI_BIAS_RESID || EPI == EPI_BIAS_GELU) {
+        float b8[8];
+        load_vec<bf16>(a.bias + n, b8);
+#pragma unroll
+        for (int t = 0; t < 8; ++t) v[t] += b8[t];
+      }
+      if (EPI == EPI_BIAS_RESID) {
+        float r8[8];
+        load_vec<bf16>(a.R + o, r8);
+#pragma unroll
+        for (int t = 0; t < 8; ++t) v[t] += r8[t];
+      }
+      if (EPI == EPI_BIAS_GELU) {
+        store_vec<bf16>(a.Z + o, v);
+#pragma unroll
+        for (int t = 0; t < 8; ++t) v[t] = gelu_fast(v[t]);
+      }
+      if (EPI == EPI_DGELU) {
+        float z8[8];
+        load_vec<bf16>(a.Z + o, z8);
+#pragma unroll
+        for (int t = 0; t < 8; ++t) v[t] *= gelu_grad_fast(z8[t]);
+      }
+      store_vec<bf16>(a.C + o, v);
     }
   }
 }
@@ -315,7 +372,8 @@ int launch_gemm_mfma(const GemmArgs<bf16>& a, hipStream_t s) {
   const bool ok_b = bk ? (a.K % 8 == 0 && a.b_rs % 8 == 0) : (a.b_rs == 1 && a.N % 8 == 0 && a.b_cs % 8 == 0);
   const int64_t ext_a = 2 * (ak ? (int64_t)a.M * a.a_rs : (int64_t)a.K * a.a_cs), ext_b = 2 * (bk ? (int64_t)a.N * a.b_rs : (int64_t)a.K * a.b_cs);
   const bool small = ext_a < (int64_t)0x7fffffff && ext_b < (int64_t)0x7fffffff;   // 32-bit buffer extents and offsets
-  if (!ok_a || !ok_b || !small || !aligned16(a.A) || !aligned16(a.B)) return launch_gemm_simple<bf16>(a, s);
+  const bool ok_c = a.N % 8 == 0 && aligned16(a.C) && aligned16(a.R) && aligned16(a.Z) && aligned16(a.bias) && aligned16(a.G);   // vector epilogue
+  if (!ok_a || !ok_b || !ok_c || !small || !aligned16(a.A) || !aligned16(a.B)) return launch_gemm_simple<bf16>(a, s);
   // Only the layout/epilogue pairs a linear layer produces are instantiated.
   if (ak && bk) {          // forward: Y = X W^T
     switch (a.epi) {
