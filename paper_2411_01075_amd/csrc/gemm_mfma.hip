@@ -244,6 +244,15 @@ __global__ void __launch_bounds__(kThreads) gemm_mfma_kernel(GemmArgs<bf16> a, i
 #pragma unroll
         for (int j = 0; j < NI; ++j)
           acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fb[cur][j], fa[cur][i], acc[i][j], 0, 0, 0);
+      // Scheduling hint: spread this k-step's fragment reads (for the next k-step) between its MFMAs, one LDS read
+      // per MFMAS_PER_READ matrix instructions, instead of bunching reads and then waiting on them.
+      constexpr int READS = (AK ? MI : 2 * MI) + (BKF ? NI : 2 * NI);
+      constexpr int MFMAS_PER_READ = (MI * NI) / READS > 0 ? (MI * NI) / READS : 1;
+#pragma unroll
+      for (int r = 0; r < READS; ++r) {
+        __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);               // one DS read
+        __builtin_amdgcn_sched_group_barrier(0x008, MFMAS_PER_READ, 0);  // then MFMAs
+      }
     }
   }
 
