@@ -286,6 +286,7 @@ __global__ void __launch_bounds__(kThreads) gemm_mfma_kernel(GemmArgs<bf16> a, i
   // accumulator layout into row-major 16-byte vectors; bias, residual and pre-activation are then read, and the
   // results written, as coalesced 16-byte accesses.  (All wavefronts are past the last barrier of the main loop
   // and hold their fragments in registers, so the operand stages are free.)
+  const int ldc = a.ldc ? a.ldc : a.N;
   constexpr int SP = WTN + 4;                           // staging pitch in floats (16 bytes of padding per row)
   constexpr int LPR = WTN / 8;                          // lanes per row when reading back 8 columns per lane
   constexpr int RPS = 64 / LPR;                         // rows per read step
@@ -310,7 +311,7 @@ __global__ void __launch_bounds__(kThreads) gemm_mfma_kernel(GemmArgs<bf16> a, i
       const f32x4 v1 = *reinterpret_cast<const LDS_AS f32x4*>(stage + r * SP + c + 4);
       const int m = m0 + wm + 32 * i + r;
       if (m >= a.M || n >= a.N) continue;
-      const int64_t o = (int64_t)m * a.N + n;
+      const int64_t o = (int64_t)m * ldc + n;
       float v[8];
 #pragma unroll
       for (int t = 0; t < 4; ++t) { v[t] = v0[t]; v[4 + t] = v1[t]; }
@@ -376,12 +377,15 @@ int launch_tiles(const GemmArgs<bf16>& a, hipStream_t s) {
 int launch_gemm_mfma(const GemmArgs<bf16>& a, hipStream_t s) {
   if (a.M <= 0 || a.N <= 0 || a.K <= 0) return fail(CEPHALO_EINVAL, "gemm: empty problem %dx%dx%d", a.M, a.N, a.K);
   const bool ak = a.a_cs == 1, bk = a.b_cs == 1;
-  // 16-byte vector loads need the contiguous extent and the strided pitch to be multiples of 8 elements.
-  const bool ok_a = ak ? (a.K % 8 == 0 && a.a_rs % 8 == 0) : (a.a_rs == 1 && a.M % 8 == 0 && a.a_cs % 8 == 0);
-  const bool ok_b = bk ? (a.K % 8 == 0 && a.b_rs % 8 == 0) : (a.b_rs == 1 && a.N % 8 == 0 && a.b_cs % 8 == 0);
+  // 16-byte vector loads: pitches are multiples of 8 elements; a contiguous extent that is not a multiple of 8 is
+  // accepted when the pitch covers it rounded up (the caller keeps that padding zero: it is read, never stored).
+  auto up8 = [](int64_t v) { return (v + 7) / 8 * 8; };
+  const bool ok_a = ak ? (a.a_rs % 8 == 0 && a.a_rs >= up8(a.K)) : (a.a_rs == 1 && a.a_cs % 8 == 0 && a.a_cs >= up8(a.M));
+  const bool ok_b = bk ? (a.b_rs % 8 == 0 && a.b_rs >= up8(a.K)) : (a.b_rs == 1 && a.b_cs % 8 == 0 && a.b_cs >= up8(a.N));
   const int64_t ext_a = 2 * (ak ? (int64_t)a.M * a.a_rs : (int64_t)a.K * a.a_cs), ext_b = 2 * (bk ? (int64_t)a.N * a.b_rs : (int64_t)a.K * a.b_cs);
   const bool small = ext_a < (int64_t)0x7fffffff && ext_b < (int64_t)0x7fffffff;   // 32-bit buffer extents and offsets
-  const bool ok_c = a.N % 8 == 0 && aligned16(a.C) && aligned16(a.R) && aligned16(a.Z) && aligned16(a.bias) && aligned16(a.G);   // vector epilogue
+  const int64_t pitch_c = a.ldc ? a.ldc : a.N;
+  const bool ok_c = pitch_c % 8 == 0 && pitch_c >= up8(a.N) && (a.epi != EPI_GRAD || a.N % 8 == 0) && aligned16(a.C) && aligned16(a.R) && aligned16(a.Z) && aligned16(a.bias) && aligned16(a.G);   // vector epilogue
   if (!ok_a || !ok_b || !ok_c || !small || !aligned16(a.A) || !aligned16(a.B)) return launch_gemm_simple<bf16>(a, s);
   // Only the layout/epilogue pairs a linear layer produces are instantiated.
   if (ak && bk) {          // forward: Y = X W^T

@@ -65,7 +65,7 @@ __global__ void __launch_bounds__(kThreads) gemm_simple_kernel(GemmArgs<T> a) {
     for (int j = 0; j < 4; ++j) {
       const int n = n0 + tx * 4 + j;
       if (n >= a.N) continue;
-      const int64_t o = (int64_t)m * a.N + n;
+      const int64_t o = a.epi == EPI_GRAD ? (int64_t)m * a.N + n : (int64_t)m * (a.ldc ? a.ldc : a.N) + n;
       float v = acc[i][j];
       switch (a.epi) {
         case EPI_NONE: a.C[o] = (T)v; break;

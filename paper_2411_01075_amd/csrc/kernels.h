@@ -94,7 +94,9 @@ struct GemmArgs {
   const T* B; int64_t b_rs, b_cs;
   int M, N, K;
   int epi;
-  T* C;            // [M,N] row-major, ldc = N (unused for EPI_GRAD)
+  T* C;            // [M,N] row-major with row pitch ldc (unused for EPI_GRAD)
+  int ldc;         // row pitch of C, R and Z in elements; 0 means N.  If N is not a multiple of 8 the pitch must cover N
+                   // rounded up to 8; the padding columns are then written too (with the products of zero B rows)
   const T* bias;   // [N]
   const T* R;      // [M,N] residual
   T* Z;            // [M,N] pre-activation: written by EPI_BIAS_GELU, read by EPI_DGELU

@@ -1,373 +1,7 @@
-// Host driver of one transformer layer on one micro-batch, and of a whole batch share:
-// argument checks in the paper's terms (batch share b, micro-batch size m, b = l*m),
-// workspace carving, and the launch sequence on the caller's stream.
-#include "kernels.h"
-#include <type_traits>
-
-#define TRY(expr) do { int rc__ = (expr); if (rc__ != CEPHALO_OK) return rc__; } while (0)
-
-namespace cephalo {
-namespace {
-
-inline size_t align_up(size_t x) { return (x + 255) & ~(size_t)255; }
-
-// Offsets (elements) of the 12 tensors of the flat layer layout.
-struct ParamOffsets {
-  int64_t ln1_g, ln1_b, w_qkv, b_qkv, w_o, b_o, ln2_g, ln2_b, w_fc1, b_fc1, w_fc2, b_fc2, total;
-};
-
-ParamOffsets param_offsets(const cephalo_layer_desc& d) {
-  const int64_t H = d.hidden, F = d.mlp;
-  ParamOffsets o;
-  int64_t p = 0;
-  o.ln1_g = p; p += H;
-  o.ln1_b = p; p += H;
-  o.w_qkv = p; p += 3 * H * H;
-  o.b_qkv = p; p += 3 * H;
-  o.w_o = p;   p += H * H;
-  o.b_o = p;   p += H;
-  o.ln2_g = p; p += H;
-  o.ln2_b = p; p += H;
-  o.w_fc1 = p; p += F * H;
-  o.b_fc1 = p; p += F;
-  o.w_fc2 = p; p += H * F;
-  o.b_fc2 = p; p += H;
-  o.total = p;
-  return o;
-}
-
-int check_desc(const cephalo_layer_desc* d) {
-  if (!d) return fail(CEPHALO_EINVAL, "layer desc is null");
-  if (d->hidden <= 0 || d->heads <= 0 || d->mlp <= 0 || d->seq <= 0)
-    return fail(CEPHALO_EINVAL, "layer desc: hidden %d heads %d mlp %d seq %d must all be positive",
-                d->hidden, d->heads, d->mlp, d->seq);
-  if (d->hidden % d->heads != 0)
-    return fail(CEPHALO_EINVAL, "layer desc: hidden %d is not a multiple of heads %d", d->hidden, d->heads);
-  if (d->dtype != CEPHALO_F32 && d->dtype != CEPHALO_BF16) return fail(CEPHALO_EINVAL, "layer desc: unknown dtype %d", d->dtype);
-  if (d->causal != 0 && d->causal != 1) return fail(CEPHALO_EINVAL, "layer desc: causal must be 0 or 1");
-  if (!(d->ln_eps >= 0.f)) return fail(CEPHALO_EINVAL, "layer desc: ln_eps %g < 0", d->ln_eps);
-  if (d->hidden % 8 != 0 || d->mlp % 8 != 0)
-    return fail(CEPHALO_EUNSUPPORTED, "layer desc: hidden %d and mlp %d must be multiples of 8 (16-byte rows)", d->hidden, d->mlp);
-  const int hd = d->hidden / d->heads;
-  if (hd > 128) return fail(CEPHALO_EUNSUPPORTED, "layer desc: head dim %d > 128", hd);
-  if (d->dtype == CEPHALO_BF16 && hd != 64 && hd != 128)
-    return fail(CEPHALO_EUNSUPPORTED, "layer desc: bf16 attention needs head dim 64 or 128, got %d", hd);
-  if (d->hidden > 8192) return fail(CEPHALO_EUNSUPPORTED, "layer desc: hidden %d > 8192", d->hidden);
-  return CEPHALO_OK;
-}
-
-// Saved activations of `n` samples, tensor-major: each tensor is one [n*S, width] matrix, so the
-// slice of a micro-batch is a row range and the whole share is one contiguous operand.
-struct SaveLayout {
-  size_t mean1, rstd1, u, qkv, lse, O, x1, mean2, rstd2, u2, z, h, total;
-};
-// Backward work area.  dz, dx1 and dqkv (the dY operands of the weight gradients) are kept for `span`
-// samples; the rest is per micro-batch of m samples.
-struct ScratchLayout {
-  size_t dz, dx1, dqkv, du2, dO, du, dvec, tpose, ln_part, col_part, col_part_bytes, total;
-  size_t ln_rows;   // rows of each of the four LayerNorm partial arrays (ln2.gamma, ln2.beta, ln1.gamma, ln1.beta)
-};
-
-SaveLayout save_layout(const cephalo_layer_desc& d, int n) {
-  const size_t es = d.dtype == CEPHALO_F32 ? 4 : 2;
-  const size_t T = (size_t)n * d.seq, H = d.hidden, F = d.mlp;
-  SaveLayout L;
-  size_t p = 0;
-  auto take = [&](size_t bytes) { size_t at = p; p += align_up(bytes); return at; };
-  L.mean1 = take(T * 4); L.rstd1 = take(T * 4);
-  L.u = take(T * H * es);
-  L.qkv = take(T * 3 * H * es);
-  L.lse = take((size_t)n * d.heads * d.seq * 4);
-  L.O = take(T * H * es);
-  L.x1 = take(T * H * es);
-  L.mean2 = take(T * 4); L.rstd2 = take(T * 4);
-  L.u2 = take(T * H * es);
-  L.z = take(T * F * es);
-  L.h = take(T * F * es);
-  L.total = p;
-  return L;
-}
-
-ScratchLayout scratch_layout(const cephalo_layer_desc& d, int m, int span) {
-  const size_t es = d.dtype == CEPHALO_F32 ? 4 : 2;
-  const size_t Tm = (size_t)m * d.seq, Ts = (size_t)span * d.seq, H = d.hidden, F = d.mlp;
-  ScratchLayout L;
-  size_t p = 0;
-  auto take = [&](size_t bytes) { size_t at = p; p += align_up(bytes); return at; };
-  L.dz = take(Ts * F * es);
-  L.dx1 = take(Ts * H * es);
-  L.dqkv = take(Ts * 3 * H * es);
-  L.du2 = take(Tm * H * es);
-  L.dO = take(Tm * H * es);
-  L.du = take(Tm * H * es);
-  L.dvec = take((size_t)m * d.heads * d.seq * 4);
-  L.tpose = take(Ts * H * es);     // [H, tokens] token-minor copy of one activation for the weight-gradient GEMMs
-  L.ln_rows = (size_t)(span / m) * ln_bwd_blocks((int)Tm);
-  L.ln_part = take(4 * L.ln_rows * H * sizeof(float));
-  const int widest = (int)(3 * H > F ? 3 * H : F);
-  L.col_part_bytes = colsum_partial_bytes((int)Ts, widest);
-  L.col_part = take(L.col_part_bytes);
-  L.total = p;
-  return L;
-}
-
-// ---- kernel selection ------------------------------------------------------------------
-template <typename T> int gemm(const GemmArgs<T>& a, hipStream_t s);
-template <> int gemm<float>(const GemmArgs<float>& a, hipStream_t s) { return launch_gemm_simple<float>(a, s); }
-template <> int gemm<bf16>(const GemmArgs<bf16>& a, hipStream_t s) { return launch_gemm_mfma(a, s); }
-
-template <typename T> int attn_fwd(const T* qkv, T* O, float* lse, int m, int S, int H, int A, int causal, hipStream_t s);
-template <> int attn_fwd<float>(const float* qkv, float* O, float* lse, int m, int S, int H, int A, int causal, hipStream_t s) {
-  return launch_attn_fwd_simple<float>(qkv, O, lse, m, S, H, A, causal, s);
-}
-template <> int attn_fwd<bf16>(const bf16* qkv, bf16* O, float* lse, int m, int S, int H, int A, int causal, hipStream_t s) {
-  return launch_attn_fwd_mfma(qkv, O, lse, m, S, H, A, causal, s);
-}
-template <typename T>
-int attn_bwd(const T* qkv, const T* O, const T* dO, const float* lse, float* dvec, T* dqkv, int m, int S, int H, int A, int causal, hipStream_t s);
-template <> int attn_bwd<float>(const float* qkv, const float* O, const float* dO, const float* lse, float* dvec, float* dqkv,
-                                int m, int S, int H, int A, int causal, hipStream_t s) {
-  return launch_attn_bwd_simple<float>(qkv, O, dO, lse, dvec, dqkv, m, S, H, A, causal, s);
-}
-template <> int attn_bwd<bf16>(const bf16* qkv, const bf16* O, const bf16* dO, const float* lse, float* dvec, bf16* dqkv,
-                               int m, int S, int H, int A, int causal, hipStream_t s) {
-  return launch_attn_bwd_mfma(qkv, O, dO, lse, dvec, dqkv, m, S, H, A, causal, s);
-}
-
-template <typename T> T* at(void* base, size_t off) { return reinterpret_cast<T*>(static_cast<char*>(base) + off); }
-template <typename T> const T* at(const void* base, size_t off) { return reinterpret_cast<const T*>(static_cast<const char*>(base) + off); }
-
-// Y[T,N] = X[T,K] W[N,K]^T (+ epilogue): both operands k-contiguous
-template <typename T>
-GemmArgs<T> linear_fwd(const T* X, const T* W, int Tn, int N, int K) {
-  GemmArgs<T> a = {};
-  a.A = X; a.a_rs = K; a.a_cs = 1;
-  a.B = W; a.b_rs = K; a.b_cs = 1;
-  a.M = Tn; a.N = N; a.K = K;
-  return a;
-}
-// dX[T,K] = dY[T,N] W[N,K]: contraction over N; B(n'=k, k'=n) = W[n*K + k]
-template <typename T>
-GemmArgs<T> linear_dgrad(const T* dY, const T* W, int Tn, int N, int K) {
-  GemmArgs<T> a = {};
-  a.A = dY; a.a_rs = N; a.a_cs = 1;
-  a.B = W; a.b_rs = 1; a.b_cs = K;
-  a.M = Tn; a.N = K; a.K = N;
-  return a;
-}
-// dW[N,K] = dY[T,N]^T X[T,K]: contraction over T; both operands strided along it
-template <typename T>
-GemmArgs<T> linear_wgrad(const T* dY, const T* X, int Tn, int N, int K, float* G, float scale, int accumulate) {
-  GemmArgs<T> a = {};
-  a.A = dY; a.a_rs = 1; a.a_cs = N;
-  a.B = X; a.b_rs = 1; a.b_cs = K;
-  a.M = N; a.N = K; a.K = Tn;
-  a.epi = EPI_GRAD; a.G = G; a.scale = scale; a.accumulate = accumulate;
-  return a;
-}
-
-// Weight gradient of a linear layer, G[N,K] (+)= scale * dY[T,N]^T X[T,K].  Both operands are strided along
-// the contracted token axis.  In bf16 the narrower of the two is first copied token-minor ([N,T] or [K,T]):
-// its MFMA fragments then come from 16-byte LDS reads, which run at about three times the rate of the
-// transposing reads the other operand needs, for one extra pass over the small matrix.
-template <typename T>
-int wgrad(const T* dY, const T* X, int Tn, int N, int K, float* G, float scale, int acc, T* tbuf, hipStream_t s);
-template <>
-int wgrad<float>(const float* dY, const float* X, int Tn, int N, int K, float* G, float scale, int acc, float*, hipStream_t s) {
-  return gemm<float>(linear_wgrad<float>(dY, X, Tn, N, K, G, scale, acc), s);
-}
-template <>
-int wgrad<bf16>(const bf16* dY, const bf16* X, int Tn, int N, int K, float* G, float scale, int acc, bf16* tbuf, hipStream_t s) {
-  GemmArgs<bf16> a = linear_wgrad<bf16>(dY, X, Tn, N, K, G, scale, acc);
-  if (Tn % 8 != 0) return gemm<bf16>(a, s);
-  if (N <= K) {   // dY^T [N, T] as the k-contiguous A operand
-    TRY(launch_transpose_bf16(dY, tbuf, Tn, N, s));
-    a.A = tbuf; a.a_rs = Tn; a.a_cs = 1;
-  } else {        // X^T [K, T] as the k-contiguous B operand
-    TRY(launch_transpose_bf16(X, tbuf, Tn, K, s));
-    a.B = tbuf; a.b_rs = Tn; a.b_cs = 1;
-  }
-  return gemm<bf16>(a, s);
-}
-
-template <typename T> struct Saved {
-  float *mean1, *rstd1, *lse, *mean2, *rstd2;
-  T *u, *qkv, *O, *x1, *u2, *z, *h;
-};
-// pointers to the saved tensors of the samples starting at `sample0` inside a save area laid out by L
-template <typename T>
-Saved<T> saved_at(void* base, const SaveLayout& L, const cephalo_layer_desc& d, int sample0) {
-  const size_t t0 = (size_t)sample0 * d.seq, H = d.hidden, F = d.mlp;
-  Saved<T> s;
-  s.mean1 = at<float>(base, L.mean1) + t0; s.rstd1 = at<float>(base, L.rstd1) + t0;
-  s.mean2 = at<float>(base, L.mean2) + t0; s.rstd2 = at<float>(base, L.rstd2) + t0;
-  s.lse = at<float>(base, L.lse) + (size_t)sample0 * d.heads * d.seq;
-  s.u = at<T>(base, L.u) + t0 * H; s.qkv = at<T>(base, L.qkv) + t0 * 3 * H; s.O = at<T>(base, L.O) + t0 * H;
-  s.x1 = at<T>(base, L.x1) + t0 * H; s.u2 = at<T>(base, L.u2) + t0 * H;
-  s.z = at<T>(base, L.z) + t0 * F; s.h = at<T>(base, L.h) + t0 * F;
-  return s;
-}
-
-template <typename T> struct Work {
-  T *dz, *dx1, *dqkv;          // at the token offset of the current micro-batch (or of the span for the parameter pass)
-  T *du2, *dO, *du, *tbuf;
-  float *dvec;
-  float *ln2_g, *ln2_b, *ln1_g, *ln1_b;   // LayerNorm partial sums, at the row offset of the current micro-batch
-  float *col_part; size_t col_part_bytes;
-};
-template <typename T>
-Work<T> work_at(void* base, const ScratchLayout& W, const cephalo_layer_desc& d, int sample0, int mb_index, int m) {
-  const size_t t0 = (size_t)sample0 * d.seq, H = d.hidden, F = d.mlp;
-  Work<T> w;
-  w.dz = at<T>(base, W.dz) + t0 * F; w.dx1 = at<T>(base, W.dx1) + t0 * H; w.dqkv = at<T>(base, W.dqkv) + t0 * 3 * H;
-  w.du2 = at<T>(base, W.du2); w.dO = at<T>(base, W.dO); w.du = at<T>(base, W.du); w.tbuf = at<T>(base, W.tpose);
-  w.dvec = at<float>(base, W.dvec);
-  float* ln = at<float>(base, W.ln_part);
-  const size_t r0 = (size_t)mb_index * ln_bwd_blocks(m * d.seq) * H, arr = W.ln_rows * H;
-  w.ln2_g = ln + r0; w.ln2_b = ln + arr + r0; w.ln1_g = ln + 2 * arr + r0; w.ln1_b = ln + 3 * arr + r0;
-  w.col_part = at<float>(base, W.col_part); w.col_part_bytes = W.col_part_bytes;
-  return w;
-}
-
-// ---- forward of one micro-batch ----------------------------------------------------------------
-template <typename T>
-int layer_fwd_t(const cephalo_layer_desc& d, const T* P, const T* x, T* y, int m, const Saved<T>& sv, hipStream_t s) {
-  const ParamOffsets o = param_offsets(d);
-  const int Tn = m * d.seq, H = d.hidden, F = d.mlp;
-  TRY(launch_ln_fwd<T>(x, P + o.ln1_g, P + o.ln1_b, sv.u, sv.mean1, sv.rstd1, Tn, H, d.ln_eps, s));
-  {
-    GemmArgs<T> a = linear_fwd<T>(sv.u, P + o.w_qkv, Tn, 3 * H, H);
-    a.epi = EPI_BIAS; a.bias = P + o.b_qkv; a.C = sv.qkv;
-    TRY(gemm<T>(a, s));
-  }
-  TRY(attn_fwd<T>(sv.qkv, sv.O, sv.lse, m, d.seq, H, d.heads, d.causal, s));
-  {
-    GemmArgs<T> a = linear_fwd<T>(sv.O, P + o.w_o, Tn, H, H);
-    a.epi = EPI_BIAS_RESID; a.bias = P + o.b_o; a.R = x; a.C = sv.x1;
-    TRY(gemm<T>(a, s));
-  }
-  TRY(launch_ln_fwd<T>(sv.x1, P + o.ln2_g, P + o.ln2_b, sv.u2, sv.mean2, sv.rstd2, Tn, H, d.ln_eps, s));
-  {
-    GemmArgs<T> a = linear_fwd<T>(sv.u2, P + o.w_fc1, Tn, F, H);
-    a.epi = EPI_BIAS_GELU; a.bias = P + o.b_fc1; a.Z = sv.z; a.C = sv.h;
-    TRY(gemm<T>(a, s));
-  }
-  {
-    GemmArgs<T> a = linear_fwd<T>(sv.h, P + o.w_fc2, Tn, H, F);
-    a.epi = EPI_BIAS_RESID; a.bias = P + o.b_fc2; a.R = sv.x1; a.C = y;
-    TRY(gemm<T>(a, s));
-  }
-  return CEPHALO_OK;
-}
-
-// ---- backward, data path of one micro-batch: dx and the dY operands (dz, dx1, dqkv) of the weight gradients --------
-template <typename T>
-int layer_bwd_data_t(const cephalo_layer_desc& d, const T* P, const T* x, const T* dy, T* dx, int m,
-                     const Saved<T>& sv, const Work<T>& w, hipStream_t s) {
-  const ParamOffsets o = param_offsets(d);
-  const int Tn = m * d.seq, H = d.hidden, F = d.mlp;
-  {
-    GemmArgs<T> a = linear_dgrad<T>(dy, P + o.w_fc2, Tn, H, F);   // dh = dy W2, then dz = dh * gelu'(z)
-    a.epi = EPI_DGELU; a.Z = sv.z; a.C = w.dz;
-    TRY(gemm<T>(a, s));
-  }
-  {
-    GemmArgs<T> a = linear_dgrad<T>(w.dz, P + o.w_fc1, Tn, F, H);
-    a.epi = EPI_NONE; a.C = w.du2;
-    TRY(gemm<T>(a, s));
-  }
-  // u2 = LN2(x1); dx1 = dy + LN2-backward(du2)
-  TRY(launch_ln_bwd<T>(w.du2, sv.x1, sv.mean2, sv.rstd2, P + o.ln2_g, dy, w.dx1, w.ln2_g, w.ln2_b, Tn, H, s));
-  {
-    GemmArgs<T> a = linear_dgrad<T>(w.dx1, P + o.w_o, Tn, H, H);
-    a.epi = EPI_NONE; a.C = w.dO;
-    TRY(gemm<T>(a, s));
-  }
-  TRY(attn_bwd<T>(sv.qkv, sv.O, w.dO, sv.lse, w.dvec, w.dqkv, m, d.seq, H, d.heads, d.causal, s));
-  {
-    GemmArgs<T> a = linear_dgrad<T>(w.dqkv, P + o.w_qkv, Tn, 3 * H, H);
-    a.epi = EPI_NONE; a.C = w.du;
-    TRY(gemm<T>(a, s));
-  }
-  // u = LN1(x); dx = dx1 + LN1-backward(du)
-  TRY(launch_ln_bwd<T>(w.du, x, sv.mean1, sv.rstd1, P + o.ln1_g, w.dx1, dx, w.ln1_g, w.ln1_b, Tn, H, s));
-  return CEPHALO_OK;
-}
-
-// ---- backward, parameter path over `tokens` tokens (one micro-batch, or the whole share at once) ---------------------
-// G <- (acc ? G : 0) + scale * (gradient summed over those tokens).  Over the whole share the sum over micro-batches
-// happens inside the fp32 MFMA accumulators and each gradient element is written exactly once.
-template <typename T>
-int layer_bwd_params_t(const cephalo_layer_desc& d, const T* dy, int tokens, int ln_chunks,
-                       const Saved<T>& sv, const Work<T>& w, float* G, float scale, int acc, hipStream_t s) {
-  const ParamOffsets o = param_offsets(d);
-  const int H = d.hidden, F = d.mlp;
-  TRY(launch_colsum<T>(dy, w.col_part, w.col_part_bytes, G + o.b_fc2, scale, acc, tokens, H, s));
-  TRY(wgrad<T>(dy, sv.h, tokens, H, F, G + o.w_fc2, scale, acc, w.tbuf, s));
-  TRY(launch_colsum<T>(w.dz, w.col_part, w.col_part_bytes, G + o.b_fc1, scale, acc, tokens, F, s));
-  TRY(wgrad<T>(w.dz, sv.u2, tokens, F, H, G + o.w_fc1, scale, acc, w.tbuf, s));
-  TRY(launch_reduce_partials(w.ln2_g, ln_chunks, H, G + o.ln2_g, scale, acc, s));
-  TRY(launch_reduce_partials(w.ln2_b, ln_chunks, H, G + o.ln2_b, scale, acc, s));
-  TRY(launch_colsum<T>(w.dx1, w.col_part, w.col_part_bytes, G + o.b_o, scale, acc, tokens, H, s));
-  TRY(wgrad<T>(w.dx1, sv.O, tokens, H, H, G + o.w_o, scale, acc, w.tbuf, s));
-  TRY(launch_colsum<T>(w.dqkv, w.col_part, w.col_part_bytes, G + o.b_qkv, scale, acc, tokens, 3 * H, s));
-  TRY(wgrad<T>(w.dqkv, sv.u, tokens, 3 * H, H, G + o.w_qkv, scale, acc, w.tbuf, s));
-  TRY(launch_reduce_partials(w.ln1_g, ln_chunks, H, G + o.ln1_g, scale, acc, s));
-  TRY(launch_reduce_partials(w.ln1_b, ln_chunks, H, G + o.ln1_b, scale, acc, s));
-  return CEPHALO_OK;
-}
-
-template <typename T>
-int run_fwd(const cephalo_layer_desc& d, const void* P, const void* x, void* y, int m, void* save, hipStream_t s) {
-  const SaveLayout L = save_layout(d, m);
-  return layer_fwd_t<T>(d, static_cast<const T*>(P), static_cast<const T*>(x), static_cast<T*>(y), m, saved_at<T>(save, L, d, 0), s);
-}
-
-template <typename T>
-int run_bwd(const cephalo_layer_desc& d, const void* P, const void* x, const void* dy, void* dx, int m, void* save,
-            float* G, float scale, int acc, void* scratch, hipStream_t s) {
-  const SaveLayout L = save_layout(d, m);
-  const ScratchLayout W = scratch_layout(d, m, m);
-  const Saved<T> sv = saved_at<T>(save, L, d, 0);
-  const Work<T> w = work_at<T>(scratch, W, d, 0, 0, m);
-  TRY(layer_bwd_data_t<T>(d, static_cast<const T*>(P), static_cast<const T*>(x), static_cast<const T*>(dy), static_cast<T*>(dx), m, sv, w, s));
-  return layer_bwd_params_t<T>(d, static_cast<const T*>(dy), m * d.seq, ln_bwd_blocks(m * d.seq), sv, w, G, scale, acc, s);
-}
-
-// Whole share: forward of every micro-batch, data-path backward of every micro-batch, then ONE parameter pass over
-// all b*S tokens (the dY operands and the saved activations of all micro-batches are contiguous by construction).
-template <typename T>
-int run_share(const cephalo_layer_desc& d, const void* Pv, const void* xv, void* yv, const void* dyv, void* dxv,
-              int b, int m, void* save, float* G, float scale, void* scratch, hipStream_t s) {
-  const T* P = static_cast<const T*>(Pv);
-  const T* x = static_cast<const T*>(xv); T* y = static_cast<T*>(yv);
-  const T* dy = static_cast<const T*>(dyv); T* dx = static_cast<T*>(dxv);
-  const SaveLayout L = save_layout(d, b);
-  const ScratchLayout W = scratch_layout(d, m, b);
-  const int l = b / m;
-  const size_t act = (size_t)m * d.seq * d.hidden;   // elements of one micro-batch of x / y / dy / dx
-  for (int j = 0; j < l; ++j)
-    TRY(layer_fwd_t<T>(d, P, x + j * act, y + j * act, m, saved_at<T>(save, L, d, j * m), s));
-  for (int j = 0; j < l; ++j)
-    TRY(layer_bwd_data_t<T>(d, P, x + j * act, dy + j * act, dx + j * act, m, saved_at<T>(save, L, d, j * m),
-                            work_at<T>(scratch, W, d, j * m, j, m), s));
-  return layer_bwd_params_t<T>(d, dy, b * d.seq, l * ln_bwd_blocks(m * d.seq), saved_at<T>(save, L, d, 0),
-                               work_at<T>(scratch, W, d, 0, 0, m), G, scale, 0, s);
-}
-
-int check_io(const char* who, const cephalo_layer_desc* d, int m, std::initializer_list<const void*> ptrs) {
-  TRY(check_desc(d));
-  if (m <= 0) return fail(CEPHALO_EINVAL, "%s: micro-batch size m = %d must be positive", who, m);
-  if ((int64_t)m * d->seq > (1 << 24)) return fail(CEPHALO_EUNSUPPORTED, "%s: m*S = %lld tokens per micro-batch is too many", who, (long long)m * d->seq);
-  for (const void* p : ptrs) {
-    if (!p) return fail(CEPHALO_EINVAL, "%s: null pointer argument", who);
-    if (!aligned16(p)) return fail(CEPHALO_EINVAL, "%s: pointer %p is not 16-byte aligned", who, p);
-  }
-  return CEPHALO_OK;
-}
-
-}  // namespace
-}  // namespace cephalo
+// C-ABI entry points of one transformer layer on one micro-batch and on a whole batch share:
+// argument checks in the paper's terms (batch share b, micro-batch size m, b = l*m), then the
+// launch sequences of layer_impl.h on the caller's stream.
+#include "layer_impl.h"
 
 using namespace cephalo;
 
