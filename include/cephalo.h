@@ -186,6 +186,39 @@ int cephalo_op_attention_fwd(const cephalo_layer_desc* desc, const void* qkv, vo
 int cephalo_op_attention_bwd(const cephalo_layer_desc* desc, const void* qkv, const void* O, const void* dO,
                              const float* lse, float* dvec, void* dqkv, int32_t micro_batch, void* stream);
 
+/* ---------------------------------------------------------------------------------------
+ * A whole stack on one GPU's batch share, in the layered order of Sec. 3.2 ("Layered Gradient
+ * Accumulation": all micro-batches pass through a layer before the next layer, forward and backward).
+ * The paper trains such models (Table 2) without describing their pieces; the form here: learned token
+ * and position embeddings x0 = wte[id] + wpe[pos], `layers` layers as above, final LayerNorm, logits =
+ * lnf(x) wte^T (tied, no bias), loss = mean cross-entropy over all b*S tokens.
+ * Flat layout: wte[V,H] wpe[S,H] layer 0 .. layer L-1 (each as above) lnf.gamma[H] lnf.beta[H].
+ */
+typedef struct cephalo_stack_desc {
+  cephalo_layer_desc layer;
+  int32_t layers;   /* L */
+  int32_t vocab;    /* V */
+} cephalo_stack_desc;
+
+/* V*H + S*H + L*P_layer + 2H; negative on a bad desc. */
+int64_t cephalo_stack_param_count(const cephalo_stack_desc* desc);
+
+/* Bytes of the single work area of cephalo_stack_step (layer-boundary activations and saved activations of
+ * every layer and micro-batch, the share's logits, backward buffers).  Host pointer out. */
+int cephalo_stack_workspace_bytes(const cephalo_stack_desc* desc, int32_t batch_share, int32_t micro_batch, size_t* bytes);
+
+/* Forward, loss and backward of the whole share (b = l*m, Sec. 3.2):
+ *   loss[0]   <- mean over the b*S tokens of the cross-entropy (device, one float)
+ *   flat_grad <- grad_scale * d(loss)/d(parameters), every element written (device, [P] fp32); grad_scale is
+ *                Eq. 1's factor.  The sum over micro-batches is formed inside the weight-gradient GEMMs.
+ *   flat_param   device, [P] in the compute dtype;  ids, targets  device, int32 [b, S]; values outside [0, V)
+ *                are clamped into range.
+ * Reproducible: no atomics; token-embedding rows are summed in ascending token order. */
+int cephalo_stack_step(const cephalo_stack_desc* desc, const void* flat_param,
+                       const int32_t* ids, const int32_t* targets, int32_t batch_share, int32_t micro_batch,
+                       float* flat_grad, float grad_scale, float* loss,
+                       void* workspace, size_t workspace_bytes, void* stream);
+
 #ifdef __cplusplus
 }
 #endif

@@ -35,6 +35,14 @@ def desc_from_config(cfg):
     return layer_desc(cfg.hidden, cfg.heads, cfg.mlp, cfg.seq, cfg.causal, F32 if cfg.dtype == "f32" else BF16)
 
 
+class StackDesc(ctypes.Structure):
+    _fields_ = [("layer", LayerDesc), ("layers", ctypes.c_int32), ("vocab", ctypes.c_int32)]
+
+
+def stack_desc_from_config(cfg):
+    return StackDesc(desc_from_config(cfg), int(cfg.layers), int(cfg.vocab))
+
+
 _vp, _i32, _i64, _f32, _sz = ctypes.c_void_p, ctypes.c_int32, ctypes.c_int64, ctypes.c_float, ctypes.c_size_t
 _dp = ctypes.POINTER(LayerDesc)
 
@@ -52,6 +60,9 @@ SIGNATURES = {
     "cephalo_grad_accum": (ctypes.c_int, [_vp, _vp, _f32, _i64, _vp]),
     "cephalo_shard_adam": (ctypes.c_int, [_vp, _vp, _vp, _vp, _vp, _i64, _i64, _i64, _f32, _f32, _f32, _f32, _i64, _vp]),
     "cephalo_cast_bf16": (ctypes.c_int, [_vp, _vp, _i64, _vp]),
+    "cephalo_stack_param_count": (_i64, [ctypes.POINTER(StackDesc)]),
+    "cephalo_stack_workspace_bytes": (ctypes.c_int, [ctypes.POINTER(StackDesc), _i32, _i32, ctypes.POINTER(_sz)]),
+    "cephalo_stack_step": (ctypes.c_int, [ctypes.POINTER(StackDesc), _vp, _vp, _vp, _i32, _i32, _vp, _f32, _vp, _vp, _sz, _vp]),
     "cephalo_op_gemm": (ctypes.c_int, [_i32, _vp, _i64, _i64, _vp, _i64, _i64, _i32, _i32, _i32, _i32, _vp, _vp, _vp, _vp,
                                        _vp, _f32, _i32, _vp]),
     "cephalo_op_attention_fwd": (ctypes.c_int, [_dp, _vp, _vp, _vp, _i32, _vp]),
@@ -194,4 +205,46 @@ def flatten_layer_params(desc, tensors):
     for name, o in zip(LAYER_TENSOR_NAMES, offs):
         t = tensors[name]
         flat[o:o + t.size] = t.reshape(-1)
+    return flat
+
+
+def cephalo_stack_param_count(sdesc):
+    n = lib().cephalo_stack_param_count(ctypes.byref(sdesc))
+    if n < 0:
+        _check(int(n))
+    return int(n)
+
+
+def cephalo_stack_workspace_bytes(sdesc, batch_share, micro_batch):
+    a = _sz(0)
+    _check(lib().cephalo_stack_workspace_bytes(ctypes.byref(sdesc), batch_share, micro_batch, ctypes.byref(a)))
+    return a.value
+
+
+def cephalo_stack_step(sdesc, flat_param, ids, targets, batch_share, micro_batch, flat_grad, grad_scale, loss, workspace,
+                       stream=None):
+    _check(lib().cephalo_stack_step(ctypes.byref(sdesc), _ptr(flat_param), _ptr(ids), _ptr(targets), batch_share, micro_batch,
+                                    _ptr(flat_grad), grad_scale, _ptr(loss), _ptr(workspace),
+                                    workspace.numel() * workspace.element_size(), _stream(stream)))
+
+
+def flatten_stack_params(sdesc, params):
+    """Host-side marshalling of a stack's parameters (wte, wpe, layers, lnf_g, lnf_b) to the fp32 flat vector."""
+    import numpy as np
+    P = cephalo_stack_param_count(sdesc)
+    PL = cephalo_layer_param_count(sdesc.layer)
+    flat = np.empty(P, dtype=np.float32)
+    pos = 0
+    for name in ("wte", "wpe"):
+        t = params[name]
+        flat[pos:pos + t.size] = t.reshape(-1)
+        pos += t.size
+    for lp in params["layers"]:
+        flat[pos:pos + PL] = flatten_layer_params(sdesc.layer, lp)
+        pos += PL
+    for name in ("lnf_g", "lnf_b"):
+        t = params[name]
+        flat[pos:pos + t.size] = t.reshape(-1)
+        pos += t.size
+    assert pos == P
     return flat

@@ -110,7 +110,12 @@ ln_bwd_kernel(const T* __restrict__ du, const T* __restrict__ x, const float* __
       const int v = lane + 64 * j;
       if (v < nv) {
         float rr[VN], o[VN];
-        load_vec<T>(resid + (int64_t)row * H + v * VN, rr);
+        if (resid) {
+          load_vec<T>(resid + (int64_t)row * H + v * VN, rr);
+        } else {
+#pragma unroll
+          for (int i = 0; i < VN; ++i) rr[i] = 0.f;
+        }
 #pragma unroll
         for (int i = 0; i < VN; ++i) o[i] = rr[i] + rs * (g[j][i] - c1 - xh[j][i] * c2);
         store_vec<T>(out + (int64_t)row * H + v * VN, o);

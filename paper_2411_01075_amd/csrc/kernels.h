@@ -114,7 +114,7 @@ template <typename T>
 int launch_ln_fwd(const T* x, const T* gamma, const T* beta, T* u, float* mean, float* rstd,
                   int rows, int H, float eps, hipStream_t s);
 
-// out = resid + LN-backward(du).  Each block of rows also writes its partial sums of dgamma (du * xhat) and
+// out = resid + LN-backward(du) (resid may be null: no residual).  Each block of rows also writes its partial sums of dgamma (du * xhat) and
 // dbeta (du) to part_g / part_b ([ln_bwd_blocks(rows)][H] fp32 each); launch_reduce_partials folds any number
 // of such partial rows into a flat-gradient slice:  g = (accumulate ? g : 0) + scale * sum over chunks.
 template <typename T>

@@ -172,23 +172,36 @@ GemmArgs<T> linear_wgrad(const T* dY, const T* X, int Tn, int N, int K, float* G
 // its MFMA fragments then come from 16-byte LDS reads, which run at about three times the rate of the
 // transposing reads the other operand needs, for one extra pass over the small matrix.
 template <typename T>
-int wgrad(const T* dY, const T* X, int Tn, int N, int K, float* G, float scale, int acc, T* tbuf, hipStream_t s);
+int wgrad(const T* dY, const T* X, int Tn, int N, int K, float* G, float scale, int acc, T* tbuf, hipStream_t s, int ldy = 0);
 template <>
-int wgrad<float>(const float* dY, const float* X, int Tn, int N, int K, float* G, float scale, int acc, float*, hipStream_t s) {
-  return gemm<float>(linear_wgrad<float>(dY, X, Tn, N, K, G, scale, acc), s);
+int wgrad<float>(const float* dY, const float* X, int Tn, int N, int K, float* G, float scale, int acc, float*, hipStream_t s, int ldy) {
+  GemmArgs<float> a = linear_wgrad<float>(dY, X, Tn, N, K, G, scale, acc);
+  if (ldy) a.a_cs = ldy;
+  return gemm<float>(a, s);
 }
 template <>
-int wgrad<bf16>(const bf16* dY, const bf16* X, int Tn, int N, int K, float* G, float scale, int acc, bf16* tbuf, hipStream_t s) {
-  GemmArgs<bf16> a = linear_wgrad<bf16>(dY, X, Tn, N, K, G, scale, acc);
-  if (Tn % 8 != 0) return gemm<bf16>(a, s);
-  if (N <= K) {   // dY^T [N, T] as the k-contiguous A operand
-    TRY(launch_transpose_bf16(dY, tbuf, Tn, N, s));
-    a.A = tbuf; a.a_rs = Tn; a.a_cs = 1;
-  } else {        // X^T [K, T] as the k-contiguous B operand
-    TRY(launch_transpose_bf16(X, tbuf, Tn, K, s));
-    a.B = tbuf; a.b_rs = Tn; a.b_cs = 1;
+int wgrad<bf16>(const bf16* dY, const bf16* X, int Tn, int N, int K, float* G, float scale, int acc, bf16* tbuf, hipStream_t s, int ldy) {
+  if (!ldy) ldy = N;
+  // the GEMM addresses its operands through 32-bit buffer descriptors: contract over the tokens in pieces below 2 GiB
+  const int64_t widest = ldy > K ? ldy : K;
+  int64_t piece = ((int64_t)0x7ff00000 / (2 * widest)) / 64 * 64;
+  if (piece <= 0) return fail(CEPHALO_EUNSUPPORTED, "wgrad: a row of %lld elements is too wide", (long long)widest);
+  for (int64_t t0 = 0; t0 < Tn; t0 += piece) {
+    const int tc = (int)(Tn - t0 < piece ? Tn - t0 : piece);
+    GemmArgs<bf16> a = linear_wgrad<bf16>(dY + t0 * ldy, X + t0 * K, tc, N, K, G, scale, t0 > 0 ? 1 : acc);
+    a.a_cs = ldy;
+    if (tc % 8 == 0) {
+      if (N <= K && ldy == N) {   // dY^T [N, T] as the k-contiguous A operand
+        TRY(launch_transpose_bf16(a.A, tbuf, tc, N, s));
+        a.A = tbuf; a.a_rs = tc; a.a_cs = 1;
+      } else {                    // X^T [K, T] as the k-contiguous B operand
+        TRY(launch_transpose_bf16(a.B, tbuf, tc, K, s));
+        a.B = tbuf; a.b_rs = tc; a.b_cs = 1;
+      }
+    }
+    TRY(gemm<bf16>(a, s));
   }
-  return gemm<bf16>(a, s);
+  return CEPHALO_OK;
 }
 
 template <typename T> struct Saved {

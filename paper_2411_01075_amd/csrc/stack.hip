@@ -1,0 +1,321 @@
+// A whole GPT-style stack on one GPU's batch share, in the layered order (every micro-batch passes
+// through a layer before the next layer runs, forward and backward): token + position embedding,
+// L layers, final LayerNorm, tied LM head with mean cross-entropy, and the matching backward with the
+// parameter-gradient pass of every layer taken once over all b*S tokens.
+#include <cstring>
+#include "layer_impl.h"
+#include <rocprim/device/device_radix_sort.hpp>
+
+namespace cephalo {
+namespace {
+
+constexpr int kThreads = 256;
+
+__device__ __forceinline__ int clamp_id(int id, int V) { return id < 0 ? 0 : (id >= V ? V - 1 : id); }
+
+// x0[t] = wte[id[t]] + wpe[t % S]; one wavefront per token.  Ids outside [0, V) are clamped.
+template <typename T>
+__global__ void __launch_bounds__(kThreads)
+embed_fwd_kernel(const int* __restrict__ ids, const T* __restrict__ wte, const T* __restrict__ wpe, T* __restrict__ x0,
+                 int tokens, int S, int H, int V) {
+  constexpr int VN = Vec<T>::N;
+  const int t = blockIdx.x * 4 + (threadIdx.x >> 6), lane = threadIdx.x & 63;
+  if (t >= tokens) return;
+  const T* e = wte + (int64_t)clamp_id(ids[t], V) * H;
+  const T* p = wpe + (int64_t)(t % S) * H;
+  for (int v = lane; v < H / VN; v += 64) {
+    float a[VN], b[VN];
+    load_vec<T>(e + v * VN, a);
+    load_vec<T>(p + v * VN, b);
+#pragma unroll
+    for (int i = 0; i < VN; ++i) a[i] += b[i];
+    store_vec<T>(x0 + (int64_t)t * H + v * VN, a);
+  }
+}
+
+__device__ __forceinline__ float block_reduce(float v, bool is_max, float* red) {
+  v = is_max ? wave_max(v) : wave_sum(v);
+  const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
+  __syncthreads();
+  if (lane == 0) red[wave] = v;
+  __syncthreads();
+  const float a = red[0], b = red[1], c = red[2], d = red[3];
+  return is_max ? fmaxf(fmaxf(a, b), fmaxf(c, d)) : (a + b) + (c + d);
+}
+
+// One block per token row of logits [rows, ld] (V valid columns).  loss[row] = logsumexp - logit[target];
+// the row is overwritten by coef * (softmax - onehot(target)); columns V..ld-1 are set to zero.
+template <typename T>
+__global__ void __launch_bounds__(kThreads)
+cross_entropy_kernel(T* __restrict__ logits, const int* __restrict__ targets, float* __restrict__ loss,
+                     int V, int ld, float coef) {
+  constexpr int VN = Vec<T>::N;
+  __shared__ float red[4];
+  T* row = logits + (int64_t)blockIdx.x * ld;
+  const int nv = ld / VN;
+  float mx = -INFINITY;
+  for (int v = threadIdx.x; v < nv; v += kThreads) {
+    float a[VN];
+    load_vec<T>(row + v * VN, a);
+#pragma unroll
+    for (int i = 0; i < VN; ++i) if (v * VN + i < V) mx = fmaxf(mx, a[i]);
+  }
+  mx = block_reduce(mx, true, red);
+  float sum = 0.f;
+  for (int v = threadIdx.x; v < nv; v += kThreads) {
+    float a[VN];
+    load_vec<T>(row + v * VN, a);
+#pragma unroll
+    for (int i = 0; i < VN; ++i) if (v * VN + i < V) sum += __expf(a[i] - mx);
+  }
+  sum = block_reduce(sum, false, red);
+  const float lse = mx + __logf(sum);
+  const int tgt = clamp_id(targets[blockIdx.x], V);
+  if (threadIdx.x == 0) loss[blockIdx.x] = lse - (float)row[tgt];
+  __syncthreads();     // the target logit has been read before the row is overwritten
+  for (int v = threadIdx.x; v < nv; v += kThreads) {
+    float a[VN];
+    load_vec<T>(row + v * VN, a);
+#pragma unroll
+    for (int i = 0; i < VN; ++i) {
+      const int c = v * VN + i;
+      a[i] = c < V ? coef * (__expf(a[i] - lse) - (c == tgt ? 1.f : 0.f)) : 0.f;
+    }
+    store_vec<T>(row + v * VN, a);
+  }
+}
+
+// out[0] = (1/n) * sum loss[0..n), one block, fixed order
+__global__ void __launch_bounds__(kThreads) mean_kernel(const float* __restrict__ loss, int n, float* __restrict__ out) {
+  __shared__ float red[4];
+  float s = 0.f;
+  for (int i = threadIdx.x; i < n; i += kThreads) s += loss[i];
+  s = block_reduce(s, false, red);
+  if (threadIdx.x == 0) out[0] = s / (float)n;
+}
+
+__global__ void __launch_bounds__(kThreads) sort_keys_kernel(const int* __restrict__ ids, int* __restrict__ keys, int* __restrict__ vals, int n, int V) {
+  const int i = blockIdx.x * kThreads + threadIdx.x;
+  if (i < n) { keys[i] = clamp_id(ids[i], V); vals[i] = i; }
+}
+
+// Token-embedding gradient: tokens sorted by id (stable, so ascending token index inside a run); the wavefront at
+// the head of each run of equal ids sums the run's rows of dx0 in that order and adds the sum to the id's row of
+// the gradient (which already holds the LM-head part).  One writer per row, fixed order: reproducible.
+template <typename T>
+__global__ void __launch_bounds__(kThreads)
+embed_bwd_kernel(const int* __restrict__ keys, const int* __restrict__ vals, const T* __restrict__ dx0, float* __restrict__ g_wte,
+                 int n, int H) {
+  constexpr int VN = Vec<T>::N;
+  const int i = blockIdx.x * 4 + (threadIdx.x >> 6), lane = threadIdx.x & 63;
+  if (i >= n) return;
+  const int key = keys[i];
+  if (i > 0 && keys[i - 1] == key) return;
+  for (int v = lane; v < H / VN; v += 64) {
+    float acc[VN];
+#pragma unroll
+    for (int c = 0; c < VN; ++c) acc[c] = 0.f;
+    for (int j = i; j < n && keys[j] == key; ++j) {
+      float a[VN];
+      load_vec<T>(dx0 + (int64_t)vals[j] * H + v * VN, a);
+#pragma unroll
+      for (int c = 0; c < VN; ++c) acc[c] += a[c];
+    }
+    float* g = g_wte + (int64_t)key * H + v * VN;
+#pragma unroll
+    for (int c = 0; c < VN; ++c) g[c] += acc[c];
+  }
+}
+
+// Position-embedding gradient: g_wpe[s] = sum over the b samples of dx0[n, s], samples in order.
+template <typename T>
+__global__ void __launch_bounds__(kThreads)
+wpe_bwd_kernel(const T* __restrict__ dx0, float* __restrict__ g_wpe, int b, int S, int H) {
+  constexpr int VN = Vec<T>::N;
+  const int64_t v = (int64_t)blockIdx.x * kThreads + threadIdx.x;    // vector index inside [S, H]
+  if (v * VN >= (int64_t)S * H) return;
+  float acc[VN];
+#pragma unroll
+  for (int c = 0; c < VN; ++c) acc[c] = 0.f;
+  for (int n = 0; n < b; ++n) {
+    float a[VN];
+    load_vec<T>(dx0 + (int64_t)n * S * H + v * VN, a);
+#pragma unroll
+    for (int c = 0; c < VN; ++c) acc[c] += a[c];
+  }
+#pragma unroll
+  for (int c = 0; c < VN; ++c) g_wpe[v * VN + c] = acc[c];
+}
+
+int check_stack(const cephalo_stack_desc* d) {
+  if (!d) return fail(CEPHALO_EINVAL, "stack desc is null");
+  TRY(check_desc(&d->layer));
+  if (d->layers <= 0 || d->vocab <= 0) return fail(CEPHALO_EINVAL, "stack desc: layers %d and vocab %d must be positive", d->layers, d->vocab);
+  return CEPHALO_OK;
+}
+
+size_t sort_temp_bytes(int n) {
+  size_t bytes = 0;
+  const hipError_t e = rocprim::radix_sort_pairs(nullptr, bytes, (int*)nullptr, (int*)nullptr, (int*)nullptr, (int*)nullptr,
+                                                 (size_t)n, 0, 32, (hipStream_t)0);
+  const size_t floor_bytes = (size_t)n * 16 + ((size_t)1 << 20);   // also covers a size query that fails without a device
+  if (e != hipSuccess) (void)hipGetLastError();
+  return (e == hipSuccess && bytes > floor_bytes) ? bytes : floor_bytes;
+}
+
+struct StackLayout {
+  size_t xs, saves, save_each, scratch, dxa, dxb, uf, meanf, rstdf, duf, logits, loss, lnf_part, keys, sort_tmp, sort_tmp_bytes, total;
+  int ldv;            // padded pitch of the logits
+  size_t lnf_rows;
+};
+
+StackLayout stack_layout(const cephalo_stack_desc& d, int b, int m) {
+  const cephalo_layer_desc& ld = d.layer;
+  const size_t es = ld.dtype == CEPHALO_F32 ? 4 : 2;
+  const size_t n = (size_t)b * ld.seq, Tm = (size_t)m * ld.seq, H = ld.hidden;
+  StackLayout L;
+  L.ldv = (d.vocab + 7) / 8 * 8;
+  size_t p = 0;
+  auto take = [&](size_t bytes) { size_t at = p; p += align_up(bytes); return at; };
+  L.xs = take((size_t)(d.layers + 1) * n * H * es);
+  L.save_each = align_up(save_layout(ld, b).total);
+  L.saves = take((size_t)d.layers * L.save_each);
+  L.scratch = take(scratch_layout(ld, m, b).total);
+  L.dxa = take(n * H * es); L.dxb = take(n * H * es);
+  L.uf = take(n * H * es); L.meanf = take(n * 4); L.rstdf = take(n * 4);
+  L.duf = take(Tm * H * es);
+  L.logits = take(n * (size_t)L.ldv * es);
+  L.loss = take(n * 4);
+  L.lnf_rows = (size_t)(b / m) * ln_bwd_blocks((int)Tm);
+  L.lnf_part = take(2 * L.lnf_rows * H * 4);
+  L.keys = take(4 * n * 4);
+  L.sort_tmp_bytes = sort_temp_bytes((int)n);
+  L.sort_tmp = take(L.sort_tmp_bytes);
+  L.total = p;
+  return L;
+}
+
+template <typename T>
+int run_stack(const cephalo_stack_desc& d, const void* Pv, const int* ids, const int* targets, int b, int m,
+              float* G, float scale, float* loss_out, void* ws, hipStream_t s) {
+  const cephalo_layer_desc& ld = d.layer;
+  const T* P = static_cast<const T*>(Pv);
+  const int S = ld.seq, H = ld.hidden, V = d.vocab, NL = d.layers, l = b / m;
+  const int n = b * S, Tm = m * S;
+  const int64_t PL = param_offsets(ld).total;
+  const int64_t o_wte = 0, o_wpe = (int64_t)V * H, o_layers = o_wpe + (int64_t)S * H, o_lnf = o_layers + NL * PL;
+  const StackLayout L = stack_layout(d, b, m);
+  const SaveLayout SL = save_layout(ld, b);
+  const ScratchLayout WL = scratch_layout(ld, m, b);
+  auto xs = [&](int layer) { return at<T>(ws, L.xs) + (size_t)layer * n * H; };
+  void* scratch = at<char>(ws, L.scratch);
+  const size_t act = (size_t)Tm * H;
+
+  // ---- forward
+  embed_fwd_kernel<T><<<(n + 3) / 4, kThreads, 0, s>>>(ids, P + o_wte, P + o_wpe, xs(0), n, S, H, V);
+  CEPHALO_CHECK_LAUNCH("embed_fwd");
+  for (int li = 0; li < NL; ++li) {
+    void* save = at<char>(ws, L.saves + (size_t)li * L.save_each);
+    for (int j = 0; j < l; ++j)
+      TRY(layer_fwd_t<T>(ld, P + o_layers + li * PL, xs(li) + j * act, xs(li + 1) + j * act, m, saved_at<T>(save, SL, ld, j * m), s));
+  }
+  // ---- head: final LN, tied logits, cross-entropy (logits become their own gradient), back to the last layer's output
+  T* uf = at<T>(ws, L.uf); T* logits = at<T>(ws, L.logits); T* duf = at<T>(ws, L.duf);
+  float* meanf = at<float>(ws, L.meanf); float* rstdf = at<float>(ws, L.rstdf);
+  float* lnf_g = at<float>(ws, L.lnf_part); float* lnf_b = lnf_g + L.lnf_rows * H;
+  T* dx_cur = at<T>(ws, L.dxa); T* dx_nxt = at<T>(ws, L.dxb);
+  const float coef = scale / (float)n;
+  const int nb = ln_bwd_blocks(Tm);
+  for (int j = 0; j < l; ++j) {
+    const size_t t0 = (size_t)j * Tm;
+    TRY(launch_ln_fwd<T>(xs(NL) + t0 * H, P + o_lnf, P + o_lnf + H, uf + t0 * H, meanf + t0, rstdf + t0, Tm, H, ld.ln_eps, s));
+    T* lg = logits + t0 * L.ldv;
+    {
+      GemmArgs<T> a = linear_fwd<T>(uf + t0 * H, P + o_wte, Tm, V, H);
+      a.epi = EPI_NONE; a.C = lg; a.ldc = L.ldv;
+      TRY(gemm<T>(a, s));
+    }
+    cross_entropy_kernel<T><<<Tm, kThreads, 0, s>>>(lg, targets + t0, at<float>(ws, L.loss) + t0, V, L.ldv, coef);
+    CEPHALO_CHECK_LAUNCH("cross_entropy");
+    {
+      GemmArgs<T> a = linear_dgrad<T>(lg, P + o_wte, Tm, V, H);   // duf = dlogits wte
+      a.a_rs = L.ldv; a.epi = EPI_NONE; a.C = duf;
+      TRY(gemm<T>(a, s));
+    }
+    TRY(launch_ln_bwd<T>(duf, xs(NL) + t0 * H, meanf + t0, rstdf + t0, P + o_lnf, (const T*)nullptr, dx_cur + t0 * H,
+                         lnf_g + (size_t)j * nb * H, lnf_b + (size_t)j * nb * H, Tm, H, s));
+  }
+  mean_kernel<<<1, kThreads, 0, s>>>(at<float>(ws, L.loss), n, loss_out);
+  CEPHALO_CHECK_LAUNCH("mean_loss");
+  {
+    Work<T> w = work_at<T>(scratch, WL, ld, 0, 0, m);
+    TRY(wgrad<T>(logits, uf, n, V, H, G + o_wte, 1.0f, 0, w.tbuf, s, L.ldv));        // LM-head part of d wte, whole share
+    TRY(launch_reduce_partials(lnf_g, l * nb, H, G + o_lnf, 1.0f, 0, s));
+    TRY(launch_reduce_partials(lnf_b, l * nb, H, G + o_lnf + H, 1.0f, 0, s));
+  }
+  // ---- backward through the layers
+  for (int li = NL - 1; li >= 0; --li) {
+    void* save = at<char>(ws, L.saves + (size_t)li * L.save_each);
+    const T* Pl = P + o_layers + li * PL;
+    for (int j = 0; j < l; ++j)
+      TRY(layer_bwd_data_t<T>(ld, Pl, xs(li) + j * act, dx_cur + j * act, dx_nxt + j * act, m, saved_at<T>(save, SL, ld, j * m),
+                              work_at<T>(scratch, WL, ld, j * m, j, m), s));
+    TRY(layer_bwd_params_t<T>(ld, dx_cur, n, l * nb, saved_at<T>(save, SL, ld, 0), work_at<T>(scratch, WL, ld, 0, 0, m),
+                              G + o_layers + li * PL, 1.0f, 0, s));
+    T* t = dx_cur; dx_cur = dx_nxt; dx_nxt = t;
+  }
+  // ---- embeddings
+  wpe_bwd_kernel<T><<<(int)(((int64_t)S * H / Vec<T>::N + kThreads - 1) / kThreads), kThreads, 0, s>>>(dx_cur, G + o_wpe, b, S, H);
+  CEPHALO_CHECK_LAUNCH("wpe_bwd");
+  int* keys_in = at<int>(ws, L.keys); int* vals_in = keys_in + n; int* keys_out = vals_in + n; int* vals_out = keys_out + n;
+  sort_keys_kernel<<<(n + kThreads - 1) / kThreads, kThreads, 0, s>>>(ids, keys_in, vals_in, n, V);
+  size_t tmp = L.sort_tmp_bytes;
+  if (rocprim::radix_sort_pairs(at<char>(ws, L.sort_tmp), tmp, keys_in, keys_out, vals_in, vals_out, (size_t)n, 0, 32, s) != hipSuccess)
+    return fail(CEPHALO_EHIP, "stack_step: sort of the token ids failed");
+  embed_bwd_kernel<T><<<(n + 3) / 4, kThreads, 0, s>>>(keys_out, vals_out, dx_cur, G + o_wte, n, H);
+  CEPHALO_CHECK_LAUNCH("embed_bwd");
+  return CEPHALO_OK;
+}
+
+}  // namespace
+}  // namespace cephalo
+
+using namespace cephalo;
+
+extern "C" int64_t cephalo_stack_param_count(const cephalo_stack_desc* d) {
+  const int rc = check_stack(d);
+  if (rc != CEPHALO_OK) return rc;
+  const int64_t H = d->layer.hidden;
+  return (int64_t)d->vocab * H + (int64_t)d->layer.seq * H + d->layers * param_offsets(d->layer).total + 2 * H;
+}
+
+extern "C" int cephalo_stack_workspace_bytes(const cephalo_stack_desc* d, int32_t batch_share, int32_t micro_batch, size_t* bytes) {
+  TRY(check_stack(d));
+  if (micro_batch <= 0 || batch_share <= 0 || batch_share % micro_batch != 0)
+    return fail(CEPHALO_EINVAL, "stack_workspace_bytes: batch share b = %d is not a positive multiple of micro-batch size m = %d",
+                batch_share, micro_batch);
+  if (!bytes) return fail(CEPHALO_EINVAL, "stack_workspace_bytes: null output");
+  *bytes = stack_layout(*d, batch_share, micro_batch).total;
+  return CEPHALO_OK;
+}
+
+extern "C" int cephalo_stack_step(const cephalo_stack_desc* d, const void* flat_param, const int32_t* ids, const int32_t* targets,
+                                  int32_t batch_share, int32_t micro_batch, float* flat_grad, float grad_scale, float* loss,
+                                  void* workspace, size_t workspace_bytes, void* stream) {
+  TRY(check_stack(d));
+  if (micro_batch <= 0 || batch_share <= 0 || batch_share % micro_batch != 0)
+    return fail(CEPHALO_EINVAL, "stack_step: batch share b = %d is not a positive multiple of micro-batch size m = %d",
+                batch_share, micro_batch);
+  if ((int64_t)batch_share * d->layer.seq > (1 << 24)) return fail(CEPHALO_EUNSUPPORTED, "stack_step: b*S is too many tokens");
+  for (const void* p : {flat_param, (const void*)ids, (const void*)targets, (const void*)flat_grad, (const void*)loss, (const void*)workspace}) {
+    if (!p) return fail(CEPHALO_EINVAL, "stack_step: null pointer argument");
+  }
+  if (!aligned16(flat_param) || !aligned16(flat_grad) || !aligned16(workspace))
+    return fail(CEPHALO_EINVAL, "stack_step: flat_param, flat_grad and workspace must be 16-byte aligned");
+  const size_t need = stack_layout(*d, batch_share, micro_batch).total;
+  if (workspace_bytes < need) return fail(CEPHALO_EWORKSPACE, "stack_step: workspace %zu B < %zu B", workspace_bytes, need);
+  hipStream_t s = static_cast<hipStream_t>(stream);
+  if (d->layer.dtype == CEPHALO_F32)
+    return run_stack<float>(*d, flat_param, ids, targets, batch_share, micro_batch, flat_grad, grad_scale, loss, workspace, s);
+  return run_stack<bf16>(*d, flat_param, ids, targets, batch_share, micro_batch, flat_grad, grad_scale, loss, workspace, s);
+}
