@@ -2,15 +2,19 @@
 """Benchmark of one GPU's share of a sharded data-parallel training step on one MI355X.
 
 A "step" is one pass of the whole hot path over one batch share: forward of every micro-batch,
-backward of every micro-batch with fp32 gradient accumulation, then Adam on this GPU's uneven
-slice of the flat training state (with the bf16 parameter copy refreshed for the slice).
-Inputs are seeded synthetic tensors already resident in HBM when the timed region starts.
+backward of every micro-batch with fp32 gradient accumulation (layered order: all micro-batches
+through a layer before the next layer), then Adam on this GPU's uneven slice of the flat training
+state (with the bf16 parameter copy refreshed for the slice).  Inputs are seeded synthetic tensors
+already resident in HBM when the timed region starts.
 
-    python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload c4]
+    python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload c5]
 
+The default workload is c5, the largest one: the full 24-layer stack with embeddings, tied LM head
+and mean cross-entropy.  c2..c4 are single-layer workloads (upstream gradient supplied).
 Prints ONE JSON line (metric, value, roofline of the dominant kernel, CPU-oracle baseline).
 """
 import argparse
+import dataclasses
 import json
 import os
 import sys
@@ -25,7 +29,7 @@ PEAK_BF16_TFLOPS = 2500.0     # MI355X dense bf16 MFMA, published
 PEAK_HBM_GBS = 8000.0         # MI355X HBM3E, published
 
 
-def model_flops_per_microbatch(cfg):
+def layer_flops_per_microbatch(cfg):
     """fwd+bwd model FLOPs of one layer on one micro-batch: GEMMs 6 * T * (4H^2 + 2HF)
     (2 per multiply-add, x3 for fwd + dgrad + wgrad) and attention 12 m S^2 H non-causal,
     half of it under a causal mask.  Recompute and masked-out work are not counted."""
@@ -35,13 +39,22 @@ def model_flops_per_microbatch(cfg):
     return gemm, attn
 
 
+def step_model_flops(cfg):
+    gemm, attn = layer_flops_per_microbatch(cfg)
+    per_micro = cfg.layers * (gemm + attn)
+    if cfg.vocab:
+        per_micro += 6.0 * cfg.tokens_per_micro * cfg.hidden * cfg.vocab      # tied LM head: logits, dgrad, wgrad
+    return cfg.n_micro * per_micro
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
-    ap.add_argument("--steps", type=int, default=10)
-    ap.add_argument("--warmup", type=int, default=3)
-    ap.add_argument("--workload", default="c4", choices=["c1", "c2", "c3", "c4"])
+    ap.add_argument("--steps", type=int, default=8)
+    ap.add_argument("--warmup", type=int, default=2)
+    ap.add_argument("--workload", default="c5", choices=["c1", "c2", "c3", "c4", "c5"])
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--no-legs", action="store_true", help="skip the per-kernel legs (whole step only)")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build covers one GPU's share of the step; it has no collectives and runs on exactly "
@@ -50,49 +63,66 @@ def main():
 
     import torch
     import paper_2411_01075_amd as C
-    from workloads import CONFIGS, shard_of, draw_layer_params, draw_activations, draw_adam_state
+    from workloads import CONFIGS, shard_of, draw_layer_params, draw_stack_params, draw_activations, draw_token_ids, draw_adam_state
 
     if not torch.cuda.is_available():
         print("bench.py: no GPU visible", file=sys.stderr)
         sys.exit(2)
     C.binding.lib()     # fail loudly if the HIP library is missing
     cfg = CONFIGS[args.workload]
-    desc = C.desc_from_config(cfg)
+    stack = cfg.layers > 1
     bf16 = cfg.dtype == "bf16"
-    dt = torch.bfloat16 if bf16 else torch.float32
-    P = C.cephalo_layer_param_count(desc)
-    off, ln = shard_of(cfg, P)
     b, m, l = cfg.batch_share, cfg.micro_batch, cfg.n_micro
+    lr = float(np.float32(cfg.lr))
 
     # ---- seeded inputs, generated on the host, then made resident in HBM
-    tensors = draw_layer_params(cfg)
-    x_h, dy_h = draw_activations(cfg)
-    flat32_h = C.flatten_layer_params(desc, tensors)
+    if stack:
+        sd = C.stack_desc_from_config(cfg)
+        desc = sd.layer
+        P = C.cephalo_stack_param_count(sd)
+        params = draw_stack_params(cfg)
+        flat32_h = C.flatten_stack_params(sd, params)
+        ids_h, tgt_h = draw_token_ids(cfg)
+    else:
+        desc = C.desc_from_config(cfg)
+        P = C.cephalo_layer_param_count(desc)
+        params = draw_layer_params(cfg)
+        flat32_h = C.flatten_layer_params(desc, params)
+        x_h, dy_h = draw_activations(cfg)
+    off, ln = shard_of(cfg, P)
     _, m_h, v_h = draw_adam_state(cfg, ln)            # moments of the slice only (a mid-training state)
     p32 = torch.from_numpy(flat32_h).cuda()
-    p32_init = p32.clone()
     if bf16:
         plow = torch.empty(P, dtype=torch.bfloat16, device="cuda")
         C.cephalo_cast_bf16(plow, p32)
         pcomp = plow
     else:
         plow, pcomp = None, p32
-    x = torch.from_numpy(x_h).cuda().to(dt).contiguous()
-    dy = torch.from_numpy(dy_h).cuda().to(dt).contiguous()
-    y, dx = torch.empty_like(x), torch.empty_like(x)
     G = torch.zeros(P, dtype=torch.float32, device="cuda")
     mom = torch.zeros(P, dtype=torch.float32, device="cuda")
     var = torch.zeros(P, dtype=torch.float32, device="cuda")
     mom[off:off + ln] = torch.from_numpy(m_h).cuda()
     var[off:off + ln] = torch.from_numpy(v_h).cuda()
-    save_b, scr_b = C.cephalo_share_workspace_bytes(desc, b, m)
-    save = torch.empty(save_b, dtype=torch.uint8, device="cuda")
-    scratch = torch.empty(scr_b, dtype=torch.uint8, device="cuda")
-    lr = float(np.float32(cfg.lr))
+    if stack:
+        ids = torch.from_numpy(ids_h).cuda()
+        tgt = torch.from_numpy(tgt_h).cuda()
+        loss = torch.zeros(1, dtype=torch.float32, device="cuda")
+        ws = torch.empty(C.cephalo_stack_workspace_bytes(sd, b, m), dtype=torch.uint8, device="cuda")
 
-    def step(t):
-        C.cephalo_share_layer_step(desc, pcomp, x, y, dy, dx, b, m, save, G, 1.0, scratch)
-        C.cephalo_shard_adam(p32, G, mom, var, plow, P, off, ln, lr, 0.9, 0.999, 1e-8, t)
+        def step(t):
+            C.cephalo_stack_step(sd, pcomp, ids, tgt, b, m, G, 1.0, loss, ws)
+            C.cephalo_shard_adam(p32, G, mom, var, plow, P, off, ln, lr, 0.9, 0.999, 1e-8, t)
+    else:
+        x = torch.from_numpy(x_h).cuda().float().contiguous()       # the residual stream is fp32
+        dy = torch.from_numpy(dy_h).cuda().float().contiguous()
+        y, dx = torch.empty_like(x), torch.empty_like(x)
+        save_b, scr_b = C.cephalo_share_workspace_bytes(desc, b, m)
+        save = torch.empty(save_b, dtype=torch.uint8, device="cuda")
+        scratch = torch.empty(scr_b, dtype=torch.uint8, device="cuda")
+
+        def step(t):
+            C.cephalo_share_layer_step(desc, pcomp, x, y, dy, dx, b, m, save, G, 1.0, scratch)
+            C.cephalo_shard_adam(p32, G, mom, var, plow, P, off, ln, lr, 0.9, 0.999, 1e-8, t)
 
     for i in range(args.warmup):
         step(7 + i)
@@ -104,8 +134,13 @@ def main():
     elapsed = time.perf_counter() - t0
     ms_per_step = 1e3 * elapsed / args.steps
     tokens_per_s = cfg.tokens_per_step * args.steps / elapsed
-    gemm_fl, attn_fl = model_flops_per_microbatch(cfg)
-    step_flops = l * (gemm_fl + attn_fl)
+    step_flops = step_model_flops(cfg)
+    extras = {}
+    if stack:
+        extras["loss"] = round(float(loss.item()), 4)
+    if bf16:
+        extras["whole_step_model_tflops"] = round(step_flops / (elapsed / args.steps) / 1e12, 1)
+        extras["whole_step_frac_of_bf16_peak"] = round(step_flops / (elapsed / args.steps) / 1e12 / PEAK_BF16_TFLOPS, 4)
 
     # ---- per-kernel legs, HIP events on the launch stream (torch's current stream is the one passed to the library)
     def timed(fn, iters):
@@ -119,36 +154,71 @@ def main():
         torch.cuda.synchronize()
         return e0.elapsed_time(e1) * 1e-3 / iters
 
-    extras = {}
-    T, H, F = cfg.tokens_per_micro, cfg.hidden, cfg.mlp
-    if bf16:
-        # dominant kernel: the weight-gradient GEMM (one kernel instantiation, four launches per micro-batch
-        # of the shapes dW_qkv, dW_o, dW_fc1, dW_fc2), exactly as the layer's backward issues it
-        shapes = [(3 * H, H), (H, H), (F, H), (H, F)]          # (N_out, K_in) of each linear
-        acts = {}
-        for n_out, k_in in shapes:
-            acts[(n_out, k_in)] = (torch.randn(T, n_out, device="cuda").to(dt), torch.randn(T, k_in, device="cuda").to(dt),
-                                   torch.zeros(n_out, k_in, device="cuda"))
+    roofline = {"kernel": "none (launch-latency bound workload)", "bound": "alu", "achieved": None, "peak": 157.3,
+                "unit": "TFLOP/s", "frac": None, "traffic": None}
+    T, H, F, V = cfg.tokens_per_micro, cfg.hidden, cfg.mlp, cfg.vocab
+    n_tok = cfg.tokens_per_step
+    if bf16 and not args.no_legs:
+        if stack:
+            del ws                      # the legs allocate their own operands
+            torch.cuda.empty_cache()
+        bt = torch.bfloat16
+        # The GEMM instantiations of the step, each launched with the shapes and operand layouts the step uses.
+        # (kind, N_out, K_in, launches per step).  Forward and dgrad run per micro-batch on T tokens; the weight
+        # gradient runs once per linear over all b*S tokens with one operand copied token-minor beforehand.
+        L = cfg.layers
+        lin = [("qkv", 3 * H, H), ("o", H, H), ("fc1", F, H), ("fc2", H, F)]
+        legs = {}
 
-        def wgrads():
-            for (n_out, k_in), (dY_, X_, G_) in acts.items():
-                C.cephalo_op_gemm(C.BF16, dY_, 1, n_out, X_, 1, k_in, n_out, k_in, T, C.EPI_GRAD, G=G_, scale=1.0, accumulate=1)
+        def add_leg(key, fn, flops, count):
+            sec = timed(fn, 3)
+            g = legs.setdefault(key, {"sec": 0.0, "flops": 0.0, "launches": 0})
+            g["sec"] += sec * count
+            g["flops"] += flops * count
+            g["launches"] += count
 
-        sec = timed(wgrads, max(3, args.steps))
-        flops_per_launch = sum(2.0 * T * n * k for n, k in shapes) / len(shapes)
-        avg_launch = sec / len(shapes)
-        achieved = flops_per_launch / avg_launch / 1e12
-        roofline = {"kernel": "gemm_mfma_kernel<..., EPI_GRAD> (weight gradient, 4 launches per micro-batch)",
-                    "bound": "mfma", "achieved": round(achieved, 1), "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s",
-                    "frac": round(achieved / PEAK_BF16_TFLOPS, 4), "traffic": None,
-                    "avg_launch_us": round(avg_launch * 1e6, 1), "flops_per_launch": flops_per_launch}
-        extras["whole_step_model_tflops"] = round(step_flops / (elapsed / args.steps) / 1e12, 1)
-        extras["whole_step_frac_of_bf16_peak"] = round(step_flops / (elapsed / args.steps) / 1e12 / PEAK_BF16_TFLOPS, 4)
-    else:
-        roofline = {"kernel": "none (launch-latency bound workload)", "bound": "alu", "achieved": None, "peak": 157.3,
-                    "unit": "TFLOP/s", "frac": None, "traffic": None}
+        for name, n_out, k_in in lin:
+            X = torch.randn(T, k_in, device="cuda").to(bt)
+            W = (torch.randn(n_out, k_in, device="cuda") * 0.02).to(bt)
+            dY = torch.randn(T, n_out, device="cuda").to(bt)
+            Yb = torch.empty(T, n_out, device="cuda", dtype=bt)
+            Yf = torch.empty(T, n_out, device="cuda")
+            Xf = torch.empty(T, k_in, device="cuda")
+            Xb = torch.empty(T, k_in, device="cuda", dtype=bt)
+            bias = torch.zeros(n_out, device="cuda", dtype=bt)
+            fl = 2.0 * T * n_out * k_in
+            add_leg("gemm forward (A, B k-contiguous)", lambda: C.cephalo_op_gemm(C.BF16, X, k_in, 1, W, k_in, 1, T, n_out, k_in, C.EPI_BIAS, C=Yb, bias=bias), fl, L * l)
+            add_leg("gemm dgrad (B row-contiguous)", lambda: C.cephalo_op_gemm(C.BF16, dY, n_out, 1, W, 1, k_in, T, k_in, n_out, C.EPI_NONE, C=Xb), fl, L * l)
+            del Yb, Yf, Xf, Xb
+            # weight gradient over the whole share
+            Xs = torch.randn(n_tok, k_in, device="cuda").to(bt)
+            dYs = torch.randn(n_tok, n_out, device="cuda").to(bt)
+            Gw = torch.zeros(n_out, k_in, device="cuda")
+            flw = 2.0 * n_tok * n_out * k_in
+            if n_out <= k_in:       # dY^T [N, tokens] as the k-contiguous A operand
+                dYt = dYs.t().contiguous()
+                add_leg("gemm wgrad (A k-contiguous, B row-contiguous, fp32 gradient epilogue)",
+                        lambda: C.cephalo_op_gemm(C.BF16, dYt, n_tok, 1, Xs, 1, k_in, n_out, k_in, n_tok, C.EPI_GRAD, G=Gw, scale=1.0, accumulate=0), flw, L)
+                del dYt
+            else:                   # X^T [K, tokens] as the k-contiguous B operand
+                Xt = Xs.t().contiguous()
+                add_leg("gemm wgrad (A row-contiguous, B k-contiguous, fp32 gradient epilogue)",
+                        lambda: C.cephalo_op_gemm(C.BF16, dYs, 1, n_out, Xt, n_tok, 1, n_out, k_in, n_tok, C.EPI_GRAD, G=Gw, scale=1.0, accumulate=0), flw, L)
+                del Xt
+            del Xs, dYs, Gw, X, W, dY
+        for g in legs.values():
+            g["TFLOP/s"] = round(g["flops"] / g["sec"] / 1e12, 1)
+            g["avg_launch_us"] = round(1e6 * g["sec"] / g["launches"], 1)
+            g["ms_per_step"] = round(1e3 * g.pop("sec"), 3)
+            g["flops_per_launch"] = g.pop("flops") / g["launches"]
+        key = max(legs, key=lambda k: legs[k]["ms_per_step"])
+        d = legs[key]
+        roofline = {"kernel": "gemm_mfma_kernel, " + key, "bound": "mfma", "achieved": d["TFLOP/s"], "peak": PEAK_BF16_TFLOPS,
+                    "unit": "TFLOP/s", "frac": round(d["TFLOP/s"] / PEAK_BF16_TFLOPS, 4), "traffic": None,
+                    "avg_launch_us": d["avg_launch_us"], "flops_per_launch": d["flops_per_launch"], "launches_per_step": d["launches"]}
+        extras["gemm_legs"] = legs
     # shard Adam alone: 28 algorithmic bytes per element (+2 for the bf16 copy)
-    adam_sec = timed(lambda: C.cephalo_shard_adam(p32, G, mom, var, plow, P, off, ln, lr, 0.9, 0.999, 1e-8, 9), 20)
+    adam_sec = timed(lambda: C.cephalo_shard_adam(p32, G, mom, var, plow, P, off, ln, lr, 0.9, 0.999, 1e-8, 9), 10)
     adam_bytes = ln * (28 + (2 if bf16 else 0))
     extras["shard_adam"] = {"elements": ln, "us": round(adam_sec * 1e6, 1), "GB/s": round(adam_bytes / adam_sec / 1e9, 1),
                             "frac_of_hbm_peak": round(adam_bytes / adam_sec / 1e9 / PEAK_HBM_GBS, 4)}
@@ -156,34 +226,72 @@ def main():
     # ---- CPU baseline: the oracle as it stands, on a bounded sample of the same workload
     cpu = None
     if not args.no_cpu_baseline:
-        from oracle import adam as oadam
-        from tests.harness import oracle_share_step
-        import dataclasses
-        sample_cfg = dataclasses.replace(cfg, n_micro=1)
-        xs, dys = x_h[:m], dy_h[:m]
-        n_ad = min(ln, max(1, ln // l))
-        threads = len(os.sched_getaffinity(0))
-        t0 = time.perf_counter()
-        _, _, G_ref = oracle_share_step(sample_cfg, tensors, xs, dys)
-        sl = slice(off, off + n_ad)
-        oadam.shard_adam(flat32_h[sl].astype(np.float64), G_ref[sl], m_h[:n_ad].astype(np.float64),
-                         v_h[:n_ad].astype(np.float64), 0, n_ad, lr, 0.9, 0.999, 1e-8, 7)
-        cpu_sec = time.perf_counter() - t0
-        cpu = {"value": round(cfg.tokens_per_micro / cpu_sec, 2), "unit": "tokens/s", "cores": threads, "kind": "oracle",
-               "sample": "1 of %d micro-batches (%d tokens) fwd+bwd in fp64 numpy + Adam on %d of %d slice elements, %.1f s"
-                         % (l, cfg.tokens_per_micro, n_ad, ln, cpu_sec)}
+        cpu = cpu_baseline(cfg, params, flat32_h, m_h, v_h, off, ln, lr,
+                           None if stack else (x_h, dy_h), (ids_h, tgt_h) if stack else None)
 
+    what = ("%d layers + embeddings + tied LM head (V=%d)" % (cfg.layers, V)) if stack else "1 layer"
     out = {
         "metric": "tokens/s per fwd+bwd+shard-Adam step on 1 MI355X",
         "value": round(tokens_per_s, 1), "unit": "tokens/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
         "ms_per_step": round(ms_per_step, 4), "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
         "dtype": "bf16" if bf16 else "f32", "data": "synthetic",
-        "config": {"workload": "%s: 1 layer H=%d A=%d F=%d S=%d %s, batch share %d = %d micro-batches x %d, shard [%d, %d) of P=%d"
-                               % (cfg.name, cfg.hidden, cfg.heads, cfg.mlp, cfg.seq, "causal" if cfg.causal else "non-causal",
+        "config": {"workload": "%s: %s H=%d A=%d F=%d S=%d %s, batch share %d = %d micro-batches x %d, shard [%d, %d) of P=%d"
+                               % (cfg.name, what, cfg.hidden, cfg.heads, cfg.mlp, cfg.seq, "causal" if cfg.causal else "non-causal",
                                   b, l, m, off, off + ln, P)},
         "roofline": roofline, "cpu_baseline": cpu, "extras": extras,
     }
     print(json.dumps(out))
+
+
+def cpu_baseline(cfg, params, flat32_h, m_h, v_h, off, ln, lr, acts, tokens):
+    """The numpy fp64 oracle, untouched, on a bounded sample; tokens/s scaled to the whole step."""
+    from oracle import adam as oadam
+    from oracle import layer as olayer
+    from oracle import stack as ostack
+    from oracle.precision import round_to_bf16
+    from tests.harness import oracle_share_step
+    threads = len(os.sched_getaffinity(0))
+    l, m = cfg.n_micro, cfg.micro_batch
+    if cfg.layers == 1:
+        x_h, dy_h = acts
+        sample_cfg = dataclasses.replace(cfg, n_micro=1)
+        n_ad = min(ln, max(1, ln // l))
+        t0 = time.perf_counter()
+        _, _, G_ref = oracle_share_step(sample_cfg, params, x_h[:m], dy_h[:m])
+        sl = slice(off, off + n_ad)
+        oadam.shard_adam(flat32_h[sl].astype(np.float64), G_ref[sl], m_h[:n_ad].astype(np.float64),
+                         v_h[:n_ad].astype(np.float64), 0, n_ad, lr, 0.9, 0.999, 1e-8, 7)
+        sec = time.perf_counter() - t0
+        return {"value": round(cfg.tokens_per_micro / sec, 2), "unit": "tokens/s", "cores": threads, "kind": "oracle",
+                "sample": "1 of %d micro-batches (%d tokens) fwd+bwd in fp64 numpy + Adam on %d of %d slice elements, %.1f s"
+                          % (l, cfg.tokens_per_micro, n_ad, ln, sec)}
+    # full stack: (a) one layer, forward + backward, on one micro-batch; (b) the oracle's whole step on a 1-layer,
+    # 1-micro-batch relative with the full vocabulary (embeddings, that layer, final LN, LM head, cross-entropy and
+    # back); (c) Adam on 1/64 of the slice.  Whole step ~ l * (L * a + (b - a)) + 64 * c.
+    ids_h, tgt_h = tokens
+    rb = (lambda a: round_to_bf16(a)) if cfg.dtype == "bf16" else (lambda a: a.astype(np.float64))
+    lp = {k: rb(v) for k, v in params["layers"][0].items()}
+    x = np.random.default_rng(0).standard_normal((m, cfg.seq, cfg.hidden))
+    t0 = time.perf_counter()
+    y, cache = olayer.layer_fwd(lp, x, cfg.heads, cfg.causal)
+    olayer.layer_bwd(lp, cache, x, cfg.heads)
+    t_layer = time.perf_counter() - t0
+    del y, cache
+    p1 = {"wte": rb(params["wte"]), "wpe": rb(params["wpe"]), "lnf_g": rb(params["lnf_g"]), "lnf_b": rb(params["lnf_b"]), "layers": [lp]}
+    t0 = time.perf_counter()
+    ostack.stack_step(p1, ids_h[:m], tgt_h[:m], cfg.heads, cfg.causal, m)
+    t_stack1 = time.perf_counter() - t0
+    n_ad = max(1, ln // 64)
+    sl = slice(off, off + n_ad)
+    t0 = time.perf_counter()
+    oadam.shard_adam(flat32_h[sl].astype(np.float64), flat32_h[sl].astype(np.float64), m_h[:n_ad].astype(np.float64),
+                     v_h[:n_ad].astype(np.float64), 0, n_ad, lr, 0.9, 0.999, 1e-8, 7)
+    t_adam = time.perf_counter() - t0
+    est = l * (cfg.layers * t_layer + max(0.0, t_stack1 - t_layer)) + 64 * t_adam
+    return {"value": round(cfg.tokens_per_step / est, 3), "unit": "tokens/s", "cores": threads, "kind": "oracle",
+            "sample": "extrapolated: one layer fwd+bwd on one micro-batch of %d tokens (%.1f s), the oracle's whole step on a "
+                      "1-layer 1-micro-batch relative with the full vocabulary (%.1f s), Adam on 1/64 of the slice (%.2f s); "
+                      "whole step estimated as l*(L*layer + head) + Adam = %.0f s" % (cfg.tokens_per_micro, t_layer, t_stack1, t_adam, est)}
 
 
 if __name__ == "__main__":

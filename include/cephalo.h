@@ -47,8 +47,10 @@ extern "C" {
 #define CEPHALO_EHIP         (-4)  /* a HIP launch reported an error                        */
 
 #define CEPHALO_F32   0  /* activations, parameters and arithmetic in fp32                  */
-#define CEPHALO_BF16  1  /* bf16 activations and parameter copy, fp32 accumulation, fp32
-                            statistics / softmax / GELU / gradients                         */
+#define CEPHALO_BF16  1  /* bf16 parameter copy and bf16 operands of every projection and of
+                            the attention; fp32 accumulation, statistics, softmax, GELU and
+                            parameter gradients.  The residual stream -- a layer's x and y and
+                            their gradients dy and dx -- is fp32 in both modes.               */
 
 /* A transformer layer: pre-LayerNorm residual blocks, exact (erf) GELU, biases on every
  * projection, scores scaled by 1/sqrt(d), optional causal mask, no dropout (Sec. 2.1 names
@@ -90,7 +92,7 @@ int cephalo_share_workspace_bytes(const cephalo_layer_desc* desc, int32_t batch_
 /* Forward of one layer on one micro-batch of m samples (Sec. 3.2; the step timed as T_f(m)
  * in Sec. 3.3).
  *   flat_param  device, [P] in the compute dtype (fp32, or the bf16 copy of the fp32 master)
- *   x, y        device, [m, S, H] in the compute dtype; y may not alias x
+ *   x, y        device, [m, S, H] fp32 (the residual stream); y may not alias x
  *   save        device, save_bytes; holds what the backward needs (x itself is not copied:
  *               the caller keeps x alive and passes it to layer_bwd)
  *   scratch     device, scratch_bytes; contents undefined afterwards */
@@ -105,7 +107,7 @@ int cephalo_layer_fwd(const cephalo_layer_desc* desc, const void* flat_param,
  * is the caller's factor (Eq. 1's N*b_i/B and any 1/b_i mean).  Every element of flat_grad
  * is written by exactly one thread block in a fixed order, so results are reproducible.
  *   x           device, the forward input of this micro-batch
- *   dy, dx      device, [m, S, H] compute dtype; dx may not alias dy
+ *   dy, dx      device, [m, S, H] fp32; dx may not alias dy
  *   flat_grad   device, [P] fp32 */
 int cephalo_layer_bwd(const cephalo_layer_desc* desc, const void* flat_param,
                       const void* x, const void* dy, void* dx, int32_t micro_batch,
@@ -121,7 +123,7 @@ int cephalo_layer_bwd(const cephalo_layer_desc* desc, const void* flat_param,
  * of flat_grad is written exactly once:  flat_grad <- grad_scale * sum_j g_j.
  * Equal to l calls of layer_fwd and layer_bwd up to the order of the fp32 additions.
  * Fails with CEPHALO_EINVAL unless batch_share = l * micro_batch for a positive integer l.
- *   x, y, dy, dx  device, [b, S, H];  save, scratch: sizes from cephalo_share_workspace_bytes */
+ *   x, y, dy, dx  device, [b, S, H] fp32;  save, scratch: sizes from cephalo_share_workspace_bytes */
 int cephalo_share_layer_step(const cephalo_layer_desc* desc, const void* flat_param,
                              const void* x, void* y, const void* dy, void* dx,
                              int32_t batch_share, int32_t micro_batch,

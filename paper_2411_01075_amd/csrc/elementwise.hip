@@ -1,6 +1,8 @@
 // LayerNorm forward/backward and column sums (bias gradients): HBM-bound row kernels.
 // One 64-lane wavefront owns a row; its lanes hold the row in registers as 16-byte
 // vectors, and row statistics are wavefront reductions (no LDS, no block barrier).
+// The residual stream (x, x1, y and their gradients) and the gradients entering LayerNorm's
+// backward are fp32; LayerNorm outputs are in the activation type T.
 #include "kernels.h"
 
 namespace cephalo {
@@ -9,9 +11,30 @@ namespace {
 constexpr int kThreads = 256;
 constexpr int kWaves = kThreads / 64;
 
+// N consecutive floats (N = 4 or 8) as 16-byte loads / stores
+template <int N> __device__ __forceinline__ void load_f32(const float* p, float (&out)[N]) {
+  typedef float f32x4 __attribute__((ext_vector_type(4)));
+#pragma unroll
+  for (int q = 0; q < N / 4; ++q) {
+    const f32x4 v = *reinterpret_cast<const f32x4*>(p + 4 * q);
+#pragma unroll
+    for (int i = 0; i < 4; ++i) out[4 * q + i] = v[i];
+  }
+}
+template <int N> __device__ __forceinline__ void store_f32(float* p, const float (&in)[N]) {
+  typedef float f32x4 __attribute__((ext_vector_type(4)));
+#pragma unroll
+  for (int q = 0; q < N / 4; ++q) {
+    f32x4 v;
+#pragma unroll
+    for (int i = 0; i < 4; ++i) v[i] = in[4 * q + i];
+    *reinterpret_cast<f32x4*>(p + 4 * q) = v;
+  }
+}
+
 template <typename T, int MAXV>
 __global__ void __launch_bounds__(kThreads)
-ln_fwd_kernel(const T* __restrict__ x, const T* __restrict__ gamma, const T* __restrict__ beta,
+ln_fwd_kernel(const float* __restrict__ x, const T* __restrict__ gamma, const T* __restrict__ beta,
               T* __restrict__ u, float* __restrict__ mean, float* __restrict__ rstd,
               int rows, int H, float eps) {
   constexpr int VN = Vec<T>::N;
@@ -19,14 +42,14 @@ ln_fwd_kernel(const T* __restrict__ x, const T* __restrict__ gamma, const T* __r
   const int nv = H / VN;
   const float inv_h = 1.0f / (float)H;
   for (int row = blockIdx.x * kWaves + wave; row < rows; row += gridDim.x * kWaves) {
-    const T* xr = x + (int64_t)row * H;
+    const float* xr = x + (int64_t)row * H;
     float vals[MAXV][VN];
     float sum = 0.f;
 #pragma unroll
     for (int j = 0; j < MAXV; ++j) {
       const int v = lane + 64 * j;
       if (v < nv) {
-        load_vec<T>(xr + v * VN, vals[j]);
+        load_f32<VN>(xr + v * VN, vals[j]);
 #pragma unroll
         for (int i = 0; i < VN; ++i) sum += vals[j][i];
       }
@@ -64,9 +87,10 @@ constexpr int kLnBwdRowsPerBlock = 16;  // 4 rows per wavefront
 // part_g[blk][h] = sum over the block's rows of du*xhat, part_b[blk][h] = sum of du
 template <typename T, int MAXV>
 __global__ void __launch_bounds__(kThreads)
-ln_bwd_kernel(const T* __restrict__ du, const T* __restrict__ x, const float* __restrict__ mean,
-              const float* __restrict__ rstd, const T* __restrict__ gamma, const T* __restrict__ resid,
-              T* __restrict__ out, float* __restrict__ part_g, float* __restrict__ part_b, int rows, int H) {
+ln_bwd_kernel(const float* __restrict__ du, const float* __restrict__ x, const float* __restrict__ mean,
+              const float* __restrict__ rstd, const T* __restrict__ gamma, const float* __restrict__ resid,
+              float* __restrict__ out, T* __restrict__ out_lowp, float* __restrict__ part_g, float* __restrict__ part_b,
+              int rows, int H) {
   constexpr int VN = Vec<T>::N;
   __shared__ float red[2][kWaves][64 * VN];
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
@@ -90,8 +114,8 @@ ln_bwd_kernel(const T* __restrict__ du, const T* __restrict__ x, const float* __
       const int v = lane + 64 * j;
       if (v < nv) {
         float d[VN], xv[VN], gm[VN];
-        load_vec<T>(du + (int64_t)row * H + v * VN, d);
-        load_vec<T>(x + (int64_t)row * H + v * VN, xv);
+        load_f32<VN>(du + (int64_t)row * H + v * VN, d);
+        load_f32<VN>(x + (int64_t)row * H + v * VN, xv);
         load_vec<T>(gamma + v * VN, gm);
 #pragma unroll
         for (int i = 0; i < VN; ++i) {
@@ -111,14 +135,15 @@ ln_bwd_kernel(const T* __restrict__ du, const T* __restrict__ x, const float* __
       if (v < nv) {
         float rr[VN], o[VN];
         if (resid) {
-          load_vec<T>(resid + (int64_t)row * H + v * VN, rr);
+          load_f32<VN>(resid + (int64_t)row * H + v * VN, rr);
         } else {
 #pragma unroll
           for (int i = 0; i < VN; ++i) rr[i] = 0.f;
         }
 #pragma unroll
         for (int i = 0; i < VN; ++i) o[i] = rr[i] + rs * (g[j][i] - c1 - xh[j][i] * c2);
-        store_vec<T>(out + (int64_t)row * H + v * VN, o);
+        store_f32<VN>(out + (int64_t)row * H + v * VN, o);
+        if (out_lowp) store_vec<T>(out_lowp + (int64_t)row * H + v * VN, o);
       }
     }
   }
@@ -240,7 +265,7 @@ template <typename T> int maxv_for(int H) {
 }  // namespace
 
 template <typename T>
-int launch_ln_fwd(const T* x, const T* gamma, const T* beta, T* u, float* mean, float* rstd,
+int launch_ln_fwd(const float* x, const T* gamma, const T* beta, T* u, float* mean, float* rstd,
                   int rows, int H, float eps, hipStream_t s) {
   const int grid = (rows + kWaves - 1) / kWaves;
 #define LN_FWD_CASE(MV)                                                                             \
@@ -259,12 +284,12 @@ int launch_ln_fwd(const T* x, const T* gamma, const T* beta, T* u, float* mean, 
 int ln_bwd_blocks(int rows) { return (rows + kLnBwdRowsPerBlock - 1) / kLnBwdRowsPerBlock; }
 
 template <typename T>
-int launch_ln_bwd(const T* du, const T* x, const float* mean, const float* rstd, const T* gamma,
-                  const T* resid, T* out, float* part_g, float* part_b, int rows, int H, hipStream_t s) {
+int launch_ln_bwd(const float* du, const float* x, const float* mean, const float* rstd, const T* gamma,
+                  const float* resid, float* out, T* out_lowp, float* part_g, float* part_b, int rows, int H, hipStream_t s) {
   const int nblocks = ln_bwd_blocks(rows);
 #define LN_BWD_CASE(MV)                                                                                               \
   case MV:                                                                                                            \
-    ln_bwd_kernel<T, MV><<<nblocks, kThreads, 0, s>>>(du, x, mean, rstd, gamma, resid, out, part_g, part_b, rows, H); \
+    ln_bwd_kernel<T, MV><<<nblocks, kThreads, 0, s>>>(du, x, mean, rstd, gamma, resid, out, out_lowp, part_g, part_b, rows, H); \
     break;
   switch (maxv_for<T>(H)) {
     LN_BWD_CASE(1) LN_BWD_CASE(2) LN_BWD_CASE(4) LN_BWD_CASE(8) LN_BWD_CASE(16)
@@ -307,10 +332,10 @@ int launch_transpose_bf16(const bf16* in, bf16* out, int rows, int cols, hipStre
   return CEPHALO_OK;
 }
 
-#define INSTANTIATE(T)                                                                                         \
-  template int launch_ln_fwd<T>(const T*, const T*, const T*, T*, float*, float*, int, int, float, hipStream_t); \
-  template int launch_ln_bwd<T>(const T*, const T*, const float*, const float*, const T*, const T*, T*, float*, \
-                                float*, int, int, hipStream_t);                                                  \
+#define INSTANTIATE(T)                                                                                          \
+  template int launch_ln_fwd<T>(const float*, const T*, const T*, T*, float*, float*, int, int, float, hipStream_t); \
+  template int launch_ln_bwd<T>(const float*, const float*, const float*, const float*, const T*, const float*, float*, \
+                                T*, float*, float*, int, int, hipStream_t);                                       \
   template int launch_colsum<T>(const T*, float*, size_t, float*, float, int, int, int, hipStream_t);
 INSTANTIATE(float)
 INSTANTIATE(bf16)

@@ -322,10 +322,16 @@ __global__ void __launch_bounds__(kThreads) gemm_mfma_kernel(GemmArgs<bf16> a, i
         for (int t = 0; t < 8; ++t) v[t] += b8[t];
       }
       if (EPI == EPI_BIAS_RESID) {
-        float r8[8];
-        load_vec<bf16>(a.R + o, r8);
+        if (a.Rf) {      // fp32 residual stream
+          const f32x4 r0 = *reinterpret_cast<const f32x4*>(a.Rf + o), r1 = *reinterpret_cast<const f32x4*>(a.Rf + o + 4);
 #pragma unroll
-        for (int t = 0; t < 8; ++t) v[t] += r8[t];
+          for (int t = 0; t < 4; ++t) { v[t] += r0[t]; v[4 + t] += r1[t]; }
+        } else {
+          float r8[8];
+          load_vec<bf16>(a.R + o, r8);
+#pragma unroll
+          for (int t = 0; t < 8; ++t) v[t] += r8[t];
+        }
       }
       if (EPI == EPI_BIAS_GELU) {
         store_vec<bf16>(a.Z + o, v);
@@ -338,7 +344,15 @@ __global__ void __launch_bounds__(kThreads) gemm_mfma_kernel(GemmArgs<bf16> a, i
 #pragma unroll
         for (int t = 0; t < 8; ++t) v[t] *= gelu_grad_fast(z8[t]);
       }
-      store_vec<bf16>(a.C + o, v);
+      if (a.Cf) {        // fp32 output (residual stream, or a gradient that an element-wise kernel reads next)
+        f32x4 w0, w1;
+#pragma unroll
+        for (int t = 0; t < 4; ++t) { w0[t] = v[t]; w1[t] = v[4 + t]; }
+        *reinterpret_cast<f32x4*>(a.Cf + o) = w0;
+        *reinterpret_cast<f32x4*>(a.Cf + o + 4) = w1;
+      } else {
+        store_vec<bf16>(a.C + o, v);
+      }
     }
   }
 }
@@ -385,7 +399,7 @@ int launch_gemm_mfma(const GemmArgs<bf16>& a, hipStream_t s) {
   const int64_t ext_a = 2 * (ak ? (int64_t)a.M * a.a_rs : (int64_t)a.K * a.a_cs), ext_b = 2 * (bk ? (int64_t)a.N * a.b_rs : (int64_t)a.K * a.b_cs);
   const bool small = ext_a < (int64_t)0x7fffffff && ext_b < (int64_t)0x7fffffff;   // 32-bit buffer extents and offsets
   const int64_t pitch_c = a.ldc ? a.ldc : a.N;
-  const bool ok_c = pitch_c % 8 == 0 && pitch_c >= up8(a.N) && (a.epi != EPI_GRAD || a.N % 8 == 0) && aligned16(a.C) && aligned16(a.R) && aligned16(a.Z) && aligned16(a.bias) && aligned16(a.G);   // vector epilogue
+  const bool ok_c = pitch_c % 8 == 0 && pitch_c >= up8(a.N) && (a.epi != EPI_GRAD || a.N % 8 == 0) && aligned16(a.C) && aligned16(a.R) && aligned16(a.Z) && aligned16(a.bias) && aligned16(a.G) && aligned16(a.Rf) && aligned16(a.Cf);   // vector epilogue
   if (!ok_a || !ok_b || !ok_c || !small || !aligned16(a.A) || !aligned16(a.B)) return launch_gemm_simple<bf16>(a, s);
   // Only the layout/epilogue pairs a linear layer produces are instantiated.
   if (ak && bk) {          // forward: Y = X W^T

@@ -67,10 +67,11 @@ __global__ void __launch_bounds__(kThreads) gemm_simple_kernel(GemmArgs<T> a) {
       if (n >= a.N) continue;
       const int64_t o = a.epi == EPI_GRAD ? (int64_t)m * a.N + n : (int64_t)m * (a.ldc ? a.ldc : a.N) + n;
       float v = acc[i][j];
+      auto put = [&](float r) { if (a.Cf) a.Cf[o] = r; else a.C[o] = (T)r; };   // fp32 output if Cf is set
       switch (a.epi) {
-        case EPI_NONE: a.C[o] = (T)v; break;
-        case EPI_BIAS: a.C[o] = (T)(v + (float)a.bias[n]); break;
-        case EPI_BIAS_RESID: a.C[o] = (T)(v + (float)a.bias[n] + (float)a.R[o]); break;
+        case EPI_NONE: put(v); break;
+        case EPI_BIAS: put(v + (float)a.bias[n]); break;
+        case EPI_BIAS_RESID: put(v + (float)a.bias[n] + (a.Rf ? a.Rf[o] : (float)a.R[o])); break;
         case EPI_BIAS_GELU: {
           const float z = v + (float)a.bias[n];
           a.Z[o] = (T)z;

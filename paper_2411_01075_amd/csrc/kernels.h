@@ -99,6 +99,8 @@ struct GemmArgs {
                    // rounded up to 8; the padding columns are then written too (with the products of zero B rows)
   const T* bias;   // [N]
   const T* R;      // [M,N] residual
+  const float* Rf; // if set, EPI_BIAS_RESID reads its residual from here in fp32 (pitch ldc) instead of R
+  float* Cf;       // if set, EPI_NONE / EPI_BIAS / EPI_BIAS_RESID write their result here in fp32 (pitch ldc) instead of C
   T* Z;            // [M,N] pre-activation: written by EPI_BIAS_GELU, read by EPI_DGELU
   float* G;        // [M,N] fp32 gradient (EPI_GRAD)
   float scale;
@@ -109,17 +111,19 @@ template <typename T> int launch_gemm_simple(const GemmArgs<T>& a, hipStream_t s
 int launch_gemm_mfma(const GemmArgs<bf16>& a, hipStream_t s);  // bf16 operands, MFMA, fp32 accumulate
 
 // ---------------------------------------------------------------------------------------
-// LayerNorm over the last axis of x[rows, H].
+// LayerNorm over the last axis of x[rows, H].  The residual stream x is fp32; the output u is in the activation type.
 template <typename T>
-int launch_ln_fwd(const T* x, const T* gamma, const T* beta, T* u, float* mean, float* rstd,
+int launch_ln_fwd(const float* x, const T* gamma, const T* beta, T* u, float* mean, float* rstd,
                   int rows, int H, float eps, hipStream_t s);
 
-// out = resid + LN-backward(du) (resid may be null: no residual).  Each block of rows also writes its partial sums of dgamma (du * xhat) and
-// dbeta (du) to part_g / part_b ([ln_bwd_blocks(rows)][H] fp32 each); launch_reduce_partials folds any number
-// of such partial rows into a flat-gradient slice:  g = (accumulate ? g : 0) + scale * sum over chunks.
+// out = resid + LN-backward(du), all fp32 (resid may be null: no residual); out_lowp, if not null, receives the same
+// values in the activation type (the copy a following GEMM reads).  Each block of rows also writes its partial sums
+// of dgamma (du * xhat) and dbeta (du) to part_g / part_b ([ln_bwd_blocks(rows)][H] fp32 each);
+// launch_reduce_partials folds any number of such partial rows into a flat-gradient slice:
+//   g = (accumulate ? g : 0) + scale * sum over chunks.
 template <typename T>
-int launch_ln_bwd(const T* du, const T* x, const float* mean, const float* rstd, const T* gamma,
-                  const T* resid, T* out, float* part_g, float* part_b, int rows, int H, hipStream_t s);
+int launch_ln_bwd(const float* du, const float* x, const float* mean, const float* rstd, const T* gamma,
+                  const float* resid, float* out, T* out_lowp, float* part_g, float* part_b, int rows, int H, hipStream_t s);
 int ln_bwd_blocks(int rows);
 int launch_reduce_partials(const float* partials, int nchunks, int N, float* g, float scale, int accumulate, hipStream_t s);
 
@@ -128,6 +132,9 @@ template <typename T>
 int launch_colsum(const T* dY, float* partials, size_t partial_bytes, float* g, float scale,
                   int accumulate, int rows, int N, hipStream_t s);
 size_t colsum_partial_bytes(int rows, int N);
+
+// dst[i] = bf16(src[i]), i in [0, n)
+int launch_cast_bf16(bf16* dst, const float* src, int64_t n, hipStream_t s);
 
 // out[c][r] = in[r][c] for a row-major bf16 matrix [rows, cols]; rows and cols multiples of 8
 int launch_transpose_bf16(const bf16* in, bf16* out, int rows, int cols, hipStream_t s);

@@ -52,8 +52,10 @@ extern "C" int cephalo_layer_fwd(const cephalo_layer_desc* desc, const void* fla
     return fail(CEPHALO_EWORKSPACE, "layer_fwd: save area %zu B < %zu B", save_bytes, save_layout(*desc, micro_batch).total);
   (void)scratch; (void)scratch_bytes;
   hipStream_t s = static_cast<hipStream_t>(stream);
-  if (desc->dtype == CEPHALO_F32) return run_fwd<float>(*desc, flat_param, x, y, micro_batch, save, s);
-  return run_fwd<bf16>(*desc, flat_param, x, y, micro_batch, save, s);
+  const float* xf = static_cast<const float*>(x);
+  float* yf = static_cast<float*>(y);
+  if (desc->dtype == CEPHALO_F32) return run_fwd<float>(*desc, flat_param, xf, yf, micro_batch, save, s);
+  return run_fwd<bf16>(*desc, flat_param, xf, yf, micro_batch, save, s);
 }
 
 extern "C" int cephalo_layer_bwd(const cephalo_layer_desc* desc, const void* flat_param,
@@ -70,9 +72,12 @@ extern "C" int cephalo_layer_bwd(const cephalo_layer_desc* desc, const void* fla
   if (scratch_bytes < need) return fail(CEPHALO_EWORKSPACE, "layer_bwd: scratch %zu B < %zu B", scratch_bytes, need);
   hipStream_t s = static_cast<hipStream_t>(stream);
   void* sv = const_cast<void*>(save);
+  const float* xf = static_cast<const float*>(x);
+  const float* dyf = static_cast<const float*>(dy);
+  float* dxf = static_cast<float*>(dx);
   if (desc->dtype == CEPHALO_F32)
-    return run_bwd<float>(*desc, flat_param, x, dy, dx, micro_batch, sv, flat_grad, grad_scale, accumulate, scratch, s);
-  return run_bwd<bf16>(*desc, flat_param, x, dy, dx, micro_batch, sv, flat_grad, grad_scale, accumulate, scratch, s);
+    return run_bwd<float>(*desc, flat_param, xf, dyf, dxf, micro_batch, sv, flat_grad, grad_scale, accumulate, scratch, s);
+  return run_bwd<bf16>(*desc, flat_param, xf, dyf, dxf, micro_batch, sv, flat_grad, grad_scale, accumulate, scratch, s);
 }
 
 extern "C" int cephalo_share_layer_step(const cephalo_layer_desc* desc, const void* flat_param,
@@ -94,7 +99,11 @@ extern "C" int cephalo_share_layer_step(const cephalo_layer_desc* desc, const vo
   const size_t need = scratch_layout(*desc, micro_batch, batch_share).total;
   if (scratch_bytes < need) return fail(CEPHALO_EWORKSPACE, "share_layer_step: scratch %zu B < %zu B", scratch_bytes, need);
   hipStream_t s = static_cast<hipStream_t>(stream);
+  const float* xf = static_cast<const float*>(x);
+  float* yf = static_cast<float*>(y);
+  const float* dyf = static_cast<const float*>(dy);
+  float* dxf = static_cast<float*>(dx);
   if (desc->dtype == CEPHALO_F32)
-    return run_share<float>(*desc, flat_param, x, y, dy, dx, batch_share, micro_batch, save, flat_grad, grad_scale, scratch, s);
-  return run_share<bf16>(*desc, flat_param, x, y, dy, dx, batch_share, micro_batch, save, flat_grad, grad_scale, scratch, s);
+    return run_share<float>(*desc, flat_param, xf, yf, dyf, dxf, batch_share, micro_batch, save, flat_grad, grad_scale, scratch, s);
+  return run_share<bf16>(*desc, flat_param, xf, yf, dyf, dxf, batch_share, micro_batch, save, flat_grad, grad_scale, scratch, s);
 }

@@ -4,6 +4,7 @@
 #pragma once
 #include "kernels.h"
 #include <initializer_list>
+#include <type_traits>
 
 #define TRY(expr) do { int rc__ = (expr); if (rc__ != CEPHALO_OK) return rc__; } while (0)
 
@@ -57,15 +58,20 @@ int check_desc(const cephalo_layer_desc* d) {
   return CEPHALO_OK;
 }
 
+// The residual stream (x, x1, y and the gradients dy, dx1, dx) is fp32 in both modes; everything a GEMM or
+// the attention reads is in the activation type T (float, or bf16 with fp32 accumulation).  Where a
+// residual-stream gradient is also a GEMM operand, the kernel that produces it writes a second copy in T
+// ("lowp"); in fp32 mode the two are the same buffer.
+//
 // Saved activations of `n` samples, tensor-major: each tensor is one [n*S, width] matrix, so the
 // slice of a micro-batch is a row range and the whole share is one contiguous operand.
 struct SaveLayout {
   size_t mean1, rstd1, u, qkv, lse, O, x1, mean2, rstd2, u2, z, h, total;
 };
-// Backward work area.  dz, dx1 and dqkv (the dY operands of the weight gradients) are kept for `span`
-// samples; the rest is per micro-batch of m samples.
+// Backward work area.  dz, dx1 and dqkv (the dY operands of the weight gradients) and the copy of dy in the
+// activation type are kept for `span` samples; the rest is per micro-batch of m samples.
 struct ScratchLayout {
-  size_t dz, dx1, dqkv, du2, dO, du, dvec, tpose, ln_part, col_part, col_part_bytes, total;
+  size_t dz, dx1, dx1l, dyl, dqkv, du2, dO, du, dvec, tpose, ln_part, col_part, col_part_bytes, total;
   size_t ln_rows;   // rows of each of the four LayerNorm partial arrays (ln2.gamma, ln2.beta, ln1.gamma, ln1.beta)
 };
 
@@ -80,7 +86,7 @@ SaveLayout save_layout(const cephalo_layer_desc& d, int n) {
   L.qkv = take(T * 3 * H * es);
   L.lse = take((size_t)n * d.heads * d.seq * 4);
   L.O = take(T * H * es);
-  L.x1 = take(T * H * es);
+  L.x1 = take(T * H * 4);
   L.mean2 = take(T * 4); L.rstd2 = take(T * 4);
   L.u2 = take(T * H * es);
   L.z = take(T * F * es);
@@ -96,11 +102,13 @@ ScratchLayout scratch_layout(const cephalo_layer_desc& d, int m, int span) {
   size_t p = 0;
   auto take = [&](size_t bytes) { size_t at = p; p += align_up(bytes); return at; };
   L.dz = take(Ts * F * es);
-  L.dx1 = take(Ts * H * es);
+  L.dx1 = take(Ts * H * 4);
+  L.dx1l = es == 4 ? L.dx1 : take(Ts * H * es);
+  L.dyl = es == 4 ? 0 : take(Ts * H * es);
   L.dqkv = take(Ts * 3 * H * es);
-  L.du2 = take(Tm * H * es);
+  L.du2 = take(Tm * H * 4);        // gradients entering the LayerNorm backward: fp32
   L.dO = take(Tm * H * es);
-  L.du = take(Tm * H * es);
+  L.du = take(Tm * H * 4);
   L.dvec = take((size_t)m * d.heads * d.seq * 4);
   L.tpose = take(Ts * H * es);     // [H, tokens] token-minor copy of one activation for the weight-gradient GEMMs
   L.ln_rows = (size_t)(span / m) * ln_bwd_blocks((int)Tm);
@@ -205,8 +213,8 @@ int wgrad<bf16>(const bf16* dY, const bf16* X, int Tn, int N, int K, float* G, f
 }
 
 template <typename T> struct Saved {
-  float *mean1, *rstd1, *lse, *mean2, *rstd2;
-  T *u, *qkv, *O, *x1, *u2, *z, *h;
+  float *mean1, *rstd1, *lse, *mean2, *rstd2, *x1;
+  T *u, *qkv, *O, *u2, *z, *h;
 };
 // pointers to the saved tensors of the samples starting at `sample0` inside a save area laid out by L
 template <typename T>
@@ -217,15 +225,16 @@ Saved<T> saved_at(void* base, const SaveLayout& L, const cephalo_layer_desc& d, 
   s.mean2 = at<float>(base, L.mean2) + t0; s.rstd2 = at<float>(base, L.rstd2) + t0;
   s.lse = at<float>(base, L.lse) + (size_t)sample0 * d.heads * d.seq;
   s.u = at<T>(base, L.u) + t0 * H; s.qkv = at<T>(base, L.qkv) + t0 * 3 * H; s.O = at<T>(base, L.O) + t0 * H;
-  s.x1 = at<T>(base, L.x1) + t0 * H; s.u2 = at<T>(base, L.u2) + t0 * H;
+  s.x1 = at<float>(base, L.x1) + t0 * H; s.u2 = at<T>(base, L.u2) + t0 * H;
   s.z = at<T>(base, L.z) + t0 * F; s.h = at<T>(base, L.h) + t0 * F;
   return s;
 }
 
 template <typename T> struct Work {
-  T *dz, *dx1, *dqkv;          // at the token offset of the current micro-batch (or of the span for the parameter pass)
-  T *du2, *dO, *du, *tbuf;
-  float *dvec;
+  T *dz, *dx1l, *dyl, *dqkv;   // at the token offset of the current micro-batch (or of the span for the parameter pass)
+  float *dx1;                  // likewise; dx1l is its copy in T (the same buffer in fp32 mode), dyl the caller's dy in T
+  T *dO, *tbuf;
+  float *du2, *du, *dvec;
   float *ln2_g, *ln2_b, *ln1_g, *ln1_b;   // LayerNorm partial sums, at the row offset of the current micro-batch
   float *col_part; size_t col_part_bytes;
 };
@@ -233,8 +242,9 @@ template <typename T>
 Work<T> work_at(void* base, const ScratchLayout& W, const cephalo_layer_desc& d, int sample0, int mb_index, int m) {
   const size_t t0 = (size_t)sample0 * d.seq, H = d.hidden, F = d.mlp;
   Work<T> w;
-  w.dz = at<T>(base, W.dz) + t0 * F; w.dx1 = at<T>(base, W.dx1) + t0 * H; w.dqkv = at<T>(base, W.dqkv) + t0 * 3 * H;
-  w.du2 = at<T>(base, W.du2); w.dO = at<T>(base, W.dO); w.du = at<T>(base, W.du); w.tbuf = at<T>(base, W.tpose);
+  w.dz = at<T>(base, W.dz) + t0 * F; w.dx1 = at<float>(base, W.dx1) + t0 * H; w.dx1l = at<T>(base, W.dx1l) + t0 * H;
+  w.dyl = at<T>(base, W.dyl) + t0 * H; w.dqkv = at<T>(base, W.dqkv) + t0 * 3 * H;
+  w.du2 = at<float>(base, W.du2); w.dO = at<T>(base, W.dO); w.du = at<float>(base, W.du); w.tbuf = at<T>(base, W.tpose);
   w.dvec = at<float>(base, W.dvec);
   float* ln = at<float>(base, W.ln_part);
   const size_t r0 = (size_t)mb_index * ln_bwd_blocks(m * d.seq) * H, arr = W.ln_rows * H;
@@ -245,7 +255,7 @@ Work<T> work_at(void* base, const ScratchLayout& W, const cephalo_layer_desc& d,
 
 // ---- forward of one micro-batch ----------------------------------------------------------------
 template <typename T>
-int layer_fwd_t(const cephalo_layer_desc& d, const T* P, const T* x, T* y, int m, const Saved<T>& sv, hipStream_t s) {
+int layer_fwd_t(const cephalo_layer_desc& d, const T* P, const float* x, float* y, int m, const Saved<T>& sv, hipStream_t s) {
   const ParamOffsets o = param_offsets(d);
   const int Tn = m * d.seq, H = d.hidden, F = d.mlp;
   TRY(launch_ln_fwd<T>(x, P + o.ln1_g, P + o.ln1_b, sv.u, sv.mean1, sv.rstd1, Tn, H, d.ln_eps, s));
@@ -257,7 +267,7 @@ int layer_fwd_t(const cephalo_layer_desc& d, const T* P, const T* x, T* y, int m
   TRY(attn_fwd<T>(sv.qkv, sv.O, sv.lse, m, d.seq, H, d.heads, d.causal, s));
   {
     GemmArgs<T> a = linear_fwd<T>(sv.O, P + o.w_o, Tn, H, H);
-    a.epi = EPI_BIAS_RESID; a.bias = P + o.b_o; a.R = x; a.C = sv.x1;
+    a.epi = EPI_BIAS_RESID; a.bias = P + o.b_o; a.Rf = x; a.Cf = sv.x1;
     TRY(gemm<T>(a, s));
   }
   TRY(launch_ln_fwd<T>(sv.x1, P + o.ln2_g, P + o.ln2_b, sv.u2, sv.mean2, sv.rstd2, Tn, H, d.ln_eps, s));
@@ -268,62 +278,75 @@ int layer_fwd_t(const cephalo_layer_desc& d, const T* P, const T* x, T* y, int m
   }
   {
     GemmArgs<T> a = linear_fwd<T>(sv.h, P + o.w_fc2, Tn, H, F);
-    a.epi = EPI_BIAS_RESID; a.bias = P + o.b_fc2; a.R = sv.x1; a.C = y;
+    a.epi = EPI_BIAS_RESID; a.bias = P + o.b_fc2; a.Rf = sv.x1; a.Cf = y;
     TRY(gemm<T>(a, s));
   }
   return CEPHALO_OK;
 }
 
+// The copy of a residual-stream gradient in the activation type: the buffer itself in fp32 mode.
+template <typename T> const T* lowp_of(const float* f, const T* l);
+template <> inline const float* lowp_of<float>(const float* f, const float*) { return f; }
+template <> inline const bf16* lowp_of<bf16>(const float*, const bf16* l) { return l; }
+template <typename T> T* lowp_out(T* l) { return std::is_same<T, float>::value ? nullptr : l; }   // nothing extra to write in fp32 mode
+
+// dst = T(src) for n elements when T is not float (used where the caller hands dy in fp32)
+template <typename T> int make_lowp(T* dst, const float* src, int64_t n, hipStream_t s);
+template <> inline int make_lowp<float>(float*, const float*, int64_t, hipStream_t) { return CEPHALO_OK; }
+template <> inline int make_lowp<bf16>(bf16* dst, const float* src, int64_t n, hipStream_t s) { return launch_cast_bf16(dst, src, n, s); }
+
 // ---- backward, data path of one micro-batch: dx and the dY operands (dz, dx1, dqkv) of the weight gradients --------
+// dyl is dy in the activation type (same rows); dxl, if not null, receives dx in the activation type as well.
 template <typename T>
-int layer_bwd_data_t(const cephalo_layer_desc& d, const T* P, const T* x, const T* dy, T* dx, int m,
+int layer_bwd_data_t(const cephalo_layer_desc& d, const T* P, const float* x, const float* dy, const T* dyl, float* dx, T* dxl, int m,
                      const Saved<T>& sv, const Work<T>& w, hipStream_t s) {
   const ParamOffsets o = param_offsets(d);
   const int Tn = m * d.seq, H = d.hidden, F = d.mlp;
   {
-    GemmArgs<T> a = linear_dgrad<T>(dy, P + o.w_fc2, Tn, H, F);   // dh = dy W2, then dz = dh * gelu'(z)
+    GemmArgs<T> a = linear_dgrad<T>(dyl, P + o.w_fc2, Tn, H, F);   // dh = dy W2, then dz = dh * gelu'(z)
     a.epi = EPI_DGELU; a.Z = sv.z; a.C = w.dz;
     TRY(gemm<T>(a, s));
   }
   {
     GemmArgs<T> a = linear_dgrad<T>(w.dz, P + o.w_fc1, Tn, F, H);
-    a.epi = EPI_NONE; a.C = w.du2;
+    a.epi = EPI_NONE; a.Cf = w.du2;
     TRY(gemm<T>(a, s));
   }
   // u2 = LN2(x1); dx1 = dy + LN2-backward(du2)
-  TRY(launch_ln_bwd<T>(w.du2, sv.x1, sv.mean2, sv.rstd2, P + o.ln2_g, dy, w.dx1, w.ln2_g, w.ln2_b, Tn, H, s));
+  TRY(launch_ln_bwd<T>(w.du2, sv.x1, sv.mean2, sv.rstd2, P + o.ln2_g, dy, w.dx1, lowp_out<T>(w.dx1l), w.ln2_g, w.ln2_b, Tn, H, s));
   {
-    GemmArgs<T> a = linear_dgrad<T>(w.dx1, P + o.w_o, Tn, H, H);
+    GemmArgs<T> a = linear_dgrad<T>(lowp_of<T>(w.dx1, w.dx1l), P + o.w_o, Tn, H, H);
     a.epi = EPI_NONE; a.C = w.dO;
     TRY(gemm<T>(a, s));
   }
   TRY(attn_bwd<T>(sv.qkv, sv.O, w.dO, sv.lse, w.dvec, w.dqkv, m, d.seq, H, d.heads, d.causal, s));
   {
     GemmArgs<T> a = linear_dgrad<T>(w.dqkv, P + o.w_qkv, Tn, 3 * H, H);
-    a.epi = EPI_NONE; a.C = w.du;
+    a.epi = EPI_NONE; a.Cf = w.du;
     TRY(gemm<T>(a, s));
   }
   // u = LN1(x); dx = dx1 + LN1-backward(du)
-  TRY(launch_ln_bwd<T>(w.du, x, sv.mean1, sv.rstd1, P + o.ln1_g, w.dx1, dx, w.ln1_g, w.ln1_b, Tn, H, s));
+  TRY(launch_ln_bwd<T>(w.du, x, sv.mean1, sv.rstd1, P + o.ln1_g, w.dx1, dx, lowp_out<T>(dxl), w.ln1_g, w.ln1_b, Tn, H, s));
   return CEPHALO_OK;
 }
 
 // ---- backward, parameter path over `tokens` tokens (one micro-batch, or the whole share at once) ---------------------
 // G <- (acc ? G : 0) + scale * (gradient summed over those tokens).  Over the whole share the sum over micro-batches
-// happens inside the fp32 MFMA accumulators and each gradient element is written exactly once.
+// happens inside the fp32 MFMA accumulators and each gradient element is written exactly once.  Bias gradients of the
+// two residual-stream projections are column sums of the fp32 gradients.
 template <typename T>
-int layer_bwd_params_t(const cephalo_layer_desc& d, const T* dy, int tokens, int ln_chunks,
+int layer_bwd_params_t(const cephalo_layer_desc& d, const float* dy, const T* dyl, int tokens, int ln_chunks,
                        const Saved<T>& sv, const Work<T>& w, float* G, float scale, int acc, hipStream_t s) {
   const ParamOffsets o = param_offsets(d);
   const int H = d.hidden, F = d.mlp;
-  TRY(launch_colsum<T>(dy, w.col_part, w.col_part_bytes, G + o.b_fc2, scale, acc, tokens, H, s));
-  TRY(wgrad<T>(dy, sv.h, tokens, H, F, G + o.w_fc2, scale, acc, w.tbuf, s));
+  TRY(launch_colsum<float>(dy, w.col_part, w.col_part_bytes, G + o.b_fc2, scale, acc, tokens, H, s));
+  TRY(wgrad<T>(dyl, sv.h, tokens, H, F, G + o.w_fc2, scale, acc, w.tbuf, s));
   TRY(launch_colsum<T>(w.dz, w.col_part, w.col_part_bytes, G + o.b_fc1, scale, acc, tokens, F, s));
   TRY(wgrad<T>(w.dz, sv.u2, tokens, F, H, G + o.w_fc1, scale, acc, w.tbuf, s));
   TRY(launch_reduce_partials(w.ln2_g, ln_chunks, H, G + o.ln2_g, scale, acc, s));
   TRY(launch_reduce_partials(w.ln2_b, ln_chunks, H, G + o.ln2_b, scale, acc, s));
-  TRY(launch_colsum<T>(w.dx1, w.col_part, w.col_part_bytes, G + o.b_o, scale, acc, tokens, H, s));
-  TRY(wgrad<T>(w.dx1, sv.O, tokens, H, H, G + o.w_o, scale, acc, w.tbuf, s));
+  TRY(launch_colsum<float>(w.dx1, w.col_part, w.col_part_bytes, G + o.b_o, scale, acc, tokens, H, s));
+  TRY(wgrad<T>(lowp_of<T>(w.dx1, w.dx1l), sv.O, tokens, H, H, G + o.w_o, scale, acc, w.tbuf, s));
   TRY(launch_colsum<T>(w.dqkv, w.col_part, w.col_part_bytes, G + o.b_qkv, scale, acc, tokens, 3 * H, s));
   TRY(wgrad<T>(w.dqkv, sv.u, tokens, 3 * H, H, G + o.w_qkv, scale, acc, w.tbuf, s));
   TRY(launch_reduce_partials(w.ln1_g, ln_chunks, H, G + o.ln1_g, scale, acc, s));
@@ -332,41 +355,44 @@ int layer_bwd_params_t(const cephalo_layer_desc& d, const T* dy, int tokens, int
 }
 
 template <typename T>
-int run_fwd(const cephalo_layer_desc& d, const void* P, const void* x, void* y, int m, void* save, hipStream_t s) {
+int run_fwd(const cephalo_layer_desc& d, const void* P, const float* x, float* y, int m, void* save, hipStream_t s) {
   const SaveLayout L = save_layout(d, m);
-  return layer_fwd_t<T>(d, static_cast<const T*>(P), static_cast<const T*>(x), static_cast<T*>(y), m, saved_at<T>(save, L, d, 0), s);
+  return layer_fwd_t<T>(d, static_cast<const T*>(P), x, y, m, saved_at<T>(save, L, d, 0), s);
 }
 
 template <typename T>
-int run_bwd(const cephalo_layer_desc& d, const void* P, const void* x, const void* dy, void* dx, int m, void* save,
+int run_bwd(const cephalo_layer_desc& d, const void* P, const float* x, const float* dy, float* dx, int m, void* save,
             float* G, float scale, int acc, void* scratch, hipStream_t s) {
   const SaveLayout L = save_layout(d, m);
   const ScratchLayout W = scratch_layout(d, m, m);
   const Saved<T> sv = saved_at<T>(save, L, d, 0);
   const Work<T> w = work_at<T>(scratch, W, d, 0, 0, m);
-  TRY(layer_bwd_data_t<T>(d, static_cast<const T*>(P), static_cast<const T*>(x), static_cast<const T*>(dy), static_cast<T*>(dx), m, sv, w, s));
-  return layer_bwd_params_t<T>(d, static_cast<const T*>(dy), m * d.seq, ln_bwd_blocks(m * d.seq), sv, w, G, scale, acc, s);
+  const int64_t act = (int64_t)m * d.seq * d.hidden;
+  TRY(make_lowp<T>(w.dyl, dy, act, s));
+  const T* dyl = lowp_of<T>(dy, w.dyl);
+  TRY(layer_bwd_data_t<T>(d, static_cast<const T*>(P), x, dy, dyl, dx, (T*)nullptr, m, sv, w, s));
+  return layer_bwd_params_t<T>(d, dy, dyl, m * d.seq, ln_bwd_blocks(m * d.seq), sv, w, G, scale, acc, s);
 }
 
 // Whole share: forward of every micro-batch, data-path backward of every micro-batch, then ONE parameter pass over
 // all b*S tokens (the dY operands and the saved activations of all micro-batches are contiguous by construction).
 template <typename T>
-int run_share(const cephalo_layer_desc& d, const void* Pv, const void* xv, void* yv, const void* dyv, void* dxv,
+int run_share(const cephalo_layer_desc& d, const void* Pv, const float* x, float* y, const float* dy, float* dx,
               int b, int m, void* save, float* G, float scale, void* scratch, hipStream_t s) {
   const T* P = static_cast<const T*>(Pv);
-  const T* x = static_cast<const T*>(xv); T* y = static_cast<T*>(yv);
-  const T* dy = static_cast<const T*>(dyv); T* dx = static_cast<T*>(dxv);
   const SaveLayout L = save_layout(d, b);
   const ScratchLayout W = scratch_layout(d, m, b);
   const int l = b / m;
   const size_t act = (size_t)m * d.seq * d.hidden;   // elements of one micro-batch of x / y / dy / dx
   for (int j = 0; j < l; ++j)
     TRY(layer_fwd_t<T>(d, P, x + j * act, y + j * act, m, saved_at<T>(save, L, d, j * m), s));
+  const Work<T> w0 = work_at<T>(scratch, W, d, 0, 0, m);
+  TRY(make_lowp<T>(w0.dyl, dy, (int64_t)l * act, s));
+  const T* dyl = lowp_of<T>(dy, w0.dyl);
   for (int j = 0; j < l; ++j)
-    TRY(layer_bwd_data_t<T>(d, P, x + j * act, dy + j * act, dx + j * act, m, saved_at<T>(save, L, d, j * m),
-                            work_at<T>(scratch, W, d, j * m, j, m), s));
-  return layer_bwd_params_t<T>(d, dy, b * d.seq, l * ln_bwd_blocks(m * d.seq), saved_at<T>(save, L, d, 0),
-                               work_at<T>(scratch, W, d, 0, 0, m), G, scale, 0, s);
+    TRY(layer_bwd_data_t<T>(d, P, x + j * act, dy + j * act, dyl + j * act, dx + j * act, (T*)nullptr, m,
+                            saved_at<T>(save, L, d, j * m), work_at<T>(scratch, W, d, j * m, j, m), s));
+  return layer_bwd_params_t<T>(d, dy, dyl, b * d.seq, l * ln_bwd_blocks(m * d.seq), saved_at<T>(save, L, d, 0), w0, G, scale, 0, s);
 }
 
 int check_io(const char* who, const cephalo_layer_desc* d, int m, std::initializer_list<const void*> ptrs) {

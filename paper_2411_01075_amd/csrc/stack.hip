@@ -16,7 +16,7 @@ __device__ __forceinline__ int clamp_id(int id, int V) { return id < 0 ? 0 : (id
 // x0[t] = wte[id[t]] + wpe[t % S]; one wavefront per token.  Ids outside [0, V) are clamped.
 template <typename T>
 __global__ void __launch_bounds__(kThreads)
-embed_fwd_kernel(const int* __restrict__ ids, const T* __restrict__ wte, const T* __restrict__ wpe, T* __restrict__ x0,
+embed_fwd_kernel(const int* __restrict__ ids, const T* __restrict__ wte, const T* __restrict__ wpe, float* __restrict__ x0,
                  int tokens, int S, int H, int V) {
   constexpr int VN = Vec<T>::N;
   const int t = blockIdx.x * 4 + (threadIdx.x >> 6), lane = threadIdx.x & 63;
@@ -28,8 +28,7 @@ embed_fwd_kernel(const int* __restrict__ ids, const T* __restrict__ wte, const T
     load_vec<T>(e + v * VN, a);
     load_vec<T>(p + v * VN, b);
 #pragma unroll
-    for (int i = 0; i < VN; ++i) a[i] += b[i];
-    store_vec<T>(x0 + (int64_t)t * H + v * VN, a);
+    for (int i = 0; i < VN; ++i) x0[(int64_t)t * H + v * VN + i] = a[i] + b[i];
   }
 }
 
@@ -43,45 +42,48 @@ __device__ __forceinline__ float block_reduce(float v, bool is_max, float* red) 
   return is_max ? fmaxf(fmaxf(a, b), fmaxf(c, d)) : (a + b) + (c + d);
 }
 
-// One block per token row of logits [rows, ld] (V valid columns).  loss[row] = logsumexp - logit[target];
-// the row is overwritten by coef * (softmax - onehot(target)); columns V..ld-1 are set to zero.
+// One block per token row of the fp32 logits [rows, ld] (V valid columns).  loss[row] = logsumexp - logit[target];
+// dlogits[row] = coef * (softmax - onehot(target)) in the activation type, columns V..ld-1 set to zero.
+// Two passes over the row: a running (max, sum of exp) pair per thread, merged across the block, then the gradient.
 template <typename T>
 __global__ void __launch_bounds__(kThreads)
-cross_entropy_kernel(T* __restrict__ logits, const int* __restrict__ targets, float* __restrict__ loss,
-                     int V, int ld, float coef) {
-  constexpr int VN = Vec<T>::N;
+cross_entropy_kernel(const float* __restrict__ logits, T* __restrict__ dlogits, const int* __restrict__ targets,
+                     float* __restrict__ loss, int V, int ld, float coef) {
+  typedef float f32x4 __attribute__((ext_vector_type(4)));
   __shared__ float red[4];
-  T* row = logits + (int64_t)blockIdx.x * ld;
-  const int nv = ld / VN;
-  float mx = -INFINITY;
+  const float* row = logits + (int64_t)blockIdx.x * ld;
+  T* drow = dlogits + (int64_t)blockIdx.x * ld;
+  const int nv = ld / 4;
+  float mx = -INFINITY, sum = 0.f;
   for (int v = threadIdx.x; v < nv; v += kThreads) {
-    float a[VN];
-    load_vec<T>(row + v * VN, a);
+    const f32x4 a = *reinterpret_cast<const f32x4*>(row + v * 4);
+    float m4 = -INFINITY;
 #pragma unroll
-    for (int i = 0; i < VN; ++i) if (v * VN + i < V) mx = fmaxf(mx, a[i]);
-  }
-  mx = block_reduce(mx, true, red);
-  float sum = 0.f;
-  for (int v = threadIdx.x; v < nv; v += kThreads) {
-    float a[VN];
-    load_vec<T>(row + v * VN, a);
+    for (int i = 0; i < 4; ++i) if (v * 4 + i < V) m4 = fmaxf(m4, a[i]);
+    if (m4 > mx) { sum *= __expf(mx - m4); mx = m4; }      // exp(-inf) = 0 covers the first step
 #pragma unroll
-    for (int i = 0; i < VN; ++i) if (v * VN + i < V) sum += __expf(a[i] - mx);
+    for (int i = 0; i < 4; ++i) if (v * 4 + i < V) sum += __expf(a[i] - mx);
   }
-  sum = block_reduce(sum, false, red);
-  const float lse = mx + __logf(sum);
+  const float bmx = block_reduce(mx, true, red);
+  sum = block_reduce(mx == -INFINITY ? 0.f : sum * __expf(mx - bmx), false, red);
+  const float lse = bmx + __logf(sum);
   const int tgt = clamp_id(targets[blockIdx.x], V);
-  if (threadIdx.x == 0) loss[blockIdx.x] = lse - (float)row[tgt];
-  __syncthreads();     // the target logit has been read before the row is overwritten
-  for (int v = threadIdx.x; v < nv; v += kThreads) {
+  if (threadIdx.x == 0) loss[blockIdx.x] = lse - row[tgt];
+  constexpr int VN = Vec<T>::N;
+  for (int v = threadIdx.x; v < ld / VN; v += kThreads) {
     float a[VN];
-    load_vec<T>(row + v * VN, a);
+#pragma unroll
+    for (int q = 0; q < VN / 4; ++q) {
+      const f32x4 r = *reinterpret_cast<const f32x4*>(row + v * VN + 4 * q);
+#pragma unroll
+      for (int i = 0; i < 4; ++i) a[4 * q + i] = r[i];
+    }
 #pragma unroll
     for (int i = 0; i < VN; ++i) {
       const int c = v * VN + i;
       a[i] = c < V ? coef * (__expf(a[i] - lse) - (c == tgt ? 1.f : 0.f)) : 0.f;
     }
-    store_vec<T>(row + v * VN, a);
+    store_vec<T>(drow + v * VN, a);
   }
 }
 
@@ -102,10 +104,10 @@ __global__ void __launch_bounds__(kThreads) sort_keys_kernel(const int* __restri
 // Token-embedding gradient: tokens sorted by id (stable, so ascending token index inside a run); the wavefront at
 // the head of each run of equal ids sums the run's rows of dx0 in that order and adds the sum to the id's row of
 // the gradient (which already holds the LM-head part).  One writer per row, fixed order: reproducible.
-template <typename T>
 __global__ void __launch_bounds__(kThreads)
-embed_bwd_kernel(const int* __restrict__ keys, const int* __restrict__ vals, const T* __restrict__ dx0, float* __restrict__ g_wte,
+embed_bwd_kernel(const int* __restrict__ keys, const int* __restrict__ vals, const float* __restrict__ dx0, float* __restrict__ g_wte,
                  int n, int H) {
+  typedef float T;
   constexpr int VN = Vec<T>::N;
   const int i = blockIdx.x * 4 + (threadIdx.x >> 6), lane = threadIdx.x & 63;
   if (i >= n) return;
@@ -128,9 +130,9 @@ embed_bwd_kernel(const int* __restrict__ keys, const int* __restrict__ vals, con
 }
 
 // Position-embedding gradient: g_wpe[s] = sum over the b samples of dx0[n, s], samples in order.
-template <typename T>
 __global__ void __launch_bounds__(kThreads)
-wpe_bwd_kernel(const T* __restrict__ dx0, float* __restrict__ g_wpe, int b, int S, int H) {
+wpe_bwd_kernel(const float* __restrict__ dx0, float* __restrict__ g_wpe, int b, int S, int H) {
+  typedef float T;
   constexpr int VN = Vec<T>::N;
   const int64_t v = (int64_t)blockIdx.x * kThreads + threadIdx.x;    // vector index inside [S, H]
   if (v * VN >= (int64_t)S * H) return;
@@ -164,7 +166,7 @@ size_t sort_temp_bytes(int n) {
 }
 
 struct StackLayout {
-  size_t xs, saves, save_each, scratch, dxa, dxb, uf, meanf, rstdf, duf, logits, loss, lnf_part, keys, sort_tmp, sort_tmp_bytes, total;
+  size_t xs, saves, save_each, scratch, dxa, dxb, dxal, dxbl, uf, meanf, rstdf, duf, logits, dlogits, loss, lnf_part, keys, sort_tmp, sort_tmp_bytes, total;
   int ldv;            // padded pitch of the logits
   size_t lnf_rows;
 };
@@ -177,14 +179,16 @@ StackLayout stack_layout(const cephalo_stack_desc& d, int b, int m) {
   L.ldv = (d.vocab + 7) / 8 * 8;
   size_t p = 0;
   auto take = [&](size_t bytes) { size_t at = p; p += align_up(bytes); return at; };
-  L.xs = take((size_t)(d.layers + 1) * n * H * es);
+  L.xs = take((size_t)(d.layers + 1) * n * H * 4);      // layer-boundary activations: the fp32 residual stream
   L.save_each = align_up(save_layout(ld, b).total);
   L.saves = take((size_t)d.layers * L.save_each);
   L.scratch = take(scratch_layout(ld, m, b).total);
-  L.dxa = take(n * H * es); L.dxb = take(n * H * es);
+  L.dxa = take(n * H * 4); L.dxb = take(n * H * 4);     // gradient of the residual stream, ping-pong between layers
+  L.dxal = es == 4 ? L.dxa : take(n * H * es); L.dxbl = es == 4 ? L.dxb : take(n * H * es);   // and its copy in the activation type
   L.uf = take(n * H * es); L.meanf = take(n * 4); L.rstdf = take(n * 4);
-  L.duf = take(Tm * H * es);
-  L.logits = take(n * (size_t)L.ldv * es);
+  L.duf = take(Tm * H * 4);
+  L.logits = take(Tm * (size_t)L.ldv * 4);        // one micro-batch of fp32 logits, reused
+  L.dlogits = take(n * (size_t)L.ldv * es);       // their gradient for the whole share (an operand of the weight gradient)
   L.loss = take(n * 4);
   L.lnf_rows = (size_t)(b / m) * ln_bwd_blocks((int)Tm);
   L.lnf_part = take(2 * L.lnf_rows * H * 4);
@@ -207,7 +211,7 @@ int run_stack(const cephalo_stack_desc& d, const void* Pv, const int* ids, const
   const StackLayout L = stack_layout(d, b, m);
   const SaveLayout SL = save_layout(ld, b);
   const ScratchLayout WL = scratch_layout(ld, m, b);
-  auto xs = [&](int layer) { return at<T>(ws, L.xs) + (size_t)layer * n * H; };
+  auto xs = [&](int layer) { return at<float>(ws, L.xs) + (size_t)layer * n * H; };
   void* scratch = at<char>(ws, L.scratch);
   const size_t act = (size_t)Tm * H;
 
@@ -219,37 +223,38 @@ int run_stack(const cephalo_stack_desc& d, const void* Pv, const int* ids, const
     for (int j = 0; j < l; ++j)
       TRY(layer_fwd_t<T>(ld, P + o_layers + li * PL, xs(li) + j * act, xs(li + 1) + j * act, m, saved_at<T>(save, SL, ld, j * m), s));
   }
-  // ---- head: final LN, tied logits, cross-entropy (logits become their own gradient), back to the last layer's output
-  T* uf = at<T>(ws, L.uf); T* logits = at<T>(ws, L.logits); T* duf = at<T>(ws, L.duf);
+  // ---- head: final LN, tied logits (fp32, one micro-batch at a time), cross-entropy and its gradient, back to the last layer's output
+  T* uf = at<T>(ws, L.uf); float* logits = at<float>(ws, L.logits); T* dlogits = at<T>(ws, L.dlogits); float* duf = at<float>(ws, L.duf);
   float* meanf = at<float>(ws, L.meanf); float* rstdf = at<float>(ws, L.rstdf);
   float* lnf_g = at<float>(ws, L.lnf_part); float* lnf_b = lnf_g + L.lnf_rows * H;
-  T* dx_cur = at<T>(ws, L.dxa); T* dx_nxt = at<T>(ws, L.dxb);
+  float* dx_cur = at<float>(ws, L.dxa); float* dx_nxt = at<float>(ws, L.dxb);
+  T* dxl_cur = at<T>(ws, L.dxal); T* dxl_nxt = at<T>(ws, L.dxbl);
   const float coef = scale / (float)n;
   const int nb = ln_bwd_blocks(Tm);
   for (int j = 0; j < l; ++j) {
     const size_t t0 = (size_t)j * Tm;
     TRY(launch_ln_fwd<T>(xs(NL) + t0 * H, P + o_lnf, P + o_lnf + H, uf + t0 * H, meanf + t0, rstdf + t0, Tm, H, ld.ln_eps, s));
-    T* lg = logits + t0 * L.ldv;
+    T* dlg = dlogits + t0 * L.ldv;
     {
       GemmArgs<T> a = linear_fwd<T>(uf + t0 * H, P + o_wte, Tm, V, H);
-      a.epi = EPI_NONE; a.C = lg; a.ldc = L.ldv;
+      a.epi = EPI_NONE; a.Cf = logits; a.ldc = L.ldv;
       TRY(gemm<T>(a, s));
     }
-    cross_entropy_kernel<T><<<Tm, kThreads, 0, s>>>(lg, targets + t0, at<float>(ws, L.loss) + t0, V, L.ldv, coef);
+    cross_entropy_kernel<T><<<Tm, kThreads, 0, s>>>(logits, dlg, targets + t0, at<float>(ws, L.loss) + t0, V, L.ldv, coef);
     CEPHALO_CHECK_LAUNCH("cross_entropy");
     {
-      GemmArgs<T> a = linear_dgrad<T>(lg, P + o_wte, Tm, V, H);   // duf = dlogits wte
-      a.a_rs = L.ldv; a.epi = EPI_NONE; a.C = duf;
+      GemmArgs<T> a = linear_dgrad<T>(dlg, P + o_wte, Tm, V, H);   // duf = dlogits wte
+      a.a_rs = L.ldv; a.epi = EPI_NONE; a.Cf = duf;
       TRY(gemm<T>(a, s));
     }
-    TRY(launch_ln_bwd<T>(duf, xs(NL) + t0 * H, meanf + t0, rstdf + t0, P + o_lnf, (const T*)nullptr, dx_cur + t0 * H,
-                         lnf_g + (size_t)j * nb * H, lnf_b + (size_t)j * nb * H, Tm, H, s));
+    TRY(launch_ln_bwd<T>(duf, xs(NL) + t0 * H, meanf + t0, rstdf + t0, P + o_lnf, (const float*)nullptr, dx_cur + t0 * H,
+                         lowp_out<T>(dxl_cur + t0 * H), lnf_g + (size_t)j * nb * H, lnf_b + (size_t)j * nb * H, Tm, H, s));
   }
   mean_kernel<<<1, kThreads, 0, s>>>(at<float>(ws, L.loss), n, loss_out);
   CEPHALO_CHECK_LAUNCH("mean_loss");
   {
     Work<T> w = work_at<T>(scratch, WL, ld, 0, 0, m);
-    TRY(wgrad<T>(logits, uf, n, V, H, G + o_wte, 1.0f, 0, w.tbuf, s, L.ldv));        // LM-head part of d wte, whole share
+    TRY(wgrad<T>(dlogits, uf, n, V, H, G + o_wte, 1.0f, 0, w.tbuf, s, L.ldv));        // LM-head part of d wte, whole share
     TRY(launch_reduce_partials(lnf_g, l * nb, H, G + o_lnf, 1.0f, 0, s));
     TRY(launch_reduce_partials(lnf_b, l * nb, H, G + o_lnf + H, 1.0f, 0, s));
   }
@@ -258,21 +263,22 @@ int run_stack(const cephalo_stack_desc& d, const void* Pv, const int* ids, const
     void* save = at<char>(ws, L.saves + (size_t)li * L.save_each);
     const T* Pl = P + o_layers + li * PL;
     for (int j = 0; j < l; ++j)
-      TRY(layer_bwd_data_t<T>(ld, Pl, xs(li) + j * act, dx_cur + j * act, dx_nxt + j * act, m, saved_at<T>(save, SL, ld, j * m),
-                              work_at<T>(scratch, WL, ld, j * m, j, m), s));
-    TRY(layer_bwd_params_t<T>(ld, dx_cur, n, l * nb, saved_at<T>(save, SL, ld, 0), work_at<T>(scratch, WL, ld, 0, 0, m),
-                              G + o_layers + li * PL, 1.0f, 0, s));
-    T* t = dx_cur; dx_cur = dx_nxt; dx_nxt = t;
+      TRY(layer_bwd_data_t<T>(ld, Pl, xs(li) + j * act, dx_cur + j * act, lowp_of<T>(dx_cur, dxl_cur) + j * act, dx_nxt + j * act,
+                              dxl_nxt + j * act, m, saved_at<T>(save, SL, ld, j * m), work_at<T>(scratch, WL, ld, j * m, j, m), s));
+    TRY(layer_bwd_params_t<T>(ld, dx_cur, lowp_of<T>(dx_cur, dxl_cur), n, l * nb, saved_at<T>(save, SL, ld, 0),
+                              work_at<T>(scratch, WL, ld, 0, 0, m), G + o_layers + li * PL, 1.0f, 0, s));
+    { float* t = dx_cur; dx_cur = dx_nxt; dx_nxt = t; }
+    { T* t = dxl_cur; dxl_cur = dxl_nxt; dxl_nxt = t; }
   }
   // ---- embeddings
-  wpe_bwd_kernel<T><<<(int)(((int64_t)S * H / Vec<T>::N + kThreads - 1) / kThreads), kThreads, 0, s>>>(dx_cur, G + o_wpe, b, S, H);
+  wpe_bwd_kernel<<<(int)(((int64_t)S * H / 4 + kThreads - 1) / kThreads), kThreads, 0, s>>>(dx_cur, G + o_wpe, b, S, H);
   CEPHALO_CHECK_LAUNCH("wpe_bwd");
   int* keys_in = at<int>(ws, L.keys); int* vals_in = keys_in + n; int* keys_out = vals_in + n; int* vals_out = keys_out + n;
   sort_keys_kernel<<<(n + kThreads - 1) / kThreads, kThreads, 0, s>>>(ids, keys_in, vals_in, n, V);
   size_t tmp = L.sort_tmp_bytes;
   if (rocprim::radix_sort_pairs(at<char>(ws, L.sort_tmp), tmp, keys_in, keys_out, vals_in, vals_out, (size_t)n, 0, 32, s) != hipSuccess)
     return fail(CEPHALO_EHIP, "stack_step: sort of the token ids failed");
-  embed_bwd_kernel<T><<<(n + 3) / 4, kThreads, 0, s>>>(keys_out, vals_out, dx_cur, G + o_wte, n, H);
+  embed_bwd_kernel<<<(n + 3) / 4, kThreads, 0, s>>>(keys_out, vals_out, dx_cur, G + o_wte, n, H);
   CEPHALO_CHECK_LAUNCH("embed_bwd");
   return CEPHALO_OK;
 }

@@ -202,6 +202,16 @@ extern "C" int cephalo_grad_accum(float* acc, const float* g, float scale, int64
   return CEPHALO_OK;
 }
 
+namespace cephalo {
+int launch_cast_bf16(bf16* dst, const float* src, int64_t n, hipStream_t s) {
+  if (n <= 0) return CEPHALO_OK;
+  const int grid = grid_for(n / 4, kStreamThreads);
+  cast_bf16_kernel<<<grid, kStreamThreads, 0, s>>>(dst, src, n);
+  CEPHALO_CHECK_LAUNCH("cast_bf16");
+  return CEPHALO_OK;
+}
+}  // namespace cephalo
+
 extern "C" int cephalo_cast_bf16(void* dst, const float* src, int64_t n, void* stream) {
   if (n < 0) return fail(CEPHALO_EINVAL, "cast_bf16: n = %lld < 0", (long long)n);
   if (n == 0) return CEPHALO_OK;

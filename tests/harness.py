@@ -52,8 +52,8 @@ def gpu_share_step(cfg, tensors, x, dy, grad_scale=1.0, via_share_call=True):
     else:
         flat = torch.empty(flat32.numel(), dtype=torch.bfloat16, device="cuda")
         C.cephalo_cast_bf16(flat, flat32)
-    xd = torch.from_numpy(x).cuda().to(dt).contiguous()
-    dyd = torch.from_numpy(dy).cuda().to(dt).contiguous()
+    xd = torch.from_numpy(x).cuda().float().contiguous()      # the residual stream is fp32 in both modes
+    dyd = torch.from_numpy(dy).cuda().float().contiguous()
     b, m = x.shape[0], cfg.micro_batch
     l = b // m
     yd = torch.empty_like(xd)
@@ -81,13 +81,12 @@ def gpu_share_step(cfg, tensors, x, dy, grad_scale=1.0, via_share_call=True):
 
 
 def oracle_share_step(cfg, tensors, x, dy, grad_scale=1.0):
-    """Oracle on the same inputs; bf16 workloads round parameters, x and dy to bf16 first."""
+    """Oracle on the same inputs; bf16 workloads round the parameters to bf16 first (x and dy reach the GPU in fp32)."""
     H, F = cfg.hidden, cfg.mlp
     flat = olayout.flatten_layer(tensors, H, F, dtype=np.float64)
     x64, dy64 = x.astype(np.float64), dy.astype(np.float64)
     if cfg.dtype == "bf16":
         flat = round_to_bf16(flat.astype(np.float32))
-        x64, dy64 = round_to_bf16(x), round_to_bf16(dy)
     return oshare.share_layer_step(flat, x64, dy64, H, F, cfg.heads, cfg.causal, cfg.micro_batch, scale=grad_scale)
 
 
