@@ -226,8 +226,9 @@ colsum_kernel(const T* __restrict__ dY, float* __restrict__ partials, int rows, 
 
 // 64x64 tile transposed through LDS: 16-byte global reads along the input rows, 16-byte global
 // writes along the output rows; the LDS tile is padded so that the column walk is conflict-free.
+// out has row pitch `pitch` >= rows; its columns [rows, pitch) are written with zeros.
 __global__ void __launch_bounds__(kThreads)
-transpose_bf16_kernel(const bf16* __restrict__ in, bf16* __restrict__ out, int rows, int cols) {
+transpose_bf16_kernel(const bf16* __restrict__ in, bf16* __restrict__ out, int rows, int cols, int pitch) {
   __shared__ bf16 tile[64][64 + 2];
   typedef bf16 bf16x8 __attribute__((ext_vector_type(8)));
   const int r0 = blockIdx.y * 64, c0 = blockIdx.x * 64;
@@ -245,11 +246,11 @@ transpose_bf16_kernel(const bf16* __restrict__ in, bf16* __restrict__ out, int r
   for (int p = 0; p < 2; ++p) {
     const int v = threadIdx.x + kThreads * p;
     const int c = v >> 3, r = (v & 7) * 8;       // output row c, output columns r..r+7
-    if (c0 + c < cols && r0 + r < rows) {
+    if (c0 + c < cols && r0 + r < pitch) {
       bf16x8 val;
 #pragma unroll
       for (int i = 0; i < 8; ++i) val[i] = tile[r + i][c];
-      *reinterpret_cast<bf16x8*>(out + (int64_t)(c0 + c) * rows + r0 + r) = val;
+      *reinterpret_cast<bf16x8*>(out + (int64_t)(c0 + c) * pitch + r0 + r) = val;
     }
   }
 }
@@ -324,10 +325,12 @@ int launch_colsum(const T* dY, float* partials, size_t partial_bytes, float* g, 
   return CEPHALO_OK;
 }
 
-int launch_transpose_bf16(const bf16* in, bf16* out, int rows, int cols, hipStream_t s) {
-  if (rows % 8 != 0 || cols % 8 != 0) return fail(CEPHALO_EINVAL, "transpose: %d x %d is not a multiple of 8 in both extents", rows, cols);
-  dim3 grid((cols + 63) / 64, (rows + 63) / 64);
-  transpose_bf16_kernel<<<grid, kThreads, 0, s>>>(in, out, rows, cols);
+int launch_transpose_bf16(const bf16* in, bf16* out, int rows, int cols, hipStream_t s, int out_pitch) {
+  if (out_pitch == 0) out_pitch = rows;
+  if (out_pitch % 8 != 0 || out_pitch < rows || cols % 8 != 0)
+    return fail(CEPHALO_EINVAL, "transpose: %d x %d into pitch %d: columns and pitch must be multiples of 8", rows, cols, out_pitch);
+  dim3 grid((cols + 63) / 64, (out_pitch + 63) / 64);
+  transpose_bf16_kernel<<<grid, kThreads, 0, s>>>(in, out, rows, cols, out_pitch);
   CEPHALO_CHECK_LAUNCH("transpose");
   return CEPHALO_OK;
 }

@@ -26,6 +26,7 @@
 // one barrier per slab.  256 threads = 4 wavefronts in a 2x2 grid; v_mfma_f32_32x32x16_bf16.
 #include "kernels.h"
 #include <cstdlib>
+#include <algorithm>
 
 namespace cephalo {
 namespace {
@@ -46,14 +47,14 @@ __device__ __forceinline__ __amdgpu_buffer_rsrc_t make_rsrc(const void* p, unsig
 }
 
 // One operand's tile: ROWS matrix rows (m or n) by BK k-values, ROWS*BK*2 bytes of LDS, unpadded.
-template <int ROWS, bool KFAST>
+template <int ROWS, bool KFAST, int NW>
 struct OperandTile {
   static constexpr int BYTES = ROWS * BK * 2;
   static constexpr int INSTR = BYTES / 1024;            // direct-to-LDS load instructions per tile (1 KiB each)
-  static constexpr int PER_WAVE = INSTR / 4;
+  static constexpr int PER_WAVE = INSTR / NW;           // NW wavefronts share the loads
   static constexpr int PITCH = KFAST ? BK * 2 : ROWS * 2;   // bytes per LDS row
   static constexpr int CHUNKS = PITCH / 16;                 // 16-byte chunks per LDS row
-  static_assert(INSTR % 4 == 0, "tile must split evenly over the 4 wavefronts");
+  static_assert(INSTR % NW == 0, "tile must split evenly over the wavefronts");
   static_assert(KFAST || ROWS >= 128, "row-contiguous tiles need at least 128 rows");
 
   // LDS row / chunk slot that lane `lane` of load instruction `j` of this wavefront fills, and the
@@ -138,11 +139,12 @@ struct OperandTile {
   }
 };
 
-template <int BM, int BN, bool AK, bool BKF, int EPI>
-__global__ void __launch_bounds__(kThreads) gemm_mfma_kernel(GemmArgs<bf16> a, int tiles_m, int tiles_n) {
-  typedef OperandTile<BM, AK> TA;
-  typedef OperandTile<BN, BKF> TB;
-  constexpr int WTM = BM / 2, WTN = BN / 2;     // wavefront tile (2x2 wavefronts)
+template <int BM, int BN, int WGM, int WGN, bool AK, bool BKF, int EPI>
+__global__ void __launch_bounds__(64 * WGM * WGN) gemm_mfma_kernel(GemmArgs<bf16> a, int tiles_m, int tiles_n, int slabs_per_split) {
+  constexpr int NW = WGM * WGN;                 // wavefronts per block, in a WGM x WGN grid
+  typedef OperandTile<BM, AK, NW> TA;
+  typedef OperandTile<BN, BKF, NW> TB;
+  constexpr int WTM = BM / WGM, WTN = BN / WGN; // wavefront tile
   constexpr int MI = WTM / 32, NI = WTN / 32;
   constexpr int STAGE = TA::BYTES + TB::BYTES;
   extern __shared__ __attribute__((aligned(1024))) char smem_raw[];
@@ -153,7 +155,8 @@ __global__ void __launch_bounds__(kThreads) gemm_mfma_kernel(GemmArgs<bf16> a, i
   // walk 4-row groups of the tile grid column by column, so that the tiles an XCD works on at
   // the same time form a compact patch sharing A row-panels and B column-panels in its L2.
   const int total = tiles_m * tiles_n;
-  int pid = blockIdx.x;
+  const int split = blockIdx.x / total;                 // which piece of the contracted axis (0 unless EPI_GRAD is split)
+  int pid = blockIdx.x % total;
   if (total % 8 == 0) pid = (pid % 8) * (total / 8) + pid / 8;
   constexpr int GROUP = 4;
   const int per_group = GROUP * tiles_n;
@@ -163,7 +166,7 @@ __global__ void __launch_bounds__(kThreads) gemm_mfma_kernel(GemmArgs<bf16> a, i
   const int m0 = tile_m * BM, n0 = tile_n * BN;
 
   const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
-  const int wm = (wave >> 1) * WTM, wn = (wave & 1) * WTN;
+  const int wm = (wave / WGN) * WTM, wn = (wave % WGN) * WTN;
 
   f32x16 acc[MI][NI];
 #pragma unroll
@@ -181,6 +184,13 @@ __global__ void __launch_bounds__(kThreads) gemm_mfma_kernel(GemmArgs<bf16> a, i
   TA::init_offsets(a.a_rs, a.a_cs, m0, a.M, a.K, offa);
   TB::init_offsets(a.b_rs, a.b_cs, n0, a.N, a.K, offb);
   const unsigned a_step = (unsigned)(2 * BK * a.a_cs), b_step = (unsigned)(2 * BK * a.b_cs);
+  const int slabs = (a.K + BK - 1) / BK;
+  const int kb0 = split * slabs_per_split;              // first k-slab of this block
+  const int nk = min(slabs - kb0, slabs_per_split);     // >= 1 by the launcher's choice of splits
+  if (kb0 > 0) {
+    TA::advance(offa, (unsigned)kb0 * a_step);
+    TB::advance(offb, (unsigned)kb0 * b_step);
+  }
   const typename TA::Frag fra = TA::frag_init(wm);
   const typename TB::Frag frb = TB::frag_init(wn);
 
@@ -190,14 +200,13 @@ __global__ void __launch_bounds__(kThreads) gemm_mfma_kernel(GemmArgs<bf16> a, i
   //     (every wavefront has finished reading this stage: its k-step-3 fragments are in registers), then
   //     start the loads of slab kt+2 into this stage and read the first fragments of slab kt+1 during
   //     the MFMAs of k-step 3.  One barrier per slab; no LDS or global latency is exposed.
-  const int nk = (a.K + BK - 1) / BK;
-  TA::load_slab(ra_rsrc, offa, 0, a.K, smem);
-  TB::load_slab(rb_rsrc, offb, 0, a.K, smem + TA::BYTES);
+  TA::load_slab(ra_rsrc, offa, kb0 * BK, a.K, smem);
+  TB::load_slab(rb_rsrc, offb, kb0 * BK, a.K, smem + TA::BYTES);
   if (nk > 1) {
     TA::advance(offa, a_step);
     TB::advance(offb, b_step);
-    TA::load_slab(ra_rsrc, offa, BK, a.K, smem + STAGE);
-    TB::load_slab(rb_rsrc, offb, BK, a.K, smem + STAGE + TA::BYTES);
+    TA::load_slab(ra_rsrc, offa, (kb0 + 1) * BK, a.K, smem + STAGE);
+    TB::load_slab(rb_rsrc, offb, (kb0 + 1) * BK, a.K, smem + STAGE + TA::BYTES);
     __builtin_amdgcn_s_waitcnt(0x0F70 | (TA::PER_WAVE + TB::PER_WAVE));   // vmcnt(loads of slab 1 may still fly)
   } else {
     __builtin_amdgcn_s_waitcnt(0x0F70);                                   // vmcnt(0)
@@ -229,8 +238,8 @@ __global__ void __launch_bounds__(kThreads) gemm_mfma_kernel(GemmArgs<bf16> a, i
         if (kt + 2 < nk) {
           TA::advance(offa, a_step);
           TB::advance(offb, b_step);
-          TA::load_slab(ra_rsrc, offa, (kt + 2) * BK, a.K, smem + (kt & 1) * STAGE);
-          TB::load_slab(rb_rsrc, offb, (kt + 2) * BK, a.K, smem + (kt & 1) * STAGE + TA::BYTES);
+          TA::load_slab(ra_rsrc, offa, (kb0 + kt + 2) * BK, a.K, smem + (kt & 1) * STAGE);
+          TB::load_slab(rb_rsrc, offb, (kb0 + kt + 2) * BK, a.K, smem + (kt & 1) * STAGE + TA::BYTES);
         }
         if (kt + 1 < nk) {
 #pragma unroll
@@ -261,7 +270,11 @@ __global__ void __launch_bounds__(kThreads) gemm_mfma_kernel(GemmArgs<bf16> a, i
   // groups of four consecutive columns.
   const int h = lane >> 5;
   if (EPI == EPI_GRAD) {
-    // fp32 gradient tile: 16-byte read-modify-write per lane
+    // fp32 gradient tile: 16-byte read-modify-write per lane (a split contraction writes its plain partial sums)
+    const bool partial = a.splits > 1;
+    float* const gbase = partial ? a.part + (int64_t)split * a.M * a.N : a.G;
+    const float scale = partial ? 1.0f : a.scale;
+    const bool accumulate = !partial && a.accumulate;
 #pragma unroll
     for (int i = 0; i < MI; ++i) {
       const int m = m0 + wm + 32 * i + (lane & 31);
@@ -272,11 +285,11 @@ __global__ void __launch_bounds__(kThreads) gemm_mfma_kernel(GemmArgs<bf16> a, i
         for (int q = 0; q < 4; ++q) {
           const int n = n0 + wn + 32 * j + 8 * q + 4 * h;
           if (n >= a.N) continue;                       // N is a multiple of 8: the group of 4 is inside or outside
-          f32x4* gp = reinterpret_cast<f32x4*>(a.G + (int64_t)m * a.N + n);
+          f32x4* gp = reinterpret_cast<f32x4*>(gbase + (int64_t)m * a.N + n);
           f32x4 v;
 #pragma unroll
-          for (int r = 0; r < 4; ++r) v[r] = a.scale * acc[i][j][4 * q + r];
-          if (a.accumulate) v += *gp;
+          for (int r = 0; r < 4; ++r) v[r] = scale * acc[i][j][4 * q + r];
+          if (accumulate) v += *gp;
           *gp = v;
         }
     }
@@ -290,7 +303,7 @@ __global__ void __launch_bounds__(kThreads) gemm_mfma_kernel(GemmArgs<bf16> a, i
   constexpr int SP = WTN + 4;                           // staging pitch in floats (16 bytes of padding per row)
   constexpr int LPR = WTN / 8;                          // lanes per row when reading back 8 columns per lane
   constexpr int RPS = 64 / LPR;                         // rows per read step
-  static_assert(4 * 32 * SP * 4 <= 2 * STAGE, "staging regions must fit in the operand stages");
+  static_assert(NW * 32 * SP * 4 <= 160 * 1024, "staging regions must fit in LDS");   // the launch reserves max(stages, staging)
   LDS_AS float* stage = (LDS_AS float*)(smem + wave * (32 * SP * 4));
 #pragma unroll
   for (int i = 0; i < MI; ++i) {
@@ -357,36 +370,91 @@ __global__ void __launch_bounds__(kThreads) gemm_mfma_kernel(GemmArgs<bf16> a, i
   }
 }
 
-template <int BM, int BN, bool AK, bool BKF, int EPI>
+// G = (accumulate ? G : 0) + scale * (part[0] + part[1] + ... ) in split order, 4 floats per thread
+__global__ void __launch_bounds__(256)
+splitk_reduce_kernel(const float* __restrict__ part, int splits, int64_t mn4, float* __restrict__ G, float scale, int accumulate) {
+  const int64_t i = (int64_t)blockIdx.x * 256 + threadIdx.x;
+  if (i >= mn4) return;
+  f32x4 sum = reinterpret_cast<const f32x4*>(part)[i];
+  for (int p = 1; p < splits; ++p) sum += reinterpret_cast<const f32x4*>(part)[(int64_t)p * mn4 + i];
+  f32x4 out = scale * sum;
+  if (accumulate) out += reinterpret_cast<const f32x4*>(G)[i];
+  reinterpret_cast<f32x4*>(G)[i] = out;
+}
+
+template <int BM, int BN, int WGM, int WGN, bool AK, bool BKF, int EPI>
 int launch_cfg(const GemmArgs<bf16>& a, hipStream_t s) {
-  typedef OperandTile<BM, AK> TA;
-  typedef OperandTile<BN, BKF> TB;
-  const size_t lds = 2 * (size_t)(TA::BYTES + TB::BYTES);
+  typedef OperandTile<BM, AK, WGM * WGN> TA;
+  typedef OperandTile<BN, BKF, WGM * WGN> TB;
+  constexpr size_t staging = (size_t)WGM * WGN * 32 * (BN / WGN + 4) * 4;      // epilogue transposition area of all wavefronts
+  const size_t lds = std::max<size_t>(2 * (size_t)(TA::BYTES + TB::BYTES), EPI == EPI_GRAD ? 0 : staging);
   const int tm = (a.M + BM - 1) / BM, tn = (a.N + BN - 1) / BN;
-  auto kern = gemm_mfma_kernel<BM, BN, AK, BKF, EPI>;
+  auto kern = gemm_mfma_kernel<BM, BN, WGM, WGN, AK, BKF, EPI>;
   static bool attr_set = false;   // per instantiation
   if (!attr_set) {
     if (hipFuncSetAttribute(reinterpret_cast<const void*>(kern), hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds) != hipSuccess)
       return fail(CEPHALO_EHIP, "gemm_mfma: cannot reserve %zu B of LDS", lds);
     attr_set = true;
   }
-  kern<<<tm * tn, kThreads, lds, s>>>(a, tm, tn);
+  const int slabs = (a.K + BK - 1) / BK;
+  int splits = (EPI == EPI_GRAD && a.splits > 1 && a.part) ? a.splits : 1;
+  int per = (slabs + splits - 1) / splits;
+  splits = (slabs + per - 1) / per;                       // every piece holds at least one k-slab
+  GemmArgs<bf16> k = a;
+  k.splits = splits;
+  kern<<<tm * tn * splits, 64 * WGM * WGN, lds, s>>>(k, tm, tn, per);
   CEPHALO_CHECK_LAUNCH("gemm_mfma");
+  if (splits > 1) {
+    const int64_t mn4 = (int64_t)a.M * a.N / 4;
+    splitk_reduce_kernel<<<(int)((mn4 + 255) / 256), 256, 0, s>>>(a.part, splits, mn4, a.G, a.scale, a.accumulate);
+    CEPHALO_CHECK_LAUNCH("splitk_reduce");
+  }
   return CEPHALO_OK;
 }
 
 template <bool AK, bool BKF, int EPI>
 int launch_tiles(const GemmArgs<bf16>& a, hipStream_t s) {
-  // Largest tile that still yields at least one block per compute unit.
-  static const int force = getenv("CEPHALO_GEMM_TILE") ? atoi(getenv("CEPHALO_GEMM_TILE")) : 0;   // tuning aid
-  const int64_t t256 = (int64_t)((a.M + 255) / 256) * ((a.N + 255) / 256);
-  const int64_t t128 = (int64_t)((a.M + 255) / 256) * ((a.N + 127) / 128);
-  if (force == 256 || (force == 0 && t256 >= 256)) return launch_cfg<256, 256, AK, BKF, EPI>(a, s);
-  if (force == 128 || (force == 0 && t128 >= 200)) return launch_cfg<256, 128, AK, BKF, EPI>(a, s);
-  return launch_cfg<128, 128, AK, BKF, EPI>(a, s);
+  static const int force = getenv("CEPHALO_GEMM_CFG") ? atoi(getenv("CEPHALO_GEMM_CFG")) : 0;   // tuning aid
+  // Tile choice: the score of a configuration is the fraction of the last round of blocks that the 256 compute
+  // units fill, times the rate its main loop reaches relative to the 256 x 256 tile (measured: bigger tiles
+  // move fewer LDS and L2 bytes per MFMA).
+  const int nsplit = (EPI == EPI_GRAD && a.splits > 1 && a.part) ? a.splits : 1;
+  auto fill = [&](int bm, int bn) {
+    const double t = (double)((a.M + bm - 1) / bm) * ((a.N + bn - 1) / bn) * nsplit;
+    return t / (256.0 * (double)(int64_t)((t + 255) / 256));
+  };
+  int cfg = force;
+  if (cfg == 0) {
+    double best = fill(256, 256); cfg = 2;
+    if (BKF) { const double v = 0.93 * fill(256, 192); if (v > best) { best = v; cfg = 7; } }
+    { const double v = 0.88 * fill(256, 128); if (v > best) { best = v; cfg = 4; } }
+    { const double v = 0.70 * fill(128, 128); if (v > best) { best = v; cfg = 6; } }
+  }
+  switch (cfg) {
+    case 1: return launch_cfg<256, 256, 2, 2, AK, BKF, EPI>(a, s);
+    case 2: return AK ? launch_cfg<256, 256, 2, 4, AK, BKF, EPI>(a, s) : launch_cfg<256, 256, 4, 2, AK, BKF, EPI>(a, s);
+    case 3: return launch_cfg<256, 128, 2, 2, AK, BKF, EPI>(a, s);
+    case 4: return launch_cfg<256, 128, 4, 2, AK, BKF, EPI>(a, s);
+    case 5: return launch_cfg<256, 128, 2, 4, AK, BKF, EPI>(a, s);
+    case 7: if constexpr (BKF) return launch_cfg<256, 192, 4, 2, AK, BKF, EPI>(a, s);
+    default: return launch_cfg<128, 128, 2, 2, AK, BKF, EPI>(a, s);
+  }
 }
 
 }  // namespace
+
+int gemm_grad_splits(int M, int N, int K) {
+  const double tiles = (double)((M + 255) / 256) * ((N + 255) / 256);
+  int best = 1;
+  double best_score = 0.0;
+  for (int sp : {1, 2, 3, 4, 6, 8}) {
+    if (sp > 1 && K / sp < 1024) break;                 // keep each piece's main loop long
+    const double t = tiles * sp;
+    const double score = t / (256.0 * (double)(int64_t)((t + 255) / 256)) * (1.0 - 0.03 * (sp - 1));   // fill, minus the second pass
+    if (score > best_score + 1e-9) { best_score = score; best = sp; }
+  }
+  return best;
+}
 
 int launch_gemm_mfma(const GemmArgs<bf16>& a, hipStream_t s) {
   if (a.M <= 0 || a.N <= 0 || a.K <= 0) return fail(CEPHALO_EINVAL, "gemm: empty problem %dx%dx%d", a.M, a.N, a.K);
@@ -408,6 +476,8 @@ int launch_gemm_mfma(const GemmArgs<bf16>& a, hipStream_t s) {
       case EPI_BIAS: return launch_tiles<true, true, EPI_BIAS>(a, s);
       case EPI_BIAS_RESID: return launch_tiles<true, true, EPI_BIAS_RESID>(a, s);
       case EPI_BIAS_GELU: return launch_tiles<true, true, EPI_BIAS_GELU>(a, s);
+      case EPI_DGELU: return launch_tiles<true, true, EPI_DGELU>(a, s);
+      case EPI_GRAD: return launch_tiles<true, true, EPI_GRAD>(a, s);
     }
   } else if (ak && !bk) {  // dgrad: dX = dY W
     switch (a.epi) {

@@ -105,7 +105,15 @@ struct GemmArgs {
   float* G;        // [M,N] fp32 gradient (EPI_GRAD)
   float scale;
   int accumulate;
+  // EPI_GRAD with the contraction split over `splits` > 1 blocks per tile (long token axes, few output tiles): each
+  // block writes its partial tile to part[split][M][N] and a second pass adds the partials in split order (fixed
+  // order: reproducible) and applies scale / accumulate.  part holds splits*M*N floats.
+  int splits;
+  float* part;
 };
+
+// Number of pieces the weight-gradient GEMM G[M,N] = sum over K tokens would like the token axis cut into (1: none).
+int gemm_grad_splits(int M, int N, int K);
 
 template <typename T> int launch_gemm_simple(const GemmArgs<T>& a, hipStream_t s);
 int launch_gemm_mfma(const GemmArgs<bf16>& a, hipStream_t s);  // bf16 operands, MFMA, fp32 accumulate
@@ -136,8 +144,9 @@ size_t colsum_partial_bytes(int rows, int N);
 // dst[i] = bf16(src[i]), i in [0, n)
 int launch_cast_bf16(bf16* dst, const float* src, int64_t n, hipStream_t s);
 
-// out[c][r] = in[r][c] for a row-major bf16 matrix [rows, cols]; rows and cols multiples of 8
-int launch_transpose_bf16(const bf16* in, bf16* out, int rows, int cols, hipStream_t s);
+// out[c][r] = in[r][c] for a row-major bf16 matrix [rows, cols]; out has row pitch out_pitch (0: rows) and its
+// columns [rows, out_pitch) are zero-filled; cols and the pitch are multiples of 8
+int launch_transpose_bf16(const bf16* in, bf16* out, int rows, int cols, hipStream_t s, int out_pitch = 0);
 
 // ---------------------------------------------------------------------------------------
 // Attention on the packed projection qkv [m*S, 3H] (Q | K | V column blocks, head a in

@@ -5,6 +5,7 @@
 #include "kernels.h"
 #include <initializer_list>
 #include <type_traits>
+#include <algorithm>
 
 #define TRY(expr) do { int rc__ = (expr); if (rc__ != CEPHALO_OK) return rc__; } while (0)
 
@@ -71,7 +72,7 @@ struct SaveLayout {
 // Backward work area.  dz, dx1 and dqkv (the dY operands of the weight gradients) and the copy of dy in the
 // activation type are kept for `span` samples; the rest is per micro-batch of m samples.
 struct ScratchLayout {
-  size_t dz, dx1, dx1l, dyl, dqkv, du2, dO, du, dvec, tpose, ln_part, col_part, col_part_bytes, total;
+  size_t dz, dx1, dx1l, dyl, dqkv, du2, dO, du, dvec, tpose, wT, wg_part, ln_part, col_part, col_part_bytes, total;
   size_t ln_rows;   // rows of each of the four LayerNorm partial arrays (ln2.gamma, ln2.beta, ln1.gamma, ln1.beta)
 };
 
@@ -111,6 +112,17 @@ ScratchLayout scratch_layout(const cephalo_layer_desc& d, int m, int span) {
   L.du = take(Tm * H * 4);
   L.dvec = take((size_t)m * d.heads * d.seq * 4);
   L.tpose = take(Ts * H * es);     // [H, tokens] token-minor copy of one activation for the weight-gradient GEMMs
+  L.wT = es == 4 ? 0 : take((size_t)param_offsets(d).total * es);   // the four weight matrices transposed, at their flat-layout offsets
+  L.wg_part = p;                    // partial weight gradients of a split token axis (largest of the four projections)
+  if (es != 4) {
+    size_t need = 0;
+    const int dims[4][2] = {{(int)(3 * H), (int)H}, {(int)H, (int)H}, {(int)F, (int)H}, {(int)H, (int)F}};
+    for (auto& nk : dims) {
+      const int sp = gemm_grad_splits(nk[0], nk[1], (int)Ts);
+      if (sp > 1) need = std::max(need, (size_t)sp * nk[0] * nk[1] * sizeof(float));
+    }
+    take(need);
+  }
   L.ln_rows = (size_t)(span / m) * ln_bwd_blocks((int)Tm);
   L.ln_part = take(4 * L.ln_rows * H * sizeof(float));
   const int widest = (int)(3 * H > F ? 3 * H : F);
@@ -164,6 +176,15 @@ GemmArgs<T> linear_dgrad(const T* dY, const T* W, int Tn, int N, int K) {
   a.M = Tn; a.N = K; a.K = N;
   return a;
 }
+// the same with the transposed weight WT[K,N] at hand: both operands contiguous along the contracted axis
+template <typename T>
+GemmArgs<T> linear_dgrad_wt(const T* dY, const T* WT, int Tn, int N, int K) {
+  GemmArgs<T> a = {};
+  a.A = dY; a.a_rs = N; a.a_cs = 1;
+  a.B = WT; a.b_rs = N; a.b_cs = 1;
+  a.M = Tn; a.N = K; a.K = N;
+  return a;
+}
 // dW[N,K] = dY[T,N]^T X[T,K]: contraction over T; both operands strided along it
 template <typename T>
 GemmArgs<T> linear_wgrad(const T* dY, const T* X, int Tn, int N, int K, float* G, float scale, int accumulate) {
@@ -180,15 +201,15 @@ GemmArgs<T> linear_wgrad(const T* dY, const T* X, int Tn, int N, int K, float* G
 // its MFMA fragments then come from 16-byte LDS reads, which run at about three times the rate of the
 // transposing reads the other operand needs, for one extra pass over the small matrix.
 template <typename T>
-int wgrad(const T* dY, const T* X, int Tn, int N, int K, float* G, float scale, int acc, T* tbuf, hipStream_t s, int ldy = 0);
+int wgrad(const T* dY, const T* X, int Tn, int N, int K, float* G, float scale, int acc, T* tbuf, float* part, hipStream_t s, int ldy = 0);
 template <>
-int wgrad<float>(const float* dY, const float* X, int Tn, int N, int K, float* G, float scale, int acc, float*, hipStream_t s, int ldy) {
+int wgrad<float>(const float* dY, const float* X, int Tn, int N, int K, float* G, float scale, int acc, float*, float*, hipStream_t s, int ldy) {
   GemmArgs<float> a = linear_wgrad<float>(dY, X, Tn, N, K, G, scale, acc);
   if (ldy) a.a_cs = ldy;
   return gemm<float>(a, s);
 }
 template <>
-int wgrad<bf16>(const bf16* dY, const bf16* X, int Tn, int N, int K, float* G, float scale, int acc, bf16* tbuf, hipStream_t s, int ldy) {
+int wgrad<bf16>(const bf16* dY, const bf16* X, int Tn, int N, int K, float* G, float scale, int acc, bf16* tbuf, float* part, hipStream_t s, int ldy) {
   if (!ldy) ldy = N;
   // the GEMM addresses its operands through 32-bit buffer descriptors: contract over the tokens in pieces below 2 GiB
   const int64_t widest = ldy > K ? ldy : K;
@@ -198,6 +219,9 @@ int wgrad<bf16>(const bf16* dY, const bf16* X, int Tn, int N, int K, float* G, f
     const int tc = (int)(Tn - t0 < piece ? Tn - t0 : piece);
     GemmArgs<bf16> a = linear_wgrad<bf16>(dY + t0 * ldy, X + t0 * K, tc, N, K, G, scale, t0 > 0 ? 1 : acc);
     a.a_cs = ldy;
+    a.splits = part ? gemm_grad_splits(N, K, tc) : 1;     // `part` was sized with the same rule for the whole token axis
+    a.part = part;
+    if (tc != Tn) a.splits = 1;
     if (tc % 8 == 0) {
       if (N <= K && ldy == N) {   // dY^T [N, T] as the k-contiguous A operand
         TRY(launch_transpose_bf16(a.A, tbuf, tc, N, s));
@@ -233,10 +257,11 @@ Saved<T> saved_at(void* base, const SaveLayout& L, const cephalo_layer_desc& d, 
 template <typename T> struct Work {
   T *dz, *dx1l, *dyl, *dqkv;   // at the token offset of the current micro-batch (or of the span for the parameter pass)
   float *dx1;                  // likewise; dx1l is its copy in T (the same buffer in fp32 mode), dyl the caller's dy in T
-  T *dO, *tbuf;
+  T *dO, *tbuf, *wT;
   float *du2, *du, *dvec;
   float *ln2_g, *ln2_b, *ln1_g, *ln1_b;   // LayerNorm partial sums, at the row offset of the current micro-batch
   float *col_part; size_t col_part_bytes;
+  float *wg_part;
 };
 template <typename T>
 Work<T> work_at(void* base, const ScratchLayout& W, const cephalo_layer_desc& d, int sample0, int mb_index, int m) {
@@ -244,12 +269,13 @@ Work<T> work_at(void* base, const ScratchLayout& W, const cephalo_layer_desc& d,
   Work<T> w;
   w.dz = at<T>(base, W.dz) + t0 * F; w.dx1 = at<float>(base, W.dx1) + t0 * H; w.dx1l = at<T>(base, W.dx1l) + t0 * H;
   w.dyl = at<T>(base, W.dyl) + t0 * H; w.dqkv = at<T>(base, W.dqkv) + t0 * 3 * H;
-  w.du2 = at<float>(base, W.du2); w.dO = at<T>(base, W.dO); w.du = at<float>(base, W.du); w.tbuf = at<T>(base, W.tpose);
+  w.du2 = at<float>(base, W.du2); w.dO = at<T>(base, W.dO); w.du = at<float>(base, W.du); w.tbuf = at<T>(base, W.tpose); w.wT = at<T>(base, W.wT);
   w.dvec = at<float>(base, W.dvec);
   float* ln = at<float>(base, W.ln_part);
   const size_t r0 = (size_t)mb_index * ln_bwd_blocks(m * d.seq) * H, arr = W.ln_rows * H;
   w.ln2_g = ln + r0; w.ln2_b = ln + arr + r0; w.ln1_g = ln + 2 * arr + r0; w.ln1_b = ln + 3 * arr + r0;
   w.col_part = at<float>(base, W.col_part); w.col_part_bytes = W.col_part_bytes;
+  w.wg_part = at<float>(base, W.wg_part);
   return w;
 }
 
@@ -295,6 +321,29 @@ template <typename T> int make_lowp(T* dst, const float* src, int64_t n, hipStre
 template <> inline int make_lowp<float>(float*, const float*, int64_t, hipStream_t) { return CEPHALO_OK; }
 template <> inline int make_lowp<bf16>(bf16* dst, const float* src, int64_t n, hipStream_t s) { return launch_cast_bf16(dst, src, n, s); }
 
+// Input-gradient contraction dX = dY W of the linear layer whose weight sits at flat offset `off`.  In bf16 mode it
+// reads the transposed copy made by prepare_dgrad_weights (so both MFMA operands come from 16-byte LDS reads, the
+// same kernel as the forward); the fp32 path reads W in place.
+template <typename T> GemmArgs<T> dgrad_args(const T* dY, const T* P, const T* wT, int64_t off, int Tn, int N, int K);
+template <> inline GemmArgs<float> dgrad_args<float>(const float* dY, const float* P, const float*, int64_t off, int Tn, int N, int K) {
+  return linear_dgrad<float>(dY, P + off, Tn, N, K);
+}
+template <> inline GemmArgs<bf16> dgrad_args<bf16>(const bf16* dY, const bf16*, const bf16* wT, int64_t off, int Tn, int N, int K) {
+  return linear_dgrad_wt<bf16>(dY, wT + off, Tn, N, K);
+}
+// Once per layer and step (the weights do not change between micro-batches): W^T of the four projections.
+template <typename T> int prepare_dgrad_weights(const cephalo_layer_desc& d, const T* P, T* wT, hipStream_t s);
+template <> inline int prepare_dgrad_weights<float>(const cephalo_layer_desc&, const float*, float*, hipStream_t) { return CEPHALO_OK; }
+template <> inline int prepare_dgrad_weights<bf16>(const cephalo_layer_desc& d, const bf16* P, bf16* wT, hipStream_t s) {
+  const ParamOffsets o = param_offsets(d);
+  const int H = d.hidden, F = d.mlp;
+  TRY(launch_transpose_bf16(P + o.w_qkv, wT + o.w_qkv, 3 * H, H, s));
+  TRY(launch_transpose_bf16(P + o.w_o, wT + o.w_o, H, H, s));
+  TRY(launch_transpose_bf16(P + o.w_fc1, wT + o.w_fc1, F, H, s));
+  TRY(launch_transpose_bf16(P + o.w_fc2, wT + o.w_fc2, H, F, s));
+  return CEPHALO_OK;
+}
+
 // ---- backward, data path of one micro-batch: dx and the dY operands (dz, dx1, dqkv) of the weight gradients --------
 // dyl is dy in the activation type (same rows); dxl, if not null, receives dx in the activation type as well.
 template <typename T>
@@ -303,25 +352,25 @@ int layer_bwd_data_t(const cephalo_layer_desc& d, const T* P, const float* x, co
   const ParamOffsets o = param_offsets(d);
   const int Tn = m * d.seq, H = d.hidden, F = d.mlp;
   {
-    GemmArgs<T> a = linear_dgrad<T>(dyl, P + o.w_fc2, Tn, H, F);   // dh = dy W2, then dz = dh * gelu'(z)
+    GemmArgs<T> a = dgrad_args<T>(dyl, P, w.wT, o.w_fc2, Tn, H, F);   // dh = dy W2, then dz = dh * gelu'(z)
     a.epi = EPI_DGELU; a.Z = sv.z; a.C = w.dz;
     TRY(gemm<T>(a, s));
   }
   {
-    GemmArgs<T> a = linear_dgrad<T>(w.dz, P + o.w_fc1, Tn, F, H);
+    GemmArgs<T> a = dgrad_args<T>(w.dz, P, w.wT, o.w_fc1, Tn, F, H);
     a.epi = EPI_NONE; a.Cf = w.du2;
     TRY(gemm<T>(a, s));
   }
   // u2 = LN2(x1); dx1 = dy + LN2-backward(du2)
   TRY(launch_ln_bwd<T>(w.du2, sv.x1, sv.mean2, sv.rstd2, P + o.ln2_g, dy, w.dx1, lowp_out<T>(w.dx1l), w.ln2_g, w.ln2_b, Tn, H, s));
   {
-    GemmArgs<T> a = linear_dgrad<T>(lowp_of<T>(w.dx1, w.dx1l), P + o.w_o, Tn, H, H);
+    GemmArgs<T> a = dgrad_args<T>(lowp_of<T>(w.dx1, w.dx1l), P, w.wT, o.w_o, Tn, H, H);
     a.epi = EPI_NONE; a.C = w.dO;
     TRY(gemm<T>(a, s));
   }
   TRY(attn_bwd<T>(sv.qkv, sv.O, w.dO, sv.lse, w.dvec, w.dqkv, m, d.seq, H, d.heads, d.causal, s));
   {
-    GemmArgs<T> a = linear_dgrad<T>(w.dqkv, P + o.w_qkv, Tn, 3 * H, H);
+    GemmArgs<T> a = dgrad_args<T>(w.dqkv, P, w.wT, o.w_qkv, Tn, 3 * H, H);
     a.epi = EPI_NONE; a.Cf = w.du;
     TRY(gemm<T>(a, s));
   }
@@ -340,15 +389,15 @@ int layer_bwd_params_t(const cephalo_layer_desc& d, const float* dy, const T* dy
   const ParamOffsets o = param_offsets(d);
   const int H = d.hidden, F = d.mlp;
   TRY(launch_colsum<float>(dy, w.col_part, w.col_part_bytes, G + o.b_fc2, scale, acc, tokens, H, s));
-  TRY(wgrad<T>(dyl, sv.h, tokens, H, F, G + o.w_fc2, scale, acc, w.tbuf, s));
+  TRY(wgrad<T>(dyl, sv.h, tokens, H, F, G + o.w_fc2, scale, acc, w.tbuf, w.wg_part, s));
   TRY(launch_colsum<T>(w.dz, w.col_part, w.col_part_bytes, G + o.b_fc1, scale, acc, tokens, F, s));
-  TRY(wgrad<T>(w.dz, sv.u2, tokens, F, H, G + o.w_fc1, scale, acc, w.tbuf, s));
+  TRY(wgrad<T>(w.dz, sv.u2, tokens, F, H, G + o.w_fc1, scale, acc, w.tbuf, w.wg_part, s));
   TRY(launch_reduce_partials(w.ln2_g, ln_chunks, H, G + o.ln2_g, scale, acc, s));
   TRY(launch_reduce_partials(w.ln2_b, ln_chunks, H, G + o.ln2_b, scale, acc, s));
   TRY(launch_colsum<float>(w.dx1, w.col_part, w.col_part_bytes, G + o.b_o, scale, acc, tokens, H, s));
-  TRY(wgrad<T>(lowp_of<T>(w.dx1, w.dx1l), sv.O, tokens, H, H, G + o.w_o, scale, acc, w.tbuf, s));
+  TRY(wgrad<T>(lowp_of<T>(w.dx1, w.dx1l), sv.O, tokens, H, H, G + o.w_o, scale, acc, w.tbuf, w.wg_part, s));
   TRY(launch_colsum<T>(w.dqkv, w.col_part, w.col_part_bytes, G + o.b_qkv, scale, acc, tokens, 3 * H, s));
-  TRY(wgrad<T>(w.dqkv, sv.u, tokens, 3 * H, H, G + o.w_qkv, scale, acc, w.tbuf, s));
+  TRY(wgrad<T>(w.dqkv, sv.u, tokens, 3 * H, H, G + o.w_qkv, scale, acc, w.tbuf, w.wg_part, s));
   TRY(launch_reduce_partials(w.ln1_g, ln_chunks, H, G + o.ln1_g, scale, acc, s));
   TRY(launch_reduce_partials(w.ln1_b, ln_chunks, H, G + o.ln1_b, scale, acc, s));
   return CEPHALO_OK;
@@ -370,6 +419,7 @@ int run_bwd(const cephalo_layer_desc& d, const void* P, const float* x, const fl
   const int64_t act = (int64_t)m * d.seq * d.hidden;
   TRY(make_lowp<T>(w.dyl, dy, act, s));
   const T* dyl = lowp_of<T>(dy, w.dyl);
+  TRY(prepare_dgrad_weights<T>(d, static_cast<const T*>(P), w.wT, s));
   TRY(layer_bwd_data_t<T>(d, static_cast<const T*>(P), x, dy, dyl, dx, (T*)nullptr, m, sv, w, s));
   return layer_bwd_params_t<T>(d, dy, dyl, m * d.seq, ln_bwd_blocks(m * d.seq), sv, w, G, scale, acc, s);
 }
@@ -389,6 +439,7 @@ int run_share(const cephalo_layer_desc& d, const void* Pv, const float* x, float
   const Work<T> w0 = work_at<T>(scratch, W, d, 0, 0, m);
   TRY(make_lowp<T>(w0.dyl, dy, (int64_t)l * act, s));
   const T* dyl = lowp_of<T>(dy, w0.dyl);
+  TRY(prepare_dgrad_weights<T>(d, P, w0.wT, s));
   for (int j = 0; j < l; ++j)
     TRY(layer_bwd_data_t<T>(d, P, x + j * act, dy + j * act, dyl + j * act, dx + j * act, (T*)nullptr, m,
                             saved_at<T>(save, L, d, j * m), work_at<T>(scratch, W, d, j * m, j, m), s));

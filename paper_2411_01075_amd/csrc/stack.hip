@@ -149,6 +149,25 @@ wpe_bwd_kernel(const float* __restrict__ dx0, float* __restrict__ g_wpe, int b, 
   for (int c = 0; c < VN; ++c) g_wpe[v * VN + c] = acc[c];
 }
 
+// Input gradient of the tied LM head, duf = dlogits wte.  bf16: through wte^T [H, ldv] (zero-padded columns), made once
+// per step, so that both operands are contiguous along the contracted vocabulary axis.
+template <typename T> GemmArgs<T> head_dgrad_args(const T* dlg, const T* wte, const T* wteT, int Tm, int V, int H, int ldv);
+template <> GemmArgs<float> head_dgrad_args<float>(const float* dlg, const float* wte, const float*, int Tm, int V, int H, int ldv) {
+  GemmArgs<float> a = linear_dgrad<float>(dlg, wte, Tm, V, H);
+  a.a_rs = ldv;
+  return a;
+}
+template <> GemmArgs<bf16> head_dgrad_args<bf16>(const bf16* dlg, const bf16*, const bf16* wteT, int Tm, int V, int H, int ldv) {
+  GemmArgs<bf16> a = linear_dgrad_wt<bf16>(dlg, wteT, Tm, V, H);
+  a.a_rs = ldv; a.b_rs = ldv;
+  return a;
+}
+template <typename T> int prepare_head_weights(const T* wte, T* wteT, int V, int H, int ldv, hipStream_t s);
+template <> int prepare_head_weights<float>(const float*, float*, int, int, int, hipStream_t) { return CEPHALO_OK; }
+template <> int prepare_head_weights<bf16>(const bf16* wte, bf16* wteT, int V, int H, int ldv, hipStream_t s) {
+  return launch_transpose_bf16(wte, wteT, V, H, s, ldv);
+}
+
 int check_stack(const cephalo_stack_desc* d) {
   if (!d) return fail(CEPHALO_EINVAL, "stack desc is null");
   TRY(check_desc(&d->layer));
@@ -166,7 +185,7 @@ size_t sort_temp_bytes(int n) {
 }
 
 struct StackLayout {
-  size_t xs, saves, save_each, scratch, dxa, dxb, dxal, dxbl, uf, meanf, rstdf, duf, logits, dlogits, loss, lnf_part, keys, sort_tmp, sort_tmp_bytes, total;
+  size_t xs, saves, save_each, scratch, dxa, dxb, dxal, dxbl, uf, meanf, rstdf, duf, logits, dlogits, wteT, loss, lnf_part, keys, sort_tmp, sort_tmp_bytes, total;
   int ldv;            // padded pitch of the logits
   size_t lnf_rows;
 };
@@ -189,6 +208,7 @@ StackLayout stack_layout(const cephalo_stack_desc& d, int b, int m) {
   L.duf = take(Tm * H * 4);
   L.logits = take(Tm * (size_t)L.ldv * 4);        // one micro-batch of fp32 logits, reused
   L.dlogits = take(n * (size_t)L.ldv * es);       // their gradient for the whole share (an operand of the weight gradient)
+  L.wteT = es == 4 ? 0 : take(H * (size_t)L.ldv * es);   // wte^T [H, ldv] for the input gradient of the LM head
   L.loss = take(n * 4);
   L.lnf_rows = (size_t)(b / m) * ln_bwd_blocks((int)Tm);
   L.lnf_part = take(2 * L.lnf_rows * H * 4);
@@ -231,6 +251,7 @@ int run_stack(const cephalo_stack_desc& d, const void* Pv, const int* ids, const
   T* dxl_cur = at<T>(ws, L.dxal); T* dxl_nxt = at<T>(ws, L.dxbl);
   const float coef = scale / (float)n;
   const int nb = ln_bwd_blocks(Tm);
+  TRY(prepare_head_weights<T>(P + o_wte, at<T>(ws, L.wteT), V, H, L.ldv, s));
   for (int j = 0; j < l; ++j) {
     const size_t t0 = (size_t)j * Tm;
     TRY(launch_ln_fwd<T>(xs(NL) + t0 * H, P + o_lnf, P + o_lnf + H, uf + t0 * H, meanf + t0, rstdf + t0, Tm, H, ld.ln_eps, s));
@@ -243,8 +264,8 @@ int run_stack(const cephalo_stack_desc& d, const void* Pv, const int* ids, const
     cross_entropy_kernel<T><<<Tm, kThreads, 0, s>>>(logits, dlg, targets + t0, at<float>(ws, L.loss) + t0, V, L.ldv, coef);
     CEPHALO_CHECK_LAUNCH("cross_entropy");
     {
-      GemmArgs<T> a = linear_dgrad<T>(dlg, P + o_wte, Tm, V, H);   // duf = dlogits wte
-      a.a_rs = L.ldv; a.epi = EPI_NONE; a.Cf = duf;
+      GemmArgs<T> a = head_dgrad_args<T>(dlg, P + o_wte, at<T>(ws, L.wteT), Tm, V, H, L.ldv);   // duf = dlogits wte
+      a.epi = EPI_NONE; a.Cf = duf;
       TRY(gemm<T>(a, s));
     }
     TRY(launch_ln_bwd<T>(duf, xs(NL) + t0 * H, meanf + t0, rstdf + t0, P + o_lnf, (const float*)nullptr, dx_cur + t0 * H,
@@ -254,7 +275,7 @@ int run_stack(const cephalo_stack_desc& d, const void* Pv, const int* ids, const
   CEPHALO_CHECK_LAUNCH("mean_loss");
   {
     Work<T> w = work_at<T>(scratch, WL, ld, 0, 0, m);
-    TRY(wgrad<T>(dlogits, uf, n, V, H, G + o_wte, 1.0f, 0, w.tbuf, s, L.ldv));        // LM-head part of d wte, whole share
+    TRY(wgrad<T>(dlogits, uf, n, V, H, G + o_wte, 1.0f, 0, w.tbuf, (float*)nullptr, s, L.ldv));        // LM-head part of d wte, whole share
     TRY(launch_reduce_partials(lnf_g, l * nb, H, G + o_lnf, 1.0f, 0, s));
     TRY(launch_reduce_partials(lnf_b, l * nb, H, G + o_lnf + H, 1.0f, 0, s));
   }
@@ -262,6 +283,7 @@ int run_stack(const cephalo_stack_desc& d, const void* Pv, const int* ids, const
   for (int li = NL - 1; li >= 0; --li) {
     void* save = at<char>(ws, L.saves + (size_t)li * L.save_each);
     const T* Pl = P + o_layers + li * PL;
+    TRY(prepare_dgrad_weights<T>(ld, Pl, work_at<T>(scratch, WL, ld, 0, 0, m).wT, s));
     for (int j = 0; j < l; ++j)
       TRY(layer_bwd_data_t<T>(ld, Pl, xs(li) + j * act, dx_cur + j * act, lowp_of<T>(dx_cur, dxl_cur) + j * act, dx_nxt + j * act,
                               dxl_nxt + j * act, m, saved_at<T>(save, SL, ld, j * m), work_at<T>(scratch, WL, ld, j * m, j, m), s));
