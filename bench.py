@@ -163,9 +163,10 @@ def main():
             del ws                      # the legs allocate their own operands
             torch.cuda.empty_cache()
         bt = torch.bfloat16
-        # The GEMM instantiations of the step, each launched with the shapes and operand layouts the step uses.
-        # (kind, N_out, K_in, launches per step).  Forward and dgrad run per micro-batch on T tokens; the weight
-        # gradient runs once per linear over all b*S tokens with one operand copied token-minor beforehand.
+        # The GEMM kernels of the step, each launched through the C ABI with the shapes, operand layouts and epilogues
+        # the step uses.  Forward and input-gradient GEMMs run per micro-batch on T tokens (the input gradients read
+        # the per-layer transposed weights, so they are the same contraction as the forward); the weight gradient
+        # runs once per linear layer over all b*S tokens (token-minor copy of one operand + GEMM + split reduction).
         L = cfg.layers
         lin = [("qkv", 3 * H, H), ("o", H, H), ("fc1", F, H), ("fc2", H, F)]
         legs = {}
@@ -177,41 +178,50 @@ def main():
             g["flops"] += flops * count
             g["launches"] += count
 
+        def rnd(*shape, scale=1.0, dtype=bt):
+            return (torch.randn(*shape, device="cuda") * scale).to(dtype)
+
         for name, n_out, k_in in lin:
-            X = torch.randn(T, k_in, device="cuda").to(bt)
-            W = (torch.randn(n_out, k_in, device="cuda") * 0.02).to(bt)
-            dY = torch.randn(T, n_out, device="cuda").to(bt)
-            Yb = torch.empty(T, n_out, device="cuda", dtype=bt)
-            Yf = torch.empty(T, n_out, device="cuda")
-            Xf = torch.empty(T, k_in, device="cuda")
-            Xb = torch.empty(T, k_in, device="cuda", dtype=bt)
+            X, W, WT, dY = rnd(T, k_in), rnd(n_out, k_in, scale=0.02), rnd(k_in, n_out, scale=0.02), rnd(T, n_out)
             bias = torch.zeros(n_out, device="cuda", dtype=bt)
             fl = 2.0 * T * n_out * k_in
-            add_leg("gemm forward (A, B k-contiguous)", lambda: C.cephalo_op_gemm(C.BF16, X, k_in, 1, W, k_in, 1, T, n_out, k_in, C.EPI_BIAS, C=Yb, bias=bias), fl, L * l)
-            add_leg("gemm dgrad (B row-contiguous)", lambda: C.cephalo_op_gemm(C.BF16, dY, n_out, 1, W, 1, k_in, T, k_in, n_out, C.EPI_NONE, C=Xb), fl, L * l)
-            del Yb, Yf, Xf, Xb
+            fwd_args = (C.BF16, X, k_in, 1, W, k_in, 1, T, n_out, k_in)
+            if name == "qkv":
+                Y = torch.empty(T, n_out, device="cuda", dtype=bt)
+                add_leg("forward, bias epilogue (qkv)", lambda: C.cephalo_op_gemm(*fwd_args, C.EPI_BIAS, C=Y, bias=bias), fl, L * l)
+            elif name == "fc1":
+                Y, Z = torch.empty(T, n_out, device="cuda", dtype=bt), torch.empty(T, n_out, device="cuda", dtype=bt)
+                add_leg("forward, bias+GELU epilogue (fc1)", lambda: C.cephalo_op_gemm(*fwd_args, C.EPI_BIAS_GELU, C=Y, bias=bias, Z=Z), fl, L * l)
+            else:
+                R, Y = rnd(T, n_out, dtype=torch.float32), torch.empty(T, n_out, device="cuda")
+                add_leg("forward, bias+residual epilogue, fp32 stream (out-proj, fc2)",
+                        lambda: C.cephalo_op_gemm(*fwd_args, C.EPI_BIAS_RESID_F32, C=Y, bias=bias, R=R), fl, L * l)
+            # input gradient dX[T, k_in] = dY[T, n_out] W, through W^T [k_in, n_out]
+            dg_args = (C.BF16, dY, n_out, 1, WT, n_out, 1, T, k_in, n_out)
+            if name == "fc2":
+                Zs, dZ = rnd(T, k_in), torch.empty(T, k_in, device="cuda", dtype=bt)
+                add_leg("input gradient, GELU' epilogue (fc2)", lambda: C.cephalo_op_gemm(*dg_args, C.EPI_DGELU, C=dZ, Z=Zs), fl, L * l)
+            elif name == "o":
+                dX = torch.empty(T, k_in, device="cuda", dtype=bt)
+                add_leg("input gradient, plain epilogue (qkv, out-proj, fc1)", lambda: C.cephalo_op_gemm(*dg_args, C.EPI_NONE, C=dX), fl, L * l)
+            else:
+                dX = torch.empty(T, k_in, device="cuda")
+                add_leg("input gradient, plain epilogue (qkv, out-proj, fc1)", lambda: C.cephalo_op_gemm(*dg_args, C.EPI_NONE_F32, C=dX), fl, L * l)
+            del X, W, WT, dY
             # weight gradient over the whole share
-            Xs = torch.randn(n_tok, k_in, device="cuda").to(bt)
-            dYs = torch.randn(n_tok, n_out, device="cuda").to(bt)
+            Xs, dYs = rnd(n_tok, k_in), rnd(n_tok, n_out)
             Gw = torch.zeros(n_out, k_in, device="cuda")
-            flw = 2.0 * n_tok * n_out * k_in
-            if n_out <= k_in:       # dY^T [N, tokens] as the k-contiguous A operand
-                dYt = dYs.t().contiguous()
-                add_leg("gemm wgrad (A k-contiguous, B row-contiguous, fp32 gradient epilogue)",
-                        lambda: C.cephalo_op_gemm(C.BF16, dYt, n_tok, 1, Xs, 1, k_in, n_out, k_in, n_tok, C.EPI_GRAD, G=Gw, scale=1.0, accumulate=0), flw, L)
-                del dYt
-            else:                   # X^T [K, tokens] as the k-contiguous B operand
-                Xt = Xs.t().contiguous()
-                add_leg("gemm wgrad (A row-contiguous, B k-contiguous, fp32 gradient epilogue)",
-                        lambda: C.cephalo_op_gemm(C.BF16, dYs, 1, n_out, Xt, n_tok, 1, n_out, k_in, n_tok, C.EPI_GRAD, G=Gw, scale=1.0, accumulate=0), flw, L)
-                del Xt
-            del Xs, dYs, Gw, X, W, dY
+            wsb = torch.empty(C.cephalo_op_linear_wgrad_workspace(C.BF16, n_tok, n_out, k_in), dtype=torch.uint8, device="cuda")
+            add_leg("weight gradient over the share (transpose + GEMM + split reduction)",
+                    lambda: C.cephalo_op_linear_wgrad(C.BF16, dYs, Xs, n_tok, n_out, k_in, Gw, 1.0, 0, wsb), 2.0 * n_tok * n_out * k_in, L)
+            del Xs, dYs, Gw, wsb
         for g in legs.values():
             g["TFLOP/s"] = round(g["flops"] / g["sec"] / 1e12, 1)
             g["avg_launch_us"] = round(1e6 * g["sec"] / g["launches"], 1)
             g["ms_per_step"] = round(1e3 * g.pop("sec"), 3)
             g["flops_per_launch"] = g.pop("flops") / g["launches"]
-        key = max(legs, key=lambda k: legs[k]["ms_per_step"])
+        single = [k for k in legs if not k.startswith("weight gradient")]      # one kernel launch per call: events bracket that kernel alone
+        key = max(single, key=lambda k: legs[k]["ms_per_step"])
         d = legs[key]
         roofline = {"kernel": "gemm_mfma_kernel, " + key, "bound": "mfma", "achieved": d["TFLOP/s"], "peak": PEAK_BF16_TFLOPS,
                     "unit": "TFLOP/s", "frac": round(d["TFLOP/s"] / PEAK_BF16_TFLOPS, 4), "traffic": None,

@@ -167,6 +167,8 @@ int cephalo_cast_bf16(void* dst_bf16, const float* src, int64_t n, void* stream)
 #define CEPHALO_EPI_BIAS_GELU   3  /* Z = acc + bias[n]; C = gelu(Z); both stored          */
 #define CEPHALO_EPI_DGELU       4  /* C = acc * gelu'(Z[m,n])                              */
 #define CEPHALO_EPI_GRAD        5  /* G = (accumulate ? G : 0) + scale * acc   (G fp32)    */
+#define CEPHALO_EPI_NONE_F32    6  /* as NONE, C is fp32 [M,N] whatever dtype says          */
+#define CEPHALO_EPI_BIAS_RESID_F32 7 /* as BIAS_RESID, R and C are fp32 [M,N] (the residual stream) */
 
 /* C[M,N] = sum_k A(m,k) * B(n,k) with a fused epilogue; the contraction of a linear layer's
  * forward (both operands k-contiguous), input gradient (B n-contiguous) and weight gradient
@@ -179,6 +181,15 @@ int cephalo_op_gemm(int32_t dtype, const void* A, int64_t a_rs, int64_t a_cs,
                     const void* B, int64_t b_rs, int64_t b_cs, int32_t M, int32_t N, int32_t K,
                     int32_t epilogue, void* C, const void* bias, const void* R, void* Z,
                     float* G, float scale, int32_t accumulate, void* stream);
+
+/* Weight gradient of a linear layer y = x W^T over T tokens, as the layer's backward computes it:
+ *   G[N,K] <- (accumulate ? G : 0) + scale * sum_t dY[t,n] X[t,k]        (dY [T,N], X [T,K] row-major in dtype, G fp32)
+ * In bf16 mode the narrower operand is first copied token-minor and, when the output has few tiles, the token axis is
+ * cut into pieces whose partial sums are added in a fixed order (reproducible).  workspace: device, at least
+ * cephalo_op_linear_wgrad_workspace(dtype, T, N, K) bytes. */
+size_t cephalo_op_linear_wgrad_workspace(int32_t dtype, int32_t T, int32_t N, int32_t K);
+int cephalo_op_linear_wgrad(int32_t dtype, const void* dY, const void* X, int32_t T, int32_t N, int32_t K,
+                            float* G, float scale, int32_t accumulate, void* workspace, size_t workspace_bytes, void* stream);
 
 /* Attention of one micro-batch on the packed projection qkv [m*S, 3H] (column blocks Q | K | V).
  * Forward writes O [m*S, H] (dtype) and lse [m, A, S] fp32, the log-sum-exp of each query row's

@@ -65,6 +65,8 @@ SIGNATURES = {
     "cephalo_stack_step": (ctypes.c_int, [ctypes.POINTER(StackDesc), _vp, _vp, _vp, _i32, _i32, _vp, _f32, _vp, _vp, _sz, _vp]),
     "cephalo_op_gemm": (ctypes.c_int, [_i32, _vp, _i64, _i64, _vp, _i64, _i64, _i32, _i32, _i32, _i32, _vp, _vp, _vp, _vp,
                                        _vp, _f32, _i32, _vp]),
+    "cephalo_op_linear_wgrad_workspace": (_sz, [_i32, _i32, _i32, _i32]),
+    "cephalo_op_linear_wgrad": (ctypes.c_int, [_i32, _vp, _vp, _i32, _i32, _i32, _vp, _f32, _i32, _vp, _sz, _vp]),
     "cephalo_op_attention_fwd": (ctypes.c_int, [_dp, _vp, _vp, _vp, _i32, _vp]),
     "cephalo_op_attention_bwd": (ctypes.c_int, [_dp, _vp, _vp, _vp, _vp, _vp, _vp, _i32, _vp]),
 }
@@ -174,13 +176,22 @@ def cephalo_cast_bf16(dst, src, n=None, stream=None):
     _check(lib().cephalo_cast_bf16(_ptr(dst), _ptr(src), n, _stream(stream)))
 
 
-EPI_NONE, EPI_BIAS, EPI_BIAS_RESID, EPI_BIAS_GELU, EPI_DGELU, EPI_GRAD = range(6)
+EPI_NONE, EPI_BIAS, EPI_BIAS_RESID, EPI_BIAS_GELU, EPI_DGELU, EPI_GRAD, EPI_NONE_F32, EPI_BIAS_RESID_F32 = range(8)
 
 
 def cephalo_op_gemm(dtype, A, a_rs, a_cs, B, b_rs, b_cs, M, N, K, epilogue, C=None, bias=None, R=None, Z=None,
                     G=None, scale=1.0, accumulate=0, stream=None):
     _check(lib().cephalo_op_gemm(dtype, _ptr(A), a_rs, a_cs, _ptr(B), b_rs, b_cs, M, N, K, epilogue,
                                  _ptr(C), _ptr(bias), _ptr(R), _ptr(Z), _ptr(G), scale, int(accumulate), _stream(stream)))
+
+
+def cephalo_op_linear_wgrad_workspace(dtype, T, N, K):
+    return int(lib().cephalo_op_linear_wgrad_workspace(dtype, T, N, K))
+
+
+def cephalo_op_linear_wgrad(dtype, dY, X, T, N, K, G, scale, accumulate, workspace, stream=None):
+    _check(lib().cephalo_op_linear_wgrad(dtype, _ptr(dY), _ptr(X), T, N, K, _ptr(G), scale, int(accumulate), _ptr(workspace),
+                                         0 if workspace is None else workspace.numel() * workspace.element_size(), _stream(stream)))
 
 
 def cephalo_op_attention_fwd(desc, qkv, O, lse, micro_batch, stream=None):

@@ -222,7 +222,7 @@ int wgrad<bf16>(const bf16* dY, const bf16* X, int Tn, int N, int K, float* G, f
     a.splits = part ? gemm_grad_splits(N, K, tc) : 1;     // `part` was sized with the same rule for the whole token axis
     a.part = part;
     if (tc != Tn) a.splits = 1;
-    if (tc % 8 == 0) {
+    if (tc % 8 == 0 && K % 8 == 0 && (N % 8 == 0 || N > K || ldy != N)) {
       if (N <= K && ldy == N) {   // dY^T [N, T] as the k-contiguous A operand
         TRY(launch_transpose_bf16(a.A, tbuf, tc, N, s));
         a.A = tbuf; a.a_rs = tc; a.a_cs = 1;

@@ -1,5 +1,5 @@
 // C-ABI entry points of the individual building blocks (GEMM family, attention).
-#include "kernels.h"
+#include "layer_impl.h"
 
 using namespace cephalo;
 
@@ -39,6 +39,9 @@ extern "C" int cephalo_op_gemm(int32_t dtype, const void* A, int64_t a_rs, int64
   if ((a_rs != 1 && a_cs != 1) || (b_rs != 1 && b_cs != 1)) return fail(CEPHALO_EINVAL, "op_gemm: one stride of each operand must be 1");
   if (a_rs <= 0 || a_cs <= 0 || b_rs <= 0 || b_cs <= 0) return fail(CEPHALO_EINVAL, "op_gemm: strides must be positive");
   bool need_c = epilogue != EPI_GRAD, need_bias = false, need_r = false, need_z = false;
+  const bool f32_out = epilogue == CEPHALO_EPI_NONE_F32 || epilogue == CEPHALO_EPI_BIAS_RESID_F32;
+  if (epilogue == CEPHALO_EPI_NONE_F32) epilogue = EPI_NONE;
+  if (epilogue == CEPHALO_EPI_BIAS_RESID_F32) epilogue = EPI_BIAS_RESID;
   switch (epilogue) {
     case EPI_NONE: break;
     case EPI_BIAS: need_bias = true; break;
@@ -54,14 +57,47 @@ extern "C" int cephalo_op_gemm(int32_t dtype, const void* A, int64_t a_rs, int64
   if (dtype == CEPHALO_F32) {
     GemmArgs<float> a = {};
     op_gemm_t<float>(A, a_rs, a_cs, B, b_rs, b_cs, M, N, K, epilogue, C, bias, R, Z, G, scale, accumulate, &a);
-    return launch_gemm_simple<float>(a, s);
+    return launch_gemm_simple<float>(a, s);     // fp32 mode: C and R are fp32 anyway
   }
   if (dtype == CEPHALO_BF16) {
     GemmArgs<bf16> a = {};
     op_gemm_t<bf16>(A, a_rs, a_cs, B, b_rs, b_cs, M, N, K, epilogue, C, bias, R, Z, G, scale, accumulate, &a);
+    if (f32_out) { a.Cf = static_cast<float*>(C); a.Rf = static_cast<const float*>(R); a.C = nullptr; a.R = nullptr; }
     return launch_gemm_mfma(a, s);
   }
   return fail(CEPHALO_EINVAL, "op_gemm: unknown dtype %d", dtype);
+}
+
+namespace {
+// workspace of linear_wgrad: [token-minor copy of the narrow operand | partial sums of a split token axis]
+size_t wgrad_tbuf_bytes(int dtype, int T, int N, int K) { return dtype == CEPHALO_BF16 ? align_up((size_t)T * (N < K ? N : K) * 2) : 0; }
+size_t wgrad_part_bytes(int dtype, int T, int N, int K) {
+  if (dtype != CEPHALO_BF16) return 0;
+  const int sp = gemm_grad_splits(N, K, T);
+  return sp > 1 ? (size_t)sp * N * K * sizeof(float) : 0;
+}
+}  // namespace
+
+extern "C" size_t cephalo_op_linear_wgrad_workspace(int32_t dtype, int32_t T, int32_t N, int32_t K) {
+  if (T <= 0 || N <= 0 || K <= 0) return 0;
+  return wgrad_tbuf_bytes(dtype, T, N, K) + wgrad_part_bytes(dtype, T, N, K) + 256;
+}
+
+extern "C" int cephalo_op_linear_wgrad(int32_t dtype, const void* dY, const void* X, int32_t T, int32_t N, int32_t K,
+                                       float* G, float scale, int32_t accumulate, void* workspace, size_t workspace_bytes, void* stream) {
+  if (T <= 0 || N <= 0 || K <= 0) return fail(CEPHALO_EINVAL, "linear_wgrad: sizes %d x %d x %d must be positive", T, N, K);
+  if (!dY || !X || !G) return fail(CEPHALO_EINVAL, "linear_wgrad: null buffer");
+  if (accumulate != 0 && accumulate != 1) return fail(CEPHALO_EINVAL, "linear_wgrad: accumulate must be 0 or 1");
+  if (dtype != CEPHALO_F32 && dtype != CEPHALO_BF16) return fail(CEPHALO_EINVAL, "linear_wgrad: unknown dtype %d", dtype);
+  if (workspace_bytes < cephalo_op_linear_wgrad_workspace(dtype, T, N, K) || (dtype == CEPHALO_BF16 && !workspace))
+    return fail(CEPHALO_EWORKSPACE, "linear_wgrad: workspace %zu B < %zu B", workspace_bytes, cephalo_op_linear_wgrad_workspace(dtype, T, N, K));
+  hipStream_t s = static_cast<hipStream_t>(stream);
+  if (dtype == CEPHALO_F32)
+    return wgrad<float>(static_cast<const float*>(dY), static_cast<const float*>(X), T, N, K, G, scale, accumulate, nullptr, nullptr, s);
+  char* ws = static_cast<char*>(workspace);
+  float* part = wgrad_part_bytes(dtype, T, N, K) ? reinterpret_cast<float*>(ws + wgrad_tbuf_bytes(dtype, T, N, K)) : nullptr;
+  return wgrad<bf16>(static_cast<const bf16*>(dY), static_cast<const bf16*>(X), T, N, K, G, scale, accumulate,
+                     reinterpret_cast<bf16*>(ws), part, s);
 }
 
 extern "C" int cephalo_op_attention_fwd(const cephalo_layer_desc* d, const void* qkv, void* O, float* lse,
