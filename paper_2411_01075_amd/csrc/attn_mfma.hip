@@ -120,14 +120,20 @@ attn_fwd_kernel(const bf16* __restrict__ qkv, bf16* __restrict__ O, float* __res
   auto Ks = [&](int st) { return smem + st * 2 * TL::ELEMS; };
   auto Vs = [&](int st) { return smem + st * 2 * TL::ELEMS + TL::ELEMS; };
 
-  const int qt = gridDim.x - 1 - blockIdx.x;       // heavy (late) causal tiles first
   const int a = blockIdx.y, n = blockIdx.z;
   const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63, h = lane >> 5;
   const int64_t ld = 3 * (int64_t)H;
   const bf16* base = qkv + (int64_t)n * S * ld + a * D;
+  const float c2 = scale * kLog2e;
+  // Under a causal mask the work of a query tile grows with its index, and a launch has about as many blocks as the
+  // chip has slots, so nothing would even the load out: each block takes tile x and then tile ntq-1-x, whose key
+  // ranges add up to the same length for every x.
+  const int ntq = (S + 127) / 128;
+  for (int pass = 0; pass < (CAUSAL ? 2 : 1); ++pass) {
+  const int qt = pass == 0 ? (int)blockIdx.x : ntq - 1 - (int)blockIdx.x;
+  if (pass == 1 && qt == (int)blockIdx.x) break;   // odd tile count: the middle tile is its own partner
   const int q0 = qt * 128 + wave * 32;             // this wavefront's 32 query rows
   const int q = q0 + (lane & 31);
-  const float c2 = scale * kLog2e;
 
   bf16x8 qf[D / 16];
   load_row_frags<D>(base, ld, q0, S, qf);
@@ -164,36 +170,46 @@ attn_fwd_kernel(const bf16* __restrict__ qkv, bf16* __restrict__ O, float* __res
         for (int kk = 0; kk < D / 16; ++kk)
           s[tb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(TL::frag_rows(Ks(cur), tb * 32, kk * 16), qf[kk], s[tb], 0, 0, 0);
       }
+      // Only tiles that touch the diagonal or the ragged end need per-element masking (wave-uniform test).
+      if ((CAUSAL && t0 + TILE - 1 > q0) || t0 + TILE > S) {
+#pragma unroll
+        for (int tb = 0; tb < 2; ++tb)
+#pragma unroll
+          for (int e = 0; e < 16; ++e) {
+            const int t = t0 + tb * 32 + 8 * (e >> 2) + 4 * h + (e & 3);
+            if (t >= S || (CAUSAL && t > q)) s[tb][e] = -INFINITY;
+          }
+      }
       float mx = -INFINITY;
 #pragma unroll
       for (int tb = 0; tb < 2; ++tb)
 #pragma unroll
-        for (int e = 0; e < 16; ++e) {
-          const int t = t0 + tb * 32 + 8 * (e >> 2) + 4 * h + (e & 3);
-          float v = s[tb][e] * c2;
-          if (t >= S || (CAUSAL && t > q)) v = -INFINITY;
-          s[tb][e] = v;
-          mx = fmaxf(mx, v);
-        }
-      mx = fmaxf(mx, __shfl_xor(mx, 32, 64));
-      const float m_new = fmaxf(m_run, mx);
-      const float m_use = (m_new == -INFINITY) ? 0.f : m_new;
-      const float alpha = __builtin_amdgcn_exp2f(m_run - m_use);
+        for (int e = 0; e < 16; ++e) mx = fmaxf(mx, s[tb][e]);
+      mx = fmaxf(mx, __shfl_xor(mx, 32, 64)) * c2;          // scores enter the exponent as s*c2 (c2 > 0)
+      // Running maximum, in the log2 domain.  It is only raised when some row of the wavefront would otherwise see
+      // an exponent above 8 (probabilities up to 2^8 are harmless in fp32 / bf16 and cancel in the final division);
+      // raising it costs a pass over the output accumulators, and after the first tiles it is rarely needed.
+      if (__any(mx > m_run + 8.0f)) {
+        const float m_new = fmaxf(m_run, mx);
+        const float alpha = (m_new == -INFINITY) ? 1.0f : __builtin_amdgcn_exp2f(m_run - m_new);
+        l_run *= alpha;
+        m_run = m_new;
+#pragma unroll
+        for (int dt = 0; dt < D / 32; ++dt)
+#pragma unroll
+          for (int e = 0; e < 16; ++e) o[dt][e] *= alpha;
+      }
+      const float neg_m = (m_run == -INFINITY) ? 0.f : -m_run;
       float psum = 0.f;
 #pragma unroll
       for (int tb = 0; tb < 2; ++tb)
 #pragma unroll
         for (int e = 0; e < 16; ++e) {
-          const float p = __builtin_amdgcn_exp2f(s[tb][e] - m_use);
+          const float p = __builtin_amdgcn_exp2f(__builtin_fmaf(s[tb][e], c2, neg_m));
           s[tb][e] = p;
           psum += p;
         }
-      l_run = l_run * alpha + psum;
-      m_run = m_new;
-#pragma unroll
-      for (int dt = 0; dt < D / 32; ++dt)
-#pragma unroll
-        for (int e = 0; e < 16; ++e) o[dt][e] *= alpha;
+      l_run += psum;
 #pragma unroll
       for (int tb = 0; tb < 2; ++tb)
 #pragma unroll
@@ -214,6 +230,7 @@ attn_fwd_kernel(const bf16* __restrict__ qkv, bf16* __restrict__ O, float* __res
   const float inv = 1.0f / l_tot;
   store_transposed<D>(o, O + (int64_t)n * S * H + a * D, H, q, S, inv);
   if (h == 0 && q < S) lse[((int64_t)n * A + a) * S + q] = (m_run + __builtin_amdgcn_logf(l_tot)) * kLn2;
+  }   // pass
 }
 
 // ------------------------------------------------------------------------------------ rowsum(dO * O)
@@ -249,14 +266,17 @@ attn_dq_kernel(const bf16* __restrict__ qkv, const bf16* __restrict__ dO, const 
   auto Ks = [&](int st) { return smem + st * 2 * TL::ELEMS; };
   auto Vs = [&](int st) { return smem + st * 2 * TL::ELEMS + TL::ELEMS; };
 
-  const int qt = gridDim.x - 1 - blockIdx.x;
   const int a = blockIdx.y, n = blockIdx.z;
   const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63, h = lane >> 5;
   const int64_t ld = 3 * (int64_t)H;
   const bf16* base = qkv + (int64_t)n * S * ld + a * D;
+  const float c2 = scale * kLog2e;
+  const int ntq = (S + 127) / 128;                 // causal: query tiles x and ntq-1-x in turn (equal work per block)
+  for (int pass = 0; pass < (CAUSAL ? 2 : 1); ++pass) {
+  const int qt = pass == 0 ? (int)blockIdx.x : ntq - 1 - (int)blockIdx.x;
+  if (pass == 1 && qt == (int)blockIdx.x) break;
   const int q0 = qt * 128 + wave * 32;
   const int q = q0 + (lane & 31);
-  const float c2 = scale * kLog2e;
 
   bf16x8 qf[D / 16], dof[D / 16];
   load_row_frags<D>(base, ld, q0, S, qf);
@@ -297,12 +317,18 @@ attn_dq_kernel(const bf16* __restrict__ qkv, const bf16* __restrict__ dO, const 
           s = __builtin_amdgcn_mfma_f32_32x32x16_bf16(TL::frag_rows(Ks(cur), tb * 32, kk * 16), qf[kk], s, 0, 0, 0);
           dp = __builtin_amdgcn_mfma_f32_32x32x16_bf16(TL::frag_rows(Vs(cur), tb * 32, kk * 16), dof[kk], dp, 0, 0, 0);
         }
+        const int tb0 = t0 + tb * 32;
+        if ((CAUSAL && tb0 + 31 > q0) || tb0 + 32 > S) {      // block touches the diagonal or the ragged end (wave-uniform)
 #pragma unroll
-        for (int e = 0; e < 16; ++e) {
-          const int t = t0 + tb * 32 + 8 * (e >> 2) + 4 * h + (e & 3);
-          float p = __builtin_amdgcn_exp2f(s[e] * c2 - lse2);
-          if (t >= S || (CAUSAL && t > q)) p = 0.f;
-          s[e] = p * (dp[e] - dv);                // dS^T
+          for (int e = 0; e < 16; ++e) {
+            const int t = tb0 + 8 * (e >> 2) + 4 * h + (e & 3);
+            float p = __builtin_amdgcn_exp2f(__builtin_fmaf(s[e], c2, -lse2));
+            if (t >= S || (CAUSAL && t > q)) p = 0.f;
+            s[e] = p * (dp[e] - dv);              // dS^T
+          }
+        } else {
+#pragma unroll
+          for (int e = 0; e < 16; ++e) s[e] = __builtin_amdgcn_exp2f(__builtin_fmaf(s[e], c2, -lse2)) * (dp[e] - dv);
         }
 #pragma unroll
         for (int jj = 0; jj < 2; ++jj) {
@@ -320,6 +346,7 @@ attn_dq_kernel(const bf16* __restrict__ qkv, const bf16* __restrict__ dO, const 
     __syncthreads();
   }
   store_transposed<D>(dq, dqkv + (int64_t)n * S * ld + a * D, ld, q, S, scale);
+  }   // pass
 }
 
 // ------------------------------------------------------------------------------------ dK, dV
@@ -334,7 +361,6 @@ attn_dkv_kernel(const bf16* __restrict__ qkv, const bf16* __restrict__ dO, const
   auto dOs = [&](int st) { return smem + st * 2 * TL::ELEMS + TL::ELEMS; };
   LDS_AS float* stats = (LDS_AS float*)(smem + 4 * TL::ELEMS);   // [2 buffers][lse2 | dvec][64]
 
-  const int tt = blockIdx.x;                       // key tile of 128 keys; early tiles are the heavy ones under a causal mask
   const int a = blockIdx.y, n = blockIdx.z;
   const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63, h = lane >> 5;
   const int64_t ld = 3 * (int64_t)H;
@@ -342,9 +368,13 @@ attn_dkv_kernel(const bf16* __restrict__ qkv, const bf16* __restrict__ dO, const
   const bf16* dObase = dO + (int64_t)n * S * H + a * D;
   const float* lse_base = lse + ((int64_t)n * A + a) * S;
   const float* dv_base = dvec + ((int64_t)n * A + a) * S;
+  const float c2 = scale * kLog2e;
+  const int ntk = (S + 127) / 128;                 // causal: key tiles x and ntk-1-x in turn (early key tiles see the most queries)
+  for (int pass = 0; pass < (CAUSAL ? 2 : 1); ++pass) {
+  const int tt = pass == 0 ? (int)blockIdx.x : ntk - 1 - (int)blockIdx.x;
+  if (pass == 1 && tt == (int)blockIdx.x) break;
   const int t0 = tt * 128 + wave * 32;             // this wavefront's 32 keys
   const int t = t0 + (lane & 31);
-  const float c2 = scale * kLog2e;
 
   bf16x8 kf[D / 16], vf[D / 16];
   load_row_frags<D>(base + H, ld, t0, S, kf);
@@ -394,6 +424,7 @@ attn_dkv_kernel(const bf16* __restrict__ qkv, const bf16* __restrict__ dO, const
           s = __builtin_amdgcn_mfma_f32_32x32x16_bf16(TL::frag_rows(Qs(cur), qb * 32, kk * 16), kf[kk], s, 0, 0, 0);
           dp = __builtin_amdgcn_mfma_f32_32x32x16_bf16(TL::frag_rows(dOs(cur), qb * 32, kk * 16), vf[kk], dp, 0, 0, 0);
         }
+        const bool edge = (CAUSAL && t0 + 31 > qb0 + qb * 32) || qb0 + qb * 32 + 32 > S;   // diagonal or ragged end (wave-uniform)
 #pragma unroll
         for (int j = 0; j < 4; ++j) {
           const int r = qb * 32 + 8 * j + 4 * h;       // 4 consecutive query rows
@@ -402,9 +433,11 @@ attn_dkv_kernel(const bf16* __restrict__ qkv, const bf16* __restrict__ dO, const
 #pragma unroll
           for (int i = 0; i < 4; ++i) {
             const int e = 4 * j + i;
-            const int qq = qb0 + r + i;
-            float p = __builtin_amdgcn_exp2f(s[e] * c2 - l4[i]);
-            if (qq >= S || (CAUSAL && t > qq)) p = 0.f;
+            float p = __builtin_amdgcn_exp2f(__builtin_fmaf(s[e], c2, -l4[i]));
+            if (edge) {
+              const int qq = qb0 + r + i;
+              if (qq >= S || (CAUSAL && t > qq)) p = 0.f;
+            }
             s[e] = p;                                  // P
             dp[e] = p * (dp[e] - d4[i]);               // dS
           }
@@ -430,6 +463,7 @@ attn_dkv_kernel(const bf16* __restrict__ qkv, const bf16* __restrict__ dO, const
   bf16* out = dqkv + (int64_t)n * S * ld + a * D;
   store_transposed<D>(dk, out + H, ld, t, S, scale);
   store_transposed<D>(dvv, out + 2 * H, ld, t, S, 1.0f);
+  }   // pass
 }
 
 template <typename K>
@@ -448,7 +482,8 @@ int fwd_cfg(const bf16* qkv, bf16* O, float* lse, int m, int S, int H, int A, hi
   auto kern = attn_fwd_kernel<D, CAUSAL>;
   int rc = reserve_lds(kern, lds);
   if (rc != CEPHALO_OK) return rc;
-  dim3 grid((S + 127) / 128, A, m);
+  const int nt = (S + 127) / 128;
+  dim3 grid(CAUSAL ? (nt + 1) / 2 : nt, A, m);     // causal: a block takes a tile and its mirror image
   kern<<<grid, kThreads, lds, s>>>(qkv, O, lse, S, H, A, 1.0f / sqrtf((float)D));
   CEPHALO_CHECK_LAUNCH("attn_fwd_mfma");
   return CEPHALO_OK;
@@ -460,7 +495,8 @@ int bwd_cfg(const bf16* qkv, const bf16* O, const bf16* dO, const float* lse, fl
   const float scale = 1.0f / sqrtf((float)D);
   const int rows = m * S;
   attn_dvec_kernel<D><<<(rows + 3) / 4, kThreads, 0, s>>>(O, dO, dvec, rows, S, H, A);
-  dim3 grid((S + 127) / 128, A, m);
+  const int nt = (S + 127) / 128;
+  dim3 grid(CAUSAL ? (nt + 1) / 2 : nt, A, m);     // causal: a block takes a tile and its mirror image
   {
     const size_t lds = 4 * (size_t)Tile<D>::ELEMS * sizeof(bf16);
     auto kern = attn_dq_kernel<D, CAUSAL>;
