@@ -84,7 +84,7 @@ struct OperandTile {
   }
   // issue the loads of the slab starting at k0 into the LDS tile at `lds` (off[] already points at that slab)
   __device__ static void load_slab(__amdgpu_buffer_rsrc_t rsrc, const unsigned (&off)[PER_WAVE], int k0, int K, LDS_AS char* lds) {
-    const int wave = threadIdx.x >> 6;
+    const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);     // the LDS address of a direct load is a scalar (M0)
 #pragma unroll
     for (int j = 0; j < PER_WAVE; ++j) {
       unsigned o = off[j];
@@ -219,6 +219,10 @@ __global__ void __launch_bounds__(64 * WGM * WGN) gemm_mfma_kernel(GemmArgs<bf16
 #pragma unroll
   for (int j = 0; j < NI; ++j) fb[0][j] = TB::fragment(smem + TA::BYTES, frb, j, 0);
 
+  // The loads of slab kt+2 and the first fragment reads of slab kt+1 are issued unconditionally, so that the loop
+  // body is one basic block and they can be interleaved with the MFMAs of k-step 3: past the end of the contraction
+  // the loads fetch nothing (their offsets are out of range, or they land in a stage that is not read again) and
+  // the fragments are not used.
   for (int kt = 0; kt < nk; ++kt) {
     const LDS_AS char* As = smem + (kt & 1) * STAGE;
     const LDS_AS char* Bs = As + TA::BYTES;
@@ -235,32 +239,40 @@ __global__ void __launch_bounds__(64 * WGM * WGN) gemm_mfma_kernel(GemmArgs<bf16
         // all LDS reads of this stage are done once lgkmcnt drains; slab kt+1 (issued one slab ago) has landed
         __builtin_amdgcn_s_waitcnt(0x0070);              // vmcnt(0) lgkmcnt(0)
         __syncthreads();
-        if (kt + 2 < nk) {
-          TA::advance(offa, a_step);
-          TB::advance(offb, b_step);
-          TA::load_slab(ra_rsrc, offa, (kb0 + kt + 2) * BK, a.K, smem + (kt & 1) * STAGE);
-          TB::load_slab(rb_rsrc, offb, (kb0 + kt + 2) * BK, a.K, smem + (kt & 1) * STAGE + TA::BYTES);
-        }
-        if (kt + 1 < nk) {
+        TA::advance(offa, a_step);
+        TB::advance(offb, b_step);
+        TA::load_slab(ra_rsrc, offa, (kb0 + kt + 2) * BK, a.K, smem + (kt & 1) * STAGE);
+        TB::load_slab(rb_rsrc, offb, (kb0 + kt + 2) * BK, a.K, smem + (kt & 1) * STAGE + TA::BYTES);
 #pragma unroll
-          for (int i = 0; i < MI; ++i) fa[nxt][i] = TA::fragment(An, fra, i, 0);
+        for (int i = 0; i < MI; ++i) fa[nxt][i] = TA::fragment(An, fra, i, 0);
 #pragma unroll
-          for (int j = 0; j < NI; ++j) fb[nxt][j] = TB::fragment(An + TA::BYTES, frb, j, 0);
-        }
+        for (int j = 0; j < NI; ++j) fb[nxt][j] = TB::fragment(An + TA::BYTES, frb, j, 0);
       }
 #pragma unroll
       for (int i = 0; i < MI; ++i)
 #pragma unroll
         for (int j = 0; j < NI; ++j)
           acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fb[cur][j], fa[cur][i], acc[i][j], 0, 0, 0);
-      // Scheduling hint: spread this k-step's fragment reads (for the next k-step) between its MFMAs, one LDS read
-      // per MFMAS_PER_READ matrix instructions, instead of bunching reads and then waiting on them.
+      // Scheduling hint: spread this k-step's fragment reads (for the next k-step) and, in k-step 3, the direct-to-LDS
+      // loads between its MFMAs instead of bunching them and then waiting.
       constexpr int READS = (AK ? MI : 2 * MI) + (BKF ? NI : 2 * NI);
-      constexpr int MFMAS_PER_READ = (MI * NI) / READS > 0 ? (MI * NI) / READS : 1;
+      constexpr int LOADS = TA::PER_WAVE + TB::PER_WAVE;
+      constexpr int SLOTS = MI * NI;
+      if (step < 3) {
+        constexpr int MFMAS_PER_READ = SLOTS / READS > 0 ? SLOTS / READS : 1;
 #pragma unroll
-      for (int r = 0; r < READS; ++r) {
-        __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);               // one DS read
-        __builtin_amdgcn_sched_group_barrier(0x008, MFMAS_PER_READ, 0);  // then MFMAs
+        for (int r = 0; r < READS; ++r) {
+          __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);               // one DS read
+          __builtin_amdgcn_sched_group_barrier(0x008, MFMAS_PER_READ, 0);  // then MFMAs
+        }
+      } else {
+        constexpr int PER_SLOT_R = (READS + SLOTS - 1) / SLOTS, PER_SLOT_L = (LOADS + SLOTS - 1) / SLOTS;
+#pragma unroll
+        for (int r = 0; r < SLOTS; ++r) {
+          __builtin_amdgcn_sched_group_barrier(0x020, PER_SLOT_L, 0);      // direct-to-LDS loads of slab kt+2
+          __builtin_amdgcn_sched_group_barrier(0x100, PER_SLOT_R, 0);      // first fragments of slab kt+1
+          __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);               // one MFMA
+        }
       }
     }
   }
