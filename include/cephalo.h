@@ -217,7 +217,9 @@ typedef struct cephalo_stack_desc {
 int64_t cephalo_stack_param_count(const cephalo_stack_desc* desc);
 
 /* Bytes of the single work area of cephalo_stack_step (layer-boundary activations and saved activations of
- * every layer and micro-batch, the share's logits, backward buffers).  Host pointer out. */
+ * every layer and micro-batch, one micro-batch of logits and the share's logit gradients, backward buffers).
+ * Host pointer out.  The area begins with the layer-boundary activations, fp32 [layers+1][b*S][H]: entry 0 is the
+ * embedding output, entry i the output of layer i-1; they are valid after cephalo_stack_step returns. */
 int cephalo_stack_workspace_bytes(const cephalo_stack_desc* desc, int32_t batch_share, int32_t micro_batch, size_t* bytes);
 
 /* Forward, loss and backward of the whole share (b = l*m, Sec. 3.2):

@@ -1,0 +1,145 @@
+"""Parity at the full sizes of the largest workloads, in the launch configurations bench.py times, on sampled
+outputs that the oracle's definitions give one by one (a row of a projection, a row of a weight gradient, one
+head of the attention), plus the full c5 stack checked layer by layer against the oracle's layer."""
+import numpy as np
+import pytest
+import torch
+
+import paper_2411_01075_amd as C
+from oracle import layer as olayer
+from oracle.precision import round_to_bf16
+from workloads import CONFIGS, draw_stack_params, draw_token_ids
+from tests.harness import rel_errors
+from tests.test_gpu_attention import oracle_attention
+
+pytestmark = pytest.mark.gpu
+bt = torch.bfloat16
+
+
+def rand_bf16(shape, scale, seed):
+    """A bf16 device tensor and its exact fp64 image on the host."""
+    g = torch.Generator(device="cuda").manual_seed(seed)
+    t = (torch.randn(shape, device="cuda", generator=g) * scale).to(bt)
+    return t, t.double().cpu().numpy()
+
+
+C5 = CONFIGS["c5"]
+H, F, T, NTOK = C5.hidden, C5.mlp, C5.tokens_per_micro, C5.tokens_per_step
+
+
+@pytest.mark.parametrize("name,n_out,k_in", [("qkv", 3 * H, H), ("o", H, H), ("fc1", F, H), ("fc2", H, F)])
+def test_c5_projections_sampled_rows(name, n_out, k_in):
+    print("full-size projection", name, flush=True)
+    X, Xh = rand_bf16((T, k_in), 1.0, 1)
+    W, Wh = rand_bf16((n_out, k_in), 0.02, 2)
+    b, bh = rand_bf16((n_out,), 0.02, 3)
+    rows = np.random.default_rng(5).choice(T, size=24, replace=False)
+    ref = Xh[rows] @ Wh.T + bh
+    if name in ("o", "fc2"):          # residual-stream projections: fp32 residual in, fp32 out
+        R = torch.randn(T, n_out, device="cuda", generator=torch.Generator(device="cuda").manual_seed(4))
+        Y = torch.full((T, n_out), float("nan"), device="cuda")
+        C.cephalo_op_gemm(C.BF16, X, k_in, 1, W, k_in, 1, T, n_out, k_in, C.EPI_BIAS_RESID_F32, C=Y, bias=b, R=R)
+        e = rel_errors(Y[rows].double().cpu().numpy(), ref + R[rows].double().cpu().numpy())
+        assert e[0] < 1e-4, e
+    elif name == "fc1":
+        Y = torch.empty(T, n_out, device="cuda", dtype=bt)
+        Z = torch.empty(T, n_out, device="cuda", dtype=bt)
+        C.cephalo_op_gemm(C.BF16, X, k_in, 1, W, k_in, 1, T, n_out, k_in, C.EPI_BIAS_GELU, C=Y, bias=b, Z=Z)
+        assert rel_errors(Z[rows].double().cpu().numpy(), ref)[0] < 6e-3
+        assert rel_errors(Y[rows].double().cpu().numpy(), olayer.gelu(ref))[0] < 6e-3
+    else:
+        Y = torch.empty(T, n_out, device="cuda", dtype=bt)
+        C.cephalo_op_gemm(C.BF16, X, k_in, 1, W, k_in, 1, T, n_out, k_in, C.EPI_BIAS, C=Y, bias=b)
+        assert rel_errors(Y[rows].double().cpu().numpy(), ref)[0] < 6e-3
+    # input gradient dX = dY W through W^T, fp32 out
+    dY, dYh = rand_bf16((T, n_out), 1.0, 6)
+    WT = W.t().contiguous()
+    dX = torch.full((T, k_in), float("nan"), device="cuda")
+    C.cephalo_op_gemm(C.BF16, dY, n_out, 1, WT, n_out, 1, T, k_in, n_out, C.EPI_NONE_F32, C=dX)
+    assert rel_errors(dX[rows].double().cpu().numpy(), dYh[rows] @ Wh)[0] < 1e-4
+
+
+@pytest.mark.parametrize("name,n_out,k_in", [("qkv", 3 * H, H), ("o", H, H), ("fc1", F, H), ("fc2", H, F)])
+def test_c5_weight_gradients_over_the_share_sampled_rows(name, n_out, k_in):
+    print("full-size weight gradient", name, flush=True)
+    X, Xh = rand_bf16((NTOK, k_in), 1.0, 11)
+    dY, dYh = rand_bf16((NTOK, n_out), 1.0, 12)
+    ws = torch.empty(C.cephalo_op_linear_wgrad_workspace(C.BF16, NTOK, n_out, k_in), dtype=torch.uint8, device="cuda")
+    G = torch.full((n_out, k_in), float("nan"), device="cuda")
+    C.cephalo_op_linear_wgrad(C.BF16, dY, X, NTOK, n_out, k_in, G, 1.0, 0, ws)
+    torch.cuda.synchronize()
+    rows = np.random.default_rng(13).choice(n_out, size=12, replace=False)
+    ref = dYh[:, rows].T @ Xh
+    e = rel_errors(G[rows].double().cpu().numpy(), ref)
+    assert e[0] < 1e-4, e
+    assert torch.isfinite(G).all()
+
+
+@pytest.mark.parametrize("cfg_name", ["c5", "c3"])
+def test_attention_full_size_one_head(cfg_name):
+    cfg = CONFIGS[cfg_name]
+    print("full-size attention", cfg_name, flush=True)
+    Hh, A, S, m, d = cfg.hidden, cfg.heads, cfg.seq, cfg.micro_batch, cfg.hidden // cfg.heads
+    desc = C.desc_from_config(cfg)
+    qkv, qkvh = rand_bf16((m * S, 3 * Hh), 1.0, 21)
+    dO, dOh = rand_bf16((m * S, Hh), 1.0, 22)
+    O = torch.full((m * S, Hh), float("nan"), dtype=bt, device="cuda")
+    lse = torch.empty((m, A, S), device="cuda")
+    dvec = torch.empty((m, A, S), device="cuda")
+    dqkv = torch.full((m * S, 3 * Hh), float("nan"), dtype=bt, device="cuda")
+    C.cephalo_op_attention_fwd(desc, qkv, O, lse, m)
+    C.cephalo_op_attention_bwd(desc, qkv, O, dO, lse, dvec, dqkv, m)
+    torch.cuda.synchronize()
+    assert torch.isfinite(O.float()).all() and torch.isfinite(dqkv.float()).all()
+    for n, a in ((0, 0), (m - 1, A - 1), (m // 2, A // 2)):
+        cols = slice(a * d, (a + 1) * d)
+        one = np.concatenate([qkvh[n * S:(n + 1) * S, i * Hh:(i + 1) * Hh][:, cols] for i in range(3)], axis=1)   # [S, 3d]
+        O_ref, lse_ref, dqkv_ref = oracle_attention(one, dOh[n * S:(n + 1) * S, cols], 1, S, 1, d, cfg.causal)
+        e = rel_errors(O[n * S:(n + 1) * S, cols].double().cpu().numpy(), O_ref)
+        assert e[0] < 2e-2 and e[1] < 5e-3, ("O", n, a, e)
+        assert np.max(np.abs(lse[n, a].double().cpu().numpy() - lse_ref[0, 0])) < 2e-3
+        got = dqkv[n * S:(n + 1) * S].double().cpu().numpy()
+        for i, nm in enumerate(("dQ", "dK", "dV")):
+            e = rel_errors(got[:, i * Hh:(i + 1) * Hh][:, cols], dqkv_ref[:, i * d:(i + 1) * d])
+            assert e[0] < 2e-2 and e[1] < 5e-3, (nm, n, a, e)
+
+
+def test_c5_stack_full_size_layer_by_layer():
+    """The whole c5 step at full size.  The oracle cannot run 24 layers x 12 samples in a test, so each sampled layer
+    is checked on its own: the GPU's input of layer i (a layer-boundary activation kept at the head of the workspace)
+    goes through the oracle's layer, and the result is compared with the GPU's input of layer i+1, for one sample.
+    The loss must be near log(V) for the N(0, 0.02^2) initialisation, and two runs must agree bit for bit."""
+    cfg = C5
+    sd = C.stack_desc_from_config(cfg)
+    params = draw_stack_params(cfg)
+    ids, tgt = draw_token_ids(cfg)
+    flat32 = torch.from_numpy(C.flatten_stack_params(sd, params)).cuda()
+    flat = torch.empty(flat32.numel(), dtype=bt, device="cuda")
+    C.cephalo_cast_bf16(flat, flat32)
+    del flat32
+    b, m, S, Hh, L = cfg.batch_share, cfg.micro_batch, cfg.seq, cfg.hidden, cfg.layers
+    ws = torch.empty(C.cephalo_stack_workspace_bytes(sd, b, m), dtype=torch.uint8, device="cuda")
+    G = torch.full((flat.numel(),), float("nan"), device="cuda")
+    loss = torch.full((1,), float("nan"), device="cuda")
+    dids, dtgt = torch.from_numpy(ids).cuda(), torch.from_numpy(tgt).cuda()
+    C.cephalo_stack_step(sd, flat, dids, dtgt, b, m, G, 1.0, loss, ws)
+    torch.cuda.synchronize()
+    l1 = float(loss.item())
+    print("c5 loss", l1, flush=True)
+    assert abs(l1 - (np.log(cfg.vocab) + 0.5 * 0.02 ** 2 * Hh)) < 0.15      # logits ~ N(0, 0.02^2 H): E[lse] = ln V + var/2
+    assert torch.isfinite(G).all()
+    xs = ws[: (L + 1) * b * S * Hh * 4].view(torch.float32).view(L + 1, b, S, Hh)
+    for li, n in ((0, 0), (11, 5), (23, 11)):
+        lp = {k: round_to_bf16(v) for k, v in params["layers"][li].items()}
+        y_ref, _ = olayer.layer_fwd(lp, xs[li, n:n + 1].double().cpu().numpy(), cfg.heads, cfg.causal)
+        e = rel_errors(xs[li + 1, n].double().cpu().numpy(), y_ref[0])
+        print("layer", li, "sample", n, e, flush=True)
+        assert e[0] < 2e-2 and e[1] < 5e-3, (li, n, e)
+    # the embedding row of a token: x0 = wte[id] + wpe[pos]
+    t = 7
+    x0_ref = round_to_bf16(params["wte"][ids[3, t]]) + round_to_bf16(params["wpe"][t])
+    assert np.max(np.abs(xs[0, 3, t].double().cpu().numpy() - x0_ref)) < 1e-6
+    G1 = G.clone()
+    C.cephalo_stack_step(sd, flat, dids, dtgt, b, m, G, 1.0, loss, ws)
+    torch.cuda.synchronize()
+    assert float(loss.item()) == l1 and torch.equal(G, G1)

@@ -85,3 +85,57 @@ def test_linear_input_and_weight_gradients(T, N, K, bf16):
     assert rel_errors(host(G), ref)[0] < 1e-5
     C.cephalo_op_gemm(dt, ddY, 1, N, dX_, 1, K, N, K, T, C.EPI_GRAD, G=G, scale=0.25, accumulate=1)
     assert rel_errors(host(G), 1.5 * ref)[0] < 1e-5
+
+
+@pytest.mark.parametrize("T,N,K", [(256, 384, 128), (200, 1600, 320), (520, 328, 72), (1024, 1024, 4096)])
+def test_input_gradient_through_transposed_weight_and_fp32_outputs(T, N, K):
+    """The layer's bf16 backward reads W^T (made once per layer and step), so dX = dY W is a contraction with both
+    operands contiguous along the contracted axis; results entering LayerNorm's backward and the residual stream
+    leave the GEMM in fp32."""
+    print("dgrad-wt", T, N, K, flush=True)
+    rng = np.random.default_rng(T + 7 * N + K)
+    W = (rng.standard_normal((N, K)) * 0.05).astype(np.float32)
+    dY = rng.standard_normal((T, N)).astype(np.float32)
+    Zp = rng.standard_normal((T, K)).astype(np.float32)
+    b = (rng.standard_normal(K) * 0.1).astype(np.float32)
+    R = rng.standard_normal((T, K)).astype(np.float32)
+    Wr, dYr, Zr, br = round_to_bf16(W), round_to_bf16(dY), round_to_bf16(Zp), round_to_bf16(b)
+    ref = dYr @ Wr
+    dWT, ddY, dZ, db = dev(np.ascontiguousarray(W.T), True), dev(dY, True), dev(Zp, True), dev(b, True)
+    dR = torch.from_numpy(R).cuda()
+    out32 = torch.full((T, K), float("nan"), dtype=torch.float32, device="cuda")
+    C.cephalo_op_gemm(C.BF16, ddY, N, 1, dWT, N, 1, T, K, N, C.EPI_NONE_F32, C=out32)
+    assert rel_errors(host(out32), ref)[0] < 1e-5            # fp32 out: only the order of the fp32 additions differs
+    out = torch.empty((T, K), dtype=torch.bfloat16, device="cuda")
+    C.cephalo_op_gemm(C.BF16, ddY, N, 1, dWT, N, 1, T, K, N, C.EPI_DGELU, C=out, Z=dZ)
+    assert rel_errors(host(out), ref * olayer.gelu_grad(Zr))[0] < 6e-3
+    C.cephalo_op_gemm(C.BF16, ddY, N, 1, dWT, N, 1, T, K, N, C.EPI_BIAS_RESID_F32, C=out32, bias=db, R=dR)
+    assert rel_errors(host(out32), ref + br + R.astype(np.float64))[0] < 1e-5
+
+
+@pytest.mark.parametrize("bf16", [False, True])
+@pytest.mark.parametrize("T,N,K", [(4096, 256, 256),      # one output tile: the token axis is cut into pieces
+                                   (4104, 320, 200),      # ragged everything, pieces of unequal length
+                                   (2048, 1024, 512), (300, 72, 136), (8192, 512, 256)])
+def test_linear_weight_gradient_op(T, N, K, bf16):
+    print("wgrad op", T, N, K, bf16, flush=True)
+    rng = np.random.default_rng(T + N * 3 + K)
+    X = rng.standard_normal((T, K)).astype(np.float32)
+    dY = rng.standard_normal((T, N)).astype(np.float32)
+    rnd = round_to_bf16 if bf16 else (lambda a: a.astype(np.float64))
+    ref = rnd(dY).T @ rnd(X)
+    dt = C.BF16 if bf16 else C.F32
+    ws = torch.empty(max(16, C.cephalo_op_linear_wgrad_workspace(dt, T, N, K)), dtype=torch.uint8, device="cuda")
+    G = torch.full((N, K), float("nan"), dtype=torch.float32, device="cuda")
+    C.cephalo_op_linear_wgrad(dt, dev(dY, bf16), dev(X, bf16), T, N, K, G, 0.5, 0, ws)
+    assert rel_errors(host(G), 0.5 * ref)[0] < 1e-5
+    first = G.clone()
+    C.cephalo_op_linear_wgrad(dt, dev(dY, bf16), dev(X, bf16), T, N, K, G, 0.25, 1, ws)
+    assert rel_errors(host(G), 0.75 * ref)[0] < 1e-5
+    G2 = torch.full((N, K), float("nan"), dtype=torch.float32, device="cuda")
+    C.cephalo_op_linear_wgrad(dt, dev(dY, bf16), dev(X, bf16), T, N, K, G2, 0.5, 0, ws)
+    assert torch.equal(first, G2)                              # fixed summation order: bit-reproducible
+    if bf16:
+        small = torch.empty(16, dtype=torch.uint8, device="cuda")
+        with pytest.raises(C.CephaloError, match="error -3"):
+            C.cephalo_op_linear_wgrad(dt, dev(dY, bf16), dev(X, bf16), T, N, K, G, 1.0, 0, small)
