@@ -172,33 +172,37 @@ ln_bwd_kernel(const float* __restrict__ du, const float* __restrict__ x, const f
   }
 }
 
-// g[n] = (accumulate ? g[n] : 0) + scale * sum_{c < nchunks} partials[c][n].  A block owns 64 columns; its four
-// wavefronts take chunks c = w, w+4, ... and their sums are combined in a fixed order, so the result does not
-// depend on scheduling.
+// out[y][n] = (accumulate ? out[y][n] : 0) + scale * sum over the chunks c of group y of partials[c][n], group y =
+// chunks [y*per_group, (y+1)*per_group).  A block owns 64 columns of one group; its four wavefronts take chunks
+// w, w+4, ... and their sums are combined in a fixed order, so the result does not depend on scheduling.
 __global__ void __launch_bounds__(kThreads)
-reduce_partials_kernel(const float* __restrict__ partials, int nchunks, int N, float* __restrict__ g,
+reduce_partials_kernel(const float* __restrict__ partials, int nchunks, int per_group, int N, float* __restrict__ out,
                        float scale, int accumulate) {
   __shared__ float red[kWaves][64];
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
   const int n = blockIdx.x * 64 + lane;
+  const int c0 = blockIdx.y * per_group, c1 = min(nchunks, c0 + per_group);
   float s0 = 0.f, s1 = 0.f, s2 = 0.f, s3 = 0.f;
   if (n < N) {
-    int c = wave;
-    for (; c + 3 * kWaves < nchunks; c += 4 * kWaves) {
+    int c = c0 + wave;
+    for (; c + 3 * kWaves < c1; c += 4 * kWaves) {
       s0 += partials[(int64_t)c * N + n];
       s1 += partials[(int64_t)(c + kWaves) * N + n];
       s2 += partials[(int64_t)(c + 2 * kWaves) * N + n];
       s3 += partials[(int64_t)(c + 3 * kWaves) * N + n];
     }
-    for (; c < nchunks; c += kWaves) s0 += partials[(int64_t)c * N + n];
+    for (; c < c1; c += kWaves) s0 += partials[(int64_t)c * N + n];
   }
   red[wave][lane] = (s0 + s1) + (s2 + s3);
   __syncthreads();
   if (wave == 0 && n < N) {
     const float s = (red[0][lane] + red[1][lane]) + (red[2][lane] + red[3][lane]);
-    g[n] = (accumulate ? g[n] : 0.f) + scale * s;
+    float* o = out + (int64_t)blockIdx.y * N + n;
+    *o = (accumulate ? *o : 0.f) + scale * s;
   }
 }
+
+constexpr int kReduceGroup = 32;    // chunks per first-stage group of a two-stage reduction
 
 constexpr int kColsumRowsPerChunk = 64;
 
@@ -301,15 +305,27 @@ int launch_ln_bwd(const float* du, const float* x, const float* mean, const floa
   return CEPHALO_OK;
 }
 
-int launch_reduce_partials(const float* partials, int nchunks, int N, float* g, float scale, int accumulate, hipStream_t s) {
-  reduce_partials_kernel<<<(N + 63) / 64, kThreads, 0, s>>>(partials, nchunks, N, g, scale, accumulate);
+size_t reduce_tmp_bytes(int nchunks, int N) {
+  return nchunks > 2 * kReduceGroup ? (size_t)((nchunks + kReduceGroup - 1) / kReduceGroup) * N * sizeof(float) : 0;
+}
+
+int launch_reduce_partials(const float* partials, int nchunks, int N, float* g, float scale, int accumulate,
+                           float* tmp, size_t tmp_bytes, hipStream_t s) {
+  const size_t need = reduce_tmp_bytes(nchunks, N);
+  if (need && tmp && tmp_bytes >= need) {     // many chunks: groups of 32 first (one block per group and 64 columns), then the groups
+    const int groups = (nchunks + kReduceGroup - 1) / kReduceGroup;
+    reduce_partials_kernel<<<dim3((N + 63) / 64, groups), kThreads, 0, s>>>(partials, nchunks, kReduceGroup, N, tmp, 1.0f, 0);
+    reduce_partials_kernel<<<dim3((N + 63) / 64, 1), kThreads, 0, s>>>(tmp, groups, groups, N, g, scale, accumulate);
+  } else {
+    reduce_partials_kernel<<<dim3((N + 63) / 64, 1), kThreads, 0, s>>>(partials, nchunks, nchunks, N, g, scale, accumulate);
+  }
   CEPHALO_CHECK_LAUNCH("reduce_partials");
   return CEPHALO_OK;
 }
 
 size_t colsum_partial_bytes(int rows, int N) {
   const size_t nchunks = (rows + kColsumRowsPerChunk - 1) / kColsumRowsPerChunk;
-  return nchunks * (size_t)N * sizeof(float);
+  return nchunks * (size_t)N * sizeof(float) + reduce_tmp_bytes((int)nchunks, N);   // chunk sums, then room for the group sums
 }
 
 template <typename T>
@@ -320,9 +336,8 @@ int launch_colsum(const T* dY, float* partials, size_t partial_bytes, float* g, 
   const int nvec = N / Vec<T>::N;
   dim3 grid((nvec + kThreads - 1) / kThreads, nchunks);
   colsum_kernel<T><<<grid, kThreads, 0, s>>>(dY, partials, rows, N);
-  reduce_partials_kernel<<<(N + 63) / 64, kThreads, 0, s>>>(partials, nchunks, N, g, scale, accumulate);
   CEPHALO_CHECK_LAUNCH("colsum");
-  return CEPHALO_OK;
+  return launch_reduce_partials(partials, nchunks, N, g, scale, accumulate, partials + (size_t)nchunks * N, reduce_tmp_bytes(nchunks, N), s);
 }
 
 int launch_transpose_bf16(const bf16* in, bf16* out, int rows, int cols, hipStream_t s, int out_pitch) {

@@ -133,7 +133,10 @@ template <typename T>
 int launch_ln_bwd(const float* du, const float* x, const float* mean, const float* rstd, const T* gamma,
                   const float* resid, float* out, T* out_lowp, float* part_g, float* part_b, int rows, int H, hipStream_t s);
 int ln_bwd_blocks(int rows);
-int launch_reduce_partials(const float* partials, int nchunks, int N, float* g, float scale, int accumulate, hipStream_t s);
+// tmp (reduce_tmp_bytes(nchunks, N) bytes, may be null) lets a long reduction run in two parallel stages.
+int launch_reduce_partials(const float* partials, int nchunks, int N, float* g, float scale, int accumulate,
+                           float* tmp, size_t tmp_bytes, hipStream_t s);
+size_t reduce_tmp_bytes(int nchunks, int N);
 
 // g[n] = (accumulate ? g[n] : 0) + scale * sum_t dY[t][n]   (bias gradient), dY [rows, N]
 template <typename T>

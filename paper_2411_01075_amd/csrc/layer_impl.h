@@ -392,14 +392,14 @@ int layer_bwd_params_t(const cephalo_layer_desc& d, const float* dy, const T* dy
   TRY(wgrad<T>(dyl, sv.h, tokens, H, F, G + o.w_fc2, scale, acc, w.tbuf, w.wg_part, s));
   TRY(launch_colsum<T>(w.dz, w.col_part, w.col_part_bytes, G + o.b_fc1, scale, acc, tokens, F, s));
   TRY(wgrad<T>(w.dz, sv.u2, tokens, F, H, G + o.w_fc1, scale, acc, w.tbuf, w.wg_part, s));
-  TRY(launch_reduce_partials(w.ln2_g, ln_chunks, H, G + o.ln2_g, scale, acc, s));
-  TRY(launch_reduce_partials(w.ln2_b, ln_chunks, H, G + o.ln2_b, scale, acc, s));
+  TRY(launch_reduce_partials(w.ln2_g, ln_chunks, H, G + o.ln2_g, scale, acc, w.col_part, w.col_part_bytes, s));
+  TRY(launch_reduce_partials(w.ln2_b, ln_chunks, H, G + o.ln2_b, scale, acc, w.col_part, w.col_part_bytes, s));
   TRY(launch_colsum<float>(w.dx1, w.col_part, w.col_part_bytes, G + o.b_o, scale, acc, tokens, H, s));
   TRY(wgrad<T>(lowp_of<T>(w.dx1, w.dx1l), sv.O, tokens, H, H, G + o.w_o, scale, acc, w.tbuf, w.wg_part, s));
   TRY(launch_colsum<T>(w.dqkv, w.col_part, w.col_part_bytes, G + o.b_qkv, scale, acc, tokens, 3 * H, s));
   TRY(wgrad<T>(w.dqkv, sv.u, tokens, 3 * H, H, G + o.w_qkv, scale, acc, w.tbuf, w.wg_part, s));
-  TRY(launch_reduce_partials(w.ln1_g, ln_chunks, H, G + o.ln1_g, scale, acc, s));
-  TRY(launch_reduce_partials(w.ln1_b, ln_chunks, H, G + o.ln1_b, scale, acc, s));
+  TRY(launch_reduce_partials(w.ln1_g, ln_chunks, H, G + o.ln1_g, scale, acc, w.col_part, w.col_part_bytes, s));
+  TRY(launch_reduce_partials(w.ln1_b, ln_chunks, H, G + o.ln1_b, scale, acc, w.col_part, w.col_part_bytes, s));
   return CEPHALO_OK;
 }
 
