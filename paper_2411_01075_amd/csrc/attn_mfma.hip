@@ -112,7 +112,7 @@ __device__ void store_transposed(const f32x16 (&acc)[D / 32], bf16* __restrict__
 
 // ------------------------------------------------------------------------------------ forward
 template <int D, bool CAUSAL>
-__global__ void __launch_bounds__(kThreads)
+__global__ void __launch_bounds__(kThreads, 2)
 attn_fwd_kernel(const bf16* __restrict__ qkv, bf16* __restrict__ O, float* __restrict__ lse, int S, int H, int A, float scale) {
   typedef Tile<D> TL;
   extern __shared__ __attribute__((aligned(16))) char smem_raw[];
@@ -161,15 +161,23 @@ attn_fwd_kernel(const bf16* __restrict__ qkv, bf16* __restrict__ O, float* __res
       TL::load_global(base + 2 * H, ld, t0 + TILE, S, rv);
     }
     if (!CAUSAL || t0 <= q0 + 31) {
+      // All K fragments of the tile are read before the first MFMA needs one, and the two 32-key blocks accumulate
+      // in turn, so neither an LDS round trip nor a dependent accumulator sits between consecutive MFMAs.
+      bf16x8 kfr[2][D / 16];
+#pragma unroll
+      for (int kk = 0; kk < D / 16; ++kk)
+#pragma unroll
+        for (int tb = 0; tb < 2; ++tb) kfr[tb][kk] = TL::frag_rows(Ks(cur), tb * 32, kk * 16);
       f32x16 s[2];
 #pragma unroll
-      for (int tb = 0; tb < 2; ++tb) {
+      for (int tb = 0; tb < 2; ++tb)
 #pragma unroll
         for (int e = 0; e < 16; ++e) s[tb][e] = 0.f;
 #pragma unroll
-        for (int kk = 0; kk < D / 16; ++kk)
-          s[tb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(TL::frag_rows(Ks(cur), tb * 32, kk * 16), qf[kk], s[tb], 0, 0, 0);
-      }
+      for (int kk = 0; kk < D / 16; ++kk)
+#pragma unroll
+        for (int tb = 0; tb < 2; ++tb)
+          s[tb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kfr[tb][kk], qf[kk], s[tb], 0, 0, 0);
       // Only tiles that touch the diagonal or the ragged end need per-element masking (wave-uniform test).
       if ((CAUSAL && t0 + TILE - 1 > q0) || t0 + TILE > S) {
 #pragma unroll
@@ -214,10 +222,13 @@ attn_fwd_kernel(const bf16* __restrict__ qkv, bf16* __restrict__ O, float* __res
       for (int tb = 0; tb < 2; ++tb)
 #pragma unroll
         for (int jj = 0; jj < 2; ++jj) {
+          bf16x8 vfr[D / 32];
+#pragma unroll
+          for (int dt = 0; dt < D / 32; ++dt) vfr[dt] = TL::frag_cols(Vs(cur), dt * 32, tb * 32 + 16 * jj);
           const bf16x8 pf = pack8(s[tb], 8 * jj);
 #pragma unroll
           for (int dt = 0; dt < D / 32; ++dt)
-            o[dt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(TL::frag_cols(Vs(cur), dt * 32, tb * 32 + 16 * jj), pf, o[dt], 0, 0, 0);
+            o[dt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vfr[dt], pf, o[dt], 0, 0, 0);
         }
     }
     if (kt + 1 < ntiles) {
@@ -257,7 +268,7 @@ attn_dvec_kernel(const bf16* __restrict__ O, const bf16* __restrict__ dO, float*
 
 // ------------------------------------------------------------------------------------ dQ
 template <int D, bool CAUSAL>
-__global__ void __launch_bounds__(kThreads)
+__global__ void __launch_bounds__(kThreads, 2)
 attn_dq_kernel(const bf16* __restrict__ qkv, const bf16* __restrict__ dO, const float* __restrict__ lse,
                const float* __restrict__ dvec, bf16* __restrict__ dqkv, int S, int H, int A, float scale) {
   typedef Tile<D> TL;
@@ -309,7 +320,7 @@ attn_dq_kernel(const bf16* __restrict__ qkv, const bf16* __restrict__ dO, const 
     if (!CAUSAL || t0 <= q0 + 31) {
 #pragma unroll
       for (int tb = 0; tb < 2; ++tb) {
-        f32x16 s, dp;
+        f32x16 s, dp;       // S^T and dP^T accumulate in turn: no dependent accumulator between consecutive MFMAs
 #pragma unroll
         for (int e = 0; e < 16; ++e) { s[e] = 0.f; dp[e] = 0.f; }
 #pragma unroll
@@ -416,14 +427,28 @@ attn_dkv_kernel(const bf16* __restrict__ qkv, const bf16* __restrict__ dO, const
     if (!CAUSAL || qb0 + TILE - 1 >= t0) {
 #pragma unroll
       for (int qb = 0; qb < 2; ++qb) {
+        bf16x8 qfr[D / 16], dofr[D / 16];     // fragments first, then S and dP accumulate in turn
+#pragma unroll
+        for (int kk = 0; kk < D / 16; ++kk) {
+          qfr[kk] = TL::frag_rows(Qs(cur), qb * 32, kk * 16);
+          dofr[kk] = TL::frag_rows(dOs(cur), qb * 32, kk * 16);
+        }
         f32x16 s, dp;
 #pragma unroll
         for (int e = 0; e < 16; ++e) { s[e] = 0.f; dp[e] = 0.f; }
 #pragma unroll
         for (int kk = 0; kk < D / 16; ++kk) {
-          s = __builtin_amdgcn_mfma_f32_32x32x16_bf16(TL::frag_rows(Qs(cur), qb * 32, kk * 16), kf[kk], s, 0, 0, 0);
-          dp = __builtin_amdgcn_mfma_f32_32x32x16_bf16(TL::frag_rows(dOs(cur), qb * 32, kk * 16), vf[kk], dp, 0, 0, 0);
+          s = __builtin_amdgcn_mfma_f32_32x32x16_bf16(qfr[kk], kf[kk], s, 0, 0, 0);
+          dp = __builtin_amdgcn_mfma_f32_32x32x16_bf16(dofr[kk], vf[kk], dp, 0, 0, 0);
         }
+        bf16x8 dotf[2][D / 32], qtf[2][D / 32];   // dO^T and Q^T fragments of the last two products, read while the exponentials run
+#pragma unroll
+        for (int jj = 0; jj < 2; ++jj)
+#pragma unroll
+          for (int dt = 0; dt < D / 32; ++dt) {
+            dotf[jj][dt] = TL::frag_cols(dOs(cur), dt * 32, qb * 32 + 16 * jj);
+            qtf[jj][dt] = TL::frag_cols(Qs(cur), dt * 32, qb * 32 + 16 * jj);
+          }
         const bool edge = (CAUSAL && t0 + 31 > qb0 + qb * 32) || qb0 + qb * 32 + 32 > S;   // diagonal or ragged end (wave-uniform)
 #pragma unroll
         for (int j = 0; j < 4; ++j) {
@@ -447,8 +472,8 @@ attn_dkv_kernel(const bf16* __restrict__ qkv, const bf16* __restrict__ dO, const
           const bf16x8 pf = pack8(s, 8 * jj), df = pack8(dp, 8 * jj);
 #pragma unroll
           for (int dt = 0; dt < D / 32; ++dt) {
-            dvv[dt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(TL::frag_cols(dOs(cur), dt * 32, qb * 32 + 16 * jj), pf, dvv[dt], 0, 0, 0);
-            dk[dt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(TL::frag_cols(Qs(cur), dt * 32, qb * 32 + 16 * jj), df, dk[dt], 0, 0, 0);
+            dvv[dt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(dotf[jj][dt], pf, dvv[dt], 0, 0, 0);
+            dk[dt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(qtf[jj][dt], df, dk[dt], 0, 0, 0);
           }
         }
       }
