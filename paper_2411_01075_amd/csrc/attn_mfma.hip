@@ -13,6 +13,7 @@
 // The other operand of those second products (V^T, K^T, dO^T, Q^T: d-major views of row-major
 // [token][d] tiles) is fetched from LDS with the transposing read ds_read_b64_tr_b16.
 #include "kernels.h"
+#include <cstdlib>
 
 namespace cephalo {
 namespace {
@@ -30,16 +31,17 @@ constexpr int TILE = 64;            // tokens per LDS tile
 constexpr float kLog2e = 1.44269504088896340736f;
 constexpr float kLn2 = 0.69314718055994530942f;
 
-template <int D> struct Tile {
+// ROWS tokens by D values of one operand in LDS, staged through registers by THREADS threads.
+template <int D, int ROWS = TILE, int THREADS = kThreads> struct Tile {
   static constexpr int LD = D + 8;                 // padded row, elements
-  static constexpr int ELEMS = TILE * LD;
-  static constexpr int PER_THREAD = TILE * D / 8 / kThreads;
+  static constexpr int ELEMS = ROWS * LD;
+  static constexpr int PER_THREAD = ROWS * D / 8 / THREADS;
 
-  // rows [row0, row0+64) of a [*, ld] matrix, columns [0, D); rows >= nrows read as zero
+  // rows [row0, row0+ROWS) of a [*, ld] matrix, columns [0, D); rows >= nrows read as zero
   __device__ static void load_global(const bf16* __restrict__ g, int64_t ld, int row0, int nrows, bf16x8 (&reg)[PER_THREAD]) {
 #pragma unroll
     for (int p = 0; p < PER_THREAD; ++p) {
-      const int v = threadIdx.x + kThreads * p;
+      const int v = threadIdx.x + THREADS * p;
       const int row = v / (D / 8), c = (v % (D / 8)) * 8;
       bf16x8 val = {0, 0, 0, 0, 0, 0, 0, 0};
       if (row0 + row < nrows) val = *reinterpret_cast<const bf16x8*>(g + (int64_t)(row0 + row) * ld + c);
@@ -49,7 +51,7 @@ template <int D> struct Tile {
   __device__ static void store_lds(lds_bf16* lds, const bf16x8 (&reg)[PER_THREAD]) {
 #pragma unroll
     for (int p = 0; p < PER_THREAD; ++p) {
-      const int v = threadIdx.x + kThreads * p;
+      const int v = threadIdx.x + THREADS * p;
       const int row = v / (D / 8), c = (v % (D / 8)) * 8;
       *reinterpret_cast<LDS_AS bf16x8*>(lds + row * LD + c) = reg[p];
     }
@@ -242,6 +244,279 @@ attn_fwd_kernel(const bf16* __restrict__ qkv, bf16* __restrict__ O, float* __res
   store_transposed<D>(o, O + (int64_t)n * S * H + a * D, H, q, S, inv);
   if (h == 0 && q < S) lse[((int64_t)n * A + a) * S + q] = (m_run + __builtin_amdgcn_logf(l_tot)) * kLn2;
   }   // pass
+}
+
+// ------------------------------------------------------------------------------------ forward, 8 wavefronts
+// The same computation with two wavefronts per SIMD: 512 threads stage 128 keys per step, wavefronts 0-3 take the
+// first 64 of them and wavefronts 4-7 the second 64, for the same four blocks of 32 queries.  Each half keeps its own
+// running maximum, sum and output; at the end the second half hands them over through LDS and the first half merges
+// (o = o0 2^(m0-m) + o1 2^(m1-m), likewise the sums).  While one wavefront of a SIMD runs its softmax on the vector
+// unit the other's MFMAs keep the matrix core busy.
+constexpr int kThreads8 = 512;
+
+template <int D, bool CAUSAL>
+__global__ void __launch_bounds__(kThreads8)
+attn_fwd8_kernel(const bf16* __restrict__ qkv, bf16* __restrict__ O, float* __restrict__ lse, int S, int H, int A, float scale) {
+  typedef Tile<D, 128, kThreads8> TL;
+  extern __shared__ __attribute__((aligned(16))) char smem_raw[];
+  lds_bf16* smem = (lds_bf16*)smem_raw;
+  auto Ks = [&](int st) { return smem + st * 2 * TL::ELEMS; };
+  auto Vs = [&](int st) { return smem + st * 2 * TL::ELEMS + TL::ELEMS; };
+
+  const int a = blockIdx.y, n = blockIdx.z;
+  const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63, h = lane >> 5;
+  const int qsub = wave & 3, kh = wave >> 2;        // block of 32 queries, half of the staged keys
+  const int64_t ld = 3 * (int64_t)H;
+  const bf16* base = qkv + (int64_t)n * S * ld + a * D;
+  const float c2 = scale * kLog2e;
+  const int ntq = (S + 127) / 128;                  // causal: query tile x, then its mirror tile (equal work per block)
+  for (int pass = 0; pass < (CAUSAL ? 2 : 1); ++pass) {
+    const int qt = pass == 0 ? (int)blockIdx.x : ntq - 1 - (int)blockIdx.x;
+    if (pass == 1 && qt == (int)blockIdx.x) break;
+    const int q0 = qt * 128 + qsub * 32;
+    const int q = q0 + (lane & 31);
+
+    bf16x8 qf[D / 16];
+    load_row_frags<D>(base, ld, q0, S, qf);
+    f32x16 o[D / 32];
+#pragma unroll
+    for (int dt = 0; dt < D / 32; ++dt)
+#pragma unroll
+      for (int e = 0; e < 16; ++e) o[dt][e] = 0.f;
+    float m_run = -INFINITY, l_run = 0.f;
+
+    const int kv_end = CAUSAL ? min(S, qt * 128 + 128) : S;
+    const int ntiles = (kv_end + 127) / 128;
+    bf16x8 rk[TL::PER_THREAD], rv[TL::PER_THREAD];
+    TL::load_global(base + H, ld, 0, S, rk);
+    TL::load_global(base + 2 * H, ld, 0, S, rv);
+    TL::store_lds(Ks(0), rk);
+    TL::store_lds(Vs(0), rv);
+    __syncthreads();
+
+    for (int kt = 0; kt < ntiles; ++kt) {
+      const int cur = kt & 1;
+      if (kt + 1 < ntiles) {
+        TL::load_global(base + H, ld, (kt + 1) * 128, S, rk);
+        TL::load_global(base + 2 * H, ld, (kt + 1) * 128, S, rv);
+      }
+      const int t0 = kt * 128 + kh * 64;            // this wavefront's 64 keys
+      const lds_bf16* Kt = Ks(cur) + kh * 64 * TL::LD;
+      const lds_bf16* Vt = Vs(cur) + kh * 64 * TL::LD;
+      if (t0 < S && (!CAUSAL || t0 <= q0 + 31)) {
+        bf16x8 kfr[2][D / 16];
+#pragma unroll
+        for (int kk = 0; kk < D / 16; ++kk)
+#pragma unroll
+          for (int tb = 0; tb < 2; ++tb) kfr[tb][kk] = TL::frag_rows(Kt, tb * 32, kk * 16);
+        f32x16 s[2];
+#pragma unroll
+        for (int tb = 0; tb < 2; ++tb)
+#pragma unroll
+          for (int e = 0; e < 16; ++e) s[tb][e] = 0.f;
+#pragma unroll
+        for (int kk = 0; kk < D / 16; ++kk)
+#pragma unroll
+          for (int tb = 0; tb < 2; ++tb)
+            s[tb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kfr[tb][kk], qf[kk], s[tb], 0, 0, 0);
+        if ((CAUSAL && t0 + 63 > q0) || t0 + 64 > S) {      // diagonal or ragged end: per-element masking
+#pragma unroll
+          for (int tb = 0; tb < 2; ++tb)
+#pragma unroll
+            for (int e = 0; e < 16; ++e) {
+              const int t = t0 + tb * 32 + 8 * (e >> 2) + 4 * h + (e & 3);
+              if (t >= S || (CAUSAL && t > q)) s[tb][e] = -INFINITY;
+            }
+        }
+        float mx = -INFINITY;
+#pragma unroll
+        for (int tb = 0; tb < 2; ++tb)
+#pragma unroll
+          for (int e = 0; e < 16; ++e) mx = fmaxf(mx, s[tb][e]);
+        mx = fmaxf(mx, __shfl_xor(mx, 32, 64)) * c2;
+        if (__any(mx > m_run + 8.0f)) {                       // lazy raise of the running maximum (log2 domain)
+          const float m_new = fmaxf(m_run, mx);
+          const float alpha = (m_new == -INFINITY) ? 1.0f : __builtin_amdgcn_exp2f(m_run - m_new);
+          l_run *= alpha;
+          m_run = m_new;
+#pragma unroll
+          for (int dt = 0; dt < D / 32; ++dt)
+#pragma unroll
+            for (int e = 0; e < 16; ++e) o[dt][e] *= alpha;
+        }
+        const float neg_m = (m_run == -INFINITY) ? 0.f : -m_run;
+        float psum = 0.f;
+#pragma unroll
+        for (int tb = 0; tb < 2; ++tb)
+#pragma unroll
+          for (int e = 0; e < 16; ++e) {
+            const float p = __builtin_amdgcn_exp2f(__builtin_fmaf(s[tb][e], c2, neg_m));
+            s[tb][e] = p;
+            psum += p;
+          }
+        l_run += psum;
+#pragma unroll
+        for (int tb = 0; tb < 2; ++tb)
+#pragma unroll
+          for (int jj = 0; jj < 2; ++jj) {
+            bf16x8 vfr[D / 32];
+#pragma unroll
+            for (int dt = 0; dt < D / 32; ++dt) vfr[dt] = TL::frag_cols(Vt, dt * 32, tb * 32 + 16 * jj);
+            const bf16x8 pf = pack8(s[tb], 8 * jj);
+#pragma unroll
+            for (int dt = 0; dt < D / 32; ++dt)
+              o[dt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vfr[dt], pf, o[dt], 0, 0, 0);
+          }
+      }
+      if (kt + 1 < ntiles) {
+        TL::store_lds(Ks(cur ^ 1), rk);
+        TL::store_lds(Vs(cur ^ 1), rv);
+      }
+      __syncthreads();
+    }
+    // merge the two key halves: [value index][lane] floats per block of queries, lanes contiguous
+    constexpr int NV = D / 32 * 16 + 2;
+    LDS_AS float* mrg = (LDS_AS float*)smem_raw + qsub * NV * 64 + lane;
+    if (kh == 1) {
+#pragma unroll
+      for (int dt = 0; dt < D / 32; ++dt)
+#pragma unroll
+        for (int e = 0; e < 16; ++e) mrg[(dt * 16 + e) * 64] = o[dt][e];
+      mrg[(NV - 2) * 64] = m_run;
+      mrg[(NV - 1) * 64] = l_run;
+    }
+    __syncthreads();
+    if (kh == 0) {
+      const float m1 = mrg[(NV - 2) * 64], l1 = mrg[(NV - 1) * 64];
+      const float m = fmaxf(m_run, m1);
+      const float a0 = (m_run == -INFINITY) ? 0.f : __builtin_amdgcn_exp2f(m_run - m);
+      const float a1 = (m1 == -INFINITY) ? 0.f : __builtin_amdgcn_exp2f(m1 - m);
+#pragma unroll
+      for (int dt = 0; dt < D / 32; ++dt)
+#pragma unroll
+        for (int e = 0; e < 16; ++e) o[dt][e] = o[dt][e] * a0 + mrg[(dt * 16 + e) * 64] * a1;
+      const float l = l_run * a0 + l1 * a1;
+      const float l_tot = l + __shfl_xor(l, 32, 64);
+      const float inv = 1.0f / l_tot;
+      store_transposed<D>(o, O + (int64_t)n * S * H + a * D, H, q, S, inv);
+      if (h == 0 && q < S) lse[((int64_t)n * A + a) * S + q] = (m + __builtin_amdgcn_logf(l_tot)) * kLn2;
+    }
+    __syncthreads();     // the merge area is staged over again by the next pass
+  }
+}
+
+// ------------------------------------------------------------------------------------ dQ, 8 wavefronts
+// As attn_dq_kernel, with the staged 128 keys split between two groups of wavefronts whose partial dQ are added at the end.
+template <int D, bool CAUSAL>
+__global__ void __launch_bounds__(kThreads8)
+attn_dq8_kernel(const bf16* __restrict__ qkv, const bf16* __restrict__ dO, const float* __restrict__ lse,
+                const float* __restrict__ dvec, bf16* __restrict__ dqkv, int S, int H, int A, float scale) {
+  typedef Tile<D, 128, kThreads8> TL;
+  extern __shared__ __attribute__((aligned(16))) char smem_raw[];
+  lds_bf16* smem = (lds_bf16*)smem_raw;
+  auto Ks = [&](int st) { return smem + st * 2 * TL::ELEMS; };
+  auto Vs = [&](int st) { return smem + st * 2 * TL::ELEMS + TL::ELEMS; };
+
+  const int a = blockIdx.y, n = blockIdx.z;
+  const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63, h = lane >> 5;
+  const int qsub = wave & 3, kh = wave >> 2;
+  const int64_t ld = 3 * (int64_t)H;
+  const bf16* base = qkv + (int64_t)n * S * ld + a * D;
+  const float c2 = scale * kLog2e;
+  const int ntq = (S + 127) / 128;
+  for (int pass = 0; pass < (CAUSAL ? 2 : 1); ++pass) {
+    const int qt = pass == 0 ? (int)blockIdx.x : ntq - 1 - (int)blockIdx.x;
+    if (pass == 1 && qt == (int)blockIdx.x) break;
+    const int q0 = qt * 128 + qsub * 32;
+    const int q = q0 + (lane & 31);
+
+    bf16x8 qf[D / 16], dof[D / 16];
+    load_row_frags<D>(base, ld, q0, S, qf);
+    load_row_frags<D>(dO + (int64_t)n * S * H + a * D, H, q0, S, dof);
+    const int64_t stat = ((int64_t)n * A + a) * S + q;
+    const float lse2 = (q < S) ? lse[stat] * kLog2e : 0.f;
+    const float dv = (q < S) ? dvec[stat] : 0.f;
+    f32x16 dq[D / 32];
+#pragma unroll
+    for (int dt = 0; dt < D / 32; ++dt)
+#pragma unroll
+      for (int e = 0; e < 16; ++e) dq[dt][e] = 0.f;
+
+    const int kv_end = CAUSAL ? min(S, qt * 128 + 128) : S;
+    const int ntiles = (kv_end + 127) / 128;
+    bf16x8 rk[TL::PER_THREAD], rv[TL::PER_THREAD];
+    TL::load_global(base + H, ld, 0, S, rk);
+    TL::load_global(base + 2 * H, ld, 0, S, rv);
+    TL::store_lds(Ks(0), rk);
+    TL::store_lds(Vs(0), rv);
+    __syncthreads();
+
+    for (int kt = 0; kt < ntiles; ++kt) {
+      const int cur = kt & 1;
+      if (kt + 1 < ntiles) {
+        TL::load_global(base + H, ld, (kt + 1) * 128, S, rk);
+        TL::load_global(base + 2 * H, ld, (kt + 1) * 128, S, rv);
+      }
+      const int t0 = kt * 128 + kh * 64;
+      const lds_bf16* Kt = Ks(cur) + kh * 64 * TL::LD;
+      const lds_bf16* Vt = Vs(cur) + kh * 64 * TL::LD;
+      if (t0 < S && (!CAUSAL || t0 <= q0 + 31)) {
+#pragma unroll
+        for (int tb = 0; tb < 2; ++tb) {
+          f32x16 s, dp;
+#pragma unroll
+          for (int e = 0; e < 16; ++e) { s[e] = 0.f; dp[e] = 0.f; }
+#pragma unroll
+          for (int kk = 0; kk < D / 16; ++kk) {
+            s = __builtin_amdgcn_mfma_f32_32x32x16_bf16(TL::frag_rows(Kt, tb * 32, kk * 16), qf[kk], s, 0, 0, 0);
+            dp = __builtin_amdgcn_mfma_f32_32x32x16_bf16(TL::frag_rows(Vt, tb * 32, kk * 16), dof[kk], dp, 0, 0, 0);
+          }
+          const int tb0 = t0 + tb * 32;
+          if ((CAUSAL && tb0 + 31 > q0) || tb0 + 32 > S) {
+#pragma unroll
+            for (int e = 0; e < 16; ++e) {
+              const int t = tb0 + 8 * (e >> 2) + 4 * h + (e & 3);
+              float p = __builtin_amdgcn_exp2f(__builtin_fmaf(s[e], c2, -lse2));
+              if (t >= S || (CAUSAL && t > q)) p = 0.f;
+              s[e] = p * (dp[e] - dv);
+            }
+          } else {
+#pragma unroll
+            for (int e = 0; e < 16; ++e) s[e] = __builtin_amdgcn_exp2f(__builtin_fmaf(s[e], c2, -lse2)) * (dp[e] - dv);
+          }
+#pragma unroll
+          for (int jj = 0; jj < 2; ++jj) {
+            const bf16x8 df = pack8(s, 8 * jj);
+#pragma unroll
+            for (int dt = 0; dt < D / 32; ++dt)
+              dq[dt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(TL::frag_cols(Kt, dt * 32, tb * 32 + 16 * jj), df, dq[dt], 0, 0, 0);
+          }
+        }
+      }
+      if (kt + 1 < ntiles) {
+        TL::store_lds(Ks(cur ^ 1), rk);
+        TL::store_lds(Vs(cur ^ 1), rv);
+      }
+      __syncthreads();
+    }
+    constexpr int NV = D / 32 * 16;
+    LDS_AS float* mrg = (LDS_AS float*)smem_raw + qsub * NV * 64 + lane;
+    if (kh == 1) {
+#pragma unroll
+      for (int dt = 0; dt < D / 32; ++dt)
+#pragma unroll
+        for (int e = 0; e < 16; ++e) mrg[(dt * 16 + e) * 64] = dq[dt][e];
+    }
+    __syncthreads();
+    if (kh == 0) {
+#pragma unroll
+      for (int dt = 0; dt < D / 32; ++dt)
+#pragma unroll
+        for (int e = 0; e < 16; ++e) dq[dt][e] += mrg[(dt * 16 + e) * 64];
+      store_transposed<D>(dq, dqkv + (int64_t)n * S * ld + a * D, ld, q, S, scale);
+    }
+    __syncthreads();
+  }
 }
 
 // ------------------------------------------------------------------------------------ rowsum(dO * O)
@@ -503,13 +778,23 @@ int reserve_lds(K kern, size_t bytes) {
 
 template <int D, bool CAUSAL>
 int fwd_cfg(const bf16* qkv, bf16* O, float* lse, int m, int S, int H, int A, hipStream_t s) {
-  const size_t lds = 4 * (size_t)Tile<D>::ELEMS * sizeof(bf16);
-  auto kern = attn_fwd_kernel<D, CAUSAL>;
-  int rc = reserve_lds(kern, lds);
-  if (rc != CEPHALO_OK) return rc;
   const int nt = (S + 127) / 128;
   dim3 grid(CAUSAL ? (nt + 1) / 2 : nt, A, m);     // causal: a block takes a tile and its mirror image
-  kern<<<grid, kThreads, lds, s>>>(qkv, O, lse, S, H, A, 1.0f / sqrtf((float)D));
+  static const int use8 = getenv("CEPHALO_ATTN8") ? atoi(getenv("CEPHALO_ATTN8")) : 1;   // tuning aid
+  if (!use8) {
+    const size_t lds4 = 4 * (size_t)Tile<D>::ELEMS * sizeof(bf16);
+    auto kern4 = attn_fwd_kernel<D, CAUSAL>;
+    int rc4 = reserve_lds(kern4, lds4);
+    if (rc4 != CEPHALO_OK) return rc4;
+    kern4<<<grid, kThreads, lds4, s>>>(qkv, O, lse, S, H, A, 1.0f / sqrtf((float)D));
+    CEPHALO_CHECK_LAUNCH("attn_fwd_mfma");
+    return CEPHALO_OK;
+  }
+  const size_t lds = 4 * (size_t)Tile<D, 128, kThreads8>::ELEMS * sizeof(bf16);
+  auto kern = attn_fwd8_kernel<D, CAUSAL>;
+  int rc = reserve_lds(kern, lds);
+  if (rc != CEPHALO_OK) return rc;
+  kern<<<grid, kThreads8, lds, s>>>(qkv, O, lse, S, H, A, 1.0f / sqrtf((float)D));
   CEPHALO_CHECK_LAUNCH("attn_fwd_mfma");
   return CEPHALO_OK;
 }
@@ -523,11 +808,11 @@ int bwd_cfg(const bf16* qkv, const bf16* O, const bf16* dO, const float* lse, fl
   const int nt = (S + 127) / 128;
   dim3 grid(CAUSAL ? (nt + 1) / 2 : nt, A, m);     // causal: a block takes a tile and its mirror image
   {
-    const size_t lds = 4 * (size_t)Tile<D>::ELEMS * sizeof(bf16);
-    auto kern = attn_dq_kernel<D, CAUSAL>;
+    const size_t lds = 4 * (size_t)Tile<D, 128, kThreads8>::ELEMS * sizeof(bf16);
+    auto kern = attn_dq8_kernel<D, CAUSAL>;
     int rc = reserve_lds(kern, lds);
     if (rc != CEPHALO_OK) return rc;
-    kern<<<grid, kThreads, lds, s>>>(qkv, dO, lse, dvec, dqkv, S, H, A, scale);
+    kern<<<grid, kThreads8, lds, s>>>(qkv, dO, lse, dvec, dqkv, S, H, A, scale);
   }
   {
     const size_t lds = 4 * (size_t)Tile<D>::ELEMS * sizeof(bf16) + 2 * 128 * sizeof(float);
