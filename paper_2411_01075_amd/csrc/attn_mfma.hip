@@ -33,7 +33,11 @@ constexpr float kLn2 = 0.69314718055994530942f;
 
 // ROWS tokens by D values of one operand in LDS, staged through registers by THREADS threads.
 template <int D, int ROWS = TILE, int THREADS = kThreads> struct Tile {
-  static constexpr int LD = D + 8;                 // padded row, elements
+  // Padded row (elements).  The row pitch in 4-byte banks, LD/2 mod 64, decides the conflicts of both kinds of read:
+  // a 16-byte fragment read has 16 lanes on 16 consecutive rows, 4 banks each (the pitches 4, 12, 20, 36, ... spread
+  // them over all 64 banks); a transposing read has each group of 16 lanes on 4 consecutive rows, 8 banks each (pitch
+  // 4 makes neighbouring rows overlap; 12 and 36 do not).  D = 64: 72 elements (pitch 36); D = 128: 152 (pitch 12).
+  static constexpr int LD = D == 128 ? D + 24 : D + 8;
   static constexpr int ELEMS = ROWS * LD;
   static constexpr int PER_THREAD = ROWS * D / 8 / THREADS;
 
@@ -405,120 +409,6 @@ attn_fwd8_kernel(const bf16* __restrict__ qkv, bf16* __restrict__ O, float* __re
   }
 }
 
-// ------------------------------------------------------------------------------------ dQ, 8 wavefronts
-// As attn_dq_kernel, with the staged 128 keys split between two groups of wavefronts whose partial dQ are added at the end.
-template <int D, bool CAUSAL>
-__global__ void __launch_bounds__(kThreads8)
-attn_dq8_kernel(const bf16* __restrict__ qkv, const bf16* __restrict__ dO, const float* __restrict__ lse,
-                const float* __restrict__ dvec, bf16* __restrict__ dqkv, int S, int H, int A, float scale) {
-  typedef Tile<D, 128, kThreads8> TL;
-  extern __shared__ __attribute__((aligned(16))) char smem_raw[];
-  lds_bf16* smem = (lds_bf16*)smem_raw;
-  auto Ks = [&](int st) { return smem + st * 2 * TL::ELEMS; };
-  auto Vs = [&](int st) { return smem + st * 2 * TL::ELEMS + TL::ELEMS; };
-
-  const int a = blockIdx.y, n = blockIdx.z;
-  const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63, h = lane >> 5;
-  const int qsub = wave & 3, kh = wave >> 2;
-  const int64_t ld = 3 * (int64_t)H;
-  const bf16* base = qkv + (int64_t)n * S * ld + a * D;
-  const float c2 = scale * kLog2e;
-  const int ntq = (S + 127) / 128;
-  for (int pass = 0; pass < (CAUSAL ? 2 : 1); ++pass) {
-    const int qt = pass == 0 ? (int)blockIdx.x : ntq - 1 - (int)blockIdx.x;
-    if (pass == 1 && qt == (int)blockIdx.x) break;
-    const int q0 = qt * 128 + qsub * 32;
-    const int q = q0 + (lane & 31);
-
-    bf16x8 qf[D / 16], dof[D / 16];
-    load_row_frags<D>(base, ld, q0, S, qf);
-    load_row_frags<D>(dO + (int64_t)n * S * H + a * D, H, q0, S, dof);
-    const int64_t stat = ((int64_t)n * A + a) * S + q;
-    const float lse2 = (q < S) ? lse[stat] * kLog2e : 0.f;
-    const float dv = (q < S) ? dvec[stat] : 0.f;
-    f32x16 dq[D / 32];
-#pragma unroll
-    for (int dt = 0; dt < D / 32; ++dt)
-#pragma unroll
-      for (int e = 0; e < 16; ++e) dq[dt][e] = 0.f;
-
-    const int kv_end = CAUSAL ? min(S, qt * 128 + 128) : S;
-    const int ntiles = (kv_end + 127) / 128;
-    bf16x8 rk[TL::PER_THREAD], rv[TL::PER_THREAD];
-    TL::load_global(base + H, ld, 0, S, rk);
-    TL::load_global(base + 2 * H, ld, 0, S, rv);
-    TL::store_lds(Ks(0), rk);
-    TL::store_lds(Vs(0), rv);
-    __syncthreads();
-
-    for (int kt = 0; kt < ntiles; ++kt) {
-      const int cur = kt & 1;
-      if (kt + 1 < ntiles) {
-        TL::load_global(base + H, ld, (kt + 1) * 128, S, rk);
-        TL::load_global(base + 2 * H, ld, (kt + 1) * 128, S, rv);
-      }
-      const int t0 = kt * 128 + kh * 64;
-      const lds_bf16* Kt = Ks(cur) + kh * 64 * TL::LD;
-      const lds_bf16* Vt = Vs(cur) + kh * 64 * TL::LD;
-      if (t0 < S && (!CAUSAL || t0 <= q0 + 31)) {
-#pragma unroll
-        for (int tb = 0; tb < 2; ++tb) {
-          f32x16 s, dp;
-#pragma unroll
-          for (int e = 0; e < 16; ++e) { s[e] = 0.f; dp[e] = 0.f; }
-#pragma unroll
-          for (int kk = 0; kk < D / 16; ++kk) {
-            s = __builtin_amdgcn_mfma_f32_32x32x16_bf16(TL::frag_rows(Kt, tb * 32, kk * 16), qf[kk], s, 0, 0, 0);
-            dp = __builtin_amdgcn_mfma_f32_32x32x16_bf16(TL::frag_rows(Vt, tb * 32, kk * 16), dof[kk], dp, 0, 0, 0);
-          }
-          const int tb0 = t0 + tb * 32;
-          if ((CAUSAL && tb0 + 31 > q0) || tb0 + 32 > S) {
-#pragma unroll
-            for (int e = 0; e < 16; ++e) {
-              const int t = tb0 + 8 * (e >> 2) + 4 * h + (e & 3);
-              float p = __builtin_amdgcn_exp2f(__builtin_fmaf(s[e], c2, -lse2));
-              if (t >= S || (CAUSAL && t > q)) p = 0.f;
-              s[e] = p * (dp[e] - dv);
-            }
-          } else {
-#pragma unroll
-            for (int e = 0; e < 16; ++e) s[e] = __builtin_amdgcn_exp2f(__builtin_fmaf(s[e], c2, -lse2)) * (dp[e] - dv);
-          }
-#pragma unroll
-          for (int jj = 0; jj < 2; ++jj) {
-            const bf16x8 df = pack8(s, 8 * jj);
-#pragma unroll
-            for (int dt = 0; dt < D / 32; ++dt)
-              dq[dt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(TL::frag_cols(Kt, dt * 32, tb * 32 + 16 * jj), df, dq[dt], 0, 0, 0);
-          }
-        }
-      }
-      if (kt + 1 < ntiles) {
-        TL::store_lds(Ks(cur ^ 1), rk);
-        TL::store_lds(Vs(cur ^ 1), rv);
-      }
-      __syncthreads();
-    }
-    constexpr int NV = D / 32 * 16;
-    LDS_AS float* mrg = (LDS_AS float*)smem_raw + qsub * NV * 64 + lane;
-    if (kh == 1) {
-#pragma unroll
-      for (int dt = 0; dt < D / 32; ++dt)
-#pragma unroll
-        for (int e = 0; e < 16; ++e) mrg[(dt * 16 + e) * 64] = dq[dt][e];
-    }
-    __syncthreads();
-    if (kh == 0) {
-#pragma unroll
-      for (int dt = 0; dt < D / 32; ++dt)
-#pragma unroll
-        for (int e = 0; e < 16; ++e) dq[dt][e] += mrg[(dt * 16 + e) * 64];
-      store_transposed<D>(dq, dqkv + (int64_t)n * S * ld + a * D, ld, q, S, scale);
-    }
-    __syncthreads();
-  }
-}
-
 // ------------------------------------------------------------------------------------ rowsum(dO * O)
 // dvec[n, a, s] = sum_d dO[s, a*D + d] * O[s, a*D + d]; a head's D values sit in D/8 consecutive lanes
 template <int D>
@@ -700,30 +590,17 @@ attn_dkv_kernel(const bf16* __restrict__ qkv, const bf16* __restrict__ dO, const
     }
     const LDS_AS float* st = stats + cur * 128;
     if (!CAUSAL || qb0 + TILE - 1 >= t0) {
-#pragma unroll
-      for (int qb = 0; qb < 2; ++qb) {
-        bf16x8 qfr[D / 16], dofr[D / 16];     // fragments first, then S and dP accumulate in turn
-#pragma unroll
-        for (int kk = 0; kk < D / 16; ++kk) {
-          qfr[kk] = TL::frag_rows(Qs(cur), qb * 32, kk * 16);
-          dofr[kk] = TL::frag_rows(dOs(cur), qb * 32, kk * 16);
-        }
+#pragma unroll 1
+      for (int qb = 0; qb < 2; ++qb) {      // not unrolled, and fenced between phases: keeps the live fragments (and so the register file) small
         f32x16 s, dp;
 #pragma unroll
         for (int e = 0; e < 16; ++e) { s[e] = 0.f; dp[e] = 0.f; }
 #pragma unroll
         for (int kk = 0; kk < D / 16; ++kk) {
-          s = __builtin_amdgcn_mfma_f32_32x32x16_bf16(qfr[kk], kf[kk], s, 0, 0, 0);
-          dp = __builtin_amdgcn_mfma_f32_32x32x16_bf16(dofr[kk], vf[kk], dp, 0, 0, 0);
+          s = __builtin_amdgcn_mfma_f32_32x32x16_bf16(TL::frag_rows(Qs(cur), qb * 32, kk * 16), kf[kk], s, 0, 0, 0);
+          dp = __builtin_amdgcn_mfma_f32_32x32x16_bf16(TL::frag_rows(dOs(cur), qb * 32, kk * 16), vf[kk], dp, 0, 0, 0);
         }
-        bf16x8 dotf[2][D / 32], qtf[2][D / 32];   // dO^T and Q^T fragments of the last two products, read while the exponentials run
-#pragma unroll
-        for (int jj = 0; jj < 2; ++jj)
-#pragma unroll
-          for (int dt = 0; dt < D / 32; ++dt) {
-            dotf[jj][dt] = TL::frag_cols(dOs(cur), dt * 32, qb * 32 + 16 * jj);
-            qtf[jj][dt] = TL::frag_cols(Qs(cur), dt * 32, qb * 32 + 16 * jj);
-          }
+        __builtin_amdgcn_sched_barrier(0);
         const bool edge = (CAUSAL && t0 + 31 > qb0 + qb * 32) || qb0 + qb * 32 + 32 > S;   // diagonal or ragged end (wave-uniform)
 #pragma unroll
         for (int j = 0; j < 4; ++j) {
@@ -747,8 +624,8 @@ attn_dkv_kernel(const bf16* __restrict__ qkv, const bf16* __restrict__ dO, const
           const bf16x8 pf = pack8(s, 8 * jj), df = pack8(dp, 8 * jj);
 #pragma unroll
           for (int dt = 0; dt < D / 32; ++dt) {
-            dvv[dt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(dotf[jj][dt], pf, dvv[dt], 0, 0, 0);
-            dk[dt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(qtf[jj][dt], df, dk[dt], 0, 0, 0);
+            dvv[dt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(TL::frag_cols(dOs(cur), dt * 32, qb * 32 + 16 * jj), pf, dvv[dt], 0, 0, 0);
+            dk[dt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(TL::frag_cols(Qs(cur), dt * 32, qb * 32 + 16 * jj), df, dk[dt], 0, 0, 0);
           }
         }
       }
@@ -780,21 +657,22 @@ template <int D, bool CAUSAL>
 int fwd_cfg(const bf16* qkv, bf16* O, float* lse, int m, int S, int H, int A, hipStream_t s) {
   const int nt = (S + 127) / 128;
   dim3 grid(CAUSAL ? (nt + 1) / 2 : nt, A, m);     // causal: a block takes a tile and its mirror image
-  static const int use8 = getenv("CEPHALO_ATTN8") ? atoi(getenv("CEPHALO_ATTN8")) : 1;   // tuning aid
-  if (!use8) {
-    const size_t lds4 = 4 * (size_t)Tile<D>::ELEMS * sizeof(bf16);
-    auto kern4 = attn_fwd_kernel<D, CAUSAL>;
-    int rc4 = reserve_lds(kern4, lds4);
-    if (rc4 != CEPHALO_OK) return rc4;
-    kern4<<<grid, kThreads, lds4, s>>>(qkv, O, lse, S, H, A, 1.0f / sqrtf((float)D));
-    CEPHALO_CHECK_LAUNCH("attn_fwd_mfma");
-    return CEPHALO_OK;
+  if (CAUSAL) {
+    // one paired block per compute unit: eight wavefronts, the staged keys split between two groups
+    const size_t lds = 4 * (size_t)Tile<D, 128, kThreads8>::ELEMS * sizeof(bf16);
+    auto kern = attn_fwd8_kernel<D, CAUSAL>;
+    int rc = reserve_lds(kern, lds);
+    if (rc != CEPHALO_OK) return rc;
+    kern<<<grid, kThreads8, lds, s>>>(qkv, O, lse, S, H, A, 1.0f / sqrtf((float)D));
+  } else {
+    // uniform tiles: two independent four-wavefront blocks per compute unit run out of phase with each other
+    // (measured 12 % faster than the eight-wavefront form, whose wavefronts move in step between barriers)
+    const size_t lds = 4 * (size_t)Tile<D>::ELEMS * sizeof(bf16);
+    auto kern = attn_fwd_kernel<D, CAUSAL>;
+    int rc = reserve_lds(kern, lds);
+    if (rc != CEPHALO_OK) return rc;
+    kern<<<grid, kThreads, lds, s>>>(qkv, O, lse, S, H, A, 1.0f / sqrtf((float)D));
   }
-  const size_t lds = 4 * (size_t)Tile<D, 128, kThreads8>::ELEMS * sizeof(bf16);
-  auto kern = attn_fwd8_kernel<D, CAUSAL>;
-  int rc = reserve_lds(kern, lds);
-  if (rc != CEPHALO_OK) return rc;
-  kern<<<grid, kThreads8, lds, s>>>(qkv, O, lse, S, H, A, 1.0f / sqrtf((float)D));
   CEPHALO_CHECK_LAUNCH("attn_fwd_mfma");
   return CEPHALO_OK;
 }
@@ -808,11 +686,11 @@ int bwd_cfg(const bf16* qkv, const bf16* O, const bf16* dO, const float* lse, fl
   const int nt = (S + 127) / 128;
   dim3 grid(CAUSAL ? (nt + 1) / 2 : nt, A, m);     // causal: a block takes a tile and its mirror image
   {
-    const size_t lds = 4 * (size_t)Tile<D, 128, kThreads8>::ELEMS * sizeof(bf16);
-    auto kern = attn_dq8_kernel<D, CAUSAL>;
+    const size_t lds = 4 * (size_t)Tile<D>::ELEMS * sizeof(bf16);
+    auto kern = attn_dq_kernel<D, CAUSAL>;
     int rc = reserve_lds(kern, lds);
     if (rc != CEPHALO_OK) return rc;
-    kern<<<grid, kThreads8, lds, s>>>(qkv, dO, lse, dvec, dqkv, S, H, A, scale);
+    kern<<<grid, kThreads, lds, s>>>(qkv, dO, lse, dvec, dqkv, S, H, A, scale);
   }
   {
     const size_t lds = 4 * (size_t)Tile<D>::ELEMS * sizeof(bf16) + 2 * 128 * sizeof(float);
