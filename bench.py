@@ -55,6 +55,8 @@ def main():
     ap.add_argument("--workload", default="c5", choices=["c1", "c2", "c3", "c4", "c5"])
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-legs", action="store_true", help="skip the per-kernel legs (whole step only)")
+    ap.add_argument("--checkpoint", action="store_true",
+                    help="c5 only: layer-boundary activation checkpointing with recomputation in the backward (one extra forward)")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build covers one GPU's share of the step; it has no collectives and runs on exactly "
@@ -77,7 +79,7 @@ def main():
 
     # ---- seeded inputs, generated on the host, then made resident in HBM
     if stack:
-        sd = C.stack_desc_from_config(cfg)
+        sd = C.stack_desc_from_config(cfg, checkpoint=args.checkpoint)
         desc = sd.layer
         P = C.cephalo_stack_param_count(sd)
         params = draw_stack_params(cfg)
@@ -138,6 +140,8 @@ def main():
     extras = {}
     if stack:
         extras["loss"] = round(float(loss.item()), 4)
+        extras["activation_checkpointing"] = bool(args.checkpoint)
+        extras["workspace_GB"] = round(ws.numel() / 1e9, 2)
     if bf16:
         extras["whole_step_model_tflops"] = round(step_flops / (elapsed / args.steps) / 1e12, 1)
         extras["whole_step_frac_of_bf16_peak"] = round(step_flops / (elapsed / args.steps) / 1e12 / PEAK_BF16_TFLOPS, 4)

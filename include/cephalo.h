@@ -209,8 +209,13 @@ int cephalo_op_attention_bwd(const cephalo_layer_desc* desc, const void* qkv, co
  */
 typedef struct cephalo_stack_desc {
   cephalo_layer_desc layer;
-  int32_t layers;   /* L */
-  int32_t vocab;    /* V */
+  int32_t layers;      /* L */
+  int32_t vocab;       /* V */
+  int32_t checkpoint;  /* 0: every layer's internal activations are kept from forward to backward (the default on a
+                          288 GB device).  1: activation checkpointing at layer boundaries (Sec. 3.2 "Activation
+                          Checkpointing and Offloading"): only the layer-boundary activations are kept, and the backward
+                          of a layer first runs that layer's forward again for all micro-batches.  Same results bit for
+                          bit; the work area holds one layer's internals instead of L; costs one extra forward. */
 } cephalo_stack_desc;
 
 /* V*H + S*H + L*P_layer + 2H; negative on a bad desc. */

@@ -36,11 +36,11 @@ def desc_from_config(cfg):
 
 
 class StackDesc(ctypes.Structure):
-    _fields_ = [("layer", LayerDesc), ("layers", ctypes.c_int32), ("vocab", ctypes.c_int32)]
+    _fields_ = [("layer", LayerDesc), ("layers", ctypes.c_int32), ("vocab", ctypes.c_int32), ("checkpoint", ctypes.c_int32)]
 
 
-def stack_desc_from_config(cfg):
-    return StackDesc(desc_from_config(cfg), int(cfg.layers), int(cfg.vocab))
+def stack_desc_from_config(cfg, checkpoint=False):
+    return StackDesc(desc_from_config(cfg), int(cfg.layers), int(cfg.vocab), int(bool(checkpoint)))
 
 
 _vp, _i32, _i64, _f32, _sz = ctypes.c_void_p, ctypes.c_int32, ctypes.c_int64, ctypes.c_float, ctypes.c_size_t

@@ -172,6 +172,7 @@ int check_stack(const cephalo_stack_desc* d) {
   if (!d) return fail(CEPHALO_EINVAL, "stack desc is null");
   TRY(check_desc(&d->layer));
   if (d->layers <= 0 || d->vocab <= 0) return fail(CEPHALO_EINVAL, "stack desc: layers %d and vocab %d must be positive", d->layers, d->vocab);
+  if (d->checkpoint != 0 && d->checkpoint != 1) return fail(CEPHALO_EINVAL, "stack desc: checkpoint must be 0 or 1");
   return CEPHALO_OK;
 }
 
@@ -200,7 +201,7 @@ StackLayout stack_layout(const cephalo_stack_desc& d, int b, int m) {
   auto take = [&](size_t bytes) { size_t at = p; p += align_up(bytes); return at; };
   L.xs = take((size_t)(d.layers + 1) * n * H * 4);      // layer-boundary activations: the fp32 residual stream
   L.save_each = align_up(save_layout(ld, b).total);
-  L.saves = take((size_t)d.layers * L.save_each);
+  L.saves = take((size_t)(d.checkpoint ? 1 : d.layers) * L.save_each);   // checkpointing: one layer's internals at a time
   L.scratch = take(scratch_layout(ld, m, b).total);
   L.dxa = take(n * H * 4); L.dxb = take(n * H * 4);     // gradient of the residual stream, ping-pong between layers
   L.dxal = es == 4 ? L.dxa : take(n * H * es); L.dxbl = es == 4 ? L.dxb : take(n * H * es);   // and its copy in the activation type
@@ -238,8 +239,9 @@ int run_stack(const cephalo_stack_desc& d, const void* Pv, const int* ids, const
   // ---- forward
   embed_fwd_kernel<T><<<(n + 3) / 4, kThreads, 0, s>>>(ids, P + o_wte, P + o_wpe, xs(0), n, S, H, V);
   CEPHALO_CHECK_LAUNCH("embed_fwd");
+  auto save_of = [&](int layer) { return at<char>(ws, L.saves + (d.checkpoint ? 0 : (size_t)layer * L.save_each)); };
   for (int li = 0; li < NL; ++li) {
-    void* save = at<char>(ws, L.saves + (size_t)li * L.save_each);
+    void* save = save_of(li);
     for (int j = 0; j < l; ++j)
       TRY(layer_fwd_t<T>(ld, P + o_layers + li * PL, xs(li) + j * act, xs(li + 1) + j * act, m, saved_at<T>(save, SL, ld, j * m), s));
   }
@@ -281,8 +283,12 @@ int run_stack(const cephalo_stack_desc& d, const void* Pv, const int* ids, const
   }
   // ---- backward through the layers
   for (int li = NL - 1; li >= 0; --li) {
-    void* save = at<char>(ws, L.saves + (size_t)li * L.save_each);
+    void* save = save_of(li);
     const T* Pl = P + o_layers + li * PL;
+    if (d.checkpoint && li != NL - 1) {   // recompute this layer's internals from its boundary input (the last layer's are still there);
+      for (int j = 0; j < l; ++j)         // its output is rewritten with the same values
+        TRY(layer_fwd_t<T>(ld, Pl, xs(li) + j * act, xs(li + 1) + j * act, m, saved_at<T>(save, SL, ld, j * m), s));
+    }
     TRY(prepare_dgrad_weights<T>(ld, Pl, work_at<T>(scratch, WL, ld, 0, 0, m).wT, s));
     for (int j = 0; j < l; ++j)
       TRY(layer_bwd_data_t<T>(ld, Pl, xs(li) + j * act, dx_cur + j * act, lowp_of<T>(dx_cur, dxl_cur) + j * act, dx_nxt + j * act,

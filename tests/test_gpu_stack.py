@@ -23,8 +23,8 @@ CASES = {
 }
 
 
-def run_gpu(cfg, params, ids, tgt, scale):
-    sd = C.stack_desc_from_config(cfg)
+def run_gpu(cfg, params, ids, tgt, scale, checkpoint=False):
+    sd = C.stack_desc_from_config(cfg, checkpoint)
     flat32 = torch.from_numpy(C.flatten_stack_params(sd, params)).cuda()
     if cfg.dtype == "bf16":
         flat = torch.empty(flat32.numel(), dtype=torch.bfloat16, device="cuda")
@@ -94,3 +94,18 @@ def test_stack_step_is_reproducible():
     a = run_gpu(cfg, params, ids, tgt, 1.0)
     b = run_gpu(cfg, params, ids, tgt, 1.0)
     assert a[0] == b[0] and np.array_equal(a[1], b[1])
+
+
+@pytest.mark.parametrize("case", ["bf16_mini", "f32_tiny", "bf16_deep6"])
+def test_activation_checkpointing_gives_identical_results_in_less_memory(case):
+    """Layer-boundary checkpointing with recomputation in the backward (Sec. 3.2): the same kernels on the same inputs,
+    so loss and every gradient element are bit-identical, and the work area holds one layer's internals instead of L."""
+    cfg = CASES[case]
+    params = draw_stack_params(cfg, perturbed=True)
+    ids, tgt = draw_token_ids(cfg)
+    a = run_gpu(cfg, params, ids, tgt, 1.25, checkpoint=False)
+    b = run_gpu(cfg, params, ids, tgt, 1.25, checkpoint=True)
+    assert a[0] == b[0] and np.array_equal(a[1], b[1])
+    full = C.cephalo_stack_workspace_bytes(C.stack_desc_from_config(cfg, False), cfg.batch_share, cfg.micro_batch)
+    ckpt = C.cephalo_stack_workspace_bytes(C.stack_desc_from_config(cfg, True), cfg.batch_share, cfg.micro_batch)
+    assert ckpt < full
