@@ -239,6 +239,45 @@ int cephalo_stack_step(const cephalo_stack_desc* desc, const void* flat_param,
                        float* flat_grad, float grad_scale, float* loss,
                        void* workspace, size_t workspace_bytes, void* stream);
 
+/* ---------------------------------------------------------------------------------------
+ * Planning on the host (no device involved): how the global batch and the training state are divided over the
+ * N GPUs of a cluster (Sec. 3.4 "Optimizer" and the supplementary Algorithm 1).
+ *
+ * The paper's notation table calls N, B "number of layers and GPUs"; the text and the algorithm use N = number of
+ * GPUs and B = global batch size, which is the reading here.  Its algorithm starts the search for the best final
+ * entry from 0 instead of infinity and writes the compute memory as M(m, l) although Sec. 3.3 makes it a function of
+ * m alone; this library starts from infinity, uses M(m) = mem_base + mem_per_sample * m, and keeps only those totals
+ * k of the micro-batch sizes whose cluster-wide memory fits (constraint III), as the text says.
+ */
+typedef struct cephalo_gpu_perf {
+  const double* t_fwd;   /* host, [max_m + 1]: forward latency of one micro-batch of m samples at index m (index 0 unused) */
+  const double* t_bwd;   /* likewise for the backward; sizes beyond max_m are extended linearly through the last two points */
+  int32_t max_m;
+  double  mem_cap;       /* bytes this GPU may use */
+} cephalo_gpu_perf;
+
+typedef struct cephalo_cluster_model {
+  double allgather, reducescatter;                /* latency of the even collectives of one unit            */
+  double allgather_uneven, reducescatter_uneven;  /* and with uneven inputs (Sec. 3.3: assumed 15 % slower)  */
+  double mem_base, mem_per_sample;                /* compute memory M(m) = mem_base + mem_per_sample * m     */
+  double state_bytes;                             /* training state of the model, 16 bytes per parameter     */
+} cephalo_cluster_model;
+
+/* Compute partition: micro-batch size m_i and micro-batch count l_i per GPU with sum_i m_i l_i = batch, minimising
+ *   max_i [ max(l_i T_f^i(m_i), AG') + max(l_i T_b^i(m_i), AG' + RS') ]
+ * where AG', RS' are the uneven latencies for a GPU whose compute memory plus an even state share exceeds its
+ * capacity; M(m_i) <= capacity_i for every GPU and the cluster-wide memory must fit.  Dynamic programme over
+ * (GPU, batch so far, sum of micro-batch sizes so far), O(N B^3 log B).  m_out, l_out: host, [n_gpus];
+ * latency_out (may be NULL): the minimised layer latency.  CEPHALO_EUNSUPPORTED if nothing fits. */
+int cephalo_plan_compute(int32_t n_gpus, const cephalo_gpu_perf* gpus, int32_t batch, const cephalo_cluster_model* cluster,
+                         int32_t* m_out, int32_t* l_out, double* latency_out);
+
+/* Training-state partition for given micro-batch sizes: ratios r_i (sum 1) that minimise the largest memory
+ * utilisation (compute memory + r_i * state) / capacity_i, by handing state to the least utilised GPU first.
+ * ratio_out: host, [n_gpus]. */
+int cephalo_plan_state(int32_t n_gpus, const cephalo_gpu_perf* gpus, const int32_t* m, const cephalo_cluster_model* cluster,
+                       double* ratio_out);
+
 #ifdef __cplusplus
 }
 #endif

@@ -43,6 +43,17 @@ def stack_desc_from_config(cfg, checkpoint=False):
     return StackDesc(desc_from_config(cfg), int(cfg.layers), int(cfg.vocab), int(bool(checkpoint)))
 
 
+class GpuPerf(ctypes.Structure):
+    _fields_ = [("t_fwd", ctypes.POINTER(ctypes.c_double)), ("t_bwd", ctypes.POINTER(ctypes.c_double)),
+                ("max_m", ctypes.c_int32), ("mem_cap", ctypes.c_double)]
+
+
+class ClusterModel(ctypes.Structure):
+    _fields_ = [("allgather", ctypes.c_double), ("reducescatter", ctypes.c_double),
+                ("allgather_uneven", ctypes.c_double), ("reducescatter_uneven", ctypes.c_double),
+                ("mem_base", ctypes.c_double), ("mem_per_sample", ctypes.c_double), ("state_bytes", ctypes.c_double)]
+
+
 _vp, _i32, _i64, _f32, _sz = ctypes.c_void_p, ctypes.c_int32, ctypes.c_int64, ctypes.c_float, ctypes.c_size_t
 _dp = ctypes.POINTER(LayerDesc)
 
@@ -67,6 +78,10 @@ SIGNATURES = {
                                        _vp, _f32, _i32, _vp]),
     "cephalo_op_linear_wgrad_workspace": (_sz, [_i32, _i32, _i32, _i32]),
     "cephalo_op_linear_wgrad": (ctypes.c_int, [_i32, _vp, _vp, _i32, _i32, _i32, _vp, _f32, _i32, _vp, _sz, _vp]),
+    "cephalo_plan_compute": (ctypes.c_int, [_i32, ctypes.POINTER(GpuPerf), _i32, ctypes.POINTER(ClusterModel),
+                                            ctypes.POINTER(_i32), ctypes.POINTER(_i32), ctypes.POINTER(ctypes.c_double)]),
+    "cephalo_plan_state": (ctypes.c_int, [_i32, ctypes.POINTER(GpuPerf), ctypes.POINTER(_i32), ctypes.POINTER(ClusterModel),
+                                          ctypes.POINTER(ctypes.c_double)]),
     "cephalo_op_attention_fwd": (ctypes.c_int, [_dp, _vp, _vp, _vp, _i32, _vp]),
     "cephalo_op_attention_bwd": (ctypes.c_int, [_dp, _vp, _vp, _vp, _vp, _vp, _vp, _i32, _vp]),
 }
@@ -259,3 +274,41 @@ def flatten_stack_params(sdesc, params):
         pos += t.size
     assert pos == P
     return flat
+
+
+def _gpu_perf_array(gpus):
+    """gpus: list of (t_fwd list indexed by m with [0] unused, t_bwd likewise, mem_cap).  Returns the ctypes array and
+    the buffers that must stay alive while it is in use."""
+    arr = (GpuPerf * len(gpus))()
+    keep = []
+    for i, (tf, tb, cap) in enumerate(gpus):
+        a = (ctypes.c_double * len(tf))(*tf)
+        b = (ctypes.c_double * len(tb))(*tb)
+        keep += [a, b]
+        arr[i] = GpuPerf(a, b, len(tf) - 1, float(cap))
+    return arr, keep
+
+
+def cluster_model(allgather, reducescatter, mem_base, mem_per_sample, state_bytes, uneven_factor=1.15):
+    """Sec. 3.3 "Communication Latency": uneven collectives are taken to be 15 % slower than even ones."""
+    return ClusterModel(allgather, reducescatter, allgather * uneven_factor, reducescatter * uneven_factor,
+                        mem_base, mem_per_sample, state_bytes)
+
+
+def cephalo_plan_compute(gpus, batch, cluster):
+    """Returns (m list, l list, layer latency)."""
+    arr, keep = _gpu_perf_array(gpus)
+    n = len(gpus)
+    m, l, lat = (_i32 * n)(), (_i32 * n)(), ctypes.c_double(0)
+    _check(lib().cephalo_plan_compute(n, arr, batch, ctypes.byref(cluster), m, l, ctypes.byref(lat)))
+    return list(m), list(l), lat.value
+
+
+def cephalo_plan_state(gpus, m, cluster):
+    """Returns the training-state ratios r_i."""
+    arr, keep = _gpu_perf_array(gpus)
+    n = len(gpus)
+    mm = (_i32 * n)(*m)
+    r = (ctypes.c_double * n)()
+    _check(lib().cephalo_plan_state(n, arr, mm, ctypes.byref(cluster), r))
+    return list(r)

@@ -1,0 +1,92 @@
+"""The host-side planner (compute partition by dynamic programming, training-state partition) against exhaustive
+search and a linear programme on tiny clusters.  No GPU involved."""
+import numpy as np
+import pytest
+
+import paper_2411_01075_amd as C
+from oracle import plan as oplan
+
+
+def random_cluster(rng, n, max_m):
+    gpus = []
+    for _ in range(n):
+        speed = rng.uniform(0.5, 3.0)
+        # latency per micro-batch: sub-linear for small m, then linear (Sec. 3.3, compute latency model)
+        tf = [0.0] + [speed * (0.6 + 0.8 * m + 0.3 * np.sqrt(m)) for m in range(1, max_m + 1)]
+        tb = [0.0] + [2.1 * t for t in tf[1:]]
+        gpus.append((tf, tb, float(rng.choice([12.0, 16.0, 24.0, 48.0]))))
+    return gpus
+
+
+@pytest.mark.parametrize("seed", range(12))
+def test_dp_matches_exhaustive_search(seed):
+    rng = np.random.default_rng(seed)
+    n = int(rng.integers(1, 4))
+    B = int(rng.integers(n, 7))
+    gpus = random_cluster(rng, n, max_m=int(rng.integers(2, 5)))
+    ag, rs = rng.uniform(0.5, 6.0), rng.uniform(0.5, 6.0)
+    mem_base, mem_per = rng.uniform(1.0, 6.0), rng.uniform(0.5, 4.0)
+    state = rng.uniform(5.0, 60.0)
+    cl = C.cluster_model(ag, rs, mem_base, mem_per, state)
+    ref, args = oplan.brute_force_plan(gpus, B, ag, rs, 1.15 * ag, 1.15 * rs, mem_base, mem_per, state)
+    if not np.isfinite(ref):
+        with pytest.raises(C.CephaloError, match="error -2"):
+            C.cephalo_plan_compute(gpus, B, cl)
+        return
+    m, l, lat = C.cephalo_plan_compute(gpus, B, cl)
+    assert abs(lat - ref) <= 1e-9 * ref
+    assert sum(a * b for a, b in zip(m, l)) == B and all(a >= 1 and b >= 1 for a, b in zip(m, l))
+    assert tuple(zip(m, l)) in [tuple(a) for a in args]          # the returned plan is one of the optima
+
+
+def test_uneven_gpus_get_uneven_batches():
+    """A GPU three times as fast takes about three times the batch (the point of Sec. 3.1's compute partitioning)."""
+    base = [0.0] + [1.0 * m for m in range(1, 9)]
+    slow = ([3 * t for t in base], [6 * t for t in base], 1e9)
+    fast = (base, [2 * t for t in base], 1e9)
+    m, l, lat = C.cephalo_plan_compute([fast, slow], 16, C.cluster_model(0.1, 0.1, 0.0, 1.0, 0.0))
+    assert m[0] * l[0] == 12 and m[1] * l[1] == 4
+    assert lat == pytest.approx(12 * 1.0 + 12 * 2.0)
+
+
+def test_memory_forces_gradient_accumulation():
+    """A small-memory GPU keeps its share of the batch by running more, smaller micro-batches (Sec. 3.2)."""
+    t = [0.0] + [1.0 * m for m in range(1, 9)]
+    g = (t, [2 * x for x in t], 3.5)          # compute memory 1 + 1 * m <= 3.5  =>  m <= 2
+    m, l, _ = C.cephalo_plan_compute([g, g], 12, C.cluster_model(0.1, 0.1, 1.0, 1.0, 0.5))
+    assert all(a <= 2 for a in m) and sum(a * b for a, b in zip(m, l)) == 12
+
+
+@pytest.mark.parametrize("seed", range(8))
+def test_state_partition_minimises_the_largest_utilisation(seed):
+    rng = np.random.default_rng(100 + seed)
+    n = int(rng.integers(2, 7))
+    gpus = random_cluster(rng, n, 4)
+    m = [int(rng.integers(1, 5)) for _ in range(n)]
+    mem_base, mem_per = rng.uniform(0.5, 3.0), rng.uniform(0.2, 2.0)
+    state = rng.uniform(1.0, 80.0)
+    r = C.cephalo_plan_state(gpus, m, C.cluster_model(1.0, 1.0, mem_base, mem_per, state))
+    assert abs(sum(r) - 1.0) < 1e-12 and min(r) >= 0.0
+    used = [mem_base + mem_per * mi for mi in m]
+    cap = [g[2] for g in gpus]
+    util = [(u + ri * state) / c for u, ri, c in zip(used, r, cap)]
+    assert max(util) <= oplan.min_max_utilisation(used, cap, state) * (1 + 1e-7)
+    # every GPU that holds state sits at the common level; the others are already above it
+    level = max(u for u, ri in zip(util, r) if ri > 0)
+    for u, ri in zip(util, r):
+        assert (ri > 0 and abs(u - level) < 1e-9) or (ri == 0 and u >= level - 1e-9)
+
+
+def test_state_ratio_can_be_none_or_all():
+    """"none of the training state to the entire training state" (Sec. 1): one roomy GPU takes everything."""
+    t = [0.0, 1.0, 2.0]
+    r = C.cephalo_plan_state([(t, t, 10.0), (t, t, 1000.0)], [2, 1], C.cluster_model(1, 1, 1.0, 2.0, 3.0))
+    assert r[0] == 0.0 and r[1] == 1.0
+
+
+def test_bad_arguments():
+    t = [0.0, 1.0]
+    with pytest.raises(C.CephaloError, match="error -1"):
+        C.cephalo_plan_compute([(t, t, 8.0)], 0, C.cluster_model(1, 1, 1, 1, 1))
+    with pytest.raises(C.CephaloError, match="error -1"):
+        C.cephalo_plan_compute([(t, t, -1.0)], 4, C.cluster_model(1, 1, 1, 1, 1))
