@@ -17,6 +17,9 @@ What it states (Cephalo, arXiv 2411.01075):
   * Sec. 2.1 / Sec. 3.3 "Memory Utilization Model": a transformer layer (self-attention +
     feed-forward) trained with Adam, 16 bytes of training state per parameter.
 
+  * Sec. 3.3 performance models (oracle.perfmodel) and Sec. 3.4 optimizer (oracle.plan: the
+    optimization problem by exhaustive search, the state partition as a linear programme).
+
 Because the method reproduces standard training exactly (Eq. 1 is an identity; sharding
 only moves where an element's update runs), every function here is the textbook
 definition written out, not a re-derivation of any kernel.
@@ -26,5 +29,7 @@ pure-Python triple loops on tiny shapes, closed forms for LayerNorm / softmax / 
 first-step Adam, torch.optim.Adam for the unsharded update, the micro-batch-sum and
 shard-partition invariants, and Eq. 1 with uneven shares.  The whole-stack loss value
 (oracle.stack) has no printed value in the paper to compare with: its pins are finite
-differences and autograd only.
+differences and autograd only.  oracle.perfmodel is pinned by closed forms of the line fit and
+by the latencies and memory the paper plots (tests/golden/); oracle.plan is the definition
+itself (every assignment enumerated), used on tiny clusters only.
 """
