@@ -12,6 +12,7 @@
 //   dK / dV      : S[q][t] = Q K^T    -> lane owns key t; rows q feed dV^T = dO^T P, dK^T = Q^T dS.
 // The other operand of those second products (V^T, K^T, dO^T, Q^T: d-major views of row-major
 // [token][d] tiles) is fetched from LDS with the transposing read ds_read_b64_tr_b16.
+#include <type_traits>
 #include "kernels.h"
 #include <cstdlib>
 
@@ -31,7 +32,12 @@ constexpr int TILE = 64;            // tokens per LDS tile
 constexpr float kLog2e = 1.44269504088896340736f;
 constexpr float kLn2 = 0.69314718055994530942f;
 
-// ROWS tokens by D values of one operand in LDS, staged through registers by THREADS threads.
+__device__ __forceinline__ __amdgpu_buffer_rsrc_t make_rsrc(const void* p, unsigned bytes) {
+  return __builtin_amdgcn_make_buffer_rsrc(const_cast<void*>(p), 0, bytes, 0x00020000);
+}
+
+// ROWS tokens by D values of one operand in LDS, staged by THREADS threads (through registers, or straight from
+// global memory).
 template <int D, int ROWS = TILE, int THREADS = kThreads> struct Tile {
   // Padded row (elements).  The row pitch in 4-byte banks, LD/2 mod 64, decides the conflicts of both kinds of read:
   // a 16-byte fragment read has 16 lanes on 16 consecutive rows, 4 banks each (the pitches 4, 12, 20, 36, ... spread
@@ -50,6 +56,25 @@ template <int D, int ROWS = TILE, int THREADS = kThreads> struct Tile {
       bf16x8 val = {0, 0, 0, 0, 0, 0, 0, 0};
       if (row0 + row < nrows) val = *reinterpret_cast<const bf16x8*>(g + (int64_t)(row0 + row) * ld + c);
       reg[p] = val;
+    }
+  }
+  // The same rows straight from global memory into LDS, no registers in between: one load instruction per row (64
+  // lanes x 2*D/64 bytes), so every row lands at its padded place.  rsrc covers one sample of the [*, ld_bytes/2]
+  // matrix, col_bytes is the head's column offset.  Rows >= nrows repeat row nrows-1 (finite values; callers mask them).
+  // The loads are asynchronous: wait for vmcnt(0) and a workgroup barrier before reading the tile.
+  // (A lane of such a load fills one 4-byte LDS slot whatever the load width, so this needs rows of 64 x 4 bytes;
+  // D = 64 keeps the register path.)
+  static constexpr bool DIRECT = D == 128;
+  static constexpr int NW = THREADS / 64, ROW_LOADS = ROWS / NW, LANE_BYTES = 4;
+  __device__ static void stage(__amdgpu_buffer_rsrc_t rsrc, unsigned col_bytes, unsigned ld_bytes, int row0, int nrows, lds_bf16* lds) {
+    static_assert(DIRECT, "rows of 256 bytes only");
+    const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+    const unsigned lane_off = (threadIdx.x & 63) * LANE_BYTES;
+#pragma unroll
+    for (int j = 0; j < ROW_LOADS; ++j) {
+      const int r = j * NW + wave;
+      const unsigned row = (unsigned)min(row0 + r, nrows - 1);
+      __builtin_amdgcn_raw_ptr_buffer_load_lds(rsrc, (LDS_AS void*)(lds + r * LD), 4, lane_off, row * ld_bytes + col_bytes, 0, 0);
     }
   }
   __device__ static void store_lds(lds_bf16* lds, const bf16x8 (&reg)[PER_THREAD]) {
@@ -93,6 +118,41 @@ __device__ void load_row_frags(const bf16* __restrict__ g, int64_t ld, int row0,
   }
 }
 
+// Order hint for a run of N1 products whose LDS fragment is R1 ds_read instructions each, followed by N2 products
+// with R2 reads each: the fragments of the first kAhead products are requested before the first product, then each
+// product is followed by the request for the product kAhead places later.  (Left alone, the compiler waits for each
+// fragment right before the product that uses it, and the matrix core idles for an LDS round trip every time.)
+template <int N1, int R1, int N2 = 0, int R2 = 0, int kAhead = 4>
+__device__ __forceinline__ void lds_ahead_schedule() {
+  constexpr int N = N1 + N2;
+  static_assert(N1 >= kAhead, "the first run covers the look-ahead");
+  __builtin_amdgcn_sched_group_barrier(0x100, kAhead * R1, 0);
+#pragma unroll
+  for (int i = 0; i < N; ++i) {
+    __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
+    if (i + kAhead < N1) __builtin_amdgcn_sched_group_barrier(0x100, R1, 0);
+    else if (i + kAhead < N) __builtin_amdgcn_sched_group_barrier(0x100, R2, 0);
+  }
+}
+
+// The same for a phase that also carries vector-unit work: PRE ds_read instructions that the vector work needs come
+// first, then every product is followed by VALU vector instructions and the request kAhead products ahead.
+constexpr int kValuPerMfma = 7;
+#ifndef DKV_PIPE
+#define DKV_PIPE 0
+#endif
+constexpr bool kDkvPipelined = DKV_PIPE;
+template <int N, int R, int PRE, int VALU, int kAhead = 4>
+__device__ __forceinline__ void mixed_schedule() {
+  __builtin_amdgcn_sched_group_barrier(0x100, PRE + kAhead * R, 0);
+#pragma unroll
+  for (int i = 0; i < N; ++i) {
+    __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
+    __builtin_amdgcn_sched_group_barrier(0x002, VALU, 0);
+    if (i + kAhead < N) __builtin_amdgcn_sched_group_barrier(0x100, R, 0);
+  }
+}
+
 __device__ __forceinline__ bf16x8 pack8(const f32x16& v, int e0) {
   bf16x8 r;
 #pragma unroll
@@ -127,7 +187,8 @@ attn_fwd_kernel(const bf16* __restrict__ qkv, bf16* __restrict__ O, float* __res
   auto Vs = [&](int st) { return smem + st * 2 * TL::ELEMS + TL::ELEMS; };
 
   const int a = blockIdx.y, n = blockIdx.z;
-  const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63, h = lane >> 5;
+  const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);   // scalar: tests on a wavefront's rows become real branches
+  const int lane = threadIdx.x & 63, h = lane >> 5;
   const int64_t ld = 3 * (int64_t)H;
   const bf16* base = qkv + (int64_t)n * S * ld + a * D;
   const float c2 = scale * kLog2e;
@@ -268,7 +329,8 @@ attn_fwd8_kernel(const bf16* __restrict__ qkv, bf16* __restrict__ O, float* __re
   auto Vs = [&](int st) { return smem + st * 2 * TL::ELEMS + TL::ELEMS; };
 
   const int a = blockIdx.y, n = blockIdx.z;
-  const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63, h = lane >> 5;
+  const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);   // scalar: tests on a wavefront's rows become real branches
+  const int lane = threadIdx.x & 63, h = lane >> 5;
   const int qsub = wave & 3, kh = wave >> 2;        // block of 32 queries, half of the staged keys
   const int64_t ld = 3 * (int64_t)H;
   const bf16* base = qkv + (int64_t)n * S * ld + a * D;
@@ -308,11 +370,6 @@ attn_fwd8_kernel(const bf16* __restrict__ qkv, bf16* __restrict__ O, float* __re
       const lds_bf16* Kt = Ks(cur) + kh * 64 * TL::LD;
       const lds_bf16* Vt = Vs(cur) + kh * 64 * TL::LD;
       if (t0 < S && (!CAUSAL || t0 <= q0 + 31)) {
-        bf16x8 kfr[2][D / 16];
-#pragma unroll
-        for (int kk = 0; kk < D / 16; ++kk)
-#pragma unroll
-          for (int tb = 0; tb < 2; ++tb) kfr[tb][kk] = TL::frag_rows(Kt, tb * 32, kk * 16);
         f32x16 s[2];
 #pragma unroll
         for (int tb = 0; tb < 2; ++tb)
@@ -321,8 +378,9 @@ attn_fwd8_kernel(const bf16* __restrict__ qkv, bf16* __restrict__ O, float* __re
 #pragma unroll
         for (int kk = 0; kk < D / 16; ++kk)
 #pragma unroll
-          for (int tb = 0; tb < 2; ++tb)
-            s[tb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kfr[tb][kk], qf[kk], s[tb], 0, 0, 0);
+          for (int tb = 0; tb < 2; ++tb)     // the two key blocks accumulate in turn: no dependent accumulator back to back
+            s[tb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(TL::frag_rows(Kt, tb * 32, kk * 16), qf[kk], s[tb], 0, 0, 0);
+        lds_ahead_schedule<D / 8, 1>();
         if ((CAUSAL && t0 + 63 > q0) || t0 + 64 > S) {      // diagonal or ragged end: per-element masking
 #pragma unroll
           for (int tb = 0; tb < 2; ++tb)
@@ -363,14 +421,12 @@ attn_fwd8_kernel(const bf16* __restrict__ qkv, bf16* __restrict__ O, float* __re
         for (int tb = 0; tb < 2; ++tb)
 #pragma unroll
           for (int jj = 0; jj < 2; ++jj) {
-            bf16x8 vfr[D / 32];
-#pragma unroll
-            for (int dt = 0; dt < D / 32; ++dt) vfr[dt] = TL::frag_cols(Vt, dt * 32, tb * 32 + 16 * jj);
             const bf16x8 pf = pack8(s[tb], 8 * jj);
 #pragma unroll
             for (int dt = 0; dt < D / 32; ++dt)
-              o[dt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vfr[dt], pf, o[dt], 0, 0, 0);
+              o[dt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(TL::frag_cols(Vt, dt * 32, tb * 32 + 16 * jj), pf, o[dt], 0, 0, 0);
           }
+        lds_ahead_schedule<D / 8, 2>();
       }
       if (kt + 1 < ntiles) {
         TL::store_lds(Ks(cur ^ 1), rk);
@@ -443,7 +499,8 @@ attn_dq_kernel(const bf16* __restrict__ qkv, const bf16* __restrict__ dO, const 
   auto Vs = [&](int st) { return smem + st * 2 * TL::ELEMS + TL::ELEMS; };
 
   const int a = blockIdx.y, n = blockIdx.z;
-  const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63, h = lane >> 5;
+  const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);   // scalar: tests on a wavefront's rows become real branches
+  const int lane = threadIdx.x & 63, h = lane >> 5;
   const int64_t ld = 3 * (int64_t)H;
   const bf16* base = qkv + (int64_t)n * S * ld + a * D;
   const float c2 = scale * kLog2e;
@@ -527,7 +584,7 @@ attn_dq_kernel(const bf16* __restrict__ qkv, const bf16* __restrict__ dO, const 
 
 // ------------------------------------------------------------------------------------ dK, dV
 template <int D, bool CAUSAL>
-__global__ void __launch_bounds__(kThreads)
+__global__ void __launch_bounds__(kThreads, 2)
 attn_dkv_kernel(const bf16* __restrict__ qkv, const bf16* __restrict__ dO, const float* __restrict__ lse,
                 const float* __restrict__ dvec, bf16* __restrict__ dqkv, int S, int H, int A, float scale) {
   typedef Tile<D> TL;
@@ -535,12 +592,22 @@ attn_dkv_kernel(const bf16* __restrict__ qkv, const bf16* __restrict__ dO, const
   lds_bf16* smem = (lds_bf16*)smem_raw;
   auto Qs = [&](int st) { return smem + st * 2 * TL::ELEMS; };
   auto dOs = [&](int st) { return smem + st * 2 * TL::ELEMS + TL::ELEMS; };
-  LDS_AS float* stats = (LDS_AS float*)(smem + 4 * TL::ELEMS);   // [2 buffers][lse2 | dvec][64]
+  // This block's 128 keys and values stay in LDS for the whole pass: held in registers (64 of them at D = 128) they
+  // push the kernel past 256, where the accumulators move to the second register file and every score has to be
+  // copied back for the vector unit.
+  typedef Tile<D, 128> TKV;
+  lds_bf16* Ks = smem + 4 * TL::ELEMS;
+  lds_bf16* Vs = Ks + TKV::ELEMS;
+  LDS_AS float* stats = (LDS_AS float*)(Vs + TKV::ELEMS);   // [2 buffers][lse2 | dvec][64]
 
   const int a = blockIdx.y, n = blockIdx.z;
-  const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63, h = lane >> 5;
+  const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);   // scalar: tests on a wavefront's rows become real branches
+  const int lane = threadIdx.x & 63, h = lane >> 5;
   const int64_t ld = 3 * (int64_t)H;
   const bf16* base = qkv + (int64_t)n * S * ld + a * D;
+  const __amdgpu_buffer_rsrc_t rs_qkv = make_rsrc(qkv + (int64_t)n * S * ld, (unsigned)(S * ld * 2));
+  const __amdgpu_buffer_rsrc_t rs_do = make_rsrc(dO + (int64_t)n * S * H, (unsigned)((int64_t)S * H * 2));
+  const unsigned col_bytes = (unsigned)(a * D * 2);
   const bf16* dObase = dO + (int64_t)n * S * H + a * D;
   const float* lse_base = lse + ((int64_t)n * A + a) * S;
   const float* dv_base = dvec + ((int64_t)n * A + a) * S;
@@ -552,9 +619,16 @@ attn_dkv_kernel(const bf16* __restrict__ qkv, const bf16* __restrict__ dO, const
   const int t0 = tt * 128 + wave * 32;             // this wavefront's 32 keys
   const int t = t0 + (lane & 31);
 
-  bf16x8 kf[D / 16], vf[D / 16];
-  load_row_frags<D>(base + H, ld, t0, S, kf);
-  load_row_frags<D>(base + 2 * H, ld, t0, S, vf);
+  if constexpr (TL::DIRECT) {
+    TKV::stage(rs_qkv, (unsigned)H * 2 + col_bytes, (unsigned)ld * 2, tt * 128, S, Ks);
+    TKV::stage(rs_qkv, (unsigned)H * 4 + col_bytes, (unsigned)ld * 2, tt * 128, S, Vs);
+  } else {
+    bf16x8 rkv[TKV::PER_THREAD];
+    TKV::load_global(base + H, ld, tt * 128, S, rkv);
+    TKV::store_lds(Ks, rkv);
+    TKV::load_global(base + 2 * H, ld, tt * 128, S, rkv);
+    TKV::store_lds(Vs, rkv);
+  }
 
   f32x16 dk[D / 32], dvv[D / 32];
 #pragma unroll
@@ -564,7 +638,6 @@ attn_dkv_kernel(const bf16* __restrict__ qkv, const bf16* __restrict__ dO, const
 
   const int first = CAUSAL ? (tt * 128) / TILE : 0;    // first query tile that can see these keys
   const int ntiles = (S + TILE - 1) / TILE;
-  bf16x8 rq[TL::PER_THREAD], rdo[TL::PER_THREAD];
   float rstat = 0.f;                                   // threads 0..63: lse2, 64..127: dvec
   auto load_stats = [&](int row0) {
     rstat = 0.f;
@@ -573,68 +646,136 @@ attn_dkv_kernel(const bf16* __restrict__ qkv, const bf16* __restrict__ dO, const
       if (r < S) rstat = threadIdx.x < 64 ? lse_base[r] * kLog2e : dv_base[r];
     }
   };
-  TL::load_global(base, ld, first * TILE, S, rq);
-  TL::load_global(dObase, H, first * TILE, S, rdo);
+  bf16x8 rq[TL::DIRECT ? 1 : TL::PER_THREAD], rdo[TL::DIRECT ? 1 : TL::PER_THREAD];   // register staging (D = 64)
+  if constexpr (TL::DIRECT) {
+    TL::stage(rs_qkv, col_bytes, (unsigned)ld * 2, first * TILE, S, Qs(0));
+    TL::stage(rs_do, col_bytes, (unsigned)H * 2, first * TILE, S, dOs(0));
+  } else {
+    TL::load_global(base, ld, first * TILE, S, rq);
+    TL::load_global(dObase, H, first * TILE, S, rdo);
+    TL::store_lds(Qs(0), rq);
+    TL::store_lds(dOs(0), rdo);
+  }
   load_stats(first * TILE);
-  TL::store_lds(Qs(0), rq);
-  TL::store_lds(dOs(0), rdo);
   if (threadIdx.x < 128) stats[threadIdx.x] = rstat;
+  __builtin_amdgcn_s_waitcnt(0x0F70);                  // vmcnt(0): this wavefront's rows have landed
   __syncthreads();
 
   for (int it = first; it < ntiles; ++it) {
     const int cur = (it - first) & 1, qb0 = it * TILE;
-    if (it + 1 < ntiles) {
-      TL::load_global(base, ld, qb0 + TILE, S, rq);
-      TL::load_global(dObase, H, qb0 + TILE, S, rdo);
+    if (it + 1 < ntiles) {                             // the next tile flies into the other stage meanwhile
+      if constexpr (TL::DIRECT) {
+        TL::stage(rs_qkv, col_bytes, (unsigned)ld * 2, qb0 + TILE, S, Qs(cur ^ 1));
+        TL::stage(rs_do, col_bytes, (unsigned)H * 2, qb0 + TILE, S, dOs(cur ^ 1));
+      } else {
+        TL::load_global(base, ld, qb0 + TILE, S, rq);
+        TL::load_global(dObase, H, qb0 + TILE, S, rdo);
+      }
       load_stats(qb0 + TILE);
     }
     const LDS_AS float* st = stats + cur * 128;
-    if (!CAUSAL || qb0 + TILE - 1 >= t0) {
-#pragma unroll 1
-      for (int qb = 0; qb < 2; ++qb) {      // not unrolled, and fenced between phases: keeps the live fragments (and so the register file) small
-        f32x16 s, dp;
+    // S and dP of 32 queries x this wavefront's 32 keys
+    auto scores = [&](int qb, f32x16& sc, f32x16& dp) {
 #pragma unroll
-        for (int e = 0; e < 16; ++e) { s[e] = 0.f; dp[e] = 0.f; }
+      for (int e = 0; e < 16; ++e) { sc[e] = 0.f; dp[e] = 0.f; }
 #pragma unroll
-        for (int kk = 0; kk < D / 16; ++kk) {
-          s = __builtin_amdgcn_mfma_f32_32x32x16_bf16(TL::frag_rows(Qs(cur), qb * 32, kk * 16), kf[kk], s, 0, 0, 0);
-          dp = __builtin_amdgcn_mfma_f32_32x32x16_bf16(TL::frag_rows(dOs(cur), qb * 32, kk * 16), vf[kk], dp, 0, 0, 0);
-        }
-        __builtin_amdgcn_sched_barrier(0);
-        const bool edge = (CAUSAL && t0 + 31 > qb0 + qb * 32) || qb0 + qb * 32 + 32 > S;   // diagonal or ragged end (wave-uniform)
+      for (int kk = 0; kk < D / 16; ++kk) {
+        sc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(TL::frag_rows(Qs(cur), qb * 32, kk * 16), TKV::frag_rows(Ks, wave * 32, kk * 16), sc, 0, 0, 0);
+        dp = __builtin_amdgcn_mfma_f32_32x32x16_bf16(TL::frag_rows(dOs(cur), qb * 32, kk * 16), TKV::frag_rows(Vs, wave * 32, kk * 16), dp, 0, 0, 0);
+      }
+    };
+    // P = exp2(S c2 - lse2) and dS = P (dP - dvec), as bf16 operands; MASKED: diagonal or ragged block
+    auto probabilities = [&](int qb, const f32x16& sc, const f32x16& dp, bf16x8 (&pf)[2], bf16x8 (&df)[2], auto masked) {
+      f32x16 pv, dsv;      // not written back into the MFMA results: those may live in the accumulator file
 #pragma unroll
-        for (int j = 0; j < 4; ++j) {
-          const int r = qb * 32 + 8 * j + 4 * h;       // 4 consecutive query rows
-          const f32x4 l4 = *reinterpret_cast<const LDS_AS f32x4*>(st + r);
-          const f32x4 d4 = *reinterpret_cast<const LDS_AS f32x4*>(st + 64 + r);
+      for (int j = 0; j < 4; ++j) {
+        const int r = qb * 32 + 8 * j + 4 * h;         // 4 consecutive query rows
+        const f32x4 l4 = *reinterpret_cast<const LDS_AS f32x4*>(st + r);
+        const f32x4 d4 = *reinterpret_cast<const LDS_AS f32x4*>(st + 64 + r);
 #pragma unroll
-          for (int i = 0; i < 4; ++i) {
-            const int e = 4 * j + i;
-            float p = __builtin_amdgcn_exp2f(__builtin_fmaf(s[e], c2, -l4[i]));
-            if (edge) {
-              const int qq = qb0 + r + i;
-              if (qq >= S || (CAUSAL && t > qq)) p = 0.f;
-            }
-            s[e] = p;                                  // P
-            dp[e] = p * (dp[e] - d4[i]);               // dS
+        for (int i = 0; i < 4; ++i) {
+          const int e = 4 * j + i;
+          float p = __builtin_amdgcn_exp2f(__builtin_fmaf(sc[e], c2, -l4[i]));
+          if (decltype(masked)::value) {
+            const int qq = qb0 + r + i;
+            if (qq >= S || (CAUSAL && t > qq)) p = 0.f;
           }
-        }
-#pragma unroll
-        for (int jj = 0; jj < 2; ++jj) {
-          const bf16x8 pf = pack8(s, 8 * jj), df = pack8(dp, 8 * jj);
-#pragma unroll
-          for (int dt = 0; dt < D / 32; ++dt) {
-            dvv[dt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(TL::frag_cols(dOs(cur), dt * 32, qb * 32 + 16 * jj), pf, dvv[dt], 0, 0, 0);
-            dk[dt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(TL::frag_cols(Qs(cur), dt * 32, qb * 32 + 16 * jj), df, dk[dt], 0, 0, 0);
-          }
+          pv[e] = p;
+          dsv[e] = p * (dp[e] - d4[i]);
         }
       }
+#pragma unroll
+      for (int jj = 0; jj < 2; ++jj) { pf[jj] = pack8(pv, 8 * jj); df[jj] = pack8(dsv, 8 * jj); }
+    };
+    // dV += P^T dO, dK += dS^T Q over the block's 32 queries
+    auto accumulate = [&](int qb, const bf16x8 (&pf)[2], const bf16x8 (&df)[2]) {
+#pragma unroll
+      for (int jj = 0; jj < 2; ++jj)
+#pragma unroll
+        for (int dt = 0; dt < D / 32; ++dt) {
+          dvv[dt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(TL::frag_cols(dOs(cur), dt * 32, qb * 32 + 16 * jj), pf[jj], dvv[dt], 0, 0, 0);
+          dk[dt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(TL::frag_cols(Qs(cur), dt * 32, qb * 32 + 16 * jj), df[jj], dk[dt], 0, 0, 0);
+        }
+    };
+    constexpr int NP = D / 8;                         // products per phase
+    if (!CAUSAL || qb0 + TILE - 1 >= t0) {
+      const bool edge = (CAUSAL && t0 + 31 > qb0) || qb0 + TILE > S;   // the tile touches the diagonal or the ragged end (wave-uniform)
+      if (!kDkvPipelined) {
+#pragma unroll 1
+        for (int qb = 0; qb < 2; ++qb) {
+          f32x16 sc, dp;
+          bf16x8 pf[2], df[2];
+          scores(qb, sc, dp);
+          lds_ahead_schedule<NP, 2>();
+          __builtin_amdgcn_sched_barrier(0);
+          if (edge) probabilities(qb, sc, dp, pf, df, std::true_type());
+          else probabilities(qb, sc, dp, pf, df, std::false_type());
+          accumulate(qb, pf, df);
+          lds_ahead_schedule<NP, 2>();
+          __builtin_amdgcn_sched_barrier(0);
+        }
+      } else if (edge) {
+#pragma unroll 1
+        for (int qb = 0; qb < 2; ++qb) {               // rare: one block at a time, masked
+          f32x16 sc, dp;
+          bf16x8 pf[2], df[2];
+          scores(qb, sc, dp);
+          lds_ahead_schedule<NP, 2>();
+          __builtin_amdgcn_sched_barrier(0);
+          probabilities(qb, sc, dp, pf, df, std::true_type());
+          accumulate(qb, pf, df);
+          lds_ahead_schedule<NP, 2>();
+          __builtin_amdgcn_sched_barrier(0);
+        }
+      } else {
+        // Interior tile: the vector-unit work of one block of 32 queries runs under the MFMAs of its neighbours
+        //   scores(0) | probabilities(0) + scores(1) | accumulate(0) + probabilities(1) | accumulate(1)
+        f32x16 s0, dp0, s1, dp1;
+        bf16x8 pf0[2], df0[2], pf1[2], df1[2];
+        scores(0, s0, dp0);
+        lds_ahead_schedule<NP, 2>();
+        __builtin_amdgcn_sched_barrier(0);
+        probabilities(0, s0, dp0, pf0, df0, std::false_type());
+        scores(1, s1, dp1);
+        mixed_schedule<NP, 2, 8, kValuPerMfma>();
+        __builtin_amdgcn_sched_barrier(0);
+        probabilities(1, s1, dp1, pf1, df1, std::false_type());
+        accumulate(0, pf0, df0);
+        mixed_schedule<NP, 2, 8, kValuPerMfma>();
+        __builtin_amdgcn_sched_barrier(0);
+        accumulate(1, pf1, df1);
+        lds_ahead_schedule<NP, 2>();
+        __builtin_amdgcn_sched_barrier(0);
+      }
     }
-    if (it + 1 < ntiles) {
-      TL::store_lds(Qs(cur ^ 1), rq);
-      TL::store_lds(dOs(cur ^ 1), rdo);
-      if (threadIdx.x < 128) stats[(cur ^ 1) * 128 + threadIdx.x] = rstat;
+    if constexpr (!TL::DIRECT) {
+      if (it + 1 < ntiles) {
+        TL::store_lds(Qs(cur ^ 1), rq);
+        TL::store_lds(dOs(cur ^ 1), rdo);
+      }
     }
+    if (it + 1 < ntiles && threadIdx.x < 128) stats[(cur ^ 1) * 128 + threadIdx.x] = rstat;
+    __builtin_amdgcn_s_waitcnt(0x0F70);                // vmcnt(0)
     __syncthreads();
   }
   bf16* out = dqkv + (int64_t)n * S * ld + a * D;
@@ -693,7 +834,7 @@ int bwd_cfg(const bf16* qkv, const bf16* O, const bf16* dO, const float* lse, fl
     kern<<<grid, kThreads, lds, s>>>(qkv, dO, lse, dvec, dqkv, S, H, A, scale);
   }
   {
-    const size_t lds = 4 * (size_t)Tile<D>::ELEMS * sizeof(bf16) + 2 * 128 * sizeof(float);
+    const size_t lds = (4 * (size_t)Tile<D>::ELEMS + 2 * (size_t)Tile<D, 128>::ELEMS) * sizeof(bf16) + 2 * 128 * sizeof(float);
     auto kern = attn_dkv_kernel<D, CAUSAL>;
     int rc = reserve_lds(kern, lds);
     if (rc != CEPHALO_OK) return rc;
@@ -718,6 +859,8 @@ int launch_attn_bwd_mfma(const bf16* qkv, const bf16* O, const bf16* dO, const f
   const int D = H / A;
   if (H % 8 != 0 || !aligned16(qkv) || !aligned16(O) || !aligned16(dO) || !aligned16(dqkv))
     return fail(CEPHALO_EINVAL, "attention: rows must be 16-byte aligned");
+  if ((int64_t)S * 3 * H * 2 >= (int64_t)1 << 31)
+    return fail(CEPHALO_EUNSUPPORTED, "attention: one sample of qkv (%lld bytes) exceeds the 2 GiB a buffer offset reaches", (long long)S * 3 * H * 2);
   if (D == 64)
     return causal ? bwd_cfg<64, true>(qkv, O, dO, lse, dvec, dqkv, m, S, H, A, s)
                   : bwd_cfg<64, false>(qkv, O, dO, lse, dvec, dqkv, m, S, H, A, s);
