@@ -135,24 +135,6 @@ __device__ __forceinline__ void lds_ahead_schedule() {
   }
 }
 
-// The same for a phase that also carries vector-unit work: PRE ds_read instructions that the vector work needs come
-// first, then every product is followed by VALU vector instructions and the request kAhead products ahead.
-constexpr int kValuPerMfma = 7;
-#ifndef DKV_PIPE
-#define DKV_PIPE 0
-#endif
-constexpr bool kDkvPipelined = DKV_PIPE;
-template <int N, int R, int PRE, int VALU, int kAhead = 4>
-__device__ __forceinline__ void mixed_schedule() {
-  __builtin_amdgcn_sched_group_barrier(0x100, PRE + kAhead * R, 0);
-#pragma unroll
-  for (int i = 0; i < N; ++i) {
-    __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
-    __builtin_amdgcn_sched_group_barrier(0x002, VALU, 0);
-    if (i + kAhead < N) __builtin_amdgcn_sched_group_barrier(0x100, R, 0);
-  }
-}
-
 __device__ __forceinline__ bf16x8 pack8(const f32x16& v, int e0) {
   bf16x8 r;
 #pragma unroll
@@ -583,19 +565,24 @@ attn_dq_kernel(const bf16* __restrict__ qkv, const bf16* __restrict__ dO, const 
 }
 
 // ------------------------------------------------------------------------------------ dK, dV
+// A block owns 128 keys (causal: tile x, then its mirror tile) and walks the query tiles that see them.  Eight
+// wavefronts: wavefront w takes the 32 keys of group w & 3 and, of every 64-query tile, the 32 queries of half w >> 2,
+// so the two wavefronts of a SIMD work on different halves and one's exponentials run under the other's MFMAs.  Each
+// half accumulates its own dK and dV; at the end of the pass the second half hands its sums over through LDS.
+//
+// The block's keys and values stay in LDS for the whole pass: held in registers (64 of them at D = 128) they push the
+// kernel past 256 registers, where the accumulators move to the second register file and every score has to be copied
+// back for the vector unit.  Query and dO tiles are double-buffered; at D = 128 they come straight from global memory.
 template <int D, bool CAUSAL>
-__global__ void __launch_bounds__(kThreads, 2)
+__global__ void __launch_bounds__(kThreads8)
 attn_dkv_kernel(const bf16* __restrict__ qkv, const bf16* __restrict__ dO, const float* __restrict__ lse,
                 const float* __restrict__ dvec, bf16* __restrict__ dqkv, int S, int H, int A, float scale) {
-  typedef Tile<D> TL;
+  typedef Tile<D, TILE, kThreads8> TL;
+  typedef Tile<D, 128, kThreads8> TKV;
   extern __shared__ __attribute__((aligned(16))) char smem_raw[];
   lds_bf16* smem = (lds_bf16*)smem_raw;
   auto Qs = [&](int st) { return smem + st * 2 * TL::ELEMS; };
   auto dOs = [&](int st) { return smem + st * 2 * TL::ELEMS + TL::ELEMS; };
-  // This block's 128 keys and values stay in LDS for the whole pass: held in registers (64 of them at D = 128) they
-  // push the kernel past 256, where the accumulators move to the second register file and every score has to be
-  // copied back for the vector unit.
-  typedef Tile<D, 128> TKV;
   lds_bf16* Ks = smem + 4 * TL::ELEMS;
   lds_bf16* Vs = Ks + TKV::ELEMS;
   LDS_AS float* stats = (LDS_AS float*)(Vs + TKV::ELEMS);   // [2 buffers][lse2 | dvec][64]
@@ -603,12 +590,13 @@ attn_dkv_kernel(const bf16* __restrict__ qkv, const bf16* __restrict__ dO, const
   const int a = blockIdx.y, n = blockIdx.z;
   const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);   // scalar: tests on a wavefront's rows become real branches
   const int lane = threadIdx.x & 63, h = lane >> 5;
+  const int kg = wave & 3, qh = wave >> 2;          // group of 32 keys, half of the query tile
   const int64_t ld = 3 * (int64_t)H;
   const bf16* base = qkv + (int64_t)n * S * ld + a * D;
+  const bf16* dObase = dO + (int64_t)n * S * H + a * D;
   const __amdgpu_buffer_rsrc_t rs_qkv = make_rsrc(qkv + (int64_t)n * S * ld, (unsigned)(S * ld * 2));
   const __amdgpu_buffer_rsrc_t rs_do = make_rsrc(dO + (int64_t)n * S * H, (unsigned)((int64_t)S * H * 2));
   const unsigned col_bytes = (unsigned)(a * D * 2);
-  const bf16* dObase = dO + (int64_t)n * S * H + a * D;
   const float* lse_base = lse + ((int64_t)n * A + a) * S;
   const float* dv_base = dvec + ((int64_t)n * A + a) * S;
   const float c2 = scale * kLog2e;
@@ -616,7 +604,7 @@ attn_dkv_kernel(const bf16* __restrict__ qkv, const bf16* __restrict__ dO, const
   for (int pass = 0; pass < (CAUSAL ? 2 : 1); ++pass) {
   const int tt = pass == 0 ? (int)blockIdx.x : ntk - 1 - (int)blockIdx.x;
   if (pass == 1 && tt == (int)blockIdx.x) break;
-  const int t0 = tt * 128 + wave * 32;             // this wavefront's 32 keys
+  const int t0 = tt * 128 + kg * 32;               // this wavefront's 32 keys
   const int t = t0 + (lane & 31);
 
   if constexpr (TL::DIRECT) {
@@ -674,99 +662,54 @@ attn_dkv_kernel(const bf16* __restrict__ qkv, const bf16* __restrict__ dO, const
       load_stats(qb0 + TILE);
     }
     const LDS_AS float* st = stats + cur * 128;
-    // S and dP of 32 queries x this wavefront's 32 keys
-    auto scores = [&](int qb, f32x16& sc, f32x16& dp) {
+    const int q0 = qb0 + qh * 32;                      // this wavefront's 32 queries
+    if (!CAUSAL || q0 + 31 >= t0) {
+      constexpr int NP = D / 8;                        // products per phase
+      // S and dP of the 32 queries x 32 keys
+      f32x16 sc, dp;
 #pragma unroll
       for (int e = 0; e < 16; ++e) { sc[e] = 0.f; dp[e] = 0.f; }
 #pragma unroll
       for (int kk = 0; kk < D / 16; ++kk) {
-        sc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(TL::frag_rows(Qs(cur), qb * 32, kk * 16), TKV::frag_rows(Ks, wave * 32, kk * 16), sc, 0, 0, 0);
-        dp = __builtin_amdgcn_mfma_f32_32x32x16_bf16(TL::frag_rows(dOs(cur), qb * 32, kk * 16), TKV::frag_rows(Vs, wave * 32, kk * 16), dp, 0, 0, 0);
+        sc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(TL::frag_rows(Qs(cur), qh * 32, kk * 16), TKV::frag_rows(Ks, kg * 32, kk * 16), sc, 0, 0, 0);
+        dp = __builtin_amdgcn_mfma_f32_32x32x16_bf16(TL::frag_rows(dOs(cur), qh * 32, kk * 16), TKV::frag_rows(Vs, kg * 32, kk * 16), dp, 0, 0, 0);
       }
-    };
-    // P = exp2(S c2 - lse2) and dS = P (dP - dvec), as bf16 operands; MASKED: diagonal or ragged block
-    auto probabilities = [&](int qb, const f32x16& sc, const f32x16& dp, bf16x8 (&pf)[2], bf16x8 (&df)[2], auto masked) {
-      f32x16 pv, dsv;      // not written back into the MFMA results: those may live in the accumulator file
+      lds_ahead_schedule<NP, 2>();
+      __builtin_amdgcn_sched_barrier(0);
+      // P = exp2(S c2 - lse2) and dS = P (dP - dvec) as bf16 operands.  They are not written back into the MFMA results.
+      f32x16 pv, dsv;
 #pragma unroll
       for (int j = 0; j < 4; ++j) {
-        const int r = qb * 32 + 8 * j + 4 * h;         // 4 consecutive query rows
+        const int r = qh * 32 + 8 * j + 4 * h;         // 4 consecutive query rows
         const f32x4 l4 = *reinterpret_cast<const LDS_AS f32x4*>(st + r);
         const f32x4 d4 = *reinterpret_cast<const LDS_AS f32x4*>(st + 64 + r);
 #pragma unroll
         for (int i = 0; i < 4; ++i) {
           const int e = 4 * j + i;
-          float p = __builtin_amdgcn_exp2f(__builtin_fmaf(sc[e], c2, -l4[i]));
-          if (decltype(masked)::value) {
-            const int qq = qb0 + r + i;
-            if (qq >= S || (CAUSAL && t > qq)) p = 0.f;
-          }
-          pv[e] = p;
-          dsv[e] = p * (dp[e] - d4[i]);
+          pv[e] = __builtin_amdgcn_exp2f(__builtin_fmaf(sc[e], c2, -l4[i]));
+          dsv[e] = dp[e] - d4[i];
+        }
+      }
+      if ((CAUSAL && t0 + 31 > q0) || q0 + 32 > S) {    // diagonal or ragged end (wave-uniform): one branch around all the masking
+#pragma unroll
+        for (int e = 0; e < 16; ++e) {
+          const int qq = q0 + 8 * (e >> 2) + 4 * h + (e & 3);
+          if (qq >= S || (CAUSAL && t > qq)) pv[e] = 0.f;
         }
       }
 #pragma unroll
-      for (int jj = 0; jj < 2; ++jj) { pf[jj] = pack8(pv, 8 * jj); df[jj] = pack8(dsv, 8 * jj); }
-    };
-    // dV += P^T dO, dK += dS^T Q over the block's 32 queries
-    auto accumulate = [&](int qb, const bf16x8 (&pf)[2], const bf16x8 (&df)[2]) {
+      for (int e = 0; e < 16; ++e) dsv[e] *= pv[e];
+      // dV += P^T dO, dK += dS^T Q
 #pragma unroll
-      for (int jj = 0; jj < 2; ++jj)
+      for (int jj = 0; jj < 2; ++jj) {
+        const bf16x8 pf = pack8(pv, 8 * jj), df = pack8(dsv, 8 * jj);
 #pragma unroll
         for (int dt = 0; dt < D / 32; ++dt) {
-          dvv[dt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(TL::frag_cols(dOs(cur), dt * 32, qb * 32 + 16 * jj), pf[jj], dvv[dt], 0, 0, 0);
-          dk[dt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(TL::frag_cols(Qs(cur), dt * 32, qb * 32 + 16 * jj), df[jj], dk[dt], 0, 0, 0);
+          dvv[dt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(TL::frag_cols(dOs(cur), dt * 32, qh * 32 + 16 * jj), pf, dvv[dt], 0, 0, 0);
+          dk[dt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(TL::frag_cols(Qs(cur), dt * 32, qh * 32 + 16 * jj), df, dk[dt], 0, 0, 0);
         }
-    };
-    constexpr int NP = D / 8;                         // products per phase
-    if (!CAUSAL || qb0 + TILE - 1 >= t0) {
-      const bool edge = (CAUSAL && t0 + 31 > qb0) || qb0 + TILE > S;   // the tile touches the diagonal or the ragged end (wave-uniform)
-      if (!kDkvPipelined) {
-#pragma unroll 1
-        for (int qb = 0; qb < 2; ++qb) {
-          f32x16 sc, dp;
-          bf16x8 pf[2], df[2];
-          scores(qb, sc, dp);
-          lds_ahead_schedule<NP, 2>();
-          __builtin_amdgcn_sched_barrier(0);
-          if (edge) probabilities(qb, sc, dp, pf, df, std::true_type());
-          else probabilities(qb, sc, dp, pf, df, std::false_type());
-          accumulate(qb, pf, df);
-          lds_ahead_schedule<NP, 2>();
-          __builtin_amdgcn_sched_barrier(0);
-        }
-      } else if (edge) {
-#pragma unroll 1
-        for (int qb = 0; qb < 2; ++qb) {               // rare: one block at a time, masked
-          f32x16 sc, dp;
-          bf16x8 pf[2], df[2];
-          scores(qb, sc, dp);
-          lds_ahead_schedule<NP, 2>();
-          __builtin_amdgcn_sched_barrier(0);
-          probabilities(qb, sc, dp, pf, df, std::true_type());
-          accumulate(qb, pf, df);
-          lds_ahead_schedule<NP, 2>();
-          __builtin_amdgcn_sched_barrier(0);
-        }
-      } else {
-        // Interior tile: the vector-unit work of one block of 32 queries runs under the MFMAs of its neighbours
-        //   scores(0) | probabilities(0) + scores(1) | accumulate(0) + probabilities(1) | accumulate(1)
-        f32x16 s0, dp0, s1, dp1;
-        bf16x8 pf0[2], df0[2], pf1[2], df1[2];
-        scores(0, s0, dp0);
-        lds_ahead_schedule<NP, 2>();
-        __builtin_amdgcn_sched_barrier(0);
-        probabilities(0, s0, dp0, pf0, df0, std::false_type());
-        scores(1, s1, dp1);
-        mixed_schedule<NP, 2, 8, kValuPerMfma>();
-        __builtin_amdgcn_sched_barrier(0);
-        probabilities(1, s1, dp1, pf1, df1, std::false_type());
-        accumulate(0, pf0, df0);
-        mixed_schedule<NP, 2, 8, kValuPerMfma>();
-        __builtin_amdgcn_sched_barrier(0);
-        accumulate(1, pf1, df1);
-        lds_ahead_schedule<NP, 2>();
-        __builtin_amdgcn_sched_barrier(0);
       }
+      lds_ahead_schedule<NP, 2>();
     }
     if constexpr (!TL::DIRECT) {
       if (it + 1 < ntiles) {
@@ -778,9 +721,32 @@ attn_dkv_kernel(const bf16* __restrict__ qkv, const bf16* __restrict__ dO, const
     __builtin_amdgcn_s_waitcnt(0x0F70);                // vmcnt(0)
     __syncthreads();
   }
-  bf16* out = dqkv + (int64_t)n * S * ld + a * D;
-  store_transposed<D>(dk, out + H, ld, t, S, scale);
-  store_transposed<D>(dvv, out + 2 * H, ld, t, S, 1.0f);
+  // the second half's sums go through LDS ([key group][value][lane], lanes contiguous) and the first half stores
+  constexpr int NV = D / 32 * 16 * 2;
+  LDS_AS float* mrg = (LDS_AS float*)smem_raw + kg * NV * 64 + lane;
+  if (qh == 1) {
+#pragma unroll
+    for (int dt = 0; dt < D / 32; ++dt)
+#pragma unroll
+      for (int e = 0; e < 16; ++e) {
+        mrg[(dt * 16 + e) * 64] = dk[dt][e];
+        mrg[(NV / 2 + dt * 16 + e) * 64] = dvv[dt][e];
+      }
+  }
+  __syncthreads();
+  if (qh == 0) {
+#pragma unroll
+    for (int dt = 0; dt < D / 32; ++dt)
+#pragma unroll
+      for (int e = 0; e < 16; ++e) {
+        dk[dt][e] += mrg[(dt * 16 + e) * 64];
+        dvv[dt][e] += mrg[(NV / 2 + dt * 16 + e) * 64];
+      }
+    bf16* out = dqkv + (int64_t)n * S * ld + a * D;
+    store_transposed<D>(dk, out + H, ld, t, S, scale);
+    store_transposed<D>(dvv, out + 2 * H, ld, t, S, 1.0f);
+  }
+  __syncthreads();     // the merge area is staged over again by the next pass
   }   // pass
 }
 
@@ -834,11 +800,14 @@ int bwd_cfg(const bf16* qkv, const bf16* O, const bf16* dO, const float* lse, fl
     kern<<<grid, kThreads, lds, s>>>(qkv, dO, lse, dvec, dqkv, S, H, A, scale);
   }
   {
-    const size_t lds = (4 * (size_t)Tile<D>::ELEMS + 2 * (size_t)Tile<D, 128>::ELEMS) * sizeof(bf16) + 2 * 128 * sizeof(float);
+    // staging (2 stages of Q and dO, the keys, the values, the row statistics) or, at the end, the merge of the halves
+    const size_t staging = (4 * (size_t)Tile<D>::ELEMS + 2 * (size_t)Tile<D, 128>::ELEMS) * sizeof(bf16) + 2 * 128 * sizeof(float);
+    const size_t merge = (size_t)4 * (D / 32 * 16 * 2) * 64 * sizeof(float);
+    const size_t lds = staging > merge ? staging : merge;
     auto kern = attn_dkv_kernel<D, CAUSAL>;
     int rc = reserve_lds(kern, lds);
     if (rc != CEPHALO_OK) return rc;
-    kern<<<grid, kThreads, lds, s>>>(qkv, dO, lse, dvec, dqkv, S, H, A, scale);
+    kern<<<grid, kThreads8, lds, s>>>(qkv, dO, lse, dvec, dqkv, S, H, A, scale);
   }
   CEPHALO_CHECK_LAUNCH("attn_bwd_mfma");
   return CEPHALO_OK;
