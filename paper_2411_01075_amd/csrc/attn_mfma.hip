@@ -316,6 +316,8 @@ attn_fwd8_kernel(const bf16* __restrict__ qkv, bf16* __restrict__ O, float* __re
   const int qsub = wave & 3, kh = wave >> 2;        // block of 32 queries, half of the staged keys
   const int64_t ld = 3 * (int64_t)H;
   const bf16* base = qkv + (int64_t)n * S * ld + a * D;
+  const __amdgpu_buffer_rsrc_t rs_qkv = make_rsrc(qkv + (int64_t)n * S * ld, (unsigned)(S * ld * 2));
+  const unsigned k_bytes = (unsigned)((H + a * D) * 2), v_bytes = (unsigned)((2 * H + a * D) * 2);
   const float c2 = scale * kLog2e;
   const int ntq = (S + 127) / 128;                  // causal: query tile x, then its mirror tile (equal work per block)
   for (int pass = 0; pass < (CAUSAL ? 2 : 1); ++pass) {
@@ -335,18 +337,29 @@ attn_fwd8_kernel(const bf16* __restrict__ qkv, bf16* __restrict__ O, float* __re
 
     const int kv_end = CAUSAL ? min(S, qt * 128 + 128) : S;
     const int ntiles = (kv_end + 127) / 128;
-    bf16x8 rk[TL::PER_THREAD], rv[TL::PER_THREAD];
-    TL::load_global(base + H, ld, 0, S, rk);
-    TL::load_global(base + 2 * H, ld, 0, S, rv);
-    TL::store_lds(Ks(0), rk);
-    TL::store_lds(Vs(0), rv);
+    bf16x8 rk[TL::DIRECT ? 1 : TL::PER_THREAD], rv[TL::DIRECT ? 1 : TL::PER_THREAD];   // register staging (D = 64)
+    if constexpr (TL::DIRECT) {
+      TL::stage(rs_qkv, k_bytes, (unsigned)ld * 2, 0, S, Ks(0));
+      TL::stage(rs_qkv, v_bytes, (unsigned)ld * 2, 0, S, Vs(0));
+    } else {
+      TL::load_global(base + H, ld, 0, S, rk);
+      TL::load_global(base + 2 * H, ld, 0, S, rv);
+      TL::store_lds(Ks(0), rk);
+      TL::store_lds(Vs(0), rv);
+    }
+    __builtin_amdgcn_s_waitcnt(0x0F70);                // vmcnt(0): this wavefront's rows have landed
     __syncthreads();
 
     for (int kt = 0; kt < ntiles; ++kt) {
       const int cur = kt & 1;
-      if (kt + 1 < ntiles) {
-        TL::load_global(base + H, ld, (kt + 1) * 128, S, rk);
-        TL::load_global(base + 2 * H, ld, (kt + 1) * 128, S, rv);
+      if (kt + 1 < ntiles) {                           // the next stage flies meanwhile
+        if constexpr (TL::DIRECT) {
+          TL::stage(rs_qkv, k_bytes, (unsigned)ld * 2, (kt + 1) * 128, S, Ks(cur ^ 1));
+          TL::stage(rs_qkv, v_bytes, (unsigned)ld * 2, (kt + 1) * 128, S, Vs(cur ^ 1));
+        } else {
+          TL::load_global(base + H, ld, (kt + 1) * 128, S, rk);
+          TL::load_global(base + 2 * H, ld, (kt + 1) * 128, S, rv);
+        }
       }
       const int t0 = kt * 128 + kh * 64;            // this wavefront's 64 keys
       const lds_bf16* Kt = Ks(cur) + kh * 64 * TL::LD;
@@ -410,10 +423,13 @@ attn_fwd8_kernel(const bf16* __restrict__ qkv, bf16* __restrict__ O, float* __re
           }
         lds_ahead_schedule<D / 8, 2>();
       }
-      if (kt + 1 < ntiles) {
-        TL::store_lds(Ks(cur ^ 1), rk);
-        TL::store_lds(Vs(cur ^ 1), rv);
+      if constexpr (!TL::DIRECT) {
+        if (kt + 1 < ntiles) {
+          TL::store_lds(Ks(cur ^ 1), rk);
+          TL::store_lds(Vs(cur ^ 1), rv);
+        }
       }
+      __builtin_amdgcn_s_waitcnt(0x0F70);              // vmcnt(0)
       __syncthreads();
     }
     // merge the two key halves: [value index][lane] floats per block of queries, lanes contiguous
@@ -470,11 +486,16 @@ attn_dvec_kernel(const bf16* __restrict__ O, const bf16* __restrict__ dO, float*
 }
 
 // ------------------------------------------------------------------------------------ dQ
+// A block owns 128 queries (causal: tile x, then its mirror tile) and walks the keys they see in stages of 128.  Eight
+// wavefronts, as in the forward kernel: wavefront w takes the 32 queries of block w & 3 and the 64 keys of half w >> 2
+// of every stage; each half accumulates its own dQ and the second hands it over through LDS at the end of the pass.
+// The products are taken transposed (S^T = K Q^T, dP^T = V dO^T), so that a lane's 16 values belong to one query and
+// its statistics are two scalars, and dS^T is at once the operand of dQ^T += K^T dS^T.
 template <int D, bool CAUSAL>
-__global__ void __launch_bounds__(kThreads, 2)
+__global__ void __launch_bounds__(kThreads8)
 attn_dq_kernel(const bf16* __restrict__ qkv, const bf16* __restrict__ dO, const float* __restrict__ lse,
                const float* __restrict__ dvec, bf16* __restrict__ dqkv, int S, int H, int A, float scale) {
-  typedef Tile<D> TL;
+  typedef Tile<D, 128, kThreads8> TL;
   extern __shared__ __attribute__((aligned(16))) char smem_raw[];
   lds_bf16* smem = (lds_bf16*)smem_raw;
   auto Ks = [&](int st) { return smem + st * 2 * TL::ELEMS; };
@@ -483,14 +504,17 @@ attn_dq_kernel(const bf16* __restrict__ qkv, const bf16* __restrict__ dO, const 
   const int a = blockIdx.y, n = blockIdx.z;
   const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);   // scalar: tests on a wavefront's rows become real branches
   const int lane = threadIdx.x & 63, h = lane >> 5;
+  const int qsub = wave & 3, kh = wave >> 2;        // block of 32 queries, half of the staged keys
   const int64_t ld = 3 * (int64_t)H;
   const bf16* base = qkv + (int64_t)n * S * ld + a * D;
+  const __amdgpu_buffer_rsrc_t rs_qkv = make_rsrc(qkv + (int64_t)n * S * ld, (unsigned)(S * ld * 2));
+  const unsigned k_bytes = (unsigned)((H + a * D) * 2), v_bytes = (unsigned)((2 * H + a * D) * 2);
   const float c2 = scale * kLog2e;
   const int ntq = (S + 127) / 128;                 // causal: query tiles x and ntq-1-x in turn (equal work per block)
   for (int pass = 0; pass < (CAUSAL ? 2 : 1); ++pass) {
   const int qt = pass == 0 ? (int)blockIdx.x : ntq - 1 - (int)blockIdx.x;
   if (pass == 1 && qt == (int)blockIdx.x) break;
-  const int q0 = qt * 128 + wave * 32;
+  const int q0 = qt * 128 + qsub * 32;
   const int q = q0 + (lane & 31);
 
   bf16x8 qf[D / 16], dof[D / 16];
@@ -507,21 +531,35 @@ attn_dq_kernel(const bf16* __restrict__ qkv, const bf16* __restrict__ dO, const 
     for (int e = 0; e < 16; ++e) dq[dt][e] = 0.f;
 
   const int kv_end = CAUSAL ? min(S, qt * 128 + 128) : S;
-  const int ntiles = (kv_end + TILE - 1) / TILE;
-  bf16x8 rk[TL::PER_THREAD], rv[TL::PER_THREAD];
-  TL::load_global(base + H, ld, 0, S, rk);
-  TL::load_global(base + 2 * H, ld, 0, S, rv);
-  TL::store_lds(Ks(0), rk);
-  TL::store_lds(Vs(0), rv);
+  const int ntiles = (kv_end + 127) / 128;
+  bf16x8 rk[TL::DIRECT ? 1 : TL::PER_THREAD], rv[TL::DIRECT ? 1 : TL::PER_THREAD];   // register staging (D = 64)
+  if constexpr (TL::DIRECT) {
+    TL::stage(rs_qkv, k_bytes, (unsigned)ld * 2, 0, S, Ks(0));
+    TL::stage(rs_qkv, v_bytes, (unsigned)ld * 2, 0, S, Vs(0));
+  } else {
+    TL::load_global(base + H, ld, 0, S, rk);
+    TL::load_global(base + 2 * H, ld, 0, S, rv);
+    TL::store_lds(Ks(0), rk);
+    TL::store_lds(Vs(0), rv);
+  }
+  __builtin_amdgcn_s_waitcnt(0x0F70);                  // vmcnt(0): this wavefront's rows have landed
   __syncthreads();
 
   for (int kt = 0; kt < ntiles; ++kt) {
-    const int cur = kt & 1, t0 = kt * TILE;
-    if (kt + 1 < ntiles) {
-      TL::load_global(base + H, ld, t0 + TILE, S, rk);
-      TL::load_global(base + 2 * H, ld, t0 + TILE, S, rv);
+    const int cur = kt & 1;
+    if (kt + 1 < ntiles) {                             // the next stage flies meanwhile
+      if constexpr (TL::DIRECT) {
+        TL::stage(rs_qkv, k_bytes, (unsigned)ld * 2, (kt + 1) * 128, S, Ks(cur ^ 1));
+        TL::stage(rs_qkv, v_bytes, (unsigned)ld * 2, (kt + 1) * 128, S, Vs(cur ^ 1));
+      } else {
+        TL::load_global(base + H, ld, (kt + 1) * 128, S, rk);
+        TL::load_global(base + 2 * H, ld, (kt + 1) * 128, S, rv);
+      }
     }
-    if (!CAUSAL || t0 <= q0 + 31) {
+    const int t0 = kt * 128 + kh * 64;                 // this wavefront's 64 keys
+    const lds_bf16* Kt = Ks(cur) + kh * 64 * TL::LD;
+    const lds_bf16* Vt = Vs(cur) + kh * 64 * TL::LD;
+    if (t0 < S && (!CAUSAL || t0 <= q0 + 31)) {
 #pragma unroll
       for (int tb = 0; tb < 2; ++tb) {
         f32x16 s, dp;       // S^T and dP^T accumulate in turn: no dependent accumulator between consecutive MFMAs
@@ -529,9 +567,12 @@ attn_dq_kernel(const bf16* __restrict__ qkv, const bf16* __restrict__ dO, const 
         for (int e = 0; e < 16; ++e) { s[e] = 0.f; dp[e] = 0.f; }
 #pragma unroll
         for (int kk = 0; kk < D / 16; ++kk) {
-          s = __builtin_amdgcn_mfma_f32_32x32x16_bf16(TL::frag_rows(Ks(cur), tb * 32, kk * 16), qf[kk], s, 0, 0, 0);
-          dp = __builtin_amdgcn_mfma_f32_32x32x16_bf16(TL::frag_rows(Vs(cur), tb * 32, kk * 16), dof[kk], dp, 0, 0, 0);
+          s = __builtin_amdgcn_mfma_f32_32x32x16_bf16(TL::frag_rows(Kt, tb * 32, kk * 16), qf[kk], s, 0, 0, 0);
+          dp = __builtin_amdgcn_mfma_f32_32x32x16_bf16(TL::frag_rows(Vt, tb * 32, kk * 16), dof[kk], dp, 0, 0, 0);
         }
+        // (the dQ products of the first key block share a basic block with the second block's scores)
+        if (tb == 0) lds_ahead_schedule<D / 8, 1>();
+        else lds_ahead_schedule<D / 16, 2, D / 8, 1>();
         const int tb0 = t0 + tb * 32;
         if ((CAUSAL && tb0 + 31 > q0) || tb0 + 32 > S) {      // block touches the diagonal or the ragged end (wave-uniform)
 #pragma unroll
@@ -550,17 +591,38 @@ attn_dq_kernel(const bf16* __restrict__ qkv, const bf16* __restrict__ dO, const 
           const bf16x8 df = pack8(s, 8 * jj);
 #pragma unroll
           for (int dt = 0; dt < D / 32; ++dt)
-            dq[dt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(TL::frag_cols(Ks(cur), dt * 32, tb * 32 + 16 * jj), df, dq[dt], 0, 0, 0);
+            dq[dt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(TL::frag_cols(Kt, dt * 32, tb * 32 + 16 * jj), df, dq[dt], 0, 0, 0);
         }
+        if (tb == 1) lds_ahead_schedule<D / 16, 2>();
       }
     }
-    if (kt + 1 < ntiles) {
-      TL::store_lds(Ks(cur ^ 1), rk);
-      TL::store_lds(Vs(cur ^ 1), rv);
+    if constexpr (!TL::DIRECT) {
+      if (kt + 1 < ntiles) {
+        TL::store_lds(Ks(cur ^ 1), rk);
+        TL::store_lds(Vs(cur ^ 1), rv);
+      }
     }
+    __builtin_amdgcn_s_waitcnt(0x0F70);                // vmcnt(0)
     __syncthreads();
   }
-  store_transposed<D>(dq, dqkv + (int64_t)n * S * ld + a * D, ld, q, S, scale);
+  // the second half's sums go through LDS ([query block][value][lane], lanes contiguous) and the first half stores
+  constexpr int NV = D / 32 * 16;
+  LDS_AS float* mrg = (LDS_AS float*)smem_raw + qsub * NV * 64 + lane;
+  if (kh == 1) {
+#pragma unroll
+    for (int dt = 0; dt < D / 32; ++dt)
+#pragma unroll
+      for (int e = 0; e < 16; ++e) mrg[(dt * 16 + e) * 64] = dq[dt][e];
+  }
+  __syncthreads();
+  if (kh == 0) {
+#pragma unroll
+    for (int dt = 0; dt < D / 32; ++dt)
+#pragma unroll
+      for (int e = 0; e < 16; ++e) dq[dt][e] += mrg[(dt * 16 + e) * 64];
+    store_transposed<D>(dq, dqkv + (int64_t)n * S * ld + a * D, ld, q, S, scale);
+  }
+  __syncthreads();     // the merge area is staged over again by the next pass
   }   // pass
 }
 
@@ -793,11 +855,11 @@ int bwd_cfg(const bf16* qkv, const bf16* O, const bf16* dO, const float* lse, fl
   const int nt = (S + 127) / 128;
   dim3 grid(CAUSAL ? (nt + 1) / 2 : nt, A, m);     // causal: a block takes a tile and its mirror image
   {
-    const size_t lds = 4 * (size_t)Tile<D>::ELEMS * sizeof(bf16);
+    const size_t lds = 4 * (size_t)Tile<D, 128, kThreads8>::ELEMS * sizeof(bf16);   // two stages of 128 keys and values
     auto kern = attn_dq_kernel<D, CAUSAL>;
     int rc = reserve_lds(kern, lds);
     if (rc != CEPHALO_OK) return rc;
-    kern<<<grid, kThreads, lds, s>>>(qkv, dO, lse, dvec, dqkv, S, H, A, scale);
+    kern<<<grid, kThreads8, lds, s>>>(qkv, dO, lse, dvec, dqkv, S, H, A, scale);
   }
   {
     // staging (2 stages of Q and dO, the keys, the values, the row statistics) or, at the end, the merge of the halves
@@ -818,6 +880,8 @@ int bwd_cfg(const bf16* qkv, const bf16* O, const bf16* dO, const float* lse, fl
 int launch_attn_fwd_mfma(const bf16* qkv, bf16* O, float* lse, int m, int S, int H, int A, int causal, hipStream_t s) {
   const int D = H / A;
   if (H % 8 != 0 || !aligned16(qkv) || !aligned16(O)) return fail(CEPHALO_EINVAL, "attention: rows must be 16-byte aligned");
+  if ((int64_t)S * 3 * H * 2 >= (int64_t)1 << 31)
+    return fail(CEPHALO_EUNSUPPORTED, "attention: one sample of qkv (%lld bytes) exceeds the 2 GiB a buffer offset reaches", (long long)S * 3 * H * 2);
   if (D == 64) return causal ? fwd_cfg<64, true>(qkv, O, lse, m, S, H, A, s) : fwd_cfg<64, false>(qkv, O, lse, m, S, H, A, s);
   if (D == 128) return causal ? fwd_cfg<128, true>(qkv, O, lse, m, S, H, A, s) : fwd_cfg<128, false>(qkv, O, lse, m, S, H, A, s);
   return fail(CEPHALO_EUNSUPPORTED, "attention (matrix-core kernel): head dim %d is not 64 or 128", D);
