@@ -139,7 +139,70 @@ struct OperandTile {
   }
 };
 
-template <int BM, int BN, int WGM, int WGN, bool AK, bool BKF, int EPI>
+// Second half of the bf16/fp32-output epilogue: 32 rows x WTN columns of fp32 results staged row-major in LDS (pitch
+// WTN + 4 floats) are read back 8 columns per lane, bias / residual / pre-activation applied, and written as
+// coalesced 16-byte accesses.  mrow0, ncol0: matrix coordinates of the staged block's corner.
+template <int EPI, int WTN>
+__device__ __forceinline__ void write_staged_rows(const GemmArgs<bf16>& a, const LDS_AS float* stage, int mrow0, int ncol0, int ldc) {
+  constexpr int SP = WTN + 4, LPR = WTN / 8, RPS = 64 / LPR;
+  const int lane = threadIdx.x & 63;
+  const int c = (lane % LPR) * 8;
+  const int n = ncol0 + c;
+#pragma unroll
+    for (int r = lane / LPR; r < 32; r += RPS) {
+      const f32x4 v0 = *reinterpret_cast<const LDS_AS f32x4*>(stage + r * SP + c);
+      const f32x4 v1 = *reinterpret_cast<const LDS_AS f32x4*>(stage + r * SP + c + 4);
+      const int m = mrow0 + r;
+      if (m >= a.M || n >= a.N) continue;
+      const int64_t o = (int64_t)m * ldc + n;
+      float v[8];
+#pragma unroll
+      for (int t = 0; t < 4; ++t) { v[t] = v0[t]; v[4 + t] = v1[t]; }
+      if (EPI == EPI_BIAS || EPI == EPI_BIAS_RESID || EPI == EPI_BIAS_GELU) {
+        float b8[8];
+        load_vec<bf16>(a.bias + n, b8);
+#pragma unroll
+        for (int t = 0; t < 8; ++t) v[t] += b8[t];
+      }
+      if (EPI == EPI_BIAS_RESID) {
+        if (a.Rf) {      // fp32 residual stream
+          const f32x4 r0 = *reinterpret_cast<const f32x4*>(a.Rf + o), r1 = *reinterpret_cast<const f32x4*>(a.Rf + o + 4);
+#pragma unroll
+          for (int t = 0; t < 4; ++t) { v[t] += r0[t]; v[4 + t] += r1[t]; }
+        } else {
+          float r8[8];
+          load_vec<bf16>(a.R + o, r8);
+#pragma unroll
+          for (int t = 0; t < 8; ++t) v[t] += r8[t];
+        }
+      }
+      if (EPI == EPI_BIAS_GELU) {
+        store_vec<bf16>(a.Z + o, v);
+#pragma unroll
+        for (int t = 0; t < 8; ++t) v[t] = gelu_fast(v[t]);
+      }
+      if (EPI == EPI_DGELU) {
+        float z8[8];
+        load_vec<bf16>(a.Z + o, z8);
+#pragma unroll
+        for (int t = 0; t < 8; ++t) v[t] *= gelu_grad_fast(z8[t]);
+      }
+      if (a.Cf) {        // fp32 output (residual stream, or a gradient that an element-wise kernel reads next)
+        f32x4 w0, w1;
+#pragma unroll
+        for (int t = 0; t < 4; ++t) { w0[t] = v[t]; w1[t] = v[4 + t]; }
+        *reinterpret_cast<f32x4*>(a.Cf + o) = w0;
+        *reinterpret_cast<f32x4*>(a.Cf + o + 4) = w1;
+      } else {
+        store_vec<bf16>(a.C + o, v);
+      }
+    }
+}
+
+// s_waitcnt operand that waits for vmcnt(n) only (6-bit counter split over two fields; the other counters at their maxima)
+constexpr int vmcnt_only(int n) { return 0x0F70 | (n & 15) | ((n >> 4) << 14); }
+
+template <int BM, int BN, int WGM, int WGN, bool AK, bool BKF, int EPI, int NS>
 __global__ void __launch_bounds__(64 * WGM * WGN) gemm_mfma_kernel(GemmArgs<bf16> a, int tiles_m, int tiles_n, int slabs_per_split) {
   constexpr int NW = WGM * WGN;                 // wavefronts per block, in a WGM x WGN grid
   typedef OperandTile<BM, AK, NW> TA;
@@ -194,23 +257,23 @@ __global__ void __launch_bounds__(64 * WGM * WGN) gemm_mfma_kernel(GemmArgs<bf16
   const typename TA::Frag fra = TA::frag_init(wm);
   const typename TB::Frag frb = TB::frag_init(wn);
 
-  // Software pipeline over k-slabs of 64 (4 MFMA k-steps of 16 each):
+  // Software pipeline over k-slabs of 64 (4 MFMA k-steps of 16 each), NS LDS stages:
   //   - fragments of k-step s+1 are read from LDS while the MFMAs of k-step s run;
-  //   - between k-steps 2 and 3 of slab kt: wait until slab kt+1 has landed in the other stage, barrier
-  //     (every wavefront has finished reading this stage: its k-step-3 fragments are in registers), then
-  //     start the loads of slab kt+2 into this stage and read the first fragments of slab kt+1 during
-  //     the MFMAs of k-step 3.  One barrier per slab; no LDS or global latency is exposed.
-  TA::load_slab(ra_rsrc, offa, kb0 * BK, a.K, smem);
-  TB::load_slab(rb_rsrc, offb, kb0 * BK, a.K, smem + TA::BYTES);
-  if (nk > 1) {
-    TA::advance(offa, a_step);
-    TB::advance(offb, b_step);
-    TA::load_slab(ra_rsrc, offa, (kb0 + 1) * BK, a.K, smem + STAGE);
-    TB::load_slab(rb_rsrc, offb, (kb0 + 1) * BK, a.K, smem + STAGE + TA::BYTES);
-    __builtin_amdgcn_s_waitcnt(0x0F70 | (TA::PER_WAVE + TB::PER_WAVE));   // vmcnt(loads of slab 1 may still fly)
-  } else {
-    __builtin_amdgcn_s_waitcnt(0x0F70);                                   // vmcnt(0)
+  //   - between k-steps 2 and 3 of slab kt: wait until slab kt+1 has landed in its stage (the loads of the NS-2 slabs
+  //     after it may still fly), barrier (every wavefront has finished reading the stage of slab kt: its k-step-3
+  //     fragments are in registers), then start the loads of slab kt+NS into that stage and read the first fragments
+  //     of slab kt+1 during the MFMAs of k-step 3.  One barrier per slab; a load has NS-1 slabs of MFMAs to arrive.
+  // Loads past the end of the contraction are issued all the same (their offsets are out of range and fetch
+  // nothing, or they land in a stage that is not read again), which keeps the loop body one basic block.
+  constexpr int LOADS = TA::PER_WAVE + TB::PER_WAVE;
+  static_assert((NS - 1) * LOADS < 64, "the outstanding loads must fit the counter");
+#pragma unroll
+  for (int p = 0; p < NS; ++p) {
+    if (p > 0) { TA::advance(offa, a_step); TB::advance(offb, b_step); }
+    TA::load_slab(ra_rsrc, offa, (kb0 + p) * BK, a.K, smem + p * STAGE);
+    TB::load_slab(rb_rsrc, offb, (kb0 + p) * BK, a.K, smem + p * STAGE + TA::BYTES);
   }
+  __builtin_amdgcn_s_waitcnt(vmcnt_only((NS - 1) * LOADS));    // slab 0 has landed
   __syncthreads();
 
   bf16x8 fa[2][MI], fb[2][NI];
@@ -219,14 +282,12 @@ __global__ void __launch_bounds__(64 * WGM * WGN) gemm_mfma_kernel(GemmArgs<bf16
 #pragma unroll
   for (int j = 0; j < NI; ++j) fb[0][j] = TB::fragment(smem + TA::BYTES, frb, j, 0);
 
-  // The loads of slab kt+2 and the first fragment reads of slab kt+1 are issued unconditionally, so that the loop
-  // body is one basic block and they can be interleaved with the MFMAs of k-step 3: past the end of the contraction
-  // the loads fetch nothing (their offsets are out of range, or they land in a stage that is not read again) and
-  // the fragments are not used.
+  int st = 0;                                              // stage of slab kt
   for (int kt = 0; kt < nk; ++kt) {
-    const LDS_AS char* As = smem + (kt & 1) * STAGE;
+    const int st1 = st + 1 == NS ? 0 : st + 1;             // stage of slab kt+1
+    const LDS_AS char* As = smem + st * STAGE;
     const LDS_AS char* Bs = As + TA::BYTES;
-    LDS_AS char* An = smem + ((kt + 1) & 1) * STAGE;     // stage of slab kt+1
+    LDS_AS char* An = smem + st1 * STAGE;
 #pragma unroll
     for (int step = 0; step < 4; ++step) {
       const int cur = step & 1, nxt = cur ^ 1;
@@ -236,13 +297,14 @@ __global__ void __launch_bounds__(64 * WGM * WGN) gemm_mfma_kernel(GemmArgs<bf16
 #pragma unroll
         for (int j = 0; j < NI; ++j) fb[nxt][j] = TB::fragment(Bs, frb, j, 16 * (step + 1));
       } else {
-        // all LDS reads of this stage are done once lgkmcnt drains; slab kt+1 (issued one slab ago) has landed
-        __builtin_amdgcn_s_waitcnt(0x0070);              // vmcnt(0) lgkmcnt(0)
+        // all LDS reads of this stage are done once lgkmcnt drains; slab kt+1 has landed once at most the loads
+        // of the NS-2 slabs after it are outstanding
+        __builtin_amdgcn_s_waitcnt(vmcnt_only((NS - 2) * LOADS) & 0xF0FF);     // ... and lgkmcnt(0)
         __syncthreads();
         TA::advance(offa, a_step);
         TB::advance(offb, b_step);
-        TA::load_slab(ra_rsrc, offa, (kb0 + kt + 2) * BK, a.K, smem + (kt & 1) * STAGE);
-        TB::load_slab(rb_rsrc, offb, (kb0 + kt + 2) * BK, a.K, smem + (kt & 1) * STAGE + TA::BYTES);
+        TA::load_slab(ra_rsrc, offa, (kb0 + kt + NS) * BK, a.K, smem + st * STAGE);
+        TB::load_slab(rb_rsrc, offb, (kb0 + kt + NS) * BK, a.K, smem + st * STAGE + TA::BYTES);
 #pragma unroll
         for (int i = 0; i < MI; ++i) fa[nxt][i] = TA::fragment(An, fra, i, 0);
 #pragma unroll
@@ -256,7 +318,6 @@ __global__ void __launch_bounds__(64 * WGM * WGN) gemm_mfma_kernel(GemmArgs<bf16
       // Scheduling hint: spread this k-step's fragment reads (for the next k-step) and, in k-step 3, the direct-to-LDS
       // loads between its MFMAs instead of bunching them and then waiting.
       constexpr int READS = (AK ? MI : 2 * MI) + (BKF ? NI : 2 * NI);
-      constexpr int LOADS = TA::PER_WAVE + TB::PER_WAVE;
       constexpr int SLOTS = MI * NI;
       if (step < 3) {
         constexpr int MFMAS_PER_READ = SLOTS / READS > 0 ? SLOTS / READS : 1;
@@ -275,6 +336,7 @@ __global__ void __launch_bounds__(64 * WGM * WGN) gemm_mfma_kernel(GemmArgs<bf16
         }
       }
     }
+    st = st1;
   }
 
   // Epilogue.  The MFMAs above were issued with the operands exchanged, so each 32x32 accumulator block holds
@@ -317,6 +379,8 @@ __global__ void __launch_bounds__(64 * WGM * WGN) gemm_mfma_kernel(GemmArgs<bf16
   constexpr int RPS = 64 / LPR;                         // rows per read step
   static_assert(NW * 32 * SP * 4 <= 160 * 1024, "staging regions must fit in LDS");   // the launch reserves max(stages, staging)
   LDS_AS float* stage = (LDS_AS float*)(smem + wave * (32 * SP * 4));
+  __builtin_amdgcn_s_waitcnt(vmcnt_only(0) & 0xF0FF);     // the last (unused) slab loads and fragment reads are over,
+  __syncthreads();                                        // in every wavefront, before the stages are overwritten
 #pragma unroll
   for (int i = 0; i < MI; ++i) {
 #pragma unroll
@@ -328,57 +392,198 @@ __global__ void __launch_bounds__(64 * WGM * WGN) gemm_mfma_kernel(GemmArgs<bf16
         for (int r = 0; r < 4; ++r) v[r] = acc[i][j][4 * q + r];
         *reinterpret_cast<LDS_AS f32x4*>(stage + (lane & 31) * SP + 32 * j + 8 * q + 4 * h) = v;
       }
-    const int c = (lane % LPR) * 8;
-    const int n = n0 + wn + c;
+    write_staged_rows<EPI, WTN>(a, stage, m0 + wm + 32 * i, n0 + wn, ldc);
+  }
+}
+
+// ---------------------------------------------------------------------------------------------------------------
+// The same contraction with v_mfma_f32_16x16x32_bf16, for two k-contiguous operands (forward and, with the weight
+// pre-transposed, input-gradient products).  On this chip a stream of 16x16x32 products sustains about a fifth more
+// than a stream of 32x32x16 products on the same data (measured with operands held in registers: 2.0 against 1.66
+// PFLOP/s), and the LDS bytes per flop depend on the wavefront tile only, not on the MFMA shape.
+//
+// Operand fragment (16 rows x 32 k): lane l holds row l%16, k-values 8*(l/16) .. +7 -- one 16-byte LDS read.
+// Accumulator of the exchanged product (C^T block): lane l owns row m = l%16 and columns n = 4*(l/16) .. +3.
+// A k-slab of 64 is two k-steps.  Register plan per wavefront (tile WTM x WTN, MI = WTM/16, NI = WTN/16): MI*NI*4
+// accumulators, the MI row-operand fragments of this k-step and of the next, and NI column-operand fragments that
+// are refilled in place: as soon as the MI products of column block j have been issued, its register takes the
+// fragment of the next k-step, which is needed a whole k-step later.
+template <int BM, int BN, int WGM, int WGN, int EPI, int NS>
+__global__ void __launch_bounds__(64 * WGM * WGN) gemm16_kernel(GemmArgs<bf16> a, int tiles_m, int tiles_n, int slabs_per_split) {
+  constexpr int NW = WGM * WGN;
+  typedef OperandTile<BM, true, NW> TA;
+  typedef OperandTile<BN, true, NW> TB;
+  constexpr int WTM = BM / WGM, WTN = BN / WGN;
+  constexpr int MI = WTM / 16, NI = WTN / 16;
+  constexpr int STAGE = TA::BYTES + TB::BYTES;
+  constexpr int PITCH = BK * 2;
+  extern __shared__ __attribute__((aligned(1024))) char smem_raw[];
+  LDS_AS char* smem = (LDS_AS char*)smem_raw;
+
+  // tile order: as in gemm_mfma_kernel (a contiguous run per XCD, 4-row groups walked column by column)
+  const int total = tiles_m * tiles_n;
+  const int split = blockIdx.x / total;
+  int pid = blockIdx.x % total;
+  if (total % 8 == 0) pid = (pid % 8) * (total / 8) + pid / 8;
+  constexpr int GROUP = 4;
+  const int per_group = GROUP * tiles_n;
+  const int g0 = (pid / per_group) * GROUP;
+  const int gsz = min(tiles_m - g0, GROUP);
+  const int tile_m = g0 + (pid % per_group) % gsz, tile_n = (pid % per_group) / gsz;
+  const int m0 = tile_m * BM, n0 = tile_n * BN;
+
+  const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
+  const int wm = (wave / WGN) * WTM, wn = (wave % WGN) * WTN;
+
+  f32x4 acc[MI][NI];
 #pragma unroll
-    for (int r = lane / LPR; r < 32; r += RPS) {
-      const f32x4 v0 = *reinterpret_cast<const LDS_AS f32x4*>(stage + r * SP + c);
-      const f32x4 v1 = *reinterpret_cast<const LDS_AS f32x4*>(stage + r * SP + c + 4);
-      const int m = m0 + wm + 32 * i + r;
-      if (m >= a.M || n >= a.N) continue;
-      const int64_t o = (int64_t)m * ldc + n;
-      float v[8];
+  for (int i = 0; i < MI; ++i)
 #pragma unroll
-      for (int t = 0; t < 4; ++t) { v[t] = v0[t]; v[4 + t] = v1[t]; }
-      if (EPI == EPI_BIAS || EPI == EPI_BIAS_RESID || EPI == EPI_BIAS_GELU) {
-        float b8[8];
-        load_vec<bf16>(a.bias + n, b8);
+    for (int j = 0; j < NI; ++j) acc[i][j] = f32x4{0.f, 0.f, 0.f, 0.f};
+
+  const unsigned a_bytes = (unsigned)(2 * (int64_t)a.M * a.a_rs), b_bytes = (unsigned)(2 * (int64_t)a.N * a.b_rs);
+  const __amdgpu_buffer_rsrc_t ra_rsrc = make_rsrc(a.A, a_bytes), rb_rsrc = make_rsrc(a.B, b_bytes);
+  unsigned offa[TA::PER_WAVE], offb[TB::PER_WAVE];
+  TA::init_offsets(a.a_rs, a.a_cs, m0, a.M, a.K, offa);
+  TB::init_offsets(a.b_rs, a.b_cs, n0, a.N, a.K, offb);
+  constexpr unsigned kStep = 2 * BK;                      // bytes per k-slab along a k-contiguous row
+  const int slabs = (a.K + BK - 1) / BK;
+  const int kb0 = split * slabs_per_split;
+  const int nk = min(slabs - kb0, slabs_per_split);
+  if (kb0 > 0) {
+    TA::advance(offa, (unsigned)kb0 * kStep);
+    TB::advance(offb, (unsigned)kb0 * kStep);
+  }
+  // fragment addresses: row (l%16) of the wavefront tile, chunk (l/16) of k-step 0; k-step 1 is chunk + 4, which
+  // under the XOR swizzle is the same address with bit 6 flipped
+  const int swz = (lane & 15) >> 1;                       // ((row >> 1) & 7) for rows that start at a multiple of 16
+  const int fa0 = (wm + (lane & 15)) * PITCH + (((lane >> 4) ^ swz) << 4);
+  const int fb0 = (wn + (lane & 15)) * PITCH + (((lane >> 4) ^ swz) << 4);
+  auto frag = [](const LDS_AS char* tile, int lane_off, int blk, int kstep) {
+    return *reinterpret_cast<const LDS_AS bf16x8*>(tile + (lane_off ^ (kstep << 6)) + blk * 16 * PITCH);
+  };
+
+  constexpr int LOADS = TA::PER_WAVE + TB::PER_WAVE;
+  static_assert((NS - 1) * LOADS < 64, "the outstanding loads must fit the counter");
 #pragma unroll
-        for (int t = 0; t < 8; ++t) v[t] += b8[t];
-      }
-      if (EPI == EPI_BIAS_RESID) {
-        if (a.Rf) {      // fp32 residual stream
-          const f32x4 r0 = *reinterpret_cast<const f32x4*>(a.Rf + o), r1 = *reinterpret_cast<const f32x4*>(a.Rf + o + 4);
+  for (int p = 0; p < NS; ++p) {
+    if (p > 0) { TA::advance(offa, kStep); TB::advance(offb, kStep); }
+    TA::load_slab(ra_rsrc, offa, (kb0 + p) * BK, a.K, smem + p * STAGE);
+    TB::load_slab(rb_rsrc, offb, (kb0 + p) * BK, a.K, smem + p * STAGE + TA::BYTES);
+  }
+  __builtin_amdgcn_s_waitcnt(vmcnt_only((NS - 1) * LOADS));
+  __syncthreads();
+
+  bf16x8 fa[2][MI], fb[NI];
 #pragma unroll
-          for (int t = 0; t < 4; ++t) { v[t] += r0[t]; v[4 + t] += r1[t]; }
-        } else {
-          float r8[8];
-          load_vec<bf16>(a.R + o, r8);
+  for (int i = 0; i < MI; ++i) fa[0][i] = frag(smem, fa0, i, 0);
 #pragma unroll
-          for (int t = 0; t < 8; ++t) v[t] += r8[t];
-        }
-      }
-      if (EPI == EPI_BIAS_GELU) {
-        store_vec<bf16>(a.Z + o, v);
+  for (int j = 0; j < NI; ++j) fb[j] = frag(smem + TA::BYTES, fb0, j, 0);
+
+  constexpr int JB = NI >= 4 ? 2 : 1;                      // column blocks of k-step 1 multiplied before the barrier
+  int st = 0;
+  for (int kt = 0; kt < nk; ++kt) {
+    const int st1 = st + 1 == NS ? 0 : st + 1;
+    const LDS_AS char* As = smem + st * STAGE;
+    const LDS_AS char* Bs = As + TA::BYTES;
+    const LDS_AS char* An = smem + st1 * STAGE;
+    const LDS_AS char* Bn = An + TA::BYTES;
+    // k-step 0: its fragments are in registers; fetch those of k-step 1 from the same stage meanwhile
 #pragma unroll
-        for (int t = 0; t < 8; ++t) v[t] = gelu_fast(v[t]);
-      }
-      if (EPI == EPI_DGELU) {
-        float z8[8];
-        load_vec<bf16>(a.Z + o, z8);
+    for (int i = 0; i < MI; ++i) fa[1][i] = frag(As, fa0, i, 1);
 #pragma unroll
-        for (int t = 0; t < 8; ++t) v[t] *= gelu_grad_fast(z8[t]);
-      }
-      if (a.Cf) {        // fp32 output (residual stream, or a gradient that an element-wise kernel reads next)
-        f32x4 w0, w1;
+    for (int j = 0; j < NI; ++j) {
 #pragma unroll
-        for (int t = 0; t < 4; ++t) { w0[t] = v[t]; w1[t] = v[4 + t]; }
-        *reinterpret_cast<f32x4*>(a.Cf + o) = w0;
-        *reinterpret_cast<f32x4*>(a.Cf + o + 4) = w1;
-      } else {
-        store_vec<bf16>(a.C + o, v);
+      for (int i = 0; i < MI; ++i) acc[i][j] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(fb[j], fa[0][i], acc[i][j], 0, 0, 0);
+      fb[j] = frag(Bs, fb0, j, 1);
+    }
+    {
+      // MI reads first (the row fragments of k-step 1), then one column fragment after every MI products
+      __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);
+#pragma unroll
+      for (int j = 0; j < NI; ++j) {
+        __builtin_amdgcn_sched_group_barrier(0x008, MI, 0);
+        if (j + 1 < MI) __builtin_amdgcn_sched_group_barrier(0x100, 2, 0);
+        else __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);
       }
     }
+    __builtin_amdgcn_sched_barrier(0);
+    // k-step 1: after the first JB column blocks every read of this stage has been issued long ago; wait for slab
+    // kt+1 (the loads of the NS-2 slabs after it may still fly), barrier, start the loads of slab kt+NS into this
+    // stage, and refill the fragment registers from the stage of slab kt+1 as they fall free.
+#pragma unroll
+    for (int j = 0; j < JB; ++j)
+#pragma unroll
+      for (int i = 0; i < MI; ++i) acc[i][j] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(fb[j], fa[1][i], acc[i][j], 0, 0, 0);
+    __builtin_amdgcn_s_waitcnt(vmcnt_only((NS - 2) * LOADS) & 0xF0FF);     // ... and lgkmcnt(0)
+    __syncthreads();
+    TA::advance(offa, kStep);
+    TB::advance(offb, kStep);
+    TA::load_slab(ra_rsrc, offa, (kb0 + kt + NS) * BK, a.K, smem + st * STAGE);
+    TB::load_slab(rb_rsrc, offb, (kb0 + kt + NS) * BK, a.K, smem + st * STAGE + TA::BYTES);
+#pragma unroll
+    for (int i = 0; i < MI; ++i) fa[0][i] = frag(An, fa0, i, 0);
+#pragma unroll
+    for (int j = 0; j < JB; ++j) fb[j] = frag(Bn, fb0, j, 0);
+#pragma unroll
+    for (int j = JB; j < NI; ++j) {
+#pragma unroll
+      for (int i = 0; i < MI; ++i) acc[i][j] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(fb[j], fa[1][i], acc[i][j], 0, 0, 0);
+      fb[j] = frag(Bn, fb0, j, 0);
+    }
+    {
+      // after the barrier: the global loads and the MI + JB early reads spread over the first products, then one
+      // column fragment after every MI products
+      constexpr int EARLY = MI + JB;
+#pragma unroll
+      for (int j = JB; j < NI; ++j) {
+        const int slot = j - JB;
+        __builtin_amdgcn_sched_group_barrier(0x020, (LOADS + NI - JB - 1) / (NI - JB), 0);
+        if (slot < EARLY) __builtin_amdgcn_sched_group_barrier(0x100, 2, 0);
+        else __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);
+        __builtin_amdgcn_sched_group_barrier(0x008, MI, 0);
+      }
+    }
+    st = st1;
+  }
+
+  // Epilogue
+  if (EPI == EPI_GRAD) {
+    const bool partial = a.splits > 1;
+    float* const gbase = partial ? a.part + (int64_t)split * a.M * a.N : a.G;
+    const float scale = partial ? 1.0f : a.scale;
+    const bool accumulate = !partial && a.accumulate;
+#pragma unroll
+    for (int i = 0; i < MI; ++i) {
+      const int m = m0 + wm + 16 * i + (lane & 15);
+      if (m >= a.M) continue;
+#pragma unroll
+      for (int j = 0; j < NI; ++j) {
+        const int n = n0 + wn + 16 * j + 4 * (lane >> 4);
+        if (n >= a.N) continue;                           // N is a multiple of 8: the group of 4 is inside or outside
+        f32x4* gp = reinterpret_cast<f32x4*>(gbase + (int64_t)m * a.N + n);
+        f32x4 v = scale * acc[i][j];
+        if (accumulate) v += *gp;
+        *gp = v;
+      }
+    }
+    return;
+  }
+  // other outputs: 32 rows at a time through the wavefront's own LDS region (see gemm_mfma_kernel)
+  const int ldc = a.ldc ? a.ldc : a.N;
+  constexpr int SP = WTN + 4;
+  static_assert(NW * 32 * SP * 4 <= 160 * 1024, "staging regions must fit in LDS");
+  LDS_AS float* stage = (LDS_AS float*)(smem + wave * (32 * SP * 4));
+  __builtin_amdgcn_s_waitcnt(vmcnt_only(0) & 0xF0FF);     // the last (unused) slab loads and fragment reads are over,
+  __syncthreads();                                        // in every wavefront, before the stages are overwritten
+#pragma unroll
+  for (int i2 = 0; i2 < MI / 2; ++i2) {
+#pragma unroll
+    for (int ii = 0; ii < 2; ++ii)
+#pragma unroll
+      for (int j = 0; j < NI; ++j)
+        *reinterpret_cast<LDS_AS f32x4*>(stage + (16 * ii + (lane & 15)) * SP + 16 * j + 4 * (lane >> 4)) = acc[2 * i2 + ii][j];
+    write_staged_rows<EPI, WTN>(a, stage, m0 + wm + 32 * i2, n0 + wn, ldc);
   }
 }
 
@@ -394,27 +599,23 @@ splitk_reduce_kernel(const float* __restrict__ part, int splits, int64_t mn4, fl
   reinterpret_cast<f32x4*>(G)[i] = out;
 }
 
-template <int BM, int BN, int WGM, int WGN, bool AK, bool BKF, int EPI>
-int launch_cfg(const GemmArgs<bf16>& a, hipStream_t s) {
-  typedef OperandTile<BM, AK, WGM * WGN> TA;
-  typedef OperandTile<BN, BKF, WGM * WGN> TB;
-  constexpr size_t staging = (size_t)WGM * WGN * 32 * (BN / WGN + 4) * 4;      // epilogue transposition area of all wavefronts
-  const size_t lds = std::max<size_t>(2 * (size_t)(TA::BYTES + TB::BYTES), EPI == EPI_GRAD ? 0 : staging);
-  const int tm = (a.M + BM - 1) / BM, tn = (a.N + BN - 1) / BN;
-  auto kern = gemm_mfma_kernel<BM, BN, WGM, WGN, AK, BKF, EPI>;
+// Launch of one instantiation: LDS reservation (once), the split of the contracted axis, the reduction of the pieces.
+template <auto KERN>
+int launch_kernel(const GemmArgs<bf16>& a, int BMv, int BNv, int threads, size_t lds, hipStream_t s) {
+  const int tm = (a.M + BMv - 1) / BMv, tn = (a.N + BNv - 1) / BNv;
   static bool attr_set = false;   // per instantiation
   if (!attr_set) {
-    if (hipFuncSetAttribute(reinterpret_cast<const void*>(kern), hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds) != hipSuccess)
+    if (hipFuncSetAttribute(reinterpret_cast<const void*>(KERN), hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds) != hipSuccess)
       return fail(CEPHALO_EHIP, "gemm_mfma: cannot reserve %zu B of LDS", lds);
     attr_set = true;
   }
   const int slabs = (a.K + BK - 1) / BK;
-  int splits = (EPI == EPI_GRAD && a.splits > 1 && a.part) ? a.splits : 1;
+  int splits = (a.epi == EPI_GRAD && a.splits > 1 && a.part) ? a.splits : 1;
   int per = (slabs + splits - 1) / splits;
   splits = (slabs + per - 1) / per;                       // every piece holds at least one k-slab
   GemmArgs<bf16> k = a;
   k.splits = splits;
-  kern<<<tm * tn * splits, 64 * WGM * WGN, lds, s>>>(k, tm, tn, per);
+  KERN<<<tm * tn * splits, threads, lds, s>>>(k, tm, tn, per);
   CEPHALO_CHECK_LAUNCH("gemm_mfma");
   if (splits > 1) {
     const int64_t mn4 = (int64_t)a.M * a.N / 4;
@@ -422,6 +623,26 @@ int launch_cfg(const GemmArgs<bf16>& a, hipStream_t s) {
     CEPHALO_CHECK_LAUNCH("splitk_reduce");
   }
   return CEPHALO_OK;
+}
+
+template <int BM, int BN, int WGM, int WGN, bool AK, bool BKF, int EPI, int NS = 2>
+int launch_cfg(const GemmArgs<bf16>& a, hipStream_t s) {
+  typedef OperandTile<BM, AK, WGM * WGN> TA;
+  typedef OperandTile<BN, BKF, WGM * WGN> TB;
+  constexpr size_t staging = (size_t)WGM * WGN * 32 * (BN / WGN + 4) * 4;      // epilogue transposition area of all wavefronts
+  static_assert(NS * (TA::BYTES + TB::BYTES) <= 160 * 1024, "the stages must fit in LDS");
+  const size_t lds = std::max<size_t>(NS * (size_t)(TA::BYTES + TB::BYTES), EPI == EPI_GRAD ? 0 : staging);
+  return launch_kernel<gemm_mfma_kernel<BM, BN, WGM, WGN, AK, BKF, EPI, NS>>(a, BM, BN, 64 * WGM * WGN, lds, s);
+}
+
+// the 16x16x32 kernel (both operands k-contiguous)
+template <int BM, int BN, int WGM, int WGN, int EPI, int NS = 2>
+int launch_cfg16(const GemmArgs<bf16>& a, hipStream_t s) {
+  constexpr size_t stages = (size_t)NS * (BM + BN) * BK * 2;
+  constexpr size_t staging = (size_t)WGM * WGN * 32 * (BN / WGN + 4) * 4;
+  static_assert(stages <= 160 * 1024, "the stages must fit in LDS");
+  const size_t lds = std::max<size_t>(stages, EPI == EPI_GRAD ? 0 : staging);
+  return launch_kernel<gemm16_kernel<BM, BN, WGM, WGN, EPI, NS>>(a, BM, BN, 64 * WGM * WGN, lds, s);
 }
 
 template <bool AK, bool BKF, int EPI>
@@ -436,7 +657,24 @@ int launch_tiles(const GemmArgs<bf16>& a, hipStream_t s) {
     return t / (256.0 * (double)(int64_t)((t + 255) / 256));
   };
   int cfg = force;
-  if (cfg == 0) {
+  if constexpr (AK && BKF) {
+    // two k-contiguous operands: the 16x16x32 kernel.  256 x 128 tiles run three LDS stages (they fit, and long
+    // contractions over few tiles gain a quarter from the deeper prefetch; short ones lose nothing).
+    if (cfg == 0) {
+      double best = fill(256, 256); cfg = 11;
+      { const double v = 0.95 * fill(256, 192); if (v > best) { best = v; cfg = 14; } }
+      { const double v = 0.83 * fill(256, 128); if (v > best) { best = v; cfg = 12; } }
+      { const double v = 0.60 * fill(128, 128); if (v > best) { best = v; cfg = 15; } }
+    }
+    switch (cfg) {
+      case 11: return launch_cfg16<256, 256, 4, 2, EPI>(a, s);
+      case 12: return launch_cfg16<256, 128, 4, 2, EPI, 3>(a, s);
+      case 14: return launch_cfg16<256, 192, 4, 2, EPI>(a, s);
+      case 15: return launch_cfg16<128, 128, 2, 2, EPI, 3>(a, s);
+      default: break;     // 1..7: the 32x32x16 kernel, for comparison
+    }
+  }
+  if (cfg == 0 || cfg > 7) {
     double best = fill(256, 256); cfg = 2;
     if (BKF) { const double v = 0.93 * fill(256, 192); if (v > best) { best = v; cfg = 7; } }
     { const double v = 0.88 * fill(256, 128); if (v > best) { best = v; cfg = 4; } }
