@@ -47,7 +47,7 @@ __device__ __forceinline__ __amdgpu_buffer_rsrc_t make_rsrc(const void* p, unsig
 }
 
 // One operand's tile: ROWS matrix rows (m or n) by BK k-values, ROWS*BK*2 bytes of LDS, unpadded.
-template <int ROWS, bool KFAST, int NW>
+template <int ROWS, bool KFAST, int NW, bool M16 = false>
 struct OperandTile {
   static constexpr int BYTES = ROWS * BK * 2;
   static constexpr int INSTR = BYTES / 1024;            // direct-to-LDS load instructions per tile (1 KiB each)
@@ -64,7 +64,9 @@ struct OperandTile {
     const int s = (wave * PER_WAVE + j) * 64 + lane;    // 16-byte slot index within the tile
     line = s / CHUNKS;
     const int cs = s % CHUNKS;
-    chunk = KFAST ? (cs ^ ((line >> 1) & 7)) : (cs ^ ((line & 3) << 2));
+    // (M16: row-contiguous tiles read as 16-row fragments of the 16x16x32 MFMA, whose half-wavefront covers k-rows
+    // k..k+3 and k+8..k+11 at two chunks each: the k bits 0, 1 and 3 spread them over the 16 chunk positions)
+    chunk = KFAST ? (cs ^ ((line >> 1) & 7)) : M16 ? (cs ^ (((line & 3) << 2) | (((line >> 3) & 1) << 1))) : (cs ^ ((line & 3) << 2));
   }
   // byte offsets into the operand for k-slab 0; rows outside the matrix get the out-of-range mark
   __device__ static void init_offsets(int64_t rs, int64_t cs, int row0, int nrows, int K, unsigned (&off)[PER_WAVE]) {
@@ -397,26 +399,25 @@ __global__ void __launch_bounds__(64 * WGM * WGN) gemm_mfma_kernel(GemmArgs<bf16
 }
 
 // ---------------------------------------------------------------------------------------------------------------
-// The same contraction with v_mfma_f32_16x16x32_bf16, for two k-contiguous operands (forward and, with the weight
-// pre-transposed, input-gradient products).  On this chip a stream of 16x16x32 products sustains about a fifth more
+// The same contraction with v_mfma_f32_16x16x32_bf16.  On this chip a stream of 16x16x32 products sustains about a fifth more
 // than a stream of 32x32x16 products on the same data (measured with operands held in registers: 2.0 against 1.66
 // PFLOP/s), and the LDS bytes per flop depend on the wavefront tile only, not on the MFMA shape.
 //
-// Operand fragment (16 rows x 32 k): lane l holds row l%16, k-values 8*(l/16) .. +7 -- one 16-byte LDS read.
+// Operand fragment (16 rows x 32 k): lane l holds row l%16, k-values 8*(l/16) .. +7 -- one 16-byte LDS read of a
+// k-contiguous tile, two transposing reads (4 k-values each) of a row-contiguous one.
 // Accumulator of the exchanged product (C^T block): lane l owns row m = l%16 and columns n = 4*(l/16) .. +3.
 // A k-slab of 64 is two k-steps.  Register plan per wavefront (tile WTM x WTN, MI = WTM/16, NI = WTN/16): MI*NI*4
 // accumulators, the MI row-operand fragments of this k-step and of the next, and NI column-operand fragments that
 // are refilled in place: as soon as the MI products of column block j have been issued, its register takes the
 // fragment of the next k-step, which is needed a whole k-step later.
-template <int BM, int BN, int WGM, int WGN, int EPI, int NS>
+template <int BM, int BN, int WGM, int WGN, bool AK, bool BKF, int EPI, int NS>
 __global__ void __launch_bounds__(64 * WGM * WGN) gemm16_kernel(GemmArgs<bf16> a, int tiles_m, int tiles_n, int slabs_per_split) {
   constexpr int NW = WGM * WGN;
-  typedef OperandTile<BM, true, NW> TA;
-  typedef OperandTile<BN, true, NW> TB;
+  typedef OperandTile<BM, AK, NW, true> TA;
+  typedef OperandTile<BN, BKF, NW, true> TB;
   constexpr int WTM = BM / WGM, WTN = BN / WGN;
   constexpr int MI = WTM / 16, NI = WTN / 16;
   constexpr int STAGE = TA::BYTES + TB::BYTES;
-  constexpr int PITCH = BK * 2;
   extern __shared__ __attribute__((aligned(1024))) char smem_raw[];
   LDS_AS char* smem = (LDS_AS char*)smem_raw;
 
@@ -441,33 +442,67 @@ __global__ void __launch_bounds__(64 * WGM * WGN) gemm16_kernel(GemmArgs<bf16> a
 #pragma unroll
     for (int j = 0; j < NI; ++j) acc[i][j] = f32x4{0.f, 0.f, 0.f, 0.f};
 
-  const unsigned a_bytes = (unsigned)(2 * (int64_t)a.M * a.a_rs), b_bytes = (unsigned)(2 * (int64_t)a.N * a.b_rs);
+  const unsigned a_bytes = (unsigned)(2 * (AK ? (int64_t)a.M * a.a_rs : (int64_t)a.K * a.a_cs));
+  const unsigned b_bytes = (unsigned)(2 * (BKF ? (int64_t)a.N * a.b_rs : (int64_t)a.K * a.b_cs));
   const __amdgpu_buffer_rsrc_t ra_rsrc = make_rsrc(a.A, a_bytes), rb_rsrc = make_rsrc(a.B, b_bytes);
   unsigned offa[TA::PER_WAVE], offb[TB::PER_WAVE];
   TA::init_offsets(a.a_rs, a.a_cs, m0, a.M, a.K, offa);
   TB::init_offsets(a.b_rs, a.b_cs, n0, a.N, a.K, offb);
-  constexpr unsigned kStep = 2 * BK;                      // bytes per k-slab along a k-contiguous row
+  const unsigned a_step = (unsigned)(2 * BK * a.a_cs), b_step = (unsigned)(2 * BK * a.b_cs);   // bytes per k-slab
   const int slabs = (a.K + BK - 1) / BK;
   const int kb0 = split * slabs_per_split;
   const int nk = min(slabs - kb0, slabs_per_split);
   if (kb0 > 0) {
-    TA::advance(offa, (unsigned)kb0 * kStep);
-    TB::advance(offb, (unsigned)kb0 * kStep);
+    TA::advance(offa, (unsigned)kb0 * a_step);
+    TB::advance(offb, (unsigned)kb0 * b_step);
   }
-  // fragment addresses: row (l%16) of the wavefront tile, chunk (l/16) of k-step 0; k-step 1 is chunk + 4, which
-  // under the XOR swizzle is the same address with bit 6 flipped
-  const int swz = (lane & 15) >> 1;                       // ((row >> 1) & 7) for rows that start at a multiple of 16
-  const int fa0 = (wm + (lane & 15)) * PITCH + (((lane >> 4) ^ swz) << 4);
-  const int fb0 = (wn + (lane & 15)) * PITCH + (((lane >> 4) ^ swz) << 4);
-  auto frag = [](const LDS_AS char* tile, int lane_off, int blk, int kstep) {
-    return *reinterpret_cast<const LDS_AS bf16x8*>(tile + (lane_off ^ (kstep << 6)) + blk * 16 * PITCH);
+  // Fragment addresses (per lane, for block 0 and k-step 0 of the wavefront tile).
+  //  k-contiguous tile [row][64 k]: row l%16, chunk l/16; k-step 1 is chunk + 4, under the XOR swizzle the same
+  //   address with bit 6 flipped; block b is 16 rows further.
+  //  row-contiguous tile [k][rows]: within a group of 16 lanes, lane i addresses 4 consecutive rows (8 bytes) of
+  //   k-row 8*(l/16) + i/4 and receives the 4 k-values of row i; a second read 4 k-rows further completes the 8.
+  //   The swizzle term of those k-rows is the same for both reads and both k-steps; block b is two chunks further,
+  //   which under the XOR is the address with b << 5 flipped (the wavefront's first chunk is a multiple of 8 or 16,
+  //   so the block bits are free).
+  auto frag_base = [&](bool kfast, int w0, int pitch) {
+    if (kfast) return (w0 + (lane & 15)) * pitch + (((lane >> 4) ^ ((lane & 15) >> 1)) << 4);
+    const int g = lane >> 4, i = lane & 15;
+    const int krow = 8 * g + (i >> 2);
+    const int sw = ((krow & 3) << 2) | ((g & 1) << 1);
+    return krow * pitch + ((((w0 >> 3) | ((i & 3) >> 1)) ^ sw) << 4) + 8 * (i & 1);
   };
+  const int fa0 = frag_base(AK, wm, TA::PITCH), fb0 = frag_base(BKF, wn, TB::PITCH);
+  auto frag_a = [&](const LDS_AS char* tile, int blk, int kstep) -> bf16x8 {
+    if constexpr (AK) {
+      return *reinterpret_cast<const LDS_AS bf16x8*>(tile + (fa0 ^ (kstep << 6)) + blk * 16 * TA::PITCH);
+    } else {
+      const LDS_AS char* p0 = tile + (fa0 ^ (blk << 5)) + kstep * 32 * TA::PITCH;
+      union { struct { s16x4 a, b; } s; bf16x8 v; } u;
+      u.s.a = __builtin_amdgcn_ds_read_tr16_b64_v4i16((LDS_AS s16x4*)(p0));
+      u.s.b = __builtin_amdgcn_ds_read_tr16_b64_v4i16((LDS_AS s16x4*)(p0 + 4 * TA::PITCH));
+      return u.v;
+    }
+  };
+  auto frag_b = [&](const LDS_AS char* tile, int blk, int kstep) -> bf16x8 {
+    if constexpr (BKF) {
+      return *reinterpret_cast<const LDS_AS bf16x8*>(tile + (fb0 ^ (kstep << 6)) + blk * 16 * TB::PITCH);
+    } else {
+      const LDS_AS char* p0 = tile + (fb0 ^ (blk << 5)) + kstep * 32 * TB::PITCH;
+      union { struct { s16x4 a, b; } s; bf16x8 v; } u;
+      u.s.a = __builtin_amdgcn_ds_read_tr16_b64_v4i16((LDS_AS s16x4*)(p0));
+      u.s.b = __builtin_amdgcn_ds_read_tr16_b64_v4i16((LDS_AS s16x4*)(p0 + 4 * TB::PITCH));
+      return u.v;
+    }
+  };
+  constexpr int RA = AK ? 1 : 2, RB = BKF ? 1 : 2;       // LDS reads per fragment
+  static_assert(AK || WTM % 64 == 0, "block bits of a row-contiguous A tile");
+  static_assert(BKF || WTN % 64 == 0, "block bits of a row-contiguous B tile");
 
   constexpr int LOADS = TA::PER_WAVE + TB::PER_WAVE;
   static_assert((NS - 1) * LOADS < 64, "the outstanding loads must fit the counter");
 #pragma unroll
   for (int p = 0; p < NS; ++p) {
-    if (p > 0) { TA::advance(offa, kStep); TB::advance(offb, kStep); }
+    if (p > 0) { TA::advance(offa, a_step); TB::advance(offb, b_step); }
     TA::load_slab(ra_rsrc, offa, (kb0 + p) * BK, a.K, smem + p * STAGE);
     TB::load_slab(rb_rsrc, offb, (kb0 + p) * BK, a.K, smem + p * STAGE + TA::BYTES);
   }
@@ -476,9 +511,9 @@ __global__ void __launch_bounds__(64 * WGM * WGN) gemm16_kernel(GemmArgs<bf16> a
 
   bf16x8 fa[2][MI], fb[NI];
 #pragma unroll
-  for (int i = 0; i < MI; ++i) fa[0][i] = frag(smem, fa0, i, 0);
+  for (int i = 0; i < MI; ++i) fa[0][i] = frag_a(smem, i, 0);
 #pragma unroll
-  for (int j = 0; j < NI; ++j) fb[j] = frag(smem + TA::BYTES, fb0, j, 0);
+  for (int j = 0; j < NI; ++j) fb[j] = frag_b(smem + TA::BYTES, j, 0);
 
   constexpr int JB = NI >= 4 ? 2 : 1;                      // column blocks of k-step 1 multiplied before the barrier
   int st = 0;
@@ -490,21 +525,21 @@ __global__ void __launch_bounds__(64 * WGM * WGN) gemm16_kernel(GemmArgs<bf16> a
     const LDS_AS char* Bn = An + TA::BYTES;
     // k-step 0: its fragments are in registers; fetch those of k-step 1 from the same stage meanwhile
 #pragma unroll
-    for (int i = 0; i < MI; ++i) fa[1][i] = frag(As, fa0, i, 1);
+    for (int i = 0; i < MI; ++i) fa[1][i] = frag_a(As, i, 1);
 #pragma unroll
     for (int j = 0; j < NI; ++j) {
 #pragma unroll
       for (int i = 0; i < MI; ++i) acc[i][j] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(fb[j], fa[0][i], acc[i][j], 0, 0, 0);
-      fb[j] = frag(Bs, fb0, j, 1);
+      fb[j] = frag_b(Bs, j, 1);
     }
     {
       // MI reads first (the row fragments of k-step 1), then one column fragment after every MI products
-      __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);
+      __builtin_amdgcn_sched_group_barrier(0x100, RA, 0);
 #pragma unroll
       for (int j = 0; j < NI; ++j) {
         __builtin_amdgcn_sched_group_barrier(0x008, MI, 0);
-        if (j + 1 < MI) __builtin_amdgcn_sched_group_barrier(0x100, 2, 0);
-        else __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);
+        if (j + 1 < MI) __builtin_amdgcn_sched_group_barrier(0x100, RA + RB, 0);
+        else __builtin_amdgcn_sched_group_barrier(0x100, RB, 0);
       }
     }
     __builtin_amdgcn_sched_barrier(0);
@@ -517,19 +552,19 @@ __global__ void __launch_bounds__(64 * WGM * WGN) gemm16_kernel(GemmArgs<bf16> a
       for (int i = 0; i < MI; ++i) acc[i][j] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(fb[j], fa[1][i], acc[i][j], 0, 0, 0);
     __builtin_amdgcn_s_waitcnt(vmcnt_only((NS - 2) * LOADS) & 0xF0FF);     // ... and lgkmcnt(0)
     __syncthreads();
-    TA::advance(offa, kStep);
-    TB::advance(offb, kStep);
+    TA::advance(offa, a_step);
+    TB::advance(offb, b_step);
     TA::load_slab(ra_rsrc, offa, (kb0 + kt + NS) * BK, a.K, smem + st * STAGE);
     TB::load_slab(rb_rsrc, offb, (kb0 + kt + NS) * BK, a.K, smem + st * STAGE + TA::BYTES);
 #pragma unroll
-    for (int i = 0; i < MI; ++i) fa[0][i] = frag(An, fa0, i, 0);
+    for (int i = 0; i < MI; ++i) fa[0][i] = frag_a(An, i, 0);
 #pragma unroll
-    for (int j = 0; j < JB; ++j) fb[j] = frag(Bn, fb0, j, 0);
+    for (int j = 0; j < JB; ++j) fb[j] = frag_b(Bn, j, 0);
 #pragma unroll
     for (int j = JB; j < NI; ++j) {
 #pragma unroll
       for (int i = 0; i < MI; ++i) acc[i][j] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(fb[j], fa[1][i], acc[i][j], 0, 0, 0);
-      fb[j] = frag(Bn, fb0, j, 0);
+      fb[j] = frag_b(Bn, j, 0);
     }
     {
       // after the barrier: the global loads and the MI + JB early reads spread over the first products, then one
@@ -539,8 +574,9 @@ __global__ void __launch_bounds__(64 * WGM * WGN) gemm16_kernel(GemmArgs<bf16> a
       for (int j = JB; j < NI; ++j) {
         const int slot = j - JB;
         __builtin_amdgcn_sched_group_barrier(0x020, (LOADS + NI - JB - 1) / (NI - JB), 0);
-        if (slot < EARLY) __builtin_amdgcn_sched_group_barrier(0x100, 2, 0);
-        else __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);
+        if (slot < MI) __builtin_amdgcn_sched_group_barrier(0x100, RA + RB, 0);
+        else if (slot < EARLY) __builtin_amdgcn_sched_group_barrier(0x100, 2 * RB, 0);
+        else __builtin_amdgcn_sched_group_barrier(0x100, RB, 0);
         __builtin_amdgcn_sched_group_barrier(0x008, MI, 0);
       }
     }
@@ -636,13 +672,13 @@ int launch_cfg(const GemmArgs<bf16>& a, hipStream_t s) {
 }
 
 // the 16x16x32 kernel (both operands k-contiguous)
-template <int BM, int BN, int WGM, int WGN, int EPI, int NS = 2>
+template <int BM, int BN, int WGM, int WGN, bool AK, bool BKF, int EPI, int NS = 2>
 int launch_cfg16(const GemmArgs<bf16>& a, hipStream_t s) {
   constexpr size_t stages = (size_t)NS * (BM + BN) * BK * 2;
   constexpr size_t staging = (size_t)WGM * WGN * 32 * (BN / WGN + 4) * 4;
   static_assert(stages <= 160 * 1024, "the stages must fit in LDS");
   const size_t lds = std::max<size_t>(stages, EPI == EPI_GRAD ? 0 : staging);
-  return launch_kernel<gemm16_kernel<BM, BN, WGM, WGN, EPI, NS>>(a, BM, BN, 64 * WGM * WGN, lds, s);
+  return launch_kernel<gemm16_kernel<BM, BN, WGM, WGN, AK, BKF, EPI, NS>>(a, BM, BN, 64 * WGM * WGN, lds, s);
 }
 
 template <bool AK, bool BKF, int EPI>
@@ -657,22 +693,20 @@ int launch_tiles(const GemmArgs<bf16>& a, hipStream_t s) {
     return t / (256.0 * (double)(int64_t)((t + 255) / 256));
   };
   int cfg = force;
-  if constexpr (AK && BKF) {
-    // two k-contiguous operands: the 16x16x32 kernel.  256 x 128 tiles run three LDS stages (they fit, and long
-    // contractions over few tiles gain a quarter from the deeper prefetch; short ones lose nothing).
-    if (cfg == 0) {
-      double best = fill(256, 256); cfg = 11;
-      { const double v = 0.95 * fill(256, 192); if (v > best) { best = v; cfg = 14; } }
-      { const double v = 0.83 * fill(256, 128); if (v > best) { best = v; cfg = 12; } }
-      { const double v = 0.60 * fill(128, 128); if (v > best) { best = v; cfg = 15; } }
-    }
-    switch (cfg) {
-      case 11: return launch_cfg16<256, 256, 4, 2, EPI>(a, s);
-      case 12: return launch_cfg16<256, 128, 4, 2, EPI, 3>(a, s);
-      case 14: return launch_cfg16<256, 192, 4, 2, EPI>(a, s);
-      case 15: return launch_cfg16<128, 128, 2, 2, EPI, 3>(a, s);
-      default: break;     // 1..7: the 32x32x16 kernel, for comparison
-    }
+  // The 16x16x32 kernel.  256 x 128 tiles run three LDS stages (they fit, and long contractions over few tiles gain
+  // a quarter from the deeper prefetch; short ones lose nothing).
+  if (cfg == 0) {
+    double best = fill(256, 256); cfg = 11;
+    if (BKF) { const double v = 0.95 * fill(256, 192); if (v > best) { best = v; cfg = 14; } }
+    { const double v = 0.83 * fill(256, 128); if (v > best) { best = v; cfg = 12; } }
+    { const double v = 0.60 * fill(128, 128); if (v > best) { best = v; cfg = 15; } }
+  }
+  switch (cfg) {
+    case 11: return launch_cfg16<256, 256, 4, 2, AK, BKF, EPI>(a, s);
+    case 12: return launch_cfg16<256, 128, 4, 2, AK, BKF, EPI, 3>(a, s);
+    case 14: if constexpr (BKF) return launch_cfg16<256, 192, 4, 2, AK, BKF, EPI>(a, s); else break;
+    case 15: return launch_cfg16<128, 128, 2, 2, AK, BKF, EPI, 3>(a, s);
+    default: break;     // 1..7: the 32x32x16 kernel, for comparison
   }
   if (cfg == 0 || cfg > 7) {
     double best = fill(256, 256); cfg = 2;
