@@ -26,6 +26,7 @@
 // one barrier per slab.  256 threads = 4 wavefronts in a 2x2 grid; v_mfma_f32_32x32x16_bf16.
 #include "kernels.h"
 #include <cstdlib>
+#include <cstdint>
 #include <algorithm>
 
 namespace cephalo {
@@ -44,6 +45,12 @@ constexpr unsigned kOob = 0x80000000u;   // byte offset beyond any buffer: such 
 // Buffer descriptor over `bytes` bytes at p: loads at offsets >= bytes return 0 (hardware range check).
 __device__ __forceinline__ __amdgpu_buffer_rsrc_t make_rsrc(const void* p, unsigned bytes) {
   return __builtin_amdgcn_make_buffer_rsrc(const_cast<void*>(p), 0, bytes, 0x00020000);
+}
+// the same descriptor as four words (base, base high half with stride 0, extent, flags), for inline assembly
+typedef int i32x4 __attribute__((ext_vector_type(4)));
+__device__ __forceinline__ i32x4 make_rsrc_words(const void* p, unsigned bytes) {
+  const uint64_t addr = (uint64_t)(uintptr_t)p;
+  return i32x4{(int)(unsigned)addr, (int)(unsigned)((addr >> 32) & 0xffffu), (int)bytes, 0x00020000};
 }
 
 // One operand's tile: ROWS matrix rows (m or n) by BK k-values, ROWS*BK*2 bytes of LDS, unpadded.
@@ -96,6 +103,23 @@ struct OperandTile {
         if (k0 + chunk * 8 >= K) o = kOob;
       }
       __builtin_amdgcn_raw_ptr_buffer_load_lds(rsrc, (LDS_AS void*)(lds + (wave * PER_WAVE + j) * 1024), 16, o, 0, 0, 0);
+    }
+  }
+  // The same loads issued behind the compiler's back.  It tracks loads that write LDS, cannot tell one stage from
+  // another, and makes the next transposing LDS read wait for all of them (a vmcnt(0) right after the loads: their
+  // whole latency, once per slab).  The kernel writes out the waits that are needed.  rsrc: the four descriptor words.
+  __device__ static void load_slab_untracked(i32x4 rsrc, const unsigned (&off)[PER_WAVE], int k0, int K, LDS_AS char* lds) {
+    const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+#pragma unroll
+    for (int j = 0; j < PER_WAVE; ++j) {
+      unsigned o = off[j];
+      if (KFAST) {
+        int line, chunk;
+        slot(j, line, chunk);
+        if (k0 + chunk * 8 >= K) o = kOob;
+      }
+      const unsigned dst = (unsigned)(uintptr_t)(lds + (wave * PER_WAVE + j) * 1024);   // LDS byte address, wave-uniform
+      asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tbuffer_load_dwordx4 %1, %2, 0 offen lds" :: "s"(dst), "v"(o), "s"(rsrc) : "m0");
     }
   }
   __device__ static void advance(unsigned (&off)[PER_WAVE], unsigned slab_bytes) {
@@ -444,7 +468,7 @@ __global__ void __launch_bounds__(64 * WGM * WGN) gemm16_kernel(GemmArgs<bf16> a
 
   const unsigned a_bytes = (unsigned)(2 * (AK ? (int64_t)a.M * a.a_rs : (int64_t)a.K * a.a_cs));
   const unsigned b_bytes = (unsigned)(2 * (BKF ? (int64_t)a.N * a.b_rs : (int64_t)a.K * a.b_cs));
-  const __amdgpu_buffer_rsrc_t ra_rsrc = make_rsrc(a.A, a_bytes), rb_rsrc = make_rsrc(a.B, b_bytes);
+  const i32x4 ra_rsrc = make_rsrc_words(a.A, a_bytes), rb_rsrc = make_rsrc_words(a.B, b_bytes);
   unsigned offa[TA::PER_WAVE], offb[TB::PER_WAVE];
   TA::init_offsets(a.a_rs, a.a_cs, m0, a.M, a.K, offa);
   TB::init_offsets(a.b_rs, a.b_cs, n0, a.N, a.K, offb);
@@ -503,8 +527,8 @@ __global__ void __launch_bounds__(64 * WGM * WGN) gemm16_kernel(GemmArgs<bf16> a
 #pragma unroll
   for (int p = 0; p < NS; ++p) {
     if (p > 0) { TA::advance(offa, a_step); TB::advance(offb, b_step); }
-    TA::load_slab(ra_rsrc, offa, (kb0 + p) * BK, a.K, smem + p * STAGE);
-    TB::load_slab(rb_rsrc, offb, (kb0 + p) * BK, a.K, smem + p * STAGE + TA::BYTES);
+    TA::load_slab_untracked(ra_rsrc, offa, (kb0 + p) * BK, a.K, smem + p * STAGE);
+    TB::load_slab_untracked(rb_rsrc, offb, (kb0 + p) * BK, a.K, smem + p * STAGE + TA::BYTES);
   }
   __builtin_amdgcn_s_waitcnt(vmcnt_only((NS - 1) * LOADS));
   __syncthreads();
@@ -554,8 +578,8 @@ __global__ void __launch_bounds__(64 * WGM * WGN) gemm16_kernel(GemmArgs<bf16> a
     __syncthreads();
     TA::advance(offa, a_step);
     TB::advance(offb, b_step);
-    TA::load_slab(ra_rsrc, offa, (kb0 + kt + NS) * BK, a.K, smem + st * STAGE);
-    TB::load_slab(rb_rsrc, offb, (kb0 + kt + NS) * BK, a.K, smem + st * STAGE + TA::BYTES);
+    TA::load_slab_untracked(ra_rsrc, offa, (kb0 + kt + NS) * BK, a.K, smem + st * STAGE);
+    TB::load_slab_untracked(rb_rsrc, offb, (kb0 + kt + NS) * BK, a.K, smem + st * STAGE + TA::BYTES);
 #pragma unroll
     for (int i = 0; i < MI; ++i) fa[0][i] = frag_a(An, i, 0);
 #pragma unroll
