@@ -1,29 +1,35 @@
 // bf16 GEMM on the gfx950 matrix cores:  C[M,N] = sum_k A(m,k) B(n,k), fp32 accumulate, fused epilogue.
 //
-// One kernel template covers the three contractions of a linear layer without any transposed
-// copy in HBM:
-//   forward   Y  = X W^T      A k-contiguous, B k-contiguous
-//   dgrad     dX = dY W       A k-contiguous, B n-contiguous (k strided)
-//   wgrad     dW = dY^T X     A m-contiguous, B n-contiguous (both strided along k = tokens)
+// One kernel template covers the contractions of a linear layer; each operand is either k-contiguous or
+// row-contiguous (strided along k):
+//   forward          Y  = X W^T        both k-contiguous
+//   input gradient   dX = dY (W^T)^T   both k-contiguous (the layer keeps a transposed copy of its weights)
+//   weight gradient  dW = dY^T X       tokens are k: one operand is transposed beforehand by the caller, the other
+//                                      is read row-contiguous
 //
-// Data path.  The kernel is bound by LDS bandwidth before it is bound by the matrix cores, so
-// the tile is as large as the accumulators allow (256 x 256 per block, 128 x 128 per wavefront:
-// every LDS byte read feeds the most MFMAs) and operand slabs go from global memory straight
-// into LDS (buffer_load ... lds, 16 bytes per lane) without passing through registers.  Those
-// loads write 64 lanes x 16 B = 1 KiB of consecutive LDS per instruction, so rows cannot be
-// padded; bank conflicts are avoided by an XOR swizzle of the 16-byte chunk index, applied to
-// the global address each lane fetches and again when fragments are read:
+// Matrix instruction: v_mfma_f32_16x16x32_bf16.  On this chip a stream of 16x16x32 products sustains about a fifth
+// more than a stream of 32x32x16 products on the same data (measured with operands held in registers: 2.0 against
+// 1.66 PFLOP/s; the chip is power-limited long before its nominal 2.5), and the LDS bytes per flop depend on the
+// wavefront tile only, not on the MFMA shape.
+//
+// Data path.  The tile is as large as the accumulators allow (256 x 256 per block of 8 wavefronts, 64 x 128 per
+// wavefront: every byte brought into LDS and every LDS byte read feeds the most MFMAs) and operand slabs of 64
+// k-values go from global memory straight into LDS (buffer_load ... lds, 16 bytes per lane) without passing through
+// registers.  Those loads write 64 lanes x 16 B = 1 KiB of consecutive LDS per instruction, so rows cannot be padded;
+// bank conflicts are avoided by an XOR swizzle of the 16-byte chunk index, applied to the global address each lane
+// fetches and again when fragments are read:
 //   k-contiguous tile [row][64 k]  (128 B rows):  chunk' = chunk ^ ((row >> 1) & 7)
-//   row-contiguous tile [k][rows]                 chunk' = chunk ^ ((k & 3) << 2)
-// A k-contiguous operand's MFMA fragment (8 consecutive k of one row per lane) is one 16-byte
-// LDS read.  A row-contiguous operand's fragment is fetched with the transposing LDS read of
-// gfx950 (ds_read_b64_tr_b16): within each 16-lane group, lane i supplies the address of 4
-// consecutive rows at k-row (i/4) and receives the 4 k-values of row i -- the MFMA layout.
-// Rows or k-values outside the matrix are never read: their buffer offsets are out of the
-// descriptor's range and the hardware returns zeros.
+//   row-contiguous tile [k][rows]:                chunk' = chunk ^ (((k & 3) << 2) | (((k >> 3) & 1) << 1))
+// A k-contiguous operand's MFMA fragment (16 rows x 32 k: 8 consecutive k of one row per lane) is one 16-byte LDS
+// read.  A row-contiguous operand's fragment is fetched with the transposing LDS read of gfx950
+// (ds_read_b64_tr_b16): within each 16-lane group, lane i supplies the address of 4 consecutive rows at one k-row
+// and receives 4 k-values of row i; two such reads make a fragment.  Both read patterns are free of bank conflicts
+// under the swizzles above (checked with the LDS conflict counters).
+// Rows or k-values outside the matrix are never read: their buffer offsets are out of the descriptor's range and the
+// hardware returns zeros.
 //
-// Pipeline: two LDS stages; the loads of slab kt+1 are in flight while slab kt is multiplied;
-// one barrier per slab.  256 threads = 4 wavefronts in a 2x2 grid; v_mfma_f32_32x32x16_bf16.
+// Pipeline: two or three LDS stages; the loads of the following slab(s) are in flight while a slab is multiplied;
+// one barrier per slab.  The loads are issued through inline assembly (see load_slab_untracked).
 #include "kernels.h"
 #include <cstdlib>
 #include <cstdint>
@@ -54,7 +60,7 @@ __device__ __forceinline__ i32x4 make_rsrc_words(const void* p, unsigned bytes) 
 }
 
 // One operand's tile: ROWS matrix rows (m or n) by BK k-values, ROWS*BK*2 bytes of LDS, unpadded.
-template <int ROWS, bool KFAST, int NW, bool M16 = false>
+template <int ROWS, bool KFAST, int NW>
 struct OperandTile {
   static constexpr int BYTES = ROWS * BK * 2;
   static constexpr int INSTR = BYTES / 1024;            // direct-to-LDS load instructions per tile (1 KiB each)
@@ -71,9 +77,9 @@ struct OperandTile {
     const int s = (wave * PER_WAVE + j) * 64 + lane;    // 16-byte slot index within the tile
     line = s / CHUNKS;
     const int cs = s % CHUNKS;
-    // (M16: row-contiguous tiles read as 16-row fragments of the 16x16x32 MFMA, whose half-wavefront covers k-rows
-    // k..k+3 and k+8..k+11 at two chunks each: the k bits 0, 1 and 3 spread them over the 16 chunk positions)
-    chunk = KFAST ? (cs ^ ((line >> 1) & 7)) : M16 ? (cs ^ (((line & 3) << 2) | (((line >> 3) & 1) << 1))) : (cs ^ ((line & 3) << 2));
+    // (row-contiguous tiles: a half-wavefront of a transposing fragment read covers k-rows k..k+3 and k+8..k+11 at two
+    // chunks each; the k bits 0, 1 and 3 spread them over the 16 chunk positions of the 64 banks)
+    chunk = KFAST ? (cs ^ ((line >> 1) & 7)) : (cs ^ (((line & 3) << 2) | (((line >> 3) & 1) << 1)));
   }
   // byte offsets into the operand for k-slab 0; rows outside the matrix get the out-of-range mark
   __device__ static void init_offsets(int64_t rs, int64_t cs, int row0, int nrows, int K, unsigned (&off)[PER_WAVE]) {
@@ -91,23 +97,10 @@ struct OperandTile {
     }
     (void)K;
   }
-  // issue the loads of the slab starting at k0 into the LDS tile at `lds` (off[] already points at that slab)
-  __device__ static void load_slab(__amdgpu_buffer_rsrc_t rsrc, const unsigned (&off)[PER_WAVE], int k0, int K, LDS_AS char* lds) {
-    const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);     // the LDS address of a direct load is a scalar (M0)
-#pragma unroll
-    for (int j = 0; j < PER_WAVE; ++j) {
-      unsigned o = off[j];
-      if (KFAST) {      // a ragged last slab: chunks past K must read as zero, not as the next row
-        int line, chunk;
-        slot(j, line, chunk);
-        if (k0 + chunk * 8 >= K) o = kOob;
-      }
-      __builtin_amdgcn_raw_ptr_buffer_load_lds(rsrc, (LDS_AS void*)(lds + (wave * PER_WAVE + j) * 1024), 16, o, 0, 0, 0);
-    }
-  }
-  // The same loads issued behind the compiler's back.  It tracks loads that write LDS, cannot tell one stage from
-  // another, and makes the next transposing LDS read wait for all of them (a vmcnt(0) right after the loads: their
-  // whole latency, once per slab).  The kernel writes out the waits that are needed.  rsrc: the four descriptor words.
+  // Issue the loads of the slab starting at k0 into the LDS tile at `lds` (off[] already points at that slab; rsrc:
+  // the four descriptor words).  Written as assembly, behind the compiler's back: it tracks loads that write LDS,
+  // cannot tell one stage from another, and makes the next transposing LDS read wait for all of them (a vmcnt(0)
+  // right after the loads: their whole latency, once per slab).  The kernel writes out the waits that are needed.
   __device__ static void load_slab_untracked(i32x4 rsrc, const unsigned (&off)[PER_WAVE], int k0, int K, LDS_AS char* lds) {
     const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
 #pragma unroll
@@ -127,42 +120,6 @@ struct OperandTile {
     for (int j = 0; j < PER_WAVE; ++j) off[j] += slab_bytes;    // the mark stays out of range (extents are < 2^31)
   }
 
-  // Per-lane constants of the fragment reads.
-  struct Frag {
-    int base;   // byte offset of the lane's row (KFAST) / of its k-row and in-chunk position (!KFAST)
-    int sw;     // swizzle term
-  };
-  __device__ static Frag frag_init(int rb0) {
-    const int lane = threadIdx.x & 63;
-    Frag f;
-    if (KFAST) {
-      const int row = rb0 + (lane & 31);
-      f.base = row * PITCH;
-      f.sw = (row >> 1) & 7;
-    } else {
-      const int g = lane >> 4, i = lane & 15;
-      f.base = (8 * (g >> 1) + (i >> 2)) * PITCH + 8 * (i & 1);
-      f.sw = (rb0 / 8 + 2 * (g & 1) + ((i & 3) >> 1)) | (((i >> 2) & 3) << 8);   // chunk of row block 0 | k&3
-    }
-    return f;
-  }
-  // MFMA 32x32x16 operand fragment: rows [rb0 + 32*blk, +32), k-values [kk, kk+16) of the tile at `lds`
-  __device__ static bf16x8 fragment(const LDS_AS char* lds, const Frag& f, int blk, int kk) {
-    if (KFAST) {
-      const int lane = threadIdx.x & 63;
-      const int c = (kk / 8 + (lane >> 5)) ^ f.sw;
-      return *reinterpret_cast<const LDS_AS bf16x8*>(lds + f.base + blk * 32 * PITCH + c * 16);
-    } else {
-      const int kq = f.sw >> 8;
-      const int c = ((f.sw & 0xff) + blk * 4) ^ (kq << 2);
-      const LDS_AS char* p0 = lds + f.base + kk * PITCH + c * 16;
-      s16x4 lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16((LDS_AS s16x4*)(p0));
-      s16x4 hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16((LDS_AS s16x4*)(p0 + 4 * PITCH));
-      union { struct { s16x4 a, b; } s; bf16x8 v; } u;
-      u.s.a = lo; u.s.b = hi;
-      return u.v;
-    }
-  }
 };
 
 // Second half of the bf16/fp32-output epilogue: 32 rows x WTN columns of fp32 results staged row-major in LDS (pitch
@@ -228,204 +185,7 @@ __device__ __forceinline__ void write_staged_rows(const GemmArgs<bf16>& a, const
 // s_waitcnt operand that waits for vmcnt(n) only (6-bit counter split over two fields; the other counters at their maxima)
 constexpr int vmcnt_only(int n) { return 0x0F70 | (n & 15) | ((n >> 4) << 14); }
 
-template <int BM, int BN, int WGM, int WGN, bool AK, bool BKF, int EPI, int NS>
-__global__ void __launch_bounds__(64 * WGM * WGN) gemm_mfma_kernel(GemmArgs<bf16> a, int tiles_m, int tiles_n, int slabs_per_split) {
-  constexpr int NW = WGM * WGN;                 // wavefronts per block, in a WGM x WGN grid
-  typedef OperandTile<BM, AK, NW> TA;
-  typedef OperandTile<BN, BKF, NW> TB;
-  constexpr int WTM = BM / WGM, WTN = BN / WGN; // wavefront tile
-  constexpr int MI = WTM / 32, NI = WTN / 32;
-  constexpr int STAGE = TA::BYTES + TB::BYTES;
-  extern __shared__ __attribute__((aligned(1024))) char smem_raw[];
-  LDS_AS char* smem = (LDS_AS char*)smem_raw;
-
-  // Tile order.  Blocks are dealt round-robin to the 8 XCDs (each with its own L2), so XCD x
-  // runs blocks x, x+8, ...: give it a contiguous run of the tile order, and make that order
-  // walk 4-row groups of the tile grid column by column, so that the tiles an XCD works on at
-  // the same time form a compact patch sharing A row-panels and B column-panels in its L2.
-  const int total = tiles_m * tiles_n;
-  const int split = blockIdx.x / total;                 // which piece of the contracted axis (0 unless EPI_GRAD is split)
-  int pid = blockIdx.x % total;
-  if (total % 8 == 0) pid = (pid % 8) * (total / 8) + pid / 8;
-  constexpr int GROUP = 4;
-  const int per_group = GROUP * tiles_n;
-  const int g0 = (pid / per_group) * GROUP;
-  const int gsz = min(tiles_m - g0, GROUP);
-  const int tile_m = g0 + (pid % per_group) % gsz, tile_n = (pid % per_group) / gsz;
-  const int m0 = tile_m * BM, n0 = tile_n * BN;
-
-  const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
-  const int wm = (wave / WGN) * WTM, wn = (wave % WGN) * WTN;
-
-  f32x16 acc[MI][NI];
-#pragma unroll
-  for (int i = 0; i < MI; ++i)
-#pragma unroll
-    for (int j = 0; j < NI; ++j)
-#pragma unroll
-      for (int e = 0; e < 16; ++e) acc[i][j][e] = 0.f;
-
-  // operand extents in bytes (dense matrices: the strided pitch times the number of strided steps)
-  const unsigned a_bytes = (unsigned)(2 * (AK ? (int64_t)a.M * a.a_rs : (int64_t)a.K * a.a_cs));
-  const unsigned b_bytes = (unsigned)(2 * (BKF ? (int64_t)a.N * a.b_rs : (int64_t)a.K * a.b_cs));
-  const __amdgpu_buffer_rsrc_t ra_rsrc = make_rsrc(a.A, a_bytes), rb_rsrc = make_rsrc(a.B, b_bytes);
-  unsigned offa[TA::PER_WAVE], offb[TB::PER_WAVE];
-  TA::init_offsets(a.a_rs, a.a_cs, m0, a.M, a.K, offa);
-  TB::init_offsets(a.b_rs, a.b_cs, n0, a.N, a.K, offb);
-  const unsigned a_step = (unsigned)(2 * BK * a.a_cs), b_step = (unsigned)(2 * BK * a.b_cs);
-  const int slabs = (a.K + BK - 1) / BK;
-  const int kb0 = split * slabs_per_split;              // first k-slab of this block
-  const int nk = min(slabs - kb0, slabs_per_split);     // >= 1 by the launcher's choice of splits
-  if (kb0 > 0) {
-    TA::advance(offa, (unsigned)kb0 * a_step);
-    TB::advance(offb, (unsigned)kb0 * b_step);
-  }
-  const typename TA::Frag fra = TA::frag_init(wm);
-  const typename TB::Frag frb = TB::frag_init(wn);
-
-  // Software pipeline over k-slabs of 64 (4 MFMA k-steps of 16 each), NS LDS stages:
-  //   - fragments of k-step s+1 are read from LDS while the MFMAs of k-step s run;
-  //   - between k-steps 2 and 3 of slab kt: wait until slab kt+1 has landed in its stage (the loads of the NS-2 slabs
-  //     after it may still fly), barrier (every wavefront has finished reading the stage of slab kt: its k-step-3
-  //     fragments are in registers), then start the loads of slab kt+NS into that stage and read the first fragments
-  //     of slab kt+1 during the MFMAs of k-step 3.  One barrier per slab; a load has NS-1 slabs of MFMAs to arrive.
-  // Loads past the end of the contraction are issued all the same (their offsets are out of range and fetch
-  // nothing, or they land in a stage that is not read again), which keeps the loop body one basic block.
-  constexpr int LOADS = TA::PER_WAVE + TB::PER_WAVE;
-  static_assert((NS - 1) * LOADS < 64, "the outstanding loads must fit the counter");
-#pragma unroll
-  for (int p = 0; p < NS; ++p) {
-    if (p > 0) { TA::advance(offa, a_step); TB::advance(offb, b_step); }
-    TA::load_slab(ra_rsrc, offa, (kb0 + p) * BK, a.K, smem + p * STAGE);
-    TB::load_slab(rb_rsrc, offb, (kb0 + p) * BK, a.K, smem + p * STAGE + TA::BYTES);
-  }
-  __builtin_amdgcn_s_waitcnt(vmcnt_only((NS - 1) * LOADS));    // slab 0 has landed
-  __syncthreads();
-
-  bf16x8 fa[2][MI], fb[2][NI];
-#pragma unroll
-  for (int i = 0; i < MI; ++i) fa[0][i] = TA::fragment(smem, fra, i, 0);
-#pragma unroll
-  for (int j = 0; j < NI; ++j) fb[0][j] = TB::fragment(smem + TA::BYTES, frb, j, 0);
-
-  int st = 0;                                              // stage of slab kt
-  for (int kt = 0; kt < nk; ++kt) {
-    const int st1 = st + 1 == NS ? 0 : st + 1;             // stage of slab kt+1
-    const LDS_AS char* As = smem + st * STAGE;
-    const LDS_AS char* Bs = As + TA::BYTES;
-    LDS_AS char* An = smem + st1 * STAGE;
-#pragma unroll
-    for (int step = 0; step < 4; ++step) {
-      const int cur = step & 1, nxt = cur ^ 1;
-      if (step < 3) {
-#pragma unroll
-        for (int i = 0; i < MI; ++i) fa[nxt][i] = TA::fragment(As, fra, i, 16 * (step + 1));
-#pragma unroll
-        for (int j = 0; j < NI; ++j) fb[nxt][j] = TB::fragment(Bs, frb, j, 16 * (step + 1));
-      } else {
-        // all LDS reads of this stage are done once lgkmcnt drains; slab kt+1 has landed once at most the loads
-        // of the NS-2 slabs after it are outstanding
-        __builtin_amdgcn_s_waitcnt(vmcnt_only((NS - 2) * LOADS) & 0xF0FF);     // ... and lgkmcnt(0)
-        __syncthreads();
-        TA::advance(offa, a_step);
-        TB::advance(offb, b_step);
-        TA::load_slab(ra_rsrc, offa, (kb0 + kt + NS) * BK, a.K, smem + st * STAGE);
-        TB::load_slab(rb_rsrc, offb, (kb0 + kt + NS) * BK, a.K, smem + st * STAGE + TA::BYTES);
-#pragma unroll
-        for (int i = 0; i < MI; ++i) fa[nxt][i] = TA::fragment(An, fra, i, 0);
-#pragma unroll
-        for (int j = 0; j < NI; ++j) fb[nxt][j] = TB::fragment(An + TA::BYTES, frb, j, 0);
-      }
-#pragma unroll
-      for (int i = 0; i < MI; ++i)
-#pragma unroll
-        for (int j = 0; j < NI; ++j)
-          acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fb[cur][j], fa[cur][i], acc[i][j], 0, 0, 0);
-      // Scheduling hint: spread this k-step's fragment reads (for the next k-step) and, in k-step 3, the direct-to-LDS
-      // loads between its MFMAs instead of bunching them and then waiting.
-      constexpr int READS = (AK ? MI : 2 * MI) + (BKF ? NI : 2 * NI);
-      constexpr int SLOTS = MI * NI;
-      if (step < 3) {
-        constexpr int MFMAS_PER_READ = SLOTS / READS > 0 ? SLOTS / READS : 1;
-#pragma unroll
-        for (int r = 0; r < READS; ++r) {
-          __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);               // one DS read
-          __builtin_amdgcn_sched_group_barrier(0x008, MFMAS_PER_READ, 0);  // then MFMAs
-        }
-      } else {
-        constexpr int PER_SLOT_R = (READS + SLOTS - 1) / SLOTS, PER_SLOT_L = (LOADS + SLOTS - 1) / SLOTS;
-#pragma unroll
-        for (int r = 0; r < SLOTS; ++r) {
-          __builtin_amdgcn_sched_group_barrier(0x020, PER_SLOT_L, 0);      // direct-to-LDS loads of slab kt+2
-          __builtin_amdgcn_sched_group_barrier(0x100, PER_SLOT_R, 0);      // first fragments of slab kt+1
-          __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);               // one MFMA
-        }
-      }
-    }
-    st = st1;
-  }
-
-  // Epilogue.  The MFMAs above were issued with the operands exchanged, so each 32x32 accumulator block holds
-  // C^T: lane l owns output row m = l%32 and, for e = 0..15, the columns n = 8*(e/4) + 4*(l/32) + e%4, i.e. four
-  // groups of four consecutive columns.
-  const int h = lane >> 5;
-  if (EPI == EPI_GRAD) {
-    // fp32 gradient tile: 16-byte read-modify-write per lane (a split contraction writes its plain partial sums)
-    const bool partial = a.splits > 1;
-    float* const gbase = partial ? a.part + (int64_t)split * a.M * a.N : a.G;
-    const float scale = partial ? 1.0f : a.scale;
-    const bool accumulate = !partial && a.accumulate;
-#pragma unroll
-    for (int i = 0; i < MI; ++i) {
-      const int m = m0 + wm + 32 * i + (lane & 31);
-      if (m >= a.M) continue;
-#pragma unroll
-      for (int j = 0; j < NI; ++j)
-#pragma unroll
-        for (int q = 0; q < 4; ++q) {
-          const int n = n0 + wn + 32 * j + 8 * q + 4 * h;
-          if (n >= a.N) continue;                       // N is a multiple of 8: the group of 4 is inside or outside
-          f32x4* gp = reinterpret_cast<f32x4*>(gbase + (int64_t)m * a.N + n);
-          f32x4 v;
-#pragma unroll
-          for (int r = 0; r < 4; ++r) v[r] = scale * acc[i][j][4 * q + r];
-          if (accumulate) v += *gp;
-          *gp = v;
-        }
-    }
-    return;
-  }
-  // bf16 outputs: each wavefront passes its tile through its own LDS region, 32 rows at a time, to turn the
-  // accumulator layout into row-major 16-byte vectors; bias, residual and pre-activation are then read, and the
-  // results written, as coalesced 16-byte accesses.  (All wavefronts are past the last barrier of the main loop
-  // and hold their fragments in registers, so the operand stages are free.)
-  const int ldc = a.ldc ? a.ldc : a.N;
-  constexpr int SP = WTN + 4;                           // staging pitch in floats (16 bytes of padding per row)
-  constexpr int LPR = WTN / 8;                          // lanes per row when reading back 8 columns per lane
-  constexpr int RPS = 64 / LPR;                         // rows per read step
-  static_assert(NW * 32 * SP * 4 <= 160 * 1024, "staging regions must fit in LDS");   // the launch reserves max(stages, staging)
-  LDS_AS float* stage = (LDS_AS float*)(smem + wave * (32 * SP * 4));
-  __builtin_amdgcn_s_waitcnt(vmcnt_only(0) & 0xF0FF);     // the last (unused) slab loads and fragment reads are over,
-  __syncthreads();                                        // in every wavefront, before the stages are overwritten
-#pragma unroll
-  for (int i = 0; i < MI; ++i) {
-#pragma unroll
-    for (int j = 0; j < NI; ++j)
-#pragma unroll
-      for (int q = 0; q < 4; ++q) {
-        f32x4 v;
-#pragma unroll
-        for (int r = 0; r < 4; ++r) v[r] = acc[i][j][4 * q + r];
-        *reinterpret_cast<LDS_AS f32x4*>(stage + (lane & 31) * SP + 32 * j + 8 * q + 4 * h) = v;
-      }
-    write_staged_rows<EPI, WTN>(a, stage, m0 + wm + 32 * i, n0 + wn, ldc);
-  }
-}
-
-// ---------------------------------------------------------------------------------------------------------------
-// The same contraction with v_mfma_f32_16x16x32_bf16.  On this chip a stream of 16x16x32 products sustains about a fifth more
-// than a stream of 32x32x16 products on the same data (measured with operands held in registers: 2.0 against 1.66
-// PFLOP/s), and the LDS bytes per flop depend on the wavefront tile only, not on the MFMA shape.
+// The kernel.
 //
 // Operand fragment (16 rows x 32 k): lane l holds row l%16, k-values 8*(l/16) .. +7 -- one 16-byte LDS read of a
 // k-contiguous tile, two transposing reads (4 k-values each) of a row-contiguous one.
@@ -435,17 +195,20 @@ __global__ void __launch_bounds__(64 * WGM * WGN) gemm_mfma_kernel(GemmArgs<bf16
 // are refilled in place: as soon as the MI products of column block j have been issued, its register takes the
 // fragment of the next k-step, which is needed a whole k-step later.
 template <int BM, int BN, int WGM, int WGN, bool AK, bool BKF, int EPI, int NS>
-__global__ void __launch_bounds__(64 * WGM * WGN) gemm16_kernel(GemmArgs<bf16> a, int tiles_m, int tiles_n, int slabs_per_split) {
+__global__ void __launch_bounds__(64 * WGM * WGN) gemm_mfma_kernel(GemmArgs<bf16> a, int tiles_m, int tiles_n, int slabs_per_split) {
   constexpr int NW = WGM * WGN;
-  typedef OperandTile<BM, AK, NW, true> TA;
-  typedef OperandTile<BN, BKF, NW, true> TB;
+  typedef OperandTile<BM, AK, NW> TA;
+  typedef OperandTile<BN, BKF, NW> TB;
   constexpr int WTM = BM / WGM, WTN = BN / WGN;
   constexpr int MI = WTM / 16, NI = WTN / 16;
   constexpr int STAGE = TA::BYTES + TB::BYTES;
   extern __shared__ __attribute__((aligned(1024))) char smem_raw[];
   LDS_AS char* smem = (LDS_AS char*)smem_raw;
 
-  // tile order: as in gemm_mfma_kernel (a contiguous run per XCD, 4-row groups walked column by column)
+  // Tile order.  Blocks are dealt round-robin to the 8 XCDs (each with its own L2), so XCD x runs blocks x, x+8, ...:
+  // give it a contiguous run of the tile order, and make that order walk 4-row groups of the tile grid column by
+  // column, so that the tiles an XCD works on at the same time form a compact patch sharing A row-panels and B
+  // column-panels in its L2.
   const int total = tiles_m * tiles_n;
   const int split = blockIdx.x / total;
   int pid = blockIdx.x % total;
@@ -629,7 +392,9 @@ __global__ void __launch_bounds__(64 * WGM * WGN) gemm16_kernel(GemmArgs<bf16> a
     }
     return;
   }
-  // other outputs: 32 rows at a time through the wavefront's own LDS region (see gemm_mfma_kernel)
+  // Other outputs: each wavefront passes its tile through its own LDS region, 32 rows at a time, to turn the
+  // accumulator layout into row-major 16-byte vectors; bias, residual and pre-activation are then read, and the
+  // results written, as coalesced 16-byte accesses.
   const int ldc = a.ldc ? a.ldc : a.N;
   constexpr int SP = WTN + 4;
   static_assert(NW * 32 * SP * 4 <= 160 * 1024, "staging regions must fit in LDS");
@@ -687,22 +452,11 @@ int launch_kernel(const GemmArgs<bf16>& a, int BMv, int BNv, int threads, size_t
 
 template <int BM, int BN, int WGM, int WGN, bool AK, bool BKF, int EPI, int NS = 2>
 int launch_cfg(const GemmArgs<bf16>& a, hipStream_t s) {
-  typedef OperandTile<BM, AK, WGM * WGN> TA;
-  typedef OperandTile<BN, BKF, WGM * WGN> TB;
-  constexpr size_t staging = (size_t)WGM * WGN * 32 * (BN / WGN + 4) * 4;      // epilogue transposition area of all wavefronts
-  static_assert(NS * (TA::BYTES + TB::BYTES) <= 160 * 1024, "the stages must fit in LDS");
-  const size_t lds = std::max<size_t>(NS * (size_t)(TA::BYTES + TB::BYTES), EPI == EPI_GRAD ? 0 : staging);
-  return launch_kernel<gemm_mfma_kernel<BM, BN, WGM, WGN, AK, BKF, EPI, NS>>(a, BM, BN, 64 * WGM * WGN, lds, s);
-}
-
-// the 16x16x32 kernel (both operands k-contiguous)
-template <int BM, int BN, int WGM, int WGN, bool AK, bool BKF, int EPI, int NS = 2>
-int launch_cfg16(const GemmArgs<bf16>& a, hipStream_t s) {
   constexpr size_t stages = (size_t)NS * (BM + BN) * BK * 2;
   constexpr size_t staging = (size_t)WGM * WGN * 32 * (BN / WGN + 4) * 4;
   static_assert(stages <= 160 * 1024, "the stages must fit in LDS");
   const size_t lds = std::max<size_t>(stages, EPI == EPI_GRAD ? 0 : staging);
-  return launch_kernel<gemm16_kernel<BM, BN, WGM, WGN, AK, BKF, EPI, NS>>(a, BM, BN, 64 * WGM * WGN, lds, s);
+  return launch_kernel<gemm_mfma_kernel<BM, BN, WGM, WGN, AK, BKF, EPI, NS>>(a, BM, BN, 64 * WGM * WGN, lds, s);
 }
 
 template <bool AK, bool BKF, int EPI>
@@ -717,35 +471,19 @@ int launch_tiles(const GemmArgs<bf16>& a, hipStream_t s) {
     return t / (256.0 * (double)(int64_t)((t + 255) / 256));
   };
   int cfg = force;
-  // The 16x16x32 kernel.  256 x 128 tiles run three LDS stages (they fit, and long contractions over few tiles gain
-  // a quarter from the deeper prefetch; short ones lose nothing).
+  // 256 x 128 tiles run three LDS stages (they fit, and long contractions over few tiles gain a quarter from the
+  // deeper prefetch; short ones lose nothing).
   if (cfg == 0) {
-    double best = fill(256, 256); cfg = 11;
-    if (BKF) { const double v = 0.95 * fill(256, 192); if (v > best) { best = v; cfg = 14; } }
-    { const double v = 0.83 * fill(256, 128); if (v > best) { best = v; cfg = 12; } }
-    { const double v = 0.60 * fill(128, 128); if (v > best) { best = v; cfg = 15; } }
+    double best = fill(256, 256); cfg = 1;
+    if (BKF) { const double v = 0.95 * fill(256, 192); if (v > best) { best = v; cfg = 2; } }
+    { const double v = 0.83 * fill(256, 128); if (v > best) { best = v; cfg = 3; } }
+    { const double v = 0.60 * fill(128, 128); if (v > best) { best = v; cfg = 4; } }
   }
   switch (cfg) {
-    case 11: return launch_cfg16<256, 256, 4, 2, AK, BKF, EPI>(a, s);
-    case 12: return launch_cfg16<256, 128, 4, 2, AK, BKF, EPI, 3>(a, s);
-    case 14: if constexpr (BKF) return launch_cfg16<256, 192, 4, 2, AK, BKF, EPI>(a, s); else break;
-    case 15: return launch_cfg16<128, 128, 2, 2, AK, BKF, EPI, 3>(a, s);
-    default: break;     // 1..7: the 32x32x16 kernel, for comparison
-  }
-  if (cfg == 0 || cfg > 7) {
-    double best = fill(256, 256); cfg = 2;
-    if (BKF) { const double v = 0.93 * fill(256, 192); if (v > best) { best = v; cfg = 7; } }
-    { const double v = 0.88 * fill(256, 128); if (v > best) { best = v; cfg = 4; } }
-    { const double v = 0.70 * fill(128, 128); if (v > best) { best = v; cfg = 6; } }
-  }
-  switch (cfg) {
-    case 1: return launch_cfg<256, 256, 2, 2, AK, BKF, EPI>(a, s);
-    case 2: return AK ? launch_cfg<256, 256, 2, 4, AK, BKF, EPI>(a, s) : launch_cfg<256, 256, 4, 2, AK, BKF, EPI>(a, s);
-    case 3: return launch_cfg<256, 128, 2, 2, AK, BKF, EPI>(a, s);
-    case 4: return launch_cfg<256, 128, 4, 2, AK, BKF, EPI>(a, s);
-    case 5: return launch_cfg<256, 128, 2, 4, AK, BKF, EPI>(a, s);
-    case 7: if constexpr (BKF) return launch_cfg<256, 192, 4, 2, AK, BKF, EPI>(a, s);
-    default: return launch_cfg<128, 128, 2, 2, AK, BKF, EPI>(a, s);
+    case 1: return launch_cfg<256, 256, 4, 2, AK, BKF, EPI>(a, s);
+    case 2: if constexpr (BKF) return launch_cfg<256, 192, 4, 2, AK, BKF, EPI>(a, s); else return launch_cfg<256, 256, 4, 2, AK, BKF, EPI>(a, s);
+    case 3: return launch_cfg<256, 128, 4, 2, AK, BKF, EPI, 3>(a, s);
+    default: return launch_cfg<128, 128, 2, 2, AK, BKF, EPI, 3>(a, s);
   }
 }
 
