@@ -232,7 +232,7 @@ def main():
         # HBM bytes per launch from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE (profiles/gemm_input_gradient_and_adam_hbm_traffic.txt),
         # measured for the c5 shapes of this leg only
         traffic = 207.0e6 if (cfg.name == "c5" and key.startswith("input gradient, plain")) else None
-        roofline = {"kernel": "gemm_mfma_kernel, " + key, "bound": "mfma", "achieved": d["TFLOP/s"], "peak": PEAK_BF16_TFLOPS,
+        roofline = {"kernel": "gemm_mfma_kernel (v_mfma_f32_16x16x32_bf16), " + key, "bound": "mfma", "achieved": d["TFLOP/s"], "peak": PEAK_BF16_TFLOPS,
                     "unit": "TFLOP/s", "frac": round(d["TFLOP/s"] / PEAK_BF16_TFLOPS, 4), "traffic": traffic,
                     "avg_launch_us": d["avg_launch_us"], "flops_per_launch": d["flops_per_launch"], "launches_per_step": d["launches"]}
         extras["gemm_legs"] = legs
