@@ -184,8 +184,8 @@ int cephalo_op_gemm(int32_t dtype, const void* A, int64_t a_rs, int64_t a_cs,
 
 /* Weight gradient of a linear layer y = x W^T over T tokens, as the layer's backward computes it:
  *   G[N,K] <- (accumulate ? G : 0) + scale * sum_t dY[t,n] X[t,k]        (dY [T,N], X [T,K] row-major in dtype, G fp32)
- * In bf16 mode the narrower operand is first copied token-minor and, when the output has few tiles, the token axis is
- * cut into pieces whose partial sums are added in a fixed order (reproducible).  workspace: device, at least
+ * Both operands are read as they lie (no transposed copy).  In bf16 mode, when the output has few tiles, the token axis
+ * is cut into pieces whose partial sums are added in a fixed order (reproducible).  workspace: device, at least
  * cephalo_op_linear_wgrad_workspace(dtype, T, N, K) bytes. */
 size_t cephalo_op_linear_wgrad_workspace(int32_t dtype, int32_t T, int32_t N, int32_t K);
 int cephalo_op_linear_wgrad(int32_t dtype, const void* dY, const void* X, int32_t T, int32_t N, int32_t K,

@@ -72,7 +72,7 @@ struct SaveLayout {
 // Backward work area.  dz, dx1 and dqkv (the dY operands of the weight gradients) and the copy of dy in the
 // activation type are kept for `span` samples; the rest is per micro-batch of m samples.
 struct ScratchLayout {
-  size_t dz, dx1, dx1l, dyl, dqkv, du2, dO, du, dvec, tpose, wT, wg_part, ln_part, col_part, col_part_bytes, total;
+  size_t dz, dx1, dx1l, dyl, dqkv, du2, dO, du, dvec, wT, wg_part, ln_part, col_part, col_part_bytes, total;
   size_t ln_rows;   // rows of each of the four LayerNorm partial arrays (ln2.gamma, ln2.beta, ln1.gamma, ln1.beta)
 };
 
@@ -111,7 +111,6 @@ ScratchLayout scratch_layout(const cephalo_layer_desc& d, int m, int span) {
   L.dO = take(Tm * H * es);
   L.du = take(Tm * H * 4);
   L.dvec = take((size_t)m * d.heads * d.seq * 4);
-  L.tpose = take(Ts * H * es);     // [H, tokens] token-minor copy of one activation for the weight-gradient GEMMs
   L.wT = es == 4 ? 0 : take((size_t)param_offsets(d).total * es);   // the four weight matrices transposed, at their flat-layout offsets
   L.wg_part = p;                    // partial weight gradients of a split token axis (largest of the four projections)
   if (es != 4) {
@@ -196,20 +195,20 @@ GemmArgs<T> linear_wgrad(const T* dY, const T* X, int Tn, int N, int K, float* G
   return a;
 }
 
-// Weight gradient of a linear layer, G[N,K] (+)= scale * dY[T,N]^T X[T,K].  Both operands are strided along
-// the contracted token axis.  In bf16 the narrower of the two is first copied token-minor ([N,T] or [K,T]):
-// its MFMA fragments then come from 16-byte LDS reads, which run at about three times the rate of the
-// transposing reads the other operand needs, for one extra pass over the small matrix.
+// Parameter gradient of a linear layer over Tn tokens: G[N, K] (+)= scale * dY^T X, dY [Tn, ldy >= N], X [Tn, K].
+// Both operands are read as they lie, token-major (the contraction runs over their rows: the GEMM reads such
+// operands with transposing LDS reads at the rate of k-contiguous ones, so no transposed copy is made).
+// `part`: room for the pieces of a split contraction (sized by gemm_grad_splits for the whole token axis), or null.
 template <typename T>
-int wgrad(const T* dY, const T* X, int Tn, int N, int K, float* G, float scale, int acc, T* tbuf, float* part, hipStream_t s, int ldy = 0);
+int wgrad(const T* dY, const T* X, int Tn, int N, int K, float* G, float scale, int acc, float* part, hipStream_t s, int ldy = 0);
 template <>
-int wgrad<float>(const float* dY, const float* X, int Tn, int N, int K, float* G, float scale, int acc, float*, float*, hipStream_t s, int ldy) {
+int wgrad<float>(const float* dY, const float* X, int Tn, int N, int K, float* G, float scale, int acc, float*, hipStream_t s, int ldy) {
   GemmArgs<float> a = linear_wgrad<float>(dY, X, Tn, N, K, G, scale, acc);
   if (ldy) a.a_cs = ldy;
   return gemm<float>(a, s);
 }
 template <>
-int wgrad<bf16>(const bf16* dY, const bf16* X, int Tn, int N, int K, float* G, float scale, int acc, bf16* tbuf, float* part, hipStream_t s, int ldy) {
+int wgrad<bf16>(const bf16* dY, const bf16* X, int Tn, int N, int K, float* G, float scale, int acc, float* part, hipStream_t s, int ldy) {
   if (!ldy) ldy = N;
   // the GEMM addresses its operands through 32-bit buffer descriptors: contract over the tokens in pieces below 2 GiB
   const int64_t widest = ldy > K ? ldy : K;
@@ -222,15 +221,6 @@ int wgrad<bf16>(const bf16* dY, const bf16* X, int Tn, int N, int K, float* G, f
     a.splits = part ? gemm_grad_splits(N, K, tc) : 1;     // `part` was sized with the same rule for the whole token axis
     a.part = part;
     if (tc != Tn) a.splits = 1;
-    if (tc % 8 == 0 && K % 8 == 0 && (N % 8 == 0 || N > K || ldy != N)) {
-      if (N <= K && ldy == N) {   // dY^T [N, T] as the k-contiguous A operand
-        TRY(launch_transpose_bf16(a.A, tbuf, tc, N, s));
-        a.A = tbuf; a.a_rs = tc; a.a_cs = 1;
-      } else {                    // X^T [K, T] as the k-contiguous B operand
-        TRY(launch_transpose_bf16(a.B, tbuf, tc, K, s));
-        a.B = tbuf; a.b_rs = tc; a.b_cs = 1;
-      }
-    }
     TRY(gemm<bf16>(a, s));
   }
   return CEPHALO_OK;
@@ -257,7 +247,7 @@ Saved<T> saved_at(void* base, const SaveLayout& L, const cephalo_layer_desc& d, 
 template <typename T> struct Work {
   T *dz, *dx1l, *dyl, *dqkv;   // at the token offset of the current micro-batch (or of the span for the parameter pass)
   float *dx1;                  // likewise; dx1l is its copy in T (the same buffer in fp32 mode), dyl the caller's dy in T
-  T *dO, *tbuf, *wT;
+  T *dO, *wT;
   float *du2, *du, *dvec;
   float *ln2_g, *ln2_b, *ln1_g, *ln1_b;   // LayerNorm partial sums, at the row offset of the current micro-batch
   float *col_part; size_t col_part_bytes;
@@ -269,7 +259,7 @@ Work<T> work_at(void* base, const ScratchLayout& W, const cephalo_layer_desc& d,
   Work<T> w;
   w.dz = at<T>(base, W.dz) + t0 * F; w.dx1 = at<float>(base, W.dx1) + t0 * H; w.dx1l = at<T>(base, W.dx1l) + t0 * H;
   w.dyl = at<T>(base, W.dyl) + t0 * H; w.dqkv = at<T>(base, W.dqkv) + t0 * 3 * H;
-  w.du2 = at<float>(base, W.du2); w.dO = at<T>(base, W.dO); w.du = at<float>(base, W.du); w.tbuf = at<T>(base, W.tpose); w.wT = at<T>(base, W.wT);
+  w.du2 = at<float>(base, W.du2); w.dO = at<T>(base, W.dO); w.du = at<float>(base, W.du); w.wT = at<T>(base, W.wT);
   w.dvec = at<float>(base, W.dvec);
   float* ln = at<float>(base, W.ln_part);
   const size_t r0 = (size_t)mb_index * ln_bwd_blocks(m * d.seq) * H, arr = W.ln_rows * H;
@@ -389,15 +379,15 @@ int layer_bwd_params_t(const cephalo_layer_desc& d, const float* dy, const T* dy
   const ParamOffsets o = param_offsets(d);
   const int H = d.hidden, F = d.mlp;
   TRY(launch_colsum<float>(dy, w.col_part, w.col_part_bytes, G + o.b_fc2, scale, acc, tokens, H, s));
-  TRY(wgrad<T>(dyl, sv.h, tokens, H, F, G + o.w_fc2, scale, acc, w.tbuf, w.wg_part, s));
+  TRY(wgrad<T>(dyl, sv.h, tokens, H, F, G + o.w_fc2, scale, acc, w.wg_part, s));
   TRY(launch_colsum<T>(w.dz, w.col_part, w.col_part_bytes, G + o.b_fc1, scale, acc, tokens, F, s));
-  TRY(wgrad<T>(w.dz, sv.u2, tokens, F, H, G + o.w_fc1, scale, acc, w.tbuf, w.wg_part, s));
+  TRY(wgrad<T>(w.dz, sv.u2, tokens, F, H, G + o.w_fc1, scale, acc, w.wg_part, s));
   TRY(launch_reduce_partials(w.ln2_g, ln_chunks, H, G + o.ln2_g, scale, acc, w.col_part, w.col_part_bytes, s));
   TRY(launch_reduce_partials(w.ln2_b, ln_chunks, H, G + o.ln2_b, scale, acc, w.col_part, w.col_part_bytes, s));
   TRY(launch_colsum<float>(w.dx1, w.col_part, w.col_part_bytes, G + o.b_o, scale, acc, tokens, H, s));
-  TRY(wgrad<T>(lowp_of<T>(w.dx1, w.dx1l), sv.O, tokens, H, H, G + o.w_o, scale, acc, w.tbuf, w.wg_part, s));
+  TRY(wgrad<T>(lowp_of<T>(w.dx1, w.dx1l), sv.O, tokens, H, H, G + o.w_o, scale, acc, w.wg_part, s));
   TRY(launch_colsum<T>(w.dqkv, w.col_part, w.col_part_bytes, G + o.b_qkv, scale, acc, tokens, 3 * H, s));
-  TRY(wgrad<T>(w.dqkv, sv.u, tokens, 3 * H, H, G + o.w_qkv, scale, acc, w.tbuf, w.wg_part, s));
+  TRY(wgrad<T>(w.dqkv, sv.u, tokens, 3 * H, H, G + o.w_qkv, scale, acc, w.wg_part, s));
   TRY(launch_reduce_partials(w.ln1_g, ln_chunks, H, G + o.ln1_g, scale, acc, w.col_part, w.col_part_bytes, s));
   TRY(launch_reduce_partials(w.ln1_b, ln_chunks, H, G + o.ln1_b, scale, acc, w.col_part, w.col_part_bytes, s));
   return CEPHALO_OK;

@@ -69,8 +69,7 @@ extern "C" int cephalo_op_gemm(int32_t dtype, const void* A, int64_t a_rs, int64
 }
 
 namespace {
-// workspace of linear_wgrad: [token-minor copy of the narrow operand | partial sums of a split token axis]
-size_t wgrad_tbuf_bytes(int dtype, int T, int N, int K) { return dtype == CEPHALO_BF16 ? align_up((size_t)T * (N < K ? N : K) * 2) : 0; }
+// workspace of linear_wgrad: the partial sums of a split token axis
 size_t wgrad_part_bytes(int dtype, int T, int N, int K) {
   if (dtype != CEPHALO_BF16) return 0;
   const int sp = gemm_grad_splits(N, K, T);
@@ -80,7 +79,7 @@ size_t wgrad_part_bytes(int dtype, int T, int N, int K) {
 
 extern "C" size_t cephalo_op_linear_wgrad_workspace(int32_t dtype, int32_t T, int32_t N, int32_t K) {
   if (T <= 0 || N <= 0 || K <= 0) return 0;
-  return wgrad_tbuf_bytes(dtype, T, N, K) + wgrad_part_bytes(dtype, T, N, K) + 256;
+  return wgrad_part_bytes(dtype, T, N, K) + 256;
 }
 
 extern "C" int cephalo_op_linear_wgrad(int32_t dtype, const void* dY, const void* X, int32_t T, int32_t N, int32_t K,
@@ -93,11 +92,9 @@ extern "C" int cephalo_op_linear_wgrad(int32_t dtype, const void* dY, const void
     return fail(CEPHALO_EWORKSPACE, "linear_wgrad: workspace %zu B < %zu B", workspace_bytes, cephalo_op_linear_wgrad_workspace(dtype, T, N, K));
   hipStream_t s = static_cast<hipStream_t>(stream);
   if (dtype == CEPHALO_F32)
-    return wgrad<float>(static_cast<const float*>(dY), static_cast<const float*>(X), T, N, K, G, scale, accumulate, nullptr, nullptr, s);
-  char* ws = static_cast<char*>(workspace);
-  float* part = wgrad_part_bytes(dtype, T, N, K) ? reinterpret_cast<float*>(ws + wgrad_tbuf_bytes(dtype, T, N, K)) : nullptr;
-  return wgrad<bf16>(static_cast<const bf16*>(dY), static_cast<const bf16*>(X), T, N, K, G, scale, accumulate,
-                     reinterpret_cast<bf16*>(ws), part, s);
+    return wgrad<float>(static_cast<const float*>(dY), static_cast<const float*>(X), T, N, K, G, scale, accumulate, nullptr, s);
+  float* part = wgrad_part_bytes(dtype, T, N, K) ? static_cast<float*>(workspace) : nullptr;
+  return wgrad<bf16>(static_cast<const bf16*>(dY), static_cast<const bf16*>(X), T, N, K, G, scale, accumulate, part, s);
 }
 
 extern "C" int cephalo_op_attention_fwd(const cephalo_layer_desc* d, const void* qkv, void* O, float* lse,

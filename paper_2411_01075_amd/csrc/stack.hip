@@ -278,7 +278,7 @@ int run_stack(const cephalo_stack_desc& d, const void* Pv, const int* ids, const
   CEPHALO_CHECK_LAUNCH("mean_loss");
   {
     Work<T> w = work_at<T>(scratch, WL, ld, 0, 0, m);
-    TRY(wgrad<T>(dlogits, uf, n, V, H, G + o_wte, 1.0f, 0, w.tbuf, (float*)nullptr, s, L.ldv));        // LM-head part of d wte, whole share
+    TRY(wgrad<T>(dlogits, uf, n, V, H, G + o_wte, 1.0f, 0, (float*)nullptr, s, L.ldv));        // LM-head part of d wte, whole share
     TRY(launch_reduce_partials(lnf_g, l * nb, H, G + o_lnf, 1.0f, 0, w.col_part, w.col_part_bytes, s));
     TRY(launch_reduce_partials(lnf_b, l * nb, H, G + o_lnf + H, 1.0f, 0, w.col_part, w.col_part_bytes, s));
   }
