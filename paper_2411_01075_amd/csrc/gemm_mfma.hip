@@ -101,19 +101,20 @@ struct OperandTile {
   // the four descriptor words).  Written as assembly, behind the compiler's back: it tracks loads that write LDS,
   // cannot tell one stage from another, and makes the next transposing LDS read wait for all of them (a vmcnt(0)
   // right after the loads: their whole latency, once per slab).  The kernel writes out the waits that are needed.
-  __device__ static void load_slab_untracked(i32x4 rsrc, const unsigned (&off)[PER_WAVE], int k0, int K, LDS_AS char* lds) {
+  __device__ static void load_one(i32x4 rsrc, const unsigned (&off)[PER_WAVE], int k0, int K, LDS_AS char* lds, int j) {
     const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
-#pragma unroll
-    for (int j = 0; j < PER_WAVE; ++j) {
-      unsigned o = off[j];
-      if (KFAST) {
-        int line, chunk;
-        slot(j, line, chunk);
-        if (k0 + chunk * 8 >= K) o = kOob;
-      }
-      const unsigned dst = (unsigned)(uintptr_t)(lds + (wave * PER_WAVE + j) * 1024);   // LDS byte address, wave-uniform
-      asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tbuffer_load_dwordx4 %1, %2, 0 offen lds" :: "s"(dst), "v"(o), "s"(rsrc) : "m0");
+    unsigned o = off[j];
+    if (KFAST) {      // a ragged last slab: chunks past K must read as zero, not as the next row
+      int line, chunk;
+      slot(j, line, chunk);
+      if (k0 + chunk * 8 >= K) o = kOob;
     }
+    const unsigned dst = (unsigned)(uintptr_t)(lds + (wave * PER_WAVE + j) * 1024);   // LDS byte address, wave-uniform
+    asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tbuffer_load_dwordx4 %1, %2, 0 offen lds" :: "s"(dst), "v"(o), "s"(rsrc) : "m0");
+  }
+  __device__ static void load_slab_untracked(i32x4 rsrc, const unsigned (&off)[PER_WAVE], int k0, int K, LDS_AS char* lds) {
+#pragma unroll
+    for (int j = 0; j < PER_WAVE; ++j) load_one(rsrc, off, k0, K, lds, j);
   }
   __device__ static void advance(unsigned (&off)[PER_WAVE], unsigned slab_bytes) {
 #pragma unroll
@@ -341,32 +342,35 @@ __global__ void __launch_bounds__(64 * WGM * WGN) gemm_mfma_kernel(GemmArgs<bf16
     __syncthreads();
     TA::advance(offa, a_step);
     TB::advance(offb, b_step);
-    TA::load_slab_untracked(ra_rsrc, offa, (kb0 + kt + NS) * BK, a.K, smem + st * STAGE);
-    TB::load_slab_untracked(rb_rsrc, offb, (kb0 + kt + NS) * BK, a.K, smem + st * STAGE + TA::BYTES);
-#pragma unroll
-    for (int i = 0; i < MI; ++i) fa[0][i] = frag_a(An, i, 0);
-#pragma unroll
-    for (int j = 0; j < JB; ++j) fb[j] = frag_b(Bn, j, 0);
+    // From here on the order is pinned: after every column block's products (and the refill of its fragment) come a
+    // share of the slab's global loads and one or two of the early fragment reads of slab kt+1.  (The loads are
+    // opaque assembly, which the scheduler otherwise bunches together and strands the products behind them.)
+    constexpr int SLOTS = NI - JB;
+    constexpr int LPS = (LOADS + SLOTS - 1) / SLOTS;      // loads per slot
+    constexpr int EARLY = MI + JB;                         // fragments wanted at the start of the next slab
+    constexpr int EPS = (EARLY + SLOTS - 1) / SLOTS;       // early fragments per slot
+    auto issue_load = [&](int q) {
+      if (q < TA::PER_WAVE) TA::load_one(ra_rsrc, offa, (kb0 + kt + NS) * BK, a.K, smem + st * STAGE, q);
+      else if (q < LOADS) TB::load_one(rb_rsrc, offb, (kb0 + kt + NS) * BK, a.K, smem + st * STAGE + TA::BYTES, q - TA::PER_WAVE);
+    };
+    auto early_read = [&](int e) {
+      if (e < MI) fa[0][e] = frag_a(An, e, 0);
+      else if (e < EARLY) fb[e - MI] = frag_b(Bn, e - MI, 0);
+    };
 #pragma unroll
     for (int j = JB; j < NI; ++j) {
+      const int slot = j - JB;
+      __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+      for (int q = 0; q < LPS; ++q) issue_load(slot * LPS + q);
+      __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+      for (int e = 0; e < EPS; ++e) early_read(slot * EPS + e);
 #pragma unroll
       for (int i = 0; i < MI; ++i) acc[i][j] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(fb[j], fa[1][i], acc[i][j], 0, 0, 0);
       fb[j] = frag_b(Bn, j, 0);
     }
-    {
-      // after the barrier: the global loads and the MI + JB early reads spread over the first products, then one
-      // column fragment after every MI products
-      constexpr int EARLY = MI + JB;
-#pragma unroll
-      for (int j = JB; j < NI; ++j) {
-        const int slot = j - JB;
-        __builtin_amdgcn_sched_group_barrier(0x020, (LOADS + NI - JB - 1) / (NI - JB), 0);
-        if (slot < MI) __builtin_amdgcn_sched_group_barrier(0x100, RA + RB, 0);
-        else if (slot < EARLY) __builtin_amdgcn_sched_group_barrier(0x100, 2 * RB, 0);
-        else __builtin_amdgcn_sched_group_barrier(0x100, RB, 0);
-        __builtin_amdgcn_sched_group_barrier(0x008, MI, 0);
-      }
-    }
+    __builtin_amdgcn_sched_barrier(0);
     st = st1;
   }
 
