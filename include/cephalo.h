@@ -278,6 +278,18 @@ int cephalo_plan_compute(int32_t n_gpus, const cephalo_gpu_perf* gpus, int32_t b
 int cephalo_plan_state(int32_t n_gpus, const cephalo_gpu_perf* gpus, const int32_t* m, const cephalo_cluster_model* cluster,
                        double* ratio_out);
 
+/* Per-unit shards for given training-state ratios (Sec. 4 "Uneven Parameter Sharding": uneven collectives cost up to
+ * 15 % whatever the skew, so as few units as possible are sharded unevenly; the paper's example: two units and a 3:1
+ * ratio over two GPUs give one unit split 1:1 and one split 1:0).  n_units identical units of unit_len elements;
+ * GPU i is to hold ratio[i] (>= 0, sum 1) of all n_units * unit_len elements (targets rounded to whole elements by
+ * largest remainder).  The first n_even units are sharded evenly, GPU i holding [floor(i L / N), floor((i+1) L / N));
+ * n_even is the largest count every GPU's target can carry.  The other units are one flat run that the GPUs divide
+ * in order, each taking what its target still lacks, so a GPU's part of a unit is one slice (possibly empty).
+ * offset_out, len_out: host, [n_units][n_gpus], unit-major: GPU i's slice of unit u is [offset, offset + len) -- the
+ * (offset, len) that cephalo_shard_adam takes for that unit.  n_even_out: host, may be NULL. */
+int cephalo_plan_units(int32_t n_gpus, const double* ratio, int32_t n_units, int64_t unit_len,
+                       int64_t* offset_out, int64_t* len_out, int32_t* n_even_out);
+
 #ifdef __cplusplus
 }
 #endif

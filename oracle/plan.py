@@ -62,3 +62,28 @@ def min_max_utilisation(used, cap, state_bytes):
     res = linprog(c, A_ub=A_ub, b_ub=b_ub, A_eq=A_eq, b_eq=[state_bytes], bounds=[(0, None)] * n + [(None, None)])
     assert res.success
     return res.x[-1]
+
+
+def max_even_units_bruteforce(targets, n_units, unit_len):
+    """Sec. 4 "Uneven Parameter Sharding": the largest number of units that can be sharded evenly (every GPU the same
+    whole share unit_len / N; unit_len must be a multiple of N here) when GPU i is to hold targets[i] elements in all
+    (sum = n_units * unit_len).  Exhaustive: every way of cutting every unit into N non-negative whole parts whose
+    column sums meet the targets is enumerated, and the even rows counted.  Tiny inputs only."""
+    n = len(targets)
+    assert unit_len % n == 0 and sum(targets) == n_units * unit_len
+    even = tuple([unit_len // n] * n)
+
+    def rows(left, parts):      # all ways to write `left` as `parts` ordered non-negative integers
+        if parts == 1:
+            yield (left,)
+            return
+        for first in range(left + 1):
+            for rest in rows(left - first, parts - 1):
+                yield (first,) + rest
+
+    all_rows = list(rows(unit_len, n))
+    best = -1
+    for combo in itertools.product(all_rows, repeat=n_units):
+        if all(sum(r[i] for r in combo) == targets[i] for i in range(n)):
+            best = max(best, sum(1 for r in combo if r == even))
+    return best

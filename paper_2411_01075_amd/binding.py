@@ -82,6 +82,8 @@ SIGNATURES = {
                                             ctypes.POINTER(_i32), ctypes.POINTER(_i32), ctypes.POINTER(ctypes.c_double)]),
     "cephalo_plan_state": (ctypes.c_int, [_i32, ctypes.POINTER(GpuPerf), ctypes.POINTER(_i32), ctypes.POINTER(ClusterModel),
                                           ctypes.POINTER(ctypes.c_double)]),
+    "cephalo_plan_units": (ctypes.c_int, [_i32, ctypes.POINTER(ctypes.c_double), _i32, ctypes.c_int64, ctypes.POINTER(ctypes.c_int64),
+                                          ctypes.POINTER(ctypes.c_int64), ctypes.POINTER(_i32)]),
     "cephalo_op_attention_fwd": (ctypes.c_int, [_dp, _vp, _vp, _vp, _i32, _vp]),
     "cephalo_op_attention_bwd": (ctypes.c_int, [_dp, _vp, _vp, _vp, _vp, _vp, _vp, _i32, _vp]),
 }
@@ -312,3 +314,16 @@ def cephalo_plan_state(gpus, m, cluster):
     r = (ctypes.c_double * n)()
     _check(lib().cephalo_plan_state(n, arr, mm, ctypes.byref(cluster), r))
     return list(r)
+
+
+def cephalo_plan_units(ratio, n_units, unit_len):
+    """Returns (offsets, lens, n_even): offsets[u][i], lens[u][i] = GPU i's slice of unit u."""
+    n = len(ratio)
+    r = (ctypes.c_double * n)(*ratio)
+    off = (ctypes.c_int64 * (n * n_units))()
+    ln = (ctypes.c_int64 * (n * n_units))()
+    ne = _i32(0)
+    _check(lib().cephalo_plan_units(n, r, n_units, unit_len, off, ln, ctypes.byref(ne)))
+    offs = [[off[u * n + i] for i in range(n)] for u in range(n_units)]
+    lens = [[ln[u * n + i] for i in range(n)] for u in range(n_units)]
+    return offs, lens, ne.value

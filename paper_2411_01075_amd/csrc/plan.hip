@@ -127,3 +127,57 @@ extern "C" int cephalo_plan_state(int32_t n, const cephalo_gpu_perf* gpus, const
   for (int i = 0; i < n; ++i) ratio_out[i] = total > 0 ? state[i] / total : 1.0 / n;
   return CEPHALO_OK;
 }
+
+extern "C" int cephalo_plan_units(int32_t n, const double* ratio, int32_t units, int64_t L, int64_t* offset_out, int64_t* len_out,
+                                  int32_t* n_even_out) {
+  if (n <= 0 || units <= 0 || L <= 0 || !ratio || !offset_out || !len_out) return fail(CEPHALO_EINVAL, "plan_units: bad arguments");
+  double sum = 0.0;
+  for (int i = 0; i < n; ++i) {
+    if (!(ratio[i] >= 0.0)) return fail(CEPHALO_EINVAL, "plan_units: ratio[%d] = %g is negative", i, ratio[i]);
+    sum += ratio[i];
+  }
+  if (!(std::fabs(sum - 1.0) <= 1e-9)) return fail(CEPHALO_EINVAL, "plan_units: the ratios sum to %.12g, not 1", sum);
+  const int64_t total = (int64_t)units * L;
+  // whole-element targets: floor, then the largest remainders take what is left (ties to the lower index)
+  std::vector<int64_t> target(n);
+  std::vector<double> rem(n);
+  int64_t given = 0;
+  for (int i = 0; i < n; ++i) {
+    const double want = ratio[i] / sum * (double)total;
+    target[i] = std::min((int64_t)std::floor(want), total);
+    rem[i] = want - (double)target[i];
+    given += target[i];
+  }
+  std::vector<int> order(n);
+  std::iota(order.begin(), order.end(), 0);
+  std::stable_sort(order.begin(), order.end(), [&](int a, int b) { return rem[a] > rem[b]; });
+  for (int p = 0; given < total; p = (p + 1) % n) { ++target[order[p]]; ++given; }
+  // even shares of one unit, and how many even units every target can carry
+  std::vector<int64_t> even_off(n + 1);
+  for (int i = 0; i <= n; ++i) even_off[i] = (int64_t)((__int128)i * L / n);
+  int64_t n_even = units;
+  for (int i = 0; i < n; ++i) {
+    const int64_t share = even_off[i + 1] - even_off[i];
+    if (share > 0) n_even = std::min(n_even, target[i] / share);
+  }
+  for (int64_t u = 0; u < n_even; ++u)
+    for (int i = 0; i < n; ++i) {
+      offset_out[u * n + i] = even_off[i];
+      len_out[u * n + i] = even_off[i + 1] - even_off[i];
+    }
+  // the remaining units as one flat run divided in GPU order
+  int64_t start = 0;                                   // position in the run, in elements
+  for (int i = 0; i < n; ++i) {
+    const int64_t lack = target[i] - n_even * (even_off[i + 1] - even_off[i]);
+    const int64_t end = start + lack;
+    for (int64_t u = n_even; u < units; ++u) {
+      const int64_t u0 = (u - n_even) * L, u1 = u0 + L;
+      const int64_t lo = std::max(start, u0), hi = std::min(end, u1);
+      offset_out[u * n + i] = hi > lo ? lo - u0 : std::min(std::max(start - u0, (int64_t)0), L);
+      len_out[u * n + i] = hi > lo ? hi - lo : 0;
+    }
+    start = end;
+  }
+  if (n_even_out) *n_even_out = (int32_t)n_even;
+  return CEPHALO_OK;
+}

@@ -90,3 +90,62 @@ def test_bad_arguments():
         C.cephalo_plan_compute([(t, t, 8.0)], 0, C.cluster_model(1, 1, 1, 1, 1))
     with pytest.raises(C.CephaloError, match="error -1"):
         C.cephalo_plan_compute([(t, t, -1.0)], 4, C.cluster_model(1, 1, 1, 1, 1))
+
+
+# ---- per-unit shards: as few unevenly sharded units as possible (Sec. 4, "Uneven Parameter Sharding")
+def check_unit_plan(ratio, n_units, L, offs, lens):
+    n = len(ratio)
+    for u in range(n_units):                      # the GPUs' slices tile each unit exactly, in GPU order
+        pos = 0
+        for i in range(n):
+            assert lens[u][i] >= 0 and 0 <= offs[u][i] <= L
+            if lens[u][i] > 0:
+                assert offs[u][i] == pos
+                pos += lens[u][i]
+        assert pos == L
+    held = [sum(lens[u][i] for u in range(n_units)) for i in range(n)]
+    assert sum(held) == n_units * L
+    for i in range(n):                            # every GPU holds its ratio of the whole, to within one element
+        assert abs(held[i] - ratio[i] * n_units * L) < 1.0 + 1e-6
+    return held
+
+
+def test_unit_plan_paper_example():
+    # the paper's example: two identical units over two GPUs in a 3:1 ratio -> one unit 1:1, the other 1:0
+    offs, lens, n_even = C.cephalo_plan_units([0.75, 0.25], 2, 1000)
+    assert n_even == 1
+    assert lens == [[500, 500], [1000, 0]] and offs[0] == [0, 500] and offs[1][0] == 0
+    check_unit_plan([0.75, 0.25], 2, 1000, offs, lens)
+
+
+@pytest.mark.parametrize("seed", range(10))
+def test_unit_plan_even_count_is_maximal(seed):
+    rng = np.random.default_rng(100 + seed)
+    n = int(rng.integers(2, 4))
+    n_units = int(rng.integers(1, 4)) if n == 3 else int(rng.integers(1, 5))
+    L = n * int(rng.integers(1, 3))               # tiny units so that every cut can be enumerated
+    total = n_units * L
+    cuts = np.sort(rng.integers(0, total + 1, size=n - 1))
+    targets = np.diff(np.concatenate([[0], cuts, [total]])).astype(int).tolist()
+    ratio = [t / total for t in targets]
+    offs, lens, n_even = C.cephalo_plan_units(ratio, n_units, L)
+    held = check_unit_plan(ratio, n_units, L, offs, lens)
+    assert held == targets                        # exact targets here: ratio * total is whole
+    assert n_even == oplan.max_even_units_bruteforce(targets, n_units, L)
+    even_rows = sum(1 for u in range(n_units) if lens[u] == [L // n] * n)
+    assert even_rows >= n_even
+
+
+def test_unit_plan_even_and_degenerate_ratios():
+    offs, lens, n_even = C.cephalo_plan_units([0.25] * 4, 24, 50358272)      # equal ratios: every unit even
+    assert n_even == 24 and all(l == [12589568] * 4 for l in lens)
+    offs, lens, n_even = C.cephalo_plan_units([1.0, 0.0], 3, 7)              # one GPU holds everything: len 0 is legal
+    assert n_even == 0 and all(l == [7, 0] for l in lens)
+    check_unit_plan([1.0, 0.0], 3, 7, offs, lens)
+    # c5-like: 24 layer units, four GPUs with memory 0.4 : 0.3 : 0.2 : 0.1 -> 9 even units (0.1 * 24 * 4 = 9.6)
+    ratio = [0.4, 0.3, 0.2, 0.1]
+    offs, lens, n_even = C.cephalo_plan_units(ratio, 24, 50358272)
+    assert n_even == 9
+    check_unit_plan(ratio, 24, 50358272, offs, lens)
+    with pytest.raises(C.CephaloError):
+        C.cephalo_plan_units([0.5, 0.6], 2, 10)
