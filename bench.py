@@ -57,6 +57,8 @@ def main():
     ap.add_argument("--no-legs", action="store_true", help="skip the per-kernel legs (whole step only)")
     ap.add_argument("--checkpoint", action="store_true",
                     help="c5 only: layer-boundary activation checkpointing with recomputation in the backward (one extra forward)")
+    ap.add_argument("--offload", action="store_true",
+                    help="c5 only, implies --checkpoint: the boundary activations live in pinned host memory and move on a second stream")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build covers one GPU's share of the step; it has no collectives and runs on exactly "
@@ -79,7 +81,7 @@ def main():
 
     # ---- seeded inputs, generated on the host, then made resident in HBM
     if stack:
-        sd = C.stack_desc_from_config(cfg, checkpoint=args.checkpoint)
+        sd = C.stack_desc_from_config(cfg, checkpoint=args.checkpoint or args.offload, offload=args.offload)
         desc = sd.layer
         P = C.cephalo_stack_param_count(sd)
         params = draw_stack_params(cfg)
@@ -111,8 +113,15 @@ def main():
         loss = torch.zeros(1, dtype=torch.float32, device="cuda")
         ws = torch.empty(C.cephalo_stack_workspace_bytes(sd, b, m), dtype=torch.uint8, device="cuda")
 
+        if args.offload:
+            host_area = torch.empty(C.cephalo_stack_host_bytes(sd, b, m) // 4, dtype=torch.float32).pin_memory()
+            copy_in, copy_out = torch.cuda.Stream(), torch.cuda.Stream()
+
         def step(t):
-            C.cephalo_stack_step(sd, pcomp, ids, tgt, b, m, G, 1.0, loss, ws)
+            if args.offload:
+                C.cephalo_stack_step_offload(sd, pcomp, ids, tgt, b, m, G, 1.0, loss, ws, host_area, copy_in, copy_out)
+            else:
+                C.cephalo_stack_step(sd, pcomp, ids, tgt, b, m, G, 1.0, loss, ws)
             C.cephalo_shard_adam(p32, G, mom, var, plow, P, off, ln, lr, 0.9, 0.999, 1e-8, t)
     else:
         x = torch.from_numpy(x_h).cuda().float().contiguous()       # the residual stream is fp32
@@ -140,7 +149,10 @@ def main():
     extras = {}
     if stack:
         extras["loss"] = round(float(loss.item()), 4)
-        extras["activation_checkpointing"] = bool(args.checkpoint)
+        extras["activation_checkpointing"] = bool(args.checkpoint or args.offload)
+        extras["activation_offload"] = bool(args.offload)
+        if args.offload:
+            extras["host_area_GB"] = round(host_area.numel() * 4 / 1e9, 2)
         extras["workspace_GB"] = round(ws.numel() / 1e9, 2)
     if bf16:
         extras["whole_step_model_tflops"] = round(step_flops / (elapsed / args.steps) / 1e12, 1)

@@ -216,6 +216,13 @@ typedef struct cephalo_stack_desc {
                           Checkpointing and Offloading"): only the layer-boundary activations are kept, and the backward
                           of a layer first runs that layer's forward again for all micro-batches.  Same results bit for
                           bit; the work area holds one layer's internals instead of L; costs one extra forward. */
+  int32_t offload;     /* 0, or 1 (needs checkpoint = 1): the layer-boundary activations live in pinned host memory instead
+                          of the work area (the same section, and the supplementary figure on activation offloading): a
+                          micro-batch's boundary activation is copied out on a second stream while the next micro-batch
+                          runs and is fetched back ahead of its use, in the forward as the next layer's input and in the
+                          backward for the recomputation; the device holds four micro-batches of them.  Same results bit
+                          for bit.  (The gradient of the residual stream, two [b*S, H] buffers, stays on the device; the
+                          paper moves that to the host too.)  Goes with cephalo_stack_step_offload. */
 } cephalo_stack_desc;
 
 /* V*H + S*H + L*P_layer + 2H; negative on a bad desc. */
@@ -223,8 +230,8 @@ int64_t cephalo_stack_param_count(const cephalo_stack_desc* desc);
 
 /* Bytes of the single work area of cephalo_stack_step (layer-boundary activations and saved activations of
  * every layer and micro-batch, one micro-batch of logits and the share's logit gradients, backward buffers).
- * Host pointer out.  The area begins with the layer-boundary activations, fp32 [layers+1][b*S][H]: entry 0 is the
- * embedding output, entry i the output of layer i-1; they are valid after cephalo_stack_step returns. */
+ * Host pointer out.  Without offload the area begins with the layer-boundary activations, fp32 [layers+1][b*S][H]:
+ * entry 0 is the embedding output, entry i the output of layer i-1; they are valid after cephalo_stack_step returns. */
 int cephalo_stack_workspace_bytes(const cephalo_stack_desc* desc, int32_t batch_share, int32_t micro_batch, size_t* bytes);
 
 /* Forward, loss and backward of the whole share (b = l*m, Sec. 3.2):
@@ -238,6 +245,23 @@ int cephalo_stack_step(const cephalo_stack_desc* desc, const void* flat_param,
                        const int32_t* ids, const int32_t* targets, int32_t batch_share, int32_t micro_batch,
                        float* flat_grad, float grad_scale, float* loss,
                        void* workspace, size_t workspace_bytes, void* stream);
+
+/* The same step for a desc with offload = 1 (Sec. 3.2 "Activation Checkpointing and Offloading").
+ *   host_area    HOST memory, page-locked (pinned) so that the copies run asynchronously, at least
+ *                cephalo_stack_host_bytes(...) bytes; afterwards it holds the layer-boundary activations, fp32
+ *                [layers+1][b*S][H] as described for the work area above.  Caller-owned.
+ *   copy_in_stream, copy_out_stream   HIP streams other than `stream` on which the library enqueues the copies to the
+ *                device and to the host (two streams keep both directions of the link busy; the same stream may be
+ *                given for both); events order them against `stream`.  When the call returns everything is enqueued
+ *                and `stream` ends behind the last copy: synchronising `stream` is enough before the host area is
+ *                read or released.
+ * The library creates and destroys a handful of HIP events per call (no device memory). */
+int cephalo_stack_host_bytes(const cephalo_stack_desc* desc, int32_t batch_share, int32_t micro_batch, size_t* bytes);
+int cephalo_stack_step_offload(const cephalo_stack_desc* desc, const void* flat_param,
+                               const int32_t* ids, const int32_t* targets, int32_t batch_share, int32_t micro_batch,
+                               float* flat_grad, float grad_scale, float* loss,
+                               void* workspace, size_t workspace_bytes, void* host_area, size_t host_bytes,
+                               void* stream, void* copy_in_stream, void* copy_out_stream);
 
 /* ---------------------------------------------------------------------------------------
  * Planning on the host (no device involved): how the global batch and the training state are divided over the

@@ -36,11 +36,12 @@ def desc_from_config(cfg):
 
 
 class StackDesc(ctypes.Structure):
-    _fields_ = [("layer", LayerDesc), ("layers", ctypes.c_int32), ("vocab", ctypes.c_int32), ("checkpoint", ctypes.c_int32)]
+    _fields_ = [("layer", LayerDesc), ("layers", ctypes.c_int32), ("vocab", ctypes.c_int32), ("checkpoint", ctypes.c_int32),
+                ("offload", ctypes.c_int32)]
 
 
-def stack_desc_from_config(cfg, checkpoint=False):
-    return StackDesc(desc_from_config(cfg), int(cfg.layers), int(cfg.vocab), int(bool(checkpoint)))
+def stack_desc_from_config(cfg, checkpoint=False, offload=False):
+    return StackDesc(desc_from_config(cfg), int(cfg.layers), int(cfg.vocab), int(bool(checkpoint)), int(bool(offload)))
 
 
 class GpuPerf(ctypes.Structure):
@@ -74,6 +75,9 @@ SIGNATURES = {
     "cephalo_stack_param_count": (_i64, [ctypes.POINTER(StackDesc)]),
     "cephalo_stack_workspace_bytes": (ctypes.c_int, [ctypes.POINTER(StackDesc), _i32, _i32, ctypes.POINTER(_sz)]),
     "cephalo_stack_step": (ctypes.c_int, [ctypes.POINTER(StackDesc), _vp, _vp, _vp, _i32, _i32, _vp, _f32, _vp, _vp, _sz, _vp]),
+    "cephalo_stack_host_bytes": (ctypes.c_int, [ctypes.POINTER(StackDesc), _i32, _i32, ctypes.POINTER(_sz)]),
+    "cephalo_stack_step_offload": (ctypes.c_int, [ctypes.POINTER(StackDesc), _vp, _vp, _vp, _i32, _i32, _vp, _f32, _vp, _vp, _sz,
+                                                  _vp, _sz, _vp, _vp, _vp]),
     "cephalo_op_gemm": (ctypes.c_int, [_i32, _vp, _i64, _i64, _vp, _i64, _i64, _i32, _i32, _i32, _i32, _vp, _vp, _vp, _vp,
                                        _vp, _f32, _i32, _vp]),
     "cephalo_op_linear_wgrad_workspace": (_sz, [_i32, _i32, _i32, _i32]),
@@ -115,6 +119,14 @@ def _ptr(t):
         return None
     if not t.is_cuda:
         raise CephaloError("expected a device tensor")
+    if not t.is_contiguous():
+        raise CephaloError("expected a contiguous tensor")
+    return t.data_ptr()
+
+
+def _pinned_ptr(t):
+    if t.is_cuda or not t.is_pinned():
+        raise CephaloError("expected a pinned host tensor")
     if not t.is_contiguous():
         raise CephaloError("expected a contiguous tensor")
     return t.data_ptr()
@@ -254,6 +266,25 @@ def cephalo_stack_step(sdesc, flat_param, ids, targets, batch_share, micro_batch
     _check(lib().cephalo_stack_step(ctypes.byref(sdesc), _ptr(flat_param), _ptr(ids), _ptr(targets), batch_share, micro_batch,
                                     _ptr(flat_grad), grad_scale, _ptr(loss), _ptr(workspace),
                                     workspace.numel() * workspace.element_size(), _stream(stream)))
+
+
+def cephalo_stack_host_bytes(sdesc, batch_share, micro_batch):
+    out = _sz(0)
+    _check(lib().cephalo_stack_host_bytes(ctypes.byref(sdesc), batch_share, micro_batch, ctypes.byref(out)))
+    return int(out.value)
+
+
+def cephalo_stack_step_offload(sdesc, flat_param, ids, targets, batch_share, micro_batch, flat_grad, grad_scale, loss, workspace,
+                               host_area, copy_in_stream, copy_out_stream=None, stream=None):
+    """host_area: a pinned CPU tensor; copy_*_stream: torch.cuda.Stream objects other than the compute stream (one for the
+    copies to the device, one for the copies to the host; the second defaults to the first)."""
+    if copy_out_stream is None:
+        copy_out_stream = copy_in_stream
+    _check(lib().cephalo_stack_step_offload(ctypes.byref(sdesc), _ptr(flat_param), _ptr(ids), _ptr(targets), batch_share, micro_batch,
+                                            _ptr(flat_grad), grad_scale, _ptr(loss), _ptr(workspace),
+                                            workspace.numel() * workspace.element_size(), _pinned_ptr(host_area),
+                                            host_area.numel() * host_area.element_size(), _stream(stream), _stream(copy_in_stream),
+                                            _stream(copy_out_stream)))
 
 
 def flatten_stack_params(sdesc, params):

@@ -173,6 +173,8 @@ int check_stack(const cephalo_stack_desc* d) {
   TRY(check_desc(&d->layer));
   if (d->layers <= 0 || d->vocab <= 0) return fail(CEPHALO_EINVAL, "stack desc: layers %d and vocab %d must be positive", d->layers, d->vocab);
   if (d->checkpoint != 0 && d->checkpoint != 1) return fail(CEPHALO_EINVAL, "stack desc: checkpoint must be 0 or 1");
+  if (d->offload != 0 && d->offload != 1) return fail(CEPHALO_EINVAL, "stack desc: offload must be 0 or 1");
+  if (d->offload && !d->checkpoint) return fail(CEPHALO_EINVAL, "stack desc: offload needs checkpoint = 1 (only boundary activations are offloaded)");
   return CEPHALO_OK;
 }
 
@@ -186,7 +188,7 @@ size_t sort_temp_bytes(int n) {
 }
 
 struct StackLayout {
-  size_t xs, saves, save_each, scratch, dxa, dxb, dxal, dxbl, uf, meanf, rstdf, duf, logits, dlogits, wteT, loss, lnf_part, keys, sort_tmp, sort_tmp_bytes, total;
+  size_t xs, xdump, saves, save_each, scratch, dxa, dxb, dxal, dxbl, uf, meanf, rstdf, duf, logits, dlogits, wteT, loss, lnf_part, keys, sort_tmp, sort_tmp_bytes, total;
   int ldv;            // padded pitch of the logits
   size_t lnf_rows;
 };
@@ -200,7 +202,10 @@ StackLayout stack_layout(const cephalo_stack_desc& d, int b, int m) {
                                        // 128-byte slab of a row straddle two cache lines: measured 658 against 893 TFLOP/s for the head's input gradient)
   size_t p = 0;
   auto take = [&](size_t bytes) { size_t at = p; p += align_up(bytes); return at; };
-  L.xs = take((size_t)(d.layers + 1) * n * H * 4);      // layer-boundary activations: the fp32 residual stream
+  // layer-boundary activations, the fp32 residual stream: all of them, or (offload) two micro-batches coming in from the
+  // host and two going out; with checkpointing also one micro-batch where the recomputed layer output is dropped
+  L.xs = take(d.offload ? 4 * Tm * H * 4 : (size_t)(d.layers + 1) * n * H * 4);
+  L.xdump = d.checkpoint ? take(Tm * H * 4) : 0;
   L.save_each = align_up(save_layout(ld, b).total);
   L.saves = take((size_t)(d.checkpoint ? 1 : d.layers) * L.save_each);   // checkpointing: one layer's internals at a time
   L.scratch = take(scratch_layout(ld, m, b).total);
@@ -221,9 +226,84 @@ StackLayout stack_layout(const cephalo_stack_desc& d, int b, int m) {
   return L;
 }
 
+// Where the layer-boundary activations [layers+1][b*S][H] live.  Resident: in the work area.  Offloaded (Sec. 3.2
+// "Activation Checkpointing and Offloading" and the supplementary figure on offloading): in pinned host memory; a
+// micro-batch's boundary activation goes to the host on the copy stream as soon as it is computed, while the next
+// micro-batch runs, and comes back (two micro-batches of look-ahead) before it is needed, in the forward as the next
+// layer's input and in the backward for the recomputation.  Accesses are sequential, so two device slots per direction
+// and a handful of events order the streams; copies to the host and copies to the device have a stream each, so that
+// both directions of the link are in use at once.
+struct Boundary {
+  bool offload = false;
+  float* base = nullptr;           // resident: device [layers+1][n][H]; offload: host, same layout
+  float* in_slot[2] = {nullptr, nullptr};
+  float* out_slot[2] = {nullptr, nullptr};
+  size_t n = 0, Tm = 0, H = 0;
+  hipStream_t c = nullptr, xin = nullptr, xout = nullptr;   // compute, host-to-device copies, device-to-host copies
+  hipEvent_t pre[2], free_in[2], comp[2], off[2], written, last;
+  long issued = 0, consumed = 0, produced = 0;
+  int err = CEPHALO_OK;
+
+  float* at(int k, int j) const { return base + ((size_t)k * n + (size_t)j * Tm) * H; }
+  void check(hipError_t e, const char* what) {
+    if (e != hipSuccess && err == CEPHALO_OK) err = fail(CEPHALO_EHIP, "stack_step (offload): %s: %s", what, hipGetErrorString(e));
+  }
+  int open() {
+    if (!offload) return CEPHALO_OK;
+    for (hipEvent_t* e : {&pre[0], &pre[1], &free_in[0], &free_in[1], &comp[0], &comp[1], &off[0], &off[1], &written, &last})
+      check(hipEventCreateWithFlags(e, hipEventDisableTiming), "event");
+    return err;
+  }
+  // start bringing boundary k of micro-batch j to the device (no-op when resident or when j is past the share)
+  void prefetch(int k, int j, int l) {
+    if (!offload || j >= l) return;
+    const int slot = (int)(issued % 2);
+    check(hipStreamWaitEvent(xin, free_in[slot], 0), "wait");         // the slot's previous reader is done
+    check(hipStreamWaitEvent(xin, written, 0), "wait");               // every copy to the host enqueued so far has landed
+    check(hipMemcpyAsync(in_slot[slot], at(k, j), Tm * H * 4, hipMemcpyHostToDevice, xin), "copy to device");
+    check(hipEventRecord(pre[slot], xin), "record");
+    ++issued;
+  }
+  const float* in(int k, int j, int l) {
+    if (!offload) return at(k, j);
+    if (consumed == issued) prefetch(k, j, l);
+    check(hipStreamWaitEvent(c, pre[consumed % 2], 0), "wait");
+    return in_slot[consumed % 2];
+  }
+  void in_done() {
+    if (!offload) return;
+    check(hipEventRecord(free_in[consumed % 2], c), "record");
+    ++consumed;
+  }
+  float* out(int k, int j) {
+    if (!offload) return at(k, j);
+    check(hipStreamWaitEvent(c, off[produced % 2], 0), "wait");        // the slot's previous content has left
+    return out_slot[produced % 2];
+  }
+  void out_done(int k, int j) {
+    if (!offload) return;
+    const int slot = (int)(produced % 2);
+    check(hipEventRecord(comp[slot], c), "record");
+    check(hipStreamWaitEvent(xout, comp[slot], 0), "wait");
+    check(hipMemcpyAsync(at(k, j), out_slot[slot], Tm * H * 4, hipMemcpyDeviceToHost, xout), "copy to host");
+    check(hipEventRecord(off[slot], xout), "record");
+    check(hipEventRecord(written, xout), "record");
+    ++produced;
+  }
+  // the compute stream ends behind the copy streams, so that a caller who waits for it may release the host area
+  int close() {
+    if (!offload) return CEPHALO_OK;
+    check(hipEventRecord(last, xin), "record");
+    check(hipStreamWaitEvent(c, last, 0), "wait");
+    check(hipStreamWaitEvent(c, written, 0), "wait");
+    for (hipEvent_t e : {pre[0], pre[1], free_in[0], free_in[1], comp[0], comp[1], off[0], off[1], written, last}) check(hipEventDestroy(e), "event");
+    return err;
+  }
+};
+
 template <typename T>
 int run_stack(const cephalo_stack_desc& d, const void* Pv, const int* ids, const int* targets, int b, int m,
-              float* G, float scale, float* loss_out, void* ws, hipStream_t s) {
+              float* G, float scale, float* loss_out, void* ws, float* host_area, hipStream_t s, hipStream_t copy_in, hipStream_t copy_out) {
   const cephalo_layer_desc& ld = d.layer;
   const T* P = static_cast<const T*>(Pv);
   const int S = ld.seq, H = ld.hidden, V = d.vocab, NL = d.layers, l = b / m;
@@ -233,18 +313,38 @@ int run_stack(const cephalo_stack_desc& d, const void* Pv, const int* ids, const
   const StackLayout L = stack_layout(d, b, m);
   const SaveLayout SL = save_layout(ld, b);
   const ScratchLayout WL = scratch_layout(ld, m, b);
-  auto xs = [&](int layer) { return at<float>(ws, L.xs) + (size_t)layer * n * H; };
   void* scratch = at<char>(ws, L.scratch);
   const size_t act = (size_t)Tm * H;
+  Boundary X;
+  X.offload = d.offload != 0;
+  X.n = n; X.Tm = Tm; X.H = H; X.c = s; X.xin = copy_in; X.xout = copy_out;
+  if (X.offload) {
+    X.base = host_area;
+    for (int i = 0; i < 2; ++i) { X.in_slot[i] = at<float>(ws, L.xs) + i * act; X.out_slot[i] = at<float>(ws, L.xs) + (2 + i) * act; }
+  } else {
+    X.base = at<float>(ws, L.xs);
+  }
+  TRY(X.open());
+  struct Closer { Boundary& x; bool done = false; ~Closer() { if (!done) (void)x.close(); } } closer{X};   // events are released on every path
 
   // ---- forward
-  embed_fwd_kernel<T><<<(n + 3) / 4, kThreads, 0, s>>>(ids, P + o_wte, P + o_wpe, xs(0), n, S, H, V);
-  CEPHALO_CHECK_LAUNCH("embed_fwd");
+  for (int j = 0; j < l; ++j) {
+    embed_fwd_kernel<T><<<(Tm + 3) / 4, kThreads, 0, s>>>(ids + (size_t)j * Tm, P + o_wte, P + o_wpe, X.out(0, j), Tm, S, H, V);
+    CEPHALO_CHECK_LAUNCH("embed_fwd");
+    X.out_done(0, j);
+  }
   auto save_of = [&](int layer) { return at<char>(ws, L.saves + (d.checkpoint ? 0 : (size_t)layer * L.save_each)); };
   for (int li = 0; li < NL; ++li) {
     void* save = save_of(li);
-    for (int j = 0; j < l; ++j)
-      TRY(layer_fwd_t<T>(ld, P + o_layers + li * PL, xs(li) + j * act, xs(li + 1) + j * act, m, saved_at<T>(save, SL, ld, j * m), s));
+    X.prefetch(li, 0, l);
+    for (int j = 0; j < l; ++j) {
+      const float* xi = X.in(li, j, l);
+      X.prefetch(li, j + 1, l);
+      float* xo = X.out(li + 1, j);
+      TRY(layer_fwd_t<T>(ld, P + o_layers + li * PL, xi, xo, m, saved_at<T>(save, SL, ld, j * m), s));
+      X.in_done();
+      X.out_done(li + 1, j);
+    }
   }
   // ---- head: final LN, tied logits (fp32, one micro-batch at a time), cross-entropy and its gradient, back to the last layer's output
   T* uf = at<T>(ws, L.uf); float* logits = at<float>(ws, L.logits); T* dlogits = at<T>(ws, L.dlogits); float* duf = at<float>(ws, L.duf);
@@ -255,9 +355,12 @@ int run_stack(const cephalo_stack_desc& d, const void* Pv, const int* ids, const
   const float coef = scale / (float)n;
   const int nb = ln_bwd_blocks(Tm);
   TRY(prepare_head_weights<T>(P + o_wte, at<T>(ws, L.wteT), V, H, L.ldv, s));
+  X.prefetch(NL, 0, l);
   for (int j = 0; j < l; ++j) {
     const size_t t0 = (size_t)j * Tm;
-    TRY(launch_ln_fwd<T>(xs(NL) + t0 * H, P + o_lnf, P + o_lnf + H, uf + t0 * H, meanf + t0, rstdf + t0, Tm, H, ld.ln_eps, s));
+    const float* xL = X.in(NL, j, l);
+    X.prefetch(NL, j + 1, l);
+    TRY(launch_ln_fwd<T>(xL, P + o_lnf, P + o_lnf + H, uf + t0 * H, meanf + t0, rstdf + t0, Tm, H, ld.ln_eps, s));
     T* dlg = dlogits + t0 * L.ldv;
     {
       GemmArgs<T> a = linear_fwd<T>(uf + t0 * H, P + o_wte, Tm, V, H);
@@ -271,8 +374,9 @@ int run_stack(const cephalo_stack_desc& d, const void* Pv, const int* ids, const
       a.epi = EPI_NONE; a.Cf = duf;
       TRY(gemm<T>(a, s));
     }
-    TRY(launch_ln_bwd<T>(duf, xs(NL) + t0 * H, meanf + t0, rstdf + t0, P + o_lnf, (const float*)nullptr, dx_cur + t0 * H,
+    TRY(launch_ln_bwd<T>(duf, xL, meanf + t0, rstdf + t0, P + o_lnf, (const float*)nullptr, dx_cur + t0 * H,
                          lowp_out<T>(dxl_cur + t0 * H), lnf_g + (size_t)j * nb * H, lnf_b + (size_t)j * nb * H, Tm, H, s));
+    X.in_done();
   }
   mean_kernel<<<1, kThreads, 0, s>>>(at<float>(ws, L.loss), n, loss_out);
   CEPHALO_CHECK_LAUNCH("mean_loss");
@@ -286,14 +390,19 @@ int run_stack(const cephalo_stack_desc& d, const void* Pv, const int* ids, const
   for (int li = NL - 1; li >= 0; --li) {
     void* save = save_of(li);
     const T* Pl = P + o_layers + li * PL;
-    if (d.checkpoint && li != NL - 1) {   // recompute this layer's internals from its boundary input (the last layer's are still there);
-      for (int j = 0; j < l; ++j)         // its output is rewritten with the same values
-        TRY(layer_fwd_t<T>(ld, Pl, xs(li) + j * act, xs(li + 1) + j * act, m, saved_at<T>(save, SL, ld, j * m), s));
-    }
     TRY(prepare_dgrad_weights<T>(ld, Pl, work_at<T>(scratch, WL, ld, 0, 0, m).wT, s));
-    for (int j = 0; j < l; ++j)
-      TRY(layer_bwd_data_t<T>(ld, Pl, xs(li) + j * act, dx_cur + j * act, lowp_of<T>(dx_cur, dxl_cur) + j * act, dx_nxt + j * act,
+    // Checkpointing: a micro-batch's internals are recomputed from its boundary input right before its backward (the
+    // last layer's are still there from the forward); the recomputed output, the same values again, is dropped.
+    const bool recompute = d.checkpoint && li != NL - 1;
+    X.prefetch(li, 0, l);
+    for (int j = 0; j < l; ++j) {
+      const float* xi = X.in(li, j, l);
+      X.prefetch(li, j + 1, l);
+      if (recompute) TRY(layer_fwd_t<T>(ld, Pl, xi, at<float>(ws, L.xdump), m, saved_at<T>(save, SL, ld, j * m), s));
+      TRY(layer_bwd_data_t<T>(ld, Pl, xi, dx_cur + j * act, lowp_of<T>(dx_cur, dxl_cur) + j * act, dx_nxt + j * act,
                               dxl_nxt + j * act, m, saved_at<T>(save, SL, ld, j * m), work_at<T>(scratch, WL, ld, j * m, j, m), s));
+      X.in_done();
+    }
     TRY(layer_bwd_params_t<T>(ld, dx_cur, lowp_of<T>(dx_cur, dxl_cur), n, l * nb, saved_at<T>(save, SL, ld, 0),
                               work_at<T>(scratch, WL, ld, 0, 0, m), G + o_layers + li * PL, 1.0f, 0, s));
     { float* t = dx_cur; dx_cur = dx_nxt; dx_nxt = t; }
@@ -309,7 +418,8 @@ int run_stack(const cephalo_stack_desc& d, const void* Pv, const int* ids, const
     return fail(CEPHALO_EHIP, "stack_step: sort of the token ids failed");
   embed_bwd_kernel<<<(n + 3) / 4, kThreads, 0, s>>>(keys_out, vals_out, dx_cur, G + o_wte, n, H);
   CEPHALO_CHECK_LAUNCH("embed_bwd");
-  return CEPHALO_OK;
+  closer.done = true;
+  return X.close();
 }
 
 }  // namespace
@@ -334,9 +444,10 @@ extern "C" int cephalo_stack_workspace_bytes(const cephalo_stack_desc* d, int32_
   return CEPHALO_OK;
 }
 
-extern "C" int cephalo_stack_step(const cephalo_stack_desc* d, const void* flat_param, const int32_t* ids, const int32_t* targets,
-                                  int32_t batch_share, int32_t micro_batch, float* flat_grad, float grad_scale, float* loss,
-                                  void* workspace, size_t workspace_bytes, void* stream) {
+namespace {
+int stack_step_checked(const cephalo_stack_desc* d, const void* flat_param, const int32_t* ids, const int32_t* targets,
+                       int32_t batch_share, int32_t micro_batch, float* flat_grad, float grad_scale, float* loss,
+                       void* workspace, size_t workspace_bytes, void* host_area, size_t host_bytes, void* stream, void* copy_in, void* copy_out) {
   TRY(check_stack(d));
   if (micro_batch <= 0 || batch_share <= 0 || batch_share % micro_batch != 0)
     return fail(CEPHALO_EINVAL, "stack_step: batch share b = %d is not a positive multiple of micro-batch size m = %d",
@@ -349,8 +460,45 @@ extern "C" int cephalo_stack_step(const cephalo_stack_desc* d, const void* flat_
     return fail(CEPHALO_EINVAL, "stack_step: flat_param, flat_grad and workspace must be 16-byte aligned");
   const size_t need = stack_layout(*d, batch_share, micro_batch).total;
   if (workspace_bytes < need) return fail(CEPHALO_EWORKSPACE, "stack_step: workspace %zu B < %zu B", workspace_bytes, need);
-  hipStream_t s = static_cast<hipStream_t>(stream);
+  if (d->offload) {
+    size_t host_need = 0;
+    TRY(cephalo_stack_host_bytes(d, batch_share, micro_batch, &host_need));
+    if (!host_area || host_bytes < host_need) return fail(CEPHALO_EWORKSPACE, "stack_step: host area %zu B < %zu B", host_bytes, host_need);
+    if (!copy_in || !copy_out || copy_in == stream || copy_out == stream)
+      return fail(CEPHALO_EINVAL, "stack_step: offload needs copy streams other than the compute stream");
+  }
+  hipStream_t s = static_cast<hipStream_t>(stream), ci = static_cast<hipStream_t>(copy_in), co = static_cast<hipStream_t>(copy_out);
   if (d->layer.dtype == CEPHALO_F32)
-    return run_stack<float>(*d, flat_param, ids, targets, batch_share, micro_batch, flat_grad, grad_scale, loss, workspace, s);
-  return run_stack<bf16>(*d, flat_param, ids, targets, batch_share, micro_batch, flat_grad, grad_scale, loss, workspace, s);
+    return run_stack<float>(*d, flat_param, ids, targets, batch_share, micro_batch, flat_grad, grad_scale, loss, workspace,
+                            static_cast<float*>(host_area), s, ci, co);
+  return run_stack<bf16>(*d, flat_param, ids, targets, batch_share, micro_batch, flat_grad, grad_scale, loss, workspace,
+                         static_cast<float*>(host_area), s, ci, co);
+}
+}  // namespace
+
+extern "C" int cephalo_stack_host_bytes(const cephalo_stack_desc* d, int32_t batch_share, int32_t micro_batch, size_t* bytes) {
+  TRY(check_stack(d));
+  if (micro_batch <= 0 || batch_share <= 0 || batch_share % micro_batch != 0)
+    return fail(CEPHALO_EINVAL, "stack_host_bytes: batch share b = %d is not a positive multiple of micro-batch size m = %d",
+                batch_share, micro_batch);
+  if (!bytes) return fail(CEPHALO_EINVAL, "stack_host_bytes: null output");
+  *bytes = d->offload ? (size_t)(d->layers + 1) * batch_share * d->layer.seq * d->layer.hidden * sizeof(float) : 0;
+  return CEPHALO_OK;
+}
+
+extern "C" int cephalo_stack_step(const cephalo_stack_desc* d, const void* flat_param, const int32_t* ids, const int32_t* targets,
+                                  int32_t batch_share, int32_t micro_batch, float* flat_grad, float grad_scale, float* loss,
+                                  void* workspace, size_t workspace_bytes, void* stream) {
+  if (d && d->offload) return fail(CEPHALO_EINVAL, "stack_step: a desc with offload = 1 goes to cephalo_stack_step_offload");
+  return stack_step_checked(d, flat_param, ids, targets, batch_share, micro_batch, flat_grad, grad_scale, loss,
+                            workspace, workspace_bytes, nullptr, 0, stream, nullptr, nullptr);
+}
+
+extern "C" int cephalo_stack_step_offload(const cephalo_stack_desc* d, const void* flat_param, const int32_t* ids, const int32_t* targets,
+                                          int32_t batch_share, int32_t micro_batch, float* flat_grad, float grad_scale, float* loss,
+                                          void* workspace, size_t workspace_bytes, void* host_area, size_t host_bytes,
+                                          void* stream, void* copy_in_stream, void* copy_out_stream) {
+  if (d && !d->offload) return fail(CEPHALO_EINVAL, "stack_step_offload: the desc has offload = 0");
+  return stack_step_checked(d, flat_param, ids, targets, batch_share, micro_batch, flat_grad, grad_scale, loss,
+                            workspace, workspace_bytes, host_area, host_bytes, stream, copy_in_stream, copy_out_stream);
 }

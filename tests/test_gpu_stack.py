@@ -23,8 +23,8 @@ CASES = {
 }
 
 
-def run_gpu(cfg, params, ids, tgt, scale, checkpoint=False):
-    sd = C.stack_desc_from_config(cfg, checkpoint)
+def run_gpu(cfg, params, ids, tgt, scale, checkpoint=False, offload=False, keep=None):
+    sd = C.stack_desc_from_config(cfg, checkpoint, offload)
     flat32 = torch.from_numpy(C.flatten_stack_params(sd, params)).cuda()
     if cfg.dtype == "bf16":
         flat = torch.empty(flat32.numel(), dtype=torch.bfloat16, device="cuda")
@@ -34,9 +34,23 @@ def run_gpu(cfg, params, ids, tgt, scale, checkpoint=False):
     ws = torch.empty(C.cephalo_stack_workspace_bytes(sd, cfg.batch_share, cfg.micro_batch), dtype=torch.uint8, device="cuda")
     G = torch.full((flat32.numel(),), float("nan"), dtype=torch.float32, device="cuda")
     loss = torch.full((1,), float("nan"), dtype=torch.float32, device="cuda")
-    C.cephalo_stack_step(sd, flat, torch.from_numpy(ids).cuda(), torch.from_numpy(tgt).cuda(), cfg.batch_share, cfg.micro_batch,
-                         G, scale, loss, ws)
-    torch.cuda.synchronize()
+    n_bound = (cfg.layers + 1) * cfg.batch_share * cfg.seq * cfg.hidden
+    if offload:
+        host = torch.full((C.cephalo_stack_host_bytes(sd, cfg.batch_share, cfg.micro_batch) // 4,), float("nan"), dtype=torch.float32).pin_memory()
+        assert host.numel() == n_bound
+        copy_in = torch.cuda.Stream()
+        copy_out = torch.cuda.Stream() if cfg.micro_batch == 1 else None      # two copy streams, or one for both directions
+        C.cephalo_stack_step_offload(sd, flat, torch.from_numpy(ids).cuda(), torch.from_numpy(tgt).cuda(), cfg.batch_share,
+                                     cfg.micro_batch, G, scale, loss, ws, host, copy_in, copy_out)
+        torch.cuda.current_stream().synchronize()     # the compute stream ends behind the last copy
+        if keep is not None:
+            keep["boundaries"] = host.numpy().copy()
+    else:
+        C.cephalo_stack_step(sd, flat, torch.from_numpy(ids).cuda(), torch.from_numpy(tgt).cuda(), cfg.batch_share, cfg.micro_batch,
+                             G, scale, loss, ws)
+        torch.cuda.synchronize()
+        if keep is not None:
+            keep["boundaries"] = ws[:4 * n_bound].view(torch.float32).cpu().numpy().copy()
     return float(loss.item()), G.cpu().numpy(), sd
 
 
@@ -109,3 +123,47 @@ def test_activation_checkpointing_gives_identical_results_in_less_memory(case):
     full = C.cephalo_stack_workspace_bytes(C.stack_desc_from_config(cfg, False), cfg.batch_share, cfg.micro_batch)
     ckpt = C.cephalo_stack_workspace_bytes(C.stack_desc_from_config(cfg, True), cfg.batch_share, cfg.micro_batch)
     assert ckpt < full
+
+
+@pytest.mark.parametrize("case", ["bf16_mini", "bf16_mini_m1", "f32_tiny", "bf16_deep6"])
+def test_boundary_activations_offloaded_to_host_give_identical_results(case):
+    """Asynchronous offload of the layer-boundary activations to pinned host memory on a second stream (Sec. 3.2 and the
+    supplementary figure on activation offloading): the same kernels on the same values, so loss and gradients are
+    bit-identical to the resident run, the host area ends up holding exactly the boundary activations of the resident
+    run, and the device work area no longer grows with the number of layers' boundaries."""
+    cfg = CASES[case]
+    params = draw_stack_params(cfg, perturbed=True)
+    ids, tgt = draw_token_ids(cfg)
+    ka, kb = {}, {}
+    a = run_gpu(cfg, params, ids, tgt, 0.75, checkpoint=True, keep=ka)
+    for repeat in range(2):                       # twice: the second call reuses a host area and slots that hold old values
+        b = run_gpu(cfg, params, ids, tgt, 0.75, checkpoint=True, offload=True, keep=kb)
+        assert a[0] == b[0] and np.array_equal(a[1], b[1])
+        assert np.array_equal(ka["boundaries"], kb["boundaries"])
+    sd_res = C.stack_desc_from_config(cfg, True, False)
+    sd_off = C.stack_desc_from_config(cfg, True, True)
+    res = C.cephalo_stack_workspace_bytes(sd_res, cfg.batch_share, cfg.micro_batch)
+    off = C.cephalo_stack_workspace_bytes(sd_off, cfg.batch_share, cfg.micro_batch)
+    saved = (cfg.layers + 1) * cfg.batch_share * cfg.seq * cfg.hidden * 4 - 4 * cfg.micro_batch * cfg.seq * cfg.hidden * 4
+    assert res - off >= saved - 4096 * 8          # the boundaries left the work area, but for four micro-batch slots
+    assert C.cephalo_stack_host_bytes(sd_res, cfg.batch_share, cfg.micro_batch) == 0
+
+
+def test_offload_argument_errors():
+    cfg = CASES["f32_tiny"]
+    with pytest.raises(C.CephaloError):           # offload without checkpointing
+        C.cephalo_stack_workspace_bytes(C.stack_desc_from_config(cfg, False, True), cfg.batch_share, cfg.micro_batch)
+    sd = C.stack_desc_from_config(cfg, True, True)
+    P = C.cephalo_stack_param_count(sd)
+    flat = torch.zeros(P, device="cuda"); G = torch.zeros(P, device="cuda"); loss = torch.zeros(1, device="cuda")
+    ids = torch.zeros(cfg.batch_share, cfg.seq, dtype=torch.int32, device="cuda")
+    ws = torch.empty(C.cephalo_stack_workspace_bytes(sd, cfg.batch_share, cfg.micro_batch), dtype=torch.uint8, device="cuda")
+    host = torch.empty(C.cephalo_stack_host_bytes(sd, cfg.batch_share, cfg.micro_batch) // 4, dtype=torch.float32).pin_memory()
+    with pytest.raises(C.CephaloError):           # the plain entry point refuses an offload desc
+        C.cephalo_stack_step(sd, flat, ids, ids, cfg.batch_share, cfg.micro_batch, G, 1.0, loss, ws)
+    with pytest.raises(C.CephaloError):           # the copy stream must differ from the compute stream
+        C.cephalo_stack_step_offload(sd, flat, ids, ids, cfg.batch_share, cfg.micro_batch, G, 1.0, loss, ws, host,
+                                     torch.cuda.current_stream())
+    with pytest.raises(C.CephaloError):           # host area too small
+        C.cephalo_stack_step_offload(sd, flat, ids, ids, cfg.batch_share, cfg.micro_batch, G, 1.0, loss, ws, host[:-8].contiguous().pin_memory(),
+                                     torch.cuda.Stream())
