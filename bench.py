@@ -34,7 +34,7 @@ def layer_flops_per_microbatch(cfg):
     (2 per multiply-add, x3 for fwd + dgrad + wgrad) and attention 12 m S^2 H non-causal,
     half of it under a causal mask.  Recompute and masked-out work are not counted."""
     T, H, F, S, m = cfg.tokens_per_micro, cfg.hidden, cfg.mlp, cfg.seq, cfg.micro_batch
-    gemm = 6.0 * T * (4 * H * H + 2 * H * F)
+    gemm = 6.0 * T * (4 * H * H + (3 if cfg.kind == "llama" else 2) * H * F)      # gated feed-forward: three F x H matrices
     attn = 12.0 * m * S * S * H * (0.5 if cfg.causal else 1.0)
     return gemm, attn
 
@@ -52,7 +52,8 @@ def main():
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=8)
     ap.add_argument("--warmup", type=int, default=2)
-    ap.add_argument("--workload", default="c5", choices=["c1", "c2", "c3", "c4", "c5"])
+    ap.add_argument("--workload", default="c5", choices=["c1", "c2", "c3", "c4", "c5", "l7b", "vitl"],
+                    help="c5 (default) is the metric's workload; l7b: a Llama-style 7B-class layer; vitl: a ViT-Large-shaped layer")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-legs", action="store_true", help="skip the per-kernel legs (whole step only)")
     ap.add_argument("--checkpoint", action="store_true",
@@ -174,7 +175,7 @@ def main():
                 "unit": "TFLOP/s", "frac": None, "traffic": None}
     T, H, F, V = cfg.tokens_per_micro, cfg.hidden, cfg.mlp, cfg.vocab
     n_tok = cfg.tokens_per_step
-    if bf16 and not args.no_legs:
+    if bf16 and not args.no_legs and cfg.kind == "gpt":      # (the legs carry the GPT-style layer's epilogues)
         if stack:
             del ws                      # the legs allocate their own operands
             torch.cuda.empty_cache()
@@ -288,7 +289,13 @@ def cpu_baseline(cfg, params, flat32_h, m_h, v_h, off, ln, lr, acts, tokens):
         sample_cfg = dataclasses.replace(cfg, n_micro=1)
         n_ad = min(ln, max(1, ln // l))
         t0 = time.perf_counter()
-        _, _, G_ref = oracle_share_step(sample_cfg, params, x_h[:m], dy_h[:m])
+        if cfg.kind == "llama":
+            from oracle import llama as ollama
+            p64 = {k: round_to_bf16(v) if cfg.dtype == "bf16" else v.astype(np.float64) for k, v in params.items()}
+            _, _, g = ollama.share_step(p64, x_h[:m].astype(np.float64), dy_h[:m].astype(np.float64), cfg.heads, m, cfg.causal)
+            G_ref = np.concatenate([g[k].reshape(-1) for k in ollama.NAMES])
+        else:
+            _, _, G_ref = oracle_share_step(sample_cfg, params, x_h[:m], dy_h[:m])
         sl = slice(off, off + n_ad)
         oadam.shard_adam(flat32_h[sl].astype(np.float64), G_ref[sl], m_h[:n_ad].astype(np.float64),
                          v_h[:n_ad].astype(np.float64), 0, n_ad, lr, 0.9, 0.999, 1e-8, 7)

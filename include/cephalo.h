@@ -52,6 +52,17 @@ extern "C" {
                             parameter gradients.  The residual stream -- a layer's x and y and
                             their gradients dy and dx -- is fp32 in both modes.               */
 
+/* Layer kinds.  GPT-style: the layer described below.  Llama-style (five of the nine models of the paper's model table
+ * are of this family): pre-RMSNorm residual blocks, no biases, rotary position embedding on queries and keys (pairs
+ * (2i, 2i+1) of a head, angle position * 10000^(-2i/d), position = token index within the sample), gated feed-forward
+ *     u = RMS1(x)  qkv = u Wqkv^T  q,k <- rotary  O = attention  x1 = x + O Wo^T
+ *     u2 = RMS2(x1)  [g | up] = u2 Wgu^T  h = silu(g) * up  y = x1 + h Wdown^T,      RMS(x) = gamma x / sqrt(mean(x^2) + eps).
+ * Its flat layout is  rms1.gamma[H] Wqkv[3H,H] Wo[H,H] rms2.gamma[H] Wgu[2F,H] Wdown[H,F]  (P = 4H^2 + 3HF + 2H): the
+ * 12 offsets of cephalo_layer_param_offsets keep their order, the beta and bias slots are empty, slot 8 (W_fc1) is
+ * Wgu with gate rows first, slot 10 (W_fc2) is Wdown.  The saved pre-activation is [g | up], 2F wide. */
+#define CEPHALO_LAYER_GPT    0
+#define CEPHALO_LAYER_LLAMA  1
+
 /* A transformer layer: pre-LayerNorm residual blocks, exact (erf) GELU, biases on every
  * projection, scores scaled by 1/sqrt(d), optional causal mask, no dropout (Sec. 2.1 names
  * only "self-attention and feed-forward"; this form is the library's reading). */
@@ -62,13 +73,15 @@ typedef struct cephalo_layer_desc {
   int32_t seq;      /* S, tokens per sample */
   int32_t causal;   /* 0 or 1 */
   int32_t dtype;    /* CEPHALO_F32 or CEPHALO_BF16 */
-  float   ln_eps;   /* added to the biased variance inside the square root */
+  float   ln_eps;   /* added to the biased variance (GPT-style) or to the mean square (Llama-style) inside the square root */
+  int32_t kind;     /* CEPHALO_LAYER_GPT (0) or CEPHALO_LAYER_LLAMA */
 } cephalo_layer_desc;
 
 /* Text of the calling thread's most recent error ("" if none). Host pointer, library-owned. */
 const char* cephalo_last_error(void);
 
-/* Number of elements P of one layer's flat buffer, 4H^2 + 2HF + 9H + F; negative on a bad desc. */
+/* Number of elements P of one layer's flat buffer, 4H^2 + 2HF + 9H + F (GPT-style) or 4H^2 + 3HF + 2H (Llama-style);
+ * negative on a bad desc. */
 int64_t cephalo_layer_param_count(const cephalo_layer_desc* desc);
 
 /* Element offset of each of the 12 tensors inside the flat buffer, in layout order, written

@@ -24,15 +24,19 @@ class CephaloError(RuntimeError):
 class LayerDesc(ctypes.Structure):
     _fields_ = [("hidden", ctypes.c_int32), ("heads", ctypes.c_int32), ("mlp", ctypes.c_int32),
                 ("seq", ctypes.c_int32), ("causal", ctypes.c_int32), ("dtype", ctypes.c_int32),
-                ("ln_eps", ctypes.c_float)]
+                ("ln_eps", ctypes.c_float), ("kind", ctypes.c_int32)]
 
 
-def layer_desc(hidden, heads, mlp, seq, causal, dtype, ln_eps=1e-5):
-    return LayerDesc(int(hidden), int(heads), int(mlp), int(seq), int(bool(causal)), int(dtype), float(ln_eps))
+LAYER_GPT, LAYER_LLAMA = 0, 1
+
+
+def layer_desc(hidden, heads, mlp, seq, causal, dtype, ln_eps=1e-5, kind=LAYER_GPT):
+    return LayerDesc(int(hidden), int(heads), int(mlp), int(seq), int(bool(causal)), int(dtype), float(ln_eps), int(kind))
 
 
 def desc_from_config(cfg):
-    return layer_desc(cfg.hidden, cfg.heads, cfg.mlp, cfg.seq, cfg.causal, F32 if cfg.dtype == "f32" else BF16)
+    kind = LAYER_LLAMA if getattr(cfg, "kind", "gpt") == "llama" else LAYER_GPT
+    return layer_desc(cfg.hidden, cfg.heads, cfg.mlp, cfg.seq, cfg.causal, F32 if cfg.dtype == "f32" else BF16, kind=kind)
 
 
 class StackDesc(ctypes.Structure):
@@ -236,13 +240,20 @@ def cephalo_op_attention_bwd(desc, qkv, O, dO, lse, dvec, dqkv, micro_batch, str
 LAYER_TENSOR_NAMES = ("ln1_g", "ln1_b", "w_qkv", "b_qkv", "w_o", "b_o", "ln2_g", "ln2_b", "w_fc1", "b_fc1", "w_fc2", "b_fc2")
 
 
+# The Llama-style layer uses six of the twelve slots (the beta and bias slots are empty).
+LLAMA_TENSOR_NAMES = ("rms1_g", None, "w_qkv", None, "w_o", None, "rms2_g", None, "w_gu", None, "w_down", None)
+
+
 def flatten_layer_params(desc, tensors):
     """Host-side marshalling: dict name -> float32 array to the fp32 flat vector, at the offsets the library reports."""
     import numpy as np
     P = cephalo_layer_param_count(desc)
     offs = cephalo_layer_param_offsets(desc)
     flat = np.empty(P, dtype=np.float32)
-    for name, o in zip(LAYER_TENSOR_NAMES, offs):
+    names = LLAMA_TENSOR_NAMES if desc.kind == LAYER_LLAMA else LAYER_TENSOR_NAMES
+    for name, o in zip(names, offs):
+        if name is None:
+            continue
         t = tensors[name]
         flat[o:o + t.size] = t.reshape(-1)
     return flat

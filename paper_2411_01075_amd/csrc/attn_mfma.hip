@@ -158,6 +158,30 @@ __device__ void store_transposed(const f32x16 (&acc)[D / 32], bf16* __restrict__
     }
 }
 
+// The same store for a gradient with respect to rotated queries or keys: each pair (2i, 2i+1) is first turned back by
+// the angle of its position, rot[token][i] = (cos, sin), so that what is stored is the gradient before the rotation.
+template <int D>
+__device__ void store_transposed_unrotated(const f32x16 (&acc)[D / 32], bf16* __restrict__ out, int64_t ld, int token, int ntokens, float mul,
+                                           const float* __restrict__ rot) {
+  if (token >= ntokens) return;
+  const int h = (threadIdx.x & 63) >> 5;
+  const f32x4* cs = reinterpret_cast<const f32x4*>(rot + (int64_t)token * D);      // D/2 pairs of (cos, sin) per position
+#pragma unroll
+  for (int dt = 0; dt < D / 32; ++dt)
+#pragma unroll
+    for (int j = 0; j < 4; ++j) {
+      const int d0 = dt * 32 + 8 * j + 4 * h;
+      const f32x4 r = cs[d0 / 4];                                                   // pairs d0/2 and d0/2 + 1
+      const float e0 = acc[dt][4 * j] * mul, o0 = acc[dt][4 * j + 1] * mul, e1 = acc[dt][4 * j + 2] * mul, o1 = acc[dt][4 * j + 3] * mul;
+      bf16x4 v;
+      v[0] = (bf16)(e0 * r[0] + o0 * r[1]);
+      v[1] = (bf16)(o0 * r[0] - e0 * r[1]);
+      v[2] = (bf16)(e1 * r[2] + o1 * r[3]);
+      v[3] = (bf16)(o1 * r[2] - e1 * r[3]);
+      *reinterpret_cast<bf16x4*>(out + (int64_t)token * ld + d0) = v;
+    }
+}
+
 // ------------------------------------------------------------------------------------ forward
 template <int D, bool CAUSAL>
 __global__ void __launch_bounds__(kThreads, 2)
@@ -491,10 +515,11 @@ attn_dvec_kernel(const bf16* __restrict__ O, const bf16* __restrict__ dO, float*
 // of every stage; each half accumulates its own dQ and the second hands it over through LDS at the end of the pass.
 // The products are taken transposed (S^T = K Q^T, dP^T = V dO^T), so that a lane's 16 values belong to one query and
 // its statistics are two scalars, and dS^T is at once the operand of dQ^T += K^T dS^T.
-template <int D, bool CAUSAL>
+template <int D, bool CAUSAL, bool ROT>
 __global__ void __launch_bounds__(kThreads8)
 attn_dq_kernel(const bf16* __restrict__ qkv, const bf16* __restrict__ dO, const float* __restrict__ lse,
-               const float* __restrict__ dvec, bf16* __restrict__ dqkv, int S, int H, int A, float scale) {
+               const float* __restrict__ dvec, bf16* __restrict__ dqkv, int S, int H, int A, float scale,
+                const float* __restrict__ rot) {
   typedef Tile<D, 128, kThreads8> TL;
   extern __shared__ __attribute__((aligned(16))) char smem_raw[];
   lds_bf16* smem = (lds_bf16*)smem_raw;
@@ -620,7 +645,8 @@ attn_dq_kernel(const bf16* __restrict__ qkv, const bf16* __restrict__ dO, const 
     for (int dt = 0; dt < D / 32; ++dt)
 #pragma unroll
       for (int e = 0; e < 16; ++e) dq[dt][e] += mrg[(dt * 16 + e) * 64];
-    store_transposed<D>(dq, dqkv + (int64_t)n * S * ld + a * D, ld, q, S, scale);
+    if (ROT) store_transposed_unrotated<D>(dq, dqkv + (int64_t)n * S * ld + a * D, ld, q, S, scale, rot);
+    else store_transposed<D>(dq, dqkv + (int64_t)n * S * ld + a * D, ld, q, S, scale);
   }
   __syncthreads();     // the merge area is staged over again by the next pass
   }   // pass
@@ -635,10 +661,11 @@ attn_dq_kernel(const bf16* __restrict__ qkv, const bf16* __restrict__ dO, const 
 // The block's keys and values stay in LDS for the whole pass: held in registers (64 of them at D = 128) they push the
 // kernel past 256 registers, where the accumulators move to the second register file and every score has to be copied
 // back for the vector unit.  Query and dO tiles are double-buffered; at D = 128 they come straight from global memory.
-template <int D, bool CAUSAL>
+template <int D, bool CAUSAL, bool ROT>
 __global__ void __launch_bounds__(kThreads8)
 attn_dkv_kernel(const bf16* __restrict__ qkv, const bf16* __restrict__ dO, const float* __restrict__ lse,
-                const float* __restrict__ dvec, bf16* __restrict__ dqkv, int S, int H, int A, float scale) {
+                const float* __restrict__ dvec, bf16* __restrict__ dqkv, int S, int H, int A, float scale,
+                const float* __restrict__ rot) {
   typedef Tile<D, TILE, kThreads8> TL;
   typedef Tile<D, 128, kThreads8> TKV;
   extern __shared__ __attribute__((aligned(16))) char smem_raw[];
@@ -797,16 +824,19 @@ attn_dkv_kernel(const bf16* __restrict__ qkv, const bf16* __restrict__ dO, const
   }
   __syncthreads();
   if (qh == 0) {
+    bf16* out = dqkv + (int64_t)n * S * ld + a * D;
 #pragma unroll
     for (int dt = 0; dt < D / 32; ++dt)
 #pragma unroll
-      for (int e = 0; e < 16; ++e) {
-        dk[dt][e] += mrg[(dt * 16 + e) * 64];
-        dvv[dt][e] += mrg[(NV / 2 + dt * 16 + e) * 64];
-      }
-    bf16* out = dqkv + (int64_t)n * S * ld + a * D;
-    store_transposed<D>(dk, out + H, ld, t, S, scale);
+      for (int e = 0; e < 16; ++e) dvv[dt][e] += mrg[(NV / 2 + dt * 16 + e) * 64];
     store_transposed<D>(dvv, out + 2 * H, ld, t, S, 1.0f);
+    __builtin_amdgcn_sched_barrier(0);      // dv leaves its registers before dk's merge (and its rotary factors) need theirs
+#pragma unroll
+    for (int dt = 0; dt < D / 32; ++dt)
+#pragma unroll
+      for (int e = 0; e < 16; ++e) dk[dt][e] += mrg[(dt * 16 + e) * 64];
+    if (ROT) store_transposed_unrotated<D>(dk, out + H, ld, t, S, scale, rot);
+    else store_transposed<D>(dk, out + H, ld, t, S, scale);
   }
   __syncthreads();     // the merge area is staged over again by the next pass
   }   // pass
@@ -846,9 +876,9 @@ int fwd_cfg(const bf16* qkv, bf16* O, float* lse, int m, int S, int H, int A, hi
   return CEPHALO_OK;
 }
 
-template <int D, bool CAUSAL>
+template <int D, bool CAUSAL, bool ROT>
 int bwd_cfg(const bf16* qkv, const bf16* O, const bf16* dO, const float* lse, float* dvec, bf16* dqkv,
-            int m, int S, int H, int A, hipStream_t s) {
+            int m, int S, int H, int A, const float* rot, hipStream_t s) {
   const float scale = 1.0f / sqrtf((float)D);
   const int rows = m * S;
   attn_dvec_kernel<D><<<(rows + 3) / 4, kThreads, 0, s>>>(O, dO, dvec, rows, S, H, A);
@@ -856,23 +886,32 @@ int bwd_cfg(const bf16* qkv, const bf16* O, const bf16* dO, const float* lse, fl
   dim3 grid(CAUSAL ? (nt + 1) / 2 : nt, A, m);     // causal: a block takes a tile and its mirror image
   {
     const size_t lds = 4 * (size_t)Tile<D, 128, kThreads8>::ELEMS * sizeof(bf16);   // two stages of 128 keys and values
-    auto kern = attn_dq_kernel<D, CAUSAL>;
+    auto kern = attn_dq_kernel<D, CAUSAL, ROT>;
     int rc = reserve_lds(kern, lds);
     if (rc != CEPHALO_OK) return rc;
-    kern<<<grid, kThreads8, lds, s>>>(qkv, dO, lse, dvec, dqkv, S, H, A, scale);
+    kern<<<grid, kThreads8, lds, s>>>(qkv, dO, lse, dvec, dqkv, S, H, A, scale, rot);
   }
   {
     // staging (2 stages of Q and dO, the keys, the values, the row statistics) or, at the end, the merge of the halves
     const size_t staging = (4 * (size_t)Tile<D>::ELEMS + 2 * (size_t)Tile<D, 128>::ELEMS) * sizeof(bf16) + 2 * 128 * sizeof(float);
     const size_t merge = (size_t)4 * (D / 32 * 16 * 2) * 64 * sizeof(float);
     const size_t lds = staging > merge ? staging : merge;
-    auto kern = attn_dkv_kernel<D, CAUSAL>;
+    auto kern = attn_dkv_kernel<D, CAUSAL, ROT>;
     int rc = reserve_lds(kern, lds);
     if (rc != CEPHALO_OK) return rc;
-    kern<<<grid, kThreads8, lds, s>>>(qkv, dO, lse, dvec, dqkv, S, H, A, scale);
+    kern<<<grid, kThreads8, lds, s>>>(qkv, dO, lse, dvec, dqkv, S, H, A, scale, rot);
   }
   CEPHALO_CHECK_LAUNCH("attn_bwd_mfma");
   return CEPHALO_OK;
+}
+
+template <int D>
+int bwd_pick(const bf16* qkv, const bf16* O, const bf16* dO, const float* lse, float* dvec, bf16* dqkv,
+             int m, int S, int H, int A, int causal, const float* rot, hipStream_t s) {
+  if (rot) return causal ? bwd_cfg<D, true, true>(qkv, O, dO, lse, dvec, dqkv, m, S, H, A, rot, s)
+                         : bwd_cfg<D, false, true>(qkv, O, dO, lse, dvec, dqkv, m, S, H, A, rot, s);
+  return causal ? bwd_cfg<D, true, false>(qkv, O, dO, lse, dvec, dqkv, m, S, H, A, rot, s)
+                : bwd_cfg<D, false, false>(qkv, O, dO, lse, dvec, dqkv, m, S, H, A, rot, s);
 }
 
 }  // namespace
@@ -888,18 +927,14 @@ int launch_attn_fwd_mfma(const bf16* qkv, bf16* O, float* lse, int m, int S, int
 }
 
 int launch_attn_bwd_mfma(const bf16* qkv, const bf16* O, const bf16* dO, const float* lse, float* dvec, bf16* dqkv,
-                         int m, int S, int H, int A, int causal, hipStream_t s) {
+                         int m, int S, int H, int A, int causal, hipStream_t s, const float* rot) {
   const int D = H / A;
-  if (H % 8 != 0 || !aligned16(qkv) || !aligned16(O) || !aligned16(dO) || !aligned16(dqkv))
+  if (H % 8 != 0 || !aligned16(qkv) || !aligned16(O) || !aligned16(dO) || !aligned16(dqkv) || !aligned16(rot))
     return fail(CEPHALO_EINVAL, "attention: rows must be 16-byte aligned");
   if ((int64_t)S * 3 * H * 2 >= (int64_t)1 << 31)
     return fail(CEPHALO_EUNSUPPORTED, "attention: one sample of qkv (%lld bytes) exceeds the 2 GiB a buffer offset reaches", (long long)S * 3 * H * 2);
-  if (D == 64)
-    return causal ? bwd_cfg<64, true>(qkv, O, dO, lse, dvec, dqkv, m, S, H, A, s)
-                  : bwd_cfg<64, false>(qkv, O, dO, lse, dvec, dqkv, m, S, H, A, s);
-  if (D == 128)
-    return causal ? bwd_cfg<128, true>(qkv, O, dO, lse, dvec, dqkv, m, S, H, A, s)
-                  : bwd_cfg<128, false>(qkv, O, dO, lse, dvec, dqkv, m, S, H, A, s);
+  if (D == 64) return bwd_pick<64>(qkv, O, dO, lse, dvec, dqkv, m, S, H, A, causal, rot, s);
+  if (D == 128) return bwd_pick<128>(qkv, O, dO, lse, dvec, dqkv, m, S, H, A, causal, rot, s);
   return fail(CEPHALO_EUNSUPPORTED, "attention (matrix-core kernel): head dim %d is not 64 or 128", D);
 }
 

@@ -32,7 +32,9 @@ template <int N> __device__ __forceinline__ void store_f32(float* p, const float
   }
 }
 
-template <typename T, int MAXV>
+// RMS: root-mean-square norm instead (no mean subtraction, no beta: u = gamma * x / sqrt(mean(x^2) + eps)); the mean
+// written is 0.
+template <typename T, int MAXV, bool RMS>
 __global__ void __launch_bounds__(kThreads)
 ln_fwd_kernel(const float* __restrict__ x, const T* __restrict__ gamma, const T* __restrict__ beta,
               T* __restrict__ u, float* __restrict__ mean, float* __restrict__ rstd,
@@ -54,7 +56,7 @@ ln_fwd_kernel(const float* __restrict__ x, const T* __restrict__ gamma, const T*
         for (int i = 0; i < VN; ++i) sum += vals[j][i];
       }
     }
-    const float mu = wave_sum(sum) * inv_h;
+    const float mu = RMS ? 0.f : wave_sum(sum) * inv_h;
     float sq = 0.f;
 #pragma unroll
     for (int j = 0; j < MAXV; ++j) {
@@ -71,7 +73,12 @@ ln_fwd_kernel(const float* __restrict__ x, const T* __restrict__ gamma, const T*
       if (v < nv) {
         float g[VN], b[VN], o[VN];
         load_vec<T>(gamma + v * VN, g);
-        load_vec<T>(beta + v * VN, b);
+        if (RMS) {
+#pragma unroll
+          for (int i = 0; i < VN; ++i) b[i] = 0.f;
+        } else {
+          load_vec<T>(beta + v * VN, b);
+        }
 #pragma unroll
         for (int i = 0; i < VN; ++i) o[i] = g[i] * ((vals[j][i] - mu) * rs) + b[i];
         store_vec<T>(ur + v * VN, o);
@@ -85,7 +92,9 @@ constexpr int kLnBwdRowsPerBlock = 16;  // 4 rows per wavefront
 
 // out = resid + rstd * (g - mean(g) - xhat * mean(g*xhat)),  g = du * gamma
 // part_g[blk][h] = sum over the block's rows of du*xhat, part_b[blk][h] = sum of du
-template <typename T, int MAXV>
+// RMS: backward of the root-mean-square norm, out = resid + rstd * (g - xhat * mean(g*xhat)) with xhat = x * rstd
+// (part_b is still written, and not used).
+template <typename T, int MAXV, bool RMS>
 __global__ void __launch_bounds__(kThreads)
 ln_bwd_kernel(const float* __restrict__ du, const float* __restrict__ x, const float* __restrict__ mean,
               const float* __restrict__ rstd, const T* __restrict__ gamma, const float* __restrict__ resid,
@@ -106,7 +115,7 @@ ln_bwd_kernel(const float* __restrict__ du, const float* __restrict__ x, const f
   for (int r = wave; r < kLnBwdRowsPerBlock; r += kWaves) {
     const int row = row0 + r;
     if (row >= rows) break;
-    const float mu = mean[row], rs = rstd[row];
+    const float mu = RMS ? 0.f : mean[row], rs = rstd[row];
     float g[MAXV][VN], xh[MAXV][VN];
     float s1 = 0.f, s2 = 0.f;
 #pragma unroll
@@ -128,7 +137,7 @@ ln_bwd_kernel(const float* __restrict__ du, const float* __restrict__ x, const f
         }
       }
     }
-    const float c1 = wave_sum(s1) * inv_h, c2 = wave_sum(s2) * inv_h;
+    const float c1 = RMS ? 0.f : wave_sum(s1) * inv_h, c2 = wave_sum(s2) * inv_h;
 #pragma unroll
     for (int j = 0; j < MAXV; ++j) {
       const int v = lane + 64 * j;
@@ -271,11 +280,12 @@ template <typename T> int maxv_for(int H) {
 
 template <typename T>
 int launch_ln_fwd(const float* x, const T* gamma, const T* beta, T* u, float* mean, float* rstd,
-                  int rows, int H, float eps, hipStream_t s) {
+                  int rows, int H, float eps, hipStream_t s, bool rms) {
   const int grid = (rows + kWaves - 1) / kWaves;
 #define LN_FWD_CASE(MV)                                                                             \
   case MV:                                                                                          \
-    ln_fwd_kernel<T, MV><<<grid, kThreads, 0, s>>>(x, gamma, beta, u, mean, rstd, rows, H, eps);    \
+    if (rms) ln_fwd_kernel<T, MV, true><<<grid, kThreads, 0, s>>>(x, gamma, beta, u, mean, rstd, rows, H, eps);    \
+    else ln_fwd_kernel<T, MV, false><<<grid, kThreads, 0, s>>>(x, gamma, beta, u, mean, rstd, rows, H, eps);    \
     break;
   switch (maxv_for<T>(H)) {
     LN_FWD_CASE(1) LN_FWD_CASE(2) LN_FWD_CASE(4) LN_FWD_CASE(8) LN_FWD_CASE(16)
@@ -290,11 +300,12 @@ int ln_bwd_blocks(int rows) { return (rows + kLnBwdRowsPerBlock - 1) / kLnBwdRow
 
 template <typename T>
 int launch_ln_bwd(const float* du, const float* x, const float* mean, const float* rstd, const T* gamma,
-                  const float* resid, float* out, T* out_lowp, float* part_g, float* part_b, int rows, int H, hipStream_t s) {
+                  const float* resid, float* out, T* out_lowp, float* part_g, float* part_b, int rows, int H, hipStream_t s, bool rms) {
   const int nblocks = ln_bwd_blocks(rows);
 #define LN_BWD_CASE(MV)                                                                                               \
   case MV:                                                                                                            \
-    ln_bwd_kernel<T, MV><<<nblocks, kThreads, 0, s>>>(du, x, mean, rstd, gamma, resid, out, out_lowp, part_g, part_b, rows, H); \
+    if (rms) ln_bwd_kernel<T, MV, true><<<nblocks, kThreads, 0, s>>>(du, x, mean, rstd, gamma, resid, out, out_lowp, part_g, part_b, rows, H); \
+    else ln_bwd_kernel<T, MV, false><<<nblocks, kThreads, 0, s>>>(du, x, mean, rstd, gamma, resid, out, out_lowp, part_g, part_b, rows, H); \
     break;
   switch (maxv_for<T>(H)) {
     LN_BWD_CASE(1) LN_BWD_CASE(2) LN_BWD_CASE(4) LN_BWD_CASE(8) LN_BWD_CASE(16)
@@ -350,10 +361,97 @@ int launch_transpose_bf16(const bf16* in, bf16* out, int rows, int cols, hipStre
   return CEPHALO_OK;
 }
 
+// ---- rotary position embedding (Llama-style layer)
+// Within each head the pair (2i, 2i+1) of the token at position t is rotated by the angle t * base^(-2i/d).
+// The angles' cosines and sines are tabulated once per call, tab[t][i] = (cos, sin) in fp32 (fp32 power, accurate
+// sincos), and every kernel that rotates (the GEMM epilogue that produces q and k, the attention backward's stores of
+// dq and dk, the stand-alone kernel below) reads the same table.
+__global__ void __launch_bounds__(kThreads)
+rotary_table_kernel(float* __restrict__ tab, int S, int d, float log2_base) {
+  const int idx = blockIdx.x * kThreads + threadIdx.x;
+  if (idx >= S * (d / 2)) return;
+  const int t = idx / (d / 2), i = idx % (d / 2);
+  const float inv = exp2f(-2.0f * (float)i / (float)d * log2_base);
+  float sn, cs;
+  sincosf((float)t * inv, &sn, &cs);
+  tab[2 * idx] = cs;
+  tab[2 * idx + 1] = sn;
+}
+
+int launch_rotary_table(float* tab, int S, int d, float base, hipStream_t s) {
+  if (d % 8 != 0) return fail(CEPHALO_EUNSUPPORTED, "rotary: head dim %d must be a multiple of 8", d);
+  const int n = S * (d / 2);
+  rotary_table_kernel<<<(n + kThreads - 1) / kThreads, kThreads, 0, s>>>(tab, S, d, log2f(base));
+  CEPHALO_CHECK_LAUNCH("rotary_table");
+  return CEPHALO_OK;
+}
+
+// In place on the Q and K thirds of qkv [rows, 3H], position t = row % S; sign = -1 turns back (the gradient's way).
+// One thread per 4 consecutive values (2 pairs).
+template <typename T>
+__global__ void __launch_bounds__(kThreads)
+rotary_kernel(T* __restrict__ qkv, const float* __restrict__ tab, int rows, int S, int H, int d, float sign) {
+  const int per_row = 2 * H / 4;                           // groups of the Q and K parts of a row
+  const int64_t idx = (int64_t)blockIdx.x * kThreads + threadIdx.x;
+  if (idx >= (int64_t)rows * per_row) return;
+  const int row = (int)(idx / per_row), col = (int)(idx % per_row) * 4;     // column within [0, 2H): Q then K
+  const int t = row % S;
+  T* p = qkv + (int64_t)row * 3 * H + col;
+  const float* r = tab + ((int64_t)t * (d / 2) + (col % d) / 2) * 2;
+#pragma unroll
+  for (int q = 0; q < 2; ++q) {
+    const float cs = r[2 * q], sn = sign * r[2 * q + 1];
+    const float e = (float)p[2 * q], o = (float)p[2 * q + 1];
+    p[2 * q] = (T)(e * cs - o * sn);
+    p[2 * q + 1] = (T)(e * sn + o * cs);
+  }
+}
+
+template <typename T>
+int launch_rotary(T* qkv, const float* tab, int rows, int S, int H, int heads, int inverse, hipStream_t s) {
+  const int d = H / heads;
+  if (H % 8 != 0 || d % 8 != 0) return fail(CEPHALO_EUNSUPPORTED, "rotary: head dim %d must be a multiple of 8", d);
+  const int64_t n = (int64_t)rows * (2 * H / 4);
+  rotary_kernel<T><<<(int)((n + kThreads - 1) / kThreads), kThreads, 0, s>>>(qkv, tab, rows, S, H, d, inverse ? -1.0f : 1.0f);
+  CEPHALO_CHECK_LAUNCH("rotary");
+  return CEPHALO_OK;
+}
+
+// ---- gated SiLU feed-forward: gu [rows, 2F] = [gate | up];  h = silu(gate) * up (the backward is an epilogue of the GEMM that produces dh)
+__device__ __forceinline__ float sigmoidf_(float z) { return 1.0f / (1.0f + __expf(-z)); }
+
+template <typename T>
+__global__ void __launch_bounds__(kThreads)
+swiglu_fwd_kernel(const T* __restrict__ gu, T* __restrict__ h, int64_t rows, int F) {
+  constexpr int VN = Vec<T>::N;
+  const int per_row = F / VN;
+  const int64_t idx = (int64_t)blockIdx.x * kThreads + threadIdx.x;
+  if (idx >= rows * per_row) return;
+  const int64_t row = idx / per_row;
+  const int c = (int)(idx % per_row) * VN;
+  float g[VN], u[VN], o[VN];
+  load_vec<T>(gu + row * 2 * F + c, g);
+  load_vec<T>(gu + row * 2 * F + F + c, u);
+#pragma unroll
+  for (int i = 0; i < VN; ++i) o[i] = g[i] * sigmoidf_(g[i]) * u[i];
+  store_vec<T>(h + row * F + c, o);
+}
+
+
+template <typename T>
+int launch_swiglu_fwd(const T* gu, T* h, int64_t rows, int F, hipStream_t s) {
+  const int64_t n = rows * (F / Vec<T>::N);
+  swiglu_fwd_kernel<T><<<(int)((n + kThreads - 1) / kThreads), kThreads, 0, s>>>(gu, h, rows, F);
+  CEPHALO_CHECK_LAUNCH("swiglu_fwd");
+  return CEPHALO_OK;
+}
+
 #define INSTANTIATE(T)                                                                                          \
-  template int launch_ln_fwd<T>(const float*, const T*, const T*, T*, float*, float*, int, int, float, hipStream_t); \
+  template int launch_ln_fwd<T>(const float*, const T*, const T*, T*, float*, float*, int, int, float, hipStream_t, bool); \
   template int launch_ln_bwd<T>(const float*, const float*, const float*, const float*, const T*, const float*, float*, \
-                                T*, float*, float*, int, int, hipStream_t);                                       \
+                                T*, float*, float*, int, int, hipStream_t, bool);                                 \
+  template int launch_rotary<T>(T*, const float*, int, int, int, int, int, hipStream_t);                          \
+  template int launch_swiglu_fwd<T>(const T*, T*, int64_t, int, hipStream_t);                                     \
   template int launch_colsum<T>(const T*, float*, size_t, float*, float, int, int, int, hipStream_t);
 INSTANTIATE(float)
 INSTANTIATE(bf16)

@@ -142,7 +142,7 @@ __device__ __forceinline__ void write_staged_rows(const GemmArgs<bf16>& a, const
       float v[8];
 #pragma unroll
       for (int t = 0; t < 4; ++t) { v[t] = v0[t]; v[4 + t] = v1[t]; }
-      if (EPI == EPI_BIAS || EPI == EPI_BIAS_RESID || EPI == EPI_BIAS_GELU) {
+      if (EPI == EPI_BIAS || EPI == EPI_BIAS_GELU || (EPI == EPI_BIAS_RESID && a.bias)) {    // (no bias: residual only)
         float b8[8];
         load_vec<bf16>(a.bias + n, b8);
 #pragma unroll
@@ -170,6 +170,29 @@ __device__ __forceinline__ void write_staged_rows(const GemmArgs<bf16>& a, const
         load_vec<bf16>(a.Z + o, z8);
 #pragma unroll
         for (int t = 0; t < 8; ++t) v[t] *= gelu_grad_fast(z8[t]);
+      }
+      if (EPI == EPI_ROPE) {
+        if (n < a.rot_cols) {       // (a group of 8 columns lies wholly inside or outside the rotated part)
+          const f32x4* cs = reinterpret_cast<const f32x4*>(a.rot + ((int64_t)(m % a.rot_S) * (a.rot_d / 2) + (n % a.rot_d) / 2) * 2);
+          const f32x4 r0 = cs[0], r1 = cs[1];
+          const float c4[4] = {r0[0], r0[2], r1[0], r1[2]}, s4[4] = {r0[1], r0[3], r1[1], r1[3]};
+#pragma unroll
+          for (int t = 0; t < 4; ++t) {
+            const float e = v[2 * t], od = v[2 * t + 1];
+            v[2 * t] = e * c4[t] - od * s4[t];
+            v[2 * t + 1] = e * s4[t] + od * c4[t];
+          }
+        }
+      }
+      if (EPI == EPI_DSWIGLU) {     // two outputs per product: the gate's and the up projection's gradient, N columns apart
+        float g8[8], u8[8], dg[8], du[8];
+        load_vec<bf16>(a.Z + o, g8);
+        load_vec<bf16>(a.Z + o + a.N, u8);
+#pragma unroll
+        for (int t = 0; t < 8; ++t) swiglu_grad(g8[t], u8[t], v[t], dg[t], du[t]);
+        store_vec<bf16>(a.C + o, dg);
+        store_vec<bf16>(a.C + o + a.N, du);
+        continue;
       }
       if (a.Cf) {        // fp32 output (residual stream, or a gradient that an element-wise kernel reads next)
         f32x4 w0, w1;
@@ -523,6 +546,7 @@ int launch_gemm_mfma(const GemmArgs<bf16>& a, hipStream_t s) {
   if (ak && bk) {          // forward: Y = X W^T
     switch (a.epi) {
       case EPI_NONE: return launch_tiles<true, true, EPI_NONE>(a, s);
+      case EPI_ROPE: if (a.rot_cols % 8 == 0 && a.rot_d % 8 == 0 && aligned16(a.rot)) return launch_tiles<true, true, EPI_ROPE>(a, s); break;
       case EPI_BIAS: return launch_tiles<true, true, EPI_BIAS>(a, s);
       case EPI_BIAS_RESID: return launch_tiles<true, true, EPI_BIAS_RESID>(a, s);
       case EPI_BIAS_GELU: return launch_tiles<true, true, EPI_BIAS_GELU>(a, s);
@@ -533,6 +557,7 @@ int launch_gemm_mfma(const GemmArgs<bf16>& a, hipStream_t s) {
     switch (a.epi) {
       case EPI_NONE: return launch_tiles<true, false, EPI_NONE>(a, s);
       case EPI_DGELU: return launch_tiles<true, false, EPI_DGELU>(a, s);
+      case EPI_DSWIGLU: if (a.N % 8 == 0) return launch_tiles<true, false, EPI_DSWIGLU>(a, s); break;
       default: break;
     }
     if (a.epi == EPI_GRAD) return launch_tiles<true, false, EPI_GRAD>(a, s);   // wgrad with dY pre-transposed

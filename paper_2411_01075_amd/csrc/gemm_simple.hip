@@ -71,13 +71,28 @@ __global__ void __launch_bounds__(kThreads) gemm_simple_kernel(GemmArgs<T> a) {
       switch (a.epi) {
         case EPI_NONE: put(v); break;
         case EPI_BIAS: put(v + (float)a.bias[n]); break;
-        case EPI_BIAS_RESID: put(v + (float)a.bias[n] + (a.Rf ? a.Rf[o] : (float)a.R[o])); break;
+        case EPI_BIAS_RESID: put(v + (a.bias ? (float)a.bias[n] : 0.f) + (a.Rf ? a.Rf[o] : (float)a.R[o])); break;
         case EPI_BIAS_GELU: {
           const float z = v + (float)a.bias[n];
           a.Z[o] = (T)z;
           a.C[o] = (T)gelu_f(z);
         } break;
         case EPI_DGELU: a.C[o] = (T)(v * gelu_grad_f((float)a.Z[o])); break;
+        case EPI_ROPE: {
+          // the partner column's product sits in the same thread (columns come in aligned groups of four)
+          float r = v;
+          if (n < a.rot_cols) {
+            const float* cs = a.rot + ((int64_t)(m % a.rot_S) * (a.rot_d / 2) + (n % a.rot_d) / 2) * 2;
+            r = (j & 1) ? acc[i][j ^ 1] * cs[1] + v * cs[0] : v * cs[0] - acc[i][j ^ 1] * cs[1];
+          }
+          put(r);
+        } break;
+        case EPI_DSWIGLU: {
+          float dg, du;
+          swiglu_grad((float)a.Z[o], (float)a.Z[o + a.N], v, dg, du);
+          a.C[o] = (T)dg;
+          a.C[o + a.N] = (T)du;
+        } break;
         case EPI_GRAD: a.G[o] = (a.accumulate ? a.G[o] : 0.f) + a.scale * v; break;
       }
     }

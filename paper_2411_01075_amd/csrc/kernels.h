@@ -86,7 +86,18 @@ enum Epilogue {
   EPI_BIAS_GELU = 3,   // Z = acc + bias[n] ; C = gelu(Z)          (Z and C both stored)
   EPI_DGELU = 4,       // C = acc * gelu'(Z[m,n])
   EPI_GRAD = 5,        // G[m,n] = (accumulate ? G[m,n] : 0) + scale * acc     (G fp32)
+  EPI_ROPE = 7,        // C = acc with each pair of columns (2i, 2i+1) below rot_cols turned by the rotary angle of its
+                       //   row's position m % rot_S and of its place in the head: (e, o) -> (e cos - o sin, e sin + o cos)
+  EPI_DSWIGLU = 8,     // gated SiLU backward, acc = dh[m,n], n < N = F; Z and C are [M, 2N] = [gate | up] (pitch ldc >= 2N):
+                       //   C[m,n] = acc * Z[m,N+n] * silu'(Z[m,n]);  C[m,N+n] = acc * silu(Z[m,n])
 };
+
+// gated SiLU feed-forward h = silu(g) * u: gradients with respect to g and u given d = dL/dh
+__device__ __forceinline__ void swiglu_grad(float g, float u, float d, float& dg, float& du) {
+  const float sg = 1.0f / (1.0f + __expf(-g));
+  dg = d * u * sg * (1.0f + g * (1.0f - sg));
+  du = d * g * sg;
+}
 
 template <typename T>
 struct GemmArgs {
@@ -101,10 +112,12 @@ struct GemmArgs {
   const T* R;      // [M,N] residual
   const float* Rf; // if set, EPI_BIAS_RESID reads its residual from here in fp32 (pitch ldc) instead of R
   float* Cf;       // if set, EPI_NONE / EPI_BIAS / EPI_BIAS_RESID write their result here in fp32 (pitch ldc) instead of C
-  T* Z;            // [M,N] pre-activation: written by EPI_BIAS_GELU, read by EPI_DGELU
+  T* Z;            // [M,N] pre-activation: written by EPI_BIAS_GELU, read by EPI_DGELU ([M,2N], read by EPI_DSWIGLU)
   float* G;        // [M,N] fp32 gradient (EPI_GRAD)
   float scale;
   int accumulate;
+  const float* rot;   // EPI_ROPE: [rot_S, rot_d/2, 2] = (cos, sin); rot_d: head width (divides rot_cols, multiple of 8)
+  int rot_S, rot_d, rot_cols;
   // EPI_GRAD with the contraction split over `splits` > 1 blocks per tile (long token axes, few output tiles): each
   // block writes its partial tile to part[split][M][N] and a second pass adds the partials in split order (fixed
   // order: reproducible) and applies scale / accumulate.  part holds splits*M*N floats.
@@ -120,9 +133,10 @@ int launch_gemm_mfma(const GemmArgs<bf16>& a, hipStream_t s);  // bf16 operands,
 
 // ---------------------------------------------------------------------------------------
 // LayerNorm over the last axis of x[rows, H].  The residual stream x is fp32; the output u is in the activation type.
+// rms: root-mean-square norm instead, u = gamma * x / sqrt(mean(x^2) + eps) (beta is not read; the mean written is 0).
 template <typename T>
 int launch_ln_fwd(const float* x, const T* gamma, const T* beta, T* u, float* mean, float* rstd,
-                  int rows, int H, float eps, hipStream_t s);
+                  int rows, int H, float eps, hipStream_t s, bool rms = false);
 
 // out = resid + LN-backward(du), all fp32 (resid may be null: no residual); out_lowp, if not null, receives the same
 // values in the activation type (the copy a following GEMM reads).  Each block of rows also writes its partial sums
@@ -131,8 +145,18 @@ int launch_ln_fwd(const float* x, const T* gamma, const T* beta, T* u, float* me
 //   g = (accumulate ? g : 0) + scale * sum over chunks.
 template <typename T>
 int launch_ln_bwd(const float* du, const float* x, const float* mean, const float* rstd, const T* gamma,
-                  const float* resid, float* out, T* out_lowp, float* part_g, float* part_b, int rows, int H, hipStream_t s);
+                  const float* resid, float* out, T* out_lowp, float* part_g, float* part_b, int rows, int H, hipStream_t s,
+                  bool rms = false);
 int ln_bwd_blocks(int rows);
+
+// Rotary position embedding in place on the Q and K thirds of qkv [rows, 3H] (row % S = position, pairs (2i, 2i+1) of
+// each head rotated by position * base^(-2i/d)); inverse: by the negative angle (the backward of the rotation).
+// Rotary embedding: tab [S, d/2, 2] = (cos, sin) of position * base^(-2i/d); launch_rotary turns the Q and K thirds of
+// qkv [rows, 3H] in place (inverse: by the negative angle).
+int launch_rotary_table(float* tab, int S, int d, float base, hipStream_t s);
+template <typename T> int launch_rotary(T* qkv, const float* tab, int rows, int S, int H, int heads, int inverse, hipStream_t s);
+// Gated SiLU: gu [rows, 2F] = [gate | up], h [rows, F] = silu(gate) * up; backward dgu from dh and gu.
+template <typename T> int launch_swiglu_fwd(const T* gu, T* h, int64_t rows, int F, hipStream_t s);
 // tmp (reduce_tmp_bytes(nchunks, N) bytes, may be null) lets a long reduction run in two parallel stages.
 int launch_reduce_partials(const float* partials, int nchunks, int N, float* g, float scale, int accumulate,
                            float* tmp, size_t tmp_bytes, hipStream_t s);
@@ -163,7 +187,8 @@ int launch_attn_bwd_simple(const T* qkv, const T* O, const T* dO, const float* l
                            int m, int S, int H, int A, int causal, hipStream_t s);
 
 int launch_attn_fwd_mfma(const bf16* qkv, bf16* O, float* lse, int m, int S, int H, int A, int causal, hipStream_t s);
+// rot: if not null, a rotary table [S, d/2, 2] by which the stored dq and dk are turned back (q and k were rotated)
 int launch_attn_bwd_mfma(const bf16* qkv, const bf16* O, const bf16* dO, const float* lse, float* dvec, bf16* dqkv,
-                         int m, int S, int H, int A, int causal, hipStream_t s);
+                         int m, int S, int H, int A, int causal, hipStream_t s, const float* rot = nullptr);
 
 }  // namespace cephalo

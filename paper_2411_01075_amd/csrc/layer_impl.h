@@ -14,6 +14,11 @@ namespace {   // internal linkage in each translation unit that includes this he
 
 inline size_t align_up(size_t x) { return (x + 255) & ~(size_t)255; }
 
+// Llama-style layers (kind 1): no biases, no beta, and the first feed-forward projection produces gate and up values,
+// 2F columns.
+inline bool is_llama(const cephalo_layer_desc& d) { return d.kind == CEPHALO_LAYER_LLAMA; }
+inline int64_t ff1_width(const cephalo_layer_desc& d) { return is_llama(d) ? 2 * (int64_t)d.mlp : d.mlp; }
+
 // Offsets (elements) of the 12 tensors of the flat layer layout.
 struct ParamOffsets {
   int64_t ln1_g, ln1_b, w_qkv, b_qkv, w_o, b_o, ln2_g, ln2_b, w_fc1, b_fc1, w_fc2, b_fc2, total;
@@ -23,18 +28,19 @@ ParamOffsets param_offsets(const cephalo_layer_desc& d) {
   const int64_t H = d.hidden, F = d.mlp;
   ParamOffsets o;
   int64_t p = 0;
+  const int64_t vec = is_llama(d) ? 0 : 1;               // beta and bias vectors exist in the GPT-style layer only
   o.ln1_g = p; p += H;
-  o.ln1_b = p; p += H;
+  o.ln1_b = p; p += vec * H;
   o.w_qkv = p; p += 3 * H * H;
-  o.b_qkv = p; p += 3 * H;
+  o.b_qkv = p; p += vec * 3 * H;
   o.w_o = p;   p += H * H;
-  o.b_o = p;   p += H;
+  o.b_o = p;   p += vec * H;
   o.ln2_g = p; p += H;
-  o.ln2_b = p; p += H;
-  o.w_fc1 = p; p += F * H;
-  o.b_fc1 = p; p += F;
+  o.ln2_b = p; p += vec * H;
+  o.w_fc1 = p; p += ff1_width(d) * H;
+  o.b_fc1 = p; p += vec * F;
   o.w_fc2 = p; p += H * F;
-  o.b_fc2 = p; p += H;
+  o.b_fc2 = p; p += vec * H;
   o.total = p;
   return o;
 }
@@ -48,6 +54,9 @@ int check_desc(const cephalo_layer_desc* d) {
     return fail(CEPHALO_EINVAL, "layer desc: hidden %d is not a multiple of heads %d", d->hidden, d->heads);
   if (d->dtype != CEPHALO_F32 && d->dtype != CEPHALO_BF16) return fail(CEPHALO_EINVAL, "layer desc: unknown dtype %d", d->dtype);
   if (d->causal != 0 && d->causal != 1) return fail(CEPHALO_EINVAL, "layer desc: causal must be 0 or 1");
+  if (d->kind != CEPHALO_LAYER_GPT && d->kind != CEPHALO_LAYER_LLAMA) return fail(CEPHALO_EINVAL, "layer desc: unknown kind %d", d->kind);
+  if (d->kind == CEPHALO_LAYER_LLAMA && (d->hidden / d->heads) % 8 != 0)
+    return fail(CEPHALO_EUNSUPPORTED, "layer desc: the rotary embedding needs a head dim that is a multiple of 8, got %d", d->hidden / d->heads);
   if (!(d->ln_eps >= 0.f)) return fail(CEPHALO_EINVAL, "layer desc: ln_eps %g < 0", d->ln_eps);
   if (d->hidden % 8 != 0 || d->mlp % 8 != 0)
     return fail(CEPHALO_EUNSUPPORTED, "layer desc: hidden %d and mlp %d must be multiples of 8 (16-byte rows)", d->hidden, d->mlp);
@@ -67,7 +76,7 @@ int check_desc(const cephalo_layer_desc* d) {
 // Saved activations of `n` samples, tensor-major: each tensor is one [n*S, width] matrix, so the
 // slice of a micro-batch is a row range and the whole share is one contiguous operand.
 struct SaveLayout {
-  size_t mean1, rstd1, u, qkv, lse, O, x1, mean2, rstd2, u2, z, h, total;
+  size_t mean1, rstd1, u, qkv, lse, O, x1, mean2, rstd2, u2, z, h, rot, total;
 };
 // Backward work area.  dz, dx1 and dqkv (the dY operands of the weight gradients) and the copy of dy in the
 // activation type are kept for `span` samples; the rest is per micro-batch of m samples.
@@ -90,8 +99,9 @@ SaveLayout save_layout(const cephalo_layer_desc& d, int n) {
   L.x1 = take(T * H * 4);
   L.mean2 = take(T * 4); L.rstd2 = take(T * 4);
   L.u2 = take(T * H * es);
-  L.z = take(T * F * es);
+  L.z = take(T * (size_t)ff1_width(d) * es);      // pre-activation (GPT-style) or gate | up (Llama-style)
   L.h = take(T * F * es);
+  L.rot = is_llama(d) ? take((size_t)d.seq * (H / d.heads) * sizeof(float)) : 0;   // rotary table [S, d/2] of (cos, sin), shared by all samples
   L.total = p;
   return L;
 }
@@ -102,7 +112,8 @@ ScratchLayout scratch_layout(const cephalo_layer_desc& d, int m, int span) {
   ScratchLayout L;
   size_t p = 0;
   auto take = [&](size_t bytes) { size_t at = p; p += align_up(bytes); return at; };
-  L.dz = take(Ts * F * es);
+  const size_t F1 = (size_t)ff1_width(d);
+  L.dz = take(Ts * F1 * es);
   L.dx1 = take(Ts * H * 4);
   L.dx1l = es == 4 ? L.dx1 : take(Ts * H * es);
   L.dyl = es == 4 ? 0 : take(Ts * H * es);
@@ -115,7 +126,7 @@ ScratchLayout scratch_layout(const cephalo_layer_desc& d, int m, int span) {
   L.wg_part = p;                    // partial weight gradients of a split token axis (largest of the four projections)
   if (es != 4) {
     size_t need = 0;
-    const int dims[4][2] = {{(int)(3 * H), (int)H}, {(int)H, (int)H}, {(int)F, (int)H}, {(int)H, (int)F}};
+    const int dims[4][2] = {{(int)(3 * H), (int)H}, {(int)H, (int)H}, {(int)F1, (int)H}, {(int)H, (int)F}};
     for (auto& nk : dims) {
       const int sp = gemm_grad_splits(nk[0], nk[1], (int)Ts);
       if (sp > 1) need = std::max(need, (size_t)sp * nk[0] * nk[1] * sizeof(float));
@@ -124,12 +135,14 @@ ScratchLayout scratch_layout(const cephalo_layer_desc& d, int m, int span) {
   }
   L.ln_rows = (size_t)(span / m) * ln_bwd_blocks((int)Tm);
   L.ln_part = take(4 * L.ln_rows * H * sizeof(float));
-  const int widest = (int)(3 * H > F ? 3 * H : F);
+  const int widest = (int)(3 * H > F1 ? 3 * H : F1);
   L.col_part_bytes = colsum_partial_bytes((int)Ts, widest);
   L.col_part = take(L.col_part_bytes);
   L.total = p;
   return L;
 }
+
+constexpr float kRopeBase = 10000.0f;   // rotary embedding: angle of pair i at position t is t * base^(-2i/d)
 
 // ---- kernel selection ------------------------------------------------------------------
 template <typename T> int gemm(const GemmArgs<T>& a, hipStream_t s);
@@ -143,15 +156,19 @@ template <> int attn_fwd<float>(const float* qkv, float* O, float* lse, int m, i
 template <> int attn_fwd<bf16>(const bf16* qkv, bf16* O, float* lse, int m, int S, int H, int A, int causal, hipStream_t s) {
   return launch_attn_fwd_mfma(qkv, O, lse, m, S, H, A, causal, s);
 }
+// rot: if not null, the rotary table of a layer whose q and k were rotated; dq and dk then come back through the rotation
 template <typename T>
-int attn_bwd(const T* qkv, const T* O, const T* dO, const float* lse, float* dvec, T* dqkv, int m, int S, int H, int A, int causal, hipStream_t s);
+int attn_bwd(const T* qkv, const T* O, const T* dO, const float* lse, float* dvec, T* dqkv, int m, int S, int H, int A, int causal, hipStream_t s,
+             const float* rot = nullptr);
 template <> int attn_bwd<float>(const float* qkv, const float* O, const float* dO, const float* lse, float* dvec, float* dqkv,
-                                int m, int S, int H, int A, int causal, hipStream_t s) {
-  return launch_attn_bwd_simple<float>(qkv, O, dO, lse, dvec, dqkv, m, S, H, A, causal, s);
+                                int m, int S, int H, int A, int causal, hipStream_t s, const float* rot) {
+  int rc = launch_attn_bwd_simple<float>(qkv, O, dO, lse, dvec, dqkv, m, S, H, A, causal, s);
+  if (rc == CEPHALO_OK && rot) rc = launch_rotary<float>(dqkv, rot, m * S, S, H, A, 1, s);
+  return rc;
 }
 template <> int attn_bwd<bf16>(const bf16* qkv, const bf16* O, const bf16* dO, const float* lse, float* dvec, bf16* dqkv,
-                               int m, int S, int H, int A, int causal, hipStream_t s) {
-  return launch_attn_bwd_mfma(qkv, O, dO, lse, dvec, dqkv, m, S, H, A, causal, s);
+                               int m, int S, int H, int A, int causal, hipStream_t s, const float* rot) {
+  return launch_attn_bwd_mfma(qkv, O, dO, lse, dvec, dqkv, m, S, H, A, causal, s, rot);   // fused into the stores of dq and dk
 }
 
 template <typename T> T* at(void* base, size_t off) { return reinterpret_cast<T*>(static_cast<char*>(base) + off); }
@@ -227,7 +244,7 @@ int wgrad<bf16>(const bf16* dY, const bf16* X, int Tn, int N, int K, float* G, f
 }
 
 template <typename T> struct Saved {
-  float *mean1, *rstd1, *lse, *mean2, *rstd2, *x1;
+  float *mean1, *rstd1, *lse, *mean2, *rstd2, *x1, *rot;
   T *u, *qkv, *O, *u2, *z, *h;
 };
 // pointers to the saved tensors of the samples starting at `sample0` inside a save area laid out by L
@@ -240,7 +257,8 @@ Saved<T> saved_at(void* base, const SaveLayout& L, const cephalo_layer_desc& d, 
   s.lse = at<float>(base, L.lse) + (size_t)sample0 * d.heads * d.seq;
   s.u = at<T>(base, L.u) + t0 * H; s.qkv = at<T>(base, L.qkv) + t0 * 3 * H; s.O = at<T>(base, L.O) + t0 * H;
   s.x1 = at<float>(base, L.x1) + t0 * H; s.u2 = at<T>(base, L.u2) + t0 * H;
-  s.z = at<T>(base, L.z) + t0 * F; s.h = at<T>(base, L.h) + t0 * F;
+  s.z = at<T>(base, L.z) + t0 * (size_t)ff1_width(d); s.h = at<T>(base, L.h) + t0 * F;
+  s.rot = at<float>(base, L.rot);
   return s;
 }
 
@@ -257,7 +275,7 @@ template <typename T>
 Work<T> work_at(void* base, const ScratchLayout& W, const cephalo_layer_desc& d, int sample0, int mb_index, int m) {
   const size_t t0 = (size_t)sample0 * d.seq, H = d.hidden, F = d.mlp;
   Work<T> w;
-  w.dz = at<T>(base, W.dz) + t0 * F; w.dx1 = at<float>(base, W.dx1) + t0 * H; w.dx1l = at<T>(base, W.dx1l) + t0 * H;
+  w.dz = at<T>(base, W.dz) + t0 * (size_t)ff1_width(d); w.dx1 = at<float>(base, W.dx1) + t0 * H; w.dx1l = at<T>(base, W.dx1l) + t0 * H;
   w.dyl = at<T>(base, W.dyl) + t0 * H; w.dqkv = at<T>(base, W.dqkv) + t0 * 3 * H;
   w.du2 = at<float>(base, W.du2); w.dO = at<T>(base, W.dO); w.du = at<float>(base, W.du); w.wT = at<T>(base, W.wT);
   w.dvec = at<float>(base, W.dvec);
@@ -274,6 +292,37 @@ template <typename T>
 int layer_fwd_t(const cephalo_layer_desc& d, const T* P, const float* x, float* y, int m, const Saved<T>& sv, hipStream_t s) {
   const ParamOffsets o = param_offsets(d);
   const int Tn = m * d.seq, H = d.hidden, F = d.mlp;
+  if (is_llama(d)) {
+    // u = RMS1(x); qkv = u Wqkv^T; rotary on q, k; attention; x1 = x + O Wo^T; u2 = RMS2(x1); [g | up] = u2 Wgu^T;
+    // h = silu(g) up; y = x1 + h Wdown^T
+    TRY(launch_ln_fwd<T>(x, P + o.ln1_g, (const T*)nullptr, sv.u, sv.mean1, sv.rstd1, Tn, H, d.ln_eps, s, true));
+    TRY(launch_rotary_table(sv.rot, d.seq, H / d.heads, kRopeBase, s));   // (every micro-batch writes the same values)
+    {
+      GemmArgs<T> a = linear_fwd<T>(sv.u, P + o.w_qkv, Tn, 3 * H, H);
+      a.epi = EPI_ROPE; a.C = sv.qkv;       // q and k leave the GEMM already rotated (one rounding, of the rotated value)
+      a.rot = sv.rot; a.rot_S = d.seq; a.rot_d = H / d.heads; a.rot_cols = 2 * H;
+      TRY(gemm<T>(a, s));
+    }
+    TRY(attn_fwd<T>(sv.qkv, sv.O, sv.lse, m, d.seq, H, d.heads, d.causal, s));
+    {
+      GemmArgs<T> a = linear_fwd<T>(sv.O, P + o.w_o, Tn, H, H);
+      a.epi = EPI_BIAS_RESID; a.bias = nullptr; a.Rf = x; a.Cf = sv.x1;
+      TRY(gemm<T>(a, s));
+    }
+    TRY(launch_ln_fwd<T>(sv.x1, P + o.ln2_g, (const T*)nullptr, sv.u2, sv.mean2, sv.rstd2, Tn, H, d.ln_eps, s, true));
+    {
+      GemmArgs<T> a = linear_fwd<T>(sv.u2, P + o.w_fc1, Tn, 2 * F, H);
+      a.epi = EPI_NONE; a.C = sv.z;
+      TRY(gemm<T>(a, s));
+    }
+    TRY(launch_swiglu_fwd<T>(sv.z, sv.h, Tn, F, s));
+    {
+      GemmArgs<T> a = linear_fwd<T>(sv.h, P + o.w_fc2, Tn, H, F);
+      a.epi = EPI_BIAS_RESID; a.bias = nullptr; a.Rf = sv.x1; a.Cf = y;
+      TRY(gemm<T>(a, s));
+    }
+    return CEPHALO_OK;
+  }
   TRY(launch_ln_fwd<T>(x, P + o.ln1_g, P + o.ln1_b, sv.u, sv.mean1, sv.rstd1, Tn, H, d.ln_eps, s));
   {
     GemmArgs<T> a = linear_fwd<T>(sv.u, P + o.w_qkv, Tn, 3 * H, H);
@@ -329,7 +378,7 @@ template <> inline int prepare_dgrad_weights<bf16>(const cephalo_layer_desc& d, 
   const int H = d.hidden, F = d.mlp;
   TRY(launch_transpose_bf16(P + o.w_qkv, wT + o.w_qkv, 3 * H, H, s));
   TRY(launch_transpose_bf16(P + o.w_o, wT + o.w_o, H, H, s));
-  TRY(launch_transpose_bf16(P + o.w_fc1, wT + o.w_fc1, F, H, s));
+  TRY(launch_transpose_bf16(P + o.w_fc1, wT + o.w_fc1, (int)ff1_width(d), H, s));
   TRY(launch_transpose_bf16(P + o.w_fc2, wT + o.w_fc2, H, F, s));
   return CEPHALO_OK;
 }
@@ -341,6 +390,32 @@ int layer_bwd_data_t(const cephalo_layer_desc& d, const T* P, const float* x, co
                      const Saved<T>& sv, const Work<T>& w, hipStream_t s) {
   const ParamOffsets o = param_offsets(d);
   const int Tn = m * d.seq, H = d.hidden, F = d.mlp;
+  if (is_llama(d)) {
+    {
+      GemmArgs<T> a = dgrad_args<T>(dyl, P, w.wT, o.w_fc2, Tn, H, F);   // dh = dy Wdown, then d[gate | up] from the fp32 products
+      a.epi = EPI_DSWIGLU; a.Z = sv.z; a.C = w.dz; a.ldc = 2 * F;
+      TRY(gemm<T>(a, s));
+    }
+    {
+      GemmArgs<T> a = dgrad_args<T>(w.dz, P, w.wT, o.w_fc1, Tn, 2 * F, H);
+      a.epi = EPI_NONE; a.Cf = w.du2;
+      TRY(gemm<T>(a, s));
+    }
+    TRY(launch_ln_bwd<T>(w.du2, sv.x1, sv.mean2, sv.rstd2, P + o.ln2_g, dy, w.dx1, lowp_out<T>(w.dx1l), w.ln2_g, w.ln2_b, Tn, H, s, true));
+    {
+      GemmArgs<T> a = dgrad_args<T>(lowp_of<T>(w.dx1, w.dx1l), P, w.wT, o.w_o, Tn, H, H);
+      a.epi = EPI_NONE; a.C = w.dO;
+      TRY(gemm<T>(a, s));
+    }
+    TRY(attn_bwd<T>(sv.qkv, sv.O, w.dO, sv.lse, w.dvec, w.dqkv, m, d.seq, H, d.heads, d.causal, s, sv.rot));   // dq, dk: turned back by the angle
+    {
+      GemmArgs<T> a = dgrad_args<T>(w.dqkv, P, w.wT, o.w_qkv, Tn, 3 * H, H);
+      a.epi = EPI_NONE; a.Cf = w.du;
+      TRY(gemm<T>(a, s));
+    }
+    TRY(launch_ln_bwd<T>(w.du, x, sv.mean1, sv.rstd1, P + o.ln1_g, w.dx1, dx, lowp_out<T>(dxl), w.ln1_g, w.ln1_b, Tn, H, s, true));
+    return CEPHALO_OK;
+  }
   {
     GemmArgs<T> a = dgrad_args<T>(dyl, P, w.wT, o.w_fc2, Tn, H, F);   // dh = dy W2, then dz = dh * gelu'(z)
     a.epi = EPI_DGELU; a.Z = sv.z; a.C = w.dz;
@@ -378,6 +453,15 @@ int layer_bwd_params_t(const cephalo_layer_desc& d, const float* dy, const T* dy
                        const Saved<T>& sv, const Work<T>& w, float* G, float scale, int acc, hipStream_t s) {
   const ParamOffsets o = param_offsets(d);
   const int H = d.hidden, F = d.mlp;
+  if (is_llama(d)) {
+    TRY(wgrad<T>(dyl, sv.h, tokens, H, F, G + o.w_fc2, scale, acc, w.wg_part, s));
+    TRY(wgrad<T>(w.dz, sv.u2, tokens, 2 * F, H, G + o.w_fc1, scale, acc, w.wg_part, s));
+    TRY(launch_reduce_partials(w.ln2_g, ln_chunks, H, G + o.ln2_g, scale, acc, w.col_part, w.col_part_bytes, s));
+    TRY(wgrad<T>(lowp_of<T>(w.dx1, w.dx1l), sv.O, tokens, H, H, G + o.w_o, scale, acc, w.wg_part, s));
+    TRY(wgrad<T>(w.dqkv, sv.u, tokens, 3 * H, H, G + o.w_qkv, scale, acc, w.wg_part, s));
+    TRY(launch_reduce_partials(w.ln1_g, ln_chunks, H, G + o.ln1_g, scale, acc, w.col_part, w.col_part_bytes, s));
+    return CEPHALO_OK;
+  }
   TRY(launch_colsum<float>(dy, w.col_part, w.col_part_bytes, G + o.b_fc2, scale, acc, tokens, H, s));
   TRY(wgrad<T>(dyl, sv.h, tokens, H, F, G + o.w_fc2, scale, acc, w.wg_part, s));
   TRY(launch_colsum<T>(w.dz, w.col_part, w.col_part_bytes, G + o.b_fc1, scale, acc, tokens, F, s));

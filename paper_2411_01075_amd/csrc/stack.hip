@@ -172,6 +172,7 @@ int check_stack(const cephalo_stack_desc* d) {
   if (!d) return fail(CEPHALO_EINVAL, "stack desc is null");
   TRY(check_desc(&d->layer));
   if (d->layers <= 0 || d->vocab <= 0) return fail(CEPHALO_EINVAL, "stack desc: layers %d and vocab %d must be positive", d->layers, d->vocab);
+  if (d->layer.kind != CEPHALO_LAYER_GPT) return fail(CEPHALO_EUNSUPPORTED, "stack desc: the stack (learned positions, LayerNorm, tied head) is built of GPT-style layers only");
   if (d->checkpoint != 0 && d->checkpoint != 1) return fail(CEPHALO_EINVAL, "stack desc: checkpoint must be 0 or 1");
   if (d->offload != 0 && d->offload != 1) return fail(CEPHALO_EINVAL, "stack desc: offload must be 0 or 1");
   if (d->offload && !d->checkpoint) return fail(CEPHALO_EINVAL, "stack desc: offload needs checkpoint = 1 (only boundary activations are offloaded)");

@@ -1,0 +1,108 @@
+"""The Llama-style layer (RMSNorm, rotary embedding, gated SiLU feed-forward, no biases) on the GPU against its oracle,
+through the C ABI: share call and per-micro-batch calls, bf16 and fp32, ragged sizes."""
+import dataclasses
+
+import numpy as np
+import pytest
+import torch
+
+import paper_2411_01075_amd as C
+from oracle import llama as ol
+from oracle.precision import round_to_bf16
+from tests.harness import TOL, assert_close, tdtype
+from workloads.configs import CONFIGS
+from workloads.generate import draw_activations, draw_layer_params
+
+pytestmark = pytest.mark.gpu
+
+CASES = {
+    "bf16_mini": CONFIGS["lmini"],                                                         # F = 688, S = 136: ragged tiles
+    "bf16_d128": dataclasses.replace(CONFIGS["lmini"], hidden=256, heads=2, mlp=344, seq=200, micro_batch=1, n_micro=3),
+    "f32_tiny": dataclasses.replace(CONFIGS["lmini"], dtype="f32", hidden=64, heads=2, mlp=96, seq=24, micro_batch=1, n_micro=3),
+    "bf16_noncausal": dataclasses.replace(CONFIGS["lmini"], causal=False, seq=96),
+}
+
+
+def run_gpu(cfg, params, x, dy, scale, via_share_call):
+    desc = C.desc_from_config(cfg)
+    assert desc.kind == C.LAYER_LLAMA
+    flat32 = torch.from_numpy(C.flatten_layer_params(desc, params)).cuda()
+    if cfg.dtype == "bf16":
+        flat = torch.empty(flat32.numel(), dtype=torch.bfloat16, device="cuda")
+        C.cephalo_cast_bf16(flat, flat32)
+    else:
+        flat = flat32
+    xd, dyd = torch.from_numpy(x).cuda().float().contiguous(), torch.from_numpy(dy).cuda().float().contiguous()
+    b, m = x.shape[0], cfg.micro_batch
+    yd, dxd = torch.empty_like(xd), torch.empty_like(xd)
+    G = torch.full((flat32.numel(),), float("nan"), dtype=torch.float32, device="cuda")
+    if via_share_call:
+        save_b, scr_b = C.cephalo_share_workspace_bytes(desc, b, m)
+        save = torch.empty(save_b, dtype=torch.uint8, device="cuda"); scratch = torch.empty(scr_b, dtype=torch.uint8, device="cuda")
+        C.cephalo_share_layer_step(desc, flat, xd, yd, dyd, dxd, b, m, save, G, scale, scratch)
+    else:
+        save_b, scr_b = C.cephalo_layer_workspace_bytes(desc, m)
+        save = torch.empty(save_b * (b // m), dtype=torch.uint8, device="cuda"); scratch = torch.empty(scr_b, dtype=torch.uint8, device="cuda")
+        for j in range(b // m):
+            sl = slice(j * m, (j + 1) * m)
+            C.cephalo_layer_fwd(desc, flat, xd[sl], yd[sl], m, save[j * save_b:(j + 1) * save_b], scratch)
+        for j in range(b // m):
+            sl = slice(j * m, (j + 1) * m)
+            C.cephalo_layer_bwd(desc, flat, xd[sl], dyd[sl], dxd[sl], m, save[j * save_b:(j + 1) * save_b], G, scale, j > 0, scratch)
+    torch.cuda.synchronize()
+    return yd.double().cpu().numpy(), dxd.double().cpu().numpy(), G.cpu().numpy(), desc
+
+
+@pytest.mark.parametrize("via_share_call", [True, False])
+@pytest.mark.parametrize("case", list(CASES))
+def test_llama_layer_matches_oracle(case, via_share_call):
+    cfg = CASES[case]
+    print("llama layer", case, via_share_call, flush=True)
+    params = draw_layer_params(cfg, perturbed=True)
+    x, dy = draw_activations(cfg)
+    scale = 0.625
+    y, dx, G, desc = run_gpu(cfg, params, x, dy, scale, via_share_call)
+    f = (lambda a: round_to_bf16(a)) if cfg.dtype == "bf16" else (lambda a: a.astype(np.float64))
+    p64 = {k: f(v) for k, v in params.items()}
+    ry, rdx, rg = ol.share_step(p64, x.astype(np.float64), dy.astype(np.float64), cfg.heads, cfg.micro_batch, causal=cfg.causal, scale=scale)
+    assert_close("y", y, ry, cfg.dtype)
+    assert_close("dx", dx, rdx, cfg.dtype)
+    offs = C.cephalo_layer_param_offsets(desc)
+    assert C.cephalo_layer_param_count(desc) == 4 * cfg.hidden ** 2 + 3 * cfg.hidden * cfg.mlp + 2 * cfg.hidden
+    for name, o in zip(C.LLAMA_TENSOR_NAMES, offs):
+        if name is None:
+            continue
+        n = rg[name].size
+        assert_close("grad " + name, G[o:o + n], rg[name].reshape(-1), cfg.dtype)
+    assert np.isfinite(G).all()                                   # every element was written
+
+
+def test_llama_is_reproducible_and_stack_refuses_it():
+    cfg = CASES["bf16_mini"]
+    params = draw_layer_params(cfg, perturbed=True)
+    x, dy = draw_activations(cfg)
+    a = run_gpu(cfg, params, x, dy, 1.0, True)
+    b = run_gpu(cfg, params, x, dy, 1.0, True)
+    assert np.array_equal(a[0], b[0]) and np.array_equal(a[1], b[1]) and np.array_equal(a[2], b[2])
+    sd = C.StackDesc(a[3], 2, 101, 0, 0)
+    with pytest.raises(C.CephaloError):
+        C.cephalo_stack_param_count(sd)
+
+
+def test_llama_7b_layer_full_size():
+    """The 7B-class layer (H 4096, 32 heads of 128, F 11008, S 2048) at the micro-batch size bench.py times, whole
+    forward and backward of one micro-batch against the oracle on the same inputs (the oracle takes some 20 s)."""
+    cfg = dataclasses.replace(CONFIGS["l7b"], n_micro=1)
+    print("llama 7B-class layer, full size", flush=True)
+    params = draw_layer_params(cfg, perturbed=True)
+    x, dy = draw_activations(cfg)
+    y, dx, G, desc = run_gpu(cfg, params, x, dy, 1.0, True)
+    p64 = {k: round_to_bf16(v) for k, v in params.items()}
+    ry, cache = ol.layer_fwd(p64, x.astype(np.float64), cfg.heads, cfg.causal)
+    rdx, rg = ol.layer_bwd(p64, cache, dy.astype(np.float64), cfg.heads)
+    assert_close("y", y, ry, "bf16")
+    assert_close("dx", dx, rdx, "bf16")
+    offs = C.cephalo_layer_param_offsets(desc)
+    for name, o in zip(C.LLAMA_TENSOR_NAMES, offs):
+        if name is not None:
+            assert_close("grad " + name, G[o:o + rg[name].size], rg[name].reshape(-1), "bf16")

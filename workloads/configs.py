@@ -25,6 +25,8 @@ class LayerConfig:
     seed: int = 0
     lr: float = 1e-3
     shard_rule: str = ""
+    kind: str = "gpt"    # "gpt": LayerNorm, biases, GELU; "llama": RMSNorm, rotary embedding, gated SiLU, no biases
+    init_std: float = 0.02   # standard deviation of the weight matrices' draws
 
     @property
     def batch_share(self):
@@ -51,6 +53,14 @@ CONFIGS = {
     # full 24-layer GPT stack with tied embedding
     "c5": LayerConfig("c5", 2048, 16, 8192, 2048, True, 2, 6, "bf16", layers=24, vocab=50257, seed=1005,
                       shard_rule="frac29_seeded"),
+    # Llama-style layers (sizes only): a 7B-class layer (H 4096, 32 heads, F 11008) and a small one for the oracle
+    # (weights N(0, 0.01^2): at H = 4096 the 0.02 of the GPT-2 family makes a random layer's branches several times larger
+    #  than the residual stream they are added to, which no trained network of this width looks like)
+    "l7b": LayerConfig("l7b", 4096, 32, 11008, 2048, True, 1, 4, "bf16", seed=1006, shard_rule="third_odd", kind="llama",
+                       init_std=0.01),
+    "lmini": LayerConfig("lmini", 256, 4, 688, 136, True, 2, 2, "bf16", seed=1106, shard_rule="frac:37:41", kind="llama"),
+    # ViT-Large-shaped encoder layer: 197 tokens per image, non-causal (the GPT-style layer form)
+    "vitl": LayerConfig("vitl", 1024, 16, 4096, 197, False, 8, 2, "bf16", seed=1007, shard_rule="frac:50:23"),
     # reduced relatives used only by parity tests (ragged tiles, small enough for the oracle)
     "c5mini": LayerConfig("c5mini", 256, 4, 1024, 128, True, 2, 2, "bf16", layers=2, vocab=1031, seed=1105,
                           shard_rule="frac29_seeded"),

@@ -24,6 +24,16 @@ LAYER_TENSORS = (
 )
 
 
+LLAMA_TENSORS = (
+    ("rms1_g", lambda H, F: (H,), "gamma"),
+    ("w_qkv", lambda H, F: (3 * H, H), "weight"),
+    ("w_o", lambda H, F: (H, H), "weight"),
+    ("rms2_g", lambda H, F: (H,), "gamma"),
+    ("w_gu", lambda H, F: (2 * F, H), "weight"),
+    ("w_down", lambda H, F: (H, F), "weight"),
+)
+
+
 def _rng(seed, name):
     return np.random.Generator(np.random.Philox(key=[seed, zlib.crc32(name.encode())]))
 
@@ -41,18 +51,18 @@ def _normal(seed, name, shape, std, chunk=1 << 24):
 
 
 def draw_layer_params(cfg, layer_index=0, perturbed=False):
-    """dict name -> float32 array.  Weights N(0, 0.02^2); biases 0; LN gamma 1, beta 0.
+    """dict name -> float32 array.  Weights N(0, cfg.init_std^2) (0.02 unless the config says otherwise); biases 0; LN gamma 1, beta 0.
 
     perturbed=True shifts biases, gamma and beta by N(0, 0.02^2) draws so that a test
     can tell tensors (and their rows) apart; the plain form hides indexing mistakes.
     """
     H, F = cfg.hidden, cfg.mlp
     out = {}
-    for name, shp, kind in LAYER_TENSORS:
+    for name, shp, kind in (LLAMA_TENSORS if getattr(cfg, "kind", "gpt") == "llama" else LAYER_TENSORS):
         shape = shp(H, F)
         tag = "L%d.%s" % (layer_index, name)
         if kind == "weight":
-            t = _normal(cfg.seed, tag, shape, 0.02)
+            t = _normal(cfg.seed, tag, shape, getattr(cfg, "init_std", 0.02))
         else:
             t = np.zeros(shape, dtype=np.float32)
             if kind == "gamma":
