@@ -255,6 +255,9 @@ def main():
     extras["shard_adam"] = {"elements": ln, "us": round(adam_sec * 1e6, 1), "GB/s": round(adam_bytes / adam_sec / 1e9, 1),
                             "frac_of_hbm_peak": round(adam_bytes / adam_sec / 1e9 / PEAK_HBM_GBS, 4)}
 
+    # bf16 GEMMs that fell off the matrix-core kernel onto the general one (0 for every workload here)
+    extras["gemm_calls_on_general_kernel"] = C.cephalo_gemm_general_count()
+
     # ---- CPU baseline: the oracle as it stands, on a bounded sample of the same workload
     cpu = None
     if not args.no_cpu_baseline:

@@ -80,6 +80,11 @@ typedef struct cephalo_layer_desc {
 /* Text of the calling thread's most recent error ("" if none). Host pointer, library-owned. */
 const char* cephalo_last_error(void);
 
+/* Number of bf16 GEMMs, since the library was loaded, that could not run on the matrix-core kernel (operand pitch or
+ * alignment, or a layout / epilogue pair it does not implement) and took the general, much slower kernel instead.  The
+ * results are the same; a caller that cares about speed checks that the count stays where it was. */
+int64_t cephalo_gemm_general_count(void);
+
 /* Number of elements P of one layer's flat buffer, 4H^2 + 2HF + 9H + F (GPT-style) or 4H^2 + 3HF + 2H (Llama-style);
  * negative on a bad desc. */
 int64_t cephalo_layer_param_count(const cephalo_layer_desc* desc);

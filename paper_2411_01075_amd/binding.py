@@ -65,6 +65,7 @@ _dp = ctypes.POINTER(LayerDesc)
 # name -> (restype, argtypes); must list every symbol include/cephalo.h declares
 SIGNATURES = {
     "cephalo_last_error": (ctypes.c_char_p, []),
+    "cephalo_gemm_general_count": (ctypes.c_int64, []),
     "cephalo_layer_param_count": (_i64, [_dp]),
     "cephalo_layer_param_offsets": (ctypes.c_int, [_dp, ctypes.POINTER(_i64)]),
     "cephalo_layer_workspace_bytes": (ctypes.c_int, [_dp, _i32, ctypes.POINTER(_sz), ctypes.POINTER(_sz)]),
@@ -144,6 +145,10 @@ def _stream(stream):
 
 def cephalo_last_error():
     return lib().cephalo_last_error().decode()
+
+
+def cephalo_gemm_general_count():
+    return int(lib().cephalo_gemm_general_count())
 
 
 def cephalo_layer_param_count(desc):

@@ -31,6 +31,7 @@
 // Pipeline: two or three LDS stages; the loads of the following slab(s) are in flight while a slab is multiplied;
 // one barrier per slab.  The loads are issued through inline assembly (see load_slab_untracked).
 #include "kernels.h"
+#include <atomic>
 #include <cstdlib>
 #include <cstdint>
 #include <algorithm>
@@ -529,6 +530,15 @@ int gemm_grad_splits(int M, int N, int K) {
   return best;
 }
 
+namespace {
+std::atomic<int64_t> general_count{0};
+int general(const GemmArgs<bf16>& a, hipStream_t s) {
+  general_count.fetch_add(1, std::memory_order_relaxed);
+  return launch_gemm_simple<bf16>(a, s);
+}
+}  // namespace
+int64_t gemm_general_count() { return general_count.load(std::memory_order_relaxed); }
+
 int launch_gemm_mfma(const GemmArgs<bf16>& a, hipStream_t s) {
   if (a.M <= 0 || a.N <= 0 || a.K <= 0) return fail(CEPHALO_EINVAL, "gemm: empty problem %dx%dx%d", a.M, a.N, a.K);
   const bool ak = a.a_cs == 1, bk = a.b_cs == 1;
@@ -541,7 +551,7 @@ int launch_gemm_mfma(const GemmArgs<bf16>& a, hipStream_t s) {
   const bool small = ext_a < (int64_t)0x7fffffff && ext_b < (int64_t)0x7fffffff;   // 32-bit buffer extents and offsets
   const int64_t pitch_c = a.ldc ? a.ldc : a.N;
   const bool ok_c = pitch_c % 8 == 0 && pitch_c >= up8(a.N) && (a.epi != EPI_GRAD || a.N % 8 == 0) && aligned16(a.C) && aligned16(a.R) && aligned16(a.Z) && aligned16(a.bias) && aligned16(a.G) && aligned16(a.Rf) && aligned16(a.Cf);   // vector epilogue
-  if (!ok_a || !ok_b || !ok_c || !small || !aligned16(a.A) || !aligned16(a.B)) return launch_gemm_simple<bf16>(a, s);
+  if (!ok_a || !ok_b || !ok_c || !small || !aligned16(a.A) || !aligned16(a.B)) return general(a, s);
   // Only the layout/epilogue pairs a linear layer produces are instantiated.
   if (ak && bk) {          // forward: Y = X W^T
     switch (a.epi) {
@@ -551,13 +561,13 @@ int launch_gemm_mfma(const GemmArgs<bf16>& a, hipStream_t s) {
       case EPI_BIAS_RESID: return launch_tiles<true, true, EPI_BIAS_RESID>(a, s);
       case EPI_BIAS_GELU: return launch_tiles<true, true, EPI_BIAS_GELU>(a, s);
       case EPI_DGELU: return launch_tiles<true, true, EPI_DGELU>(a, s);
+      case EPI_DSWIGLU: if (a.N % 8 == 0) return launch_tiles<true, true, EPI_DSWIGLU>(a, s); break;
       case EPI_GRAD: return launch_tiles<true, true, EPI_GRAD>(a, s);
     }
   } else if (ak && !bk) {  // dgrad: dX = dY W
     switch (a.epi) {
       case EPI_NONE: return launch_tiles<true, false, EPI_NONE>(a, s);
       case EPI_DGELU: return launch_tiles<true, false, EPI_DGELU>(a, s);
-      case EPI_DSWIGLU: if (a.N % 8 == 0) return launch_tiles<true, false, EPI_DSWIGLU>(a, s); break;
       default: break;
     }
     if (a.epi == EPI_GRAD) return launch_tiles<true, false, EPI_GRAD>(a, s);   // wgrad with dY pre-transposed
@@ -566,7 +576,7 @@ int launch_gemm_mfma(const GemmArgs<bf16>& a, hipStream_t s) {
   } else {                  // wgrad with X pre-transposed
     if (a.epi == EPI_GRAD) return launch_tiles<false, true, EPI_GRAD>(a, s);
   }
-  return launch_gemm_simple<bf16>(a, s);
+  return general(a, s);
 }
 
 }  // namespace cephalo

@@ -130,6 +130,7 @@ int gemm_grad_splits(int M, int N, int K);
 
 template <typename T> int launch_gemm_simple(const GemmArgs<T>& a, hipStream_t s);
 int launch_gemm_mfma(const GemmArgs<bf16>& a, hipStream_t s);  // bf16 operands, MFMA, fp32 accumulate
+int64_t gemm_general_count();   // calls of launch_gemm_mfma that ended in launch_gemm_simple
 
 // ---------------------------------------------------------------------------------------
 // LayerNorm over the last axis of x[rows, H].  The residual stream x is fp32; the output u is in the activation type.

@@ -30,6 +30,8 @@ int check_attn(const cephalo_layer_desc* d, int m) {
 }
 }  // namespace
 
+extern "C" int64_t cephalo_gemm_general_count(void) { return cephalo::gemm_general_count(); }
+
 extern "C" int cephalo_op_gemm(int32_t dtype, const void* A, int64_t a_rs, int64_t a_cs,
                                const void* B, int64_t b_rs, int64_t b_cs, int32_t M, int32_t N, int32_t K,
                                int32_t epilogue, void* C, const void* bias, const void* R, void* Z,

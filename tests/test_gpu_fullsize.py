@@ -122,8 +122,10 @@ def test_c5_stack_full_size_layer_by_layer():
     G = torch.full((flat.numel(),), float("nan"), device="cuda")
     loss = torch.full((1,), float("nan"), device="cuda")
     dids, dtgt = torch.from_numpy(ids).cuda(), torch.from_numpy(tgt).cuda()
+    general = C.cephalo_gemm_general_count()
     C.cephalo_stack_step(sd, flat, dids, dtgt, b, m, G, 1.0, loss, ws)
     torch.cuda.synchronize()
+    assert C.cephalo_gemm_general_count() == general           # every GEMM of the step ran on the matrix-core kernel
     l1 = float(loss.item())
     print("c5 loss", l1, flush=True)
     assert abs(l1 - (np.log(cfg.vocab) + 0.5 * 0.02 ** 2 * Hh)) < 0.15      # logits ~ N(0, 0.02^2 H): E[lse] = ln V + var/2

@@ -26,6 +26,8 @@ CASES = {
     "bf16_c2_small": small(CONFIGS["c2"], name="bf16_c2s", hidden=256, heads=4, mlp=1024, seq=192, micro_batch=2, n_micro=2),
     "bf16_c3_small": small(CONFIGS["c3"], name="bf16_c3s", hidden=320, heads=5, mlp=1280, seq=200, micro_batch=2, n_micro=3),
     "bf16_c4_small": small(CONFIGS["c4"], name="bf16_c4s", hidden=512, heads=4, mlp=2048, seq=320, micro_batch=1, n_micro=2),
+    # the ViT-Large-shaped encoder layer at its full size: 197 tokens per image (a ragged attention tile), non-causal
+    "bf16_vitl": CONFIGS["vitl"],
 }
 
 

@@ -96,7 +96,9 @@ def test_llama_7b_layer_full_size():
     print("llama 7B-class layer, full size", flush=True)
     params = draw_layer_params(cfg, perturbed=True)
     x, dy = draw_activations(cfg)
+    general = C.cephalo_gemm_general_count()
     y, dx, G, desc = run_gpu(cfg, params, x, dy, 1.0, True)
+    assert C.cephalo_gemm_general_count() == general           # every GEMM of the step ran on the matrix-core kernel
     p64 = {k: round_to_bf16(v) for k, v in params.items()}
     ry, cache = ol.layer_fwd(p64, x.astype(np.float64), cfg.heads, cfg.causal)
     rdx, rg = ol.layer_bwd(p64, cache, dy.astype(np.float64), cfg.heads)
