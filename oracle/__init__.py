@@ -29,7 +29,8 @@ pure-Python triple loops on tiny shapes, closed forms for LayerNorm / softmax / 
 first-step Adam, torch.optim.Adam for the unsharded update, the micro-batch-sum and
 shard-partition invariants, and Eq. 1 with uneven shares.  The whole-stack loss value
 (oracle.stack) has no printed value in the paper to compare with: its pins are finite
-differences and autograd only.  oracle.llama (the Llama-style layer: RMSNorm, rotary embedding, gated SiLU feed-forward, no biases) is pinned
+differences and autograd only.  oracle.llama (the Llama-style layer: RMSNorm, rotary embedding, gated SiLU feed-forward, no biases; and a stack of
+them with a token embedding, a final RMSNorm and a head of its own) is pinned
 by tests/test_oracle_llama.py: closed forms, rotation invariants, finite differences and an independent torch
 implementation under autograd.  oracle.perfmodel is pinned by closed forms of the line fit and
 by the latencies and memory the paper plots (tests/golden/); oracle.plan is the definition

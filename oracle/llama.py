@@ -124,3 +124,58 @@ def share_step(p, x, dy, heads, micro_batch, causal=True, eps=1e-5, scale=1.0):
         ys.append(y); dxs.append(dx)
         total = g if total is None else {k: total[k] + g[k] for k in g}
     return np.concatenate(ys), np.concatenate(dxs), {k: scale * v for k, v in total.items()}
+
+
+def stack_step(params, ids, targets, heads, causal, m, scale=1.0, eps=1e-5):
+    """A whole Llama-style stack on one GPU's batch share, in the layered order of Sec. 3.2 (every micro-batch through a
+    layer before the next layer, forward and backward).  The paper names the models (Sec. 5.1, model table) and gives
+    none of their pieces; the form here: x0 = wte[id] (the positions enter through the rotation inside each layer),
+    L layers as above, a final RMSNorm, logits = normf(x) w_head^T with a head of its own (not tied to wte), loss =
+    mean over all b*S tokens of the cross-entropy against the target ids.
+
+    params: dict with 'wte' [V,H], 'layers' (list of layer dicts), 'normf_g' [H], 'w_head' [V,H] (fp64).
+    ids, targets: [b, S] ints.  Returns (mean loss, scale * gradient in the same structure)."""
+    from .stack import cross_entropy
+    b, S = ids.shape
+    H = params["wte"].shape[1]
+    L = len(params["layers"])
+    assert b % m == 0
+    micro = [(lo, lo + m) for lo in range(0, b, m)]
+    n_tok = b * S
+    xs = [[params["wte"][ids[lo:hi]] for lo, hi in micro]]
+    caches = []
+    for li in range(L):
+        outs, cs = [], []
+        for j in range(len(micro)):
+            y, c = layer_fwd(params["layers"][li], xs[li][j], heads, causal, eps)
+            outs.append(y)
+            cs.append(c)
+        xs.append(outs)
+        caches.append(cs)
+    g = {"wte": np.zeros_like(params["wte"]), "normf_g": np.zeros(H), "w_head": np.zeros_like(params["w_head"]),
+         "layers": [{k: np.zeros_like(v) for k, v in lp.items()} for lp in params["layers"]]}
+    total = 0.0
+    dxs = []
+    for j, (lo, hi) in enumerate(micro):
+        u, xhat, rstd = rms_norm_fwd(xs[L][j], params["normf_g"], eps)
+        u2 = u.reshape(-1, H)
+        logits = u2 @ params["w_head"].T
+        tgt = targets[lo:hi].reshape(-1)
+        loss, prob = cross_entropy(logits, tgt)
+        total += loss.sum()
+        dlogits = prob
+        dlogits[np.arange(tgt.size), tgt] -= 1.0
+        dlogits *= scale / n_tok
+        g["w_head"] += dlogits.T @ u2
+        du = (dlogits @ params["w_head"]).reshape(u.shape)
+        dx, dgam = rms_norm_bwd(du, xhat, rstd, params["normf_g"])
+        g["normf_g"] += dgam
+        dxs.append(dx)
+    for li in reversed(range(L)):
+        for j in range(len(micro)):
+            dxs[j], gl = layer_bwd(params["layers"][li], caches[li][j], dxs[j], heads)
+            for k, v in gl.items():
+                g["layers"][li][k] += v
+    for j, (lo, hi) in enumerate(micro):
+        np.add.at(g["wte"], ids[lo:hi].reshape(-1), dxs[j].reshape(-1, H))      # a token id met twice collects both gradients
+    return total / n_tok, g

@@ -143,3 +143,68 @@ def test_planted_mistake_is_caught():
     pp["w_qkv"][idx] += eps; pm["w_qkv"][idx] -= eps
     num = (loss_of(pp, x, dy, A) - loss_of(pm, x, dy, A)) / (2 * eps)
     assert abs(num - g["w_qkv"][idx]) > 1e-4 * max(1.0, abs(num))
+
+
+# ---- the stack
+
+def tiny_stack(rng, V, H, F, L):
+    shp = ol.shapes(H, F)
+    layers = [{k: (1 + 0.2 * rng.standard_normal(s)) if k.endswith("_g") else 0.4 * rng.standard_normal(s) for k, s in shp.items()}
+              for _ in range(L)]
+    return {"wte": 0.5 * rng.standard_normal((V, H)), "layers": layers, "normf_g": 1 + 0.2 * rng.standard_normal(H),
+            "w_head": 0.5 * rng.standard_normal((V, H))}
+
+
+def test_stack_against_torch_autograd_and_microbatch_invariance():
+    rng = np.random.default_rng(31)
+    V, S, H, F, L, A, b = 11, 5, 8, 12, 2, 2, 4
+    p = tiny_stack(rng, V, H, F, L)
+    ids = rng.integers(0, V, (b, S))
+    ids[0, :3] = 4                       # repeated tokens: their embedding gradients must add up
+    tgt = rng.integers(0, V, (b, S))
+    loss, g = ol.stack_step(p, ids, tgt, A, True, m=2)
+    tp = {k: torch.tensor(v, requires_grad=True) for k, v in p.items() if k != "layers"}
+    tl = [{k: torch.tensor(v, requires_grad=True) for k, v in lp.items()} for lp in p["layers"]]
+    x = tp["wte"][torch.tensor(ids)]
+    for lp in tl:
+        x = torch_layer(lp, x, A)
+    u = tp["normf_g"] * x * torch.rsqrt((x * x).mean(-1, keepdim=True) + 1e-5)
+    tloss = torch.nn.functional.cross_entropy((u @ tp["w_head"].T).reshape(-1, V), torch.tensor(tgt).reshape(-1))
+    tloss.backward()
+    assert abs(tloss.item() - loss) < 1e-12
+    for k in tp:
+        assert np.max(np.abs(tp[k].grad.numpy() - g[k])) < 1e-11, k
+    for li in range(L):
+        for k in tl[li]:
+            assert np.max(np.abs(tl[li][k].grad.numpy() - g["layers"][li][k])) < 1e-11, (li, k)
+    for m in (1, 4):                     # any split of the share into micro-batches: the same loss and gradient
+        loss2, g2 = ol.stack_step(p, ids, tgt, A, True, m=m)
+        assert abs(loss2 - loss) < 1e-13
+        assert np.max(np.abs(g2["wte"] - g["wte"])) < 1e-13 and np.max(np.abs(g2["w_head"] - g["w_head"])) < 1e-13
+        assert np.max(np.abs(g2["layers"][0]["w_gu"] - g["layers"][0]["w_gu"])) < 1e-13
+
+
+def test_stack_finite_differences_scale_and_closed_forms():
+    rng = np.random.default_rng(32)
+    V, S, H, F, L, A, b = 7, 4, 8, 8, 1, 2, 2
+    p = tiny_stack(rng, V, H, F, L)
+    ids, tgt = rng.integers(0, V, (b, S)), rng.integers(0, V, (b, S))
+    loss, g = ol.stack_step(p, ids, tgt, A, True, m=1)
+    _, g3 = ol.stack_step(p, ids, tgt, A, True, m=1, scale=3.0)
+    assert np.allclose(g3["w_head"], 3.0 * g["w_head"], rtol=1e-13, atol=0)
+    h = 1e-6
+    for t, gt in ((p["wte"], g["wte"]), (p["w_head"], g["w_head"]), (p["normf_g"], g["normf_g"]),
+                  (p["layers"][0]["w_qkv"], g["layers"][0]["w_qkv"]), (p["layers"][0]["w_gu"], g["layers"][0]["w_gu"])):
+        flat, gf = t.reshape(-1), gt.reshape(-1)          # views: the perturbation reaches the stack's own arrays
+        for i in rng.choice(flat.size, 6, replace=False):
+            keep = flat[i]
+            flat[i] = keep + h; lp = ol.stack_step(p, ids, tgt, A, True, m=2)[0]
+            flat[i] = keep - h; lm = ol.stack_step(p, ids, tgt, A, True, m=2)[0]
+            flat[i] = keep
+            assert abs((lp - lm) / (2 * h) - gf[i]) <= 1e-7 * max(1.0, abs(gf[i]))
+    unused = np.setdiff1d(np.arange(V), ids.reshape(-1))
+    assert np.all(g["wte"][unused] == 0.0)                # a token that does not occur gets no embedding gradient
+    z = dict(p, w_head=np.zeros_like(p["w_head"]))        # zero logits: the loss is ln V and nothing flows below the head
+    lz, gz = ol.stack_step(z, ids, tgt, A, True, m=2)
+    assert abs(lz - np.log(V)) < 1e-14 and np.all(gz["wte"] == 0.0) and np.all(gz["layers"][0]["w_o"] == 0.0)
+    assert np.allclose(gz["w_head"].sum(axis=0), 0.0, atol=1e-15)      # softmax - onehot sums to zero over the vocabulary
