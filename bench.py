@@ -43,7 +43,7 @@ def step_model_flops(cfg):
     gemm, attn = layer_flops_per_microbatch(cfg)
     per_micro = cfg.layers * (gemm + attn)
     if cfg.vocab:
-        per_micro += 6.0 * cfg.tokens_per_micro * cfg.hidden * cfg.vocab      # tied LM head: logits, dgrad, wgrad
+        per_micro += 6.0 * cfg.tokens_per_micro * cfg.hidden * cfg.vocab      # LM head (tied or not): logits, dgrad, wgrad
     return cfg.n_micro * per_micro
 
 
@@ -52,14 +52,15 @@ def main():
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=8)
     ap.add_argument("--warmup", type=int, default=2)
-    ap.add_argument("--workload", default="c5", choices=["c1", "c2", "c3", "c4", "c5", "l7b", "vitl"],
-                    help="c5 (default) is the metric's workload; l7b: a Llama-style 7B-class layer; vitl: a ViT-Large-shaped layer")
+    ap.add_argument("--workload", default="c5", choices=["c1", "c2", "c3", "c4", "c5", "l7b", "ltiny", "vitl"],
+                    help="c5 (default) is the metric's workload; l7b: a Llama-style 7B-class layer; ltiny: a TinyLlama-shaped 22-layer "
+                         "stack; vitl: a ViT-Large-shaped layer")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-legs", action="store_true", help="skip the per-kernel legs (whole step only)")
     ap.add_argument("--checkpoint", action="store_true",
-                    help="c5 only: layer-boundary activation checkpointing with recomputation in the backward (one extra forward)")
+                    help="stacks only: layer-boundary activation checkpointing with recomputation in the backward (one extra forward)")
     ap.add_argument("--offload", action="store_true",
-                    help="c5 only, implies --checkpoint: the boundary activations live in pinned host memory and move on a second stream")
+                    help="stacks only, implies --checkpoint: the boundary activations live in pinned host memory and move on a second stream")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build covers one GPU's share of the step; it has no collectives and runs on exactly "
@@ -313,14 +314,20 @@ def cpu_baseline(cfg, params, flat32_h, m_h, v_h, off, ln, lr, acts, tokens):
     rb = (lambda a: round_to_bf16(a)) if cfg.dtype == "bf16" else (lambda a: a.astype(np.float64))
     lp = {k: rb(v) for k, v in params["layers"][0].items()}
     x = np.random.default_rng(0).standard_normal((m, cfg.seq, cfg.hidden))
+    if cfg.kind == "llama":
+        from oracle import llama as olayer          # the Llama-style layer and stack
+        stack_step = olayer.stack_step
+        p1 = {"wte": rb(params["wte"]), "normf_g": rb(params["normf_g"]), "w_head": rb(params["w_head"]), "layers": [lp]}
+    else:
+        stack_step = ostack.stack_step
+        p1 = {"wte": rb(params["wte"]), "wpe": rb(params["wpe"]), "lnf_g": rb(params["lnf_g"]), "lnf_b": rb(params["lnf_b"]), "layers": [lp]}
     t0 = time.perf_counter()
     y, cache = olayer.layer_fwd(lp, x, cfg.heads, cfg.causal)
     olayer.layer_bwd(lp, cache, x, cfg.heads)
     t_layer = time.perf_counter() - t0
     del y, cache
-    p1 = {"wte": rb(params["wte"]), "wpe": rb(params["wpe"]), "lnf_g": rb(params["lnf_g"]), "lnf_b": rb(params["lnf_b"]), "layers": [lp]}
     t0 = time.perf_counter()
-    ostack.stack_step(p1, ids_h[:m], tgt_h[:m], cfg.heads, cfg.causal, m)
+    stack_step(p1, ids_h[:m], tgt_h[:m], cfg.heads, cfg.causal, m)
     t_stack1 = time.perf_counter() - t0
     n_ad = max(1, ln // 64)
     sl = slice(off, off + n_ad)

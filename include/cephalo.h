@@ -224,6 +224,9 @@ int cephalo_op_attention_bwd(const cephalo_layer_desc* desc, const void* qkv, co
  * and position embeddings x0 = wte[id] + wpe[pos], `layers` layers as above, final LayerNorm, logits =
  * lnf(x) wte^T (tied, no bias), loss = mean cross-entropy over all b*S tokens.
  * Flat layout: wte[V,H] wpe[S,H] layer 0 .. layer L-1 (each as above) lnf.gamma[H] lnf.beta[H].
+ * With Llama-style layers (layer.kind = CEPHALO_LAYER_LLAMA; five of the nine models of Sec. 5.1's table): x0 = wte[id]
+ * (positions enter through the rotation inside the layers), a final RMSNorm, logits = normf(x) w_head^T with a head
+ * of its own.  Flat layout: wte[V,H] layer 0 .. layer L-1 normf.gamma[H] w_head[V,H].
  */
 typedef struct cephalo_stack_desc {
   cephalo_layer_desc layer;
@@ -243,8 +246,13 @@ typedef struct cephalo_stack_desc {
                           paper moves that to the host too.)  Goes with cephalo_stack_step_offload. */
 } cephalo_stack_desc;
 
-/* V*H + S*H + L*P_layer + 2H; negative on a bad desc. */
+/* V*H + S*H + L*P_layer + 2H (GPT-style) or 2*V*H + L*P_layer + H (Llama-style); negative on a bad desc. */
 int64_t cephalo_stack_param_count(const cephalo_stack_desc* desc);
+
+/* Element offsets inside the stack's flat buffer, written to host array offsets[5]: token embedding, learned positions
+ * (an empty range, equal to the next offset, where the stack has none), layer 0 (layer i follows at i * P_layer), the
+ * final norm's parameters, the head (the token embedding's offset where the head is tied to it). */
+int cephalo_stack_param_offsets(const cephalo_stack_desc* desc, int64_t* offsets);
 
 /* Bytes of the single work area of cephalo_stack_step (layer-boundary activations and saved activations of
  * every layer and micro-batch, one micro-batch of logits and the share's logit gradients, backward buffers).
@@ -258,7 +266,8 @@ int cephalo_stack_workspace_bytes(const cephalo_stack_desc* desc, int32_t batch_
  *                Eq. 1's factor.  The sum over micro-batches is formed inside the weight-gradient GEMMs.
  *   flat_param   device, [P] in the compute dtype;  ids, targets  device, int32 [b, S]; values outside [0, V)
  *                are clamped into range.
- * Reproducible: no atomics; token-embedding rows are summed in ascending token order. */
+ * Reproducible: no atomics; token-embedding rows are summed in ascending token order (rows of ids that do not occur get
+ * the head's part where the head is tied, zero otherwise). */
 int cephalo_stack_step(const cephalo_stack_desc* desc, const void* flat_param,
                        const int32_t* ids, const int32_t* targets, int32_t batch_share, int32_t micro_batch,
                        float* flat_grad, float grad_scale, float* loss,

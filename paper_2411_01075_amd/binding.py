@@ -78,6 +78,7 @@ SIGNATURES = {
     "cephalo_shard_adam": (ctypes.c_int, [_vp, _vp, _vp, _vp, _vp, _i64, _i64, _i64, _f32, _f32, _f32, _f32, _i64, _vp]),
     "cephalo_cast_bf16": (ctypes.c_int, [_vp, _vp, _i64, _vp]),
     "cephalo_stack_param_count": (_i64, [ctypes.POINTER(StackDesc)]),
+    "cephalo_stack_param_offsets": (ctypes.c_int, [ctypes.POINTER(StackDesc), ctypes.POINTER(_i64)]),
     "cephalo_stack_workspace_bytes": (ctypes.c_int, [ctypes.POINTER(StackDesc), _i32, _i32, ctypes.POINTER(_sz)]),
     "cephalo_stack_step": (ctypes.c_int, [ctypes.POINTER(StackDesc), _vp, _vp, _vp, _i32, _i32, _vp, _f32, _vp, _vp, _sz, _vp]),
     "cephalo_stack_host_bytes": (ctypes.c_int, [ctypes.POINTER(StackDesc), _i32, _i32, ctypes.POINTER(_sz)]),
@@ -271,6 +272,13 @@ def cephalo_stack_param_count(sdesc):
     return int(n)
 
 
+def cephalo_stack_param_offsets(sdesc):
+    """Offsets of (token embedding, learned positions, layer 0, final norm, head) in the stack's flat buffer."""
+    out = (_i64 * 5)()
+    _check(lib().cephalo_stack_param_offsets(ctypes.byref(sdesc), out))
+    return list(out)
+
+
 def cephalo_stack_workspace_bytes(sdesc, batch_share, micro_batch):
     a = _sz(0)
     _check(lib().cephalo_stack_workspace_bytes(ctypes.byref(sdesc), batch_share, micro_batch, ctypes.byref(a)))
@@ -304,24 +312,27 @@ def cephalo_stack_step_offload(sdesc, flat_param, ids, targets, batch_share, mic
 
 
 def flatten_stack_params(sdesc, params):
-    """Host-side marshalling of a stack's parameters (wte, wpe, layers, lnf_g, lnf_b) to the fp32 flat vector."""
+    """Host-side marshalling of a stack's parameters to the fp32 flat vector.  GPT-style: wte, wpe, layers, lnf_g, lnf_b;
+    Llama-style: wte, layers, normf_g, w_head."""
     import numpy as np
     P = cephalo_stack_param_count(sdesc)
     PL = cephalo_layer_param_count(sdesc.layer)
-    flat = np.empty(P, dtype=np.float32)
-    pos = 0
-    for name in ("wte", "wpe"):
-        t = params[name]
+    o_wte, o_wpe, o_layers, o_norm, o_head = cephalo_stack_param_offsets(sdesc)
+    flat = np.full(P, np.nan, dtype=np.float32)
+
+    def put(pos, t):
         flat[pos:pos + t.size] = t.reshape(-1)
-        pos += t.size
-    for lp in params["layers"]:
-        flat[pos:pos + PL] = flatten_layer_params(sdesc.layer, lp)
-        pos += PL
-    for name in ("lnf_g", "lnf_b"):
-        t = params[name]
-        flat[pos:pos + t.size] = t.reshape(-1)
-        pos += t.size
-    assert pos == P
+        return pos + t.size
+    put(o_wte, params["wte"])
+    for i, lp in enumerate(params["layers"]):
+        put(o_layers + i * PL, flatten_layer_params(sdesc.layer, lp))
+    if sdesc.layer.kind == LAYER_LLAMA:
+        put(o_norm, params["normf_g"])
+        assert put(o_head, params["w_head"]) == P
+    else:
+        put(o_wpe, params["wpe"])
+        assert put(put(o_norm, params["lnf_g"]), params["lnf_b"]) == P
+    assert not np.isnan(flat).any()
     return flat
 
 

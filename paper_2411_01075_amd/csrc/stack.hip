@@ -13,7 +13,7 @@ constexpr int kThreads = 256;
 
 __device__ __forceinline__ int clamp_id(int id, int V) { return id < 0 ? 0 : (id >= V ? V - 1 : id); }
 
-// x0[t] = wte[id[t]] + wpe[t % S]; one wavefront per token.  Ids outside [0, V) are clamped.
+// x0[t] = wte[id[t]] + wpe[t % S] (wpe null: no learned positions); one wavefront per token.  Ids outside [0, V) are clamped.
 template <typename T>
 __global__ void __launch_bounds__(kThreads)
 embed_fwd_kernel(const int* __restrict__ ids, const T* __restrict__ wte, const T* __restrict__ wpe, float* __restrict__ x0,
@@ -22,13 +22,17 @@ embed_fwd_kernel(const int* __restrict__ ids, const T* __restrict__ wte, const T
   const int t = blockIdx.x * 4 + (threadIdx.x >> 6), lane = threadIdx.x & 63;
   if (t >= tokens) return;
   const T* e = wte + (int64_t)clamp_id(ids[t], V) * H;
-  const T* p = wpe + (int64_t)(t % S) * H;
+  const T* p = wpe ? wpe + (int64_t)(t % S) * H : nullptr;
   for (int v = lane; v < H / VN; v += 64) {
     float a[VN], b[VN];
     load_vec<T>(e + v * VN, a);
-    load_vec<T>(p + v * VN, b);
+    if (p) {
+      load_vec<T>(p + v * VN, b);
 #pragma unroll
-    for (int i = 0; i < VN; ++i) x0[(int64_t)t * H + v * VN + i] = a[i] + b[i];
+      for (int i = 0; i < VN; ++i) a[i] += b[i];
+    }
+#pragma unroll
+    for (int i = 0; i < VN; ++i) x0[(int64_t)t * H + v * VN + i] = a[i];
   }
 }
 
@@ -168,11 +172,34 @@ template <> int prepare_head_weights<bf16>(const bf16* wte, bf16* wteT, int V, i
   return launch_transpose_bf16(wte, wteT, V, H, s, ldv);
 }
 
+__global__ void __launch_bounds__(kThreads) zero_kernel(float* __restrict__ p, int64_t n4) {
+  const int64_t i = (int64_t)blockIdx.x * kThreads + threadIdx.x;
+  if (i < n4) reinterpret_cast<float4*>(p)[i] = make_float4(0.f, 0.f, 0.f, 0.f);
+}
+
+// Flat layout of a stack.  GPT-style: wte[V,H] wpe[S,H] layers lnf.gamma[H] lnf.beta[H], the head tied to wte.
+// Llama-style: wte[V,H] layers normf.gamma[H] w_head[V,H] (no learned positions, no beta, a head of its own).
+struct StackOffsets {
+  int64_t wte, wpe, layers, normf, head, total;
+  bool tied, positions;
+};
+StackOffsets stack_offsets(const cephalo_stack_desc& d) {
+  const int64_t H = d.layer.hidden, V = d.vocab, PL = param_offsets(d.layer).total;
+  StackOffsets o;
+  o.tied = o.positions = !is_llama(d.layer);
+  o.wte = 0;
+  o.wpe = V * H;
+  o.layers = o.wpe + (o.positions ? (int64_t)d.layer.seq * H : 0);
+  o.normf = o.layers + d.layers * PL;
+  o.head = o.tied ? o.wte : o.normf + H;
+  o.total = o.tied ? o.normf + 2 * H : o.head + V * H;
+  return o;
+}
+
 int check_stack(const cephalo_stack_desc* d) {
   if (!d) return fail(CEPHALO_EINVAL, "stack desc is null");
   TRY(check_desc(&d->layer));
   if (d->layers <= 0 || d->vocab <= 0) return fail(CEPHALO_EINVAL, "stack desc: layers %d and vocab %d must be positive", d->layers, d->vocab);
-  if (d->layer.kind != CEPHALO_LAYER_GPT) return fail(CEPHALO_EUNSUPPORTED, "stack desc: the stack (learned positions, LayerNorm, tied head) is built of GPT-style layers only");
   if (d->checkpoint != 0 && d->checkpoint != 1) return fail(CEPHALO_EINVAL, "stack desc: checkpoint must be 0 or 1");
   if (d->offload != 0 && d->offload != 1) return fail(CEPHALO_EINVAL, "stack desc: offload must be 0 or 1");
   if (d->offload && !d->checkpoint) return fail(CEPHALO_EINVAL, "stack desc: offload needs checkpoint = 1 (only boundary activations are offloaded)");
@@ -310,7 +337,9 @@ int run_stack(const cephalo_stack_desc& d, const void* Pv, const int* ids, const
   const int S = ld.seq, H = ld.hidden, V = d.vocab, NL = d.layers, l = b / m;
   const int n = b * S, Tm = m * S;
   const int64_t PL = param_offsets(ld).total;
-  const int64_t o_wte = 0, o_wpe = (int64_t)V * H, o_layers = o_wpe + (int64_t)S * H, o_lnf = o_layers + NL * PL;
+  const StackOffsets SO = stack_offsets(d);
+  const int64_t o_wte = SO.wte, o_wpe = SO.wpe, o_layers = SO.layers, o_lnf = SO.normf, o_head = SO.head;
+  const bool rms = is_llama(ld);
   const StackLayout L = stack_layout(d, b, m);
   const SaveLayout SL = save_layout(ld, b);
   const ScratchLayout WL = scratch_layout(ld, m, b);
@@ -330,7 +359,7 @@ int run_stack(const cephalo_stack_desc& d, const void* Pv, const int* ids, const
 
   // ---- forward
   for (int j = 0; j < l; ++j) {
-    embed_fwd_kernel<T><<<(Tm + 3) / 4, kThreads, 0, s>>>(ids + (size_t)j * Tm, P + o_wte, P + o_wpe, X.out(0, j), Tm, S, H, V);
+    embed_fwd_kernel<T><<<(Tm + 3) / 4, kThreads, 0, s>>>(ids + (size_t)j * Tm, P + o_wte, SO.positions ? P + o_wpe : (const T*)nullptr, X.out(0, j), Tm, S, H, V);
     CEPHALO_CHECK_LAUNCH("embed_fwd");
     X.out_done(0, j);
   }
@@ -355,37 +384,37 @@ int run_stack(const cephalo_stack_desc& d, const void* Pv, const int* ids, const
   T* dxl_cur = at<T>(ws, L.dxal); T* dxl_nxt = at<T>(ws, L.dxbl);
   const float coef = scale / (float)n;
   const int nb = ln_bwd_blocks(Tm);
-  TRY(prepare_head_weights<T>(P + o_wte, at<T>(ws, L.wteT), V, H, L.ldv, s));
+  TRY(prepare_head_weights<T>(P + o_head, at<T>(ws, L.wteT), V, H, L.ldv, s));
   X.prefetch(NL, 0, l);
   for (int j = 0; j < l; ++j) {
     const size_t t0 = (size_t)j * Tm;
     const float* xL = X.in(NL, j, l);
     X.prefetch(NL, j + 1, l);
-    TRY(launch_ln_fwd<T>(xL, P + o_lnf, P + o_lnf + H, uf + t0 * H, meanf + t0, rstdf + t0, Tm, H, ld.ln_eps, s));
+    TRY(launch_ln_fwd<T>(xL, P + o_lnf, rms ? (const T*)nullptr : P + o_lnf + H, uf + t0 * H, meanf + t0, rstdf + t0, Tm, H, ld.ln_eps, s, rms));
     T* dlg = dlogits + t0 * L.ldv;
     {
-      GemmArgs<T> a = linear_fwd<T>(uf + t0 * H, P + o_wte, Tm, V, H);
+      GemmArgs<T> a = linear_fwd<T>(uf + t0 * H, P + o_head, Tm, V, H);
       a.epi = EPI_NONE; a.Cf = logits; a.ldc = L.ldv;
       TRY(gemm<T>(a, s));
     }
     cross_entropy_kernel<T><<<Tm, kThreads, 0, s>>>(logits, dlg, targets + t0, at<float>(ws, L.loss) + t0, V, L.ldv, coef);
     CEPHALO_CHECK_LAUNCH("cross_entropy");
     {
-      GemmArgs<T> a = head_dgrad_args<T>(dlg, P + o_wte, at<T>(ws, L.wteT), Tm, V, H, L.ldv);   // duf = dlogits wte
+      GemmArgs<T> a = head_dgrad_args<T>(dlg, P + o_head, at<T>(ws, L.wteT), Tm, V, H, L.ldv);   // duf = dlogits W_head
       a.epi = EPI_NONE; a.Cf = duf;
       TRY(gemm<T>(a, s));
     }
     TRY(launch_ln_bwd<T>(duf, xL, meanf + t0, rstdf + t0, P + o_lnf, (const float*)nullptr, dx_cur + t0 * H,
-                         lowp_out<T>(dxl_cur + t0 * H), lnf_g + (size_t)j * nb * H, lnf_b + (size_t)j * nb * H, Tm, H, s));
+                         lowp_out<T>(dxl_cur + t0 * H), lnf_g + (size_t)j * nb * H, lnf_b + (size_t)j * nb * H, Tm, H, s, rms));
     X.in_done();
   }
   mean_kernel<<<1, kThreads, 0, s>>>(at<float>(ws, L.loss), n, loss_out);
   CEPHALO_CHECK_LAUNCH("mean_loss");
   {
     Work<T> w = work_at<T>(scratch, WL, ld, 0, 0, m);
-    TRY(wgrad<T>(dlogits, uf, n, V, H, G + o_wte, 1.0f, 0, (float*)nullptr, s, L.ldv));        // LM-head part of d wte, whole share
+    TRY(wgrad<T>(dlogits, uf, n, V, H, G + o_head, 1.0f, 0, (float*)nullptr, s, L.ldv));       // the head's gradient (tied: the head's part of d wte), whole share
     TRY(launch_reduce_partials(lnf_g, l * nb, H, G + o_lnf, 1.0f, 0, w.col_part, w.col_part_bytes, s));
-    TRY(launch_reduce_partials(lnf_b, l * nb, H, G + o_lnf + H, 1.0f, 0, w.col_part, w.col_part_bytes, s));
+    if (!rms) TRY(launch_reduce_partials(lnf_b, l * nb, H, G + o_lnf + H, 1.0f, 0, w.col_part, w.col_part_bytes, s));
   }
   // ---- backward through the layers
   for (int li = NL - 1; li >= 0; --li) {
@@ -410,8 +439,15 @@ int run_stack(const cephalo_stack_desc& d, const void* Pv, const int* ids, const
     { T* t = dxl_cur; dxl_cur = dxl_nxt; dxl_nxt = t; }
   }
   // ---- embeddings
-  wpe_bwd_kernel<<<(int)(((int64_t)S * H / 4 + kThreads - 1) / kThreads), kThreads, 0, s>>>(dx_cur, G + o_wpe, b, S, H);
-  CEPHALO_CHECK_LAUNCH("wpe_bwd");
+  if (SO.positions) {
+    wpe_bwd_kernel<<<(int)(((int64_t)S * H / 4 + kThreads - 1) / kThreads), kThreads, 0, s>>>(dx_cur, G + o_wpe, b, S, H);
+    CEPHALO_CHECK_LAUNCH("wpe_bwd");
+  }
+  if (!SO.tied) {      // the rows of d wte do not hold a head's part: they start at zero (rows of unused ids stay there)
+    const int64_t n4 = (int64_t)V * H / 4;
+    zero_kernel<<<(int)((n4 + kThreads - 1) / kThreads), kThreads, 0, s>>>(G + o_wte, n4);
+    CEPHALO_CHECK_LAUNCH("zero_wte_grad");
+  }
   int* keys_in = at<int>(ws, L.keys); int* vals_in = keys_in + n; int* keys_out = vals_in + n; int* vals_out = keys_out + n;
   sort_keys_kernel<<<(n + kThreads - 1) / kThreads, kThreads, 0, s>>>(ids, keys_in, vals_in, n, V);
   size_t tmp = L.sort_tmp_bytes;
@@ -431,8 +467,15 @@ using namespace cephalo;
 extern "C" int64_t cephalo_stack_param_count(const cephalo_stack_desc* d) {
   const int rc = check_stack(d);
   if (rc != CEPHALO_OK) return rc;
-  const int64_t H = d->layer.hidden;
-  return (int64_t)d->vocab * H + (int64_t)d->layer.seq * H + d->layers * param_offsets(d->layer).total + 2 * H;
+  return stack_offsets(*d).total;
+}
+
+extern "C" int cephalo_stack_param_offsets(const cephalo_stack_desc* d, int64_t* offsets) {
+  TRY(check_stack(d));
+  if (!offsets) return fail(CEPHALO_EINVAL, "stack_param_offsets: null output");
+  const StackOffsets o = stack_offsets(*d);
+  offsets[0] = o.wte; offsets[1] = o.wpe; offsets[2] = o.layers; offsets[3] = o.normf; offsets[4] = o.head;
+  return CEPHALO_OK;
 }
 
 extern "C" int cephalo_stack_workspace_bytes(const cephalo_stack_desc* d, int32_t batch_share, int32_t micro_batch, size_t* bytes) {

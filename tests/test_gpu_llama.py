@@ -10,8 +10,10 @@ import paper_2411_01075_amd as C
 from oracle import llama as ol
 from oracle.precision import round_to_bf16
 from tests.harness import TOL, assert_close, tdtype
+from tests.harness import rel_errors as Hn_rel
 from workloads.configs import CONFIGS
-from workloads.generate import draw_activations, draw_layer_params
+from workloads.generate import draw_activations, draw_layer_params, draw_stack_params, draw_token_ids
+from tests.test_gpu_stack import run_gpu as run_stack_gpu
 
 pytestmark = pytest.mark.gpu
 
@@ -77,16 +79,13 @@ def test_llama_layer_matches_oracle(case, via_share_call):
     assert np.isfinite(G).all()                                   # every element was written
 
 
-def test_llama_is_reproducible_and_stack_refuses_it():
+def test_llama_is_reproducible():
     cfg = CASES["bf16_mini"]
     params = draw_layer_params(cfg, perturbed=True)
     x, dy = draw_activations(cfg)
     a = run_gpu(cfg, params, x, dy, 1.0, True)
     b = run_gpu(cfg, params, x, dy, 1.0, True)
     assert np.array_equal(a[0], b[0]) and np.array_equal(a[1], b[1]) and np.array_equal(a[2], b[2])
-    sd = C.StackDesc(a[3], 2, 101, 0, 0)
-    with pytest.raises(C.CephaloError):
-        C.cephalo_stack_param_count(sd)
 
 
 def test_llama_7b_layer_full_size():
@@ -108,3 +107,66 @@ def test_llama_7b_layer_full_size():
     for name, o in zip(C.LLAMA_TENSOR_NAMES, offs):
         if name is not None:
             assert_close("grad " + name, G[o:o + rg[name].size], rg[name].reshape(-1), "bf16")
+
+
+# ---- the Llama-style stack (token embedding, layers, final RMSNorm, untied head) through the stack entry points
+
+STACKS = {
+    "bf16_mini": CONFIGS["lstackmini"],                                   # V = 1031, F = 688, S = 136: ragged everywhere
+    "bf16_m1_d128": dataclasses.replace(CONFIGS["lstackmini"], heads=2, micro_batch=1, n_micro=3, seq=200, layers=3),
+    "f32_tiny": dataclasses.replace(CONFIGS["lstackmini"], dtype="f32", hidden=64, heads=2, mlp=96, seq=24, vocab=101,
+                                    micro_batch=1, n_micro=3),
+}
+
+
+def stack_to64(params, bf16):
+    f = (lambda a: round_to_bf16(a)) if bf16 else (lambda a: a.astype(np.float64))
+    return {"wte": f(params["wte"]), "normf_g": f(params["normf_g"]), "w_head": f(params["w_head"]),
+            "layers": [{k: f(v) for k, v in lp.items()} for lp in params["layers"]]}
+
+
+@pytest.mark.parametrize("case", list(STACKS))
+def test_llama_stack_step_matches_oracle(case):
+    cfg = STACKS[case]
+    print("llama stack", case, flush=True)
+    params = draw_stack_params(cfg, perturbed=True)
+    ids, tgt = draw_token_ids(cfg)
+    ids[0, :5] = ids[0, 0]                      # repeated tokens in one sample
+    ids[-1, -3:] = ids[0, 0]                    # and across samples / micro-batches
+    scale = 1.5
+    loss, G, sd = run_stack_gpu(cfg, params, ids, tgt, scale)
+    ref_loss, ref = ol.stack_step(stack_to64(params, cfg.dtype == "bf16"), ids, tgt, cfg.heads, cfg.causal, cfg.micro_batch, scale=scale)
+    tmax, tmean = TOL[cfg.dtype]
+    depth = float(cfg.layers) ** 0.5 if cfg.dtype == "bf16" else 1.0      # independent roundings of chained layers add in quadrature
+    assert abs(loss - ref_loss) <= (2e-3 if cfg.dtype == "bf16" else 1e-5) * abs(ref_loss), (loss, ref_loss)
+    assert np.isfinite(G).all()                                          # every element was written
+    V, H = cfg.vocab, cfg.hidden
+    PL = C.cephalo_layer_param_count(sd.layer)
+    o_wte, o_wpe, o_layers, o_norm, o_head = C.cephalo_stack_param_offsets(sd)
+    assert (o_wte, o_wpe, o_layers, o_norm, o_head) == (0, V * H, V * H, V * H + cfg.layers * PL, V * H + cfg.layers * PL + H)
+    assert C.cephalo_stack_param_count(sd) == 2 * V * H + cfg.layers * PL + H
+    checks = [("wte", G[:V * H], ref["wte"]), ("normf_g", G[o_norm:o_norm + H], ref["normf_g"]), ("w_head", G[o_head:], ref["w_head"])]
+    offs = C.cephalo_layer_param_offsets(sd.layer)
+    for li in range(cfg.layers):
+        for name, o in zip(C.LLAMA_TENSOR_NAMES, offs):
+            if name is not None:
+                n = ref["layers"][li][name].size
+                checks.append(("L%d.%s" % (li, name), G[o_layers + li * PL + o:o_layers + li * PL + o + n], ref["layers"][li][name]))
+    worst = (0, "")
+    for name, got, want in checks:
+        mx, mean = Hn_rel(got, want.reshape(-1))
+        worst = max(worst, (mean, name))
+        assert mx <= tmax * depth and mean <= tmean * depth, "%s: max-rel %.3e mean-rel %.3e" % (name, mx, mean)
+    unused = np.setdiff1d(np.arange(V), ids.reshape(-1))
+    assert unused.size > 0 and np.all(G[:V * H].reshape(V, H)[unused] == 0.0)      # ids that do not occur: exactly zero rows
+    print("loss", loss, ref_loss, "worst mean-rel", worst, flush=True)
+
+
+def test_llama_stack_checkpointing_and_offload_are_bit_identical():
+    cfg = STACKS["bf16_m1_d128"]
+    params = draw_stack_params(cfg, perturbed=True)
+    ids, tgt = draw_token_ids(cfg)
+    a = run_stack_gpu(cfg, params, ids, tgt, 1.25)
+    b = run_stack_gpu(cfg, params, ids, tgt, 1.25, checkpoint=True)
+    c = run_stack_gpu(cfg, params, ids, tgt, 1.25, checkpoint=True, offload=True)
+    assert a[0] == b[0] == c[0] and np.array_equal(a[1], b[1]) and np.array_equal(a[1], c[1])

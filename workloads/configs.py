@@ -58,6 +58,12 @@ CONFIGS = {
     #  than the residual stream they are added to, which no trained network of this width looks like)
     "l7b": LayerConfig("l7b", 4096, 32, 11008, 2048, True, 1, 4, "bf16", seed=1006, shard_rule="third_odd", kind="llama",
                        init_std=0.01),
+    # TinyLlama-shaped stack (the paper's model table: 22 layers, H 2048, 32 heads; F 5632 and a 32000-entry vocabulary
+    # are that model family's): the Llama-style counterpart of c5
+    "ltiny": LayerConfig("ltiny", 2048, 32, 5632, 2048, True, 2, 6, "bf16", layers=22, vocab=32000, seed=1008,
+                         shard_rule="frac29_seeded", kind="llama"),
+    "lstackmini": LayerConfig("lstackmini", 256, 4, 688, 136, True, 2, 2, "bf16", layers=2, vocab=1031, seed=1108,
+                              shard_rule="frac:37:41", kind="llama"),
     "lmini": LayerConfig("lmini", 256, 4, 688, 136, True, 2, 2, "bf16", seed=1106, shard_rule="frac:37:41", kind="llama"),
     # ViT-Large-shaped encoder layer: 197 tokens per image, non-causal (the GPT-style layer form)
     "vitl": LayerConfig("vitl", 1024, 16, 4096, 197, False, 8, 2, "bf16", seed=1007, shard_rule="frac:50:23"),

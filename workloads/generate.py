@@ -74,8 +74,19 @@ def draw_layer_params(cfg, layer_index=0, perturbed=False):
 
 
 def draw_stack_params(cfg, perturbed=False):
-    """Parameters of a full stack: wte [V,H], wpe [S,H], per-layer dicts, final LN."""
+    """Parameters of a full stack: wte [V,H], wpe [S,H], per-layer dicts, final LN (Llama-style: wte, layers, final
+    RMSNorm gamma, w_head [V,H])."""
     H = cfg.hidden
+    if getattr(cfg, "kind", "gpt") == "llama":          # token embedding, layers, final RMSNorm, a head of its own
+        out = {
+            "wte": _normal(cfg.seed, "wte", (cfg.vocab, H), 0.02),
+            "layers": [draw_layer_params(cfg, i, perturbed) for i in range(cfg.layers)],
+            "normf_g": np.ones((H,), dtype=np.float32),
+            "w_head": _normal(cfg.seed, "w_head", (cfg.vocab, H), 0.02),
+        }
+        if perturbed:
+            out["normf_g"] += _normal(cfg.seed, "normf_g", (H,), 0.02)
+        return out
     out = {
         "wte": _normal(cfg.seed, "wte", (cfg.vocab, H), 0.02),
         "wpe": _normal(cfg.seed, "wpe", (cfg.seq, H), 0.02),
