@@ -172,7 +172,8 @@ def main():
         torch.cuda.synchronize()
         return e0.elapsed_time(e1) * 1e-3 / iters
 
-    roofline = {"kernel": "none (launch-latency bound workload)", "bound": "alu", "achieved": None, "peak": 157.3,
+    roofline = {"kernel": "not broken out (the GEMM legs are timed for the bf16 GPT-style workloads; see whole_step_model_tflops)",
+                "bound": "mfma" if bf16 else "alu", "achieved": None, "peak": PEAK_BF16_TFLOPS if bf16 else 157.3,
                 "unit": "TFLOP/s", "frac": None, "traffic": None}
     T, H, F, V = cfg.tokens_per_micro, cfg.hidden, cfg.mlp, cfg.vocab
     n_tok = cfg.tokens_per_step
@@ -265,7 +266,8 @@ def main():
         cpu = cpu_baseline(cfg, params, flat32_h, m_h, v_h, off, ln, lr,
                            None if stack else (x_h, dy_h), (ids_h, tgt_h) if stack else None)
 
-    what = ("%d layers + embeddings + tied LM head (V=%d)" % (cfg.layers, V)) if stack else "1 layer"
+    what = ("%d %s layers + embeddings + %s LM head (V=%d)" % (cfg.layers, "Llama-style" if cfg.kind == "llama" else "GPT-style",
+                                                               "untied" if cfg.kind == "llama" else "tied", V)) if stack else "1 layer"
     out = {
         "metric": "tokens/s per fwd+bwd+shard-Adam step on 1 MI355X",
         "value": round(tokens_per_s, 1), "unit": "tokens/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
