@@ -59,6 +59,8 @@ def main():
     ap.add_argument("--no-legs", action="store_true", help="skip the per-kernel legs (whole step only)")
     ap.add_argument("--checkpoint", action="store_true",
                     help="stacks only: layer-boundary activation checkpointing with recomputation in the backward (one extra forward)")
+    ap.add_argument("--single-stream", action="store_true",
+                    help="stacks only: one micro-batch at a time on one stream (the default runs two micro-batches side by side on two streams)")
     ap.add_argument("--offload", action="store_true",
                     help="stacks only, implies --checkpoint: the boundary activations live in pinned host memory and move on a second stream")
     args = ap.parse_args()
@@ -83,7 +85,8 @@ def main():
 
     # ---- seeded inputs, generated on the host, then made resident in HBM
     if stack:
-        sd = C.stack_desc_from_config(cfg, checkpoint=args.checkpoint or args.offload, offload=args.offload)
+        interleave = not (args.single_stream or args.offload)
+        sd = C.stack_desc_from_config(cfg, checkpoint=args.checkpoint or args.offload, offload=args.offload, interleave=interleave)
         desc = sd.layer
         P = C.cephalo_stack_param_count(sd)
         params = draw_stack_params(cfg)
@@ -119,9 +122,14 @@ def main():
             host_area = torch.empty(C.cephalo_stack_host_bytes(sd, b, m) // 4, dtype=torch.float32).pin_memory()
             copy_in, copy_out = torch.cuda.Stream(), torch.cuda.Stream()
 
+        if interleave:
+            side = torch.cuda.Stream()
+
         def step(t):
             if args.offload:
                 C.cephalo_stack_step_offload(sd, pcomp, ids, tgt, b, m, G, 1.0, loss, ws, host_area, copy_in, copy_out)
+            elif interleave:
+                C.cephalo_stack_step_interleaved(sd, pcomp, ids, tgt, b, m, G, 1.0, loss, ws, side)
             else:
                 C.cephalo_stack_step(sd, pcomp, ids, tgt, b, m, G, 1.0, loss, ws)
             C.cephalo_shard_adam(p32, G, mom, var, plow, P, off, ln, lr, 0.9, 0.999, 1e-8, t)
@@ -153,6 +161,7 @@ def main():
         extras["loss"] = round(float(loss.item()), 4)
         extras["activation_checkpointing"] = bool(args.checkpoint or args.offload)
         extras["activation_offload"] = bool(args.offload)
+        extras["micro_batches_in_flight"] = 2 if interleave else 1
         if args.offload:
             extras["host_area_GB"] = round(host_area.numel() * 4 / 1e9, 2)
         extras["workspace_GB"] = round(ws.numel() / 1e9, 2)

@@ -244,6 +244,12 @@ typedef struct cephalo_stack_desc {
                           backward for the recomputation; the device holds four micro-batches of them.  Same results bit
                           for bit.  (The gradient of the residual stream, two [b*S, H] buffers, stays on the device; the
                           paper moves that to the host too.)  Goes with cephalo_stack_step_offload. */
+  int32_t interleave;  /* 0, or 1 (not with offload): two micro-batches are in flight at once, micro-batch j on stream j mod 2
+                          (the caller's compute stream and a side stream), so that the bandwidth-bound kernels of one
+                          overlap the matrix-core kernels of the other and GEMMs with few output tiles share the compute
+                          units.  The order of a micro-batch's own kernels, and every reduction order, are unchanged: same
+                          results bit for bit.  The work area holds the per-micro-batch buffers twice.  Goes with
+                          cephalo_stack_step_interleaved. */
 } cephalo_stack_desc;
 
 /* V*H + S*H + L*P_layer + 2H (GPT-style) or 2*V*H + L*P_layer + H (Llama-style); negative on a bad desc. */
@@ -289,6 +295,16 @@ int cephalo_stack_step_offload(const cephalo_stack_desc* desc, const void* flat_
                                float* flat_grad, float grad_scale, float* loss,
                                void* workspace, size_t workspace_bytes, void* host_area, size_t host_bytes,
                                void* stream, void* copy_in_stream, void* copy_out_stream);
+
+/* The same step for a desc with interleave = 1 (Sec. 3.2's layered order leaves the micro-batches of a layer independent
+ * of each other; here two of them run side by side).  side_stream: a second stream of the same device, other than
+ * `stream`, at the default priority.  The call joins the streams before it returns: work enqueued on `stream`
+ * afterwards runs after the whole step; the side stream may be reused at once.  Arguments otherwise as for
+ * cephalo_stack_step; workspace size from cephalo_stack_workspace_bytes with the same desc. */
+int cephalo_stack_step_interleaved(const cephalo_stack_desc* desc, const void* flat_param,
+                                   const int32_t* ids, const int32_t* targets, int32_t batch_share, int32_t micro_batch,
+                                   float* flat_grad, float grad_scale, float* loss,
+                                   void* workspace, size_t workspace_bytes, void* stream, void* side_stream);
 
 /* ---------------------------------------------------------------------------------------
  * Planning on the host (no device involved): how the global batch and the training state are divided over the

@@ -41,11 +41,12 @@ def desc_from_config(cfg):
 
 class StackDesc(ctypes.Structure):
     _fields_ = [("layer", LayerDesc), ("layers", ctypes.c_int32), ("vocab", ctypes.c_int32), ("checkpoint", ctypes.c_int32),
-                ("offload", ctypes.c_int32)]
+                ("offload", ctypes.c_int32), ("interleave", ctypes.c_int32)]
 
 
-def stack_desc_from_config(cfg, checkpoint=False, offload=False):
-    return StackDesc(desc_from_config(cfg), int(cfg.layers), int(cfg.vocab), int(bool(checkpoint)), int(bool(offload)))
+def stack_desc_from_config(cfg, checkpoint=False, offload=False, interleave=False):
+    return StackDesc(desc_from_config(cfg), int(cfg.layers), int(cfg.vocab), int(bool(checkpoint)), int(bool(offload)),
+                     int(bool(interleave)))
 
 
 class GpuPerf(ctypes.Structure):
@@ -81,6 +82,7 @@ SIGNATURES = {
     "cephalo_stack_param_offsets": (ctypes.c_int, [ctypes.POINTER(StackDesc), ctypes.POINTER(_i64)]),
     "cephalo_stack_workspace_bytes": (ctypes.c_int, [ctypes.POINTER(StackDesc), _i32, _i32, ctypes.POINTER(_sz)]),
     "cephalo_stack_step": (ctypes.c_int, [ctypes.POINTER(StackDesc), _vp, _vp, _vp, _i32, _i32, _vp, _f32, _vp, _vp, _sz, _vp]),
+    "cephalo_stack_step_interleaved": (ctypes.c_int, [ctypes.POINTER(StackDesc), _vp, _vp, _vp, _i32, _i32, _vp, _f32, _vp, _vp, _sz, _vp, _vp]),
     "cephalo_stack_host_bytes": (ctypes.c_int, [ctypes.POINTER(StackDesc), _i32, _i32, ctypes.POINTER(_sz)]),
     "cephalo_stack_step_offload": (ctypes.c_int, [ctypes.POINTER(StackDesc), _vp, _vp, _vp, _i32, _i32, _vp, _f32, _vp, _vp, _sz,
                                                   _vp, _sz, _vp, _vp, _vp]),
@@ -290,6 +292,13 @@ def cephalo_stack_step(sdesc, flat_param, ids, targets, batch_share, micro_batch
     _check(lib().cephalo_stack_step(ctypes.byref(sdesc), _ptr(flat_param), _ptr(ids), _ptr(targets), batch_share, micro_batch,
                                     _ptr(flat_grad), grad_scale, _ptr(loss), _ptr(workspace),
                                     workspace.numel() * workspace.element_size(), _stream(stream)))
+
+
+def cephalo_stack_step_interleaved(sdesc, flat_param, ids, targets, batch_share, micro_batch, flat_grad, grad_scale, loss, workspace,
+                                   side_stream, stream=None):
+    _check(lib().cephalo_stack_step_interleaved(ctypes.byref(sdesc), _ptr(flat_param), _ptr(ids), _ptr(targets), batch_share, micro_batch,
+                                                _ptr(flat_grad), grad_scale, _ptr(loss), _ptr(workspace),
+                                                workspace.numel() * workspace.element_size(), _stream(stream), _stream(side_stream)))
 
 
 def cephalo_stack_host_bytes(sdesc, batch_share, micro_batch):

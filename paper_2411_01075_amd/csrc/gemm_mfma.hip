@@ -487,6 +487,8 @@ int launch_cfg(const GemmArgs<bf16>& a, hipStream_t s) {
   return launch_kernel<gemm_mfma_kernel<BM, BN, WGM, WGN, AK, BKF, EPI, NS>>(a, BM, BN, 64 * WGM * WGN, lds, s);
 }
 
+thread_local int side_by_side = 1;     // kernels the caller runs at once (GemmSideBySide)
+
 template <bool AK, bool BKF, int EPI>
 int launch_tiles(const GemmArgs<bf16>& a, hipStream_t s) {
   static const int force = getenv("CEPHALO_GEMM_CFG") ? atoi(getenv("CEPHALO_GEMM_CFG")) : 0;   // tuning aid
@@ -494,9 +496,10 @@ int launch_tiles(const GemmArgs<bf16>& a, hipStream_t s) {
   // units fill, times the rate its main loop reaches relative to the 256 x 256 tile (measured: bigger tiles
   // move fewer LDS and L2 bytes per MFMA).
   const int nsplit = (EPI == EPI_GRAD && a.splits > 1 && a.part) ? a.splits : 1;
+  const double cus = 256.0 / side_by_side;        // compute units this launch can count on
   auto fill = [&](int bm, int bn) {
     const double t = (double)((a.M + bm - 1) / bm) * ((a.N + bn - 1) / bn) * nsplit;
-    return t / (256.0 * (double)(int64_t)((t + 255) / 256));
+    return t / (cus * (double)(int64_t)((t + cus - 1) / cus));
   };
   int cfg = force;
   // 256 x 128 tiles run three LDS stages (they fit, and long contractions over few tiles gain a quarter from the
@@ -538,6 +541,9 @@ int general(const GemmArgs<bf16>& a, hipStream_t s) {
 }
 }  // namespace
 int64_t gemm_general_count() { return general_count.load(std::memory_order_relaxed); }
+GemmSideBySide::GemmSideBySide(int kernels) : before(side_by_side) { side_by_side = kernels < 1 ? 1 : kernels; }
+GemmSideBySide::~GemmSideBySide() { side_by_side = before; }
+void GemmSideBySide::now(int kernels) { side_by_side = kernels < 1 ? 1 : kernels; }
 
 int launch_gemm_mfma(const GemmArgs<bf16>& a, hipStream_t s) {
   if (a.M <= 0 || a.N <= 0 || a.K <= 0) return fail(CEPHALO_EINVAL, "gemm: empty problem %dx%dx%d", a.M, a.N, a.K);

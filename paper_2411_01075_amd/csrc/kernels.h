@@ -130,6 +130,14 @@ int gemm_grad_splits(int M, int N, int K);
 
 template <typename T> int launch_gemm_simple(const GemmArgs<T>& a, hipStream_t s);
 int launch_gemm_mfma(const GemmArgs<bf16>& a, hipStream_t s);  // bf16 operands, MFMA, fp32 accumulate
+// While one of these is alive on a thread, that thread's GEMM launches choose their tiles for 256 / `kernels` compute
+// units: the caller runs that many kernels side by side on different streams (results do not depend on the choice).
+struct GemmSideBySide {
+  explicit GemmSideBySide(int kernels);
+  ~GemmSideBySide();
+  void now(int kernels);       // change the number for the launches that follow
+  int before;
+};
 int64_t gemm_general_count();   // calls of launch_gemm_mfma that ended in launch_gemm_simple
 
 // ---------------------------------------------------------------------------------------

@@ -82,6 +82,7 @@ struct SaveLayout {
 // activation type are kept for `span` samples; the rest is per micro-batch of m samples.
 struct ScratchLayout {
   size_t dz, dx1, dx1l, dyl, dqkv, du2, dO, du, dvec, wT, wg_part, ln_part, col_part, col_part_bytes, total;
+  size_t slot_each; // bytes of one slot's du2, dO, du, dvec (slot k's copies lie k * slot_each further on)
   size_t ln_rows;   // rows of each of the four LayerNorm partial arrays (ln2.gamma, ln2.beta, ln1.gamma, ln1.beta)
 };
 
@@ -106,7 +107,8 @@ SaveLayout save_layout(const cephalo_layer_desc& d, int n) {
   return L;
 }
 
-ScratchLayout scratch_layout(const cephalo_layer_desc& d, int m, int span) {
+// slots: how many micro-batches may be in their backward at once (each needs its own per-micro-batch buffers)
+ScratchLayout scratch_layout(const cephalo_layer_desc& d, int m, int span, int slots = 1) {
   const size_t es = d.dtype == CEPHALO_F32 ? 4 : 2;
   const size_t Tm = (size_t)m * d.seq, Ts = (size_t)span * d.seq, H = d.hidden, F = d.mlp;
   ScratchLayout L;
@@ -118,10 +120,12 @@ ScratchLayout scratch_layout(const cephalo_layer_desc& d, int m, int span) {
   L.dx1l = es == 4 ? L.dx1 : take(Ts * H * es);
   L.dyl = es == 4 ? 0 : take(Ts * H * es);
   L.dqkv = take(Ts * 3 * H * es);
+  L.slot_each = align_up(Tm * H * 4) + align_up(Tm * H * es) + align_up(Tm * H * 4) + align_up((size_t)m * d.heads * d.seq * 4);
   L.du2 = take(Tm * H * 4);        // gradients entering the LayerNorm backward: fp32
   L.dO = take(Tm * H * es);
   L.du = take(Tm * H * 4);
   L.dvec = take((size_t)m * d.heads * d.seq * 4);
+  if (slots > 1) take((size_t)(slots - 1) * L.slot_each);      // the same four again per further slot
   L.wT = es == 4 ? 0 : take((size_t)param_offsets(d).total * es);   // the four weight matrices transposed, at their flat-layout offsets
   L.wg_part = p;                    // partial weight gradients of a split token axis (largest of the four projections)
   if (es != 4) {
@@ -272,13 +276,14 @@ template <typename T> struct Work {
   float *wg_part;
 };
 template <typename T>
-Work<T> work_at(void* base, const ScratchLayout& W, const cephalo_layer_desc& d, int sample0, int mb_index, int m) {
+Work<T> work_at(void* base, const ScratchLayout& W, const cephalo_layer_desc& d, int sample0, int mb_index, int m, int slot = 0) {
   const size_t t0 = (size_t)sample0 * d.seq, H = d.hidden, F = d.mlp;
   Work<T> w;
   w.dz = at<T>(base, W.dz) + t0 * (size_t)ff1_width(d); w.dx1 = at<float>(base, W.dx1) + t0 * H; w.dx1l = at<T>(base, W.dx1l) + t0 * H;
   w.dyl = at<T>(base, W.dyl) + t0 * H; w.dqkv = at<T>(base, W.dqkv) + t0 * 3 * H;
-  w.du2 = at<float>(base, W.du2); w.dO = at<T>(base, W.dO); w.du = at<float>(base, W.du); w.wT = at<T>(base, W.wT);
-  w.dvec = at<float>(base, W.dvec);
+  const size_t so = (size_t)slot * W.slot_each;
+  w.du2 = at<float>(base, W.du2 + so); w.dO = at<T>(base, W.dO + so); w.du = at<float>(base, W.du + so); w.wT = at<T>(base, W.wT);
+  w.dvec = at<float>(base, W.dvec + so);
   float* ln = at<float>(base, W.ln_part);
   const size_t r0 = (size_t)mb_index * ln_bwd_blocks(m * d.seq) * H, arr = W.ln_rows * H;
   w.ln2_g = ln + r0; w.ln2_b = ln + arr + r0; w.ln1_g = ln + 2 * arr + r0; w.ln1_b = ln + 3 * arr + r0;

@@ -203,6 +203,8 @@ int check_stack(const cephalo_stack_desc* d) {
   if (d->checkpoint != 0 && d->checkpoint != 1) return fail(CEPHALO_EINVAL, "stack desc: checkpoint must be 0 or 1");
   if (d->offload != 0 && d->offload != 1) return fail(CEPHALO_EINVAL, "stack desc: offload must be 0 or 1");
   if (d->offload && !d->checkpoint) return fail(CEPHALO_EINVAL, "stack desc: offload needs checkpoint = 1 (only boundary activations are offloaded)");
+  if (d->interleave != 0 && d->interleave != 1) return fail(CEPHALO_EINVAL, "stack desc: interleave must be 0 or 1");
+  if (d->interleave && d->offload) return fail(CEPHALO_EUNSUPPORTED, "stack desc: interleave and offload do not go together");
   return CEPHALO_OK;
 }
 
@@ -233,15 +235,15 @@ StackLayout stack_layout(const cephalo_stack_desc& d, int b, int m) {
   // layer-boundary activations, the fp32 residual stream: all of them, or (offload) two micro-batches coming in from the
   // host and two going out; with checkpointing also one micro-batch where the recomputed layer output is dropped
   L.xs = take(d.offload ? 4 * Tm * H * 4 : (size_t)(d.layers + 1) * n * H * 4);
-  L.xdump = d.checkpoint ? take(Tm * H * 4) : 0;
+  L.xdump = d.checkpoint ? take((d.interleave ? 2 : 1) * Tm * H * 4) : 0;
   L.save_each = align_up(save_layout(ld, b).total);
   L.saves = take((size_t)(d.checkpoint ? 1 : d.layers) * L.save_each);   // checkpointing: one layer's internals at a time
-  L.scratch = take(scratch_layout(ld, m, b).total);
+  L.scratch = take(scratch_layout(ld, m, b, d.interleave ? 2 : 1).total);
   L.dxa = take(n * H * 4); L.dxb = take(n * H * 4);     // gradient of the residual stream, ping-pong between layers
   L.dxal = es == 4 ? L.dxa : take(n * H * es); L.dxbl = es == 4 ? L.dxb : take(n * H * es);   // and its copy in the activation type
   L.uf = take(n * H * es); L.meanf = take(n * 4); L.rstdf = take(n * 4);
-  L.duf = take(Tm * H * 4);
-  L.logits = take(Tm * (size_t)L.ldv * 4);        // one micro-batch of fp32 logits, reused
+  L.duf = take((d.interleave ? 2 : 1) * Tm * H * 4);
+  L.logits = take((d.interleave ? 2 : 1) * Tm * (size_t)L.ldv * 4);   // one micro-batch of fp32 logits, reused (interleave: one per stream)
   L.dlogits = take(n * (size_t)L.ldv * es);       // their gradient for the whole share (an operand of the weight gradient)
   L.wteT = es == 4 ? 0 : take(H * (size_t)L.ldv * es);   // wte^T [H, ldv] for the input gradient of the LM head
   L.loss = take(n * 4);
@@ -329,9 +331,45 @@ struct Boundary {
   }
 };
 
+// The two compute streams of an interleaved step.  fork: the side stream continues from where the main stream is;
+// join: the main stream continues only after the side stream's work so far.  Without interleave both do nothing.
+struct Streams {
+  hipStream_t main = nullptr, side = nullptr;
+  bool on = false;
+  hipEvent_t forked, joined;
+  int err = CEPHALO_OK;
+  void check(hipError_t e, const char* what) {
+    if (e != hipSuccess && err == CEPHALO_OK) err = fail(CEPHALO_EHIP, "stack_step (interleave): %s: %s", what, hipGetErrorString(e));
+  }
+  int open() {
+    if (!on) return CEPHALO_OK;
+    check(hipEventCreateWithFlags(&forked, hipEventDisableTiming), "event");
+    check(hipEventCreateWithFlags(&joined, hipEventDisableTiming), "event");
+    return err;
+  }
+  void fork() {
+    if (!on) return;
+    check(hipEventRecord(forked, main), "record");
+    check(hipStreamWaitEvent(side, forked, 0), "wait");
+  }
+  void join() {
+    if (!on) return;
+    check(hipEventRecord(joined, side), "record");
+    check(hipStreamWaitEvent(main, joined, 0), "wait");
+  }
+  int close() {          // the call ends joined: whoever waits for the main stream has waited for everything
+    if (!on) return CEPHALO_OK;
+    join();
+    check(hipEventDestroy(forked), "event");
+    check(hipEventDestroy(joined), "event");
+    return err;
+  }
+};
+
 template <typename T>
 int run_stack(const cephalo_stack_desc& d, const void* Pv, const int* ids, const int* targets, int b, int m,
-              float* G, float scale, float* loss_out, void* ws, float* host_area, hipStream_t s, hipStream_t copy_in, hipStream_t copy_out) {
+              float* G, float scale, float* loss_out, void* ws, float* host_area, hipStream_t s, hipStream_t copy_in, hipStream_t copy_out,
+              hipStream_t side) {
   const cephalo_layer_desc& ld = d.layer;
   const T* P = static_cast<const T*>(Pv);
   const int S = ld.seq, H = ld.hidden, V = d.vocab, NL = d.layers, l = b / m;
@@ -342,8 +380,18 @@ int run_stack(const cephalo_stack_desc& d, const void* Pv, const int* ids, const
   const bool rms = is_llama(ld);
   const StackLayout L = stack_layout(d, b, m);
   const SaveLayout SL = save_layout(ld, b);
-  const ScratchLayout WL = scratch_layout(ld, m, b);
+  const int nst = d.interleave ? 2 : 1;
+  const ScratchLayout WL = scratch_layout(ld, m, b, nst);
   void* scratch = at<char>(ws, L.scratch);
+  // Interleave: micro-batch j runs on stream j % 2, so that the bandwidth-bound kernels of one micro-batch overlap the
+  // matrix-core kernels of the other and GEMMs with few output tiles share the compute units.  A micro-batch's whole
+  // chain through the layers stays on its stream; the streams meet where the share is handled as one (weight
+  // gradients, shared weight transposes, the embeddings), through fork / join events.
+  hipStream_t st[2] = {s, d.interleave ? side : s};
+  Streams J;
+  J.main = s; J.side = side; J.on = d.interleave != 0;
+  TRY(J.open());
+  struct JCloser { Streams& j; ~JCloser() { (void)j.close(); } } jcloser{J};
   const size_t act = (size_t)Tm * H;
   Boundary X;
   X.offload = d.offload != 0;
@@ -358,8 +406,11 @@ int run_stack(const cephalo_stack_desc& d, const void* Pv, const int* ids, const
   struct Closer { Boundary& x; bool done = false; ~Closer() { if (!done) (void)x.close(); } } closer{X};   // events are released on every path
 
   // ---- forward
+  TRY(prepare_head_weights<T>(P + o_head, at<T>(ws, L.wteT), V, H, L.ldv, s));
+  J.fork();
+  GemmSideBySide hint(nst);     // until the join: two kernels share the device
   for (int j = 0; j < l; ++j) {
-    embed_fwd_kernel<T><<<(Tm + 3) / 4, kThreads, 0, s>>>(ids + (size_t)j * Tm, P + o_wte, SO.positions ? P + o_wpe : (const T*)nullptr, X.out(0, j), Tm, S, H, V);
+    embed_fwd_kernel<T><<<(Tm + 3) / 4, kThreads, 0, st[j % nst]>>>(ids + (size_t)j * Tm, P + o_wte, SO.positions ? P + o_wpe : (const T*)nullptr, X.out(0, j), Tm, S, H, V);
     CEPHALO_CHECK_LAUNCH("embed_fwd");
     X.out_done(0, j);
   }
@@ -371,7 +422,7 @@ int run_stack(const cephalo_stack_desc& d, const void* Pv, const int* ids, const
       const float* xi = X.in(li, j, l);
       X.prefetch(li, j + 1, l);
       float* xo = X.out(li + 1, j);
-      TRY(layer_fwd_t<T>(ld, P + o_layers + li * PL, xi, xo, m, saved_at<T>(save, SL, ld, j * m), s));
+      TRY(layer_fwd_t<T>(ld, P + o_layers + li * PL, xi, xo, m, saved_at<T>(save, SL, ld, j * m), st[j % nst]));
       X.in_done();
       X.out_done(li + 1, j);
     }
@@ -384,30 +435,34 @@ int run_stack(const cephalo_stack_desc& d, const void* Pv, const int* ids, const
   T* dxl_cur = at<T>(ws, L.dxal); T* dxl_nxt = at<T>(ws, L.dxbl);
   const float coef = scale / (float)n;
   const int nb = ln_bwd_blocks(Tm);
-  TRY(prepare_head_weights<T>(P + o_head, at<T>(ws, L.wteT), V, H, L.ldv, s));
   X.prefetch(NL, 0, l);
   for (int j = 0; j < l; ++j) {
     const size_t t0 = (size_t)j * Tm;
+    hipStream_t sj = st[j % nst];
+    float* logits_j = logits + (size_t)(j % nst) * Tm * L.ldv;
+    float* duf_j = duf + (size_t)(j % nst) * Tm * H;
     const float* xL = X.in(NL, j, l);
     X.prefetch(NL, j + 1, l);
-    TRY(launch_ln_fwd<T>(xL, P + o_lnf, rms ? (const T*)nullptr : P + o_lnf + H, uf + t0 * H, meanf + t0, rstdf + t0, Tm, H, ld.ln_eps, s, rms));
+    TRY(launch_ln_fwd<T>(xL, P + o_lnf, rms ? (const T*)nullptr : P + o_lnf + H, uf + t0 * H, meanf + t0, rstdf + t0, Tm, H, ld.ln_eps, sj, rms));
     T* dlg = dlogits + t0 * L.ldv;
     {
       GemmArgs<T> a = linear_fwd<T>(uf + t0 * H, P + o_head, Tm, V, H);
-      a.epi = EPI_NONE; a.Cf = logits; a.ldc = L.ldv;
-      TRY(gemm<T>(a, s));
+      a.epi = EPI_NONE; a.Cf = logits_j; a.ldc = L.ldv;
+      TRY(gemm<T>(a, sj));
     }
-    cross_entropy_kernel<T><<<Tm, kThreads, 0, s>>>(logits, dlg, targets + t0, at<float>(ws, L.loss) + t0, V, L.ldv, coef);
+    cross_entropy_kernel<T><<<Tm, kThreads, 0, sj>>>(logits_j, dlg, targets + t0, at<float>(ws, L.loss) + t0, V, L.ldv, coef);
     CEPHALO_CHECK_LAUNCH("cross_entropy");
     {
       GemmArgs<T> a = head_dgrad_args<T>(dlg, P + o_head, at<T>(ws, L.wteT), Tm, V, H, L.ldv);   // duf = dlogits W_head
-      a.epi = EPI_NONE; a.Cf = duf;
-      TRY(gemm<T>(a, s));
+      a.epi = EPI_NONE; a.Cf = duf_j;
+      TRY(gemm<T>(a, sj));
     }
-    TRY(launch_ln_bwd<T>(duf, xL, meanf + t0, rstdf + t0, P + o_lnf, (const float*)nullptr, dx_cur + t0 * H,
-                         lowp_out<T>(dxl_cur + t0 * H), lnf_g + (size_t)j * nb * H, lnf_b + (size_t)j * nb * H, Tm, H, s, rms));
+    TRY(launch_ln_bwd<T>(duf_j, xL, meanf + t0, rstdf + t0, P + o_lnf, (const float*)nullptr, dx_cur + t0 * H,
+                         lowp_out<T>(dxl_cur + t0 * H), lnf_g + (size_t)j * nb * H, lnf_b + (size_t)j * nb * H, Tm, H, sj, rms));
     X.in_done();
   }
+  J.join();
+  hint.now(1);
   mean_kernel<<<1, kThreads, 0, s>>>(at<float>(ws, L.loss), n, loss_out);
   CEPHALO_CHECK_LAUNCH("mean_loss");
   {
@@ -421,6 +476,8 @@ int run_stack(const cephalo_stack_desc& d, const void* Pv, const int* ids, const
     void* save = save_of(li);
     const T* Pl = P + o_layers + li * PL;
     TRY(prepare_dgrad_weights<T>(ld, Pl, work_at<T>(scratch, WL, ld, 0, 0, m).wT, s));
+    J.fork();        // (after the previous layer's weight gradients too: they read what this layer's data pass overwrites)
+    hint.now(nst);
     // Checkpointing: a micro-batch's internals are recomputed from its boundary input right before its backward (the
     // last layer's are still there from the forward); the recomputed output, the same values again, is dropped.
     const bool recompute = d.checkpoint && li != NL - 1;
@@ -428,11 +485,13 @@ int run_stack(const cephalo_stack_desc& d, const void* Pv, const int* ids, const
     for (int j = 0; j < l; ++j) {
       const float* xi = X.in(li, j, l);
       X.prefetch(li, j + 1, l);
-      if (recompute) TRY(layer_fwd_t<T>(ld, Pl, xi, at<float>(ws, L.xdump), m, saved_at<T>(save, SL, ld, j * m), s));
+      if (recompute) TRY(layer_fwd_t<T>(ld, Pl, xi, at<float>(ws, L.xdump) + (size_t)(j % nst) * act, m, saved_at<T>(save, SL, ld, j * m), st[j % nst]));
       TRY(layer_bwd_data_t<T>(ld, Pl, xi, dx_cur + j * act, lowp_of<T>(dx_cur, dxl_cur) + j * act, dx_nxt + j * act,
-                              dxl_nxt + j * act, m, saved_at<T>(save, SL, ld, j * m), work_at<T>(scratch, WL, ld, j * m, j, m), s));
+                              dxl_nxt + j * act, m, saved_at<T>(save, SL, ld, j * m), work_at<T>(scratch, WL, ld, j * m, j, m, j % nst), st[j % nst]));
       X.in_done();
     }
+    J.join();
+    hint.now(1);
     TRY(layer_bwd_params_t<T>(ld, dx_cur, lowp_of<T>(dx_cur, dxl_cur), n, l * nb, saved_at<T>(save, SL, ld, 0),
                               work_at<T>(scratch, WL, ld, 0, 0, m), G + o_layers + li * PL, 1.0f, 0, s));
     { float* t = dx_cur; dx_cur = dx_nxt; dx_nxt = t; }
@@ -491,7 +550,8 @@ extern "C" int cephalo_stack_workspace_bytes(const cephalo_stack_desc* d, int32_
 namespace {
 int stack_step_checked(const cephalo_stack_desc* d, const void* flat_param, const int32_t* ids, const int32_t* targets,
                        int32_t batch_share, int32_t micro_batch, float* flat_grad, float grad_scale, float* loss,
-                       void* workspace, size_t workspace_bytes, void* host_area, size_t host_bytes, void* stream, void* copy_in, void* copy_out) {
+                       void* workspace, size_t workspace_bytes, void* host_area, size_t host_bytes, void* stream, void* copy_in, void* copy_out,
+                       void* side = nullptr) {
   TRY(check_stack(d));
   if (micro_batch <= 0 || batch_share <= 0 || batch_share % micro_batch != 0)
     return fail(CEPHALO_EINVAL, "stack_step: batch share b = %d is not a positive multiple of micro-batch size m = %d",
@@ -511,12 +571,15 @@ int stack_step_checked(const cephalo_stack_desc* d, const void* flat_param, cons
     if (!copy_in || !copy_out || copy_in == stream || copy_out == stream)
       return fail(CEPHALO_EINVAL, "stack_step: offload needs copy streams other than the compute stream");
   }
+  if (d->interleave && (!side || side == stream))
+    return fail(CEPHALO_EINVAL, "stack_step: interleave needs a side stream other than the compute stream");
   hipStream_t s = static_cast<hipStream_t>(stream), ci = static_cast<hipStream_t>(copy_in), co = static_cast<hipStream_t>(copy_out);
+  hipStream_t sd = static_cast<hipStream_t>(side);
   if (d->layer.dtype == CEPHALO_F32)
     return run_stack<float>(*d, flat_param, ids, targets, batch_share, micro_batch, flat_grad, grad_scale, loss, workspace,
-                            static_cast<float*>(host_area), s, ci, co);
+                            static_cast<float*>(host_area), s, ci, co, sd);
   return run_stack<bf16>(*d, flat_param, ids, targets, batch_share, micro_batch, flat_grad, grad_scale, loss, workspace,
-                         static_cast<float*>(host_area), s, ci, co);
+                         static_cast<float*>(host_area), s, ci, co, sd);
 }
 }  // namespace
 
@@ -534,6 +597,7 @@ extern "C" int cephalo_stack_step(const cephalo_stack_desc* d, const void* flat_
                                   int32_t batch_share, int32_t micro_batch, float* flat_grad, float grad_scale, float* loss,
                                   void* workspace, size_t workspace_bytes, void* stream) {
   if (d && d->offload) return fail(CEPHALO_EINVAL, "stack_step: a desc with offload = 1 goes to cephalo_stack_step_offload");
+  if (d && d->interleave) return fail(CEPHALO_EINVAL, "stack_step: a desc with interleave = 1 goes to cephalo_stack_step_interleaved");
   return stack_step_checked(d, flat_param, ids, targets, batch_share, micro_batch, flat_grad, grad_scale, loss,
                             workspace, workspace_bytes, nullptr, 0, stream, nullptr, nullptr);
 }
@@ -545,4 +609,12 @@ extern "C" int cephalo_stack_step_offload(const cephalo_stack_desc* d, const voi
   if (d && !d->offload) return fail(CEPHALO_EINVAL, "stack_step_offload: the desc has offload = 0");
   return stack_step_checked(d, flat_param, ids, targets, batch_share, micro_batch, flat_grad, grad_scale, loss,
                             workspace, workspace_bytes, host_area, host_bytes, stream, copy_in_stream, copy_out_stream);
+}
+
+extern "C" int cephalo_stack_step_interleaved(const cephalo_stack_desc* d, const void* flat_param, const int32_t* ids, const int32_t* targets,
+                                              int32_t batch_share, int32_t micro_batch, float* flat_grad, float grad_scale, float* loss,
+                                              void* workspace, size_t workspace_bytes, void* stream, void* side_stream) {
+  if (d && !d->interleave) return fail(CEPHALO_EINVAL, "stack_step_interleaved: the desc has interleave = 0");
+  return stack_step_checked(d, flat_param, ids, targets, batch_share, micro_batch, flat_grad, grad_scale, loss,
+                            workspace, workspace_bytes, nullptr, 0, stream, nullptr, nullptr, side_stream);
 }

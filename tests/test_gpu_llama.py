@@ -162,7 +162,7 @@ def test_llama_stack_step_matches_oracle(case):
     print("loss", loss, ref_loss, "worst mean-rel", worst, flush=True)
 
 
-def test_llama_stack_checkpointing_and_offload_are_bit_identical():
+def test_llama_stack_checkpointing_offload_and_interleave_are_bit_identical():
     cfg = STACKS["bf16_m1_d128"]
     params = draw_stack_params(cfg, perturbed=True)
     ids, tgt = draw_token_ids(cfg)
@@ -170,6 +170,9 @@ def test_llama_stack_checkpointing_and_offload_are_bit_identical():
     b = run_stack_gpu(cfg, params, ids, tgt, 1.25, checkpoint=True)
     c = run_stack_gpu(cfg, params, ids, tgt, 1.25, checkpoint=True, offload=True)
     assert a[0] == b[0] == c[0] and np.array_equal(a[1], b[1]) and np.array_equal(a[1], c[1])
+    d = run_stack_gpu(cfg, params, ids, tgt, 1.25, interleave=True)              # two micro-batches in flight on two streams
+    e = run_stack_gpu(cfg, params, ids, tgt, 1.25, checkpoint=True, interleave=True)
+    assert a[0] == d[0] == e[0] and np.array_equal(a[1], d[1]) and np.array_equal(a[1], e[1])
 
 
 def test_tinyllama_stack_full_size_layer_by_layer():

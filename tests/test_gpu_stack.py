@@ -23,8 +23,8 @@ CASES = {
 }
 
 
-def run_gpu(cfg, params, ids, tgt, scale, checkpoint=False, offload=False, keep=None):
-    sd = C.stack_desc_from_config(cfg, checkpoint, offload)
+def run_gpu(cfg, params, ids, tgt, scale, checkpoint=False, offload=False, keep=None, interleave=False):
+    sd = C.stack_desc_from_config(cfg, checkpoint, offload, interleave)
     flat32 = torch.from_numpy(C.flatten_stack_params(sd, params)).cuda()
     if cfg.dtype == "bf16":
         flat = torch.empty(flat32.numel(), dtype=torch.bfloat16, device="cuda")
@@ -46,9 +46,14 @@ def run_gpu(cfg, params, ids, tgt, scale, checkpoint=False, offload=False, keep=
         if keep is not None:
             keep["boundaries"] = host.numpy().copy()
     else:
-        C.cephalo_stack_step(sd, flat, torch.from_numpy(ids).cuda(), torch.from_numpy(tgt).cuda(), cfg.batch_share, cfg.micro_batch,
-                             G, scale, loss, ws)
-        torch.cuda.synchronize()
+        if interleave:
+            C.cephalo_stack_step_interleaved(sd, flat, torch.from_numpy(ids).cuda(), torch.from_numpy(tgt).cuda(), cfg.batch_share,
+                                             cfg.micro_batch, G, scale, loss, ws, torch.cuda.Stream())
+            torch.cuda.current_stream().synchronize()     # the call joins the side stream into the compute stream
+        else:
+            C.cephalo_stack_step(sd, flat, torch.from_numpy(ids).cuda(), torch.from_numpy(tgt).cuda(), cfg.batch_share, cfg.micro_batch,
+                                 G, scale, loss, ws)
+            torch.cuda.synchronize()
         if keep is not None:
             keep["boundaries"] = ws[:4 * n_bound].view(torch.float32).cpu().numpy().copy()
     return float(loss.item()), G.cpu().numpy(), sd
@@ -147,6 +152,43 @@ def test_boundary_activations_offloaded_to_host_give_identical_results(case):
     saved = (cfg.layers + 1) * cfg.batch_share * cfg.seq * cfg.hidden * 4 - 4 * cfg.micro_batch * cfg.seq * cfg.hidden * 4
     assert res - off >= saved - 4096 * 8          # the boundaries left the work area, but for four micro-batch slots
     assert C.cephalo_stack_host_bytes(sd_res, cfg.batch_share, cfg.micro_batch) == 0
+
+
+@pytest.mark.parametrize("case", ["bf16_mini", "bf16_mini_m1", "f32_tiny", "bf16_deep6"])
+@pytest.mark.parametrize("checkpoint", [False, True])
+def test_two_micro_batches_in_flight_give_identical_results(case, checkpoint):
+    """Micro-batches alternating between two streams (the layered order of Sec. 3.2 leaves the micro-batches of a layer
+    independent of each other): each micro-batch's own kernels run in the same order and every reduction keeps its
+    order, so the loss and every gradient element are bit-identical to the one-stream run; so are the layer-boundary
+    activations left in the work area.  Twice, the second time over a work area that holds the first run's values."""
+    cfg = CASES[case]
+    params = draw_stack_params(cfg, perturbed=True)
+    ids, tgt = draw_token_ids(cfg)
+    ka, kb = {}, {}
+    a = run_gpu(cfg, params, ids, tgt, 0.75, checkpoint=checkpoint, keep=ka)
+    for repeat in range(2):
+        b = run_gpu(cfg, params, ids, tgt, 0.75, checkpoint=checkpoint, interleave=True, keep=kb)
+        assert a[0] == b[0] and np.array_equal(a[1], b[1])
+        assert np.array_equal(ka["boundaries"], kb["boundaries"])
+
+
+def test_interleave_argument_errors():
+    cfg = CASES["f32_tiny"]
+    with pytest.raises(C.CephaloError):           # not together with offload
+        C.cephalo_stack_workspace_bytes(C.stack_desc_from_config(cfg, True, True, True), cfg.batch_share, cfg.micro_batch)
+    sd = C.stack_desc_from_config(cfg, False, False, True)
+    P = C.cephalo_stack_param_count(sd)
+    flat = torch.zeros(P, device="cuda"); G = torch.zeros(P, device="cuda"); loss = torch.zeros(1, device="cuda")
+    ids = torch.zeros(cfg.batch_share, cfg.seq, dtype=torch.int32, device="cuda")
+    ws = torch.empty(C.cephalo_stack_workspace_bytes(sd, cfg.batch_share, cfg.micro_batch), dtype=torch.uint8, device="cuda")
+    with pytest.raises(C.CephaloError):           # the plain entry point refuses an interleave desc
+        C.cephalo_stack_step(sd, flat, ids, ids, cfg.batch_share, cfg.micro_batch, G, 1.0, loss, ws)
+    with pytest.raises(C.CephaloError):           # the side stream must differ from the compute stream
+        C.cephalo_stack_step_interleaved(sd, flat, ids, ids, cfg.batch_share, cfg.micro_batch, G, 1.0, loss, ws, torch.cuda.current_stream())
+    plain = C.stack_desc_from_config(cfg)
+    with pytest.raises(C.CephaloError):           # and the interleaved entry point a plain desc
+        C.cephalo_stack_step_interleaved(plain, flat, ids, ids, cfg.batch_share, cfg.micro_batch, G, 1.0, loss, ws, torch.cuda.Stream())
+    assert C.cephalo_stack_workspace_bytes(sd, cfg.batch_share, cfg.micro_batch) > C.cephalo_stack_workspace_bytes(plain, cfg.batch_share, cfg.micro_batch)
 
 
 def test_offload_argument_errors():
