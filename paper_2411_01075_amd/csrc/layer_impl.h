@@ -455,30 +455,31 @@ int layer_bwd_data_t(const cephalo_layer_desc& d, const T* P, const float* x, co
 // two residual-stream projections are column sums of the fp32 gradients.
 template <typename T>
 int layer_bwd_params_t(const cephalo_layer_desc& d, const float* dy, const T* dyl, int tokens, int ln_chunks,
-                       const Saved<T>& sv, const Work<T>& w, float* G, float scale, int acc, hipStream_t s) {
+                       const Saved<T>& sv, const Work<T>& w, float* G, float scale, int acc, hipStream_t s, hipStream_t s2 = nullptr) {
+  if (!s2) s2 = s;      // s2: where the bandwidth-bound reductions (bias column sums, norm-parameter partials) run, beside the GEMMs on s
   const ParamOffsets o = param_offsets(d);
   const int H = d.hidden, F = d.mlp;
   if (is_llama(d)) {
     TRY(wgrad<T>(dyl, sv.h, tokens, H, F, G + o.w_fc2, scale, acc, w.wg_part, s));
     TRY(wgrad<T>(w.dz, sv.u2, tokens, 2 * F, H, G + o.w_fc1, scale, acc, w.wg_part, s));
-    TRY(launch_reduce_partials(w.ln2_g, ln_chunks, H, G + o.ln2_g, scale, acc, w.col_part, w.col_part_bytes, s));
+    TRY(launch_reduce_partials(w.ln2_g, ln_chunks, H, G + o.ln2_g, scale, acc, w.col_part, w.col_part_bytes, s2));
     TRY(wgrad<T>(lowp_of<T>(w.dx1, w.dx1l), sv.O, tokens, H, H, G + o.w_o, scale, acc, w.wg_part, s));
     TRY(wgrad<T>(w.dqkv, sv.u, tokens, 3 * H, H, G + o.w_qkv, scale, acc, w.wg_part, s));
-    TRY(launch_reduce_partials(w.ln1_g, ln_chunks, H, G + o.ln1_g, scale, acc, w.col_part, w.col_part_bytes, s));
+    TRY(launch_reduce_partials(w.ln1_g, ln_chunks, H, G + o.ln1_g, scale, acc, w.col_part, w.col_part_bytes, s2));
     return CEPHALO_OK;
   }
-  TRY(launch_colsum<float>(dy, w.col_part, w.col_part_bytes, G + o.b_fc2, scale, acc, tokens, H, s));
+  TRY(launch_colsum<float>(dy, w.col_part, w.col_part_bytes, G + o.b_fc2, scale, acc, tokens, H, s2));
   TRY(wgrad<T>(dyl, sv.h, tokens, H, F, G + o.w_fc2, scale, acc, w.wg_part, s));
-  TRY(launch_colsum<T>(w.dz, w.col_part, w.col_part_bytes, G + o.b_fc1, scale, acc, tokens, F, s));
+  TRY(launch_colsum<T>(w.dz, w.col_part, w.col_part_bytes, G + o.b_fc1, scale, acc, tokens, F, s2));
   TRY(wgrad<T>(w.dz, sv.u2, tokens, F, H, G + o.w_fc1, scale, acc, w.wg_part, s));
-  TRY(launch_reduce_partials(w.ln2_g, ln_chunks, H, G + o.ln2_g, scale, acc, w.col_part, w.col_part_bytes, s));
-  TRY(launch_reduce_partials(w.ln2_b, ln_chunks, H, G + o.ln2_b, scale, acc, w.col_part, w.col_part_bytes, s));
-  TRY(launch_colsum<float>(w.dx1, w.col_part, w.col_part_bytes, G + o.b_o, scale, acc, tokens, H, s));
+  TRY(launch_reduce_partials(w.ln2_g, ln_chunks, H, G + o.ln2_g, scale, acc, w.col_part, w.col_part_bytes, s2));
+  TRY(launch_reduce_partials(w.ln2_b, ln_chunks, H, G + o.ln2_b, scale, acc, w.col_part, w.col_part_bytes, s2));
+  TRY(launch_colsum<float>(w.dx1, w.col_part, w.col_part_bytes, G + o.b_o, scale, acc, tokens, H, s2));
   TRY(wgrad<T>(lowp_of<T>(w.dx1, w.dx1l), sv.O, tokens, H, H, G + o.w_o, scale, acc, w.wg_part, s));
-  TRY(launch_colsum<T>(w.dqkv, w.col_part, w.col_part_bytes, G + o.b_qkv, scale, acc, tokens, 3 * H, s));
+  TRY(launch_colsum<T>(w.dqkv, w.col_part, w.col_part_bytes, G + o.b_qkv, scale, acc, tokens, 3 * H, s2));
   TRY(wgrad<T>(w.dqkv, sv.u, tokens, 3 * H, H, G + o.w_qkv, scale, acc, w.wg_part, s));
-  TRY(launch_reduce_partials(w.ln1_g, ln_chunks, H, G + o.ln1_g, scale, acc, w.col_part, w.col_part_bytes, s));
-  TRY(launch_reduce_partials(w.ln1_b, ln_chunks, H, G + o.ln1_b, scale, acc, w.col_part, w.col_part_bytes, s));
+  TRY(launch_reduce_partials(w.ln1_g, ln_chunks, H, G + o.ln1_g, scale, acc, w.col_part, w.col_part_bytes, s2));
+  TRY(launch_reduce_partials(w.ln1_b, ln_chunks, H, G + o.ln1_b, scale, acc, w.col_part, w.col_part_bytes, s2));
   return CEPHALO_OK;
 }
 

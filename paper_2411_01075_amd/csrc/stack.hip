@@ -492,8 +492,10 @@ int run_stack(const cephalo_stack_desc& d, const void* Pv, const int* ids, const
     }
     J.join();
     hint.now(1);
+    J.fork();        // the parameter pass: weight-gradient GEMMs on the main stream, the bandwidth-bound reductions beside them
     TRY(layer_bwd_params_t<T>(ld, dx_cur, lowp_of<T>(dx_cur, dxl_cur), n, l * nb, saved_at<T>(save, SL, ld, 0),
-                              work_at<T>(scratch, WL, ld, 0, 0, m), G + o_layers + li * PL, 1.0f, 0, s));
+                              work_at<T>(scratch, WL, ld, 0, 0, m), G + o_layers + li * PL, 1.0f, 0, s, st[1]));
+    J.join();
     { float* t = dx_cur; dx_cur = dx_nxt; dx_nxt = t; }
     { T* t = dxl_cur; dxl_cur = dxl_nxt; dxl_nxt = t; }
   }
