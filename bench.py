@@ -27,6 +27,10 @@ sys.path.insert(0, ROOT)
 
 PEAK_BF16_TFLOPS = 2500.0     # MI355X dense bf16 MFMA, published
 PEAK_HBM_GBS = 8000.0         # MI355X HBM3E, published
+# HBM bytes per launch (rocprofv3 --pmc FETCH_SIZE + WRITE_SIZE, scaled by the copy-kernel calibration; see
+# profiles/gemm_input_gradient_and_adam_hbm_traffic.txt) of the c5 input-gradient GEMM, mean of its three shapes, by the
+# number of kernels run side by side (which fixes the tile): 1: 256 x 128 tiles, 2: 256 x 256 tiles
+TRAFFIC_C5_DGRAD = {1: 207.0e6, 2: 207.0e6}
 
 
 def layer_flops_per_microbatch(cfg):
@@ -181,6 +185,23 @@ def main():
         torch.cuda.synchronize()
         return e0.elapsed_time(e1) * 1e-3 / iters
 
+    def timed_pairs(fn, iters):
+        """fn(i) launches on stream i of two; pairs run side by side as in the interleaved step.  Returns the time of a pair."""
+        s0 = torch.cuda.current_stream()
+        fn(0, s0); fn(1, side)
+        torch.cuda.synchronize()
+        e0, e1, ej = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True), torch.cuda.Event()
+        e0.record(s0)
+        side.wait_event(e0)
+        for _ in range(iters):
+            fn(0, s0)
+            fn(1, side)
+        ej.record(side)
+        s0.wait_event(ej)
+        e1.record(s0)
+        torch.cuda.synchronize()
+        return e0.elapsed_time(e1) * 1e-3 / iters
+
     roofline = {"kernel": "not broken out (the GEMM legs are timed for the bf16 GPT-style workloads; see whole_step_model_tflops)",
                 "bound": "mfma" if bf16 else "alu", "achieved": None, "peak": PEAK_BF16_TFLOPS if bf16 else 157.3,
                 "unit": "TFLOP/s", "frac": None, "traffic": None}
@@ -199,17 +220,32 @@ def main():
         lin = [("qkv", 3 * H, H), ("o", H, H), ("fc1", F, H), ("fc2", H, F)]
         legs = {}
 
-        def add_leg(key, fn, flops, count):
-            # enough back-to-back launches (about 30 ms) that the clocks settle where they sit during the step
-            first = timed(fn, 2)
-            sec = timed(fn, max(3, min(400, int(0.03 / max(first, 1e-6)))))
-            g = legs.setdefault(key, {"sec": 0.0, "flops": 0.0, "launches": 0})
+        pairs = stack and interleave      # per-micro-batch GEMMs run two side by side, one per stream, as in the step
+
+        def add_leg(key, fn, flops, count, alone=False):
+            # enough back-to-back launches (about 30 ms) that the clocks settle where they sit during the step.
+            # fn(i, stream): launch number i of a pair (its own output buffers) on that stream.
+            if pairs and not alone:
+                C.cephalo_gemm_side_by_side(2)
+                first = timed_pairs(fn, 2)
+                dur = timed_pairs(fn, max(3, min(400, int(0.03 / max(first, 1e-6)))))      # a kernel's duration = the pair's
+                sec = dur / 2                                                                  # device time per launch
+                C.cephalo_gemm_side_by_side(1)
+            else:
+                one = lambda: fn(0, None)
+                first = timed(one, 2)
+                dur = sec = timed(one, max(3, min(400, int(0.03 / max(first, 1e-6)))))
+            g = legs.setdefault(key, {"sec": 0.0, "dur": 0.0, "flops": 0.0, "launches": 0, "side_by_side": 2 if (pairs and not alone) else 1})
             g["sec"] += sec * count
+            g["dur"] += dur * count
             g["flops"] += flops * count
             g["launches"] += count
 
         def rnd(*shape, scale=1.0, dtype=bt):
             return (torch.randn(*shape, device="cuda") * scale).to(dtype)
+
+        def two(*shape, dtype=bt):
+            return [torch.empty(*shape, device="cuda", dtype=dtype) for _ in range(2)]
 
         for name, n_out, k_in in lin:
             X, W, WT, dY = rnd(T, k_in), rnd(n_out, k_in, scale=0.02), rnd(k_in, n_out, scale=0.02), rnd(T, n_out)
@@ -217,48 +253,52 @@ def main():
             fl = 2.0 * T * n_out * k_in
             fwd_args = (C.BF16, X, k_in, 1, W, k_in, 1, T, n_out, k_in)
             if name == "qkv":
-                Y = torch.empty(T, n_out, device="cuda", dtype=bt)
-                add_leg("forward, bias epilogue (qkv)", lambda: C.cephalo_op_gemm(*fwd_args, C.EPI_BIAS, C=Y, bias=bias), fl, L * l)
+                Y = two(T, n_out)
+                add_leg("forward, bias epilogue (qkv)", lambda i, st: C.cephalo_op_gemm(*fwd_args, C.EPI_BIAS, C=Y[i], bias=bias, stream=st), fl, L * l)
             elif name == "fc1":
-                Y, Z = torch.empty(T, n_out, device="cuda", dtype=bt), torch.empty(T, n_out, device="cuda", dtype=bt)
-                add_leg("forward, bias+GELU epilogue (fc1)", lambda: C.cephalo_op_gemm(*fwd_args, C.EPI_BIAS_GELU, C=Y, bias=bias, Z=Z), fl, L * l)
+                Y, Z = two(T, n_out), two(T, n_out)
+                add_leg("forward, bias+GELU epilogue (fc1)",
+                        lambda i, st: C.cephalo_op_gemm(*fwd_args, C.EPI_BIAS_GELU, C=Y[i], bias=bias, Z=Z[i], stream=st), fl, L * l)
             else:
-                R, Y = rnd(T, n_out, dtype=torch.float32), torch.empty(T, n_out, device="cuda")
+                R, Y = rnd(T, n_out, dtype=torch.float32), two(T, n_out, dtype=torch.float32)
                 add_leg("forward, bias+residual epilogue, fp32 stream (out-proj, fc2)",
-                        lambda: C.cephalo_op_gemm(*fwd_args, C.EPI_BIAS_RESID_F32, C=Y, bias=bias, R=R), fl, L * l)
+                        lambda i, st: C.cephalo_op_gemm(*fwd_args, C.EPI_BIAS_RESID_F32, C=Y[i], bias=bias, R=R, stream=st), fl, L * l)
             # input gradient dX[T, k_in] = dY[T, n_out] W, through W^T [k_in, n_out]
             dg_args = (C.BF16, dY, n_out, 1, WT, n_out, 1, T, k_in, n_out)
             if name == "fc2":
-                Zs, dZ = rnd(T, k_in), torch.empty(T, k_in, device="cuda", dtype=bt)
-                add_leg("input gradient, GELU' epilogue (fc2)", lambda: C.cephalo_op_gemm(*dg_args, C.EPI_DGELU, C=dZ, Z=Zs), fl, L * l)
+                Zs, dZ = rnd(T, k_in), two(T, k_in)
+                add_leg("input gradient, GELU' epilogue (fc2)", lambda i, st: C.cephalo_op_gemm(*dg_args, C.EPI_DGELU, C=dZ[i], Z=Zs, stream=st), fl, L * l)
             elif name == "o":
-                dX = torch.empty(T, k_in, device="cuda", dtype=bt)
-                add_leg("input gradient, plain epilogue (qkv, out-proj, fc1)", lambda: C.cephalo_op_gemm(*dg_args, C.EPI_NONE, C=dX), fl, L * l)
+                dX = two(T, k_in)
+                add_leg("input gradient, plain epilogue (qkv, out-proj, fc1)", lambda i, st: C.cephalo_op_gemm(*dg_args, C.EPI_NONE, C=dX[i], stream=st), fl, L * l)
             else:
-                dX = torch.empty(T, k_in, device="cuda")
-                add_leg("input gradient, plain epilogue (qkv, out-proj, fc1)", lambda: C.cephalo_op_gemm(*dg_args, C.EPI_NONE_F32, C=dX), fl, L * l)
+                dX = two(T, k_in, dtype=torch.float32)
+                add_leg("input gradient, plain epilogue (qkv, out-proj, fc1)", lambda i, st: C.cephalo_op_gemm(*dg_args, C.EPI_NONE_F32, C=dX[i], stream=st), fl, L * l)
             del X, W, WT, dY
-            # weight gradient over the whole share
+            # weight gradient over the whole share: alone on the main stream
             Xs, dYs = rnd(n_tok, k_in), rnd(n_tok, n_out)
             Gw = torch.zeros(n_out, k_in, device="cuda")
             wsb = torch.empty(C.cephalo_op_linear_wgrad_workspace(C.BF16, n_tok, n_out, k_in), dtype=torch.uint8, device="cuda")
-            add_leg("weight gradient over the share (transpose + GEMM + split reduction)",
-                    lambda: C.cephalo_op_linear_wgrad(C.BF16, dYs, Xs, n_tok, n_out, k_in, Gw, 1.0, 0, wsb), 2.0 * n_tok * n_out * k_in, L)
+            add_leg("weight gradient over the share (GEMM + split reduction)",
+                    lambda i, st: C.cephalo_op_linear_wgrad(C.BF16, dYs, Xs, n_tok, n_out, k_in, Gw, 1.0, 0, wsb), 2.0 * n_tok * n_out * k_in, L, alone=True)
             del Xs, dYs, Gw, wsb
         for g in legs.values():
             g["TFLOP/s"] = round(g["flops"] / g["sec"] / 1e12, 1)
-            g["avg_launch_us"] = round(1e6 * g["sec"] / g["launches"], 1)
+            g["avg_launch_us"] = round(1e6 * g.pop("dur") / g["launches"], 1)      # a kernel's own duration (side by side: while sharing the device)
             g["ms_per_step"] = round(1e3 * g.pop("sec"), 3)
             g["flops_per_launch"] = g.pop("flops") / g["launches"]
-        single = [k for k in legs if not k.startswith("weight gradient")]      # one kernel launch per call: events bracket that kernel alone
+        single = [k for k in legs if not k.startswith("weight gradient")]      # one kernel launch per call
         key = max(single, key=lambda k: legs[k]["ms_per_step"])
         d = legs[key]
         # HBM bytes per launch from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE (profiles/gemm_input_gradient_and_adam_hbm_traffic.txt),
         # measured for the c5 shapes of this leg only
-        traffic = 207.0e6 if (cfg.name == "c5" and key.startswith("input gradient, plain")) else None
+        traffic = TRAFFIC_C5_DGRAD.get(d["side_by_side"]) if (cfg.name == "c5" and key.startswith("input gradient, plain")) else None
         roofline = {"kernel": "gemm_mfma_kernel (v_mfma_f32_16x16x32_bf16), " + key, "bound": "mfma", "achieved": d["TFLOP/s"], "peak": PEAK_BF16_TFLOPS,
                     "unit": "TFLOP/s", "frac": round(d["TFLOP/s"] / PEAK_BF16_TFLOPS, 4), "traffic": traffic,
-                    "avg_launch_us": d["avg_launch_us"], "flops_per_launch": d["flops_per_launch"], "launches_per_step": d["launches"]}
+                    "avg_launch_us": d["avg_launch_us"], "flops_per_launch": d["flops_per_launch"], "launches_per_step": d["launches"],
+                    # side_by_side = 2: two such kernels share the device, one per stream; `achieved` is their joint rate,
+                    # 2 * flops_per_launch / avg_launch_us, against the whole device's peak
+                    "side_by_side": d["side_by_side"]}
         extras["gemm_legs"] = legs
     # shard Adam alone: 28 algorithmic bytes per element (+2 for the bf16 copy)
     adam_sec = timed(lambda: C.cephalo_shard_adam(p32, G, mom, var, plow, P, off, ln, lr, 0.9, 0.999, 1e-8, 9), 10)

@@ -85,6 +85,12 @@ const char* cephalo_last_error(void);
  * results are the same; a caller that cares about speed checks that the count stays where it was. */
 int64_t cephalo_gemm_general_count(void);
 
+/* Tells the tile choice of the calling thread's later bf16 GEMM launches (cephalo_op_gemm and every call built on it)
+ * how many kernels the caller runs side by side on different streams: each then plans for 256 / kernels compute units
+ * (a GEMM with 128 output tiles of 256 x 256 fills half the device; two of them on two streams fill it).  1 is the
+ * default; values below 1 count as 1.  Results do not depend on it.  Returns the previous value. */
+int32_t cephalo_gemm_side_by_side(int32_t kernels);
+
 /* Number of elements P of one layer's flat buffer, 4H^2 + 2HF + 9H + F (GPT-style) or 4H^2 + 3HF + 2H (Llama-style);
  * negative on a bad desc. */
 int64_t cephalo_layer_param_count(const cephalo_layer_desc* desc);

@@ -67,6 +67,7 @@ _dp = ctypes.POINTER(LayerDesc)
 SIGNATURES = {
     "cephalo_last_error": (ctypes.c_char_p, []),
     "cephalo_gemm_general_count": (ctypes.c_int64, []),
+    "cephalo_gemm_side_by_side": (ctypes.c_int32, [ctypes.c_int32]),
     "cephalo_layer_param_count": (_i64, [_dp]),
     "cephalo_layer_param_offsets": (ctypes.c_int, [_dp, ctypes.POINTER(_i64)]),
     "cephalo_layer_workspace_bytes": (ctypes.c_int, [_dp, _i32, ctypes.POINTER(_sz), ctypes.POINTER(_sz)]),
@@ -152,6 +153,10 @@ def cephalo_last_error():
 
 def cephalo_gemm_general_count():
     return int(lib().cephalo_gemm_general_count())
+
+
+def cephalo_gemm_side_by_side(kernels):
+    return int(lib().cephalo_gemm_side_by_side(int(kernels)))
 
 
 def cephalo_layer_param_count(desc):

@@ -544,6 +544,7 @@ int64_t gemm_general_count() { return general_count.load(std::memory_order_relax
 GemmSideBySide::GemmSideBySide(int kernels) : before(side_by_side) { side_by_side = kernels < 1 ? 1 : kernels; }
 GemmSideBySide::~GemmSideBySide() { side_by_side = before; }
 void GemmSideBySide::now(int kernels) { side_by_side = kernels < 1 ? 1 : kernels; }
+int gemm_set_side_by_side(int kernels) { const int was = side_by_side; side_by_side = kernels < 1 ? 1 : kernels; return was; }
 
 int launch_gemm_mfma(const GemmArgs<bf16>& a, hipStream_t s) {
   if (a.M <= 0 || a.N <= 0 || a.K <= 0) return fail(CEPHALO_EINVAL, "gemm: empty problem %dx%dx%d", a.M, a.N, a.K);

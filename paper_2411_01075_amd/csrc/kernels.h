@@ -138,6 +138,7 @@ struct GemmSideBySide {
   void now(int kernels);       // change the number for the launches that follow
   int before;
 };
+int gemm_set_side_by_side(int kernels);   // the same number, set for good; returns the previous value
 int64_t gemm_general_count();   // calls of launch_gemm_mfma that ended in launch_gemm_simple
 
 // ---------------------------------------------------------------------------------------

@@ -30,6 +30,7 @@ int check_attn(const cephalo_layer_desc* d, int m) {
 }
 }  // namespace
 
+extern "C" int32_t cephalo_gemm_side_by_side(int32_t kernels) { return cephalo::gemm_set_side_by_side(kernels); }
 extern "C" int64_t cephalo_gemm_general_count(void) { return cephalo::gemm_general_count(); }
 
 extern "C" int cephalo_op_gemm(int32_t dtype, const void* A, int64_t a_rs, int64_t a_cs,

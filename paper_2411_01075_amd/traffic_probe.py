@@ -1,5 +1,6 @@
 """Launches, three times each, the kernels whose HBM traffic the benchmark reports: the input-gradient GEMM of the
-largest workload's three N = H projections (through the transposed weight, as the layer's backward issues them), a
+largest workload's three N = H projections (through the transposed weight and on the tile the interleaved step runs
+them on, two side by side, as the layer's backward issues them), a
 1 GiB device copy (the calibration of the counters) and the shard Adam on a 64 Mi-element slice.  Meant to run under
 
     rocprofv3 --pmc FETCH_SIZE --output-format csv -d <dir> -o t -- python3 paper_2411_01075_amd/traffic_probe.py
@@ -17,6 +18,7 @@ import paper_2411_01075_amd as C  # noqa: E402
 
 T, H, F = 4096, 2048, 8192
 bt = torch.bfloat16
+C.cephalo_gemm_side_by_side(2)      # the tile choice of the step with two micro-batches in flight
 def dgrad(n_out, k_in, f32):
     # input gradient dX[T,k_in] = dY[T,n_out] W through W^T [k_in, n_out]
     dY = torch.randn(T, n_out, device='cuda').to(bt); WT = (torch.randn(k_in, n_out, device='cuda') * 0.02).to(bt)
