@@ -64,7 +64,7 @@ def main():
     ap.add_argument("--checkpoint", action="store_true",
                     help="stacks only: layer-boundary activation checkpointing with recomputation in the backward (one extra forward)")
     ap.add_argument("--single-stream", action="store_true",
-                    help="stacks only: one micro-batch at a time on one stream (the default runs two micro-batches side by side on two streams)")
+                    help="one micro-batch at a time on one stream (the default runs two micro-batches side by side on two streams)")
     ap.add_argument("--offload", action="store_true",
                     help="stacks only, implies --checkpoint: the boundary activations live in pinned host memory and move on a second stream")
     args = ap.parse_args()
@@ -145,8 +145,15 @@ def main():
         save = torch.empty(save_b, dtype=torch.uint8, device="cuda")
         scratch = torch.empty(scr_b, dtype=torch.uint8, device="cuda")
 
+        interleave = not args.single_stream and l > 1
+        if interleave:
+            side = torch.cuda.Stream()
+
         def step(t):
-            C.cephalo_share_layer_step(desc, pcomp, x, y, dy, dx, b, m, save, G, 1.0, scratch)
+            if interleave:
+                C.cephalo_share_layer_step_interleaved(desc, pcomp, x, y, dy, dx, b, m, save, G, 1.0, scratch, side)
+            else:
+                C.cephalo_share_layer_step(desc, pcomp, x, y, dy, dx, b, m, save, G, 1.0, scratch)
             C.cephalo_shard_adam(p32, G, mom, var, plow, P, off, ln, lr, 0.9, 0.999, 1e-8, t)
 
     for i in range(args.warmup):
@@ -165,10 +172,11 @@ def main():
         extras["loss"] = round(float(loss.item()), 4)
         extras["activation_checkpointing"] = bool(args.checkpoint or args.offload)
         extras["activation_offload"] = bool(args.offload)
-        extras["micro_batches_in_flight"] = 2 if interleave else 1
+
         if args.offload:
             extras["host_area_GB"] = round(host_area.numel() * 4 / 1e9, 2)
         extras["workspace_GB"] = round(ws.numel() / 1e9, 2)
+    extras["micro_batches_in_flight"] = 2 if interleave else 1
     if bf16:
         extras["whole_step_model_tflops"] = round(step_flops / (elapsed / args.steps) / 1e12, 1)
         extras["whole_step_frac_of_bf16_peak"] = round(step_flops / (elapsed / args.steps) / 1e12 / PEAK_BF16_TFLOPS, 4)
@@ -220,7 +228,7 @@ def main():
         lin = [("qkv", 3 * H, H), ("o", H, H), ("fc1", F, H), ("fc2", H, F)]
         legs = {}
 
-        pairs = stack and interleave      # per-micro-batch GEMMs run two side by side, one per stream, as in the step
+        pairs = interleave      # per-micro-batch GEMMs run two side by side, one per stream, as in the step
 
         def add_leg(key, fn, flops, count, alone=False):
             # enough back-to-back launches (about 30 ms) that the clocks settle where they sit during the step.

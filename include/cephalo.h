@@ -155,6 +155,18 @@ int cephalo_share_layer_step(const cephalo_layer_desc* desc, const void* flat_pa
                              float* flat_grad, float grad_scale,
                              void* scratch, size_t scratch_bytes, void* stream);
 
+/* The same with two micro-batches in flight: micro-batch j runs on stream j mod 2 (`stream` and `side_stream`, another
+ * stream of the same device at the default priority), so that the bandwidth-bound kernels of one run under the
+ * matrix-core kernels of the other and GEMMs with few output tiles share the compute units.  Every micro-batch's own
+ * kernel order and every reduction order are those of cephalo_share_layer_step: same results bit for bit, same work
+ * areas.  The call joins the streams before it returns: work enqueued on `stream` afterwards runs after the whole step. */
+int cephalo_share_layer_step_interleaved(const cephalo_layer_desc* desc, const void* flat_param,
+                                         const void* x, void* y, const void* dy, void* dx,
+                                         int32_t batch_share, int32_t micro_batch,
+                                         void* save, size_t save_bytes_total,
+                                         float* flat_grad, float grad_scale,
+                                         void* scratch, size_t scratch_bytes, void* stream, void* side_stream);
+
 /* acc[i] <- acc[i] + scale * g[i], i in [0, n): gradient accumulation across micro-batches
  * (Sec. 3.2) as a stand-alone pass.  acc, g device fp32, n >= 0. */
 int cephalo_grad_accum(float* acc, const float* g, float scale, int64_t n, void* stream);

@@ -76,6 +76,8 @@ SIGNATURES = {
     "cephalo_layer_bwd": (ctypes.c_int, [_dp, _vp, _vp, _vp, _vp, _i32, _vp, _sz, _vp, _f32, _i32, _vp, _sz, _vp]),
     "cephalo_share_layer_step": (ctypes.c_int, [_dp, _vp, _vp, _vp, _vp, _vp, _i32, _i32, _vp, _sz, _vp, _f32,
                                                 _vp, _sz, _vp]),
+    "cephalo_share_layer_step_interleaved": (ctypes.c_int, [_dp, _vp, _vp, _vp, _vp, _vp, _i32, _i32, _vp, _sz, _vp, _f32,
+                                                _vp, _sz, _vp, _vp]),
     "cephalo_grad_accum": (ctypes.c_int, [_vp, _vp, _f32, _i64, _vp]),
     "cephalo_shard_adam": (ctypes.c_int, [_vp, _vp, _vp, _vp, _vp, _i64, _i64, _i64, _f32, _f32, _f32, _f32, _i64, _vp]),
     "cephalo_cast_bf16": (ctypes.c_int, [_vp, _vp, _i64, _vp]),
@@ -205,6 +207,15 @@ def cephalo_share_layer_step(desc, flat_param, x, y, dy, dx, batch_share, micro_
                                           _ptr(save), save.numel() * save.element_size(),
                                           _ptr(flat_grad), grad_scale,
                                           _ptr(scratch), scratch.numel() * scratch.element_size(), _stream(stream)))
+
+def cephalo_share_layer_step_interleaved(desc, flat_param, x, y, dy, dx, batch_share, micro_batch, save, flat_grad,
+                                         grad_scale, scratch, side_stream, stream=None):
+    _check(lib().cephalo_share_layer_step_interleaved(ctypes.byref(desc), _ptr(flat_param), _ptr(x), _ptr(y), _ptr(dy), _ptr(dx),
+                                                      batch_share, micro_batch,
+                                                      _ptr(save), save.numel() * save.element_size(),
+                                                      _ptr(flat_grad), grad_scale,
+                                                      _ptr(scratch), scratch.numel() * scratch.element_size(), _stream(stream),
+                                                      _stream(side_stream)))
 
 
 def cephalo_grad_accum(acc, g, scale, n=None, stream=None):

@@ -38,7 +38,7 @@ extern "C" int cephalo_share_workspace_bytes(const cephalo_layer_desc* desc, int
                 batch_share, micro_batch);
   if (!save_bytes_total || !scratch_bytes) return fail(CEPHALO_EINVAL, "share_workspace_bytes: null output");
   *save_bytes_total = save_layout(*desc, batch_share).total;
-  *scratch_bytes = scratch_layout(*desc, micro_batch, batch_share).total;
+  *scratch_bytes = scratch_layout(*desc, micro_batch, batch_share, 2).total;
   return CEPHALO_OK;
 }
 
@@ -80,12 +80,13 @@ extern "C" int cephalo_layer_bwd(const cephalo_layer_desc* desc, const void* fla
   return run_bwd<bf16>(*desc, flat_param, xf, dyf, dxf, micro_batch, sv, flat_grad, grad_scale, accumulate, scratch, s);
 }
 
-extern "C" int cephalo_share_layer_step(const cephalo_layer_desc* desc, const void* flat_param,
-                                        const void* x, void* y, const void* dy, void* dx,
-                                        int32_t batch_share, int32_t micro_batch,
-                                        void* save, size_t save_bytes_total,
-                                        float* flat_grad, float grad_scale,
-                                        void* scratch, size_t scratch_bytes, void* stream) {
+namespace {
+int share_step_checked(const cephalo_layer_desc* desc, const void* flat_param,
+                       const void* x, void* y, const void* dy, void* dx,
+                       int32_t batch_share, int32_t micro_batch,
+                       void* save, size_t save_bytes_total,
+                       float* flat_grad, float grad_scale,
+                       void* scratch, size_t scratch_bytes, void* stream, void* side_stream) {
   TRY(check_io("share_layer_step", desc, micro_batch, {flat_param, x, y, dy, dx, save, flat_grad, scratch}));
   if (batch_share <= 0 || batch_share % micro_batch != 0)
     return fail(CEPHALO_EINVAL, "share_layer_step: batch share b = %d is not a positive multiple of micro-batch size m = %d",
@@ -96,14 +97,38 @@ extern "C" int cephalo_share_layer_step(const cephalo_layer_desc* desc, const vo
   const size_t need_save = save_layout(*desc, batch_share).total;
   if (save_bytes_total < need_save)
     return fail(CEPHALO_EWORKSPACE, "share_layer_step: save area %zu B < %zu B", save_bytes_total, need_save);
-  const size_t need = scratch_layout(*desc, micro_batch, batch_share).total;
+  const size_t need = scratch_layout(*desc, micro_batch, batch_share, 2).total;
   if (scratch_bytes < need) return fail(CEPHALO_EWORKSPACE, "share_layer_step: scratch %zu B < %zu B", scratch_bytes, need);
   hipStream_t s = static_cast<hipStream_t>(stream);
   const float* xf = static_cast<const float*>(x);
   float* yf = static_cast<float*>(y);
   const float* dyf = static_cast<const float*>(dy);
   float* dxf = static_cast<float*>(dx);
+  hipStream_t s2 = static_cast<hipStream_t>(side_stream);
   if (desc->dtype == CEPHALO_F32)
-    return run_share<float>(*desc, flat_param, xf, yf, dyf, dxf, batch_share, micro_batch, save, flat_grad, grad_scale, scratch, s);
-  return run_share<bf16>(*desc, flat_param, xf, yf, dyf, dxf, batch_share, micro_batch, save, flat_grad, grad_scale, scratch, s);
+    return run_share<float>(*desc, flat_param, xf, yf, dyf, dxf, batch_share, micro_batch, save, flat_grad, grad_scale, scratch, s, s2);
+  return run_share<bf16>(*desc, flat_param, xf, yf, dyf, dxf, batch_share, micro_batch, save, flat_grad, grad_scale, scratch, s, s2);
+}
+}  // namespace
+
+extern "C" int cephalo_share_layer_step(const cephalo_layer_desc* desc, const void* flat_param,
+                                        const void* x, void* y, const void* dy, void* dx,
+                                        int32_t batch_share, int32_t micro_batch,
+                                        void* save, size_t save_bytes_total,
+                                        float* flat_grad, float grad_scale,
+                                        void* scratch, size_t scratch_bytes, void* stream) {
+  return share_step_checked(desc, flat_param, x, y, dy, dx, batch_share, micro_batch, save, save_bytes_total, flat_grad, grad_scale,
+                            scratch, scratch_bytes, stream, nullptr);
+}
+
+extern "C" int cephalo_share_layer_step_interleaved(const cephalo_layer_desc* desc, const void* flat_param,
+                                                    const void* x, void* y, const void* dy, void* dx,
+                                                    int32_t batch_share, int32_t micro_batch,
+                                                    void* save, size_t save_bytes_total,
+                                                    float* flat_grad, float grad_scale,
+                                                    void* scratch, size_t scratch_bytes, void* stream, void* side_stream) {
+  if (!side_stream || side_stream == stream)
+    return fail(CEPHALO_EINVAL, "share_layer_step_interleaved: needs a side stream other than the compute stream");
+  return share_step_checked(desc, flat_param, x, y, dy, dx, batch_share, micro_batch, save, save_bytes_total, flat_grad, grad_scale,
+                            scratch, scratch_bytes, stream, side_stream);
 }

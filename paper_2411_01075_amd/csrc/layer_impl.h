@@ -504,26 +504,75 @@ int run_bwd(const cephalo_layer_desc& d, const void* P, const float* x, const fl
   return layer_bwd_params_t<T>(d, dy, dyl, m * d.seq, ln_bwd_blocks(m * d.seq), sv, w, G, scale, acc, s);
 }
 
+// The two compute streams of an interleaved step.  fork: the side stream continues from where the main stream is;
+// join: the main stream continues only after the side stream's work so far.  Without interleave both do nothing.
+struct Streams {
+  hipStream_t main = nullptr, side = nullptr;
+  bool on = false;
+  hipEvent_t forked, joined;
+  int err = CEPHALO_OK;
+  void check(hipError_t e, const char* what) {
+    if (e != hipSuccess && err == CEPHALO_OK) err = fail(CEPHALO_EHIP, "interleaved step: %s: %s", what, hipGetErrorString(e));
+  }
+  int open() {
+    if (!on) return CEPHALO_OK;
+    check(hipEventCreateWithFlags(&forked, hipEventDisableTiming), "event");
+    check(hipEventCreateWithFlags(&joined, hipEventDisableTiming), "event");
+    return err;
+  }
+  void fork() {
+    if (!on) return;
+    check(hipEventRecord(forked, main), "record");
+    check(hipStreamWaitEvent(side, forked, 0), "wait");
+  }
+  void join() {
+    if (!on) return;
+    check(hipEventRecord(joined, side), "record");
+    check(hipStreamWaitEvent(main, joined, 0), "wait");
+  }
+  int close() {          // the call ends joined: whoever waits for the main stream has waited for everything
+    if (!on) return CEPHALO_OK;
+    join();
+    check(hipEventDestroy(forked), "event");
+    check(hipEventDestroy(joined), "event");
+    return err;
+  }
+};
+
 // Whole share: forward of every micro-batch, data-path backward of every micro-batch, then ONE parameter pass over
 // all b*S tokens (the dY operands and the saved activations of all micro-batches are contiguous by construction).
 template <typename T>
 int run_share(const cephalo_layer_desc& d, const void* Pv, const float* x, float* y, const float* dy, float* dx,
-              int b, int m, void* save, float* G, float scale, void* scratch, hipStream_t s) {
+              int b, int m, void* save, float* G, float scale, void* scratch, hipStream_t s, hipStream_t side = nullptr) {
   const T* P = static_cast<const T*>(Pv);
   const SaveLayout L = save_layout(d, b);
-  const ScratchLayout W = scratch_layout(d, m, b);
+  const ScratchLayout W = scratch_layout(d, m, b, 2);
   const int l = b / m;
   const size_t act = (size_t)m * d.seq * d.hidden;   // elements of one micro-batch of x / y / dy / dx
-  for (int j = 0; j < l; ++j)
-    TRY(layer_fwd_t<T>(d, P, x + j * act, y + j * act, m, saved_at<T>(save, L, d, j * m), s));
+  // side: micro-batch j runs on stream j % 2 (two in flight, see Streams); what the micro-batches share is made first
+  const int nst = side ? 2 : 1;
+  hipStream_t st[2] = {s, side ? side : s};
+  Streams J;
+  J.main = s; J.side = side; J.on = side != nullptr;
+  TRY(J.open());
+  struct JCloser { Streams& j; ~JCloser() { (void)j.close(); } } jcloser{J};
   const Work<T> w0 = work_at<T>(scratch, W, d, 0, 0, m);
   TRY(make_lowp<T>(w0.dyl, dy, (int64_t)l * act, s));
   const T* dyl = lowp_of<T>(dy, w0.dyl);
   TRY(prepare_dgrad_weights<T>(d, P, w0.wT, s));
-  for (int j = 0; j < l; ++j)
-    TRY(layer_bwd_data_t<T>(d, P, x + j * act, dy + j * act, dyl + j * act, dx + j * act, (T*)nullptr, m,
-                            saved_at<T>(save, L, d, j * m), work_at<T>(scratch, W, d, j * m, j, m), s));
-  return layer_bwd_params_t<T>(d, dy, dyl, b * d.seq, l * ln_bwd_blocks(m * d.seq), saved_at<T>(save, L, d, 0), w0, G, scale, 0, s);
+  J.fork();
+  {
+    GemmSideBySide hint(nst);
+    for (int j = 0; j < l; ++j)
+      TRY(layer_fwd_t<T>(d, P, x + j * act, y + j * act, m, saved_at<T>(save, L, d, j * m), st[j % nst]));
+    for (int j = 0; j < l; ++j)
+      TRY(layer_bwd_data_t<T>(d, P, x + j * act, dy + j * act, dyl + j * act, dx + j * act, (T*)nullptr, m,
+                              saved_at<T>(save, L, d, j * m), work_at<T>(scratch, W, d, j * m, j, m, j % nst), st[j % nst]));
+  }
+  J.join();
+  J.fork();      // the parameter pass's reductions beside its GEMMs
+  TRY(layer_bwd_params_t<T>(d, dy, dyl, b * d.seq, l * ln_bwd_blocks(m * d.seq), saved_at<T>(save, L, d, 0), w0, G, scale, 0, s, st[1]));
+  return J.err;   // (the closer joins)
 }
 
 int check_io(const char* who, const cephalo_layer_desc* d, int m, std::initializer_list<const void*> ptrs) {

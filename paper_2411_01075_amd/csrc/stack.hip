@@ -331,41 +331,6 @@ struct Boundary {
   }
 };
 
-// The two compute streams of an interleaved step.  fork: the side stream continues from where the main stream is;
-// join: the main stream continues only after the side stream's work so far.  Without interleave both do nothing.
-struct Streams {
-  hipStream_t main = nullptr, side = nullptr;
-  bool on = false;
-  hipEvent_t forked, joined;
-  int err = CEPHALO_OK;
-  void check(hipError_t e, const char* what) {
-    if (e != hipSuccess && err == CEPHALO_OK) err = fail(CEPHALO_EHIP, "stack_step (interleave): %s: %s", what, hipGetErrorString(e));
-  }
-  int open() {
-    if (!on) return CEPHALO_OK;
-    check(hipEventCreateWithFlags(&forked, hipEventDisableTiming), "event");
-    check(hipEventCreateWithFlags(&joined, hipEventDisableTiming), "event");
-    return err;
-  }
-  void fork() {
-    if (!on) return;
-    check(hipEventRecord(forked, main), "record");
-    check(hipStreamWaitEvent(side, forked, 0), "wait");
-  }
-  void join() {
-    if (!on) return;
-    check(hipEventRecord(joined, side), "record");
-    check(hipStreamWaitEvent(main, joined, 0), "wait");
-  }
-  int close() {          // the call ends joined: whoever waits for the main stream has waited for everything
-    if (!on) return CEPHALO_OK;
-    join();
-    check(hipEventDestroy(forked), "event");
-    check(hipEventDestroy(joined), "event");
-    return err;
-  }
-};
-
 template <typename T>
 int run_stack(const cephalo_stack_desc& d, const void* Pv, const int* ids, const int* targets, int b, int m,
               float* G, float scale, float* loss_out, void* ws, float* host_area, hipStream_t s, hipStream_t copy_in, hipStream_t copy_out,

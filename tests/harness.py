@@ -42,7 +42,7 @@ def assert_close(name, got, ref, dtype, scale=1.0):
     return mx, mean
 
 
-def gpu_share_step(cfg, tensors, x, dy, grad_scale=1.0, via_share_call=True):
+def gpu_share_step(cfg, tensors, x, dy, grad_scale=1.0, via_share_call=True, interleave=False):
     """Runs forward+backward of the whole share on the GPU.  Returns y, dx (float64 numpy) and G (float32)."""
     desc = C.desc_from_config(cfg)
     dt = tdtype(cfg)
@@ -63,7 +63,11 @@ def gpu_share_step(cfg, tensors, x, dy, grad_scale=1.0, via_share_call=True):
         save_b, scr_b = C.cephalo_share_workspace_bytes(desc, b, m)
         save = torch.empty(save_b, dtype=torch.uint8, device="cuda")
         scratch = torch.empty(scr_b, dtype=torch.uint8, device="cuda")
-        C.cephalo_share_layer_step(desc, flat, xd, yd, dyd, dxd, b, m, save, G, grad_scale, scratch)
+        if interleave:      # two micro-batches in flight on two streams; the call joins them into the current stream
+            C.cephalo_share_layer_step_interleaved(desc, flat, xd, yd, dyd, dxd, b, m, save, G, grad_scale, scratch, torch.cuda.Stream())
+            torch.cuda.current_stream().synchronize()
+        else:
+            C.cephalo_share_layer_step(desc, flat, xd, yd, dyd, dxd, b, m, save, G, grad_scale, scratch)
     else:
         save_b, scr_b = C.cephalo_layer_workspace_bytes(desc, m)
         save = torch.empty(save_b * l, dtype=torch.uint8, device="cuda")

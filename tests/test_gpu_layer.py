@@ -60,6 +60,34 @@ def test_per_microbatch_calls_match_share_call(case):
     Hn.compare_share(cfg, b, ref)
 
 
+@pytest.mark.parametrize("case", ["f32_ragged", "bf16_c2_small", "bf16_c3_small", "bf16_vitl"])
+def test_two_micro_batches_in_flight_give_identical_results(case):
+    """The share call with micro-batches alternating between two streams: every micro-batch's kernels and every
+    reduction keep their order, so y, dx and the gradient are bit-identical to the one-stream call (an odd number of
+    micro-batches included).  Twice, the second time over work areas holding the first run's values."""
+    cfg = CASES[case]
+    tensors = draw_layer_params(cfg, perturbed=True)
+    x, dy = draw_activations(cfg)
+    a = Hn.gpu_share_step(cfg, tensors, x, dy, grad_scale=0.75)
+    for repeat in range(2):
+        b = Hn.gpu_share_step(cfg, tensors, x, dy, grad_scale=0.75, interleave=True)
+        assert np.array_equal(a[0], b[0]) and np.array_equal(a[1], b[1]) and np.array_equal(a[2], b[2])
+
+
+def test_interleaved_share_call_needs_a_second_stream():
+    cfg = CASES["f32_ragged"]
+    desc = C.desc_from_config(cfg)
+    P = C.cephalo_layer_param_count(desc)
+    b, m = cfg.batch_share, cfg.micro_batch
+    x = torch.zeros(b, cfg.seq, cfg.hidden, device="cuda")
+    y, dx = torch.empty_like(x), torch.empty_like(x)
+    flat, G = torch.zeros(P, device="cuda"), torch.zeros(P, device="cuda")
+    save_b, scr_b = C.cephalo_share_workspace_bytes(desc, b, m)
+    save, scratch = torch.empty(save_b, dtype=torch.uint8, device="cuda"), torch.empty(scr_b, dtype=torch.uint8, device="cuda")
+    with pytest.raises(C.CephaloError):
+        C.cephalo_share_layer_step_interleaved(desc, flat, x, y, x, dx, b, m, save, G, 1.0, scratch, torch.cuda.current_stream())
+
+
 def test_grad_scale_is_eq1_factor():
     """Accumulating with scale s equals s times the unit-scale result (Eq. 1's factor enters linearly)."""
     cfg = CASES["f32_ragged"]

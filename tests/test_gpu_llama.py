@@ -25,7 +25,7 @@ CASES = {
 }
 
 
-def run_gpu(cfg, params, x, dy, scale, via_share_call):
+def run_gpu(cfg, params, x, dy, scale, via_share_call, interleave=False):
     desc = C.desc_from_config(cfg)
     assert desc.kind == C.LAYER_LLAMA
     flat32 = torch.from_numpy(C.flatten_layer_params(desc, params)).cuda()
@@ -41,7 +41,10 @@ def run_gpu(cfg, params, x, dy, scale, via_share_call):
     if via_share_call:
         save_b, scr_b = C.cephalo_share_workspace_bytes(desc, b, m)
         save = torch.empty(save_b, dtype=torch.uint8, device="cuda"); scratch = torch.empty(scr_b, dtype=torch.uint8, device="cuda")
-        C.cephalo_share_layer_step(desc, flat, xd, yd, dyd, dxd, b, m, save, G, scale, scratch)
+        if interleave:
+            C.cephalo_share_layer_step_interleaved(desc, flat, xd, yd, dyd, dxd, b, m, save, G, scale, scratch, torch.cuda.Stream())
+        else:
+            C.cephalo_share_layer_step(desc, flat, xd, yd, dyd, dxd, b, m, save, G, scale, scratch)
     else:
         save_b, scr_b = C.cephalo_layer_workspace_bytes(desc, m)
         save = torch.empty(save_b * (b // m), dtype=torch.uint8, device="cuda"); scratch = torch.empty(scr_b, dtype=torch.uint8, device="cuda")
@@ -86,6 +89,13 @@ def test_llama_is_reproducible():
     a = run_gpu(cfg, params, x, dy, 1.0, True)
     b = run_gpu(cfg, params, x, dy, 1.0, True)
     assert np.array_equal(a[0], b[0]) and np.array_equal(a[1], b[1]) and np.array_equal(a[2], b[2])
+    for case in ("bf16_mini", "bf16_d128"):        # two micro-batches in flight on two streams: the same bits
+        cfg = CASES[case]
+        params = draw_layer_params(cfg, perturbed=True)
+        x, dy = draw_activations(cfg)
+        a = run_gpu(cfg, params, x, dy, 1.0, True)
+        b = run_gpu(cfg, params, x, dy, 1.0, True, interleave=True)
+        assert np.array_equal(a[0], b[0]) and np.array_equal(a[1], b[1]) and np.array_equal(a[2], b[2])
 
 
 def test_llama_7b_layer_full_size():
