@@ -56,9 +56,9 @@ def main():
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=8)
     ap.add_argument("--warmup", type=int, default=2)
-    ap.add_argument("--workload", default="c5", choices=["c1", "c2", "c3", "c4", "c5", "l7b", "ltiny", "vitl"],
+    ap.add_argument("--workload", default="c5", choices=["c1", "c2", "c3", "c4", "c5", "l7b", "ltiny", "vitl", "vitg", "g27"],
                     help="c5 (default) is the metric's workload; l7b: a Llama-style 7B-class layer; ltiny: a TinyLlama-shaped 22-layer "
-                         "stack; vitl: a ViT-Large-shaped layer")
+                         "stack; vitl / vitg: ViT-Large- / ViT-G-shaped layers; g27: a GPT 2.7B-shaped layer (80 heads of 32)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-legs", action="store_true", help="skip the per-kernel legs (whole step only)")
     ap.add_argument("--checkpoint", action="store_true",

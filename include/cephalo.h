@@ -67,7 +67,8 @@ extern "C" {
  * projection, scores scaled by 1/sqrt(d), optional causal mask, no dropout (Sec. 2.1 names
  * only "self-attention and feed-forward"; this form is the library's reading). */
 typedef struct cephalo_layer_desc {
-  int32_t hidden;   /* H, a multiple of heads; head dim d = H/heads must be 64 or 128 in BF16 mode */
+  int32_t hidden;   /* H, a multiple of heads; head dim d = H/heads <= 128, in BF16 mode a multiple of 8 (widths other than
+                       64 and 128 run on the next of those two tiles with the further columns held at zero) */
   int32_t heads;    /* A */
   int32_t mlp;      /* F */
   int32_t seq;      /* S, tokens per sample */

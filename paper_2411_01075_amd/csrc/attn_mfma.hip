@@ -47,14 +47,15 @@ template <int D, int ROWS = TILE, int THREADS = kThreads> struct Tile {
   static constexpr int ELEMS = ROWS * LD;
   static constexpr int PER_THREAD = ROWS * D / 8 / THREADS;
 
-  // rows [row0, row0+ROWS) of a [*, ld] matrix, columns [0, D); rows >= nrows read as zero
-  __device__ static void load_global(const bf16* __restrict__ g, int64_t ld, int row0, int nrows, bf16x8 (&reg)[PER_THREAD]) {
+  // rows [row0, row0+ROWS) of a [*, ld] matrix, columns [0, D); rows >= nrows and columns >= d (the head's own width,
+  // a multiple of 8, when it is narrower than the tile) read as zero
+  __device__ static void load_global(const bf16* __restrict__ g, int64_t ld, int row0, int nrows, bf16x8 (&reg)[PER_THREAD], int d) {
 #pragma unroll
     for (int p = 0; p < PER_THREAD; ++p) {
       const int v = threadIdx.x + THREADS * p;
       const int row = v / (D / 8), c = (v % (D / 8)) * 8;
       bf16x8 val = {0, 0, 0, 0, 0, 0, 0, 0};
-      if (row0 + row < nrows) val = *reinterpret_cast<const bf16x8*>(g + (int64_t)(row0 + row) * ld + c);
+      if (row0 + row < nrows && c < d) val = *reinterpret_cast<const bf16x8*>(g + (int64_t)(row0 + row) * ld + c);
       reg[p] = val;
     }
   }
@@ -66,10 +67,13 @@ template <int D, int ROWS = TILE, int THREADS = kThreads> struct Tile {
   // D = 64 keeps the register path.)
   static constexpr bool DIRECT = D == 128;
   static constexpr int NW = THREADS / 64, ROW_LOADS = ROWS / NW, LANE_BYTES = 4;
-  __device__ static void stage(__amdgpu_buffer_rsrc_t rsrc, unsigned col_bytes, unsigned ld_bytes, int row0, int nrows, lds_bf16* lds) {
+  // Lanes past the head's own width d (2*d bytes of the 256) carry an offset beyond the buffer's range: the hardware's
+  // range check makes them write zeros.
+  __device__ static void stage(__amdgpu_buffer_rsrc_t rsrc, unsigned col_bytes, unsigned ld_bytes, int row0, int nrows, lds_bf16* lds, int d) {
     static_assert(DIRECT, "rows of 256 bytes only");
     const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
-    const unsigned lane_off = (threadIdx.x & 63) * LANE_BYTES;
+    const unsigned in_row = (threadIdx.x & 63) * LANE_BYTES;
+    const unsigned lane_off = in_row < 2u * (unsigned)d ? in_row : 0x80000000u;
 #pragma unroll
     for (int j = 0; j < ROW_LOADS; ++j) {
       const int r = j * NW + wave;
@@ -107,13 +111,14 @@ template <int D, int ROWS = TILE, int THREADS = kThreads> struct Tile {
 
 // fragment of 32 rows of a row-major [*, ld] matrix straight from global memory (rows = MFMA rows)
 template <int D>
-__device__ void load_row_frags(const bf16* __restrict__ g, int64_t ld, int row0, int nrows, bf16x8 (&f)[D / 16]) {
+__device__ void load_row_frags(const bf16* __restrict__ g, int64_t ld, int row0, int nrows, bf16x8 (&f)[D / 16], int d) {
   const int lane = threadIdx.x & 63;
   const int row = row0 + (lane & 31);
 #pragma unroll
   for (int kk = 0; kk < D / 16; ++kk) {
     bf16x8 val = {0, 0, 0, 0, 0, 0, 0, 0};
-    if (row < nrows) val = *reinterpret_cast<const bf16x8*>(g + (int64_t)row * ld + kk * 16 + (lane >> 5) * 8);
+    const int c = kk * 16 + (lane >> 5) * 8;
+    if (row < nrows && c < d) val = *reinterpret_cast<const bf16x8*>(g + (int64_t)row * ld + c);
     f[kk] = val;
   }
 }
@@ -144,7 +149,7 @@ __device__ __forceinline__ bf16x8 pack8(const f32x16& v, int e0) {
 
 // accumulator rows d (4 consecutive per group) of column token -> out[token][d0 + d], scaled
 template <int D>
-__device__ void store_transposed(const f32x16 (&acc)[D / 32], bf16* __restrict__ out, int64_t ld, int token, int ntokens, float mul) {
+__device__ void store_transposed(const f32x16 (&acc)[D / 32], bf16* __restrict__ out, int64_t ld, int token, int ntokens, float mul, int d) {
   if (token >= ntokens) return;
   const int h = (threadIdx.x & 63) >> 5;
 #pragma unroll
@@ -154,7 +159,8 @@ __device__ void store_transposed(const f32x16 (&acc)[D / 32], bf16* __restrict__
       bf16x4 v;
 #pragma unroll
       for (int i = 0; i < 4; ++i) v[i] = (bf16)(acc[dt][4 * j + i] * mul);
-      *reinterpret_cast<bf16x4*>(out + (int64_t)token * ld + dt * 32 + 8 * j + 4 * h) = v;
+      const int d0 = dt * 32 + 8 * j + 4 * h;
+      if (d0 < d) *reinterpret_cast<bf16x4*>(out + (int64_t)token * ld + d0) = v;      // (d is a multiple of 8: a group of 4 is in or out)
     }
 }
 
@@ -162,15 +168,16 @@ __device__ void store_transposed(const f32x16 (&acc)[D / 32], bf16* __restrict__
 // the angle of its position, rot[token][i] = (cos, sin), so that what is stored is the gradient before the rotation.
 template <int D>
 __device__ void store_transposed_unrotated(const f32x16 (&acc)[D / 32], bf16* __restrict__ out, int64_t ld, int token, int ntokens, float mul,
-                                           const float* __restrict__ rot) {
+                                           const float* __restrict__ rot, int d) {
   if (token >= ntokens) return;
   const int h = (threadIdx.x & 63) >> 5;
-  const f32x4* cs = reinterpret_cast<const f32x4*>(rot + (int64_t)token * D);      // D/2 pairs of (cos, sin) per position
+  const f32x4* cs = reinterpret_cast<const f32x4*>(rot + (int64_t)token * d);      // d/2 pairs of (cos, sin) per position
 #pragma unroll
   for (int dt = 0; dt < D / 32; ++dt)
 #pragma unroll
     for (int j = 0; j < 4; ++j) {
       const int d0 = dt * 32 + 8 * j + 4 * h;
+      if (d0 >= d) continue;
       const f32x4 r = cs[d0 / 4];                                                   // pairs d0/2 and d0/2 + 1
       const float e0 = acc[dt][4 * j] * mul, o0 = acc[dt][4 * j + 1] * mul, e1 = acc[dt][4 * j + 2] * mul, o1 = acc[dt][4 * j + 3] * mul;
       bf16x4 v;
@@ -193,10 +200,11 @@ attn_fwd_kernel(const bf16* __restrict__ qkv, bf16* __restrict__ O, float* __res
   auto Vs = [&](int st) { return smem + st * 2 * TL::ELEMS + TL::ELEMS; };
 
   const int a = blockIdx.y, n = blockIdx.z;
+  const int d = H / A;        // the head's own width: D, or less (a multiple of 8) with the tiles' further columns held at zero
   const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);   // scalar: tests on a wavefront's rows become real branches
   const int lane = threadIdx.x & 63, h = lane >> 5;
   const int64_t ld = 3 * (int64_t)H;
-  const bf16* base = qkv + (int64_t)n * S * ld + a * D;
+  const bf16* base = qkv + (int64_t)n * S * ld + a * d;
   const float c2 = scale * kLog2e;
   // Under a causal mask the work of a query tile grows with its index, and a launch has about as many blocks as the
   // chip has slots, so nothing would even the load out: each block takes tile x and then tile ntq-1-x, whose key
@@ -209,7 +217,7 @@ attn_fwd_kernel(const bf16* __restrict__ qkv, bf16* __restrict__ O, float* __res
   const int q = q0 + (lane & 31);
 
   bf16x8 qf[D / 16];
-  load_row_frags<D>(base, ld, q0, S, qf);
+  load_row_frags<D>(base, ld, q0, S, qf, d);
 
   f32x16 o[D / 32];
 #pragma unroll
@@ -221,8 +229,8 @@ attn_fwd_kernel(const bf16* __restrict__ qkv, bf16* __restrict__ O, float* __res
   const int kv_end = CAUSAL ? min(S, qt * 128 + 128) : S;
   const int ntiles = (kv_end + TILE - 1) / TILE;
   bf16x8 rk[TL::PER_THREAD], rv[TL::PER_THREAD];
-  TL::load_global(base + H, ld, 0, S, rk);
-  TL::load_global(base + 2 * H, ld, 0, S, rv);
+  TL::load_global(base + H, ld, 0, S, rk, d);
+  TL::load_global(base + 2 * H, ld, 0, S, rv, d);
   TL::store_lds(Ks(0), rk);
   TL::store_lds(Vs(0), rv);
   __syncthreads();
@@ -230,8 +238,8 @@ attn_fwd_kernel(const bf16* __restrict__ qkv, bf16* __restrict__ O, float* __res
   for (int kt = 0; kt < ntiles; ++kt) {
     const int cur = kt & 1, t0 = kt * TILE;
     if (kt + 1 < ntiles) {
-      TL::load_global(base + H, ld, t0 + TILE, S, rk);
-      TL::load_global(base + 2 * H, ld, t0 + TILE, S, rv);
+      TL::load_global(base + H, ld, t0 + TILE, S, rk, d);
+      TL::load_global(base + 2 * H, ld, t0 + TILE, S, rv, d);
     }
     if (!CAUSAL || t0 <= q0 + 31) {
       // All K fragments of the tile are read before the first MFMA needs one, and the two 32-key blocks accumulate
@@ -312,7 +320,7 @@ attn_fwd_kernel(const bf16* __restrict__ qkv, bf16* __restrict__ O, float* __res
   }
   const float l_tot = l_run + __shfl_xor(l_run, 32, 64);
   const float inv = 1.0f / l_tot;
-  store_transposed<D>(o, O + (int64_t)n * S * H + a * D, H, q, S, inv);
+  store_transposed<D>(o, O + (int64_t)n * S * H + a * d, H, q, S, inv, d);
   if (h == 0 && q < S) lse[((int64_t)n * A + a) * S + q] = (m_run + __builtin_amdgcn_logf(l_tot)) * kLn2;
   }   // pass
 }
@@ -335,13 +343,14 @@ attn_fwd8_kernel(const bf16* __restrict__ qkv, bf16* __restrict__ O, float* __re
   auto Vs = [&](int st) { return smem + st * 2 * TL::ELEMS + TL::ELEMS; };
 
   const int a = blockIdx.y, n = blockIdx.z;
+  const int d = H / A;        // the head's own width: D, or less (a multiple of 8) with the tiles' further columns held at zero
   const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);   // scalar: tests on a wavefront's rows become real branches
   const int lane = threadIdx.x & 63, h = lane >> 5;
   const int qsub = wave & 3, kh = wave >> 2;        // block of 32 queries, half of the staged keys
   const int64_t ld = 3 * (int64_t)H;
-  const bf16* base = qkv + (int64_t)n * S * ld + a * D;
+  const bf16* base = qkv + (int64_t)n * S * ld + a * d;
   const __amdgpu_buffer_rsrc_t rs_qkv = make_rsrc(qkv + (int64_t)n * S * ld, (unsigned)(S * ld * 2));
-  const unsigned k_bytes = (unsigned)((H + a * D) * 2), v_bytes = (unsigned)((2 * H + a * D) * 2);
+  const unsigned k_bytes = (unsigned)((H + a * d) * 2), v_bytes = (unsigned)((2 * H + a * d) * 2);
   const float c2 = scale * kLog2e;
   const int ntq = (S + 127) / 128;                  // causal: query tile x, then its mirror tile (equal work per block)
   for (int pass = 0; pass < (CAUSAL ? 2 : 1); ++pass) {
@@ -351,7 +360,7 @@ attn_fwd8_kernel(const bf16* __restrict__ qkv, bf16* __restrict__ O, float* __re
     const int q = q0 + (lane & 31);
 
     bf16x8 qf[D / 16];
-    load_row_frags<D>(base, ld, q0, S, qf);
+    load_row_frags<D>(base, ld, q0, S, qf, d);
     f32x16 o[D / 32];
 #pragma unroll
     for (int dt = 0; dt < D / 32; ++dt)
@@ -363,11 +372,11 @@ attn_fwd8_kernel(const bf16* __restrict__ qkv, bf16* __restrict__ O, float* __re
     const int ntiles = (kv_end + 127) / 128;
     bf16x8 rk[TL::DIRECT ? 1 : TL::PER_THREAD], rv[TL::DIRECT ? 1 : TL::PER_THREAD];   // register staging (D = 64)
     if constexpr (TL::DIRECT) {
-      TL::stage(rs_qkv, k_bytes, (unsigned)ld * 2, 0, S, Ks(0));
-      TL::stage(rs_qkv, v_bytes, (unsigned)ld * 2, 0, S, Vs(0));
+      TL::stage(rs_qkv, k_bytes, (unsigned)ld * 2, 0, S, Ks(0), d);
+      TL::stage(rs_qkv, v_bytes, (unsigned)ld * 2, 0, S, Vs(0), d);
     } else {
-      TL::load_global(base + H, ld, 0, S, rk);
-      TL::load_global(base + 2 * H, ld, 0, S, rv);
+      TL::load_global(base + H, ld, 0, S, rk, d);
+      TL::load_global(base + 2 * H, ld, 0, S, rv, d);
       TL::store_lds(Ks(0), rk);
       TL::store_lds(Vs(0), rv);
     }
@@ -378,11 +387,11 @@ attn_fwd8_kernel(const bf16* __restrict__ qkv, bf16* __restrict__ O, float* __re
       const int cur = kt & 1;
       if (kt + 1 < ntiles) {                           // the next stage flies meanwhile
         if constexpr (TL::DIRECT) {
-          TL::stage(rs_qkv, k_bytes, (unsigned)ld * 2, (kt + 1) * 128, S, Ks(cur ^ 1));
-          TL::stage(rs_qkv, v_bytes, (unsigned)ld * 2, (kt + 1) * 128, S, Vs(cur ^ 1));
+          TL::stage(rs_qkv, k_bytes, (unsigned)ld * 2, (kt + 1) * 128, S, Ks(cur ^ 1), d);
+          TL::stage(rs_qkv, v_bytes, (unsigned)ld * 2, (kt + 1) * 128, S, Vs(cur ^ 1), d);
         } else {
-          TL::load_global(base + H, ld, (kt + 1) * 128, S, rk);
-          TL::load_global(base + 2 * H, ld, (kt + 1) * 128, S, rv);
+          TL::load_global(base + H, ld, (kt + 1) * 128, S, rk, d);
+          TL::load_global(base + 2 * H, ld, (kt + 1) * 128, S, rv, d);
         }
       }
       const int t0 = kt * 128 + kh * 64;            // this wavefront's 64 keys
@@ -480,7 +489,7 @@ attn_fwd8_kernel(const bf16* __restrict__ qkv, bf16* __restrict__ O, float* __re
       const float l = l_run * a0 + l1 * a1;
       const float l_tot = l + __shfl_xor(l, 32, 64);
       const float inv = 1.0f / l_tot;
-      store_transposed<D>(o, O + (int64_t)n * S * H + a * D, H, q, S, inv);
+      store_transposed<D>(o, O + (int64_t)n * S * H + a * d, H, q, S, inv, d);
       if (h == 0 && q < S) lse[((int64_t)n * A + a) * S + q] = (m + __builtin_amdgcn_logf(l_tot)) * kLn2;
     }
     __syncthreads();     // the merge area is staged over again by the next pass
@@ -509,6 +518,24 @@ attn_dvec_kernel(const bf16* __restrict__ O, const bf16* __restrict__ dO, float*
   }
 }
 
+// the same for a head width d that is not a power of two: one thread per (token, head), d/8 vectors each
+__global__ void __launch_bounds__(kThreads)
+attn_dvec_any_kernel(const bf16* __restrict__ O, const bf16* __restrict__ dO, float* __restrict__ dvec, int rows, int S, int H, int A) {
+  const int64_t idx = (int64_t)blockIdx.x * kThreads + threadIdx.x;
+  if (idx >= (int64_t)rows * A) return;
+  const int row = (int)(idx / A), a = (int)(idx % A), d = H / A;
+  const int n = row / S, s = row % S;
+  float acc = 0.f;
+  for (int v = 0; v < d / 8; ++v) {
+    float a8[8], b8[8];
+    load_vec<bf16>(O + (int64_t)row * H + a * d + v * 8, a8);
+    load_vec<bf16>(dO + (int64_t)row * H + a * d + v * 8, b8);
+#pragma unroll
+    for (int i = 0; i < 8; ++i) acc += a8[i] * b8[i];
+  }
+  dvec[((int64_t)n * A + a) * S + s] = acc;
+}
+
 // ------------------------------------------------------------------------------------ dQ
 // A block owns 128 queries (causal: tile x, then its mirror tile) and walks the keys they see in stages of 128.  Eight
 // wavefronts, as in the forward kernel: wavefront w takes the 32 queries of block w & 3 and the 64 keys of half w >> 2
@@ -527,13 +554,14 @@ attn_dq_kernel(const bf16* __restrict__ qkv, const bf16* __restrict__ dO, const 
   auto Vs = [&](int st) { return smem + st * 2 * TL::ELEMS + TL::ELEMS; };
 
   const int a = blockIdx.y, n = blockIdx.z;
+  const int d = H / A;        // the head's own width: D, or less (a multiple of 8) with the tiles' further columns held at zero
   const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);   // scalar: tests on a wavefront's rows become real branches
   const int lane = threadIdx.x & 63, h = lane >> 5;
   const int qsub = wave & 3, kh = wave >> 2;        // block of 32 queries, half of the staged keys
   const int64_t ld = 3 * (int64_t)H;
-  const bf16* base = qkv + (int64_t)n * S * ld + a * D;
+  const bf16* base = qkv + (int64_t)n * S * ld + a * d;
   const __amdgpu_buffer_rsrc_t rs_qkv = make_rsrc(qkv + (int64_t)n * S * ld, (unsigned)(S * ld * 2));
-  const unsigned k_bytes = (unsigned)((H + a * D) * 2), v_bytes = (unsigned)((2 * H + a * D) * 2);
+  const unsigned k_bytes = (unsigned)((H + a * d) * 2), v_bytes = (unsigned)((2 * H + a * d) * 2);
   const float c2 = scale * kLog2e;
   const int ntq = (S + 127) / 128;                 // causal: query tiles x and ntq-1-x in turn (equal work per block)
   for (int pass = 0; pass < (CAUSAL ? 2 : 1); ++pass) {
@@ -543,8 +571,8 @@ attn_dq_kernel(const bf16* __restrict__ qkv, const bf16* __restrict__ dO, const 
   const int q = q0 + (lane & 31);
 
   bf16x8 qf[D / 16], dof[D / 16];
-  load_row_frags<D>(base, ld, q0, S, qf);
-  load_row_frags<D>(dO + (int64_t)n * S * H + a * D, H, q0, S, dof);
+  load_row_frags<D>(base, ld, q0, S, qf, d);
+  load_row_frags<D>(dO + (int64_t)n * S * H + a * d, H, q0, S, dof, d);
   const int64_t stat = ((int64_t)n * A + a) * S + q;
   const float lse2 = (q < S) ? lse[stat] * kLog2e : 0.f;
   const float dv = (q < S) ? dvec[stat] : 0.f;
@@ -559,11 +587,11 @@ attn_dq_kernel(const bf16* __restrict__ qkv, const bf16* __restrict__ dO, const 
   const int ntiles = (kv_end + 127) / 128;
   bf16x8 rk[TL::DIRECT ? 1 : TL::PER_THREAD], rv[TL::DIRECT ? 1 : TL::PER_THREAD];   // register staging (D = 64)
   if constexpr (TL::DIRECT) {
-    TL::stage(rs_qkv, k_bytes, (unsigned)ld * 2, 0, S, Ks(0));
-    TL::stage(rs_qkv, v_bytes, (unsigned)ld * 2, 0, S, Vs(0));
+    TL::stage(rs_qkv, k_bytes, (unsigned)ld * 2, 0, S, Ks(0), d);
+    TL::stage(rs_qkv, v_bytes, (unsigned)ld * 2, 0, S, Vs(0), d);
   } else {
-    TL::load_global(base + H, ld, 0, S, rk);
-    TL::load_global(base + 2 * H, ld, 0, S, rv);
+    TL::load_global(base + H, ld, 0, S, rk, d);
+    TL::load_global(base + 2 * H, ld, 0, S, rv, d);
     TL::store_lds(Ks(0), rk);
     TL::store_lds(Vs(0), rv);
   }
@@ -574,11 +602,11 @@ attn_dq_kernel(const bf16* __restrict__ qkv, const bf16* __restrict__ dO, const 
     const int cur = kt & 1;
     if (kt + 1 < ntiles) {                             // the next stage flies meanwhile
       if constexpr (TL::DIRECT) {
-        TL::stage(rs_qkv, k_bytes, (unsigned)ld * 2, (kt + 1) * 128, S, Ks(cur ^ 1));
-        TL::stage(rs_qkv, v_bytes, (unsigned)ld * 2, (kt + 1) * 128, S, Vs(cur ^ 1));
+        TL::stage(rs_qkv, k_bytes, (unsigned)ld * 2, (kt + 1) * 128, S, Ks(cur ^ 1), d);
+        TL::stage(rs_qkv, v_bytes, (unsigned)ld * 2, (kt + 1) * 128, S, Vs(cur ^ 1), d);
       } else {
-        TL::load_global(base + H, ld, (kt + 1) * 128, S, rk);
-        TL::load_global(base + 2 * H, ld, (kt + 1) * 128, S, rv);
+        TL::load_global(base + H, ld, (kt + 1) * 128, S, rk, d);
+        TL::load_global(base + 2 * H, ld, (kt + 1) * 128, S, rv, d);
       }
     }
     const int t0 = kt * 128 + kh * 64;                 // this wavefront's 64 keys
@@ -645,8 +673,8 @@ attn_dq_kernel(const bf16* __restrict__ qkv, const bf16* __restrict__ dO, const 
     for (int dt = 0; dt < D / 32; ++dt)
 #pragma unroll
       for (int e = 0; e < 16; ++e) dq[dt][e] += mrg[(dt * 16 + e) * 64];
-    if (ROT) store_transposed_unrotated<D>(dq, dqkv + (int64_t)n * S * ld + a * D, ld, q, S, scale, rot);
-    else store_transposed<D>(dq, dqkv + (int64_t)n * S * ld + a * D, ld, q, S, scale);
+    if (ROT) store_transposed_unrotated<D>(dq, dqkv + (int64_t)n * S * ld + a * d, ld, q, S, scale, rot, d);
+    else store_transposed<D>(dq, dqkv + (int64_t)n * S * ld + a * d, ld, q, S, scale, d);
   }
   __syncthreads();     // the merge area is staged over again by the next pass
   }   // pass
@@ -677,15 +705,16 @@ attn_dkv_kernel(const bf16* __restrict__ qkv, const bf16* __restrict__ dO, const
   LDS_AS float* stats = (LDS_AS float*)(Vs + TKV::ELEMS);   // [2 buffers][lse2 | dvec][64]
 
   const int a = blockIdx.y, n = blockIdx.z;
+  const int d = H / A;        // the head's own width: D, or less (a multiple of 8) with the tiles' further columns held at zero
   const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);   // scalar: tests on a wavefront's rows become real branches
   const int lane = threadIdx.x & 63, h = lane >> 5;
   const int kg = wave & 3, qh = wave >> 2;          // group of 32 keys, half of the query tile
   const int64_t ld = 3 * (int64_t)H;
-  const bf16* base = qkv + (int64_t)n * S * ld + a * D;
-  const bf16* dObase = dO + (int64_t)n * S * H + a * D;
+  const bf16* base = qkv + (int64_t)n * S * ld + a * d;
+  const bf16* dObase = dO + (int64_t)n * S * H + a * d;
   const __amdgpu_buffer_rsrc_t rs_qkv = make_rsrc(qkv + (int64_t)n * S * ld, (unsigned)(S * ld * 2));
   const __amdgpu_buffer_rsrc_t rs_do = make_rsrc(dO + (int64_t)n * S * H, (unsigned)((int64_t)S * H * 2));
-  const unsigned col_bytes = (unsigned)(a * D * 2);
+  const unsigned col_bytes = (unsigned)(a * d * 2);
   const float* lse_base = lse + ((int64_t)n * A + a) * S;
   const float* dv_base = dvec + ((int64_t)n * A + a) * S;
   const float c2 = scale * kLog2e;
@@ -697,13 +726,13 @@ attn_dkv_kernel(const bf16* __restrict__ qkv, const bf16* __restrict__ dO, const
   const int t = t0 + (lane & 31);
 
   if constexpr (TL::DIRECT) {
-    TKV::stage(rs_qkv, (unsigned)H * 2 + col_bytes, (unsigned)ld * 2, tt * 128, S, Ks);
-    TKV::stage(rs_qkv, (unsigned)H * 4 + col_bytes, (unsigned)ld * 2, tt * 128, S, Vs);
+    TKV::stage(rs_qkv, (unsigned)H * 2 + col_bytes, (unsigned)ld * 2, tt * 128, S, Ks, d);
+    TKV::stage(rs_qkv, (unsigned)H * 4 + col_bytes, (unsigned)ld * 2, tt * 128, S, Vs, d);
   } else {
     bf16x8 rkv[TKV::PER_THREAD];
-    TKV::load_global(base + H, ld, tt * 128, S, rkv);
+    TKV::load_global(base + H, ld, tt * 128, S, rkv, d);
     TKV::store_lds(Ks, rkv);
-    TKV::load_global(base + 2 * H, ld, tt * 128, S, rkv);
+    TKV::load_global(base + 2 * H, ld, tt * 128, S, rkv, d);
     TKV::store_lds(Vs, rkv);
   }
 
@@ -725,11 +754,11 @@ attn_dkv_kernel(const bf16* __restrict__ qkv, const bf16* __restrict__ dO, const
   };
   bf16x8 rq[TL::DIRECT ? 1 : TL::PER_THREAD], rdo[TL::DIRECT ? 1 : TL::PER_THREAD];   // register staging (D = 64)
   if constexpr (TL::DIRECT) {
-    TL::stage(rs_qkv, col_bytes, (unsigned)ld * 2, first * TILE, S, Qs(0));
-    TL::stage(rs_do, col_bytes, (unsigned)H * 2, first * TILE, S, dOs(0));
+    TL::stage(rs_qkv, col_bytes, (unsigned)ld * 2, first * TILE, S, Qs(0), d);
+    TL::stage(rs_do, col_bytes, (unsigned)H * 2, first * TILE, S, dOs(0), d);
   } else {
-    TL::load_global(base, ld, first * TILE, S, rq);
-    TL::load_global(dObase, H, first * TILE, S, rdo);
+    TL::load_global(base, ld, first * TILE, S, rq, d);
+    TL::load_global(dObase, H, first * TILE, S, rdo, d);
     TL::store_lds(Qs(0), rq);
     TL::store_lds(dOs(0), rdo);
   }
@@ -742,11 +771,11 @@ attn_dkv_kernel(const bf16* __restrict__ qkv, const bf16* __restrict__ dO, const
     const int cur = (it - first) & 1, qb0 = it * TILE;
     if (it + 1 < ntiles) {                             // the next tile flies into the other stage meanwhile
       if constexpr (TL::DIRECT) {
-        TL::stage(rs_qkv, col_bytes, (unsigned)ld * 2, qb0 + TILE, S, Qs(cur ^ 1));
-        TL::stage(rs_do, col_bytes, (unsigned)H * 2, qb0 + TILE, S, dOs(cur ^ 1));
+        TL::stage(rs_qkv, col_bytes, (unsigned)ld * 2, qb0 + TILE, S, Qs(cur ^ 1), d);
+        TL::stage(rs_do, col_bytes, (unsigned)H * 2, qb0 + TILE, S, dOs(cur ^ 1), d);
       } else {
-        TL::load_global(base, ld, qb0 + TILE, S, rq);
-        TL::load_global(dObase, H, qb0 + TILE, S, rdo);
+        TL::load_global(base, ld, qb0 + TILE, S, rq, d);
+        TL::load_global(dObase, H, qb0 + TILE, S, rdo, d);
       }
       load_stats(qb0 + TILE);
     }
@@ -824,19 +853,19 @@ attn_dkv_kernel(const bf16* __restrict__ qkv, const bf16* __restrict__ dO, const
   }
   __syncthreads();
   if (qh == 0) {
-    bf16* out = dqkv + (int64_t)n * S * ld + a * D;
+    bf16* out = dqkv + (int64_t)n * S * ld + a * d;
 #pragma unroll
     for (int dt = 0; dt < D / 32; ++dt)
 #pragma unroll
       for (int e = 0; e < 16; ++e) dvv[dt][e] += mrg[(NV / 2 + dt * 16 + e) * 64];
-    store_transposed<D>(dvv, out + 2 * H, ld, t, S, 1.0f);
+    store_transposed<D>(dvv, out + 2 * H, ld, t, S, 1.0f, d);
     __builtin_amdgcn_sched_barrier(0);      // dv leaves its registers before dk's merge (and its rotary factors) need theirs
 #pragma unroll
     for (int dt = 0; dt < D / 32; ++dt)
 #pragma unroll
       for (int e = 0; e < 16; ++e) dk[dt][e] += mrg[(dt * 16 + e) * 64];
-    if (ROT) store_transposed_unrotated<D>(dk, out + H, ld, t, S, scale, rot);
-    else store_transposed<D>(dk, out + H, ld, t, S, scale);
+    if (ROT) store_transposed_unrotated<D>(dk, out + H, ld, t, S, scale, rot, d);
+    else store_transposed<D>(dk, out + H, ld, t, S, scale, d);
   }
   __syncthreads();     // the merge area is staged over again by the next pass
   }   // pass
@@ -862,7 +891,7 @@ int fwd_cfg(const bf16* qkv, bf16* O, float* lse, int m, int S, int H, int A, hi
     auto kern = attn_fwd8_kernel<D, CAUSAL>;
     int rc = reserve_lds(kern, lds);
     if (rc != CEPHALO_OK) return rc;
-    kern<<<grid, kThreads8, lds, s>>>(qkv, O, lse, S, H, A, 1.0f / sqrtf((float)D));
+    kern<<<grid, kThreads8, lds, s>>>(qkv, O, lse, S, H, A, 1.0f / sqrtf((float)(H / A)));
   } else {
     // uniform tiles: two independent four-wavefront blocks per compute unit run out of phase with each other
     // (measured 12 % faster than the eight-wavefront form, whose wavefronts move in step between barriers)
@@ -870,7 +899,7 @@ int fwd_cfg(const bf16* qkv, bf16* O, float* lse, int m, int S, int H, int A, hi
     auto kern = attn_fwd_kernel<D, CAUSAL>;
     int rc = reserve_lds(kern, lds);
     if (rc != CEPHALO_OK) return rc;
-    kern<<<grid, kThreads, lds, s>>>(qkv, O, lse, S, H, A, 1.0f / sqrtf((float)D));
+    kern<<<grid, kThreads, lds, s>>>(qkv, O, lse, S, H, A, 1.0f / sqrtf((float)(H / A)));
   }
   CEPHALO_CHECK_LAUNCH("attn_fwd_mfma");
   return CEPHALO_OK;
@@ -879,9 +908,12 @@ int fwd_cfg(const bf16* qkv, bf16* O, float* lse, int m, int S, int H, int A, hi
 template <int D, bool CAUSAL, bool ROT>
 int bwd_cfg(const bf16* qkv, const bf16* O, const bf16* dO, const float* lse, float* dvec, bf16* dqkv,
             int m, int S, int H, int A, const float* rot, hipStream_t s) {
-  const float scale = 1.0f / sqrtf((float)D);
+  const int d = H / A;
+  const float scale = 1.0f / sqrtf((float)d);
   const int rows = m * S;
-  attn_dvec_kernel<D><<<(rows + 3) / 4, kThreads, 0, s>>>(O, dO, dvec, rows, S, H, A);
+  if (d == D) attn_dvec_kernel<D><<<(rows + 3) / 4, kThreads, 0, s>>>(O, dO, dvec, rows, S, H, A);
+  else if (d == 32) attn_dvec_kernel<32><<<(rows + 3) / 4, kThreads, 0, s>>>(O, dO, dvec, rows, S, H, A);
+  else attn_dvec_any_kernel<<<(int)(((int64_t)rows * A + kThreads - 1) / kThreads), kThreads, 0, s>>>(O, dO, dvec, rows, S, H, A);
   const int nt = (S + 127) / 128;
   dim3 grid(CAUSAL ? (nt + 1) / 2 : nt, A, m);     // causal: a block takes a tile and its mirror image
   {
@@ -917,25 +949,28 @@ int bwd_pick(const bf16* qkv, const bf16* O, const bf16* dO, const float* lse, f
 }  // namespace
 
 int launch_attn_fwd_mfma(const bf16* qkv, bf16* O, float* lse, int m, int S, int H, int A, int causal, hipStream_t s) {
-  const int D = H / A;
+  const int D = A > 0 ? H / A : 0;
   if (H % 8 != 0 || !aligned16(qkv) || !aligned16(O)) return fail(CEPHALO_EINVAL, "attention: rows must be 16-byte aligned");
   if ((int64_t)S * 3 * H * 2 >= (int64_t)1 << 31)
     return fail(CEPHALO_EUNSUPPORTED, "attention: one sample of qkv (%lld bytes) exceeds the 2 GiB a buffer offset reaches", (long long)S * 3 * H * 2);
-  if (D == 64) return causal ? fwd_cfg<64, true>(qkv, O, lse, m, S, H, A, s) : fwd_cfg<64, false>(qkv, O, lse, m, S, H, A, s);
-  if (D == 128) return causal ? fwd_cfg<128, true>(qkv, O, lse, m, S, H, A, s) : fwd_cfg<128, false>(qkv, O, lse, m, S, H, A, s);
-  return fail(CEPHALO_EUNSUPPORTED, "attention (matrix-core kernel): head dim %d is not 64 or 128", D);
+  // a head narrower than the 64- or 128-wide tile runs on that tile with its further columns held at zero
+  if (A <= 0 || H % A != 0 || D % 8 != 0 || D > 128)
+    return fail(CEPHALO_EUNSUPPORTED, "attention (matrix-core kernel): head dim %d is not a multiple of 8 up to 128", A > 0 ? D : 0);
+  if (D <= 64) return causal ? fwd_cfg<64, true>(qkv, O, lse, m, S, H, A, s) : fwd_cfg<64, false>(qkv, O, lse, m, S, H, A, s);
+  return causal ? fwd_cfg<128, true>(qkv, O, lse, m, S, H, A, s) : fwd_cfg<128, false>(qkv, O, lse, m, S, H, A, s);
 }
 
 int launch_attn_bwd_mfma(const bf16* qkv, const bf16* O, const bf16* dO, const float* lse, float* dvec, bf16* dqkv,
                          int m, int S, int H, int A, int causal, hipStream_t s, const float* rot) {
-  const int D = H / A;
+  const int D = A > 0 ? H / A : 0;
   if (H % 8 != 0 || !aligned16(qkv) || !aligned16(O) || !aligned16(dO) || !aligned16(dqkv) || !aligned16(rot))
     return fail(CEPHALO_EINVAL, "attention: rows must be 16-byte aligned");
   if ((int64_t)S * 3 * H * 2 >= (int64_t)1 << 31)
     return fail(CEPHALO_EUNSUPPORTED, "attention: one sample of qkv (%lld bytes) exceeds the 2 GiB a buffer offset reaches", (long long)S * 3 * H * 2);
-  if (D == 64) return bwd_pick<64>(qkv, O, dO, lse, dvec, dqkv, m, S, H, A, causal, rot, s);
-  if (D == 128) return bwd_pick<128>(qkv, O, dO, lse, dvec, dqkv, m, S, H, A, causal, rot, s);
-  return fail(CEPHALO_EUNSUPPORTED, "attention (matrix-core kernel): head dim %d is not 64 or 128", D);
+  if (A <= 0 || H % A != 0 || D % 8 != 0 || D > 128)
+    return fail(CEPHALO_EUNSUPPORTED, "attention (matrix-core kernel): head dim %d is not a multiple of 8 up to 128", A > 0 ? D : 0);
+  if (D <= 64) return bwd_pick<64>(qkv, O, dO, lse, dvec, dqkv, m, S, H, A, causal, rot, s);
+  return bwd_pick<128>(qkv, O, dO, lse, dvec, dqkv, m, S, H, A, causal, rot, s);
 }
 
 }  // namespace cephalo

@@ -62,8 +62,8 @@ int check_desc(const cephalo_layer_desc* d) {
     return fail(CEPHALO_EUNSUPPORTED, "layer desc: hidden %d and mlp %d must be multiples of 8 (16-byte rows)", d->hidden, d->mlp);
   const int hd = d->hidden / d->heads;
   if (hd > 128) return fail(CEPHALO_EUNSUPPORTED, "layer desc: head dim %d > 128", hd);
-  if (d->dtype == CEPHALO_BF16 && hd != 64 && hd != 128)
-    return fail(CEPHALO_EUNSUPPORTED, "layer desc: bf16 attention needs head dim 64 or 128, got %d", hd);
+  if (d->dtype == CEPHALO_BF16 && hd % 8 != 0)
+    return fail(CEPHALO_EUNSUPPORTED, "layer desc: bf16 attention needs a head dim that is a multiple of 8, got %d", hd);
   if (d->hidden > 8192) return fail(CEPHALO_EUNSUPPORTED, "layer desc: hidden %d > 8192", d->hidden);
   return CEPHALO_OK;
 }

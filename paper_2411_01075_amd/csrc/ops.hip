@@ -23,8 +23,8 @@ int check_attn(const cephalo_layer_desc* d, int m) {
     return fail(CEPHALO_EINVAL, "attention: bad sizes hidden %d heads %d seq %d m %d", d->hidden, d->heads, d->seq, m);
   const int hd = d->hidden / d->heads;
   if (hd > 128) return fail(CEPHALO_EUNSUPPORTED, "attention: head dim %d > 128", hd);
-  if (d->dtype == CEPHALO_BF16 && hd != 64 && hd != 128)
-    return fail(CEPHALO_EUNSUPPORTED, "attention: bf16 needs head dim 64 or 128, got %d", hd);
+  if (d->dtype == CEPHALO_BF16 && hd % 8 != 0)
+    return fail(CEPHALO_EUNSUPPORTED, "attention: bf16 needs a head dim that is a multiple of 8, got %d", hd);
   if (d->dtype != CEPHALO_F32 && d->dtype != CEPHALO_BF16) return fail(CEPHALO_EINVAL, "attention: unknown dtype %d", d->dtype);
   return CEPHALO_OK;
 }

@@ -68,7 +68,7 @@ def test_bad_desc_is_rejected(kw):
 
 def test_unsupported_head_dim():
     with pytest.raises(C.CephaloError) as e:
-        C.cephalo_layer_param_count(C.layer_desc(96, 2, 384, 16, True, C.BF16))   # head dim 48
+        C.cephalo_layer_param_count(C.layer_desc(200, 2, 384, 16, True, C.BF16))   # head dim 100: not a multiple of 8
     assert "cephalo error -2" in str(e.value)
 
 

@@ -18,6 +18,13 @@ CASES = [  # bf16?, m, S, heads, head dim, causal
     (True, 1, 128, 1, 128, False),
     (True, 1, 40, 2, 64, True),        # shorter than one tile
     (True, 1, 1024, 2, 64, True),
+    # head widths between the 64- and 128-wide tiles (the paper's model table has 32, 104 and 112 among others)
+    (True, 2, 200, 3, 32, True),
+    (True, 1, 333, 2, 104, True),
+    (True, 2, 197, 2, 112, False),
+    (True, 1, 150, 5, 8, True),
+    (True, 1, 260, 2, 96, False),
+    (True, 1, 130, 3, 40, False),
     (False, 2, 70, 3, 24, True),
     (False, 1, 128, 2, 64, False),
 ]

@@ -26,6 +26,11 @@ CASES = {
     "bf16_c2_small": small(CONFIGS["c2"], name="bf16_c2s", hidden=256, heads=4, mlp=1024, seq=192, micro_batch=2, n_micro=2),
     "bf16_c3_small": small(CONFIGS["c3"], name="bf16_c3s", hidden=320, heads=5, mlp=1280, seq=200, micro_batch=2, n_micro=3),
     "bf16_c4_small": small(CONFIGS["c4"], name="bf16_c4s", hidden=512, heads=4, mlp=2048, seq=320, micro_batch=1, n_micro=2),
+    # head widths other than 64 and 128 (the paper's model table: GPT 2.7B / 6.7B have 32, ViT-G 104, ViT-e 112)
+    "bf16_d32": small(CONFIGS["c3"], name="bf16_d32", hidden=320, heads=10, mlp=1280, seq=200, micro_batch=2, n_micro=2),
+    "bf16_d104": small(CONFIGS["c2"], name="bf16_d104", hidden=208, heads=2, mlp=832, seq=150, micro_batch=1, n_micro=3),
+    # a ViT-G-shaped layer (16 heads of 104, 257 tokens per image) at its full width, one micro-batch of 4 images
+    "bf16_vitg": small(CONFIGS["vitg"], micro_batch=4, n_micro=1),
     # the ViT-Large-shaped encoder layer at its full size: 197 tokens per image (a ragged attention tile), non-causal
     "bf16_vitl": CONFIGS["vitl"],
 }

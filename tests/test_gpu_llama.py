@@ -22,6 +22,9 @@ CASES = {
     "bf16_d128": dataclasses.replace(CONFIGS["lmini"], hidden=256, heads=2, mlp=344, seq=200, micro_batch=1, n_micro=3),
     "f32_tiny": dataclasses.replace(CONFIGS["lmini"], dtype="f32", hidden=64, heads=2, mlp=96, seq=24, micro_batch=1, n_micro=3),
     "bf16_noncausal": dataclasses.replace(CONFIGS["lmini"], causal=False, seq=96),
+    # a head width between the tiles: the rotary table and the backward's stores work on the head's own width
+    "bf16_d96": dataclasses.replace(CONFIGS["lmini"], hidden=192, heads=2, mlp=344, seq=150, micro_batch=1, n_micro=2),
+    "bf16_d32": dataclasses.replace(CONFIGS["lmini"], hidden=128, heads=4, mlp=344, seq=150, micro_batch=1, n_micro=2),
 }
 
 

@@ -67,6 +67,10 @@ CONFIGS = {
     "lmini": LayerConfig("lmini", 256, 4, 688, 136, True, 2, 2, "bf16", seed=1106, shard_rule="frac:37:41", kind="llama"),
     # ViT-Large-shaped encoder layer: 197 tokens per image, non-causal (the GPT-style layer form)
     "vitl": LayerConfig("vitl", 1024, 16, 4096, 197, False, 8, 2, "bf16", seed=1007, shard_rule="frac:50:23"),
+    # two more of the paper's model table whose head widths are neither 64 nor 128: a GPT 2.7B-shaped layer (80 heads
+    # of 32) and a ViT-G-shaped one (16 heads of 104, 257 tokens per image)
+    "g27": LayerConfig("g27", 2560, 80, 10240, 2048, True, 1, 4, "bf16", seed=1009, shard_rule="third_odd"),
+    "vitg": LayerConfig("vitg", 1664, 16, 8192, 257, False, 8, 2, "bf16", seed=1010, shard_rule="frac:50:23"),
     # reduced relatives used only by parity tests (ragged tiles, small enough for the oracle)
     "c5mini": LayerConfig("c5mini", 256, 4, 1024, 128, True, 2, 2, "bf16", layers=2, vocab=1031, seed=1105,
                           shard_rule="frac29_seeded"),
