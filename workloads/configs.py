@@ -69,8 +69,10 @@ CONFIGS = {
     "vitl": LayerConfig("vitl", 1024, 16, 4096, 197, False, 8, 2, "bf16", seed=1007, shard_rule="frac:50:23"),
     # two more of the paper's model table whose head widths are neither 64 nor 128: a GPT 2.7B-shaped layer (80 heads
     # of 32) and a ViT-G-shaped one (16 heads of 104, 257 tokens per image)
-    "g27": LayerConfig("g27", 2560, 80, 10240, 2048, True, 1, 4, "bf16", seed=1009, shard_rule="third_odd"),
-    "vitg": LayerConfig("vitg", 1664, 16, 8192, 257, False, 8, 2, "bf16", seed=1010, shard_rule="frac:50:23"),
+    # (weights N(0, 0.01^2) as for l7b: with 0.02 the feed-forward branch of a random layer of these widths has a gain
+    #  above one, 0.02 sqrt(F) * 0.02 sqrt(H) = 1.5 and 2.0)
+    "g27": LayerConfig("g27", 2560, 80, 10240, 2048, True, 1, 4, "bf16", seed=1009, shard_rule="third_odd", init_std=0.01),
+    "vitg": LayerConfig("vitg", 1664, 16, 8192, 257, False, 8, 2, "bf16", seed=1010, shard_rule="frac:50:23", init_std=0.01),
     # reduced relatives used only by parity tests (ragged tiles, small enough for the oracle)
     "c5mini": LayerConfig("c5mini", 256, 4, 1024, 128, True, 2, 2, "bf16", layers=2, vocab=1031, seed=1105,
                           shard_rule="frac29_seeded"),
