@@ -145,3 +145,32 @@ def test_c5_stack_full_size_layer_by_layer():
     C.cephalo_stack_step(sd, flat, dids, dtgt, b, m, G, 1.0, loss, ws)
     torch.cuda.synchronize()
     assert float(loss.item()) == l1 and torch.equal(G, G1)
+
+
+@pytest.mark.parametrize("name,kw", [("c3", dict(micro_batch=1, n_micro=1)),
+                                     ("c5", dict(layers=1, vocab=0, micro_batch=1, n_micro=1)),
+                                     ("c4", dict(micro_batch=1, n_micro=1, seq=1024))])
+def test_layer_at_full_width_forward_and_backward(name, kw):
+    """One whole layer of the three widest workloads at their full widths (one sample; c4 at half its sequence length
+    so that the oracle takes seconds), every output and every gradient tensor against the oracle.  With the N(0, 0.02^2)
+    weights these widths make a *random* layer's feed-forward branch amplify what enters it: gain 0.02 sqrt(F) *
+    0.02 sqrt(H) = 1.3 (c3), 1.6 (c5), 3.3 (c4), against at most 0.8 in the oracle-sized cases.  The distance between
+    any chain that stores its GEMM operands in bf16 and the unrounded oracle grows with that gain on the gradients
+    upstream of the branch (rounding the stored tensors of the oracle's own chain to bf16 shows the same), so the
+    budget of a well-conditioned layer is scaled by it here."""
+    import dataclasses
+    from tests import harness as Hn
+    from workloads import draw_layer_params, draw_activations
+    cfg = dataclasses.replace(CONFIGS[name], **kw)
+    gain = 0.02 ** 2 * (cfg.hidden * cfg.mlp) ** 0.5
+    assert gain > 1.0
+    print("full-width layer", name, "gain %.2f" % gain, flush=True)
+    tensors = draw_layer_params(cfg, perturbed=True)
+    x, dy = draw_activations(cfg)
+    general = C.cephalo_gemm_general_count()
+    got = Hn.gpu_share_step(cfg, tensors, x, dy)
+    assert C.cephalo_gemm_general_count() == general
+    ref = Hn.oracle_share_step(cfg, tensors, x, dy)
+    rep = Hn.compare_share(cfg, got, ref, scale=gain)
+    print({k: "%.1e/%.1e" % v for k, v in rep.items()}, flush=True)
+    assert rep["y"][1] < 5e-3 and rep["w_fc2"][1] < 5e-3      # not upstream of the branch: the unscaled budget
