@@ -65,7 +65,7 @@ def test_per_microbatch_calls_match_share_call(case):
     Hn.compare_share(cfg, b, ref)
 
 
-@pytest.mark.parametrize("case", ["f32_ragged", "bf16_c2_small", "bf16_c3_small", "bf16_vitl"])
+@pytest.mark.parametrize("case", ["f32_ragged", "f32_noncausal", "bf16_c2_small", "bf16_c3_small", "bf16_vitl", "bf16_vitg"])     # (f32_noncausal, bf16_vitg: a single micro-batch)
 def test_two_micro_batches_in_flight_give_identical_results(case):
     """The share call with micro-batches alternating between two streams: every micro-batch's kernels and every
     reduction keep their order, so y, dx and the gradient are bit-identical to the one-stream call (an odd number of

@@ -172,6 +172,15 @@ def test_two_micro_batches_in_flight_give_identical_results(case, checkpoint):
         assert np.array_equal(ka["boundaries"], kb["boundaries"])
 
 
+def test_interleaved_step_with_a_single_micro_batch():
+    cfg = dataclasses.replace(CASES["bf16_mini"], micro_batch=4, n_micro=1)
+    params = draw_stack_params(cfg, perturbed=True)
+    ids, tgt = draw_token_ids(cfg)
+    a = run_gpu(cfg, params, ids, tgt, 1.0)
+    b = run_gpu(cfg, params, ids, tgt, 1.0, interleave=True)
+    assert a[0] == b[0] and np.array_equal(a[1], b[1])
+
+
 def test_interleave_argument_errors():
     cfg = CASES["f32_tiny"]
     with pytest.raises(C.CephaloError):           # not together with offload
