@@ -134,3 +134,36 @@ def test_device_argument_errors_launch_nothing():
     with pytest.raises(C.CephaloError, match="positive"):
         C.cephalo_layer_fwd(desc, flat, x, y, 0, save, scratch)
     torch.cuda.synchronize()
+
+
+def test_share_step_replays_from_a_hip_graph():
+    """The library only enqueues kernels and stream-ordering events on the caller's streams, so a caller may capture a
+    step, two-stream form included, into a HIP graph.  Replays (with eager work and synchronisations in between, output
+    buffers cleared each time) must reproduce the eager results bit for bit."""
+    cfg = CASES["bf16_c2_small"]
+    desc = C.desc_from_config(cfg)
+    P = C.cephalo_layer_param_count(desc)
+    flat32 = torch.from_numpy(C.flatten_layer_params(desc, draw_layer_params(cfg, perturbed=True))).cuda()
+    flat = torch.empty(P, dtype=torch.bfloat16, device="cuda")
+    C.cephalo_cast_bf16(flat, flat32)
+    x_h, dy_h = draw_activations(cfg)
+    x, dy = torch.from_numpy(x_h).cuda(), torch.from_numpy(dy_h).cuda()
+    y, dx, G = torch.empty_like(x), torch.empty_like(x), torch.zeros(P, device="cuda")
+    b, m = cfg.batch_share, cfg.micro_batch
+    sb, cb = C.cephalo_share_workspace_bytes(desc, b, m)
+    save, scratch = torch.empty(sb, dtype=torch.uint8, device="cuda"), torch.empty(cb, dtype=torch.uint8, device="cuda")
+    side = torch.cuda.Stream()
+    C.cephalo_share_layer_step_interleaved(desc, flat, x, y, dy, dx, b, m, save, G, 1.0, scratch, side)
+    torch.cuda.synchronize()
+    ref = (y.clone(), dx.clone(), G.clone())
+    graph, cap = torch.cuda.CUDAGraph(), torch.cuda.Stream()
+    with torch.cuda.stream(cap):
+        with torch.cuda.graph(graph, stream=cap):
+            C.cephalo_share_layer_step_interleaved(desc, flat, x, y, dy, dx, b, m, save, G, 1.0, scratch, side, stream=cap)
+    torch.cuda.synchronize()
+    for replay in range(3):
+        y.zero_(); dx.zero_(); G.fill_(float("nan")); save.zero_()
+        torch.cuda.synchronize()
+        graph.replay()
+        torch.cuda.synchronize()
+        assert torch.equal(y, ref[0]) and torch.equal(dx, ref[1]) and torch.equal(G, ref[2]), replay
