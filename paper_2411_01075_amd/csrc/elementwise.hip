@@ -366,7 +366,7 @@ int launch_transpose_bf16(const bf16* in, bf16* out, int rows, int cols, hipStre
 // The angles' cosines and sines are tabulated once per call, tab[t][i] = (cos, sin) in fp32 (fp32 power, accurate
 // sincos), and every kernel that rotates (the GEMM epilogue that produces q and k, the attention backward's stores of
 // dq and dk, the stand-alone kernel below) reads the same table.
-__global__ void __launch_bounds__(kThreads)
+static __global__ void __launch_bounds__(kThreads)
 rotary_table_kernel(float* __restrict__ tab, int S, int d, float log2_base) {
   const int idx = blockIdx.x * kThreads + threadIdx.x;
   if (idx >= S * (d / 2)) return;
@@ -389,7 +389,7 @@ int launch_rotary_table(float* tab, int S, int d, float base, hipStream_t s) {
 // In place on the Q and K thirds of qkv [rows, 3H], position t = row % S; sign = -1 turns back (the gradient's way).
 // One thread per 4 consecutive values (2 pairs).
 template <typename T>
-__global__ void __launch_bounds__(kThreads)
+static __global__ void __launch_bounds__(kThreads)
 rotary_kernel(T* __restrict__ qkv, const float* __restrict__ tab, int rows, int S, int H, int d, float sign) {
   const int per_row = 2 * H / 4;                           // groups of the Q and K parts of a row
   const int64_t idx = (int64_t)blockIdx.x * kThreads + threadIdx.x;
@@ -421,7 +421,7 @@ int launch_rotary(T* qkv, const float* tab, int rows, int S, int H, int heads, i
 __device__ __forceinline__ float sigmoidf_(float z) { return 1.0f / (1.0f + __expf(-z)); }
 
 template <typename T>
-__global__ void __launch_bounds__(kThreads)
+static __global__ void __launch_bounds__(kThreads)
 swiglu_fwd_kernel(const T* __restrict__ gu, T* __restrict__ h, int64_t rows, int F) {
   constexpr int VN = Vec<T>::N;
   const int per_row = F / VN;
