@@ -17,7 +17,10 @@
  *   - Every pointer marked "device" is GPU memory owned by the caller; the library
  *     allocates nothing, keeps no state between calls and frees nothing.
  *   - `stream` is a hipStream_t passed as void* (NULL = the default stream).  Calls only
- *     enqueue work on it and return; there is no hidden synchronisation.
+ *     enqueue work on it and return; there is no hidden synchronisation.  The offload and
+ *     interleaved steps also enqueue on the further streams they are given, ordered by events
+ *     that the call creates and releases; all of it is joined into `stream` before the call
+ *     returns, so stream order on `stream` is all a caller needs.
  *   - Return value: 0 on success, a negative CEPHALO_E* code otherwise.  Arguments are
  *     validated on the host before anything is launched, so an error return means no
  *     kernel ran.  cephalo_last_error() gives a text for the calling thread's last error.
