@@ -88,7 +88,7 @@ ln_fwd_kernel(const float* __restrict__ x, const T* __restrict__ gamma, const T*
   }
 }
 
-constexpr int kLnBwdRowsPerBlock = 16;  // 4 rows per wavefront
+constexpr int kLnBwdRowsPerBlock = 8;   // 2 rows per wavefront: two blocks (8 wavefronts) per compute unit at 4096 rows keep more loads in flight
 
 // out = resid + rstd * (g - mean(g) - xhat * mean(g*xhat)),  g = du * gamma
 // part_g[blk][h] = sum over the block's rows of du*xhat, part_b[blk][h] = sum of du
@@ -116,7 +116,7 @@ ln_bwd_kernel(const float* __restrict__ du, const float* __restrict__ x, const f
     const int row = row0 + r;
     if (row >= rows) break;
     const float mu = RMS ? 0.f : mean[row], rs = rstd[row];
-    float g[MAXV][VN], xh[MAXV][VN];
+    float g[MAXV][VN], xh[MAXV][VN], rr[MAXV][VN];
     float s1 = 0.f, s2 = 0.f;
 #pragma unroll
     for (int j = 0; j < MAXV; ++j) {
@@ -126,6 +126,12 @@ ln_bwd_kernel(const float* __restrict__ du, const float* __restrict__ x, const f
         load_f32<VN>(du + (int64_t)row * H + v * VN, d);
         load_f32<VN>(x + (int64_t)row * H + v * VN, xv);
         load_vec<T>(gamma + v * VN, gm);
+        if (resid) {      // asked for together with the row: its latency is not paid a second time after the reduction
+          load_f32<VN>(resid + (int64_t)row * H + v * VN, rr[j]);
+        } else {
+#pragma unroll
+          for (int i = 0; i < VN; ++i) rr[j][i] = 0.f;
+        }
 #pragma unroll
         for (int i = 0; i < VN; ++i) {
           xh[j][i] = (xv[i] - mu) * rs;
@@ -142,15 +148,9 @@ ln_bwd_kernel(const float* __restrict__ du, const float* __restrict__ x, const f
     for (int j = 0; j < MAXV; ++j) {
       const int v = lane + 64 * j;
       if (v < nv) {
-        float rr[VN], o[VN];
-        if (resid) {
-          load_f32<VN>(resid + (int64_t)row * H + v * VN, rr);
-        } else {
+        float o[VN];
 #pragma unroll
-          for (int i = 0; i < VN; ++i) rr[i] = 0.f;
-        }
-#pragma unroll
-        for (int i = 0; i < VN; ++i) o[i] = rr[i] + rs * (g[j][i] - c1 - xh[j][i] * c2);
+        for (int i = 0; i < VN; ++i) o[i] = rr[j][i] + rs * (g[j][i] - c1 - xh[j][i] * c2);
         store_f32<VN>(out + (int64_t)row * H + v * VN, o);
         if (out_lowp) store_vec<T>(out_lowp + (int64_t)row * H + v * VN, o);
       }
