@@ -265,8 +265,8 @@ def main():
                 add_leg("forward, bias epilogue (qkv)", lambda i, st: C.cephalo_op_gemm(*fwd_args, C.EPI_BIAS, C=Y[i], bias=bias, stream=st), fl, L * l)
             elif name == "fc1":
                 Y, Z = two(T, n_out), two(T, n_out)
-                add_leg("forward, bias+GELU epilogue (fc1)",
-                        lambda i, st: C.cephalo_op_gemm(*fwd_args, C.EPI_BIAS_GELU, C=Y[i], bias=bias, Z=Z[i], stream=st), fl, L * l)
+                add_leg("forward, bias+GELU epilogue, derivative saved (fc1)",
+                        lambda i, st: C.cephalo_op_gemm(*fwd_args, C.EPI_BIAS_GELU_DERIV, C=Y[i], bias=bias, Z=Z[i], stream=st), fl, L * l)
             else:
                 R, Y = rnd(T, n_out, dtype=torch.float32), two(T, n_out, dtype=torch.float32)
                 add_leg("forward, bias+residual epilogue, fp32 stream (out-proj, fc2)",
@@ -275,7 +275,7 @@ def main():
             dg_args = (C.BF16, dY, n_out, 1, WT, n_out, 1, T, k_in, n_out)
             if name == "fc2":
                 Zs, dZ = rnd(T, k_in), two(T, k_in)
-                add_leg("input gradient, GELU' epilogue (fc2)", lambda i, st: C.cephalo_op_gemm(*dg_args, C.EPI_DGELU, C=dZ[i], Z=Zs, stream=st), fl, L * l)
+                add_leg("input gradient, times the saved GELU' (fc2)", lambda i, st: C.cephalo_op_gemm(*dg_args, C.EPI_MUL, C=dZ[i], Z=Zs, stream=st), fl, L * l)
             elif name == "o":
                 dX = two(T, k_in)
                 add_leg("input gradient, plain epilogue (qkv, out-proj, fc1)", lambda i, st: C.cephalo_op_gemm(*dg_args, C.EPI_NONE, C=dX[i], stream=st), fl, L * l)

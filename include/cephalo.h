@@ -209,6 +209,8 @@ int cephalo_cast_bf16(void* dst_bf16, const float* src, int64_t n, void* stream)
 #define CEPHALO_EPI_GRAD        5  /* G = (accumulate ? G : 0) + scale * acc   (G fp32)    */
 #define CEPHALO_EPI_NONE_F32    6  /* as NONE, C is fp32 [M,N] whatever dtype says          */
 #define CEPHALO_EPI_BIAS_RESID_F32 7 /* as BIAS_RESID, R and C are fp32 [M,N] (the residual stream) */
+#define CEPHALO_EPI_BIAS_GELU_DERIV 8 /* z = acc + bias[n]; C = gelu(z); Z = gelu'(z): what the layer's forward saves */
+#define CEPHALO_EPI_MUL         9  /* C = acc * Z[m,n]: the layer's backward through GELU, with Z = gelu'(z) saved   */
 
 /* C[M,N] = sum_k A(m,k) * B(n,k) with a fused epilogue; the contraction of a linear layer's
  * forward (both operands k-contiguous), input gradient (B n-contiguous) and weight gradient

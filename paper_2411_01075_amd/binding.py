@@ -233,7 +233,7 @@ def cephalo_cast_bf16(dst, src, n=None, stream=None):
     _check(lib().cephalo_cast_bf16(_ptr(dst), _ptr(src), n, _stream(stream)))
 
 
-EPI_NONE, EPI_BIAS, EPI_BIAS_RESID, EPI_BIAS_GELU, EPI_DGELU, EPI_GRAD, EPI_NONE_F32, EPI_BIAS_RESID_F32 = range(8)
+EPI_NONE, EPI_BIAS, EPI_BIAS_RESID, EPI_BIAS_GELU, EPI_DGELU, EPI_GRAD, EPI_NONE_F32, EPI_BIAS_RESID_F32, EPI_BIAS_GELU_DERIV, EPI_MUL = range(10)
 
 
 def cephalo_op_gemm(dtype, A, a_rs, a_cs, B, b_rs, b_cs, M, N, K, epilogue, C=None, bias=None, R=None, Z=None,

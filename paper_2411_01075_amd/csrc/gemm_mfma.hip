@@ -143,7 +143,7 @@ __device__ __forceinline__ void write_staged_rows(const GemmArgs<bf16>& a, const
       float v[8];
 #pragma unroll
       for (int t = 0; t < 4; ++t) { v[t] = v0[t]; v[4 + t] = v1[t]; }
-      if (EPI == EPI_BIAS || EPI == EPI_BIAS_GELU || (EPI == EPI_BIAS_RESID && a.bias)) {    // (no bias: residual only)
+      if (EPI == EPI_BIAS || EPI == EPI_BIAS_GELU || EPI == EPI_BIAS_GELU_DERIV || (EPI == EPI_BIAS_RESID && a.bias)) {    // (no bias: residual only)
         float b8[8];
         load_vec<bf16>(a.bias + n, b8);
 #pragma unroll
@@ -171,6 +171,18 @@ __device__ __forceinline__ void write_staged_rows(const GemmArgs<bf16>& a, const
         load_vec<bf16>(a.Z + o, z8);
 #pragma unroll
         for (int t = 0; t < 8; ++t) v[t] *= gelu_grad_fast(z8[t]);
+      }
+      if (EPI == EPI_BIAS_GELU_DERIV) {
+        float d8[8];
+#pragma unroll
+        for (int t = 0; t < 8; ++t) gelu_and_grad_fast(v[t], v[t], d8[t]);
+        store_vec<bf16>(a.Z + o, d8);
+      }
+      if (EPI == EPI_MUL) {
+        float z8[8];
+        load_vec<bf16>(a.Z + o, z8);
+#pragma unroll
+        for (int t = 0; t < 8; ++t) v[t] *= z8[t];
       }
       if (EPI == EPI_ROPE) {
         if (n < a.rot_cols) {       // (a group of 8 columns lies wholly inside or outside the rotated part)
@@ -568,6 +580,8 @@ int launch_gemm_mfma(const GemmArgs<bf16>& a, hipStream_t s) {
       case EPI_BIAS_RESID: return launch_tiles<true, true, EPI_BIAS_RESID>(a, s);
       case EPI_BIAS_GELU: return launch_tiles<true, true, EPI_BIAS_GELU>(a, s);
       case EPI_DGELU: return launch_tiles<true, true, EPI_DGELU>(a, s);
+      case EPI_BIAS_GELU_DERIV: return launch_tiles<true, true, EPI_BIAS_GELU_DERIV>(a, s);
+      case EPI_MUL: return launch_tiles<true, true, EPI_MUL>(a, s);
       case EPI_DSWIGLU: if (a.N % 8 == 0) return launch_tiles<true, true, EPI_DSWIGLU>(a, s); break;
       case EPI_GRAD: return launch_tiles<true, true, EPI_GRAD>(a, s);
     }

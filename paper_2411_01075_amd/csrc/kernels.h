@@ -74,6 +74,13 @@ __device__ __forceinline__ float gelu_grad_fast(float z) {
   gelu_terms_fast(z, cdf, e);
   return cdf + z * (0.39894228040143267794f * e);
 }
+// both at once: gelu(z) and gelu'(z)
+__device__ __forceinline__ void gelu_and_grad_fast(float z, float& y, float& dy) {
+  float cdf, e;
+  gelu_terms_fast(z, cdf, e);
+  y = z * cdf;
+  dy = cdf + z * (0.39894228040143267794f * e);
+}
 
 // ---------------------------------------------------------------------------------------
 // GEMM:  C[M,N] = sum_k A(m,k) * B(n,k)  followed by an epilogue.
@@ -88,6 +95,9 @@ enum Epilogue {
   EPI_GRAD = 5,        // G[m,n] = (accumulate ? G[m,n] : 0) + scale * acc     (G fp32)
   EPI_ROPE = 7,        // C = acc with each pair of columns (2i, 2i+1) below rot_cols turned by the rotary angle of its
                        //   row's position m % rot_S and of its place in the head: (e, o) -> (e cos - o sin, e sin + o cos)
+  EPI_BIAS_GELU_DERIV = 9,  // z = acc + bias[n];  C = gelu(z);  Z = gelu'(z)   (the derivative is saved in place of the pre-activation:
+                            //   Phi(z) and exp(-z^2/2) are at hand in the forward, and the backward becomes EPI_MUL)
+  EPI_MUL = 10,             // C = acc * Z[m,n]
   EPI_DSWIGLU = 8,     // gated SiLU backward, acc = dh[m,n], n < N = F; Z and C are [M, 2N] = [gate | up] (pitch ldc >= 2N):
                        //   C[m,n] = acc * Z[m,N+n] * silu'(Z[m,n]);  C[m,N+n] = acc * silu(Z[m,n])
 };
@@ -112,7 +122,8 @@ struct GemmArgs {
   const T* R;      // [M,N] residual
   const float* Rf; // if set, EPI_BIAS_RESID reads its residual from here in fp32 (pitch ldc) instead of R
   float* Cf;       // if set, EPI_NONE / EPI_BIAS / EPI_BIAS_RESID write their result here in fp32 (pitch ldc) instead of C
-  T* Z;            // [M,N] pre-activation: written by EPI_BIAS_GELU, read by EPI_DGELU ([M,2N], read by EPI_DSWIGLU)
+  T* Z;            // [M,N] pre-activation: written by EPI_BIAS_GELU, read by EPI_DGELU ([M,2N], read by EPI_DSWIGLU);
+                   // EPI_BIAS_GELU_DERIV writes gelu'(z) here and EPI_MUL reads it as a factor
   float* G;        // [M,N] fp32 gradient (EPI_GRAD)
   float scale;
   int accumulate;

@@ -100,7 +100,7 @@ SaveLayout save_layout(const cephalo_layer_desc& d, int n) {
   L.x1 = take(T * H * 4);
   L.mean2 = take(T * 4); L.rstd2 = take(T * 4);
   L.u2 = take(T * H * es);
-  L.z = take(T * (size_t)ff1_width(d) * es);      // pre-activation (GPT-style) or gate | up (Llama-style)
+  L.z = take(T * (size_t)ff1_width(d) * es);      // derivative of the activation at the pre-activation (GPT-style) or gate | up (Llama-style)
   L.h = take(T * F * es);
   L.rot = is_llama(d) ? take((size_t)d.seq * (H / d.heads) * sizeof(float)) : 0;   // rotary table [S, d/2] of (cos, sin), shared by all samples
   L.total = p;
@@ -343,7 +343,7 @@ int layer_fwd_t(const cephalo_layer_desc& d, const T* P, const float* x, float* 
   TRY(launch_ln_fwd<T>(sv.x1, P + o.ln2_g, P + o.ln2_b, sv.u2, sv.mean2, sv.rstd2, Tn, H, d.ln_eps, s));
   {
     GemmArgs<T> a = linear_fwd<T>(sv.u2, P + o.w_fc1, Tn, F, H);
-    a.epi = EPI_BIAS_GELU; a.bias = P + o.b_fc1; a.Z = sv.z; a.C = sv.h;
+    a.epi = EPI_BIAS_GELU_DERIV; a.bias = P + o.b_fc1; a.Z = sv.z; a.C = sv.h;      // saved: gelu'(z), the factor the backward needs
     TRY(gemm<T>(a, s));
   }
   {
@@ -422,8 +422,8 @@ int layer_bwd_data_t(const cephalo_layer_desc& d, const T* P, const float* x, co
     return CEPHALO_OK;
   }
   {
-    GemmArgs<T> a = dgrad_args<T>(dyl, P, w.wT, o.w_fc2, Tn, H, F);   // dh = dy W2, then dz = dh * gelu'(z)
-    a.epi = EPI_DGELU; a.Z = sv.z; a.C = w.dz;
+    GemmArgs<T> a = dgrad_args<T>(dyl, P, w.wT, o.w_fc2, Tn, H, F);   // dh = dy W2, then dz = dh * gelu'(z), the factor saved by the forward
+    a.epi = EPI_MUL; a.Z = sv.z; a.C = w.dz;
     TRY(gemm<T>(a, s));
   }
   {

@@ -45,12 +45,17 @@ extern "C" int cephalo_op_gemm(int32_t dtype, const void* A, int64_t a_rs, int64
   const bool f32_out = epilogue == CEPHALO_EPI_NONE_F32 || epilogue == CEPHALO_EPI_BIAS_RESID_F32;
   if (epilogue == CEPHALO_EPI_NONE_F32) epilogue = EPI_NONE;
   if (epilogue == CEPHALO_EPI_BIAS_RESID_F32) epilogue = EPI_BIAS_RESID;
+  if (epilogue == CEPHALO_EPI_BIAS_GELU_DERIV) epilogue = EPI_BIAS_GELU_DERIV;      // (public and internal numbers differ)
+  else if (epilogue == CEPHALO_EPI_MUL) epilogue = EPI_MUL;
+  else if (epilogue == EPI_BIAS_GELU_DERIV || epilogue == EPI_MUL) epilogue = -1;
   switch (epilogue) {
     case EPI_NONE: break;
     case EPI_BIAS: need_bias = true; break;
     case EPI_BIAS_RESID: need_bias = need_r = true; break;
     case EPI_BIAS_GELU: need_bias = need_z = true; break;
     case EPI_DGELU: need_z = true; break;
+    case EPI_BIAS_GELU_DERIV: need_bias = need_z = true; break;
+    case EPI_MUL: need_z = true; break;
     case EPI_GRAD: if (!G) return fail(CEPHALO_EINVAL, "op_gemm: EPI_GRAD needs G"); break;
     default: return fail(CEPHALO_EINVAL, "op_gemm: unknown epilogue %d", epilogue);
   }
