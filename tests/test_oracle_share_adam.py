@@ -134,6 +134,46 @@ def test_adam_unsharded_matches_torch_optimizer():
         assert np.max(np.abs(tp.detach().numpy() - p)) < 1e-13, t
 
 
+def test_adam_weight_decay_is_the_l2_term_of_torch_adam():
+    """weight_decay * p joins the gradient (torch.optim.Adam's weight_decay), not the decoupled AdamW form."""
+    rng = np.random.default_rng(17)
+    P, wd = 129, 0.05
+    p0 = rng.standard_normal(P)
+    tp = torch.tensor(p0, dtype=torch.float64, requires_grad=True)
+    opt = torch.optim.Adam([tp], lr=HYP["lr"], betas=(HYP["beta1"], HYP["beta2"]), eps=HYP["eps"], weight_decay=wd)
+    tw = torch.tensor(p0, dtype=torch.float64, requires_grad=True)
+    optw = torch.optim.AdamW([tw], lr=HYP["lr"], betas=(HYP["beta1"], HYP["beta2"]), eps=HYP["eps"], weight_decay=wd)
+    p, m, v = p0.copy(), np.zeros(P), np.zeros(P)
+    for t in range(1, 6):
+        g = rng.standard_normal(P) * 0.1
+        tp.grad = torch.tensor(g)
+        tw.grad = torch.tensor(g)
+        opt.step()
+        optw.step()
+        p, m, v = A.shard_adam(p, g, m, v, 0, P, t=t, weight_decay=wd, **HYP)
+        assert np.max(np.abs(tp.detach().numpy() - p)) < 1e-13, t
+    assert np.max(np.abs(tw.detach().numpy() - p)) > 1e-6          # the decoupled form is a different update
+    # closed form at t = 1 from zero moments: the step is -lr * g' / (|g'| + eps) with g' = g + wd * p
+    z = np.zeros(P)
+    g = rng.standard_normal(P)
+    p1, m1, v1 = A.shard_adam(p0, g, z, z, 0, P, t=1, weight_decay=wd, **HYP)
+    gp = g + wd * p0
+    assert np.allclose(p1, p0 - HYP["lr"] * gp / (np.abs(gp) + HYP["eps"]), rtol=0, atol=1e-15)
+    assert np.allclose(m1, 0.1 * gp) and np.allclose(v1, 0.001 * gp * gp)
+    # zero gradient: only the decay moves p, towards zero; weight_decay = 0 is the plain update, bit for bit
+    pz, _, _ = A.shard_adam(p0, z, z, z, 0, P, t=1, weight_decay=wd, **HYP)
+    assert np.all(np.abs(pz) < np.abs(p0))
+    a = A.shard_adam(p0, g, m, v, 3, 100, t=4, weight_decay=0.0, **HYP)
+    b = A.shard_adam(p0, g, m, v, 3, 100, t=4, **HYP)
+    assert all(np.array_equal(x, y) for x, y in zip(a, b))
+    # partition invariance holds with decay as well (each element's update reads only its own p, g, m, v)
+    full = A.shard_adam(p0, g, m, v, 0, P, t=4, weight_decay=wd, **HYP)
+    left = A.shard_adam(p0, g, m, v, 0, 50, t=4, weight_decay=wd, **HYP)
+    right = A.shard_adam(p0, g, m, v, 50, P - 50, t=4, weight_decay=wd, **HYP)
+    for f, l, r in zip(full, left, right):
+        assert np.array_equal(f[:50], l[:50]) and np.array_equal(f[50:], r[50:])
+
+
 def test_adam_partition_invariant_and_outside_untouched():
     rng = np.random.default_rng(15)
     P = 1000
