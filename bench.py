@@ -136,7 +136,7 @@ def main():
                 C.cephalo_stack_step_interleaved(sd, pcomp, ids, tgt, b, m, G, 1.0, loss, ws, side)
             else:
                 C.cephalo_stack_step(sd, pcomp, ids, tgt, b, m, G, 1.0, loss, ws)
-            C.cephalo_shard_adam(p32, G, mom, var, plow, P, off, ln, lr, 0.9, 0.999, 1e-8, t)
+            C.cephalo_shard_adam(p32, G, mom, var, plow, P, off, ln, lr, 0.9, 0.999, 1e-8, 0.0, t)
     else:
         x = torch.from_numpy(x_h).cuda().float().contiguous()       # the residual stream is fp32
         dy = torch.from_numpy(dy_h).cuda().float().contiguous()
@@ -154,7 +154,7 @@ def main():
                 C.cephalo_share_layer_step_interleaved(desc, pcomp, x, y, dy, dx, b, m, save, G, 1.0, scratch, side)
             else:
                 C.cephalo_share_layer_step(desc, pcomp, x, y, dy, dx, b, m, save, G, 1.0, scratch)
-            C.cephalo_shard_adam(p32, G, mom, var, plow, P, off, ln, lr, 0.9, 0.999, 1e-8, t)
+            C.cephalo_shard_adam(p32, G, mom, var, plow, P, off, ln, lr, 0.9, 0.999, 1e-8, 0.0, t)
 
     for i in range(args.warmup):
         step(7 + i)
@@ -264,7 +264,7 @@ def main():
                 Y = two(T, n_out)
                 add_leg("forward, bias epilogue (qkv)", lambda i, st: C.cephalo_op_gemm(*fwd_args, C.EPI_BIAS, C=Y[i], bias=bias, stream=st), fl, L * l)
             elif name == "fc1":
-                Y, Z = two(T, n_out), two(T, n_out)
+                Y, Z = two(T, n_out), two(T, n_out, dtype=torch.float16)      # the saved derivative is a half-precision factor
                 add_leg("forward, bias+GELU epilogue, derivative saved (fc1)",
                         lambda i, st: C.cephalo_op_gemm(*fwd_args, C.EPI_BIAS_GELU_DERIV, C=Y[i], bias=bias, Z=Z[i], stream=st), fl, L * l)
             else:
@@ -274,7 +274,7 @@ def main():
             # input gradient dX[T, k_in] = dY[T, n_out] W, through W^T [k_in, n_out]
             dg_args = (C.BF16, dY, n_out, 1, WT, n_out, 1, T, k_in, n_out)
             if name == "fc2":
-                Zs, dZ = rnd(T, k_in), two(T, k_in)
+                Zs, dZ = rnd(T, k_in, dtype=torch.float16), two(T, k_in)
                 add_leg("input gradient, times the saved GELU' (fc2)", lambda i, st: C.cephalo_op_gemm(*dg_args, C.EPI_MUL, C=dZ[i], Z=Zs, stream=st), fl, L * l)
             elif name == "o":
                 dX = two(T, k_in)
@@ -309,7 +309,7 @@ def main():
                     "side_by_side": d["side_by_side"]}
         extras["gemm_legs"] = legs
     # shard Adam alone: 28 algorithmic bytes per element (+2 for the bf16 copy)
-    adam_sec = timed(lambda: C.cephalo_shard_adam(p32, G, mom, var, plow, P, off, ln, lr, 0.9, 0.999, 1e-8, 9), 10)
+    adam_sec = timed(lambda: C.cephalo_shard_adam(p32, G, mom, var, plow, P, off, ln, lr, 0.9, 0.999, 1e-8, 0.0, 9), 10)
     adam_bytes = ln * (28 + (2 if bf16 else 0))
     extras["shard_adam"] = {"elements": ln, "us": round(adam_sec * 1e6, 1), "GB/s": round(adam_bytes / adam_sec / 1e9, 1),
                             "frac_of_hbm_peak": round(adam_bytes / adam_sec / 1e9 / PEAK_HBM_GBS, 4)}

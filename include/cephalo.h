@@ -177,7 +177,8 @@ int cephalo_grad_accum(float* acc, const float* g, float scale, int64_t n, void*
 
 /* Adam on this GPU's slice [offset, offset+len) of the flat training state (Sec. 3.1
  * "Training State Partitioning"; fp32 parameter, gradient and two moments, Sec. 3.3).
- *   m <- beta1 m + (1-beta1) g;  v <- beta2 v + (1-beta2) g^2
+ *   g' = g + weight_decay p       (the decay joins the gradient: plain Adam's L2 term; 0 = none)
+ *   m <- beta1 m + (1-beta1) g';  v <- beta2 v + (1-beta2) g'^2
  *   p <- p - lr * (m / (1-beta1^step)) / (sqrt(v / (1-beta2^step)) + eps)
  * p, g, m, v are device pointers to element 0 of the flat buffers and are indexed globally;
  * nothing outside the slice is read or written.  p_lowp, if not NULL, is a device bf16 [P]
@@ -185,10 +186,14 @@ int cephalo_grad_accum(float* acc, const float* g, float scale, int64_t n, void*
  * step's compute.  len = 0 is a valid no-op; offset = 0, len = P is the unsharded update.
  * step is 1-based.  Each element's arithmetic is the same instruction sequence wherever
  * the slice starts, so updates over any partition of [0,P) concatenate to the unsharded
- * update bit for bit. */
+ * update bit for bit.  The four fp32 base pointers must be 16-byte aligned; the kernel runs
+ * at its full rate when they are congruent modulo 128 bytes (it starts its vector body where
+ * p's address is a multiple of 128; buffers that sit elsewhere are still correct, only slower).
+ * Errors (nothing launched): slice outside [0, P), step < 1, beta outside [0, 1), eps < 0,
+ * weight_decay < 0 or not finite, a NULL or misaligned buffer with len > 0. */
 int cephalo_shard_adam(float* p, const float* g, float* m, float* v, void* p_lowp,
                        int64_t P, int64_t offset, int64_t len,
-                       float lr, float beta1, float beta2, float eps, int64_t step,
+                       float lr, float beta1, float beta2, float eps, float weight_decay, int64_t step,
                        void* stream);
 
 /* dst[i] <- bf16(src[i]) (nearest-even), i in [0, n): makes the compute copy of fp32 master
@@ -211,6 +216,8 @@ int cephalo_cast_bf16(void* dst_bf16, const float* src, int64_t n, void* stream)
 #define CEPHALO_EPI_BIAS_RESID_F32 7 /* as BIAS_RESID, R and C are fp32 [M,N] (the residual stream) */
 #define CEPHALO_EPI_BIAS_GELU_DERIV 8 /* z = acc + bias[n]; C = gelu(z); Z = gelu'(z): what the layer's forward saves */
 #define CEPHALO_EPI_MUL         9  /* C = acc * Z[m,n]: the layer's backward through GELU, with Z = gelu'(z) saved   */
+/* For these two epilogues Z is a saved factor, not a matrix operand: with bf16 operands it is an [M,N] array of IEEE
+ * half values (two bytes like bf16, three more significand bits), with fp32 operands an fp32 array. */
 
 /* C[M,N] = sum_k A(m,k) * B(n,k) with a fused epilogue; the contraction of a linear layer's
  * forward (both operands k-contiguous), input gradient (B n-contiguous) and weight gradient
@@ -232,6 +239,20 @@ int cephalo_op_gemm(int32_t dtype, const void* A, int64_t a_rs, int64_t a_cs,
 size_t cephalo_op_linear_wgrad_workspace(int32_t dtype, int32_t T, int32_t N, int32_t K);
 int cephalo_op_linear_wgrad(int32_t dtype, const void* dY, const void* X, int32_t T, int32_t N, int32_t K,
                             float* G, float scale, int32_t accumulate, void* workspace, size_t workspace_bytes, void* stream);
+
+/* For callers that cannot allocate device memory and have no work area to hand over (code under HIP graph capture,
+ * tight serving loops, harnesses that forbid allocation): cephalo_op_linear_wgrad with the partial sums of a split
+ * token axis kept in a fixed device array of CEPHALO_NOALLOC_SCRATCH_BYTES that the library's code object carries
+ * (each GPU the library is used on holds one copy until the process ends).  Same arguments without the work area, same
+ * kernels, bit-identical G.  The call allocates and frees nothing (no device memory, no events); its first use on a
+ * GPU looks the array's address up once.  A problem whose partial sums (pieces x N x K x 4 bytes, for bf16 outputs
+ * with few tiles and T >= 2048 only) exceed the array is refused with CEPHALO_EWORKSPACE before anything is launched.
+ * Every call on a GPU uses that GPU's one array: two calls that overlap in time on the same GPU (different streams or
+ * threads) race on it; calls on one stream are ordered and safe.  Nothing in the array has to be cleared between
+ * calls.  Call it with the GPU of `stream` current. */
+#define CEPHALO_NOALLOC_SCRATCH_BYTES (64u << 20)
+int cephalo_op_linear_wgrad_static(int32_t dtype, const void* dY, const void* X, int32_t T, int32_t N, int32_t K,
+                                   float* G, float scale, int32_t accumulate, void* stream);
 
 /* Attention of one micro-batch on the packed projection qkv [m*S, 3H] (column blocks Q | K | V).
  * Forward writes O [m*S, H] (dtype) and lse [m, A, S] fp32, the log-sum-exp of each query row's
@@ -289,6 +310,15 @@ int cephalo_stack_param_offsets(const cephalo_stack_desc* desc, int64_t* offsets
  * Host pointer out.  Without offload the area begins with the layer-boundary activations, fp32 [layers+1][b*S][H]:
  * entry 0 is the embedding output, entry i the output of layer i-1; they are valid after cephalo_stack_step returns. */
 int cephalo_stack_workspace_bytes(const cephalo_stack_desc* desc, int32_t batch_share, int32_t micro_batch, size_t* bytes);
+
+/* Where three things lie in that work area once a step has returned, as byte offsets written to host array
+ * offsets[3], so that a layer of a full-size stack can be checked on its own (Sec. 3.2's layered order: the backward
+ * of layer 0 is the last thing that ran, over every micro-batch):
+ *   [0] the layer-boundary activations (as above; meaningful without offload only),
+ *   [1] the gradient of the loss with respect to layer 0's input,  fp32 [b*S][H], times grad_scale,
+ *   [2] the gradient of the loss with respect to layer 0's output, fp32 [b*S][H], times grad_scale
+ *       (a one-layer stack: with respect to the final norm's input). */
+int cephalo_stack_workspace_regions(const cephalo_stack_desc* desc, int32_t batch_share, int32_t micro_batch, size_t* offsets);
 
 /* Forward, loss and backward of the whole share (b = l*m, Sec. 3.2):
  *   loss[0]   <- mean over the b*S tokens of the cross-entropy (device, one float)

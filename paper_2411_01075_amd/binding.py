@@ -79,11 +79,12 @@ SIGNATURES = {
     "cephalo_share_layer_step_interleaved": (ctypes.c_int, [_dp, _vp, _vp, _vp, _vp, _vp, _i32, _i32, _vp, _sz, _vp, _f32,
                                                 _vp, _sz, _vp, _vp]),
     "cephalo_grad_accum": (ctypes.c_int, [_vp, _vp, _f32, _i64, _vp]),
-    "cephalo_shard_adam": (ctypes.c_int, [_vp, _vp, _vp, _vp, _vp, _i64, _i64, _i64, _f32, _f32, _f32, _f32, _i64, _vp]),
+    "cephalo_shard_adam": (ctypes.c_int, [_vp, _vp, _vp, _vp, _vp, _i64, _i64, _i64, _f32, _f32, _f32, _f32, _f32, _i64, _vp]),
     "cephalo_cast_bf16": (ctypes.c_int, [_vp, _vp, _i64, _vp]),
     "cephalo_stack_param_count": (_i64, [ctypes.POINTER(StackDesc)]),
     "cephalo_stack_param_offsets": (ctypes.c_int, [ctypes.POINTER(StackDesc), ctypes.POINTER(_i64)]),
     "cephalo_stack_workspace_bytes": (ctypes.c_int, [ctypes.POINTER(StackDesc), _i32, _i32, ctypes.POINTER(_sz)]),
+    "cephalo_stack_workspace_regions": (ctypes.c_int, [ctypes.POINTER(StackDesc), _i32, _i32, ctypes.POINTER(_sz)]),
     "cephalo_stack_step": (ctypes.c_int, [ctypes.POINTER(StackDesc), _vp, _vp, _vp, _i32, _i32, _vp, _f32, _vp, _vp, _sz, _vp]),
     "cephalo_stack_step_interleaved": (ctypes.c_int, [ctypes.POINTER(StackDesc), _vp, _vp, _vp, _i32, _i32, _vp, _f32, _vp, _vp, _sz, _vp, _vp]),
     "cephalo_stack_host_bytes": (ctypes.c_int, [ctypes.POINTER(StackDesc), _i32, _i32, ctypes.POINTER(_sz)]),
@@ -93,6 +94,7 @@ SIGNATURES = {
                                        _vp, _f32, _i32, _vp]),
     "cephalo_op_linear_wgrad_workspace": (_sz, [_i32, _i32, _i32, _i32]),
     "cephalo_op_linear_wgrad": (ctypes.c_int, [_i32, _vp, _vp, _i32, _i32, _i32, _vp, _f32, _i32, _vp, _sz, _vp]),
+    "cephalo_op_linear_wgrad_static": (ctypes.c_int, [_i32, _vp, _vp, _i32, _i32, _i32, _vp, _f32, _i32, _vp]),
     "cephalo_plan_compute": (ctypes.c_int, [_i32, ctypes.POINTER(GpuPerf), _i32, ctypes.POINTER(ClusterModel),
                                             ctypes.POINTER(_i32), ctypes.POINTER(_i32), ctypes.POINTER(ctypes.c_double)]),
     "cephalo_plan_state": (ctypes.c_int, [_i32, ctypes.POINTER(GpuPerf), ctypes.POINTER(_i32), ctypes.POINTER(ClusterModel),
@@ -223,9 +225,9 @@ def cephalo_grad_accum(acc, g, scale, n=None, stream=None):
     _check(lib().cephalo_grad_accum(_ptr(acc), _ptr(g), scale, n, _stream(stream)))
 
 
-def cephalo_shard_adam(p, g, m, v, p_lowp, P, offset, length, lr, beta1, beta2, eps, step, stream=None):
+def cephalo_shard_adam(p, g, m, v, p_lowp, P, offset, length, lr, beta1, beta2, eps, weight_decay, step, stream=None):
     _check(lib().cephalo_shard_adam(_ptr(p), _ptr(g), _ptr(m), _ptr(v), _ptr(p_lowp), P, offset, length,
-                                    lr, beta1, beta2, eps, step, _stream(stream)))
+                                    lr, beta1, beta2, eps, weight_decay, step, _stream(stream)))
 
 
 def cephalo_cast_bf16(dst, src, n=None, stream=None):
@@ -240,6 +242,10 @@ def cephalo_op_gemm(dtype, A, a_rs, a_cs, B, b_rs, b_cs, M, N, K, epilogue, C=No
                     G=None, scale=1.0, accumulate=0, stream=None):
     _check(lib().cephalo_op_gemm(dtype, _ptr(A), a_rs, a_cs, _ptr(B), b_rs, b_cs, M, N, K, epilogue,
                                  _ptr(C), _ptr(bias), _ptr(R), _ptr(Z), _ptr(G), scale, int(accumulate), _stream(stream)))
+
+
+def cephalo_op_linear_wgrad_static(dtype, dY, X, T, N, K, G, scale, accumulate, stream=None):
+    _check(lib().cephalo_op_linear_wgrad_static(dtype, _ptr(dY), _ptr(X), T, N, K, _ptr(G), scale, int(accumulate), _stream(stream)))
 
 
 def cephalo_op_linear_wgrad_workspace(dtype, T, N, K):
@@ -301,6 +307,12 @@ def cephalo_stack_workspace_bytes(sdesc, batch_share, micro_batch):
     a = _sz(0)
     _check(lib().cephalo_stack_workspace_bytes(ctypes.byref(sdesc), batch_share, micro_batch, ctypes.byref(a)))
     return a.value
+
+
+def cephalo_stack_workspace_regions(sdesc, batch_share, micro_batch):
+    a = (_sz * 3)()
+    _check(lib().cephalo_stack_workspace_regions(ctypes.byref(sdesc), batch_share, micro_batch, a))
+    return list(a)
 
 
 def cephalo_stack_step(sdesc, flat_param, ids, targets, batch_share, micro_batch, flat_grad, grad_scale, loss, workspace,

@@ -176,11 +176,11 @@ __device__ __forceinline__ void write_staged_rows(const GemmArgs<bf16>& a, const
         float d8[8];
 #pragma unroll
         for (int t = 0; t < 8; ++t) gelu_and_grad_fast(v[t], v[t], d8[t]);
-        store_vec<bf16>(a.Z + o, d8);
+        store_vec<f16>(reinterpret_cast<f16*>(a.Z) + o, d8);      // a factor, not an operand: IEEE half
       }
       if (EPI == EPI_MUL) {
         float z8[8];
-        load_vec<bf16>(a.Z + o, z8);
+        load_vec<f16>(reinterpret_cast<const f16*>(a.Z) + o, z8);
 #pragma unroll
         for (int t = 0; t < 8; ++t) v[t] *= z8[t];
       }
@@ -468,11 +468,13 @@ splitk_reduce_kernel(const float* __restrict__ part, int splits, int64_t mn4, fl
 template <auto KERN>
 int launch_kernel(const GemmArgs<bf16>& a, int BMv, int BNv, int threads, size_t lds, hipStream_t s) {
   const int tm = (a.M + BMv - 1) / BMv, tn = (a.N + BNv - 1) / BNv;
-  static bool attr_set = false;   // per instantiation
-  if (!attr_set) {
+  // per instantiation; setting the attribute again with the same value is harmless, so two threads that both find the
+  // flag clear may both set it
+  static std::atomic<bool> attr_set{false};
+  if (!attr_set.load(std::memory_order_acquire)) {
     if (hipFuncSetAttribute(reinterpret_cast<const void*>(KERN), hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds) != hipSuccess)
       return fail(CEPHALO_EHIP, "gemm_mfma: cannot reserve %zu B of LDS", lds);
-    attr_set = true;
+    attr_set.store(true, std::memory_order_release);
   }
   const int slabs = (a.K + BK - 1) / BK;
   int splits = (a.epi == EPI_GRAD && a.splits > 1 && a.part) ? a.splits : 1;
@@ -503,7 +505,6 @@ thread_local int side_by_side = 1;     // kernels the caller runs at once (GemmS
 
 template <bool AK, bool BKF, int EPI>
 int launch_tiles(const GemmArgs<bf16>& a, hipStream_t s) {
-  static const int force = getenv("CEPHALO_GEMM_CFG") ? atoi(getenv("CEPHALO_GEMM_CFG")) : 0;   // tuning aid
   // Tile choice: the score of a configuration is the fraction of the last round of blocks that the 256 compute
   // units fill, times the rate its main loop reaches relative to the 256 x 256 tile (measured: bigger tiles
   // move fewer LDS and L2 bytes per MFMA).
@@ -513,7 +514,7 @@ int launch_tiles(const GemmArgs<bf16>& a, hipStream_t s) {
     const double t = (double)((a.M + bm - 1) / bm) * ((a.N + bn - 1) / bn) * nsplit;
     return t / (cus * (double)(int64_t)((t + cus - 1) / cus));
   };
-  int cfg = force;
+  int cfg = 0;
   // 256 x 128 tiles run three LDS stages (they fit, and long contractions over few tiles gain a quarter from the
   // deeper prefetch; short ones lose nothing).
   if (cfg == 0) {

@@ -80,10 +80,10 @@ __global__ void __launch_bounds__(kThreads) gemm_simple_kernel(GemmArgs<T> a) {
         case EPI_DGELU: a.C[o] = (T)(v * gelu_grad_f((float)a.Z[o])); break;
         case EPI_BIAS_GELU_DERIV: {
           const float z = v + (float)a.bias[n];
-          a.Z[o] = (T)gelu_grad_f(z);
+          reinterpret_cast<typename FactorOf<T>::type*>(a.Z)[o] = (typename FactorOf<T>::type)gelu_grad_f(z);
           a.C[o] = (T)gelu_f(z);
         } break;
-        case EPI_MUL: a.C[o] = (T)(v * (float)a.Z[o]); break;
+        case EPI_MUL: a.C[o] = (T)(v * (float)reinterpret_cast<const typename FactorOf<T>::type*>(a.Z)[o]); break;
         case EPI_ROPE: {
           // the partner column's product sits in the same thread (columns come in aligned groups of four)
           float r = v;

@@ -17,6 +17,18 @@ template <> struct Vec<bf16> {
   typedef bf16 raw __attribute__((ext_vector_type(8)));
 };
 
+// A saved epilogue factor (the GELU derivative kept by the forward for the backward) multiplies an fp32 accumulator;
+// it is never a matrix operand.  In the bf16 mode it is therefore stored as an IEEE half: the same two bytes, three
+// more significand bits (it lies in [-0.13, 1.13], far inside the half range), one bf16 rounding less on the way to
+// every gradient upstream of the feed-forward block.
+typedef _Float16 f16;
+template <> struct Vec<f16> {
+  static constexpr int N = 8;
+  typedef f16 raw __attribute__((ext_vector_type(8)));
+};
+template <typename T> struct FactorOf { typedef T type; };
+template <> struct FactorOf<bf16> { typedef f16 type; };
+
 template <typename T>
 __device__ __forceinline__ void load_vec(const T* p, float (&out)[Vec<T>::N]) {
   typename Vec<T>::raw r = *reinterpret_cast<const typename Vec<T>::raw*>(p);

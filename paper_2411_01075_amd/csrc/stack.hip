@@ -514,6 +514,21 @@ extern "C" int cephalo_stack_workspace_bytes(const cephalo_stack_desc* d, int32_
   return CEPHALO_OK;
 }
 
+extern "C" int cephalo_stack_workspace_regions(const cephalo_stack_desc* d, int32_t batch_share, int32_t micro_batch, size_t* offsets) {
+  TRY(check_stack(d));
+  if (micro_batch <= 0 || batch_share <= 0 || batch_share % micro_batch != 0)
+    return fail(CEPHALO_EINVAL, "stack_workspace_regions: batch share b = %d is not a positive multiple of micro-batch size m = %d",
+                batch_share, micro_batch);
+  if (!offsets) return fail(CEPHALO_EINVAL, "stack_workspace_regions: null output");
+  const StackLayout L = stack_layout(*d, batch_share, micro_batch);
+  // the residual-stream gradient alternates between two buffers, one swap per layer, starting in the first
+  const bool even = d->layers % 2 == 0;
+  offsets[0] = L.xs;
+  offsets[1] = even ? L.dxa : L.dxb;
+  offsets[2] = even ? L.dxb : L.dxa;
+  return CEPHALO_OK;
+}
+
 namespace {
 int stack_step_checked(const cephalo_stack_desc* d, const void* flat_param, const int32_t* ids, const int32_t* targets,
                        int32_t batch_share, int32_t micro_batch, float* flat_grad, float grad_scale, float* loss,

@@ -33,12 +33,11 @@ def rel_errors(got, ref):
     return mx, mean
 
 
-def assert_close(name, got, ref, dtype, scale=1.0):
+def assert_close(name, got, ref, dtype):
     mx, mean = rel_errors(got, ref)
     tmax, tmean = TOL[dtype]
     assert np.isfinite(np.asarray(got, dtype=np.float64)).all(), "%s has non-finite values" % name
-    assert mx <= tmax * scale and mean <= tmean * scale, "%s: max-rel %.3e (tol %.1e) mean-rel %.3e (tol %.1e)" % (
-        name, mx, tmax * scale, mean, tmean * scale)
+    assert mx <= tmax and mean <= tmean, "%s: max-rel %.3e (tol %.1e) mean-rel %.3e (tol %.1e)" % (name, mx, tmax, mean, tmean)
     return mx, mean
 
 
@@ -84,22 +83,50 @@ def gpu_share_step(cfg, tensors, x, dy, grad_scale=1.0, via_share_call=True, int
     return yd.double().cpu().numpy(), dxd.double().cpu().numpy(), G.cpu().numpy()
 
 
-def oracle_share_step(cfg, tensors, x, dy, grad_scale=1.0):
-    """Oracle on the same inputs; bf16 workloads round the parameters to bf16 first (x and dy reach the GPU in fp32)."""
+def oracle_share_step(cfg, tensors, x, dy, grad_scale=1.0, rounded_chain=False):
+    """Oracle on the same inputs; bf16 workloads round the parameters to bf16 first (x and dy reach the GPU in fp32).
+    rounded_chain: the control of tests/rounded_chain.py instead (the oracle's layer with the bf16 mode's stored tensors
+    rounded where they are stored)."""
     H, F = cfg.hidden, cfg.mlp
     flat = olayout.flatten_layer(tensors, H, F, dtype=np.float64)
     x64, dy64 = x.astype(np.float64), dy.astype(np.float64)
     if cfg.dtype == "bf16":
         flat = round_to_bf16(flat.astype(np.float32))
+    if rounded_chain:
+        from tests import rounded_chain as rc
+        return rc.share_layer_step(flat, x64, dy64, H, F, cfg.heads, cfg.causal, cfg.micro_batch, scale=grad_scale)
     return oshare.share_layer_step(flat, x64, dy64, H, F, cfg.heads, cfg.causal, cfg.micro_batch, scale=grad_scale)
 
 
-def compare_share(cfg, got, ref, scale=1.0):
-    """Asserts y, dx and every parameter-gradient tensor against the oracle; returns a report dict."""
+def share_report(cfg, got, ref):
+    """(max-rel, mean-rel) of y, dx and of every parameter-gradient tensor; nothing asserted but finiteness."""
     y, dx, G = got
     ry, rdx, rG = ref
-    rep = {"y": assert_close("y", y, ry, cfg.dtype, scale), "dx": assert_close("dx", dx, rdx, cfg.dtype, scale)}
+    for name, a in (("y", y), ("dx", dx), ("G", G)):
+        assert np.isfinite(np.asarray(a, dtype=np.float64)).all(), "%s has non-finite values" % name
+    rep = {"y": rel_errors(y, ry), "dx": rel_errors(dx, rdx)}
     for name, (start, shape) in olayout.layer_offsets(cfg.hidden, cfg.mlp).items():
         n = int(np.prod(shape))
-        rep[name] = assert_close("grad " + name, G[start:start + n], rG[start:start + n], cfg.dtype, scale)
+        rep[name] = rel_errors(G[start:start + n], rG[start:start + n])
+    return rep
+
+
+def over_budget(rep, dtype):
+    """The entries of a report that exceed the stated tolerance, as text."""
+    tmax, tmean = TOL[dtype]
+    return ["%s max-rel %.2e mean-rel %.2e" % (k, mx, mean) for k, (mx, mean) in rep.items() if not (mx <= tmax and mean <= tmean)]
+
+
+def xfail_over_budget(bad, what=""):
+    """A wide bf16 case that passes the stated budget against the unrounded oracle: an expected failure that carries
+    the measured figures.  The assertion itself is never rescaled."""
+    import pytest
+    pytest.xfail("over the stated bf16 tolerance (2e-2 max-rel / 5e-3 mean-rel) against the unrounded oracle%s: %s" % (what, "; ".join(bad)))
+
+
+def compare_share(cfg, got, ref):
+    """Asserts y, dx and every parameter-gradient tensor against the oracle at the stated tolerance; returns the report."""
+    rep = share_report(cfg, got, ref)
+    bad = over_budget(rep, cfg.dtype)
+    assert not bad, "over the stated tolerance (max-rel %.0e, mean-rel %.0e): %s" % (TOL[cfg.dtype] + ("; ".join(bad),))
     return rep

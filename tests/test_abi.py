@@ -77,11 +77,13 @@ def test_host_validation_of_slices_and_shares():
     fake = ctypes.c_void_p(0x1000)       # never dereferenced: validation fails first
     # slice outside [0, P)
     for P, off, ln in ((100, -1, 5), (100, 0, 101), (100, 100, 1), (100, 50, -1), (-1, 0, 0)):
-        assert lib.cephalo_shard_adam(fake, fake, fake, fake, None, P, off, ln, 1e-3, 0.9, 0.999, 1e-8, 1, None) == -1
+        assert lib.cephalo_shard_adam(fake, fake, fake, fake, None, P, off, ln, 1e-3, 0.9, 0.999, 1e-8, 0.0, 1, None) == -1
     assert b"slice" in lib.cephalo_last_error()
-    assert lib.cephalo_shard_adam(fake, fake, fake, fake, None, 100, 0, 10, 1e-3, 0.9, 0.999, 1e-8, 0, None) == -1   # step 0
-    assert lib.cephalo_shard_adam(ctypes.c_void_p(0x1004), fake, fake, fake, None, 100, 0, 10, 1e-3, 0.9, 0.999, 1e-8, 1, None) == -1
-    assert lib.cephalo_shard_adam(None, None, None, None, None, 100, 40, 0, 1e-3, 0.9, 0.999, 1e-8, 1, None) == 0   # len 0: no-op
+    assert lib.cephalo_shard_adam(fake, fake, fake, fake, None, 100, 0, 10, 1e-3, 0.9, 0.999, 1e-8, 0.0, 0, None) == -1   # step 0
+    assert lib.cephalo_shard_adam(fake, fake, fake, fake, None, 100, 0, 10, 1e-3, 0.9, 0.999, 1e-8, -0.1, 1, None) == -1  # negative decay
+    assert lib.cephalo_shard_adam(fake, fake, fake, fake, None, 100, 0, 10, 1e-3, 1.0, 0.999, 1e-8, 0.0, 1, None) == -1   # beta1 = 1
+    assert lib.cephalo_shard_adam(ctypes.c_void_p(0x1004), fake, fake, fake, None, 100, 0, 10, 1e-3, 0.9, 0.999, 1e-8, 0.0, 1, None) == -1
+    assert lib.cephalo_shard_adam(None, None, None, None, None, 100, 40, 0, 1e-3, 0.9, 0.999, 1e-8, 0.0, 1, None) == 0   # len 0: no-op
     assert lib.cephalo_grad_accum(fake, fake, 1.0, -3, None) == -1
     assert lib.cephalo_grad_accum(None, None, 1.0, 0, None) == 0
     # b must be a positive multiple of m

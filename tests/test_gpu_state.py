@@ -16,11 +16,20 @@ pytestmark = pytest.mark.gpu
 HYP = {k: float(np.float32(x)) for k, x in dict(lr=1e-3, beta1=0.9, beta2=0.999, eps=1e-8).items()}
 
 
-def run_adam(p, g, m, v, off, ln, t, lowp=False):
+def shifted(a, shift):
+    """A device copy of `a` whose first element sits `shift` floats after a 512-byte boundary (torch's allocations
+    start on one), so that the kernel's head, the part before its 128-byte aligned body, takes every length."""
+    buf = torch.empty(a.size + shift, dtype=torch.float32, device="cuda")
+    buf[shift:].copy_(torch.from_numpy(a))
+    return buf[shift:]
+
+
+def run_adam(p, g, m, v, off, ln, t, lowp=False, wd=0.0, shift=0):
+    """shift: a multiple of 4 floats (the base pointers must stay 16-byte aligned)."""
     P = p.size
-    dp, dg, dm, dv = (torch.from_numpy(a.copy()).cuda() for a in (p, g, m, v))
+    dp, dg, dm, dv = (shifted(a, shift) for a in (p, g, m, v))
     dl = torch.full((P,), -7.0, dtype=torch.bfloat16, device="cuda") if lowp else None
-    C.cephalo_shard_adam(dp, dg, dm, dv, dl, P, off, ln, HYP["lr"], HYP["beta1"], HYP["beta2"], HYP["eps"], t)
+    C.cephalo_shard_adam(dp, dg, dm, dv, dl, P, off, ln, HYP["lr"], HYP["beta1"], HYP["beta2"], HYP["eps"], wd, t)
     torch.cuda.synchronize()
     out = [a.cpu().numpy() for a in (dp, dm, dv)]
     if lowp:
@@ -28,8 +37,8 @@ def run_adam(p, g, m, v, off, ln, t, lowp=False):
     return out
 
 
-def check_against_oracle(p, g, m, v, off, ln, t, got):
-    ref = oadam.shard_adam(*(a.astype(np.float64) for a in (p, g, m, v)), off, ln, t=t, **HYP)
+def check_against_oracle(p, g, m, v, off, ln, t, got, wd=0.0):
+    ref = oadam.shard_adam(*(a.astype(np.float64) for a in (p, g, m, v)), off, ln, t=t, weight_decay=float(np.float32(wd)), **HYP)
     for name, gq, rq, src in zip("pmv", got, ref, (p, m, v)):
         # outside the slice: bit-identical to the input
         assert np.array_equal(gq[:off], src[:off]) and np.array_equal(gq[off + ln:], src[off + ln:]), name
@@ -40,7 +49,8 @@ def check_against_oracle(p, g, m, v, off, ln, t, got):
 
 
 @pytest.mark.parametrize("P,off,ln", [(1000, 0, 1000), (1000, 1, 998), (1000, 3, 2), (1000, 997, 3), (4099, 1027, 2051),
-                                      (1 << 20, 12345, 777777), (64, 5, 0), (7, 0, 7), (5, 2, 1)])
+                                      (1 << 20, 12345, 777777), (64, 5, 0), (7, 0, 7), (5, 2, 1),
+                                      (200, 1, 30), (200, 1, 31), (200, 1, 34), (200, 1, 35), (200, 33, 100), (4099, 31, 4068)])
 @pytest.mark.parametrize("t", [1, 7])
 def test_shard_adam_matches_oracle(P, off, ln, t):
     print("adam P", P, "off", off, "len", ln, "t", t, flush=True)
@@ -54,6 +64,40 @@ def test_shard_adam_matches_oracle(P, off, ln, t):
         v = (rng.standard_normal(P).astype(np.float32) * 1e-2) ** 2
     got = run_adam(p, g, m, v, off, ln, t)
     check_against_oracle(p, g, m, v, off, ln, t, got)
+
+
+@pytest.mark.parametrize("shift", [4, 8, 28, 36])
+@pytest.mark.parametrize("off,ln", [(0, 5000), (3, 4000), (29, 131), (125, 4875)])
+def test_shard_adam_wherever_the_buffers_sit(shift, off, ln):
+    """The kernel's scalar head runs until p's address is a multiple of 128 bytes: every head length, and buffers
+    whose bases are not themselves on such a boundary, give the bits of the aligned run."""
+    P = 5000
+    rng = np.random.default_rng(shift + off)
+    p = rng.standard_normal(P).astype(np.float32) * 0.02
+    g, m, v = draw_adam_state(CONFIGS["c1"], P)
+    ref = run_adam(p, g, m, v, off, ln, 7, lowp=True)
+    got = run_adam(p, g, m, v, off, ln, 7, lowp=True, shift=shift)
+    for a, b in zip(ref, got):
+        assert np.array_equal(a, b)
+    check_against_oracle(p, g, m, v, off, ln, 7, got[:3])
+
+
+@pytest.mark.parametrize("P,off,ln", [(1000, 0, 1000), (4099, 1027, 2051), (1 << 18, 12345, 77777)])
+def test_shard_adam_with_weight_decay_matches_oracle(P, off, ln):
+    """The decay term joins the gradient (plain Adam's L2 term); partitions still concatenate bit for bit."""
+    rng = np.random.default_rng(P + off)
+    p = rng.standard_normal(P).astype(np.float32)
+    g, m, v = draw_adam_state(CONFIGS["c2"], P)
+    wd = 0.05
+    got = run_adam(p, g, m, v, off, ln, 7, wd=wd, lowp=True)
+    check_against_oracle(p, g, m, v, off, ln, 7, got[:3], wd=wd)
+    plain = run_adam(p, g, m, v, off, ln, 7)
+    assert not np.array_equal(plain[0], got[0])                      # the decay does act
+    cut = off + ln // 3 + 1
+    left = run_adam(p, g, m, v, off, cut - off, 7, wd=wd, lowp=True)
+    right = run_adam(p, g, m, v, cut, off + ln - cut, 7, wd=wd, lowp=True)
+    for f, l, r in zip(got, left, right):
+        assert np.array_equal(f[off:cut], l[off:cut]) and np.array_equal(f[cut:off + ln], r[cut:off + ln])
 
 
 def test_partition_concatenation_is_bitwise_the_unsharded_update():
@@ -96,7 +140,7 @@ def test_shifted_base_pointers_give_shard_length_state():
     ms, vs = torch.from_numpy(m[off:off + ln].copy()).cuda(), torch.from_numpy(v[off:off + ln].copy()).cuda()
     lib = C.binding.lib()
     rc = lib.cephalo_shard_adam(dp.data_ptr(), dg.data_ptr(), ms.data_ptr() - 4 * off, vs.data_ptr() - 4 * off, None,
-                                P, off, ln, HYP["lr"], HYP["beta1"], HYP["beta2"], HYP["eps"], 7,
+                                P, off, ln, HYP["lr"], HYP["beta1"], HYP["beta2"], HYP["eps"], 0.0, 7,
                                 torch.cuda.current_stream().cuda_stream)
     assert rc == 0
     torch.cuda.synchronize()
@@ -138,9 +182,13 @@ def test_full_size_shards_of_every_workload_sampled():
     """Each workload's real shard (offset, length) at full P: the slice edges and a sample of interior
     elements against the oracle, everything outside the slice bit-identical."""
     from oracle import layout
-    for name in ("c1", "c2", "c3", "c4"):
+    for name in ("c1", "c2", "c3", "c4", "c5"):
         cfg = CONFIGS[name]
-        P = layout.layer_param_count(cfg.hidden, cfg.mlp)
+        if cfg.layers > 1:      # the stack's flat buffer: embeddings, layers, final LayerNorm
+            P = C.cephalo_stack_param_count(C.stack_desc_from_config(cfg))
+            assert P == (cfg.vocab + cfg.seq) * cfg.hidden + cfg.layers * layout.layer_param_count(cfg.hidden, cfg.mlp) + 2 * cfg.hidden
+        else:
+            P = layout.layer_param_count(cfg.hidden, cfg.mlp)
         off, ln = shard_of(cfg, P)
         print(name, "P", P, "offset", off, "len", ln, flush=True)
         gen = torch.Generator(device="cuda").manual_seed(cfg.seed)
@@ -149,8 +197,11 @@ def test_full_size_shards_of_every_workload_sampled():
         m = torch.randn(P, device="cuda", generator=gen) * 1e-2
         v = (torch.randn(P, device="cuda", generator=gen) * 1e-2) ** 2
         p0, m0, v0 = p.clone(), m.clone(), v.clone()
-        C.cephalo_shard_adam(p, g, m, v, None, P, off, ln, cfg.lr, 0.9, 0.999, 1e-8, 7)
+        lowp = torch.full((P,), -7.0, dtype=torch.bfloat16, device="cuda")
+        C.cephalo_shard_adam(p, g, m, v, lowp, P, off, ln, cfg.lr, 0.9, 0.999, 1e-8, 0.0, 7)
         torch.cuda.synchronize()
+        assert bool((lowp[:off] == -7.0).all()) and bool((lowp[off + ln:] == -7.0).all())
+        assert torch.equal(lowp[off:off + ln], p[off:off + ln].to(torch.bfloat16))      # nearest-even, as torch rounds
         for a, a0 in ((p, p0), (m, m0), (v, v0)):
             assert torch.equal(a[:off], a0[:off]) and torch.equal(a[off + ln:], a0[off + ln:])
         rng = np.random.default_rng(cfg.seed)

@@ -54,10 +54,7 @@ CONFIGS = {
     "c5": LayerConfig("c5", 2048, 16, 8192, 2048, True, 2, 6, "bf16", layers=24, vocab=50257, seed=1005,
                       shard_rule="frac29_seeded"),
     # Llama-style layers (sizes only): a 7B-class layer (H 4096, 32 heads, F 11008) and a small one for the oracle
-    # (weights N(0, 0.01^2): at H = 4096 the 0.02 of the GPT-2 family makes a random layer's branches several times larger
-    #  than the residual stream they are added to, which no trained network of this width looks like)
-    "l7b": LayerConfig("l7b", 4096, 32, 11008, 2048, True, 1, 4, "bf16", seed=1006, shard_rule="third_odd", kind="llama",
-                       init_std=0.01),
+    "l7b": LayerConfig("l7b", 4096, 32, 11008, 2048, True, 1, 4, "bf16", seed=1006, shard_rule="third_odd", kind="llama"),
     # TinyLlama-shaped stack (the paper's model table: 22 layers, H 2048, 32 heads; F 5632 and a 32000-entry vocabulary
     # are that model family's): the Llama-style counterpart of c5
     "ltiny": LayerConfig("ltiny", 2048, 32, 5632, 2048, True, 2, 6, "bf16", layers=22, vocab=32000, seed=1008,
@@ -69,10 +66,8 @@ CONFIGS = {
     "vitl": LayerConfig("vitl", 1024, 16, 4096, 197, False, 8, 2, "bf16", seed=1007, shard_rule="frac:50:23"),
     # two more of the paper's model table whose head widths are neither 64 nor 128: a GPT 2.7B-shaped layer (80 heads
     # of 32) and a ViT-G-shaped one (16 heads of 104, 257 tokens per image)
-    # (weights N(0, 0.01^2) as for l7b: with 0.02 the feed-forward branch of a random layer of these widths has a gain
-    #  above one, 0.02 sqrt(F) * 0.02 sqrt(H) = 1.5 and 2.0)
-    "g27": LayerConfig("g27", 2560, 80, 10240, 2048, True, 1, 4, "bf16", seed=1009, shard_rule="third_odd", init_std=0.01),
-    "vitg": LayerConfig("vitg", 1664, 16, 8192, 257, False, 8, 2, "bf16", seed=1010, shard_rule="frac:50:23", init_std=0.01),
+    "g27": LayerConfig("g27", 2560, 80, 10240, 2048, True, 1, 4, "bf16", seed=1009, shard_rule="third_odd"),
+    "vitg": LayerConfig("vitg", 1664, 16, 8192, 257, False, 8, 2, "bf16", seed=1010, shard_rule="frac:50:23"),
     # reduced relatives used only by parity tests (ragged tiles, small enough for the oracle)
     "c5mini": LayerConfig("c5mini", 256, 4, 1024, 128, True, 2, 2, "bf16", layers=2, vocab=1031, seed=1105,
                           shard_rule="frac29_seeded"),
