@@ -187,8 +187,8 @@ int cephalo_grad_accum(float* acc, const float* g, float scale, int64_t n, void*
  * step is 1-based.  Each element's arithmetic is the same instruction sequence wherever
  * the slice starts, so updates over any partition of [0,P) concatenate to the unsharded
  * update bit for bit.  The four fp32 base pointers must be 16-byte aligned; the kernel runs
- * at its full rate when they are congruent modulo 128 bytes (it starts its vector body where
- * p's address is a multiple of 128; buffers that sit elsewhere are still correct, only slower).
+ * at its full rate when they are congruent modulo 256 bytes (it starts its vector body where
+ * p's address is a multiple of 256; buffers that sit elsewhere are still correct, only slower).
  * Errors (nothing launched): slice outside [0, P), step < 1, beta outside [0, 1), eps < 0,
  * weight_decay < 0 or not finite, a NULL or misaligned buffer with len > 0. */
 int cephalo_shard_adam(float* p, const float* g, float* m, float* v, void* p_lowp,
@@ -387,9 +387,12 @@ typedef struct cephalo_cluster_model {
 /* Compute partition: micro-batch size m_i and micro-batch count l_i per GPU with sum_i m_i l_i = batch, minimising
  *   max_i [ max(l_i T_f^i(m_i), AG') + max(l_i T_b^i(m_i), AG' + RS') ]
  * where AG', RS' are the uneven latencies for a GPU whose compute memory plus an even state share exceeds its
- * capacity; M(m_i) <= capacity_i for every GPU and the cluster-wide memory must fit.  Dynamic programme over
- * (GPU, batch so far, sum of micro-batch sizes so far), O(N B^3 log B).  m_out, l_out: host, [n_gpus];
- * latency_out (may be NULL): the minimised layer latency.  CEPHALO_EUNSUPPORTED if nothing fits. */
+ * capacity; M(m_i) <= capacity_i for every GPU and the cluster-wide memory must fit; every GPU takes at least one
+ * sample.  Solved as a bottleneck problem: bisection over the candidate latencies, and for a candidate a dynamic
+ * programme over (GPU, batch so far) that keeps the least sum of micro-batch sizes, which is all the cluster-wide
+ * memory depends on: O(N B^2 log(N B)) time, tables of N x B entries (the supplementary algorithm spends N B^4 steps
+ * on a table of N x B x B).  m_out, l_out: host, [n_gpus]; latency_out (may be NULL): the minimised layer latency.
+ * CEPHALO_EUNSUPPORTED if nothing fits, if batch < n_gpus, or if n_gpus x batch exceeds 2^26. */
 int cephalo_plan_compute(int32_t n_gpus, const cephalo_gpu_perf* gpus, int32_t batch, const cephalo_cluster_model* cluster,
                          int32_t* m_out, int32_t* l_out, double* latency_out);
 
