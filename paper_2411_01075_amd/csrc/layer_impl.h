@@ -64,7 +64,9 @@ int check_desc(const cephalo_layer_desc* d) {
   if (hd > 128) return fail(CEPHALO_EUNSUPPORTED, "layer desc: head dim %d > 128", hd);
   if (d->dtype == CEPHALO_BF16 && hd % 8 != 0)
     return fail(CEPHALO_EUNSUPPORTED, "layer desc: bf16 attention needs a head dim that is a multiple of 8, got %d", hd);
-  if (d->hidden > 8192) return fail(CEPHALO_EUNSUPPORTED, "layer desc: hidden %d > 8192", d->hidden);
+  // a wavefront of the norm kernels holds one row in registers: 64 lanes x 16 vectors of 16 bytes of the activation type
+  const int widest = d->dtype == CEPHALO_F32 ? 4096 : 8192;
+  if (d->hidden > widest) return fail(CEPHALO_EUNSUPPORTED, "layer desc: hidden %d > %d (the limit for this dtype)", d->hidden, widest);
   return CEPHALO_OK;
 }
 
@@ -555,7 +557,7 @@ int run_share(const cephalo_layer_desc& d, const void* Pv, const float* x, float
   Streams J;
   J.main = s; J.side = side; J.on = side != nullptr;
   TRY(J.open());
-  struct JCloser { Streams& j; ~JCloser() { (void)j.close(); } } jcloser{J};
+  struct JCloser { Streams& j; bool done = false; ~JCloser() { if (!done) (void)j.close(); } } jcloser{J};   // early exits still join
   const Work<T> w0 = work_at<T>(scratch, W, d, 0, 0, m);
   TRY(make_lowp<T>(w0.dyl, dy, (int64_t)l * act, s));
   const T* dyl = lowp_of<T>(dy, w0.dyl);
@@ -572,7 +574,8 @@ int run_share(const cephalo_layer_desc& d, const void* Pv, const float* x, float
   J.join();
   J.fork();      // the parameter pass's reductions beside its GEMMs
   TRY(layer_bwd_params_t<T>(d, dy, dyl, b * d.seq, l * ln_bwd_blocks(m * d.seq), saved_at<T>(save, L, d, 0), w0, G, scale, 0, s, st[1]));
-  return J.err;   // (the closer joins)
+  jcloser.done = true;
+  return J.close();      // joins the streams; an error of the join or of the event release is the call's result
 }
 
 int check_io(const char* who, const cephalo_layer_desc* d, int m, std::initializer_list<const void*> ptrs) {

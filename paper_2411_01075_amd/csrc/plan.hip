@@ -5,6 +5,7 @@
 #include <algorithm>
 #include <cmath>
 #include <limits>
+#include <new>
 #include <numeric>
 #include <vector>
 
@@ -17,7 +18,7 @@ constexpr double kInf = std::numeric_limits<double>::infinity();
 int check_plan_args(int32_t n, const cephalo_gpu_perf* g, int32_t B, const cephalo_cluster_model* c) {
   if (n <= 0 || B <= 0) return fail(CEPHALO_EINVAL, "plan: %d GPUs and batch %d must be positive", n, B);
   if (!g || !c) return fail(CEPHALO_EINVAL, "plan: null model");
-  if ((int64_t)n * B * B > ((int64_t)1 << 31)) return fail(CEPHALO_EUNSUPPORTED, "plan: table of %d x %d x %d entries is too large", n, B, B);
+  if ((int64_t)n * B > ((int64_t)1 << 26)) return fail(CEPHALO_EUNSUPPORTED, "plan: %d GPUs x batch %d is beyond the planner's tables (2^26 entries)", n, B);
   for (int i = 0; i < n; ++i) {
     if (!g[i].t_fwd || !g[i].t_bwd) return fail(CEPHALO_EINVAL, "plan: GPU %d has no latency table", i);
     if (g[i].max_m < 1) return fail(CEPHALO_EINVAL, "plan: GPU %d: latency tables must cover micro-batch size 1", i);
@@ -35,6 +36,90 @@ double latency(const double* table, int max_m, int m) {
   return table[max_m] + slope * (m - max_m);
 }
 
+// One way for a GPU to take a share: l micro-batches of m samples, and what a layer then costs on that GPU.
+struct Option {
+  double t;      // max(l T_f(m), AG') + max(l T_b(m), AG' + RS')
+  int32_t m, l;
+};
+
+// The compute partition as a bottleneck problem.  The objective is the largest per-GPU latency, so the optimum is one
+// of the finitely many option latencies, and "is there a plan in which no GPU exceeds tau" is monotone in tau.  For a
+// given tau a GPU's admissible options reduce to cost(b) = the smallest micro-batch size with which it can take a
+// share of b samples within tau; the cluster-wide memory (constraint III) grows with the sum of the micro-batch sizes
+// and with nothing else, so a plan exists iff the least sum over all ways to split the batch fits:
+//   least[i][j] = min over b of least[i-1][j-b] + cost_i(b)          (first i GPUs take j samples between them)
+// The threshold is found by bisection over the sorted option latencies.  O(N B^2) per probe, O(log(N B log B))
+// probes, tables of N x B entries (the supplementary algorithm's table has N x B x B and its loops N B^4 steps).
+struct Planner {
+  int n, B;
+  const cephalo_gpu_perf* gpus;
+  const cephalo_cluster_model* c;
+  std::vector<std::vector<Option>> options;      // per GPU, every (m, l) whose compute memory fits that GPU
+  std::vector<int32_t> least, pick_m, pick_l;    // [(n + 1) x (B + 1)]; least = kNone where no split exists
+  std::vector<int32_t> cost, cost_l;             // [B + 1], of the GPU at hand
+  double cap_sum = 0.0;
+  static constexpr int32_t kNone = std::numeric_limits<int32_t>::max();
+
+  Planner(int n_, int B_, const cephalo_gpu_perf* g, const cephalo_cluster_model* c_) : n(n_), B(B_), gpus(g), c(c_) {
+    const double state_even = c->state_bytes / n;
+    options.resize(n);
+    for (int i = 0; i < n; ++i) {
+      cap_sum += g[i].mem_cap;
+      for (int m = 1; m <= B; ++m) {
+        const double mem = c->mem_base + c->mem_per_sample * m;
+        if (mem > g[i].mem_cap) break;                          // constraint II; the compute memory grows with m
+        const bool uneven = mem + state_even > g[i].mem_cap;    // this GPU cannot hold an even share of the state as well
+        const double ag = uneven ? c->allgather_uneven : c->allgather, rs = uneven ? c->reducescatter_uneven : c->reducescatter;
+        const double tf = latency(g[i].t_fwd, g[i].max_m, m), tb = latency(g[i].t_bwd, g[i].max_m, m);
+        for (int l = 1; l * m <= B; ++l) options[i].push_back({std::max(l * tf, ag) + std::max(l * tb, ag + rs), m, l});
+      }
+    }
+    least.assign((size_t)(n + 1) * (B + 1), kNone);
+    pick_m.assign(least.size(), 0);
+    pick_l.assign(least.size(), 0);
+    cost.resize(B + 1);
+    cost_l.resize(B + 1);
+  }
+  bool memory_fits(int64_t sum_m) const { return !(c->state_bytes + n * c->mem_base + c->mem_per_sample * (double)sum_m > cap_sum); }
+
+  // Is there a plan with every GPU within tau?  Leaves the tables filled for read_plan().
+  bool feasible(double tau) {
+    std::fill(least.begin(), least.end(), kNone);
+    least[0] = 0;
+    for (int i = 1; i <= n; ++i) {
+      std::fill(cost.begin(), cost.end(), kNone);
+      for (const Option& o : options[i - 1]) {
+        const int b = o.m * o.l;
+        if (o.t <= tau && o.m < cost[b]) { cost[b] = o.m; cost_l[b] = o.l; }
+      }
+      const int32_t* prev = &least[(size_t)(i - 1) * (B + 1)];
+      int32_t* cur = &least[(size_t)i * (B + 1)];
+      for (int j = i; j <= B - (n - i); ++j) {        // every GPU takes at least one sample
+        int32_t best = kNone, bm = 0, bl = 0;
+        for (int b = 1; b <= j - (i - 1); ++b) {
+          if (cost[b] == kNone || prev[j - b] == kNone) continue;
+          const int32_t v = prev[j - b] + cost[b];
+          if (v < best) { best = v; bm = cost[b]; bl = cost_l[b]; }
+        }
+        cur[j] = best;
+        pick_m[(size_t)i * (B + 1) + j] = bm;
+        pick_l[(size_t)i * (B + 1) + j] = bl;
+      }
+    }
+    const int32_t total = least[(size_t)n * (B + 1) + B];
+    return total != kNone && memory_fits(total);
+  }
+  void read_plan(int32_t* m_out, int32_t* l_out) const {
+    int j = B;
+    for (int i = n; i >= 1; --i) {
+      const size_t at = (size_t)i * (B + 1) + j;
+      m_out[i - 1] = pick_m[at];
+      l_out[i - 1] = pick_l[at];
+      j -= pick_m[at] * pick_l[at];
+    }
+  }
+};
+
 }  // namespace
 
 extern "C" int cephalo_plan_compute(int32_t n, const cephalo_gpu_perf* gpus, int32_t B, const cephalo_cluster_model* c,
@@ -44,55 +129,27 @@ extern "C" int cephalo_plan_compute(int32_t n, const cephalo_gpu_perf* gpus, int
     if (rc != CEPHALO_OK) return rc;
   }
   if (!m_out || !l_out) return fail(CEPHALO_EINVAL, "plan: null output");
-  const double state_even = c->state_bytes / n;       // an even share of the training state
-  auto mem = [&](int m) { return c->mem_base + c->mem_per_sample * m; };
-  // D[i][j][k]: least achievable layer latency for the first i GPUs to take batch j with micro-batch sizes summing to k
-  const size_t stride_i = (size_t)(B + 1) * (B + 1), stride_j = (size_t)(B + 1);
-  std::vector<double> D((size_t)(n + 1) * stride_i, kInf);
-  std::vector<int32_t> choice_m((size_t)(n + 1) * stride_i, 0), choice_l((size_t)(n + 1) * stride_i, 0);
-  D[0] = 0.0;
-  for (int i = 1; i <= n; ++i) {
-    const cephalo_gpu_perf& g = gpus[i - 1];
-    for (int j = 1; j <= B; ++j)
-      for (int k = 1; k <= j; ++k) {
-        double best = kInf;
-        int bm = 0, bl = 0;
-        for (int m = 1; m <= k; ++m) {
-          if (mem(m) > g.mem_cap) break;              // compute memory alone must fit (and it grows with m)
-          const bool uneven = mem(m) + state_even > g.mem_cap;    // then this GPU cannot hold an even share of the state
-          const double ag = uneven ? c->allgather_uneven : c->allgather, rs = uneven ? c->reducescatter_uneven : c->reducescatter;
-          const double tf1 = latency(g.t_fwd, g.max_m, m), tb1 = latency(g.t_bwd, g.max_m, m);
-          for (int l = 1; l * m <= j; ++l) {
-            const double prev = D[(size_t)(i - 1) * stride_i + (size_t)(j - l * m) * stride_j + (k - m)];
-            if (prev == kInf) continue;
-            const double t = std::max(l * tf1, ag) + std::max(l * tb1, ag + rs);
-            const double r = std::max(prev, t);
-            if (r < best) { best = r; bm = m; bl = l; }
-          }
-        }
-        const size_t at = (size_t)i * stride_i + (size_t)j * stride_j + k;
-        D[at] = best; choice_m[at] = bm; choice_l[at] = bl;
-      }
+  if (B < n) return fail(CEPHALO_EUNSUPPORTED, "plan: batch %d cannot give each of %d GPUs a sample", B, n);
+  try {
+    Planner P(n, B, gpus, c);
+    std::vector<double> taus;
+    for (const auto& v : P.options)
+      for (const Option& o : v) taus.push_back(o.t);
+    std::sort(taus.begin(), taus.end());
+    taus.erase(std::unique(taus.begin(), taus.end()), taus.end());
+    if (taus.empty() || !P.feasible(taus.back()))
+      return fail(CEPHALO_EUNSUPPORTED, "plan: no assignment of batch %d to %d GPUs fits in memory", B, n);
+    size_t lo = 0, hi = taus.size() - 1;            // the least feasible threshold lies in [lo, hi]
+    while (lo < hi) {
+      const size_t mid = lo + (hi - lo) / 2;
+      if (P.feasible(taus[mid])) hi = mid; else lo = mid + 1;
+    }
+    P.feasible(taus[lo]);                           // (the tables of the answer)
+    P.read_plan(m_out, l_out);
+    if (latency_out) *latency_out = taus[lo];
+  } catch (const std::bad_alloc&) {
+    return fail(CEPHALO_EUNSUPPORTED, "plan: out of host memory for %d GPUs x batch %d", n, B);
   }
-  // the total micro-batch size k fixes the aggregate compute memory: keep the k whose cluster-wide memory fits
-  double cap_sum = 0.0;
-  for (int i = 0; i < n; ++i) cap_sum += gpus[i].mem_cap;
-  double best = kInf;
-  int best_k = -1;
-  for (int k = 1; k <= B; ++k) {
-    const double aggregate = c->state_bytes + n * c->mem_base + c->mem_per_sample * k;
-    if (aggregate > cap_sum) continue;
-    const double v = D[(size_t)n * stride_i + (size_t)B * stride_j + k];
-    if (v < best) { best = v; best_k = k; }
-  }
-  if (best_k < 0) return fail(CEPHALO_EUNSUPPORTED, "plan: no assignment of batch %d to %d GPUs fits in memory", B, n);
-  int j = B, k = best_k;
-  for (int i = n; i >= 1; --i) {
-    const size_t at = (size_t)i * stride_i + (size_t)j * stride_j + k;
-    m_out[i - 1] = choice_m[at]; l_out[i - 1] = choice_l[at];
-    j -= choice_m[at] * choice_l[at]; k -= choice_m[at];
-  }
-  if (latency_out) *latency_out = best;
   return CEPHALO_OK;
 }
 

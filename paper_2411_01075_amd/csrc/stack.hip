@@ -4,7 +4,6 @@
 // parameter-gradient pass of every layer taken once over all b*S tokens.
 #include <cstring>
 #include "layer_impl.h"
-#include <rocprim/device/device_radix_sort.hpp>
 
 namespace cephalo {
 namespace {
@@ -100,30 +99,92 @@ __global__ void __launch_bounds__(kThreads) mean_kernel(const float* __restrict_
   if (threadIdx.x == 0) out[0] = s / (float)n;
 }
 
-__global__ void __launch_bounds__(kThreads) sort_keys_kernel(const int* __restrict__ ids, int* __restrict__ keys, int* __restrict__ vals, int n, int V) {
+// ---- sort of the tokens by id.  A key is (id << 32) | token index: all keys differ, so any sorting network gives the
+// one ascending order, which inside a run of equal ids is ascending token index.  Bitonic network over npad = a power
+// of two >= n keys (the padding holds the largest key and stays at the end): compare-exchange partners at distance
+// j < kSortTile are handled inside LDS, a tile of kSortTile keys per block; larger distances take one pass over global
+// memory each.  b*S <= 2^24 tokens: at most 24 stages.
+typedef unsigned long long u64;
+constexpr int kSortTile = 2048;                 // keys per block (16 KiB of LDS), two per thread
+constexpr int kSortThreads = kSortTile / 2;
+
+__global__ void __launch_bounds__(kThreads) sort_keys_kernel(const int* __restrict__ ids, u64* __restrict__ keys, int n, int npad, int V) {
   const int i = blockIdx.x * kThreads + threadIdx.x;
-  if (i < n) { keys[i] = clamp_id(ids[i], V); vals[i] = i; }
+  if (i < npad) keys[i] = i < n ? ((u64)(unsigned)clamp_id(ids[i], V) << 32) | (unsigned)i : ~(u64)0;
 }
 
-// Token-embedding gradient: tokens sorted by id (stable, so ascending token index inside a run); the wavefront at
-// the head of each run of equal ids sums the run's rows of dx0 in that order and adds the sum to the id's row of
-// the gradient (which already holds the LM-head part).  One writer per row, fixed order: reproducible.
+// Stages k = k_lo, 2 k_lo, .. k_hi of the network, each from partner distance min(k / 2, kSortTile / 2) down to 1.
+// (2 .. kSortTile: sorts every tile; k_lo = k_hi > kSortTile: the tail of stage k after its global passes.)
+__global__ void __launch_bounds__(kSortThreads) bitonic_tile_kernel(u64* __restrict__ keys, int k_lo, int k_hi) {
+  __shared__ u64 tile[kSortTile];
+  const int t = threadIdx.x, base = blockIdx.x * kSortTile;
+  tile[t] = keys[base + t];
+  tile[t + kSortThreads] = keys[base + t + kSortThreads];
+  __syncthreads();
+  for (int k = k_lo; k <= k_hi; k <<= 1) {
+    for (int j = (k >> 1) < kSortThreads ? (k >> 1) : kSortThreads; j > 0; j >>= 1) {
+      const int i = ((t & ~(j - 1)) << 1) | (t & (j - 1)), l = i | j;
+      const bool ascending = ((base + i) & k) == 0;
+      const u64 a = tile[i], b = tile[l];
+      if ((a > b) == ascending) { tile[i] = b; tile[l] = a; }
+      __syncthreads();
+    }
+  }
+  keys[base + t] = tile[t];
+  keys[base + t + kSortThreads] = tile[t + kSortThreads];
+}
+
+// One pass of stage k at partner distance j >= kSortTile, straight on global memory; one pair per thread.
+__global__ void __launch_bounds__(kThreads) bitonic_pass_kernel(u64* __restrict__ keys, int k, int j, int pairs) {
+  const int t = blockIdx.x * kThreads + threadIdx.x;
+  if (t >= pairs) return;
+  const int i = ((t & ~(j - 1)) << 1) | (t & (j - 1)), l = i | j;
+  const bool ascending = (i & k) == 0;
+  const u64 a = keys[i], b = keys[l];
+  if ((a > b) == ascending) { keys[i] = b; keys[l] = a; }
+}
+
+int sort_pad(int n) {
+  int p = kSortTile;
+  while (p < n) p <<= 1;
+  return p;
+}
+
+int launch_sort_tokens(const int* ids, u64* keys, int n, int V, hipStream_t s) {
+  const int npad = sort_pad(n);
+  sort_keys_kernel<<<(npad + kThreads - 1) / kThreads, kThreads, 0, s>>>(ids, keys, n, npad, V);
+  CEPHALO_CHECK_LAUNCH("sort_keys");
+  bitonic_tile_kernel<<<npad / kSortTile, kSortThreads, 0, s>>>(keys, 2, kSortTile);
+  CEPHALO_CHECK_LAUNCH("bitonic_tile");
+  for (int k = 2 * kSortTile; k <= npad; k <<= 1) {
+    for (int j = k >> 1; j >= kSortTile; j >>= 1) {
+      bitonic_pass_kernel<<<(npad / 2 + kThreads - 1) / kThreads, kThreads, 0, s>>>(keys, k, j, npad / 2);
+      CEPHALO_CHECK_LAUNCH("bitonic_pass");
+    }
+    bitonic_tile_kernel<<<npad / kSortTile, kSortThreads, 0, s>>>(keys, k, k);
+    CEPHALO_CHECK_LAUNCH("bitonic_tile");
+  }
+  return CEPHALO_OK;
+}
+
+// Token-embedding gradient: tokens sorted by (id, token index); the wavefront at the head of each run of equal ids
+// sums the run's rows of dx0 in that order and adds the sum to the id's row of the gradient (which already holds
+// the LM-head part).  One writer per row, fixed order: reproducible.
 __global__ void __launch_bounds__(kThreads)
-embed_bwd_kernel(const int* __restrict__ keys, const int* __restrict__ vals, const float* __restrict__ dx0, float* __restrict__ g_wte,
-                 int n, int H) {
+embed_bwd_kernel(const u64* __restrict__ sorted, const float* __restrict__ dx0, float* __restrict__ g_wte, int n, int H) {
   typedef float T;
   constexpr int VN = Vec<T>::N;
   const int i = blockIdx.x * 4 + (threadIdx.x >> 6), lane = threadIdx.x & 63;
   if (i >= n) return;
-  const int key = keys[i];
-  if (i > 0 && keys[i - 1] == key) return;
+  const unsigned key = (unsigned)(sorted[i] >> 32);
+  if (i > 0 && (unsigned)(sorted[i - 1] >> 32) == key) return;
   for (int v = lane; v < H / VN; v += 64) {
     float acc[VN];
 #pragma unroll
     for (int c = 0; c < VN; ++c) acc[c] = 0.f;
-    for (int j = i; j < n && keys[j] == key; ++j) {
+    for (int j = i; j < n && (unsigned)(sorted[j] >> 32) == key; ++j) {
       float a[VN];
-      load_vec<T>(dx0 + (int64_t)vals[j] * H + v * VN, a);
+      load_vec<T>(dx0 + (int64_t)(unsigned)sorted[j] * H + v * VN, a);
 #pragma unroll
       for (int c = 0; c < VN; ++c) acc[c] += a[c];
     }
@@ -208,17 +269,8 @@ int check_stack(const cephalo_stack_desc* d) {
   return CEPHALO_OK;
 }
 
-size_t sort_temp_bytes(int n) {
-  size_t bytes = 0;
-  const hipError_t e = rocprim::radix_sort_pairs(nullptr, bytes, (int*)nullptr, (int*)nullptr, (int*)nullptr, (int*)nullptr,
-                                                 (size_t)n, 0, 32, (hipStream_t)0);
-  const size_t floor_bytes = (size_t)n * 16 + ((size_t)1 << 20);   // also covers a size query that fails without a device
-  if (e != hipSuccess) (void)hipGetLastError();
-  return (e == hipSuccess && bytes > floor_bytes) ? bytes : floor_bytes;
-}
-
 struct StackLayout {
-  size_t xs, xdump, saves, save_each, scratch, dxa, dxb, dxal, dxbl, uf, meanf, rstdf, duf, logits, dlogits, wteT, loss, lnf_part, keys, sort_tmp, sort_tmp_bytes, total;
+  size_t xs, xdump, saves, save_each, scratch, dxa, dxb, dxal, dxbl, uf, meanf, rstdf, duf, logits, dlogits, wteT, loss, lnf_part, keys, total;
   int ldv;            // padded pitch of the logits
   size_t lnf_rows;
 };
@@ -249,9 +301,7 @@ StackLayout stack_layout(const cephalo_stack_desc& d, int b, int m) {
   L.loss = take(n * 4);
   L.lnf_rows = (size_t)(b / m) * ln_bwd_blocks((int)Tm);
   L.lnf_part = take(2 * L.lnf_rows * H * 4);
-  L.keys = take(4 * n * 4);
-  L.sort_tmp_bytes = sort_temp_bytes((int)n);
-  L.sort_tmp = take(L.sort_tmp_bytes);
+  L.keys = take((size_t)sort_pad((int)n) * sizeof(u64));      // (id, token index) keys of the embedding gradient's sort
   L.total = p;
   return L;
 }
@@ -356,7 +406,7 @@ int run_stack(const cephalo_stack_desc& d, const void* Pv, const int* ids, const
   Streams J;
   J.main = s; J.side = side; J.on = d.interleave != 0;
   TRY(J.open());
-  struct JCloser { Streams& j; ~JCloser() { (void)j.close(); } } jcloser{J};
+  struct JCloser { Streams& j; bool done = false; ~JCloser() { if (!done) (void)j.close(); } } jcloser{J};   // early exits still join
   const size_t act = (size_t)Tm * H;
   Boundary X;
   X.offload = d.offload != 0;
@@ -474,15 +524,14 @@ int run_stack(const cephalo_stack_desc& d, const void* Pv, const int* ids, const
     zero_kernel<<<(int)((n4 + kThreads - 1) / kThreads), kThreads, 0, s>>>(G + o_wte, n4);
     CEPHALO_CHECK_LAUNCH("zero_wte_grad");
   }
-  int* keys_in = at<int>(ws, L.keys); int* vals_in = keys_in + n; int* keys_out = vals_in + n; int* vals_out = keys_out + n;
-  sort_keys_kernel<<<(n + kThreads - 1) / kThreads, kThreads, 0, s>>>(ids, keys_in, vals_in, n, V);
-  size_t tmp = L.sort_tmp_bytes;
-  if (rocprim::radix_sort_pairs(at<char>(ws, L.sort_tmp), tmp, keys_in, keys_out, vals_in, vals_out, (size_t)n, 0, 32, s) != hipSuccess)
-    return fail(CEPHALO_EHIP, "stack_step: sort of the token ids failed");
-  embed_bwd_kernel<<<(n + 3) / 4, kThreads, 0, s>>>(keys_out, vals_out, dx_cur, G + o_wte, n, H);
+  u64* keys = at<u64>(ws, L.keys);
+  TRY(launch_sort_tokens(ids, keys, n, V, s));
+  embed_bwd_kernel<<<(n + 3) / 4, kThreads, 0, s>>>(keys, dx_cur, G + o_wte, n, H);
   CEPHALO_CHECK_LAUNCH("embed_bwd");
   closer.done = true;
-  return X.close();
+  jcloser.done = true;
+  const int rc_join = J.close(), rc_copy = X.close();      // errors of the final join and of the event releases are the call's result
+  return rc_join != CEPHALO_OK ? rc_join : rc_copy;
 }
 
 }  // namespace

@@ -34,12 +34,12 @@ __device__ __forceinline__ void adam_element(float& p, float g, float& m, float&
 constexpr int kAdamThreads = 64;
 // The body starts where p's address is a multiple of this many bytes.  A wavefront's 1 KiB store that starts inside
 // a 128-byte line leaves two partly written lines behind, and streaming stores are not merged afterwards: the same
-// slice starting 32 bytes into a line runs at 4.5 TB/s instead of 5.5.
-constexpr int kAdamAlignBytes = 128;
-static_assert(kAdamAlignBytes / 4 - 1 < 32 && kAdamThreads >= 32 + 3, "head lanes 0..30 and tail lanes 32..34 of block 0");
+// slice starting 32 bytes into a line runs at 4.5 TB/s instead of 5.5.  256 rather than 128, so that the bf16 copy's
+// 512-byte stores (half as many bytes per element) start on a line as well.
+constexpr int kAdamAlignBytes = 256;
 
-// Slice = head (scalar, up to 31 elements, until p's address is a multiple of 128 bytes; with all four base pointers
-//               congruent modulo 128 that holds for every buffer)
+// Slice = head (scalar, up to 63 elements, until p's address is a multiple of 256 bytes; with all four base pointers
+//               congruent modulo 256 that holds for every buffer)
 //       + body (nvec groups of 4, 16-byte aligned in every buffer) + tail (scalar, up to 3).
 template <bool kLowp, bool kDecay>
 __global__ void __launch_bounds__(kAdamThreads)
@@ -72,15 +72,12 @@ shard_adam_kernel(float* __restrict__ p, const float* __restrict__ g, float* __r
       __builtin_nontemporal_store(q, reinterpret_cast<bf16x4*>(p_lowp + body0) + i);
     }
   }
-  // Scalar head and tail: at most 31 + 3 elements, taken by the lanes of block 0 (head: lanes 0..30, tail: 32..34).
+  // Scalar head and tail: at most 63 + 3 elements, taken by the lanes of block 0.
   if (blockIdx.x == 0) {
     const int64_t tail0 = head + 4 * nvec;  // slice-relative start of the tail
     const int64_t ntail = len - tail0;
-    int64_t rel = -1;
-    if ((int64_t)threadIdx.x < head) rel = threadIdx.x;
-    else if ((int64_t)threadIdx.x >= 32 && (int64_t)threadIdx.x - 32 < ntail) rel = tail0 + (threadIdx.x - 32);
-    if (rel >= 0) {
-      const int64_t i = offset + rel;
+    for (int64_t r = threadIdx.x; r < head + ntail; r += kAdamThreads) {
+      const int64_t i = offset + (r < head ? r : tail0 + (r - head));
       float pi = p[i], mi = m[i], vi = v[i];
       adam_element<kDecay>(pi, g[i], mi, vi, h);
       p[i] = pi; m[i] = mi; v[i] = vi;

@@ -66,6 +66,17 @@ def test_bad_desc_is_rejected(kw):
     assert "cephalo error -1" in str(e.value)
 
 
+def test_widths_the_norm_kernels_cannot_hold_are_refused_up_front():
+    """A row of the norm kernels lives in one wavefront's registers: up to 8192 columns of bf16-mode activations, 4096
+    in fp32 mode.  The desc check refuses wider layers, so no launch sequence starts that could not finish."""
+    assert C.cephalo_layer_param_count(C.layer_desc(8192, 64, 8192, 16, True, C.BF16)) > 0
+    assert C.cephalo_layer_param_count(C.layer_desc(4096, 32, 4096, 16, True, C.F32)) > 0
+    for H, dt in ((8200, C.BF16), (4104, C.F32), (8192, C.F32)):
+        with pytest.raises(C.CephaloError) as e:
+            C.cephalo_layer_param_count(C.layer_desc(H, H // 8, 64, 16, True, dt))
+        assert "cephalo error -2" in str(e.value)
+
+
 def test_unsupported_head_dim():
     with pytest.raises(C.CephaloError) as e:
         C.cephalo_layer_param_count(C.layer_desc(200, 2, 384, 16, True, C.BF16))   # head dim 100: not a multiple of 8

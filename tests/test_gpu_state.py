@@ -18,7 +18,7 @@ HYP = {k: float(np.float32(x)) for k, x in dict(lr=1e-3, beta1=0.9, beta2=0.999,
 
 def shifted(a, shift):
     """A device copy of `a` whose first element sits `shift` floats after a 512-byte boundary (torch's allocations
-    start on one), so that the kernel's head, the part before its 128-byte aligned body, takes every length."""
+    start on one), so that the kernel's head, the part before its 256-byte aligned body, takes every length."""
     buf = torch.empty(a.size + shift, dtype=torch.float32, device="cuda")
     buf[shift:].copy_(torch.from_numpy(a))
     return buf[shift:]
@@ -66,10 +66,10 @@ def test_shard_adam_matches_oracle(P, off, ln, t):
     check_against_oracle(p, g, m, v, off, ln, t, got)
 
 
-@pytest.mark.parametrize("shift", [4, 8, 28, 36])
-@pytest.mark.parametrize("off,ln", [(0, 5000), (3, 4000), (29, 131), (125, 4875)])
+@pytest.mark.parametrize("shift", [4, 8, 28, 36, 60])
+@pytest.mark.parametrize("off,ln", [(0, 5000), (3, 4000), (29, 131), (125, 4875), (1, 62), (1, 63), (1, 66), (1, 67), (65, 70)])
 def test_shard_adam_wherever_the_buffers_sit(shift, off, ln):
-    """The kernel's scalar head runs until p's address is a multiple of 128 bytes: every head length, and buffers
+    """The kernel's scalar head runs until p's address is a multiple of 256 bytes: every head length, and buffers
     whose bases are not themselves on such a boundary, give the bits of the aligned run."""
     P = 5000
     rng = np.random.default_rng(shift + off)

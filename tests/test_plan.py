@@ -39,6 +39,46 @@ def test_dp_matches_exhaustive_search(seed):
     assert tuple(zip(m, l)) in [tuple(a) for a in args]          # the returned plan is one of the optima
 
 
+@pytest.mark.parametrize("seed", range(4))
+def test_dp_matches_exhaustive_search_with_tight_memory(seed):
+    """Three GPUs, batch up to 10, capacities chosen so that constraint II caps the micro-batch sizes and constraint III
+    (cluster-wide memory) excludes the plans with the largest micro-batches."""
+    rng = np.random.default_rng(40 + seed)
+    n, B = 3, int(rng.integers(7, 11))
+    gpus = [(g[0], g[1], float(rng.uniform(6.0, 14.0))) for g in random_cluster(rng, n, 4)]
+    ag, rs = rng.uniform(0.5, 6.0), rng.uniform(0.5, 6.0)
+    mem_base, mem_per, state = 1.0, float(rng.uniform(0.8, 1.5)), float(rng.uniform(8.0, 16.0))
+    cl = C.cluster_model(ag, rs, mem_base, mem_per, state)
+    ref, args = oplan.brute_force_plan(gpus, B, ag, rs, 1.15 * ag, 1.15 * rs, mem_base, mem_per, state)
+    if not np.isfinite(ref):
+        with pytest.raises(C.CephaloError, match="error -2"):
+            C.cephalo_plan_compute(gpus, B, cl)
+        return
+    m, l, lat = C.cephalo_plan_compute(gpus, B, cl)
+    assert abs(lat - ref) <= 1e-9 * ref
+    assert tuple(zip(m, l)) in [tuple(a) for a in args]
+
+
+def test_planner_scales_to_a_cluster():
+    """16 GPUs of four kinds and a global batch of 512 (the paper's largest clusters and batches are of this order): the
+    plan is feasible, exact in its batch, and found in seconds with tables of N x B entries."""
+    import time
+    rng = np.random.default_rng(7)
+    gpus = random_cluster(rng, 16, 8)
+    cl = C.cluster_model(2.0, 2.0, 1.0, 0.5, 100.0)
+    t0 = time.perf_counter()
+    m, l, lat = C.cephalo_plan_compute(gpus, 512, cl)
+    assert time.perf_counter() - t0 < 30.0
+    assert sum(a * b for a, b in zip(m, l)) == 512 and all(a >= 1 and b >= 1 for a, b in zip(m, l))
+    per_gpu = [oplan.gpu_latency(g[0], g[1], g[2], a, b, 1.0, 0.5, 100.0 / 16, 2.0, 2.0, 2.3, 2.3) for g, a, b in zip(gpus, m, l)]
+    assert max(per_gpu) == pytest.approx(lat, rel=1e-12)
+    assert all(1.0 + 0.5 * a <= g[2] for g, a in zip(gpus, m))
+    assert 100.0 + sum(1.0 + 0.5 * a for a in m) <= sum(g[2] for g in gpus)
+    # fewer samples than GPUs: no plan
+    with pytest.raises(C.CephaloError, match="error -2"):
+        C.cephalo_plan_compute(gpus, 8, cl)
+
+
 def test_uneven_gpus_get_uneven_batches():
     """A GPU three times as fast takes about three times the batch (the point of Sec. 3.1's compute partitioning)."""
     base = [0.0] + [1.0 * m for m in range(1, 9)]
