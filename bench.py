@@ -27,10 +27,21 @@ sys.path.insert(0, ROOT)
 
 PEAK_BF16_TFLOPS = 2500.0     # MI355X dense bf16 MFMA, published
 PEAK_HBM_GBS = 8000.0         # MI355X HBM3E, published
-# HBM bytes per launch (rocprofv3 --pmc FETCH_SIZE + WRITE_SIZE, scaled by the copy-kernel calibration; see
-# profiles/gemm_input_gradient_and_adam_hbm_traffic.txt) of the c5 input-gradient GEMM, mean of its three shapes, by the
-# number of kernels run side by side (which fixes the tile): 1: 256 x 128 tiles, 2: 256 x 256 tiles
-TRAFFIC_C5_DGRAD = {1: 207.0e6, 2: 207.0e6}
+TRAFFIC_FILE = os.path.join(ROOT, "profiles", "gemm_input_gradient_and_adam_hbm_traffic.txt")
+
+
+def traffic_from_profiles(key):
+    """HBM bytes per launch of a kernel, as measured with rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE (scaled by the
+    copy-kernel calibration) and recorded in profiles/: the line 'BENCH <key> = <bytes>'.  None if it is not there."""
+    try:
+        with open(TRAFFIC_FILE) as f:
+            for line in f:
+                parts = line.split()
+                if len(parts) == 4 and parts[0] == "BENCH" and parts[1] == key and parts[2] == "=":
+                    return float(parts[3])
+    except OSError:
+        pass
+    return None
 
 
 def layer_flops_per_microbatch(cfg):
@@ -65,6 +76,12 @@ def main():
                     help="stacks only: layer-boundary activation checkpointing with recomputation in the backward (one extra forward)")
     ap.add_argument("--single-stream", action="store_true",
                     help="one micro-batch at a time on one stream (the default runs two micro-batches side by side on two streams)")
+    ap.add_argument("--legs-only", action="store_true",
+                    help="skip the timed steps and run only the per-kernel legs (for a profile in which each GEMM kernel's line holds "
+                         "the legs' launches and nothing else); `value` is then null")
+    ap.add_argument("--traffic-probe", action="store_true",
+                    help="instead of the benchmark: launch, three times each, the kernels whose HBM traffic the roofline quotes (the "
+                         "dominant GEMM's shapes, a 1 GiB copy as calibration, the shard Adam), for a run under rocprofv3 --pmc")
     ap.add_argument("--offload", action="store_true",
                     help="stacks only, implies --checkpoint: the boundary activations live in pinned host memory and move on a second stream")
     args = ap.parse_args()
@@ -81,6 +98,9 @@ def main():
         print("bench.py: no GPU visible", file=sys.stderr)
         sys.exit(2)
     C.binding.lib()     # fail loudly if the HIP library is missing
+    if args.traffic_probe:
+        traffic_probe(C, torch, CONFIGS[args.workload])
+        return
     cfg = CONFIGS[args.workload]
     stack = cfg.layers > 1
     bf16 = cfg.dtype == "bf16"
@@ -156,18 +176,24 @@ def main():
                 C.cephalo_share_layer_step(desc, pcomp, x, y, dy, dx, b, m, save, G, 1.0, scratch)
             C.cephalo_shard_adam(p32, G, mom, var, plow, P, off, ln, lr, 0.9, 0.999, 1e-8, 0.0, t)
 
+    if args.legs_only:
+        args.steps, args.warmup = 0, 0
     for i in range(args.warmup):
         step(7 + i)
     torch.cuda.synchronize()
+    marks = [torch.cuda.Event(enable_timing=True) for _ in range(args.steps + 1)]      # on the stream every step starts and ends on
     t0 = time.perf_counter()
+    marks[0].record()
     for i in range(args.steps):
         step(7 + args.warmup + i)
+        marks[i + 1].record()
     torch.cuda.synchronize()
-    elapsed = time.perf_counter() - t0
-    ms_per_step = 1e3 * elapsed / args.steps
+    elapsed = time.perf_counter() - t0 if args.steps else float("nan")
+    ms_per_step = 1e3 * elapsed / max(args.steps, 1)
+    per_step = sorted(marks[i].elapsed_time(marks[i + 1]) for i in range(args.steps)) or [float("nan")]
     tokens_per_s = cfg.tokens_per_step * args.steps / elapsed
     step_flops = step_model_flops(cfg)
-    extras = {}
+    extras = {"step_ms_median": round(per_step[len(per_step) // 2], 4), "step_ms_min": round(per_step[0], 4)} if args.steps else {}
     if stack:
         extras["loss"] = round(float(loss.item()), 4)
         extras["activation_checkpointing"] = bool(args.checkpoint or args.offload)
@@ -177,7 +203,7 @@ def main():
             extras["host_area_GB"] = round(host_area.numel() * 4 / 1e9, 2)
         extras["workspace_GB"] = round(ws.numel() / 1e9, 2)
     extras["micro_batches_in_flight"] = 2 if interleave else 1
-    if bf16:
+    if bf16 and args.steps:
         extras["whole_step_model_tflops"] = round(step_flops / (elapsed / args.steps) / 1e12, 1)
         extras["whole_step_frac_of_bf16_peak"] = round(step_flops / (elapsed / args.steps) / 1e12 / PEAK_BF16_TFLOPS, 4)
 
@@ -233,6 +259,11 @@ def main():
         def add_leg(key, fn, flops, count, alone=False):
             # enough back-to-back launches (about 30 ms) that the clocks settle where they sit during the step.
             # fn(i, stream): launch number i of a pair (its own output buffers) on that stream.
+            # Every leg is timed alone on one stream; a per-micro-batch leg of a two-stream step is also timed the way
+            # that step launches it, in pairs, one kernel per stream, on the tile chosen for half the device.
+            one = lambda: fn(0, None)
+            first = timed(one, 2)
+            dur1 = timed(one, max(3, min(400, int(0.03 / max(first, 1e-6)))))
             if pairs and not alone:
                 C.cephalo_gemm_side_by_side(2)
                 first = timed_pairs(fn, 2)
@@ -240,12 +271,11 @@ def main():
                 sec = dur / 2                                                                  # device time per launch
                 C.cephalo_gemm_side_by_side(1)
             else:
-                one = lambda: fn(0, None)
-                first = timed(one, 2)
-                dur = sec = timed(one, max(3, min(400, int(0.03 / max(first, 1e-6)))))
-            g = legs.setdefault(key, {"sec": 0.0, "dur": 0.0, "flops": 0.0, "launches": 0, "side_by_side": 2 if (pairs and not alone) else 1})
+                dur = sec = dur1
+            g = legs.setdefault(key, {"sec": 0.0, "dur": 0.0, "dur1": 0.0, "flops": 0.0, "launches": 0, "side_by_side": 2 if (pairs and not alone) else 1})
             g["sec"] += sec * count
             g["dur"] += dur * count
+            g["dur1"] += dur1 * count
             g["flops"] += flops * count
             g["launches"] += count
 
@@ -292,27 +322,119 @@ def main():
             del Xs, dYs, Gw, wsb
         for g in legs.values():
             g["TFLOP/s"] = round(g["flops"] / g["sec"] / 1e12, 1)
+            g["frac_of_bf16_peak"] = round(g["flops"] / g["sec"] / 1e12 / PEAK_BF16_TFLOPS, 4)
             g["avg_launch_us"] = round(1e6 * g.pop("dur") / g["launches"], 1)      # a kernel's own duration (side by side: while sharing the device)
             g["ms_per_step"] = round(1e3 * g.pop("sec"), 3)
+            one = g.pop("dur1")
+            g["one_stream"] = {"TFLOP/s": round(g["flops"] / one / 1e12, 1), "frac_of_bf16_peak": round(g["flops"] / one / 1e12 / PEAK_BF16_TFLOPS, 4),
+                               "avg_launch_us": round(1e6 * one / g["launches"], 1), "ms_per_step": round(1e3 * one, 3)}
             g["flops_per_launch"] = g.pop("flops") / g["launches"]
         single = [k for k in legs if not k.startswith("weight gradient")]      # one kernel launch per call
         key = max(single, key=lambda k: legs[k]["ms_per_step"])
         d = legs[key]
-        # HBM bytes per launch from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE (profiles/gemm_input_gradient_and_adam_hbm_traffic.txt),
-        # measured for the c5 shapes of this leg only
-        traffic = TRAFFIC_C5_DGRAD.get(d["side_by_side"]) if (cfg.name == "c5" and key.startswith("input gradient, plain")) else None
+        # HBM bytes per launch from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE, read from the committed summary of
+        # `bench.py --traffic-probe` (measured for the c5 shapes of this leg only)
+        traffic = traffic_from_profiles("c5_input_gradient_bytes_per_launch") if (cfg.name == "c5" and key.startswith("input gradient, plain")) else None
         roofline = {"kernel": "gemm_mfma_kernel (v_mfma_f32_16x16x32_bf16), " + key, "bound": "mfma", "achieved": d["TFLOP/s"], "peak": PEAK_BF16_TFLOPS,
                     "unit": "TFLOP/s", "frac": round(d["TFLOP/s"] / PEAK_BF16_TFLOPS, 4), "traffic": traffic,
                     "avg_launch_us": d["avg_launch_us"], "flops_per_launch": d["flops_per_launch"], "launches_per_step": d["launches"],
-                    # side_by_side = 2: two such kernels share the device, one per stream; `achieved` is their joint rate,
-                    # 2 * flops_per_launch / avg_launch_us, against the whole device's peak
-                    "side_by_side": d["side_by_side"]}
+                    # side_by_side = 2: two such kernels share the device, one per stream, as the step runs them; `achieved`
+                    # is their joint rate, 2 * flops_per_launch / avg_launch_us, against the whole device's peak.  one_stream:
+                    # the same launches one at a time (each kernel has the device to itself, on the tile chosen for that).
+                    "side_by_side": d["side_by_side"], "one_stream": d["one_stream"]}
+        tot_pair = sum(g["ms_per_step"] for g in legs.values())
+        tot_one = sum(g["one_stream"]["ms_per_step"] for g in legs.values())
+        gemm_flops = sum(g["flops_per_launch"] * g["launches"] for g in legs.values())
+        extras["gemm_all_legs"] = {"flops_per_step": gemm_flops, "ms_per_step": round(tot_pair, 3),
+                                   "frac_of_bf16_peak": round(gemm_flops / (tot_pair * 1e-3) / 1e12 / PEAK_BF16_TFLOPS, 4),
+                                   "one_stream_ms_per_step": round(tot_one, 3),
+                                   "one_stream_frac_of_bf16_peak": round(gemm_flops / (tot_one * 1e-3) / 1e12 / PEAK_BF16_TFLOPS, 4)}
         extras["gemm_legs"] = legs
+
+        # ---- attention alone (forward; backward = rowsum(dO*O) + dQ kernel + dK/dV kernel), at the workload's shape.
+        # Model flops: 4 m S^2 H forward (half under a causal mask), twice that backward; the backward kernels recompute
+        # the scores and dP (7 products instead of 4), which is not counted.
+        A, S, m_ = cfg.heads, cfg.seq, cfg.micro_batch
+        qkv = rnd(T, 3 * H)
+        dO = rnd(T, H)
+        O = torch.empty(T, H, device="cuda", dtype=bt)
+        lse = torch.empty(m_ * A * S, device="cuda")
+        dvec = torch.empty(m_ * A * S, device="cuda")
+        dqkv = torch.empty(T, 3 * H, device="cuda", dtype=bt)
+        af = 4.0 * m_ * S * S * H * (0.5 if cfg.causal else 1.0)
+        t_f = timed(lambda: C.cephalo_op_attention_fwd(desc, qkv, O, lse, m_), 50)
+        t_b = timed(lambda: C.cephalo_op_attention_bwd(desc, qkv, O, dO, lse, dvec, dqkv, m_), 30)
+        extras["attention"] = {
+            "forward": {"us": round(t_f * 1e6, 1), "model_TFLOP/s": round(af / t_f / 1e12, 1), "frac_of_bf16_peak": round(af / t_f / 1e12 / PEAK_BF16_TFLOPS, 4)},
+            "backward": {"us": round(t_b * 1e6, 1), "model_TFLOP/s": round(2 * af / t_b / 1e12, 1), "frac_of_bf16_peak": round(2 * af / t_b / 1e12 / PEAK_BF16_TFLOPS, 4)},
+            "ms_per_step": round(1e3 * (t_f + t_b) * cfg.layers * l, 3)}
+        del qkv, dO, O, dqkv
+
+        # ---- the bandwidth-bound kernels alone: algorithmic bytes / time against the HBM peak
+        def gbs(nbytes, sec):
+            return {"us": round(sec * 1e6, 1), "GB/s": round(nbytes / sec / 1e9, 1), "frac_of_hbm_peak": round(nbytes / sec / 1e9 / PEAK_HBM_GBS, 4)}
+        xr = torch.randn(T, H, device="cuda")
+        gam, bet = torch.ones(H, device="cuda", dtype=bt), torch.zeros(H, device="cuda", dtype=bt)
+        u_ = torch.empty(T, H, device="cuda", dtype=bt)
+        mean_, rstd_ = torch.empty(T, device="cuda"), torch.empty(T, device="cuda")
+        t_lnf = timed(lambda: C.cephalo_op_norm_fwd(C.BF16, False, xr, gam, bet, u_, mean_, rstd_, T, H, 1e-5), 100)
+        du_, res_, dx_ = torch.randn(T, H, device="cuda"), torch.randn(T, H, device="cuda"), torch.empty(T, H, device="cuda")
+        dxl_ = torch.empty(T, H, device="cuda", dtype=bt)
+        dg_, db_ = torch.empty(H, device="cuda"), torch.empty(H, device="cuda")
+        wsn = torch.empty(C.cephalo_op_norm_bwd_workspace(T, H), dtype=torch.uint8, device="cuda")
+        t_lnb = timed(lambda: C.cephalo_op_norm_bwd(C.BF16, False, du_, xr, mean_, rstd_, gam, res_, dx_, dxl_, dg_, db_, T, H, wsn), 100)
+        dzs = rnd(n_tok, F)
+        wsc = torch.empty(C.cephalo_op_colsum_workspace(n_tok, F), dtype=torch.uint8, device="cuda")
+        gF = torch.empty(F, device="cuda")
+        t_cs = timed(lambda: C.cephalo_op_colsum(C.BF16, dzs, n_tok, F, gF, 1.0, 0, wsc), 30)
+        extras["elementwise"] = {
+            # LayerNorm forward: reads the fp32 row, writes it in bf16 (+ 8 B of statistics per row)
+            "layer_norm_forward": gbs(T * (H * 6 + 8), t_lnf),
+            # backward with the partial sums of d gamma / d beta and their fixed-order reduction: reads du, x and the
+            # residual in fp32 (+ statistics), writes dx in fp32 and in bf16
+            "layer_norm_backward": gbs(T * (H * 18 + 8), t_lnb),
+            # bias gradient of the first feed-forward projection over the whole share: reads d z [b*S, F] in bf16
+            "bias_column_sum": gbs(n_tok * F * 2, t_cs),
+        }
+        del xr, u_, du_, res_, dx_, dxl_, dzs
+        if stack:
+            ldv = (V + 63) // 64 * 64
+            lg = torch.randn(T, ldv, device="cuda")
+            tg = torch.randint(0, V, (T,), device="cuda", dtype=torch.int32)
+            dl_ = torch.empty(T, ldv, device="cuda", dtype=bt)
+            lr_ = torch.empty(T, device="cuda")
+            t_ce = timed(lambda: C.cephalo_op_cross_entropy(C.BF16, lg, ldv, tg, dl_, lr_, T, V, 1.0 / n_tok), 30)
+            # two passes over the fp32 logits of a micro-batch, one write of their bf16 gradient
+            extras["elementwise"]["cross_entropy"] = gbs(T * ldv * (4 + 4 + 2), t_ce)
+            del lg, dl_
+
+    # ---- what this device sustains (probes of the library): a register-only stream of the GEMM's matrix instruction on
+    # random operands, and streaming reads / writes / copies of 1 GiB
+    if bf16:
+        seed = (torch.randn(32768, device="cuda")).to(torch.bfloat16)
+        sink = torch.zeros(4, device="cuda")
+        fl = C.cephalo_probe_mfma(seed, 1024, 2000, sink)
+        t_m = timed(lambda: C.cephalo_probe_mfma(seed, 1024, 2000, sink), 10)      # about 50 ms of back-to-back launches: a sustained rate
+        nb = 1 << 30
+        a_ = torch.empty(nb // 4, device="cuda"); b_ = torch.empty(nb // 4, device="cuda")
+        a_.fill_(1.0); b_.fill_(2.0)
+        t_r = timed(lambda: C.cephalo_probe_stream(0, None, a_, nb, sink), 20)
+        t_w = timed(lambda: C.cephalo_probe_stream(1, b_, None, nb, sink), 20)
+        t_c = timed(lambda: C.cephalo_probe_stream(2, b_, a_, nb, sink), 20)
+        mp = {"mfma_16x16x32_bf16_registers_only_TFLOP/s": round(fl / t_m / 1e12, 1), "read_GB/s": round(nb / t_r / 1e9, 1),
+              "write_GB/s": round(nb / t_w / 1e9, 1), "copy_GB/s": round(2 * nb / t_c / 1e9, 1)}
+        extras["measured_on_this_device"] = mp
+        if roofline.get("achieved"):
+            roofline["frac_of_measured_mfma_stream"] = round(roofline["achieved"] / mp["mfma_16x16x32_bf16_registers_only_TFLOP/s"], 4)
+        del a_, b_
     # shard Adam alone: 28 algorithmic bytes per element (+2 for the bf16 copy)
     adam_sec = timed(lambda: C.cephalo_shard_adam(p32, G, mom, var, plow, P, off, ln, lr, 0.9, 0.999, 1e-8, 0.0, 9), 10)
     adam_bytes = ln * (28 + (2 if bf16 else 0))
     extras["shard_adam"] = {"elements": ln, "us": round(adam_sec * 1e6, 1), "GB/s": round(adam_bytes / adam_sec / 1e9, 1),
-                            "frac_of_hbm_peak": round(adam_bytes / adam_sec / 1e9 / PEAK_HBM_GBS, 4)}
+                            "frac_of_hbm_peak": round(adam_bytes / adam_sec / 1e9 / PEAK_HBM_GBS, 4),
+                            "traffic_bytes_per_element": traffic_from_profiles("shard_adam_bytes_per_element")}
+    if "measured_on_this_device" in extras:
+        extras["shard_adam"]["frac_of_measured_copy"] = round(adam_bytes / adam_sec / 1e9 / extras["measured_on_this_device"]["copy_GB/s"], 4)
 
     # bf16 GEMMs that fell off the matrix-core kernel onto the general one (0 for every workload here)
     extras["gemm_calls_on_general_kernel"] = C.cephalo_gemm_general_count()
@@ -327,8 +449,8 @@ def main():
                                                                "untied" if cfg.kind == "llama" else "tied", V)) if stack else "1 layer"
     out = {
         "metric": "tokens/s per fwd+bwd+shard-Adam step on 1 MI355X",
-        "value": round(tokens_per_s, 1), "unit": "tokens/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
-        "ms_per_step": round(ms_per_step, 4), "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "value": round(tokens_per_s, 1) if args.steps else None, "unit": "tokens/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+        "ms_per_step": round(ms_per_step, 4) if args.steps else None, "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
         "dtype": "bf16" if bf16 else "f32", "data": "synthetic",
         "config": {"workload": "%s: %s H=%d A=%d F=%d S=%d %s, batch share %d = %d micro-batches x %d, shard [%d, %d) of P=%d"
                                % (cfg.name, what, cfg.hidden, cfg.heads, cfg.mlp, cfg.seq, "causal" if cfg.causal else "non-causal",
@@ -336,6 +458,41 @@ def main():
         "roofline": roofline, "cpu_baseline": cpu, "extras": extras,
     }
     print(json.dumps(out))
+
+
+def traffic_probe(C, torch, cfg):
+    """Launches, three times each, the kernels whose HBM traffic the benchmark quotes: the input-gradient GEMM of the
+    workload's three projections with N = H outputs (through the transposed weight, on the tile the two-stream step runs
+    them on), a 1 GiB device copy (the calibration of the counters: 2^30 bytes read, 2^30 written) and the shard Adam
+    on a 64 Mi-element slice with the bf16 copy.  Meant to run under
+        rocprofv3 --pmc FETCH_SIZE --output-format csv -d <dir> -o t -- python3 bench.py --traffic-probe
+        rocprofv3 --pmc WRITE_SIZE --output-format csv -d <dir> -o t -- python3 bench.py --traffic-probe
+    (one counter per run); the per-dispatch values are in <dir>/t_counter_collection.csv, in KiB."""
+    T, H, F = cfg.tokens_per_micro, cfg.hidden, cfg.mlp
+    bt = torch.bfloat16
+    C.cephalo_gemm_side_by_side(2)
+
+    def dgrad(n_out, k_in, f32):      # dX[T, k_in] = dY[T, n_out] W through W^T [k_in, n_out]
+        dY = torch.randn(T, n_out, device="cuda").to(bt)
+        WT = (torch.randn(k_in, n_out, device="cuda") * 0.02).to(bt)
+        dX = torch.empty(T, k_in, device="cuda", dtype=torch.float32 if f32 else bt)
+        for _ in range(3):
+            C.cephalo_op_gemm(C.BF16, dY, n_out, 1, WT, n_out, 1, T, k_in, n_out, C.EPI_NONE_F32 if f32 else C.EPI_NONE, C=dX)
+        torch.cuda.synchronize()
+    dgrad(3 * H, H, True)     # qkv
+    dgrad(H, H, False)        # out-proj
+    dgrad(F, H, True)         # fc1
+    a = torch.empty(1 << 28, device="cuda"); b = torch.empty(1 << 28, device="cuda")
+    a.fill_(1.0)
+    for _ in range(3):
+        b.copy_(a)
+    n = 1 << 26
+    p = torch.zeros(n, device="cuda"); g = torch.ones(n, device="cuda") * 1e-2; m = torch.zeros(n, device="cuda"); v = torch.zeros(n, device="cuda")
+    lp = torch.empty(n, device="cuda", dtype=bt)
+    for i in range(3):
+        C.cephalo_shard_adam(p, g, m, v, lp, n, 0, n, 1e-3, 0.9, 0.999, 1e-8, 0.0, i + 1)
+    torch.cuda.synchronize()
+    print("traffic probe done", flush=True)
 
 
 def cpu_baseline(cfg, params, flat32_h, m_h, v_h, off, ln, lr, acts, tokens):

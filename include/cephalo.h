@@ -254,6 +254,35 @@ int cephalo_op_linear_wgrad(int32_t dtype, const void* dY, const void* X, int32_
 int cephalo_op_linear_wgrad_static(int32_t dtype, const void* dY, const void* X, int32_t T, int32_t N, int32_t K,
                                    float* G, float scale, int32_t accumulate, void* stream);
 
+/* The bandwidth-bound pieces of the layer and of the stack's head, one call each (one wavefront per row; fp32
+ * statistics).  dtype selects the activation type (fp32, or bf16 for u / gamma / beta / dx_lowp / dlogits); the
+ * residual stream x, the incoming gradient du, the result dx and every parameter gradient are fp32 in both modes.
+ *
+ * norm_fwd: u[r] = gamma * (x[r] - mean_r) * rstd_r + beta over the H columns of each of `rows` rows, biased variance,
+ *   eps inside the square root; mean, rstd: fp32 [rows], saved for the backward.  rms != 0: root-mean-square norm,
+ *   u = gamma * x / sqrt(mean(x^2) + eps); beta is not read and may be NULL.  H a multiple of 8, at most 8192 (4096 in
+ *   fp32 mode).
+ * norm_bwd: dx = resid + rstd * (g - mean_h(g) - xhat * mean_h(g * xhat)),  g = du * gamma  (resid may be NULL: none;
+ *   rms: the mean_h(g) term is absent); dx_lowp, if not NULL, receives dx in the activation type as well;
+ *   dgamma[h] = sum_r du * xhat, dbeta[h] = sum_r du (rms: dbeta untouched, may be NULL), summed in a fixed order.
+ *   workspace: device, cephalo_op_norm_bwd_workspace(rows, H) bytes.
+ * colsum: g[n] = (accumulate ? g[n] : 0) + scale * sum_r X[r][n], X [rows, N] in dtype (a bias gradient), fixed order.
+ * cross_entropy: for each row of fp32 logits [rows, ld] (V valid columns, ld >= V a multiple of 8):
+ *   loss_rows[r] = logsumexp(row) - row[target],  dlogits[r] = coef * (softmax(row) - onehot(target)) in dtype, columns
+ *   V..ld-1 zero; targets int32 [rows], clamped to [0, V).
+ * Errors as elsewhere: nothing is launched when an argument is refused. */
+int cephalo_op_norm_fwd(int32_t dtype, int32_t rms, const float* x, const void* gamma, const void* beta, void* u,
+                        float* mean, float* rstd, int32_t rows, int32_t H, float eps, void* stream);
+size_t cephalo_op_norm_bwd_workspace(int32_t rows, int32_t H);
+int cephalo_op_norm_bwd(int32_t dtype, int32_t rms, const float* du, const float* x, const float* mean, const float* rstd,
+                        const void* gamma, const float* resid, float* dx, void* dx_lowp, float* dgamma, float* dbeta,
+                        int32_t rows, int32_t H, void* workspace, size_t workspace_bytes, void* stream);
+size_t cephalo_op_colsum_workspace(int32_t rows, int32_t N);
+int cephalo_op_colsum(int32_t dtype, const void* X, int32_t rows, int32_t N, float* g, float scale, int32_t accumulate,
+                      void* workspace, size_t workspace_bytes, void* stream);
+int cephalo_op_cross_entropy(int32_t dtype, const float* logits, int32_t ld, const int32_t* targets, void* dlogits,
+                             float* loss_rows, int32_t rows, int32_t V, float coef, void* stream);
+
 /* Attention of one micro-batch on the packed projection qkv [m*S, 3H] (column blocks Q | K | V).
  * Forward writes O [m*S, H] (dtype) and lse [m, A, S] fp32, the log-sum-exp of each query row's
  * scaled, masked scores.  Backward writes dqkv [m*S, 3H]; dvec [m, A, S] fp32 is scratch. */
@@ -359,6 +388,19 @@ int cephalo_stack_step_interleaved(const cephalo_stack_desc* desc, const void* f
                                    const int32_t* ids, const int32_t* targets, int32_t batch_share, int32_t micro_batch,
                                    float* flat_grad, float grad_scale, float* loss,
                                    void* workspace, size_t workspace_bytes, void* stream, void* side_stream);
+
+/* ---------------------------------------------------------------------------------------
+ * Measurement probes (bench.py --peaks): what this device sustains, to be quoted beside the published peaks.
+ *
+ * probe_mfma: `blocks` blocks of eight wavefronts, each issuing iters x 32 products v_mfma_f32_16x16x32_bf16 on operands
+ *   held in registers (the GEMM kernel's wavefront tile without any LDS or memory traffic).  seed_bf16: device, 64 KiB of
+ *   bf16 values the operands are taken from (the sustained rate depends on the data: fill it with random values);
+ *   sink: device, one float; flops_out (host, may be NULL) receives the flops of the launch.
+ * probe_stream: mode 0 reads `bytes` of src, 1 writes `bytes` of dst, 2 copies src to dst, with streaming 16-byte
+ *   accesses (bytes a multiple of 16; both buffers device memory, 16-byte aligned).
+ * Both only enqueue on `stream`; the caller times them. */
+int cephalo_probe_mfma(const void* seed_bf16, int32_t blocks, int32_t iters, float* sink, double* flops_out, void* stream);
+int cephalo_probe_stream(int32_t mode, void* dst, const void* src, int64_t bytes, float* sink, void* stream);
 
 /* ---------------------------------------------------------------------------------------
  * Planning on the host (no device involved): how the global batch and the training state are divided over the

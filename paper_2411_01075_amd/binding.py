@@ -45,7 +45,7 @@ class StackDesc(ctypes.Structure):
 
 
 def stack_desc_from_config(cfg, checkpoint=False, offload=False, interleave=False):
-    return StackDesc(desc_from_config(cfg), int(cfg.layers), int(cfg.vocab), int(bool(checkpoint)), int(bool(offload)),
+    return StackDesc(desc_from_config(cfg), int(cfg.layers), int(cfg.vocab), int(bool(checkpoint)), int(offload),
                      int(bool(interleave)))
 
 
@@ -95,6 +95,14 @@ SIGNATURES = {
     "cephalo_op_linear_wgrad_workspace": (_sz, [_i32, _i32, _i32, _i32]),
     "cephalo_op_linear_wgrad": (ctypes.c_int, [_i32, _vp, _vp, _i32, _i32, _i32, _vp, _f32, _i32, _vp, _sz, _vp]),
     "cephalo_op_linear_wgrad_static": (ctypes.c_int, [_i32, _vp, _vp, _i32, _i32, _i32, _vp, _f32, _i32, _vp]),
+    "cephalo_op_norm_fwd": (ctypes.c_int, [_i32, _i32, _vp, _vp, _vp, _vp, _vp, _vp, _i32, _i32, _f32, _vp]),
+    "cephalo_op_norm_bwd_workspace": (_sz, [_i32, _i32]),
+    "cephalo_op_norm_bwd": (ctypes.c_int, [_i32, _i32, _vp, _vp, _vp, _vp, _vp, _vp, _vp, _vp, _vp, _vp, _i32, _i32, _vp, _sz, _vp]),
+    "cephalo_op_colsum_workspace": (_sz, [_i32, _i32]),
+    "cephalo_op_colsum": (ctypes.c_int, [_i32, _vp, _i32, _i32, _vp, _f32, _i32, _vp, _sz, _vp]),
+    "cephalo_op_cross_entropy": (ctypes.c_int, [_i32, _vp, _i32, _vp, _vp, _vp, _i32, _i32, _f32, _vp]),
+    "cephalo_probe_mfma": (ctypes.c_int, [_vp, _i32, _i32, _vp, ctypes.POINTER(ctypes.c_double), _vp]),
+    "cephalo_probe_stream": (ctypes.c_int, [_i32, _vp, _vp, _i64, _vp, _vp]),
     "cephalo_plan_compute": (ctypes.c_int, [_i32, ctypes.POINTER(GpuPerf), _i32, ctypes.POINTER(ClusterModel),
                                             ctypes.POINTER(_i32), ctypes.POINTER(_i32), ctypes.POINTER(ctypes.c_double)]),
     "cephalo_plan_state": (ctypes.c_int, [_i32, ctypes.POINTER(GpuPerf), ctypes.POINTER(_i32), ctypes.POINTER(ClusterModel),
@@ -242,6 +250,46 @@ def cephalo_op_gemm(dtype, A, a_rs, a_cs, B, b_rs, b_cs, M, N, K, epilogue, C=No
                     G=None, scale=1.0, accumulate=0, stream=None):
     _check(lib().cephalo_op_gemm(dtype, _ptr(A), a_rs, a_cs, _ptr(B), b_rs, b_cs, M, N, K, epilogue,
                                  _ptr(C), _ptr(bias), _ptr(R), _ptr(Z), _ptr(G), scale, int(accumulate), _stream(stream)))
+
+
+def _nbytes(t):
+    return 0 if t is None else t.numel() * t.element_size()
+
+
+def cephalo_op_norm_fwd(dtype, rms, x, gamma, beta, u, mean, rstd, rows, H, eps, stream=None):
+    _check(lib().cephalo_op_norm_fwd(dtype, int(rms), _ptr(x), _ptr(gamma), _ptr(beta), _ptr(u), _ptr(mean), _ptr(rstd), rows, H, eps, _stream(stream)))
+
+
+def cephalo_op_norm_bwd_workspace(rows, H):
+    return int(lib().cephalo_op_norm_bwd_workspace(rows, H))
+
+
+def cephalo_op_norm_bwd(dtype, rms, du, x, mean, rstd, gamma, resid, dx, dx_lowp, dgamma, dbeta, rows, H, workspace, stream=None):
+    _check(lib().cephalo_op_norm_bwd(dtype, int(rms), _ptr(du), _ptr(x), _ptr(mean), _ptr(rstd), _ptr(gamma), _ptr(resid), _ptr(dx),
+                                     _ptr(dx_lowp), _ptr(dgamma), _ptr(dbeta), rows, H, _ptr(workspace), _nbytes(workspace), _stream(stream)))
+
+
+def cephalo_op_colsum_workspace(rows, N):
+    return int(lib().cephalo_op_colsum_workspace(rows, N))
+
+
+def cephalo_op_colsum(dtype, X, rows, N, g, scale, accumulate, workspace, stream=None):
+    _check(lib().cephalo_op_colsum(dtype, _ptr(X), rows, N, _ptr(g), scale, int(accumulate), _ptr(workspace), _nbytes(workspace), _stream(stream)))
+
+
+def cephalo_op_cross_entropy(dtype, logits, ld, targets, dlogits, loss_rows, rows, V, coef, stream=None):
+    _check(lib().cephalo_op_cross_entropy(dtype, _ptr(logits), ld, _ptr(targets), _ptr(dlogits), _ptr(loss_rows), rows, V, coef, _stream(stream)))
+
+
+def cephalo_probe_mfma(seed, blocks, iters, sink, stream=None):
+    """Returns the flops of the launch."""
+    fl = ctypes.c_double(0.0)
+    _check(lib().cephalo_probe_mfma(_ptr(seed), blocks, iters, _ptr(sink), ctypes.byref(fl), _stream(stream)))
+    return fl.value
+
+
+def cephalo_probe_stream(mode, dst, src, nbytes, sink, stream=None):
+    _check(lib().cephalo_probe_stream(mode, _ptr(dst), _ptr(src), nbytes, _ptr(sink), _stream(stream)))
 
 
 def cephalo_op_linear_wgrad_static(dtype, dY, X, T, N, K, G, scale, accumulate, stream=None):

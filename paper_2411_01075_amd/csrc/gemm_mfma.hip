@@ -576,6 +576,7 @@ int launch_gemm_mfma(const GemmArgs<bf16>& a, hipStream_t s) {
   if (ak && bk) {          // forward: Y = X W^T
     switch (a.epi) {
       case EPI_NONE: return launch_tiles<true, true, EPI_NONE>(a, s);
+      case EPI_NONE_HEAD: return launch_tiles<true, true, EPI_NONE_HEAD>(a, s);
       case EPI_ROPE: if (a.rot_cols % 8 == 0 && a.rot_d % 8 == 0 && aligned16(a.rot)) return launch_tiles<true, true, EPI_ROPE>(a, s); break;
       case EPI_BIAS: return launch_tiles<true, true, EPI_BIAS>(a, s);
       case EPI_BIAS_RESID: return launch_tiles<true, true, EPI_BIAS_RESID>(a, s);

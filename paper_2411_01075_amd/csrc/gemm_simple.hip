@@ -69,7 +69,7 @@ __global__ void __launch_bounds__(kThreads) gemm_simple_kernel(GemmArgs<T> a) {
       float v = acc[i][j];
       auto put = [&](float r) { if (a.Cf) a.Cf[o] = r; else a.C[o] = (T)r; };   // fp32 output if Cf is set
       switch (a.epi) {
-        case EPI_NONE: put(v); break;
+        case EPI_NONE: case EPI_NONE_HEAD: put(v); break;
         case EPI_BIAS: put(v + (float)a.bias[n]); break;
         case EPI_BIAS_RESID: put(v + (a.bias ? (float)a.bias[n] : 0.f) + (a.Rf ? a.Rf[o] : (float)a.R[o])); break;
         case EPI_BIAS_GELU: {

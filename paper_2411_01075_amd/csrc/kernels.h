@@ -109,6 +109,8 @@ enum Epilogue {
                        //   row's position m % rot_S and of its place in the head: (e, o) -> (e cos - o sin, e sin + o cos)
   EPI_BIAS_GELU_DERIV = 9,  // z = acc + bias[n];  C = gelu(z);  Z = gelu'(z)   (the derivative is saved in place of the pre-activation:
                             //   Phi(z) and exp(-z^2/2) are at hand in the forward, and the backward becomes EPI_MUL)
+  EPI_NONE_HEAD = 11,       // as EPI_NONE; the vocabulary projections of a stack's head use it, so that they are kernels of their own
+                            //   in a profile and do not mix into the figures of the layers' projections
   EPI_MUL = 10,             // C = acc * Z[m,n]
   EPI_DSWIGLU = 8,     // gated SiLU backward, acc = dh[m,n], n < N = F; Z and C are [M, 2N] = [gate | up] (pitch ldc >= 2N):
                        //   C[m,n] = acc * Z[m,N+n] * silu'(Z[m,n]);  C[m,N+n] = acc * silu(Z[m,n])

@@ -262,10 +262,13 @@ int check_stack(const cephalo_stack_desc* d) {
   TRY(check_desc(&d->layer));
   if (d->layers <= 0 || d->vocab <= 0) return fail(CEPHALO_EINVAL, "stack desc: layers %d and vocab %d must be positive", d->layers, d->vocab);
   if (d->checkpoint != 0 && d->checkpoint != 1) return fail(CEPHALO_EINVAL, "stack desc: checkpoint must be 0 or 1");
-  if (d->offload != 0 && d->offload != 1) return fail(CEPHALO_EINVAL, "stack desc: offload must be 0 or 1");
+  if (d->offload < 0 || d->offload > 2) return fail(CEPHALO_EINVAL, "stack desc: offload must be 0, 1 or 2");
   if (d->offload && !d->checkpoint) return fail(CEPHALO_EINVAL, "stack desc: offload needs checkpoint = 1 (only boundary activations are offloaded)");
   if (d->interleave != 0 && d->interleave != 1) return fail(CEPHALO_EINVAL, "stack desc: interleave must be 0 or 1");
   if (d->interleave && d->offload) return fail(CEPHALO_EUNSUPPORTED, "stack desc: interleave and offload do not go together");
+  if (d->offload == 2 && d->layer.dtype == CEPHALO_F32)
+    return fail(CEPHALO_EUNSUPPORTED, "stack desc: offload = 2 needs the bf16 mode (in fp32 mode the weight gradients read the whole share's fp32 "
+                "gradient of the residual stream, which therefore stays on the device)");
   return CEPHALO_OK;
 }
 
@@ -291,7 +294,9 @@ StackLayout stack_layout(const cephalo_stack_desc& d, int b, int m) {
   L.save_each = align_up(save_layout(ld, b).total);
   L.saves = take((size_t)(d.checkpoint ? 1 : d.layers) * L.save_each);   // checkpointing: one layer's internals at a time
   L.scratch = take(scratch_layout(ld, m, b, d.interleave ? 2 : 1).total);
-  L.dxa = take(n * H * 4); L.dxb = take(n * H * 4);     // gradient of the residual stream, ping-pong between layers
+  // gradient of the residual stream, ping-pong between layers; offload = 2: the first buffer only takes the last result
+  // (the gradient with respect to the embedding output), everything before passes through four micro-batch slots
+  L.dxa = take(n * H * 4); L.dxb = take(d.offload == 2 ? 4 * Tm * H * 4 : n * H * 4);
   L.dxal = es == 4 ? L.dxa : take(n * H * es); L.dxbl = es == 4 ? L.dxb : take(n * H * es);   // and its copy in the activation type
   L.uf = take(n * H * es); L.meanf = take(n * 4); L.rstdf = take(n * 4);
   L.duf = take((d.interleave ? 2 : 1) * Tm * H * 4);
@@ -419,6 +424,19 @@ int run_stack(const cephalo_stack_desc& d, const void* Pv, const int* ids, const
   }
   TRY(X.open());
   struct Closer { Boundary& x; bool done = false; ~Closer() { if (!done) (void)x.close(); } } closer{X};   // events are released on every path
+  // offload = 2: the gradient of the residual stream takes the same road (the supplementary figure's GC^g / CG^g): the
+  // gradient with respect to boundary k of micro-batch j goes to the host as soon as layer k's backward has produced it
+  // and comes back, one micro-batch ahead, when layer k-1's backward of that micro-batch needs it.  Two boundaries are
+  // alive at a time, so the host keeps two [b*S][H] images (boundary k in image k mod 2) after the activations.
+  Boundary Gx;
+  Gx.offload = d.offload == 2;
+  Gx.n = n; Gx.Tm = Tm; Gx.H = H; Gx.c = s; Gx.xin = copy_in; Gx.xout = copy_out;
+  if (Gx.offload) {
+    Gx.base = host_area + (size_t)(NL + 1) * n * H;
+    for (int i = 0; i < 2; ++i) { Gx.in_slot[i] = at<float>(ws, L.dxb) + i * act; Gx.out_slot[i] = at<float>(ws, L.dxb) + (2 + i) * act; }
+  }
+  TRY(Gx.open());
+  struct GCloser { Boundary& x; bool done = false; ~GCloser() { if (!done) (void)x.close(); } } gcloser{Gx};
 
   // ---- forward
   TRY(prepare_head_weights<T>(P + o_head, at<T>(ws, L.wteT), V, H, L.ldv, s));
@@ -462,18 +480,20 @@ int run_stack(const cephalo_stack_desc& d, const void* Pv, const int* ids, const
     T* dlg = dlogits + t0 * L.ldv;
     {
       GemmArgs<T> a = linear_fwd<T>(uf + t0 * H, P + o_head, Tm, V, H);
-      a.epi = EPI_NONE; a.Cf = logits_j; a.ldc = L.ldv;
+      a.epi = EPI_NONE_HEAD; a.Cf = logits_j; a.ldc = L.ldv;
       TRY(gemm<T>(a, sj));
     }
     cross_entropy_kernel<T><<<Tm, kThreads, 0, sj>>>(logits_j, dlg, targets + t0, at<float>(ws, L.loss) + t0, V, L.ldv, coef);
     CEPHALO_CHECK_LAUNCH("cross_entropy");
     {
       GemmArgs<T> a = head_dgrad_args<T>(dlg, P + o_head, at<T>(ws, L.wteT), Tm, V, H, L.ldv);   // duf = dlogits W_head
-      a.epi = EPI_NONE; a.Cf = duf_j;
+      a.epi = EPI_NONE_HEAD; a.Cf = duf_j;
       TRY(gemm<T>(a, sj));
     }
-    TRY(launch_ln_bwd<T>(duf_j, xL, meanf + t0, rstdf + t0, P + o_lnf, (const float*)nullptr, dx_cur + t0 * H,
+    float* dxo = Gx.offload ? Gx.out(NL % 2, j) : dx_cur + t0 * H;
+    TRY(launch_ln_bwd<T>(duf_j, xL, meanf + t0, rstdf + t0, P + o_lnf, (const float*)nullptr, dxo,
                          lowp_out<T>(dxl_cur + t0 * H), lnf_g + (size_t)j * nb * H, lnf_b + (size_t)j * nb * H, Tm, H, sj, rms));
+    Gx.out_done(NL % 2, j);
     X.in_done();
   }
   J.join();
@@ -497,24 +517,36 @@ int run_stack(const cephalo_stack_desc& d, const void* Pv, const int* ids, const
     // last layer's are still there from the forward); the recomputed output, the same values again, is dropped.
     const bool recompute = d.checkpoint && li != NL - 1;
     X.prefetch(li, 0, l);
+    Gx.prefetch((li + 1) % 2, 0, l);
     for (int j = 0; j < l; ++j) {
       const float* xi = X.in(li, j, l);
       X.prefetch(li, j + 1, l);
       if (recompute) TRY(layer_fwd_t<T>(ld, Pl, xi, at<float>(ws, L.xdump) + (size_t)(j % nst) * act, m, saved_at<T>(save, SL, ld, j * m), st[j % nst]));
-      TRY(layer_bwd_data_t<T>(ld, Pl, xi, dx_cur + j * act, lowp_of<T>(dx_cur, dxl_cur) + j * act, dx_nxt + j * act,
+      // the fp32 gradient arriving at this layer's output and the one leaving at its input: resident buffers, or (offload = 2)
+      // a slot just fetched from the host and a slot about to leave for it; layer 0's result stays on the device for the embeddings
+      const float* dyj = Gx.offload ? Gx.in((li + 1) % 2, j, l) : dx_cur + j * act;
+      Gx.prefetch((li + 1) % 2, j + 1, l);
+      float* dxj = !Gx.offload ? dx_nxt + j * act : (li == 0 ? at<float>(ws, L.dxa) + j * act : Gx.out(li % 2, j));
+      if (Gx.offload && !rms)      // the bias gradient of the second feed-forward projection sums this gradient's columns: now, while it is here
+        TRY(launch_colsum<float>(dyj, work_at<T>(scratch, WL, ld, 0, 0, m).col_part, work_at<T>(scratch, WL, ld, 0, 0, m).col_part_bytes,
+                                 G + o_layers + li * PL + param_offsets(ld).b_fc2, 1.0f, j > 0, Tm, H, st[j % nst]));
+      TRY(layer_bwd_data_t<T>(ld, Pl, xi, dyj, dxl_cur + j * act, dxj,
                               dxl_nxt + j * act, m, saved_at<T>(save, SL, ld, j * m), work_at<T>(scratch, WL, ld, j * m, j, m, j % nst), st[j % nst]));
+      Gx.in_done();
+      if (Gx.offload && li > 0) Gx.out_done(li % 2, j);
       X.in_done();
     }
     J.join();
     hint.now(1);
     J.fork();        // the parameter pass: weight-gradient GEMMs on the main stream, the bandwidth-bound reductions beside them
-    TRY(layer_bwd_params_t<T>(ld, dx_cur, lowp_of<T>(dx_cur, dxl_cur), n, l * nb, saved_at<T>(save, SL, ld, 0),
-                              work_at<T>(scratch, WL, ld, 0, 0, m), G + o_layers + li * PL, 1.0f, 0, s, st[1]));
+    TRY(layer_bwd_params_t<T>(ld, Gx.offload ? (const float*)nullptr : dx_cur, Gx.offload ? dxl_cur : lowp_of<T>(dx_cur, dxl_cur), n, l * nb,
+                              saved_at<T>(save, SL, ld, 0), work_at<T>(scratch, WL, ld, 0, 0, m), G + o_layers + li * PL, 1.0f, 0, s, st[1]));
     J.join();
     { float* t = dx_cur; dx_cur = dx_nxt; dx_nxt = t; }
     { T* t = dxl_cur; dxl_cur = dxl_nxt; dxl_nxt = t; }
   }
   // ---- embeddings
+  if (Gx.offload) dx_cur = at<float>(ws, L.dxa);      // layer 0 left its result there
   if (SO.positions) {
     wpe_bwd_kernel<<<(int)(((int64_t)S * H / 4 + kThreads - 1) / kThreads), kThreads, 0, s>>>(dx_cur, G + o_wpe, b, S, H);
     CEPHALO_CHECK_LAUNCH("wpe_bwd");
@@ -529,9 +561,10 @@ int run_stack(const cephalo_stack_desc& d, const void* Pv, const int* ids, const
   embed_bwd_kernel<<<(n + 3) / 4, kThreads, 0, s>>>(keys, dx_cur, G + o_wte, n, H);
   CEPHALO_CHECK_LAUNCH("embed_bwd");
   closer.done = true;
+  gcloser.done = true;
   jcloser.done = true;
-  const int rc_join = J.close(), rc_copy = X.close();      // errors of the final join and of the event releases are the call's result
-  return rc_join != CEPHALO_OK ? rc_join : rc_copy;
+  const int rc_join = J.close(), rc_grad = Gx.close(), rc_copy = X.close();      // errors of the final join and of the event releases are the call's result
+  return rc_join != CEPHALO_OK ? rc_join : (rc_grad != CEPHALO_OK ? rc_grad : rc_copy);
 }
 
 }  // namespace
@@ -563,6 +596,20 @@ extern "C" int cephalo_stack_workspace_bytes(const cephalo_stack_desc* d, int32_
   return CEPHALO_OK;
 }
 
+extern "C" int cephalo_op_cross_entropy(int32_t dtype, const float* logits, int32_t ld, const int32_t* targets, void* dlogits,
+                                        float* loss_rows, int32_t rows, int32_t V, float coef, void* stream) {
+  if (dtype != CEPHALO_F32 && dtype != CEPHALO_BF16) return fail(CEPHALO_EINVAL, "cross_entropy: unknown dtype %d", dtype);
+  if (rows <= 0 || V <= 0 || ld < V) return fail(CEPHALO_EINVAL, "cross_entropy: %d rows, %d classes, pitch %d", rows, V, ld);
+  if (ld % 8 != 0) return fail(CEPHALO_EUNSUPPORTED, "cross_entropy: the pitch %d must be a multiple of 8", ld);
+  if (!logits || !targets || !dlogits || !loss_rows) return fail(CEPHALO_EINVAL, "cross_entropy: null buffer");
+  if (!aligned16(logits) || !aligned16(dlogits)) return fail(CEPHALO_EINVAL, "cross_entropy: buffers must be 16-byte aligned");
+  hipStream_t s = static_cast<hipStream_t>(stream);
+  if (dtype == CEPHALO_F32) cross_entropy_kernel<float><<<rows, kThreads, 0, s>>>(logits, static_cast<float*>(dlogits), targets, loss_rows, V, ld, coef);
+  else cross_entropy_kernel<bf16><<<rows, kThreads, 0, s>>>(logits, static_cast<bf16*>(dlogits), targets, loss_rows, V, ld, coef);
+  CEPHALO_CHECK_LAUNCH("cross_entropy");
+  return CEPHALO_OK;
+}
+
 extern "C" int cephalo_stack_workspace_regions(const cephalo_stack_desc* d, int32_t batch_share, int32_t micro_batch, size_t* offsets) {
   TRY(check_stack(d));
   if (micro_batch <= 0 || batch_share <= 0 || batch_share % micro_batch != 0)
@@ -573,8 +620,8 @@ extern "C" int cephalo_stack_workspace_regions(const cephalo_stack_desc* d, int3
   // the residual-stream gradient alternates between two buffers, one swap per layer, starting in the first
   const bool even = d->layers % 2 == 0;
   offsets[0] = L.xs;
-  offsets[1] = even ? L.dxa : L.dxb;
-  offsets[2] = even ? L.dxb : L.dxa;
+  offsets[1] = d->offload == 2 ? L.dxa : (even ? L.dxa : L.dxb);
+  offsets[2] = even ? L.dxb : L.dxa;      // (offload = 2: not resident; the host area's gradient image 1 holds it)
   return CEPHALO_OK;
 }
 
@@ -620,7 +667,8 @@ extern "C" int cephalo_stack_host_bytes(const cephalo_stack_desc* d, int32_t bat
     return fail(CEPHALO_EINVAL, "stack_host_bytes: batch share b = %d is not a positive multiple of micro-batch size m = %d",
                 batch_share, micro_batch);
   if (!bytes) return fail(CEPHALO_EINVAL, "stack_host_bytes: null output");
-  *bytes = d->offload ? (size_t)(d->layers + 1) * batch_share * d->layer.seq * d->layer.hidden * sizeof(float) : 0;
+  // the layer-boundary activations; offload = 2: and two images of the residual stream's gradient behind them
+  *bytes = d->offload ? (size_t)(d->layers + 1 + (d->offload == 2 ? 2 : 0)) * batch_share * d->layer.seq * d->layer.hidden * sizeof(float) : 0;
   return CEPHALO_OK;
 }
 
