@@ -261,13 +261,16 @@ def main():
             # fn(i, stream): launch number i of a pair (its own output buffers) on that stream.
             # Every leg is timed alone on one stream; a per-micro-batch leg of a two-stream step is also timed the way
             # that step launches it, in pairs, one kernel per stream, on the tile chosen for half the device.
+            # (--legs-only: the same number of launches for every shape, so that a profile's per-kernel average weighs the
+            #  shapes that share a kernel as the step does, equally)
+            reps = (lambda first: 40) if args.legs_only else (lambda first: max(3, min(400, int(0.03 / max(first, 1e-6)))))
             one = lambda: fn(0, None)
             first = timed(one, 2)
-            dur1 = timed(one, max(3, min(400, int(0.03 / max(first, 1e-6)))))
+            dur1 = timed(one, reps(first))
             if pairs and not alone:
                 C.cephalo_gemm_side_by_side(2)
                 first = timed_pairs(fn, 2)
-                dur = timed_pairs(fn, max(3, min(400, int(0.03 / max(first, 1e-6)))))      # a kernel's duration = the pair's
+                dur = timed_pairs(fn, reps(first))      # a kernel's duration = the pair's
                 sec = dur / 2                                                                  # device time per launch
                 C.cephalo_gemm_side_by_side(1)
             else:

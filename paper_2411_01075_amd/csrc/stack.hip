@@ -167,32 +167,81 @@ int launch_sort_tokens(const int* ids, u64* keys, int n, int V, hipStream_t s) {
   return CEPHALO_OK;
 }
 
-// Token-embedding gradient: tokens sorted by (id, token index); the wavefront at the head of each run of equal ids
-// sums the run's rows of dx0 in that order and adds the sum to the id's row of the gradient (which already holds
-// the LM-head part).  One writer per row, fixed order: reproducible.
+// Token-embedding gradient.  The tokens are sorted by (id, token index), so the rows of dx0 that belong to one id form
+// a run of the sorted order.  The sorted order is cut into segments of kEmbedSeg positions with one wavefront each
+// (however often an id occurs, no wavefront walks more than a segment).  Pass 1: a wavefront sums each piece of a run
+// inside its segment in order; a run that lies wholly inside the segment is added to its row of the gradient at once
+// (the row already holds the head's part where the head is tied; nobody else writes that row), the piece that came in
+// from the previous segment and the piece that goes on into the next are parked in part[segment][0 / 1].  Pass 2: the
+// wavefront of the segment in which a cut run starts adds up its parked pieces, segment after segment, and adds the
+// total to the row.  Every sum has a fixed order: reproducible.
+constexpr int kEmbedSeg = 32;
+
+__device__ __forceinline__ unsigned key_id(u64 k) { return (unsigned)(k >> 32); }
+
 __global__ void __launch_bounds__(kThreads)
-embed_bwd_kernel(const u64* __restrict__ sorted, const float* __restrict__ dx0, float* __restrict__ g_wte, int n, int H) {
-  typedef float T;
-  constexpr int VN = Vec<T>::N;
-  const int i = blockIdx.x * 4 + (threadIdx.x >> 6), lane = threadIdx.x & 63;
-  if (i >= n) return;
-  const unsigned key = (unsigned)(sorted[i] >> 32);
-  if (i > 0 && (unsigned)(sorted[i - 1] >> 32) == key) return;
+embed_bwd_segments_kernel(const u64* __restrict__ sorted, const float* __restrict__ dx0, float* __restrict__ g_wte,
+                          float* __restrict__ part, int n, int H) {
+  constexpr int VN = 4;
+  const int seg = blockIdx.x * 4 + (threadIdx.x >> 6), lane = threadIdx.x & 63;
+  const int p0 = seg * kEmbedSeg;
+  if (p0 >= n) return;
+  const int p1 = min(n, p0 + kEmbedSeg);
+  int i = p0;
+  while (i < p1) {
+    const unsigned id = key_id(sorted[i]);
+    int e = i + 1;
+    while (e < p1 && key_id(sorted[e]) == id) ++e;
+    const bool from_before = i == p0 && p0 > 0 && key_id(sorted[p0 - 1]) == id;
+    const bool goes_on = e == p1 && p1 < n && key_id(sorted[p1]) == id;
+    float* dst = from_before ? part + ((size_t)seg * 2 + 0) * H : (goes_on ? part + ((size_t)seg * 2 + 1) * H : g_wte + (size_t)id * H);
+    const bool add = !from_before && !goes_on;      // a whole run: onto the row; a piece: stored
+    for (int v = lane; v < H / VN; v += 64) {
+      float acc[VN] = {0.f, 0.f, 0.f, 0.f};
+      for (int j = i; j < e; ++j) {
+        float a[VN];
+        load_vec<float>(dx0 + (int64_t)(unsigned)sorted[j] * H + v * VN, a);
+#pragma unroll
+        for (int c = 0; c < VN; ++c) acc[c] += a[c];
+      }
+#pragma unroll
+      for (int c = 0; c < VN; ++c) dst[v * VN + c] = add ? dst[v * VN + c] + acc[c] : acc[c];
+    }
+    i = e;
+  }
+}
+
+__global__ void __launch_bounds__(kThreads)
+embed_bwd_joins_kernel(const u64* __restrict__ sorted, float* __restrict__ g_wte, const float* __restrict__ part, int n, int H) {
+  constexpr int VN = 4;
+  const int seg = blockIdx.x * 4 + (threadIdx.x >> 6), lane = threadIdx.x & 63;
+  const int p0 = seg * kEmbedSeg;
+  if (p0 >= n) return;
+  const int p1 = min(n, p0 + kEmbedSeg);
+  if (p1 >= n) return;                                       // nothing goes on past the last segment
+  const unsigned id = key_id(sorted[p1 - 1]);
+  if (key_id(sorted[p1]) != id) return;                      // the last run of this segment ends here
+  if (key_id(sorted[p0]) == id && p0 > 0 && key_id(sorted[p0 - 1]) == id) return;   // the run started in an earlier segment: its wavefront joins it
+  // the run starts in this segment: its piece here is part[seg][1] -- unless it fills the segment from its first
+  // position (then pass 1 saw no difference from "came in from before" only if p0 > 0, excluded above), and the
+  // following segments hold part[.][0] while the run lasts
+  int last = seg + 1;                                        // last segment the run reaches
+  while ((int64_t)(last + 1) * kEmbedSeg < n && key_id(sorted[(last + 1) * kEmbedSeg]) == id && key_id(sorted[(last + 1) * kEmbedSeg - 1]) == id) ++last;
   for (int v = lane; v < H / VN; v += 64) {
     float acc[VN];
 #pragma unroll
-    for (int c = 0; c < VN; ++c) acc[c] = 0.f;
-    for (int j = i; j < n && (unsigned)(sorted[j] >> 32) == key; ++j) {
-      float a[VN];
-      load_vec<T>(dx0 + (int64_t)(unsigned)sorted[j] * H + v * VN, a);
+    for (int c = 0; c < VN; ++c) acc[c] = part[((size_t)seg * 2 + 1) * H + v * VN + c];
+    for (int q = seg + 1; q <= last; ++q) {
 #pragma unroll
-      for (int c = 0; c < VN; ++c) acc[c] += a[c];
+      for (int c = 0; c < VN; ++c) acc[c] += part[((size_t)q * 2 + 0) * H + v * VN + c];
     }
-    float* g = g_wte + (int64_t)key * H + v * VN;
+    float* g = g_wte + (size_t)id * H + v * VN;
 #pragma unroll
     for (int c = 0; c < VN; ++c) g[c] += acc[c];
   }
 }
+
+int embed_segments(int n) { return (n + kEmbedSeg - 1) / kEmbedSeg; }
 
 // Position-embedding gradient: g_wpe[s] = sum over the b samples of dx0[n, s], samples in order.
 __global__ void __launch_bounds__(kThreads)
@@ -273,7 +322,7 @@ int check_stack(const cephalo_stack_desc* d) {
 }
 
 struct StackLayout {
-  size_t xs, xdump, saves, save_each, scratch, dxa, dxb, dxal, dxbl, uf, meanf, rstdf, duf, logits, dlogits, wteT, loss, lnf_part, keys, total;
+  size_t xs, xdump, saves, save_each, scratch, dxa, dxb, dxal, dxbl, uf, meanf, rstdf, duf, logits, dlogits, wteT, loss, lnf_part, keys, embed_part, total;
   int ldv;            // padded pitch of the logits
   size_t lnf_rows;
 };
@@ -307,6 +356,7 @@ StackLayout stack_layout(const cephalo_stack_desc& d, int b, int m) {
   L.lnf_rows = (size_t)(b / m) * ln_bwd_blocks((int)Tm);
   L.lnf_part = take(2 * L.lnf_rows * H * 4);
   L.keys = take((size_t)sort_pad((int)n) * sizeof(u64));      // (id, token index) keys of the embedding gradient's sort
+  L.embed_part = take((size_t)embed_segments((int)n) * 2 * H * 4);   // pieces of runs of equal ids that cross a segment boundary
   L.total = p;
   return L;
 }
@@ -558,8 +608,11 @@ int run_stack(const cephalo_stack_desc& d, const void* Pv, const int* ids, const
   }
   u64* keys = at<u64>(ws, L.keys);
   TRY(launch_sort_tokens(ids, keys, n, V, s));
-  embed_bwd_kernel<<<(n + 3) / 4, kThreads, 0, s>>>(keys, dx_cur, G + o_wte, n, H);
-  CEPHALO_CHECK_LAUNCH("embed_bwd");
+  const int nseg = embed_segments(n);
+  embed_bwd_segments_kernel<<<(nseg + 3) / 4, kThreads, 0, s>>>(keys, dx_cur, G + o_wte, at<float>(ws, L.embed_part), n, H);
+  CEPHALO_CHECK_LAUNCH("embed_bwd_segments");
+  embed_bwd_joins_kernel<<<(nseg + 3) / 4, kThreads, 0, s>>>(keys, G + o_wte, at<float>(ws, L.embed_part), n, H);
+  CEPHALO_CHECK_LAUNCH("embed_bwd_joins");
   closer.done = true;
   gcloser.done = true;
   jcloser.done = true;

@@ -121,6 +121,31 @@ def test_stack_step_matches_oracle(case):
     report_over(cfg, compare_with_oracle(cfg, sd, loss, G, ref_loss, ref))
 
 
+@pytest.mark.parametrize("case", ["f32_tiny", "bf16_mini"])
+def test_one_token_id_covers_most_of_the_share(case):
+    """A padding-like id that makes up most of the tokens, runs of it crossing micro-batch and sample boundaries, plus
+    ids that occur once and ids that never occur: the token-embedding gradient sums each id's rows in pieces of at most
+    32 sorted positions and joins the pieces in order, so no wavefront walks a long run alone.  Against the oracle, and
+    twice for bit-reproducibility."""
+    cfg = CASES[case]
+    params = draw_stack_params(cfg, perturbed=True)
+    ids, tgt = draw_token_ids(cfg)
+    rng = np.random.default_rng(3)
+    mask = rng.random(ids.shape) < 0.7
+    ids[mask] = 5
+    ids[0, :40] = 5                              # a run from the very first sorted position
+    ids[-1, -1] = cfg.vocab - 1                  # the largest id, once, at the very end
+    loss, G, sd = run_gpu(cfg, params, ids, tgt, 1.0)
+    ref_loss, ref = oracle_of(cfg, params, ids, tgt, 1.0)
+    over = compare_with_oracle(cfg, sd, loss, G, ref_loss, ref, "dominant id")
+    again = run_gpu(cfg, params, ids, tgt, 1.0)
+    assert again[0] == loss and np.array_equal(again[1], G)
+    V, H = cfg.vocab, cfg.hidden
+    e = rel_errors(G[5 * H: 6 * H], ref["wte"][5])      # the dominant id's own row
+    assert e[0] <= TOL[cfg.dtype][0], e
+    report_over(cfg, over)
+
+
 def test_stack_step_is_reproducible():
     cfg = CASES["bf16_mini"]
     params = draw_stack_params(cfg)
