@@ -38,14 +38,22 @@ __device__ __forceinline__ __amdgpu_buffer_rsrc_t make_rsrc(const void* p, unsig
 
 // ROWS tokens by D values of one operand in LDS, staged by THREADS threads (through registers, or straight from
 // global memory).
+//
+// Two layouts.  D = 64: rows padded to 72 elements (pitch 36 banks: a 16-byte fragment read has 16 lanes on 16
+// consecutive rows, a transposing read has each group of 16 lanes on 4 consecutive rows; both fall on distinct banks).
+// D = 128: rows of exactly 256 bytes (all 64 banks) with the 16-byte chunks of a row permuted,
+//     chunk c of row r lives at chunk  c ^ swz(r),   swz(r) = ((r & 7) << 1) | ((r >> 3) & 1),
+// so that 16 consecutive rows put the same chunk on 16 different places (fragment reads) and 4 consecutive rows put a
+// pair of neighbouring chunks on 4 different pairs (transposing reads).  Without padding a direct-to-LDS load of 16
+// bytes per lane fills 1 KiB = 4 whole rows at once; the permutation is applied by the address each lane fetches.
+// (With padded rows only 4-byte-per-lane loads fit a row, and those run at a quarter of the rate: at 64 KB per key
+// tile the forward pass spent more time staging than multiplying.)
 template <int D, int ROWS = TILE, int THREADS = kThreads> struct Tile {
-  // Padded row (elements).  The row pitch in 4-byte banks, LD/2 mod 64, decides the conflicts of both kinds of read:
-  // a 16-byte fragment read has 16 lanes on 16 consecutive rows, 4 banks each (the pitches 4, 12, 20, 36, ... spread
-  // them over all 64 banks); a transposing read has each group of 16 lanes on 4 consecutive rows, 8 banks each (pitch
-  // 4 makes neighbouring rows overlap; 12 and 36 do not).  D = 64: 72 elements (pitch 36); D = 128: 152 (pitch 12).
-  static constexpr int LD = D == 128 ? D + 24 : D + 8;
+  static constexpr bool DIRECT = D == 128;
+  static constexpr int LD = DIRECT ? D : D + 8;
   static constexpr int ELEMS = ROWS * LD;
   static constexpr int PER_THREAD = ROWS * D / 8 / THREADS;
+  __device__ static constexpr int swz(int r) { return ((r & 7) << 1) | ((r >> 3) & 1); }
 
   // rows [row0, row0+ROWS) of a [*, ld] matrix, columns [0, D); rows >= nrows and columns >= d (the head's own width,
   // a multiple of 8, when it is narrower than the tile) read as zero
@@ -59,55 +67,86 @@ template <int D, int ROWS = TILE, int THREADS = kThreads> struct Tile {
       reg[p] = val;
     }
   }
-  // The same rows straight from global memory into LDS, no registers in between: one load instruction per row (64
-  // lanes x 2*D/64 bytes), so every row lands at its padded place.  rsrc covers one sample of the [*, ld_bytes/2]
-  // matrix, col_bytes is the head's column offset.  Rows >= nrows repeat row nrows-1 (finite values; callers mask them).
+  // The same rows straight from global memory into LDS, no registers in between (D = 128): 16 bytes per lane, a load
+  // instruction fills 4 rows.  rsrc covers exactly one sample of the [*, ld_bytes/2] matrix, col_bytes is the head's
+  // column offset.  Rows past the sample's end and chunks past the head's own width d are beyond the buffer's range
+  // (every part of the address is in the range-checked offset): the hardware makes them zeros; callers mask such keys.
   // The loads are asynchronous: wait for vmcnt(0) and a workgroup barrier before reading the tile.
-  // (A lane of such a load fills one 4-byte LDS slot whatever the load width, so this needs rows of 64 x 4 bytes;
-  // D = 64 keeps the register path.)
-  static constexpr bool DIRECT = D == 128;
-  static constexpr int NW = THREADS / 64, ROW_LOADS = ROWS / NW, LANE_BYTES = 4;
-  // Lanes past the head's own width d (2*d bytes of the 256) carry an offset beyond the buffer's range: the hardware's
-  // range check makes them write zeros.
-  __device__ static void stage(__amdgpu_buffer_rsrc_t rsrc, unsigned col_bytes, unsigned ld_bytes, int row0, int nrows, lds_bf16* lds, int d) {
-    static_assert(DIRECT, "rows of 256 bytes only");
+  static constexpr int NW = THREADS / 64, LOADS = ROWS / 4, PER_WAVE = LOADS / NW;
+  // the part of the offset that belongs to the lane (the same for every tile: the compiler keeps it out of the loops)
+  __device__ static unsigned stage_lane(int j, unsigned ld_bytes, int d) {
+    const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6), lane = threadIdx.x & 63;
+    const int row = (wave * PER_WAVE + j) * 4 + (lane >> 4);
+    const int c = (lane & 15) ^ swz(row);
+    return c * 8 < d ? (unsigned)row * ld_bytes + (unsigned)c * 16 : 0x80000000u;
+  }
+  __device__ static void stage(__amdgpu_buffer_rsrc_t rsrc, unsigned col_bytes, unsigned ld_bytes, int row0, lds_bf16* lds, int d) {
+    static_assert(DIRECT && LOADS % NW == 0, "rows of 256 bytes, loads split evenly over the wavefronts");
     const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
-    const unsigned in_row = (threadIdx.x & 63) * LANE_BYTES;
-    const unsigned lane_off = in_row < 2u * (unsigned)d ? in_row : 0x80000000u;
+    const unsigned tile = (unsigned)row0 * ld_bytes + col_bytes;
 #pragma unroll
-    for (int j = 0; j < ROW_LOADS; ++j) {
-      const int r = j * NW + wave;
-      const unsigned row = (unsigned)min(row0 + r, nrows - 1);
-      __builtin_amdgcn_raw_ptr_buffer_load_lds(rsrc, (LDS_AS void*)(lds + r * LD), 4, lane_off, row * ld_bytes + col_bytes, 0, 0);
-    }
+    for (int j = 0; j < PER_WAVE; ++j)
+      __builtin_amdgcn_raw_ptr_buffer_load_lds(rsrc, (LDS_AS void*)(lds + (wave * PER_WAVE + j) * 4 * LD), 16,
+                                               stage_lane(j, ld_bytes, d) + tile, 0, 0, 0);
   }
   __device__ static void store_lds(lds_bf16* lds, const bf16x8 (&reg)[PER_THREAD]) {
 #pragma unroll
     for (int p = 0; p < PER_THREAD; ++p) {
       const int v = threadIdx.x + THREADS * p;
-      const int row = v / (D / 8), c = (v % (D / 8)) * 8;
-      *reinterpret_cast<LDS_AS bf16x8*>(lds + row * LD + c) = reg[p];
+      const int row = v / (D / 8), c = v % (D / 8);
+      *reinterpret_cast<LDS_AS bf16x8*>(lds + row * LD + (DIRECT ? c ^ swz(row) : c) * 8) = reg[p];
     }
   }
-  // operand with MFMA rows = tile rows [rb, rb+32), contraction over d in [kk, kk+16)
+  // operand with MFMA rows = tile rows [rb, rb+32), contraction over d in [kk, kk+16)   (rb: a multiple of 16 rows from
+  // the tile's first row, so that a row's place in its group of 16 is the lane's)
   __device__ static bf16x8 frag_rows(const lds_bf16* lds, int rb, int kk) {
     const int lane = threadIdx.x & 63;
-    return *reinterpret_cast<const LDS_AS bf16x8*>(lds + (rb + (lane & 31)) * LD + kk + (lane >> 5) * 8);
+    if constexpr (DIRECT) {
+      // chunk (kk/8 + h) ^ swz = (kk/8) ^ (h ^ swz): the lane's part once, the fragment's part as an XOR of the byte address
+      const unsigned own = (unsigned)(lane & 31) * (LD * 2) + (unsigned)(((lane >> 5) ^ swz(lane & 15)) << 4);
+      return *reinterpret_cast<const LDS_AS bf16x8*>((const LDS_AS char*)lds + rb * (LD * 2) + (own ^ (unsigned)(kk * 2)));
+    } else {
+      return *reinterpret_cast<const LDS_AS bf16x8*>(lds + (rb + (lane & 31)) * LD + kk + (lane >> 5) * 8);
+    }
   }
   // operand with MFMA rows = d in [db, db+32), contraction over 16 tile rows in the order the
   // accumulator of a preceding 32x32 product holds them: slot 4c+i of half-wave h is tile row
-  // tb + 8c + 4h + i  (tb = first of the 16 rows)
+  // tb + 8c + 4h + i  (tb = first of the 16 rows, a multiple of 16 rows from the tile's first row)
   __device__ static bf16x8 frag_cols(const lds_bf16* lds, int db, int tb) {
     const int lane = threadIdx.x & 63;
     const int g = lane >> 4, i = lane & 15;
-    const lds_bf16* p0 = lds + (tb + 4 * (g >> 1) + (i >> 2)) * LD + db + 16 * (g & 1) + 4 * (i & 3);
-    s16x4 lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16((LDS_AS s16x4*)(p0));
-    s16x4 hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16((LDS_AS s16x4*)(p0 + 8 * LD));
+    s16x4 lo, hi;
+    if constexpr (DIRECT) {
+      // rows r and r + 8 (r < 8): swz(r + 8) = swz(r) | 1, so the second read is the first with chunk bit 0 flipped
+      const int r = 4 * (g >> 1) + (i >> 2);
+      const unsigned own = (unsigned)r * (LD * 2) + (unsigned)(((2 * (g & 1) + ((i & 3) >> 1)) ^ swz(r)) << 4) + 8u * (i & 1);
+      const LDS_AS char* p0 = (const LDS_AS char*)lds + tb * (LD * 2);
+      lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16((LDS_AS s16x4*)(p0 + (own ^ (unsigned)(db * 2))));
+      hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16((LDS_AS s16x4*)(p0 + 8 * (LD * 2) + ((own ^ 16u) ^ (unsigned)(db * 2))));
+    } else {
+      const lds_bf16* p0 = lds + (tb + 4 * (g >> 1) + (i >> 2)) * LD + db + 16 * (g & 1) + 4 * (i & 3);
+      lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16((LDS_AS s16x4*)(p0));
+      hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16((LDS_AS s16x4*)(p0 + 8 * LD));
+    }
     union { struct { s16x4 a, b; } s; bf16x8 v; } u;
     u.s.a = lo; u.s.b = hi;
     return u.v;
   }
 };
+
+// Which (tile pair, head, sample) a block works on.  Blocks are dealt round-robin to the 8 XCDs, each with an L2 of its
+// own, and the blocks of one head (its query-tile pairs) all stream that head's keys and values: dealt out in launch
+// order they land on 8 different XCDs, every XCD fetches every head's keys and values from memory and every staged
+// tile pays the full memory latency.  Give each XCD a contiguous run of the (pair, head, sample) order instead, so the
+// blocks of a head sit behind one L2: the first to ask for a tile brings it in, the others hit.
+struct BlockCoords { int x, y, z; };
+__device__ __forceinline__ BlockCoords block_coords() {
+  const int gx = gridDim.x, gy = gridDim.y, n = gx * gy * gridDim.z;
+  int l = blockIdx.x + gx * (blockIdx.y + gy * blockIdx.z);
+  if (n % 8 == 0) l = (l % 8) * (n / 8) + l / 8;
+  // (the divisions run on the vector unit; readfirstlane tells the compiler that the results are uniform)
+  return {__builtin_amdgcn_readfirstlane(l % gx), __builtin_amdgcn_readfirstlane((l / gx) % gy), __builtin_amdgcn_readfirstlane(l / (gx * gy))};
+}
 
 // fragment of 32 rows of a row-major [*, ld] matrix straight from global memory (rows = MFMA rows)
 template <int D>
@@ -199,7 +238,8 @@ attn_fwd_kernel(const bf16* __restrict__ qkv, bf16* __restrict__ O, float* __res
   auto Ks = [&](int st) { return smem + st * 2 * TL::ELEMS; };
   auto Vs = [&](int st) { return smem + st * 2 * TL::ELEMS + TL::ELEMS; };
 
-  const int a = blockIdx.y, n = blockIdx.z;
+  const BlockCoords blk = block_coords();
+  const int a = blk.y, n = blk.z;
   const int d = H / A;        // the head's own width: D, or less (a multiple of 8) with the tiles' further columns held at zero
   const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);   // scalar: tests on a wavefront's rows become real branches
   const int lane = threadIdx.x & 63, h = lane >> 5;
@@ -211,8 +251,8 @@ attn_fwd_kernel(const bf16* __restrict__ qkv, bf16* __restrict__ O, float* __res
   // ranges add up to the same length for every x.
   const int ntq = (S + 127) / 128;
   for (int pass = 0; pass < (CAUSAL ? 2 : 1); ++pass) {
-  const int qt = pass == 0 ? (int)blockIdx.x : ntq - 1 - (int)blockIdx.x;
-  if (pass == 1 && qt == (int)blockIdx.x) break;   // odd tile count: the middle tile is its own partner
+  const int qt = pass == 0 ? blk.x : ntq - 1 - blk.x;
+  if (pass == 1 && qt == blk.x) break;   // odd tile count: the middle tile is its own partner
   const int q0 = qt * 128 + wave * 32;             // this wavefront's 32 query rows
   const int q = q0 + (lane & 31);
 
@@ -342,7 +382,8 @@ attn_fwd8_kernel(const bf16* __restrict__ qkv, bf16* __restrict__ O, float* __re
   auto Ks = [&](int st) { return smem + st * 2 * TL::ELEMS; };
   auto Vs = [&](int st) { return smem + st * 2 * TL::ELEMS + TL::ELEMS; };
 
-  const int a = blockIdx.y, n = blockIdx.z;
+  const BlockCoords blk = block_coords();
+  const int a = blk.y, n = blk.z;
   const int d = H / A;        // the head's own width: D, or less (a multiple of 8) with the tiles' further columns held at zero
   const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);   // scalar: tests on a wavefront's rows become real branches
   const int lane = threadIdx.x & 63, h = lane >> 5;
@@ -354,8 +395,8 @@ attn_fwd8_kernel(const bf16* __restrict__ qkv, bf16* __restrict__ O, float* __re
   const float c2 = scale * kLog2e;
   const int ntq = (S + 127) / 128;                  // causal: query tile x, then its mirror tile (equal work per block)
   for (int pass = 0; pass < (CAUSAL ? 2 : 1); ++pass) {
-    const int qt = pass == 0 ? (int)blockIdx.x : ntq - 1 - (int)blockIdx.x;
-    if (pass == 1 && qt == (int)blockIdx.x) break;
+    const int qt = pass == 0 ? blk.x : ntq - 1 - blk.x;
+    if (pass == 1 && qt == blk.x) break;
     const int q0 = qt * 128 + qsub * 32;
     const int q = q0 + (lane & 31);
 
@@ -372,8 +413,8 @@ attn_fwd8_kernel(const bf16* __restrict__ qkv, bf16* __restrict__ O, float* __re
     const int ntiles = (kv_end + 127) / 128;
     bf16x8 rk[TL::DIRECT ? 1 : TL::PER_THREAD], rv[TL::DIRECT ? 1 : TL::PER_THREAD];   // register staging (D = 64)
     if constexpr (TL::DIRECT) {
-      TL::stage(rs_qkv, k_bytes, (unsigned)ld * 2, 0, S, Ks(0), d);
-      TL::stage(rs_qkv, v_bytes, (unsigned)ld * 2, 0, S, Vs(0), d);
+      TL::stage(rs_qkv, k_bytes, (unsigned)ld * 2, 0, Ks(0), d);
+      TL::stage(rs_qkv, v_bytes, (unsigned)ld * 2, 0, Vs(0), d);
     } else {
       TL::load_global(base + H, ld, 0, S, rk, d);
       TL::load_global(base + 2 * H, ld, 0, S, rv, d);
@@ -387,8 +428,8 @@ attn_fwd8_kernel(const bf16* __restrict__ qkv, bf16* __restrict__ O, float* __re
       const int cur = kt & 1;
       if (kt + 1 < ntiles) {                           // the next stage flies meanwhile
         if constexpr (TL::DIRECT) {
-          TL::stage(rs_qkv, k_bytes, (unsigned)ld * 2, (kt + 1) * 128, S, Ks(cur ^ 1), d);
-          TL::stage(rs_qkv, v_bytes, (unsigned)ld * 2, (kt + 1) * 128, S, Vs(cur ^ 1), d);
+          TL::stage(rs_qkv, k_bytes, (unsigned)ld * 2, (kt + 1) * 128, Ks(cur ^ 1), d);
+          TL::stage(rs_qkv, v_bytes, (unsigned)ld * 2, (kt + 1) * 128, Vs(cur ^ 1), d);
         } else {
           TL::load_global(base + H, ld, (kt + 1) * 128, S, rk, d);
           TL::load_global(base + 2 * H, ld, (kt + 1) * 128, S, rv, d);
@@ -496,6 +537,251 @@ attn_fwd8_kernel(const bf16* __restrict__ qkv, bf16* __restrict__ O, float* __re
   }
 }
 
+// The matrix-core step of one wavefront, written as an explicit pipeline: the LDS fragment of product i + kAhead is
+// requested right after product i is issued, into the register product i just freed.  PV: the 16 products
+// O^T += V^T P^T of the tile before (fragments by transposing reads); QK: the 16 products S^T = K Q^T of this tile.
+// `between(i)` runs after product i is issued (the staging loads of the next tiles are dealt out there, a few at a time:
+// issued in one bunch they hold the wavefront until the memory pipeline has taken them all).
+template <int D, bool PV, bool QK, typename TL, typename Between>
+__device__ __forceinline__ void turn_products(const lds_bf16* Vt, const lds_bf16* Kt, const bf16x8 (&pf)[2][2], const bf16x8 (&qf)[D / 16],
+                                              f32x16 (&o)[D / 32], f32x16 (&s)[2], Between between) {
+  static_assert(D == 128, "16 + 16 products");
+  constexpr int NPV = PV ? 16 : 0, N = NPV + (QK ? 16 : 0), kAhead = 4;      // (3 to 8 ahead measure the same)
+  auto fetch = [&](int i) -> bf16x8 {
+    if (i < NPV) return TL::frag_cols(Vt, (i % 4) * 32, (i / 8) * 32 + 16 * ((i / 4) % 2));
+    const int j = i - NPV;
+    return TL::frag_rows(Kt, (j % 2) * 32, (j / 2) * 16);
+  };
+  bf16x8 f[kAhead];
+#pragma unroll
+  for (int i = 0; i < kAhead; ++i) f[i] = fetch(i);
+  if (QK) {
+#pragma unroll
+    for (int tb = 0; tb < 2; ++tb)
+#pragma unroll
+      for (int e = 0; e < 16; ++e) s[tb][e] = 0.f;
+  }
+  __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+  for (int i = 0; i < N; ++i) {
+    if (i < NPV) {
+      o[i % 4] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(f[i % kAhead], pf[i / 8][(i / 4) % 2], o[i % 4], 0, 0, 0);
+    } else {
+      const int j = i - NPV;
+      s[j % 2] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(f[i % kAhead], qf[j / 2], s[j % 2], 0, 0, 0);
+    }
+    if (i + kAhead < N) f[i % kAhead] = fetch(i + kAhead);
+    between(i);
+    __builtin_amdgcn_sched_barrier(0);
+  }
+}
+
+// ------------------------------------------------------------------------------------ forward, two groups in turns
+// The eight-wavefront forward above leaves its two groups in step: the barrier of every key tile starts them together,
+// so both multiply at the same time (sharing the matrix core) and then both run their softmax at the same time (sharing
+// the vector unit) -- a tile costs the sum of the two, not the larger.  Here the groups take turns.  Time is cut into
+// phases closed by a barrier; in a phase one group multiplies (the products of its softmax of the tile before, then the
+// scores of the next tile) while the other runs its softmax, and in the next phase they swap:
+//   step 2k   of a group:  O^T += V_{k-1}^T P_{k-1}^T ;  S_k^T = K_k Q^T        (matrix core, LDS reads)
+//   step 2k+1 of a group:  P_k = softmax piece of S_k                            (vector unit)
+// group 0 runs step p in phase p, group 1 runs step p-1.  K_{k+1} and V_k are staged during phases 2k and 2k+1 (V is
+// wanted one tile later than K now) into the buffers that K_{k-1} and V_{k-2} left at the end of phase 2k-1: group 0
+// issues the loads between the products of its step 2k and waits for them at the end of phase 2k+1.  The staging
+// loads are issued behind the compiler's back (it would make the next transposing LDS read wait for them).
+typedef int i32x4 __attribute__((ext_vector_type(4)));
+
+template <int D, bool CAUSAL>
+__global__ void __launch_bounds__(kThreads8)
+attn_fwd_turns_kernel(const bf16* __restrict__ qkv, bf16* __restrict__ O, float* __restrict__ lse, int S, int H, int A, float scale) {
+  typedef Tile<D, 128, kThreads8> TL;
+  static_assert(TL::DIRECT, "rows of 256 bytes");
+  extern __shared__ __attribute__((aligned(1024))) char smem_raw[];
+  lds_bf16* smem = (lds_bf16*)smem_raw;
+  auto Ks = [&](int st) { return smem + st * 2 * TL::ELEMS; };
+  auto Vs = [&](int st) { return smem + st * 2 * TL::ELEMS + TL::ELEMS; };
+
+  const BlockCoords blk = block_coords();
+  const int a = blk.y, n = blk.z;
+  const int d = H / A;
+  const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+  const int lane = threadIdx.x & 63, h = lane >> 5;
+  const int qsub = wave & 3, kh = wave >> 2;
+  const int64_t ld = 3 * (int64_t)H;
+  const bf16* base = qkv + (int64_t)n * S * ld + a * d;
+  const unsigned ld_bytes = (unsigned)ld * 2;
+  const unsigned k_bytes = (unsigned)((H + a * d) * 2), v_bytes = (unsigned)((2 * H + a * d) * 2);
+  const uint64_t addr = (uint64_t)(uintptr_t)(qkv + (int64_t)n * S * ld);
+  const i32x4 rsrc = {(int)(unsigned)addr, (int)(unsigned)((addr >> 32) & 0xffffu), (int)(unsigned)(S * ld * 2), 0x00020000};
+  // Staging is group 0's job (its four wavefronts split a tile's 32 load instructions: 8 each per operand), dealt out
+  // between the products of its matrix-core step.  Load q of a tile pair: q < 8 the keys, else the values.
+  typedef Tile<D, 128, 256> TS;
+  unsigned lane_part[TS::PER_WAVE];
+#pragma unroll
+  for (int j = 0; j < TS::PER_WAVE; ++j) lane_part[j] = kh == 0 ? TS::stage_lane(j, ld_bytes, d) : 0x80000000u;
+  auto stage_one = [&](int j, unsigned col_bytes, int row0, lds_bf16* lds) {
+    const unsigned dst = (unsigned)(uintptr_t)(lds + (wave * TS::PER_WAVE + j) * 4 * TL::LD);
+    const unsigned off = lane_part[j] + ((unsigned)row0 * ld_bytes + col_bytes);
+    asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tbuffer_load_dwordx4 %1, %2, 0 offen lds" :: "s"(dst), "v"(off), "s"(rsrc) : "m0");
+  };
+  const float c2 = scale * kLog2e;
+  const int ntq = (S + 127) / 128;
+  for (int pass = 0; pass < (CAUSAL ? 2 : 1); ++pass) {
+    const int qt = pass == 0 ? blk.x : ntq - 1 - blk.x;
+    if (pass == 1 && qt == blk.x) break;
+    const int q0 = qt * 128 + qsub * 32;
+    const int q = q0 + (lane & 31);
+
+    bf16x8 qf[D / 16];
+    load_row_frags<D>(base, ld, q0, S, qf, d);
+    f32x16 o[D / 32];
+#pragma unroll
+    for (int dt = 0; dt < D / 32; ++dt)
+#pragma unroll
+      for (int e = 0; e < 16; ++e) o[dt][e] = 0.f;
+    float m_run = -INFINITY, l_run = 0.f;
+
+    const int kv_end = CAUSAL ? min(S, qt * 128 + 128) : S;
+    const int ntiles = (kv_end + 127) / 128;
+    // this wavefront's 64 keys of tile k start at t0(k); the piece is skipped when it lies wholly past the queries
+    auto first_key = [&](int k) { return k * 128 + kh * 64; };
+    auto wanted = [&](int k) { const int t0 = first_key(k); return k < ntiles && t0 < S && (!CAUSAL || t0 <= q0 + 31); };
+
+    if (kh == 0) {
+#pragma unroll
+      for (int j = 0; j < TS::PER_WAVE; ++j) stage_one(j, k_bytes, 0, Ks(0));
+    }
+    __builtin_amdgcn_s_waitcnt(0x0F70);                // vmcnt(0)
+    __syncthreads();
+
+    f32x16 s[2];
+    bf16x8 pf[2][2];
+    // the matrix-core step for tile k (products of tile k-1's probabilities, then tile k's scores)
+    // (tile k's scores come from K buffer k & 1, tile k-1's values from V buffer (k - 1) & 1)
+    auto Vprev = [&](int k) { return Vs((k + 1) & 1) + kh * 64 * TL::LD; };
+    auto Kcur = [&](int k) { return Ks(k & 1) + kh * 64 * TL::LD; };
+    // the vector-unit step for tile k
+    auto soften = [&](int k) {
+      if (!wanted(k)) {       // this wavefront's keys lie past its queries (or past the sequence): its products add nothing
+#pragma unroll
+        for (int tb = 0; tb < 2; ++tb)
+#pragma unroll
+          for (int jj = 0; jj < 2; ++jj) pf[tb][jj] = bf16x8{0, 0, 0, 0, 0, 0, 0, 0};
+        return;
+      }
+      const int t0 = first_key(k);
+      if ((CAUSAL && t0 + 63 > q0) || t0 + 64 > S) {      // diagonal or ragged end: per-element masking
+#pragma unroll
+        for (int tb = 0; tb < 2; ++tb)
+#pragma unroll
+          for (int e = 0; e < 16; ++e) {
+            const int t = t0 + tb * 32 + 8 * (e >> 2) + 4 * h + (e & 3);
+            if (t >= S || (CAUSAL && t > q)) s[tb][e] = -INFINITY;
+          }
+      }
+      float mx = -INFINITY;
+#pragma unroll
+      for (int tb = 0; tb < 2; ++tb)
+#pragma unroll
+        for (int e = 0; e < 16; ++e) mx = fmaxf(mx, s[tb][e]);
+      mx = fmaxf(mx, __shfl_xor(mx, 32, 64)) * c2;
+      if (__any(mx > m_run + 8.0f)) {                       // lazy raise of the running maximum (log2 domain)
+        const float m_new = fmaxf(m_run, mx);
+        const float alpha = (m_new == -INFINITY) ? 1.0f : __builtin_amdgcn_exp2f(m_run - m_new);
+        l_run *= alpha;
+        m_run = m_new;
+#pragma unroll
+        for (int dt = 0; dt < D / 32; ++dt)
+#pragma unroll
+          for (int e = 0; e < 16; ++e) o[dt][e] *= alpha;
+      }
+      const float neg_m = (m_run == -INFINITY) ? 0.f : -m_run;
+      float psum = 0.f;
+#pragma unroll
+      for (int tb = 0; tb < 2; ++tb)
+#pragma unroll
+        for (int e = 0; e < 16; ++e) {
+          const float p = __builtin_amdgcn_exp2f(__builtin_fmaf(s[tb][e], c2, neg_m));
+          s[tb][e] = p;
+          psum += p;
+        }
+      l_run += psum;
+#pragma unroll
+      for (int tb = 0; tb < 2; ++tb)
+#pragma unroll
+        for (int jj = 0; jj < 2; ++jj) pf[tb][jj] = pack8(s[tb], 8 * jj);
+    };
+    // load q (0..15) of the pair staged while tile k is multiplied: K of tile k+1, V of tile k
+    auto stage_next = [&](int k, int q) {
+      if (q < TS::PER_WAVE) { if (k + 1 < ntiles) stage_one(q, k_bytes, (k + 1) * 128, Ks((k + 1) & 1)); }
+      else if (k < ntiles) stage_one(q - TS::PER_WAVE, v_bytes, k * 128, Vs(k & 1));
+    };
+    auto close_phase = [&](bool landed) {
+      if (landed) __builtin_amdgcn_s_waitcnt(0x0F70);  // vmcnt(0): the tiles staged in the phase before have landed
+      __syncthreads();
+    };
+    // Every wavefront runs every product of the schedule (an unwanted piece multiplies zeros: it occurs only on the
+    // diagonal tile), so the loop body is one straight line per group.
+    auto nothing = [](int) {};
+    if (kh == 0) {
+      turn_products<D, false, true, TL>(nullptr, Kcur(0), pf, qf, o, s, [&](int i) { stage_next(0, i); });
+      close_phase(false);
+      soften(0);
+      close_phase(true);
+      for (int k = 1; k < ntiles; ++k) {
+        turn_products<D, true, true, TL>(Vprev(k), Kcur(k), pf, qf, o, s, [&](int i) { if (i & 1) stage_next(k, i >> 1); });
+        close_phase(false);
+        soften(k);
+        close_phase(true);
+      }
+      turn_products<D, true, false, TL>(Vprev(ntiles), nullptr, pf, qf, o, s, nothing);
+      close_phase(false);
+      close_phase(false);
+    } else {
+      close_phase(false);
+      turn_products<D, false, true, TL>(nullptr, Kcur(0), pf, qf, o, s, nothing);
+      close_phase(false);
+      for (int k = 1; k < ntiles; ++k) {
+        soften(k - 1);
+        close_phase(false);
+        turn_products<D, true, true, TL>(Vprev(k), Kcur(k), pf, qf, o, s, nothing);
+        close_phase(false);
+      }
+      soften(ntiles - 1);
+      close_phase(false);
+      turn_products<D, true, false, TL>(Vprev(ntiles), nullptr, pf, qf, o, s, nothing);
+      close_phase(false);
+    }
+    // merge the two key halves: [value index][lane] floats per block of queries, lanes contiguous
+    constexpr int NV = D / 32 * 16 + 2;
+    LDS_AS float* mrg = (LDS_AS float*)smem_raw + qsub * NV * 64 + lane;
+    if (kh == 1) {
+#pragma unroll
+      for (int dt = 0; dt < D / 32; ++dt)
+#pragma unroll
+        for (int e = 0; e < 16; ++e) mrg[(dt * 16 + e) * 64] = o[dt][e];
+      mrg[(NV - 2) * 64] = m_run;
+      mrg[(NV - 1) * 64] = l_run;
+    }
+    __syncthreads();
+    if (kh == 0) {
+      const float m1 = mrg[(NV - 2) * 64], l1 = mrg[(NV - 1) * 64];
+      const float m = fmaxf(m_run, m1);
+      const float a0 = (m_run == -INFINITY) ? 0.f : __builtin_amdgcn_exp2f(m_run - m);
+      const float a1 = (m1 == -INFINITY) ? 0.f : __builtin_amdgcn_exp2f(m1 - m);
+#pragma unroll
+      for (int dt = 0; dt < D / 32; ++dt)
+#pragma unroll
+        for (int e = 0; e < 16; ++e) o[dt][e] = o[dt][e] * a0 + mrg[(dt * 16 + e) * 64] * a1;
+      const float l = l_run * a0 + l1 * a1;
+      const float l_tot = l + __shfl_xor(l, 32, 64);
+      const float inv = 1.0f / l_tot;
+      store_transposed<D>(o, O + (int64_t)n * S * H + a * d, H, q, S, inv, d);
+      if (h == 0 && q < S) lse[((int64_t)n * A + a) * S + q] = (m + __builtin_amdgcn_logf(l_tot)) * kLn2;
+    }
+    __syncthreads();     // the merge area is staged over again by the next pass
+  }
+}
+
 // ------------------------------------------------------------------------------------ rowsum(dO * O)
 // dvec[n, a, s] = sum_d dO[s, a*D + d] * O[s, a*D + d]; a head's D values sit in D/8 consecutive lanes
 template <int D>
@@ -553,7 +839,8 @@ attn_dq_kernel(const bf16* __restrict__ qkv, const bf16* __restrict__ dO, const 
   auto Ks = [&](int st) { return smem + st * 2 * TL::ELEMS; };
   auto Vs = [&](int st) { return smem + st * 2 * TL::ELEMS + TL::ELEMS; };
 
-  const int a = blockIdx.y, n = blockIdx.z;
+  const BlockCoords blk = block_coords();
+  const int a = blk.y, n = blk.z;
   const int d = H / A;        // the head's own width: D, or less (a multiple of 8) with the tiles' further columns held at zero
   const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);   // scalar: tests on a wavefront's rows become real branches
   const int lane = threadIdx.x & 63, h = lane >> 5;
@@ -565,8 +852,8 @@ attn_dq_kernel(const bf16* __restrict__ qkv, const bf16* __restrict__ dO, const 
   const float c2 = scale * kLog2e;
   const int ntq = (S + 127) / 128;                 // causal: query tiles x and ntq-1-x in turn (equal work per block)
   for (int pass = 0; pass < (CAUSAL ? 2 : 1); ++pass) {
-  const int qt = pass == 0 ? (int)blockIdx.x : ntq - 1 - (int)blockIdx.x;
-  if (pass == 1 && qt == (int)blockIdx.x) break;
+  const int qt = pass == 0 ? blk.x : ntq - 1 - blk.x;
+  if (pass == 1 && qt == blk.x) break;
   const int q0 = qt * 128 + qsub * 32;
   const int q = q0 + (lane & 31);
 
@@ -587,8 +874,8 @@ attn_dq_kernel(const bf16* __restrict__ qkv, const bf16* __restrict__ dO, const 
   const int ntiles = (kv_end + 127) / 128;
   bf16x8 rk[TL::DIRECT ? 1 : TL::PER_THREAD], rv[TL::DIRECT ? 1 : TL::PER_THREAD];   // register staging (D = 64)
   if constexpr (TL::DIRECT) {
-    TL::stage(rs_qkv, k_bytes, (unsigned)ld * 2, 0, S, Ks(0), d);
-    TL::stage(rs_qkv, v_bytes, (unsigned)ld * 2, 0, S, Vs(0), d);
+    TL::stage(rs_qkv, k_bytes, (unsigned)ld * 2, 0, Ks(0), d);
+    TL::stage(rs_qkv, v_bytes, (unsigned)ld * 2, 0, Vs(0), d);
   } else {
     TL::load_global(base + H, ld, 0, S, rk, d);
     TL::load_global(base + 2 * H, ld, 0, S, rv, d);
@@ -602,8 +889,8 @@ attn_dq_kernel(const bf16* __restrict__ qkv, const bf16* __restrict__ dO, const 
     const int cur = kt & 1;
     if (kt + 1 < ntiles) {                             // the next stage flies meanwhile
       if constexpr (TL::DIRECT) {
-        TL::stage(rs_qkv, k_bytes, (unsigned)ld * 2, (kt + 1) * 128, S, Ks(cur ^ 1), d);
-        TL::stage(rs_qkv, v_bytes, (unsigned)ld * 2, (kt + 1) * 128, S, Vs(cur ^ 1), d);
+        TL::stage(rs_qkv, k_bytes, (unsigned)ld * 2, (kt + 1) * 128, Ks(cur ^ 1), d);
+        TL::stage(rs_qkv, v_bytes, (unsigned)ld * 2, (kt + 1) * 128, Vs(cur ^ 1), d);
       } else {
         TL::load_global(base + H, ld, (kt + 1) * 128, S, rk, d);
         TL::load_global(base + 2 * H, ld, (kt + 1) * 128, S, rv, d);
@@ -704,7 +991,8 @@ attn_dkv_kernel(const bf16* __restrict__ qkv, const bf16* __restrict__ dO, const
   lds_bf16* Vs = Ks + TKV::ELEMS;
   LDS_AS float* stats = (LDS_AS float*)(Vs + TKV::ELEMS);   // [2 buffers][lse2 | dvec][64]
 
-  const int a = blockIdx.y, n = blockIdx.z;
+  const BlockCoords blk = block_coords();
+  const int a = blk.y, n = blk.z;
   const int d = H / A;        // the head's own width: D, or less (a multiple of 8) with the tiles' further columns held at zero
   const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);   // scalar: tests on a wavefront's rows become real branches
   const int lane = threadIdx.x & 63, h = lane >> 5;
@@ -720,14 +1008,14 @@ attn_dkv_kernel(const bf16* __restrict__ qkv, const bf16* __restrict__ dO, const
   const float c2 = scale * kLog2e;
   const int ntk = (S + 127) / 128;                 // causal: key tiles x and ntk-1-x in turn (early key tiles see the most queries)
   for (int pass = 0; pass < (CAUSAL ? 2 : 1); ++pass) {
-  const int tt = pass == 0 ? (int)blockIdx.x : ntk - 1 - (int)blockIdx.x;
-  if (pass == 1 && tt == (int)blockIdx.x) break;
+  const int tt = pass == 0 ? blk.x : ntk - 1 - blk.x;
+  if (pass == 1 && tt == blk.x) break;
   const int t0 = tt * 128 + kg * 32;               // this wavefront's 32 keys
   const int t = t0 + (lane & 31);
 
   if constexpr (TL::DIRECT) {
-    TKV::stage(rs_qkv, (unsigned)H * 2 + col_bytes, (unsigned)ld * 2, tt * 128, S, Ks, d);
-    TKV::stage(rs_qkv, (unsigned)H * 4 + col_bytes, (unsigned)ld * 2, tt * 128, S, Vs, d);
+    TKV::stage(rs_qkv, (unsigned)H * 2 + col_bytes, (unsigned)ld * 2, tt * 128, Ks, d);
+    TKV::stage(rs_qkv, (unsigned)H * 4 + col_bytes, (unsigned)ld * 2, tt * 128, Vs, d);
   } else {
     bf16x8 rkv[TKV::PER_THREAD];
     TKV::load_global(base + H, ld, tt * 128, S, rkv, d);
@@ -754,8 +1042,8 @@ attn_dkv_kernel(const bf16* __restrict__ qkv, const bf16* __restrict__ dO, const
   };
   bf16x8 rq[TL::DIRECT ? 1 : TL::PER_THREAD], rdo[TL::DIRECT ? 1 : TL::PER_THREAD];   // register staging (D = 64)
   if constexpr (TL::DIRECT) {
-    TL::stage(rs_qkv, col_bytes, (unsigned)ld * 2, first * TILE, S, Qs(0), d);
-    TL::stage(rs_do, col_bytes, (unsigned)H * 2, first * TILE, S, dOs(0), d);
+    TL::stage(rs_qkv, col_bytes, (unsigned)ld * 2, first * TILE, Qs(0), d);
+    TL::stage(rs_do, col_bytes, (unsigned)H * 2, first * TILE, dOs(0), d);
   } else {
     TL::load_global(base, ld, first * TILE, S, rq, d);
     TL::load_global(dObase, H, first * TILE, S, rdo, d);
@@ -771,8 +1059,8 @@ attn_dkv_kernel(const bf16* __restrict__ qkv, const bf16* __restrict__ dO, const
     const int cur = (it - first) & 1, qb0 = it * TILE;
     if (it + 1 < ntiles) {                             // the next tile flies into the other stage meanwhile
       if constexpr (TL::DIRECT) {
-        TL::stage(rs_qkv, col_bytes, (unsigned)ld * 2, qb0 + TILE, S, Qs(cur ^ 1), d);
-        TL::stage(rs_do, col_bytes, (unsigned)H * 2, qb0 + TILE, S, dOs(cur ^ 1), d);
+        TL::stage(rs_qkv, col_bytes, (unsigned)ld * 2, qb0 + TILE, Qs(cur ^ 1), d);
+        TL::stage(rs_do, col_bytes, (unsigned)H * 2, qb0 + TILE, dOs(cur ^ 1), d);
       } else {
         TL::load_global(base, ld, qb0 + TILE, S, rq, d);
         TL::load_global(dObase, H, qb0 + TILE, S, rdo, d);
@@ -888,10 +1176,18 @@ int fwd_cfg(const bf16* qkv, bf16* O, float* lse, int m, int S, int H, int A, hi
   if (CAUSAL) {
     // one paired block per compute unit: eight wavefronts, the staged keys split between two groups
     const size_t lds = 4 * (size_t)Tile<D, 128, kThreads8>::ELEMS * sizeof(bf16);
-    auto kern = attn_fwd8_kernel<D, CAUSAL>;
-    int rc = reserve_lds(kern, lds);
-    if (rc != CEPHALO_OK) return rc;
-    kern<<<grid, kThreads8, lds, s>>>(qkv, O, lse, S, H, A, 1.0f / sqrtf((float)(H / A)));
+    if constexpr (Tile<D, 128, kThreads8>::DIRECT) {
+      // (tiles staged straight into LDS: the two groups take turns on the matrix core and the vector unit)
+      auto kern = attn_fwd_turns_kernel<D, CAUSAL>;
+      int rc = reserve_lds(kern, lds);
+      if (rc != CEPHALO_OK) return rc;
+      kern<<<grid, kThreads8, lds, s>>>(qkv, O, lse, S, H, A, 1.0f / sqrtf((float)(H / A)));
+    } else {
+      auto kern = attn_fwd8_kernel<D, CAUSAL>;
+      int rc = reserve_lds(kern, lds);
+      if (rc != CEPHALO_OK) return rc;
+      kern<<<grid, kThreads8, lds, s>>>(qkv, O, lse, S, H, A, 1.0f / sqrtf((float)(H / A)));
+    }
   } else {
     // uniform tiles: two independent four-wavefront blocks per compute unit run out of phase with each other
     // (measured 12 % faster than the eight-wavefront form, whose wavefronts move in step between barriers)

@@ -231,7 +231,14 @@ constexpr int vmcnt_only(int n) { return 0x0F70 | (n & 15) | ((n >> 4) << 14); }
 // accumulators, the MI row-operand fragments of this k-step and of the next, and NI column-operand fragments that
 // are refilled in place: as soon as the MI products of column block j have been issued, its register takes the
 // fragment of the next k-step, which is needed a whole k-step later.
-template <int BM, int BN, int WGM, int WGN, bool AK, bool BKF, int EPI, int NS>
+//
+// L2 prefetch (PF > 0: the distance in slabs).  The blocks of an XCD walk the contracted axis in step, so the slab they
+// all ask for next is in no L2 yet and every direct-to-LDS load pays the full memory latency inside a budget of one
+// slab period (two stages).  One tile of the XCD's patch therefore touches each 128-byte line of the slab PF slabs
+// beyond the one being loaded: a 4-byte direct-to-LDS load per wavefront and slab into a scratch line of LDS that
+// nothing reads (a load without a register result, so nothing can be clobbered when it lands).  The loads proper then
+// hit L2.  The prefetch is last in issue order, so the waits leave one more operation outstanding.
+template <int BM, int BN, int WGM, int WGN, bool AK, bool BKF, int EPI, int NS, int PF>
 __global__ void __launch_bounds__(64 * WGM * WGN) gemm_mfma_kernel(GemmArgs<bf16> a, int tiles_m, int tiles_n, int slabs_per_split) {
   constexpr int NW = WGM * WGN;
   typedef OperandTile<BM, AK, NW> TA;
@@ -323,14 +330,64 @@ __global__ void __launch_bounds__(64 * WGM * WGN) gemm_mfma_kernel(GemmArgs<bf16
   static_assert(BKF || WTN % 64 == 0, "block bits of a row-contiguous B tile");
 
   constexpr int LOADS = TA::PER_WAVE + TB::PER_WAVE;
-  static_assert((NS - 1) * LOADS < 64, "the outstanding loads must fit the counter");
+  constexpr int PER_SLAB = LOADS + (PF > 0 ? 1 : 0);      // memory operations a wavefront issues per slab
+  constexpr int LAST = PF > 0 ? 1 : 0;                     // ... of which these come after the slab's own loads
+  static_assert((NS - 1) * PER_SLAB + LAST < 64, "the outstanding loads must fit the counter");
+  // Prefetch bookkeeping.  A panel of R rows has R lines per slab in either layout (k-contiguous: a row's 64 k-values;
+  // row-contiguous: 64 k-rows of R / 64 lines each).  pf_k: the k-row within the slab that this lane's line belongs to
+  // (0 for k-contiguous panels).
+  unsigned pf_off = kOob, pf_step = 0;
+  int pf_k = 0, pf_slab = kb0 + NS;
+  i32x4 pf_rsrc = ra_rsrc;
+  const unsigned pf_lds = (unsigned)(uintptr_t)(smem + NS * STAGE);
+  if constexpr (PF > 0) {
+    // The 32 tiles an XCD runs at a time are 4 tile rows by 8 tile columns: a row panel of A is wanted by 8 of them, a
+    // column panel of B by 4, and one touch per line is enough -- the tile in column c of the patch takes the c-th
+    // eighth of its A panel's lines, the tile in row r the r-th quarter of its B panel's.  Wavefront 0 touches A,
+    // wavefront 1 touches B, the others issue the same instruction with every lane out of range (the waits count
+    // operations).  Tiles that are not in step with their patch only lose the benefit.
+    const int wv = __builtin_amdgcn_readfirstlane((int)threadIdx.x >> 6);
+    const bool in_a = wv == 0;
+    const int lane_ = (int)threadIdx.x & 63;
+    const bool kf = in_a ? AK : BKF;
+    const int rows = in_a ? BM : BN, row0 = in_a ? m0 : n0, nrows = in_a ? a.M : a.N;
+    const int share = in_a ? 8 : 4, part = in_a ? (tile_n & 7) : (tile_m & 3);
+    const int lines = rows / share;                        // this tile's share of the panel's lines (<= 64)
+    const int64_t rs = in_a ? a.a_rs : a.b_rs, cs = in_a ? a.a_cs : a.b_cs;
+    if (wv < 2 && lane_ < lines) {
+      const int t = part * lines + lane_;
+      if (kf) {
+        if (row0 + t < nrows) pf_off = (unsigned)(2 * ((int64_t)(row0 + t) * rs));
+      } else {
+        const int lpk = rows / 64, seg = t % lpk;
+        pf_k = t / lpk;
+        if (row0 + seg * 64 < nrows) pf_off = (unsigned)(2 * ((int64_t)pf_k * cs + row0 + seg * 64));
+      }
+    }
+    pf_step = in_a ? a_step : b_step;
+    if (!in_a) pf_rsrc = rb_rsrc;
+    if (pf_off != kOob) pf_off += (unsigned)pf_slab * pf_step;
+  }
+  auto prefetch_next = [&]() {            // touch the lines of slab pf_slab, move on to the next slab
+    if constexpr (PF > 0) {
+      const unsigned o = (pf_slab * BK + pf_k < a.K) ? pf_off : kOob;
+      asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tbuffer_load_dword %1, %2, 0 offen lds" :: "s"(pf_lds), "v"(o), "s"(pf_rsrc) : "m0");
+      if (pf_off != kOob) pf_off += pf_step;
+      ++pf_slab;
+    }
+  };
+  auto prefetch_none = [&]() {            // keeps the count of operations per slab
+    if constexpr (PF > 0)
+      asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tbuffer_load_dword %1, %2, 0 offen lds" :: "s"(pf_lds), "v"(kOob), "s"(pf_rsrc) : "m0");
+  };
 #pragma unroll
   for (int p = 0; p < NS; ++p) {
     if (p > 0) { TA::advance(offa, a_step); TB::advance(offb, b_step); }
     TA::load_slab_untracked(ra_rsrc, offa, (kb0 + p) * BK, a.K, smem + p * STAGE);
     TB::load_slab_untracked(rb_rsrc, offb, (kb0 + p) * BK, a.K, smem + p * STAGE + TA::BYTES);
+    if (p < PF) prefetch_next(); else prefetch_none();
   }
-  __builtin_amdgcn_s_waitcnt(vmcnt_only((NS - 1) * LOADS));
+  __builtin_amdgcn_s_waitcnt(vmcnt_only((NS - 1) * PER_SLAB + LAST));
   __syncthreads();
 
   bf16x8 fa[2][MI], fb[NI];
@@ -381,7 +438,7 @@ __global__ void __launch_bounds__(64 * WGM * WGN) gemm_mfma_kernel(GemmArgs<bf16
     for (int j = 0; j < JB; ++j)
 #pragma unroll
       for (int i = 0; i < MI; ++i) acc[i][j] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(fb[j], fa[1][i], acc[i][j], 0, 0, 0);
-    __builtin_amdgcn_s_waitcnt(vmcnt_only((NS - 2) * LOADS) & 0xF0FF);     // ... and lgkmcnt(0)
+    __builtin_amdgcn_s_waitcnt(vmcnt_only((NS - 2) * PER_SLAB + LAST) & 0xF0FF);     // ... and lgkmcnt(0)
     __syncthreads();
     __builtin_amdgcn_s_setprio(2);
     TA::advance(offa, a_step);
@@ -407,6 +464,7 @@ __global__ void __launch_bounds__(64 * WGM * WGN) gemm_mfma_kernel(GemmArgs<bf16
       __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
       for (int q = 0; q < LPS; ++q) issue_load(slot * LPS + q);
+      if (j == NI - 1) prefetch_next();
       __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
       for (int e = 0; e < EPS; ++e) early_read(slot * EPS + e);
@@ -503,11 +561,14 @@ int launch_kernel(const GemmArgs<bf16>& a, int BMv, int BNv, int threads, size_t
 
 template <int BM, int BN, int WGM, int WGN, bool AK, bool BKF, int EPI, int NS = 2>
 int launch_cfg(const GemmArgs<bf16>& a, hipStream_t s) {
-  constexpr size_t stages = (size_t)NS * (BM + BN) * BK * 2;
+  // The L2 prefetch pays where both operands are read token-major (the weight gradients: +3..5 % on c5's shapes); the
+  // k-contiguous kernels lose 1..6 % with it, so they run without.
+  constexpr int PF = (!AK && !BKF) ? 2 : 0;
+  constexpr size_t stages = (size_t)NS * (BM + BN) * BK * 2 + (PF > 0 ? 256 : 0);    // + the prefetches' scratch line
   constexpr size_t staging = (size_t)WGM * WGN * 32 * (BN / WGN + 4) * 4;
   static_assert(stages <= 160 * 1024, "the stages must fit in LDS");
   const size_t lds = std::max<size_t>(stages, EPI == EPI_GRAD ? 0 : staging);
-  return launch_kernel<gemm_mfma_kernel<BM, BN, WGM, WGN, AK, BKF, EPI, NS>>(a, BM, BN, 64 * WGM * WGN, lds, s);
+  return launch_kernel<gemm_mfma_kernel<BM, BN, WGM, WGN, AK, BKF, EPI, NS, PF>>(a, BM, BN, 64 * WGM * WGN, lds, s);
 }
 
 thread_local int side_by_side = 1;     // kernels the caller runs at once (GemmSideBySide)
