@@ -35,6 +35,12 @@ constexpr float kLn2 = 0.69314718055994530942f;
 __device__ __forceinline__ __amdgpu_buffer_rsrc_t make_rsrc(const void* p, unsigned bytes) {
   return __builtin_amdgcn_make_buffer_rsrc(const_cast<void*>(p), 0, bytes, 0x00020000);
 }
+// the same descriptor as four words (base, base high half with stride 0, extent, flags), for inline assembly
+typedef int i32x4 __attribute__((ext_vector_type(4)));
+__device__ __forceinline__ i32x4 make_rsrc_words(const void* p, unsigned bytes) {
+  const uint64_t addr = (uint64_t)(uintptr_t)p;
+  return i32x4{(int)(unsigned)addr, (int)(unsigned)((addr >> 32) & 0xffffu), (int)bytes, 0x00020000};
+}
 
 // ROWS tokens by D values of one operand in LDS, staged by THREADS threads (through registers, or straight from
 // global memory).
@@ -74,20 +80,27 @@ template <int D, int ROWS = TILE, int THREADS = kThreads> struct Tile {
   // The loads are asynchronous: wait for vmcnt(0) and a workgroup barrier before reading the tile.
   static constexpr int NW = THREADS / 64, LOADS = ROWS / 4, PER_WAVE = LOADS / NW;
   // the part of the offset that belongs to the lane (the same for every tile: the compiler keeps it out of the loops)
-  __device__ static unsigned stage_lane(int j, unsigned ld_bytes, int d) {
-    const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6), lane = threadIdx.x & 63;
+  // (wave: this wavefront's place among the THREADS / 64 that stage the tile; by default its place in the block)
+  __device__ static unsigned stage_lane(int j, unsigned ld_bytes, int d, int wave = -1) {
+    if (wave < 0) wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+    const int lane = threadIdx.x & 63;
     const int row = (wave * PER_WAVE + j) * 4 + (lane >> 4);
     const int c = (lane & 15) ^ swz(row);
     return c * 8 < d ? (unsigned)row * ld_bytes + (unsigned)c * 16 : 0x80000000u;
   }
-  __device__ static void stage(__amdgpu_buffer_rsrc_t rsrc, unsigned col_bytes, unsigned ld_bytes, int row0, lds_bf16* lds, int d) {
-    static_assert(DIRECT && LOADS % NW == 0, "rows of 256 bytes, loads split evenly over the wavefronts");
+  // The loads are issued behind the compiler's back: it tracks loads that write LDS, cannot tell one buffer from
+  // another, and makes later LDS reads of the tile being multiplied wait for them (the whole memory latency, every
+  // tile).  Callers wait (vmcnt(0)) and synchronise before they read what was staged.
+  __device__ static void stage_one(i32x4 rsrc, int j, unsigned tile_bytes, unsigned ld_bytes, lds_bf16* lds, int d) {
     const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
-    const unsigned tile = (unsigned)row0 * ld_bytes + col_bytes;
+    const unsigned dst = (unsigned)(uintptr_t)(lds + (wave * PER_WAVE + j) * 4 * LD);
+    const unsigned off = stage_lane(j, ld_bytes, d) + tile_bytes;
+    asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tbuffer_load_dwordx4 %1, %2, 0 offen lds" :: "s"(dst), "v"(off), "s"(rsrc) : "m0");
+  }
+  __device__ static void stage(i32x4 rsrc, unsigned col_bytes, unsigned ld_bytes, int row0, lds_bf16* lds, int d) {
+    static_assert(DIRECT && LOADS % NW == 0, "rows of 256 bytes, loads split evenly over the wavefronts");
 #pragma unroll
-    for (int j = 0; j < PER_WAVE; ++j)
-      __builtin_amdgcn_raw_ptr_buffer_load_lds(rsrc, (LDS_AS void*)(lds + (wave * PER_WAVE + j) * 4 * LD), 16,
-                                               stage_lane(j, ld_bytes, d) + tile, 0, 0, 0);
+    for (int j = 0; j < PER_WAVE; ++j) stage_one(rsrc, j, (unsigned)row0 * ld_bytes + col_bytes, ld_bytes, lds, d);
   }
   __device__ static void store_lds(lds_bf16* lds, const bf16x8 (&reg)[PER_THREAD]) {
 #pragma unroll
@@ -390,7 +403,7 @@ attn_fwd8_kernel(const bf16* __restrict__ qkv, bf16* __restrict__ O, float* __re
   const int qsub = wave & 3, kh = wave >> 2;        // block of 32 queries, half of the staged keys
   const int64_t ld = 3 * (int64_t)H;
   const bf16* base = qkv + (int64_t)n * S * ld + a * d;
-  const __amdgpu_buffer_rsrc_t rs_qkv = make_rsrc(qkv + (int64_t)n * S * ld, (unsigned)(S * ld * 2));
+  const i32x4 rs_qkv = make_rsrc_words(qkv + (int64_t)n * S * ld, (unsigned)(S * ld * 2));
   const unsigned k_bytes = (unsigned)((H + a * d) * 2), v_bytes = (unsigned)((2 * H + a * d) * 2);
   const float c2 = scale * kLog2e;
   const int ntq = (S + 127) / 128;                  // causal: query tile x, then its mirror tile (equal work per block)
@@ -588,8 +601,6 @@ __device__ __forceinline__ void turn_products(const lds_bf16* Vt, const lds_bf16
 // wanted one tile later than K now) into the buffers that K_{k-1} and V_{k-2} left at the end of phase 2k-1: group 0
 // issues the loads between the products of its step 2k and waits for them at the end of phase 2k+1.  The staging
 // loads are issued behind the compiler's back (it would make the next transposing LDS read wait for them).
-typedef int i32x4 __attribute__((ext_vector_type(4)));
-
 template <int D, bool CAUSAL>
 __global__ void __launch_bounds__(kThreads8)
 attn_fwd_turns_kernel(const bf16* __restrict__ qkv, bf16* __restrict__ O, float* __restrict__ lse, int S, int H, int A, float scale) {
@@ -610,8 +621,7 @@ attn_fwd_turns_kernel(const bf16* __restrict__ qkv, bf16* __restrict__ O, float*
   const bf16* base = qkv + (int64_t)n * S * ld + a * d;
   const unsigned ld_bytes = (unsigned)ld * 2;
   const unsigned k_bytes = (unsigned)((H + a * d) * 2), v_bytes = (unsigned)((2 * H + a * d) * 2);
-  const uint64_t addr = (uint64_t)(uintptr_t)(qkv + (int64_t)n * S * ld);
-  const i32x4 rsrc = {(int)(unsigned)addr, (int)(unsigned)((addr >> 32) & 0xffffu), (int)(unsigned)(S * ld * 2), 0x00020000};
+  const i32x4 rsrc = make_rsrc_words(qkv + (int64_t)n * S * ld, (unsigned)(S * ld * 2));
   // Staging is group 0's job (its four wavefronts split a tile's 32 load instructions: 8 each per operand), dealt out
   // between the products of its matrix-core step.  Load q of a tile pair: q < 8 the keys, else the values.
   typedef Tile<D, 128, 256> TS;
@@ -847,7 +857,7 @@ attn_dq_kernel(const bf16* __restrict__ qkv, const bf16* __restrict__ dO, const 
   const int qsub = wave & 3, kh = wave >> 2;        // block of 32 queries, half of the staged keys
   const int64_t ld = 3 * (int64_t)H;
   const bf16* base = qkv + (int64_t)n * S * ld + a * d;
-  const __amdgpu_buffer_rsrc_t rs_qkv = make_rsrc(qkv + (int64_t)n * S * ld, (unsigned)(S * ld * 2));
+  const i32x4 rs_qkv = make_rsrc_words(qkv + (int64_t)n * S * ld, (unsigned)(S * ld * 2));
   const unsigned k_bytes = (unsigned)((H + a * d) * 2), v_bytes = (unsigned)((2 * H + a * d) * 2);
   const float c2 = scale * kLog2e;
   const int ntq = (S + 127) / 128;                 // causal: query tiles x and ntq-1-x in turn (equal work per block)
@@ -1000,8 +1010,8 @@ attn_dkv_kernel(const bf16* __restrict__ qkv, const bf16* __restrict__ dO, const
   const int64_t ld = 3 * (int64_t)H;
   const bf16* base = qkv + (int64_t)n * S * ld + a * d;
   const bf16* dObase = dO + (int64_t)n * S * H + a * d;
-  const __amdgpu_buffer_rsrc_t rs_qkv = make_rsrc(qkv + (int64_t)n * S * ld, (unsigned)(S * ld * 2));
-  const __amdgpu_buffer_rsrc_t rs_do = make_rsrc(dO + (int64_t)n * S * H, (unsigned)((int64_t)S * H * 2));
+  const i32x4 rs_qkv = make_rsrc_words(qkv + (int64_t)n * S * ld, (unsigned)(S * ld * 2));
+  const i32x4 rs_do = make_rsrc_words(dO + (int64_t)n * S * H, (unsigned)((int64_t)S * H * 2));
   const unsigned col_bytes = (unsigned)(a * d * 2);
   const float* lse_base = lse + ((int64_t)n * A + a) * S;
   const float* dv_base = dvec + ((int64_t)n * A + a) * S;
