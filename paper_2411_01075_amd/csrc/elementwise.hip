@@ -1,6 +1,7 @@
 // LayerNorm forward/backward and column sums (bias gradients): HBM-bound row kernels.
-// One 64-lane wavefront owns a row; its lanes hold the row in registers as 16-byte
+// Forward: one 64-lane wavefront owns a row; its lanes hold the row in registers as 16-byte
 // vectors, and row statistics are wavefront reductions (no LDS, no block barrier).
+// Backward: a block of four wavefronts shares each row (see ln_bwd_kernel).
 // The residual stream (x, x1, y and their gradients) and the gradients entering LayerNorm's
 // backward are fp32; LayerNorm outputs are in the activation type T.
 #include "kernels.h"
@@ -88,95 +89,151 @@ ln_fwd_kernel(const float* __restrict__ x, const T* __restrict__ gamma, const T*
   }
 }
 
-constexpr int kLnBwdRowsPerBlock = 8;   // 2 rows per wavefront: two blocks (8 wavefronts) per compute unit at 4096 rows keep more loads in flight
+constexpr int kLnBwdRowsPerBlock = 8;
 
 // out = resid + rstd * (g - mean(g) - xhat * mean(g*xhat)),  g = du * gamma
 // part_g[blk][h] = sum over the block's rows of du*xhat, part_b[blk][h] = sum of du
 // RMS: backward of the root-mean-square norm, out = resid + rstd * (g - xhat * mean(g*xhat)) with xhat = x * rstd
 // (part_b is still written, and not used).
-template <typename T, int MAXV, bool RMS>
+//
+// A block of four wavefronts works on its 8 rows together, two rows at a time: a thread owns the same MV 16-byte
+// column groups of every row, so the column sums of the parameter gradients stay in its registers from the first row to
+// the last (no reduction across wavefronts at the end) and a row costs it 3 x MV vectors.  With so few registers per
+// row the loads of the next two rows are in flight while these two are reduced and written.  (One wavefront per row,
+// the row in registers, needed 234 registers at H = 2048 and left two wavefronts per SIMD taking turns between a burst
+// of loads and a burst of stores: 0.50-0.57 of the memory's rate.)  The two row sums go through LDS: one barrier per
+// pair of rows, the slots alternate so that a second one is not needed.
+template <typename T, int MV, bool RMS>
 __global__ void __launch_bounds__(kThreads)
 ln_bwd_kernel(const float* __restrict__ du, const float* __restrict__ x, const float* __restrict__ mean,
               const float* __restrict__ rstd, const T* __restrict__ gamma, const float* __restrict__ resid,
               float* __restrict__ out, T* __restrict__ out_lowp, float* __restrict__ part_g, float* __restrict__ part_b,
               int rows, int H) {
   constexpr int VN = Vec<T>::N;
-  __shared__ float red[2][kWaves][64 * VN];
+  constexpr int R = 2;                                   // rows per step
+  constexpr int STEPS = kLnBwdRowsPerBlock / R;
+  constexpr bool AHEAD = MV <= 2;                        // wide rows: no room for the next step's rows
+  __shared__ float red[2][R][2][kWaves];
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
   const int nv = H / VN;
   const float inv_h = 1.0f / (float)H;
-  float dg[MAXV][VN], db[MAXV][VN];
+  const int row0 = blockIdx.x * kLnBwdRowsPerBlock;
+
+  float gm[MV][VN], dg[MV][VN], db[MV][VN];
 #pragma unroll
-  for (int j = 0; j < MAXV; ++j)
+  for (int j = 0; j < MV; ++j) {
+    const int v = threadIdx.x + kThreads * j;
+    if (v < nv) {
+      load_vec<T>(gamma + v * VN, gm[j]);
+    } else {
+#pragma unroll
+      for (int i = 0; i < VN; ++i) gm[j][i] = 0.f;
+    }
 #pragma unroll
     for (int i = 0; i < VN; ++i) { dg[j][i] = 0.f; db[j][i] = 0.f; }
+  }
 
-  const int row0 = blockIdx.x * kLnBwdRowsPerBlock;
-  for (int r = wave; r < kLnBwdRowsPerBlock; r += kWaves) {
-    const int row = row0 + r;
-    if (row >= rows) break;
-    const float mu = RMS ? 0.f : mean[row], rs = rstd[row];
-    float g[MAXV][VN], xh[MAXV][VN], rr[MAXV][VN];
-    float s1 = 0.f, s2 = 0.f;
+  struct Rows { float d[R][MV][VN], xv[R][MV][VN], rr[R][MV][VN]; };
+  auto fetch = [&](Rows& b, int step) {
 #pragma unroll
-    for (int j = 0; j < MAXV; ++j) {
-      const int v = lane + 64 * j;
-      if (v < nv) {
-        float d[VN], xv[VN], gm[VN];
-        load_f32<VN>(du + (int64_t)row * H + v * VN, d);
-        load_f32<VN>(x + (int64_t)row * H + v * VN, xv);
-        load_vec<T>(gamma + v * VN, gm);
-        if (resid) {      // asked for together with the row: its latency is not paid a second time after the reduction
-          load_f32<VN>(resid + (int64_t)row * H + v * VN, rr[j]);
-        } else {
+    for (int r = 0; r < R; ++r) {
+      const int row = row0 + step * R + r;
 #pragma unroll
-          for (int i = 0; i < VN; ++i) rr[j][i] = 0.f;
+      for (int j = 0; j < MV; ++j) {
+        const int v = threadIdx.x + kThreads * j;
+        if (row < rows && v < nv) {
+          const int64_t o = (int64_t)row * H + v * VN;
+          load_f32<VN>(du + o, b.d[r][j]);
+          load_f32<VN>(x + o, b.xv[r][j]);
+          if (resid) {
+            load_f32<VN>(resid + o, b.rr[r][j]);
+          } else {
+#pragma unroll
+            for (int i = 0; i < VN; ++i) b.rr[r][j][i] = 0.f;
+          }
+        } else {       // past the last row or the row's end: contributes nothing, is not stored
+#pragma unroll
+          for (int i = 0; i < VN; ++i) { b.d[r][j][i] = 0.f; b.xv[r][j][i] = 0.f; b.rr[r][j][i] = 0.f; }
         }
+      }
+    }
+  };
+  auto reduce_and_store = [&](Rows& b, int step) {
+    float rs[R];
+#pragma unroll
+    for (int r = 0; r < R; ++r) {
+      const int row = min(row0 + step * R + r, rows - 1);
+      const float mu = RMS ? 0.f : mean[row];
+      rs[r] = rstd[row];
+      float s1 = 0.f, s2 = 0.f;
+#pragma unroll
+      for (int j = 0; j < MV; ++j)
 #pragma unroll
         for (int i = 0; i < VN; ++i) {
-          xh[j][i] = (xv[i] - mu) * rs;
-          g[j][i] = d[i] * gm[i];
-          s1 += g[j][i];
-          s2 += g[j][i] * xh[j][i];
-          dg[j][i] += d[i] * xh[j][i];
-          db[j][i] += d[i];
+          const float d = b.d[r][j][i];
+          const float xh = (b.xv[r][j][i] - mu) * rs[r];
+          const float g = d * gm[j][i];
+          s1 += g;
+          s2 += g * xh;
+          dg[j][i] += d * xh;
+          db[j][i] += d;
+          b.xv[r][j][i] = xh;
+          b.d[r][j][i] = g;
+        }
+      s1 = wave_sum(s1);
+      s2 = wave_sum(s2);
+      if (lane == 0) { red[step & 1][r][0][wave] = s1; red[step & 1][r][1][wave] = s2; }
+    }
+    __syncthreads();
+#pragma unroll
+    for (int r = 0; r < R; ++r) {
+      const int row = row0 + step * R + r;
+      float c1 = 0.f, c2 = 0.f;
+#pragma unroll
+      for (int w = 0; w < kWaves; ++w) { c1 += red[step & 1][r][0][w]; c2 += red[step & 1][r][1][w]; }
+      c1 = RMS ? 0.f : c1 * inv_h;
+      c2 *= inv_h;
+      if (row < rows) {
+#pragma unroll
+        for (int j = 0; j < MV; ++j) {
+          const int v = threadIdx.x + kThreads * j;
+          if (v < nv) {
+            float o[VN];
+#pragma unroll
+            for (int i = 0; i < VN; ++i) o[i] = b.rr[r][j][i] + rs[r] * (b.d[r][j][i] - c1 - b.xv[r][j][i] * c2);
+            store_f32<VN>(out + (int64_t)row * H + v * VN, o);
+            if (out_lowp) store_vec<T>(out_lowp + (int64_t)row * H + v * VN, o);
+          }
         }
       }
     }
-    const float c1 = RMS ? 0.f : wave_sum(s1) * inv_h, c2 = wave_sum(s2) * inv_h;
+  };
+  if constexpr (AHEAD) {
+    Rows b0, b1;
+    fetch(b0, 0);
 #pragma unroll
-    for (int j = 0; j < MAXV; ++j) {
-      const int v = lane + 64 * j;
-      if (v < nv) {
-        float o[VN];
-#pragma unroll
-        for (int i = 0; i < VN; ++i) o[i] = rr[j][i] + rs * (g[j][i] - c1 - xh[j][i] * c2);
-        store_f32<VN>(out + (int64_t)row * H + v * VN, o);
-        if (out_lowp) store_vec<T>(out_lowp + (int64_t)row * H + v * VN, o);
-      }
+    for (int step = 0; step < STEPS; step += 2) {
+      fetch(b1, step + 1);
+      reduce_and_store(b0, step);
+      if (step + 2 < STEPS) fetch(b0, step + 2);
+      reduce_and_store(b1, step + 1);
+    }
+  } else {
+    Rows b0;
+#pragma unroll 1
+    for (int step = 0; step < STEPS; ++step) {
+      fetch(b0, step);
+      reduce_and_store(b0, step);
     }
   }
-  // cross-wavefront sum of the column partials, one 64*VN-column slab at a time
   float* pg = part_g + (int64_t)blockIdx.x * H;
   float* pb = part_b + (int64_t)blockIdx.x * H;
 #pragma unroll
-  for (int j = 0; j < MAXV; ++j) {
-    __syncthreads();
-#pragma unroll
-    for (int i = 0; i < VN; ++i) {
-      red[0][wave][lane * VN + i] = dg[j][i];
-      red[1][wave][lane * VN + i] = db[j][i];
-    }
-    __syncthreads();
-    for (int c = threadIdx.x; c < 64 * VN; c += kThreads) {
-      const int col = j * 64 * VN + c;
-      if (col < H) {
-        float a = 0.f, b = 0.f;
-#pragma unroll
-        for (int w = 0; w < kWaves; ++w) { a += red[0][w][c]; b += red[1][w][c]; }
-        pg[col] = a;
-        pb[col] = b;
-      }
+  for (int j = 0; j < MV; ++j) {
+    const int v = threadIdx.x + kThreads * j;
+    if (v < nv) {
+      store_f32<VN>(pg + v * VN, dg[j]);
+      store_f32<VN>(pb + v * VN, db[j]);
     }
   }
 }
@@ -302,13 +359,16 @@ template <typename T>
 int launch_ln_bwd(const float* du, const float* x, const float* mean, const float* rstd, const T* gamma,
                   const float* resid, float* out, T* out_lowp, float* part_g, float* part_b, int rows, int H, hipStream_t s, bool rms) {
   const int nblocks = ln_bwd_blocks(rows);
+  const int nv = H / Vec<T>::N;
+  int mv = 1;
+  while (mv * kThreads < nv) mv *= 2;          // 16-byte column groups per thread
 #define LN_BWD_CASE(MV)                                                                                               \
   case MV:                                                                                                            \
     if (rms) ln_bwd_kernel<T, MV, true><<<nblocks, kThreads, 0, s>>>(du, x, mean, rstd, gamma, resid, out, out_lowp, part_g, part_b, rows, H); \
     else ln_bwd_kernel<T, MV, false><<<nblocks, kThreads, 0, s>>>(du, x, mean, rstd, gamma, resid, out, out_lowp, part_g, part_b, rows, H); \
     break;
-  switch (maxv_for<T>(H)) {
-    LN_BWD_CASE(1) LN_BWD_CASE(2) LN_BWD_CASE(4) LN_BWD_CASE(8) LN_BWD_CASE(16)
+  switch (mv) {
+    LN_BWD_CASE(1) LN_BWD_CASE(2) LN_BWD_CASE(4)
     default: return fail(CEPHALO_EUNSUPPORTED, "layer norm: hidden width %d too large", H);
   }
 #undef LN_BWD_CASE
