@@ -408,7 +408,7 @@ def main():
             lr_ = torch.empty(T, device="cuda")
             t_ce = timed(lambda: C.cephalo_op_cross_entropy(C.BF16, lg, ldv, tg, dl_, lr_, T, V, 1.0 / n_tok), 30)
             # two passes over the fp32 logits of a micro-batch, one write of their bf16 gradient
-            extras["elementwise"]["cross_entropy"] = gbs(T * ldv * (4 + 4 + 2), t_ce)
+            extras["elementwise"]["cross_entropy"] = gbs(T * ldv * (4 + 2), t_ce)      # fp32 logits read once (the row stays in registers), bf16 gradient written
             del lg, dl_
 
     # ---- what this device sustains (probes of the library): a register-only stream of the GEMM's matrix instruction on

@@ -90,6 +90,85 @@ cross_entropy_kernel(const float* __restrict__ logits, T* __restrict__ dlogits, 
   }
 }
 
+// The same with the row held in registers: a block of 1024 threads reads its row once (thread t keeps groups t,
+// t + 1024, ... of 16 bytes of output each), so the logits cross the memory bus once instead of twice.  Rows of up to
+// 1024 * MAXG groups; wider ones take the two-pass kernel above.
+constexpr int kCeThreads = 1024;
+template <typename T, int MAXG>
+__global__ void __launch_bounds__(kCeThreads)
+cross_entropy_row_kernel(const float* __restrict__ logits, T* __restrict__ dlogits, const int* __restrict__ targets,
+                         float* __restrict__ loss, int V, int ld, float coef) {
+  typedef float f32x4 __attribute__((ext_vector_type(4)));
+  constexpr int VN = Vec<T>::N, NW = kCeThreads / 64;
+  __shared__ float red[2][NW];
+  const float* row = logits + (int64_t)blockIdx.x * ld;
+  T* drow = dlogits + (int64_t)blockIdx.x * ld;
+  const int ng = ld / VN;
+  const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
+  float a[MAXG][VN];
+  float mx = -INFINITY;
+#pragma unroll
+  for (int j = 0; j < MAXG; ++j) {
+    const int g = threadIdx.x + kCeThreads * j;
+    if (g < ng) {
+#pragma unroll
+      for (int q = 0; q < VN / 4; ++q) {
+        const f32x4 r = *reinterpret_cast<const f32x4*>(row + g * VN + 4 * q);
+#pragma unroll
+        for (int i = 0; i < 4; ++i) a[j][4 * q + i] = r[i];
+      }
+#pragma unroll
+      for (int i = 0; i < VN; ++i) if (g * VN + i < V) mx = fmaxf(mx, a[j][i]);
+    }
+  }
+  mx = wave_max(mx);
+  if (lane == 0) red[0][wave] = mx;
+  __syncthreads();
+  float bmx = red[0][0];
+#pragma unroll
+  for (int w = 1; w < NW; ++w) bmx = fmaxf(bmx, red[0][w]);
+  float sum = 0.f;
+#pragma unroll
+  for (int j = 0; j < MAXG; ++j) {
+    const int g = threadIdx.x + kCeThreads * j;
+    if (g < ng) {
+#pragma unroll
+      for (int i = 0; i < VN; ++i) if (g * VN + i < V) sum += __expf(a[j][i] - bmx);
+    }
+  }
+  sum = wave_sum(sum);
+  if (lane == 0) red[1][wave] = sum;
+  __syncthreads();
+  float bsum = 0.f;
+#pragma unroll
+  for (int w = 0; w < NW; ++w) bsum += red[1][w];
+  const float lse = bmx + __logf(bsum);
+  const int tgt = clamp_id(targets[blockIdx.x], V);
+  if (threadIdx.x == 0) loss[blockIdx.x] = lse - row[tgt];
+#pragma unroll
+  for (int j = 0; j < MAXG; ++j) {
+    const int g = threadIdx.x + kCeThreads * j;
+    if (g < ng) {
+      float o[VN];
+#pragma unroll
+      for (int i = 0; i < VN; ++i) {
+        const int c = g * VN + i;
+        o[i] = c < V ? coef * (__expf(a[j][i] - lse) - (c == tgt ? 1.f : 0.f)) : 0.f;
+      }
+      store_vec<T>(drow + g * VN, o);
+    }
+  }
+}
+
+template <typename T>
+void launch_cross_entropy(const float* logits, T* dlogits, const int* targets, float* loss, int rows, int V, int ld, float coef, hipStream_t s) {
+  const int per_thread = (ld / Vec<T>::N + kCeThreads - 1) / kCeThreads;
+  if (per_thread <= 4) cross_entropy_row_kernel<T, 4><<<rows, kCeThreads, 0, s>>>(logits, dlogits, targets, loss, V, ld, coef);
+  else if (per_thread <= 8) cross_entropy_row_kernel<T, 8><<<rows, kCeThreads, 0, s>>>(logits, dlogits, targets, loss, V, ld, coef);
+  else if (per_thread <= 16) cross_entropy_row_kernel<T, 16><<<rows, kCeThreads, 0, s>>>(logits, dlogits, targets, loss, V, ld, coef);
+  else cross_entropy_kernel<T><<<rows, kThreads, 0, s>>>(logits, dlogits, targets, loss, V, ld, coef);
+}
+
 // out[0] = (1/n) * sum loss[0..n), one block, fixed order
 __global__ void __launch_bounds__(kThreads) mean_kernel(const float* __restrict__ loss, int n, float* __restrict__ out) {
   __shared__ float red[4];
@@ -533,7 +612,7 @@ int run_stack(const cephalo_stack_desc& d, const void* Pv, const int* ids, const
       a.epi = EPI_NONE_HEAD; a.Cf = logits_j; a.ldc = L.ldv;
       TRY(gemm<T>(a, sj));
     }
-    cross_entropy_kernel<T><<<Tm, kThreads, 0, sj>>>(logits_j, dlg, targets + t0, at<float>(ws, L.loss) + t0, V, L.ldv, coef);
+    launch_cross_entropy<T>(logits_j, dlg, targets + t0, at<float>(ws, L.loss) + t0, Tm, V, L.ldv, coef, sj);
     CEPHALO_CHECK_LAUNCH("cross_entropy");
     {
       GemmArgs<T> a = head_dgrad_args<T>(dlg, P + o_head, at<T>(ws, L.wteT), Tm, V, H, L.ldv);   // duf = dlogits W_head
@@ -657,8 +736,8 @@ extern "C" int cephalo_op_cross_entropy(int32_t dtype, const float* logits, int3
   if (!logits || !targets || !dlogits || !loss_rows) return fail(CEPHALO_EINVAL, "cross_entropy: null buffer");
   if (!aligned16(logits) || !aligned16(dlogits)) return fail(CEPHALO_EINVAL, "cross_entropy: buffers must be 16-byte aligned");
   hipStream_t s = static_cast<hipStream_t>(stream);
-  if (dtype == CEPHALO_F32) cross_entropy_kernel<float><<<rows, kThreads, 0, s>>>(logits, static_cast<float*>(dlogits), targets, loss_rows, V, ld, coef);
-  else cross_entropy_kernel<bf16><<<rows, kThreads, 0, s>>>(logits, static_cast<bf16*>(dlogits), targets, loss_rows, V, ld, coef);
+  if (dtype == CEPHALO_F32) launch_cross_entropy<float>(logits, static_cast<float*>(dlogits), targets, loss_rows, rows, V, ld, coef, s);
+  else launch_cross_entropy<bf16>(logits, static_cast<bf16*>(dlogits), targets, loss_rows, rows, V, ld, coef, s);
   CEPHALO_CHECK_LAUNCH("cross_entropy");
   return CEPHALO_OK;
 }
