@@ -25,6 +25,11 @@ CASES = [  # bf16?, m, S, heads, head dim, causal
     (True, 1, 150, 5, 8, True),
     (True, 1, 260, 2, 96, False),
     (True, 1, 130, 3, 40, False),
+    # the 128-wide causal forward (two wavefront groups in turns): a single tile, an even tile count, a narrow head on the wide tile
+    (True, 1, 100, 2, 128, True),
+    (True, 2, 256, 2, 128, True),
+    (True, 1, 300, 2, 72, True),
+    (True, 1, 640, 1, 128, True),
     (False, 2, 70, 3, 24, True),
     (False, 1, 128, 2, 64, False),
 ]
