@@ -396,7 +396,7 @@ __global__ void __launch_bounds__(64 * WGM * WGN) gemm_mfma_kernel(GemmArgs<bf16
 #pragma unroll
   for (int j = 0; j < NI; ++j) fb[j] = frag_b(smem + TA::BYTES, j, 0);
 
-  constexpr int JB = NI >= 4 ? 2 : 1;                      // column blocks of k-step 1 multiplied before the barrier
+  constexpr int JB = 1;                                    // column blocks of k-step 1 multiplied before the barrier
   int st = 0;
   for (int kt = 0; kt < nk; ++kt) {
     const int st1 = st + 1 == NS ? 0 : st + 1;
@@ -445,9 +445,11 @@ __global__ void __launch_bounds__(64 * WGM * WGN) gemm_mfma_kernel(GemmArgs<bf16
     TB::advance(offb, b_step);
     // From here on the order is pinned: after every column block's products (and the refill of its fragment) come a
     // share of the slab's global loads and one or two of the early fragment reads of slab kt+1.  (The loads are
-    // opaque assembly, which the scheduler otherwise bunches together and strands the products behind them.)
+    // opaque assembly, which the scheduler otherwise bunches together and strands the products behind them.)  The
+    // loads are dealt evenly over all the blocks left in the slab, and only one block is multiplied before the barrier:
+    // a load instruction keeps the address unit busy for 16 cycles, the 64 of a slab issued within four blocks by all
+    // eight wavefronts saturate it and the wavefronts queue at issue (evenly over seven blocks: +2 %).
     constexpr int SLOTS = NI - JB;
-    constexpr int LPS = (LOADS + SLOTS - 1) / SLOTS;      // loads per slot
     constexpr int EARLY = MI + JB;                         // fragments wanted at the start of the next slab
     constexpr int EPS = (EARLY + SLOTS - 1) / SLOTS;       // early fragments per slot
     auto issue_load = [&](int q) {
@@ -463,7 +465,7 @@ __global__ void __launch_bounds__(64 * WGM * WGN) gemm_mfma_kernel(GemmArgs<bf16
       const int slot = j - JB;
       __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
-      for (int q = 0; q < LPS; ++q) issue_load(slot * LPS + q);
+      for (int q = slot * LOADS / SLOTS; q < (slot + 1) * LOADS / SLOTS; ++q) issue_load(q);
       if (j == NI - 1) prefetch_next();
       __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
