@@ -238,7 +238,13 @@ constexpr int vmcnt_only(int n) { return 0x0F70 | (n & 15) | ((n >> 4) << 14); }
 // beyond the one being loaded: a 4-byte direct-to-LDS load per wavefront and slab into a scratch line of LDS that
 // nothing reads (a load without a register result, so nothing can be clobbered when it lands).  The loads proper then
 // hit L2.  The prefetch is last in issue order, so the waits leave one more operation outstanding.
-template <int BM, int BN, int WGM, int WGN, bool AK, bool BKF, int EPI, int NS, int PF>
+//
+// Three A buffers, two B buffers (A3; NS = 2, no prefetch).  With two whole stages every load of a slab has to be issued
+// between the mid-slab barrier (its stage falls free there) and the end of the slab, and the address unit, 16 cycles per
+// load, is saturated in that window while it idles in the other half.  A third buffer for A alone still fits (5 x 32 KB
+// at 256 x 256): the A tile of slab kt+2 goes into the buffer that slab kt-1 left at the previous barrier and is loaded
+// during k-step 0 of slab kt, with a whole slab to land; only the B tile is loaded after the barrier.
+template <int BM, int BN, int WGM, int WGN, bool AK, bool BKF, int EPI, int NS, int PF, bool A3 = false>
 __global__ void __launch_bounds__(64 * WGM * WGN) gemm_mfma_kernel(GemmArgs<bf16> a, int tiles_m, int tiles_n, int slabs_per_split) {
   constexpr int NW = WGM * WGN;
   typedef OperandTile<BM, AK, NW> TA;
@@ -380,11 +386,15 @@ __global__ void __launch_bounds__(64 * WGM * WGN) gemm_mfma_kernel(GemmArgs<bf16
     if constexpr (PF > 0)
       asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tbuffer_load_dword %1, %2, 0 offen lds" :: "s"(pf_lds), "v"(kOob), "s"(pf_rsrc) : "m0");
   };
+  static_assert(!A3 || (NS == 2 && PF == 0), "the third A buffer goes with two B buffers and no prefetch");
+  // where slab k's tiles live: whole stages [A | B] one after the other, or (A3) three A buffers and then two B buffers
+  auto a_tile = [&](int stage3, int stage) { return A3 ? smem + stage3 * TA::BYTES : smem + stage * STAGE; };
+  auto b_tile = [&](int stage) { return A3 ? smem + 3 * TA::BYTES + stage * TB::BYTES : smem + stage * STAGE + TA::BYTES; };
 #pragma unroll
   for (int p = 0; p < NS; ++p) {
     if (p > 0) { TA::advance(offa, a_step); TB::advance(offb, b_step); }
-    TA::load_slab_untracked(ra_rsrc, offa, (kb0 + p) * BK, a.K, smem + p * STAGE);
-    TB::load_slab_untracked(rb_rsrc, offb, (kb0 + p) * BK, a.K, smem + p * STAGE + TA::BYTES);
+    TA::load_slab_untracked(ra_rsrc, offa, (kb0 + p) * BK, a.K, a_tile(p, p));
+    TB::load_slab_untracked(rb_rsrc, offb, (kb0 + p) * BK, a.K, b_tile(p));
     if (p < PF) prefetch_next(); else prefetch_none();
   }
   __builtin_amdgcn_s_waitcnt(vmcnt_only((NS - 1) * PER_SLAB + LAST));
@@ -392,18 +402,19 @@ __global__ void __launch_bounds__(64 * WGM * WGN) gemm_mfma_kernel(GemmArgs<bf16
 
   bf16x8 fa[2][MI], fb[NI];
 #pragma unroll
-  for (int i = 0; i < MI; ++i) fa[0][i] = frag_a(smem, i, 0);
+  for (int i = 0; i < MI; ++i) fa[0][i] = frag_a(a_tile(0, 0), i, 0);
 #pragma unroll
-  for (int j = 0; j < NI; ++j) fb[j] = frag_b(smem + TA::BYTES, j, 0);
+  for (int j = 0; j < NI; ++j) fb[j] = frag_b(b_tile(0), j, 0);
 
   constexpr int JB = 1;                                    // column blocks of k-step 1 multiplied before the barrier
-  int st = 0;
+  int st = 0, st3 = 0;                                     // slab kt's stage; (A3) its A buffer
   for (int kt = 0; kt < nk; ++kt) {
     const int st1 = st + 1 == NS ? 0 : st + 1;
-    const LDS_AS char* As = smem + st * STAGE;
-    const LDS_AS char* Bs = As + TA::BYTES;
-    const LDS_AS char* An = smem + st1 * STAGE;
-    const LDS_AS char* Bn = An + TA::BYTES;
+    const int st31 = st3 + 1 == 3 ? 0 : st3 + 1, st32 = st31 + 1 == 3 ? 0 : st31 + 1;
+    const LDS_AS char* As = a_tile(st3, st);
+    const LDS_AS char* Bs = b_tile(st);
+    const LDS_AS char* An = a_tile(st31, st1);
+    const LDS_AS char* Bn = b_tile(st1);
     // Wave priority falls as a wavefront moves through a slab (2 after the barrier, 1 during k-step 0, 0 on the way
     // to the barrier).  The two wavefronts of a SIMD compete for its matrix core; left alone the older one wins every
     // time, races ahead and then sits at the barrier while the younger one runs alone and cannot keep the matrix core
@@ -411,6 +422,24 @@ __global__ void __launch_bounds__(64 * WGM * WGN) gemm_mfma_kernel(GemmArgs<bf16
     // priority tied to progress the one that is behind goes first: the slab period dropped by 9 %.
     __builtin_amdgcn_s_setprio(1);
     // k-step 0: its fragments are in registers; fetch those of k-step 1 from the same stage meanwhile
+    if constexpr (A3) {
+      // pinned: block j's products, its column fragment of k-step 1, a row fragment of k-step 1, and the A tile of slab
+      // kt+2, one load after each of the first blocks
+      if (kt == 0) TA::advance(offa, a_step);              // (the prologue left the offsets at slab 1)
+      fa[1][0] = frag_a(As, 0, 1);
+#pragma unroll
+      for (int j = 0; j < NI; ++j) {
+#pragma unroll
+        for (int i = 0; i < MI; ++i) acc[i][j] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(fb[j], fa[0][i], acc[i][j], 0, 0, 0);
+        fb[j] = frag_b(Bs, j, 1);
+        if (j + 1 < MI) fa[1][j + 1] = frag_a(As, j + 1, 1);
+#pragma unroll
+        for (int q = j * TA::PER_WAVE / NI; q < (j + 1) * TA::PER_WAVE / NI; ++q)
+          TA::load_one(ra_rsrc, offa, (kb0 + kt + 2) * BK, a.K, smem + st32 * TA::BYTES, q);
+        __builtin_amdgcn_sched_barrier(0);
+      }
+      TA::advance(offa, a_step);
+    } else {
 #pragma unroll
     for (int i = 0; i < MI; ++i) fa[1][i] = frag_a(As, i, 1);
 #pragma unroll
@@ -429,6 +458,7 @@ __global__ void __launch_bounds__(64 * WGM * WGN) gemm_mfma_kernel(GemmArgs<bf16
         else __builtin_amdgcn_sched_group_barrier(0x100, RB, 0);
       }
     }
+    }
     __builtin_amdgcn_sched_barrier(0);
     __builtin_amdgcn_s_setprio(0);
     // k-step 1: after the first JB column blocks every read of this stage has been issued long ago; wait for slab
@@ -438,10 +468,11 @@ __global__ void __launch_bounds__(64 * WGM * WGN) gemm_mfma_kernel(GemmArgs<bf16
     for (int j = 0; j < JB; ++j)
 #pragma unroll
       for (int i = 0; i < MI; ++i) acc[i][j] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(fb[j], fa[1][i], acc[i][j], 0, 0, 0);
-    __builtin_amdgcn_s_waitcnt(vmcnt_only((NS - 2) * PER_SLAB + LAST) & 0xF0FF);     // ... and lgkmcnt(0)
+    // (A3: the A tile of slab kt+2, issued during k-step 0 just now, may still fly)
+    __builtin_amdgcn_s_waitcnt(vmcnt_only(A3 ? TA::PER_WAVE : (NS - 2) * PER_SLAB + LAST) & 0xF0FF);     // ... and lgkmcnt(0)
     __syncthreads();
     __builtin_amdgcn_s_setprio(2);
-    TA::advance(offa, a_step);
+    if constexpr (!A3) TA::advance(offa, a_step);
     TB::advance(offb, b_step);
     // From here on the order is pinned: after every column block's products (and the refill of its fragment) come a
     // share of the slab's global loads and one or two of the early fragment reads of slab kt+1.  (The loads are
@@ -452,9 +483,14 @@ __global__ void __launch_bounds__(64 * WGM * WGN) gemm_mfma_kernel(GemmArgs<bf16
     constexpr int SLOTS = NI - JB;
     constexpr int EARLY = MI + JB;                         // fragments wanted at the start of the next slab
     constexpr int EPS = (EARLY + SLOTS - 1) / SLOTS;       // early fragments per slot
+    constexpr int NOW = A3 ? TB::PER_WAVE : LOADS;         // loads issued after the barrier
     auto issue_load = [&](int q) {
-      if (q < TA::PER_WAVE) TA::load_one(ra_rsrc, offa, (kb0 + kt + NS) * BK, a.K, smem + st * STAGE, q);
-      else if (q < LOADS) TB::load_one(rb_rsrc, offb, (kb0 + kt + NS) * BK, a.K, smem + st * STAGE + TA::BYTES, q - TA::PER_WAVE);
+      if constexpr (A3) {
+        TB::load_one(rb_rsrc, offb, (kb0 + kt + NS) * BK, a.K, smem + 3 * TA::BYTES + st * TB::BYTES, q);
+      } else {
+        if (q < TA::PER_WAVE) TA::load_one(ra_rsrc, offa, (kb0 + kt + NS) * BK, a.K, smem + st * STAGE, q);
+        else if (q < LOADS) TB::load_one(rb_rsrc, offb, (kb0 + kt + NS) * BK, a.K, smem + st * STAGE + TA::BYTES, q - TA::PER_WAVE);
+      }
     };
     auto early_read = [&](int e) {
       if (e < MI) fa[0][e] = frag_a(An, e, 0);
@@ -465,7 +501,7 @@ __global__ void __launch_bounds__(64 * WGM * WGN) gemm_mfma_kernel(GemmArgs<bf16
       const int slot = j - JB;
       __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
-      for (int q = slot * LOADS / SLOTS; q < (slot + 1) * LOADS / SLOTS; ++q) issue_load(q);
+      for (int q = slot * NOW / SLOTS; q < (slot + 1) * NOW / SLOTS; ++q) issue_load(q);
       if (j == NI - 1) prefetch_next();
       __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
@@ -476,6 +512,7 @@ __global__ void __launch_bounds__(64 * WGM * WGN) gemm_mfma_kernel(GemmArgs<bf16
     }
     __builtin_amdgcn_sched_barrier(0);
     st = st1;
+    st3 = st31;
   }
 
   __builtin_amdgcn_s_setprio(0);
@@ -566,11 +603,13 @@ int launch_cfg(const GemmArgs<bf16>& a, hipStream_t s) {
   // The L2 prefetch pays where both operands are read token-major (the weight gradients: +3..5 % on c5's shapes); the
   // k-contiguous kernels lose 1..6 % with it, so they run without.
   constexpr int PF = (!AK && !BKF) ? 2 : 0;
-  constexpr size_t stages = (size_t)NS * (BM + BN) * BK * 2 + (PF > 0 ? 256 : 0);    // + the prefetches' scratch line
+  // a third buffer for A where it fits beside two whole stages (the 256 x 256 and 256 x 192 tiles)
+  constexpr bool A3 = NS == 2 && PF == 0 && (size_t)(3 * BM + 2 * BN) * BK * 2 <= 160 * 1024;
+  constexpr size_t stages = A3 ? (size_t)(3 * BM + 2 * BN) * BK * 2 : (size_t)NS * (BM + BN) * BK * 2 + (PF > 0 ? 256 : 0);    // + the prefetches' scratch line
   constexpr size_t staging = (size_t)WGM * WGN * 32 * (BN / WGN + 4) * 4;
   static_assert(stages <= 160 * 1024, "the stages must fit in LDS");
   const size_t lds = std::max<size_t>(stages, EPI == EPI_GRAD ? 0 : staging);
-  return launch_kernel<gemm_mfma_kernel<BM, BN, WGM, WGN, AK, BKF, EPI, NS, PF>>(a, BM, BN, 64 * WGM * WGN, lds, s);
+  return launch_kernel<gemm_mfma_kernel<BM, BN, WGM, WGN, AK, BKF, EPI, NS, PF, A3>>(a, BM, BN, 64 * WGM * WGN, lds, s);
 }
 
 thread_local int side_by_side = 1;     // kernels the caller runs at once (GemmSideBySide)
