@@ -407,6 +407,7 @@ __global__ void __launch_bounds__(64 * WGM * WGN) gemm_mfma_kernel(GemmArgs<bf16
   for (int j = 0; j < NI; ++j) fb[j] = frag_b(b_tile(0), j, 0);
 
   constexpr int JB = 1;                                    // column blocks of k-step 1 multiplied before the barrier
+  if constexpr (A3) TA::advance(offa, a_step);             // (the prologue left the offsets at slab 1; A's next load is slab 2)
   int st = 0, st3 = 0;                                     // slab kt's stage; (A3) its A buffer
   for (int kt = 0; kt < nk; ++kt) {
     const int st1 = st + 1 == NS ? 0 : st + 1;
@@ -425,7 +426,6 @@ __global__ void __launch_bounds__(64 * WGM * WGN) gemm_mfma_kernel(GemmArgs<bf16
     if constexpr (A3) {
       // pinned: block j's products, its column fragment of k-step 1, a row fragment of k-step 1, and the A tile of slab
       // kt+2, one load after each of the first blocks
-      if (kt == 0) TA::advance(offa, a_step);              // (the prologue left the offsets at slab 1)
       fa[1][0] = frag_a(As, 0, 1);
 #pragma unroll
       for (int j = 0; j < NI; ++j) {
