@@ -1183,7 +1183,7 @@ template <int D, bool CAUSAL>
 int fwd_cfg(const bf16* qkv, bf16* O, float* lse, int m, int S, int H, int A, hipStream_t s) {
   const int nt = (S + 127) / 128;
   dim3 grid(CAUSAL ? (nt + 1) / 2 : nt, A, m);     // causal: a block takes a tile and its mirror image
-  if (CAUSAL) {
+  if constexpr (CAUSAL) {
     // one paired block per compute unit: eight wavefronts, the staged keys split between two groups
     const size_t lds = 4 * (size_t)Tile<D, 128, kThreads8>::ELEMS * sizeof(bf16);
     if constexpr (Tile<D, 128, kThreads8>::DIRECT) {

@@ -92,7 +92,7 @@ cross_entropy_kernel(const float* __restrict__ logits, T* __restrict__ dlogits, 
 
 // The same with the row held in registers: a block of 1024 threads reads its row once (thread t keeps groups t,
 // t + 1024, ... of 16 bytes of output each), so the logits cross the memory bus once instead of twice.  Rows of up to
-// 1024 * MAXG groups; wider ones take the two-pass kernel above.
+// 1024 * MAXG groups, 64 Ki columns in all; wider ones take the two-pass kernel above.
 constexpr int kCeThreads = 1024;
 template <typename T, int MAXG>
 __global__ void __launch_bounds__(kCeThreads)
@@ -162,10 +162,12 @@ cross_entropy_row_kernel(const float* __restrict__ logits, T* __restrict__ dlogi
 
 template <typename T>
 void launch_cross_entropy(const float* logits, T* dlogits, const int* targets, float* loss, int rows, int V, int ld, float coef, hipStream_t s) {
+  // (a thread of a 1024-thread block has 128 registers: at most 64 of them hold the row)
+  constexpr int kMost = 64 / Vec<T>::N;
   const int per_thread = (ld / Vec<T>::N + kCeThreads - 1) / kCeThreads;
   if (per_thread <= 4) cross_entropy_row_kernel<T, 4><<<rows, kCeThreads, 0, s>>>(logits, dlogits, targets, loss, V, ld, coef);
   else if (per_thread <= 8) cross_entropy_row_kernel<T, 8><<<rows, kCeThreads, 0, s>>>(logits, dlogits, targets, loss, V, ld, coef);
-  else if (per_thread <= 16) cross_entropy_row_kernel<T, 16><<<rows, kCeThreads, 0, s>>>(logits, dlogits, targets, loss, V, ld, coef);
+  else if (per_thread <= kMost) cross_entropy_row_kernel<T, kMost><<<rows, kCeThreads, 0, s>>>(logits, dlogits, targets, loss, V, ld, coef);
   else cross_entropy_kernel<T><<<rows, kThreads, 0, s>>>(logits, dlogits, targets, loss, V, ld, coef);
 }
 

@@ -100,7 +100,7 @@ def test_bias_column_sum(rows, N, bf16):
 
 
 @pytest.mark.parametrize("bf16", [False, True])
-# (a row of up to 1024 x 16 groups of 16 output bytes stays in registers; 70001 fp32 / 140003 bf16 columns take the two-pass kernel)
+# (a row of up to 64 Ki columns stays in registers; 70001 and 140003 columns take the two-pass kernel)
 @pytest.mark.parametrize("rows,V", [(7, 101), (130, 1031), (16, 50257), (5, 20011), (3, 70001), (2, 140003)])
 def test_cross_entropy_rows(rows, V, bf16):
     rng = np.random.default_rng(rows + V)
