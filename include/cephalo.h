@@ -240,6 +240,19 @@ size_t cephalo_op_linear_wgrad_workspace(int32_t dtype, int32_t T, int32_t N, in
 int cephalo_op_linear_wgrad(int32_t dtype, const void* dY, const void* X, int32_t T, int32_t N, int32_t K,
                             float* G, float scale, int32_t accumulate, void* workspace, size_t workspace_bytes, void* stream);
 
+/* The same weight gradient together with the bias gradient of the projection (Sec. 3.2: both belong to the gradient
+ * the share accumulates over its micro-batches):
+ *   gb[N] <- (accumulate ? gb : 0) + scale * sum_t dY[t,n]                 (fp32)
+ * In bf16 mode the GEMM forms the column sums on the way: dY's tiles pass through its registers anyway, every tile is
+ * summed by exactly one wavefront, and the pieces are added in a fixed order (reproducible).  With fp32 operands, or
+ * a token axis so long that the GEMM runs in several calls (operands beyond 2 GiB), a column-sum kernel runs after
+ * the GEMM on the same stream.  N must be a multiple of 8; buffers 16-byte aligned, all device memory.
+ * workspace: at least cephalo_op_linear_wgrad_bias_workspace(dtype, T, N, K) bytes. */
+size_t cephalo_op_linear_wgrad_bias_workspace(int32_t dtype, int32_t T, int32_t N, int32_t K);
+int cephalo_op_linear_wgrad_bias(int32_t dtype, const void* dY, const void* X, int32_t T, int32_t N, int32_t K,
+                                 float* G, float* gb, float scale, int32_t accumulate, void* workspace,
+                                 size_t workspace_bytes, void* stream);
+
 /* For callers that cannot allocate device memory and have no work area to hand over (code under HIP graph capture,
  * tight serving loops, harnesses that forbid allocation): cephalo_op_linear_wgrad with the partial sums of a split
  * token axis kept in a fixed device array of CEPHALO_NOALLOC_SCRATCH_BYTES that the library's code object carries

@@ -94,6 +94,8 @@ SIGNATURES = {
                                        _vp, _f32, _i32, _vp]),
     "cephalo_op_linear_wgrad_workspace": (_sz, [_i32, _i32, _i32, _i32]),
     "cephalo_op_linear_wgrad": (ctypes.c_int, [_i32, _vp, _vp, _i32, _i32, _i32, _vp, _f32, _i32, _vp, _sz, _vp]),
+    "cephalo_op_linear_wgrad_bias_workspace": (_sz, [_i32, _i32, _i32, _i32]),
+    "cephalo_op_linear_wgrad_bias": (ctypes.c_int, [_i32, _vp, _vp, _i32, _i32, _i32, _vp, _vp, _f32, _i32, _vp, _sz, _vp]),
     "cephalo_op_linear_wgrad_static": (ctypes.c_int, [_i32, _vp, _vp, _i32, _i32, _i32, _vp, _f32, _i32, _vp]),
     "cephalo_op_norm_fwd": (ctypes.c_int, [_i32, _i32, _vp, _vp, _vp, _vp, _vp, _vp, _i32, _i32, _f32, _vp]),
     "cephalo_op_norm_bwd_workspace": (_sz, [_i32, _i32]),
@@ -303,6 +305,15 @@ def cephalo_op_linear_wgrad_workspace(dtype, T, N, K):
 def cephalo_op_linear_wgrad(dtype, dY, X, T, N, K, G, scale, accumulate, workspace, stream=None):
     _check(lib().cephalo_op_linear_wgrad(dtype, _ptr(dY), _ptr(X), T, N, K, _ptr(G), scale, int(accumulate), _ptr(workspace),
                                          0 if workspace is None else workspace.numel() * workspace.element_size(), _stream(stream)))
+
+
+def cephalo_op_linear_wgrad_bias_workspace(dtype, T, N, K):
+    return int(lib().cephalo_op_linear_wgrad_bias_workspace(dtype, T, N, K))
+
+
+def cephalo_op_linear_wgrad_bias(dtype, dY, X, T, N, K, G, gb, scale, accumulate, workspace, stream=None):
+    _check(lib().cephalo_op_linear_wgrad_bias(dtype, _ptr(dY), _ptr(X), T, N, K, _ptr(G), _ptr(gb), scale, int(accumulate),
+                                              _ptr(workspace), workspace.numel() * workspace.element_size(), _stream(stream)))
 
 
 def cephalo_op_attention_fwd(desc, qkv, O, lse, micro_batch, stream=None):

@@ -406,6 +406,24 @@ __global__ void __launch_bounds__(64 * WGM * WGN) gemm_mfma_kernel(GemmArgs<bf16
 #pragma unroll
   for (int j = 0; j < NI; ++j) fb[j] = frag_b(b_tile(0), j, 0);
 
+  // Row sums of A (GemmArgs::rowsum).  The wavefronts that hold the same rows of A, over the blocks of a tile row and
+  // the WGN wavefront columns of each, take the k-slabs in turn.  One accumulator serves the four row fragments:
+  // fragment i is multiplied by a left operand whose rows 4i..4i+3 are ones and whose other rows are zero, so that
+  // result row 4i + x, column c is the sum of row c of fragment i -- lane l ends up with the sum of the wavefront's row l.
+  const int owners = tiles_n * WGN, owner = tile_n * WGN + wave % WGN;
+  int next_sum = 0x7fffffff;
+  f32x4 rsum = {0.f, 0.f, 0.f, 0.f};
+  if constexpr (EPI == EPI_GRAD) {
+    static_assert(EPI != EPI_GRAD || MI == 4, "four row fragments share the accumulator");
+    if (a.rowsum_part) next_sum = ((owner - kb0) % owners + owners) % owners;
+  }
+  auto ones_for = [&](int i, int row4) -> bf16x8 {         // row4: (this lane's operand row) / 4
+    union { unsigned u[4]; bf16x8 v; } sel;
+    const unsigned w = (row4 == i) ? 0x3F803F80u : 0u;      // two bf16 ones
+    sel.u[0] = w; sel.u[1] = w; sel.u[2] = w; sel.u[3] = w;
+    return sel.v;
+  };
+
   constexpr int JB = 1;                                    // column blocks of k-step 1 multiplied before the barrier
   if constexpr (A3) TA::advance(offa, a_step);             // (the prologue left the offsets at slab 1; A's next load is slab 2)
   int st = 0, st3 = 0;                                     // slab kt's stage; (A3) its A buffer
@@ -461,6 +479,20 @@ __global__ void __launch_bounds__(64 * WGM * WGN) gemm_mfma_kernel(GemmArgs<bf16
     }
     __builtin_amdgcn_sched_barrier(0);
     __builtin_amdgcn_s_setprio(0);
+    if constexpr (EPI == EPI_GRAD) {
+      if (kt == next_sum) {                                // this wavefront's turn: both k-steps' row fragments are in registers
+        next_sum += owners;
+        int row4 = (lane & 15) >> 2;
+        asm volatile("" : "+v"(row4));                     // (computed here each time: kept across the loop, the four operands cost 16 registers)
+#pragma unroll
+        for (int i = 0; i < MI; ++i) {
+          const bf16x8 sel = ones_for(i, row4);
+          rsum = __builtin_amdgcn_mfma_f32_16x16x32_bf16(sel, fa[0][i], rsum, 0, 0, 0);
+          rsum = __builtin_amdgcn_mfma_f32_16x16x32_bf16(sel, fa[1][i], rsum, 0, 0, 0);
+        }
+      }
+      __builtin_amdgcn_sched_barrier(0);
+    }
     // k-step 1: after the first JB column blocks every read of this stage has been issued long ago; wait for slab
     // kt+1 (the loads of the NS-2 slabs after it may still fly), barrier, start the loads of slab kt+NS into this
     // stage, and refill the fragment registers from the stage of slab kt+1 as they fall free.
@@ -518,6 +550,10 @@ __global__ void __launch_bounds__(64 * WGM * WGN) gemm_mfma_kernel(GemmArgs<bf16
   __builtin_amdgcn_s_setprio(0);
   // Epilogue
   if (EPI == EPI_GRAD) {
+    if (a.rowsum_part) {
+      const int m = m0 + wm + lane;
+      if (m < a.M) a.rowsum_part[((int64_t)split * owners + owner) * a.M + m] = rsum[0];
+    }
     const bool partial = a.splits > 1;
     float* const gbase = partial ? a.part + (int64_t)split * a.M * a.N : a.G;
     const float scale = partial ? 1.0f : a.scale;
@@ -572,7 +608,7 @@ splitk_reduce_kernel(const float* __restrict__ part, int splits, int64_t mn4, fl
 
 // Launch of one instantiation: LDS reservation (once), the split of the contracted axis, the reduction of the pieces.
 template <auto KERN>
-int launch_kernel(const GemmArgs<bf16>& a, int BMv, int BNv, int threads, size_t lds, hipStream_t s) {
+int launch_kernel(const GemmArgs<bf16>& a, int BMv, int BNv, int wgn, int threads, size_t lds, hipStream_t s) {
   const int tm = (a.M + BMv - 1) / BMv, tn = (a.N + BNv - 1) / BNv;
   // per instantiation; setting the attribute again with the same value is harmless, so two threads that both find the
   // flag clear may both set it
@@ -588,8 +624,17 @@ int launch_kernel(const GemmArgs<bf16>& a, int BMv, int BNv, int threads, size_t
   splits = (slabs + per - 1) / per;                       // every piece holds at least one k-slab
   GemmArgs<bf16> k = a;
   k.splits = splits;
+  const bool rowsum = a.epi == EPI_GRAD && a.rowsum;
+  const int pieces = splits * tn * wgn;                   // of the row sums: one per split and owner
+  if (rowsum && (!a.rowsum_part || a.rowsum_part_bytes < (size_t)pieces * a.M * sizeof(float)))
+    return fail(CEPHALO_EWORKSPACE, "gemm_mfma: %zu B for the %d pieces of %d row sums", a.rowsum_part_bytes, pieces, a.M);
+  if (!rowsum) k.rowsum_part = nullptr;
   KERN<<<tm * tn * splits, threads, lds, s>>>(k, tm, tn, per);
   CEPHALO_CHECK_LAUNCH("gemm_mfma");
+  if (rowsum) {
+    const int rc = launch_reduce_partials(a.rowsum_part, pieces, a.M, a.rowsum, a.scale, a.accumulate, nullptr, 0, s);
+    if (rc != CEPHALO_OK) return rc;
+  }
   if (splits > 1) {
     const int64_t mn4 = (int64_t)a.M * a.N / 4;
     splitk_reduce_kernel<<<(int)((mn4 + 255) / 256), 256, 0, s>>>(a.part, splits, mn4, a.G, a.scale, a.accumulate);
@@ -609,7 +654,7 @@ int launch_cfg(const GemmArgs<bf16>& a, hipStream_t s) {
   constexpr size_t staging = (size_t)WGM * WGN * 32 * (BN / WGN + 4) * 4;
   static_assert(stages <= 160 * 1024, "the stages must fit in LDS");
   const size_t lds = std::max<size_t>(stages, EPI == EPI_GRAD ? 0 : staging);
-  return launch_kernel<gemm_mfma_kernel<BM, BN, WGM, WGN, AK, BKF, EPI, NS, PF, A3>>(a, BM, BN, 64 * WGM * WGN, lds, s);
+  return launch_kernel<gemm_mfma_kernel<BM, BN, WGM, WGN, AK, BKF, EPI, NS, PF, A3>>(a, BM, BN, WGN, 64 * WGM * WGN, lds, s);
 }
 
 thread_local int side_by_side = 1;     // kernels the caller runs at once (GemmSideBySide)
@@ -670,8 +715,14 @@ GemmSideBySide::~GemmSideBySide() { side_by_side = before; }
 void GemmSideBySide::now(int kernels) { side_by_side = kernels < 1 ? 1 : kernels; }
 int gemm_set_side_by_side(int kernels) { const int was = side_by_side; side_by_side = kernels < 1 ? 1 : kernels; return was; }
 
-int launch_gemm_mfma(const GemmArgs<bf16>& a, hipStream_t s) {
-  if (a.M <= 0 || a.N <= 0 || a.K <= 0) return fail(CEPHALO_EINVAL, "gemm: empty problem %dx%dx%d", a.M, a.N, a.K);
+size_t gemm_rowsum_part_bytes(int M, int N) {
+  // the most splits of gemm_grad_splits, the narrowest tile (128 columns) and its two wavefront columns
+  return (size_t)8 * ((N + 127) / 128) * 2 * (size_t)M * sizeof(float);
+}
+
+namespace {
+// operands and outputs fit the vector loads, buffer descriptors and vector epilogue of the MFMA kernels
+bool fits_mfma(const GemmArgs<bf16>& a) {
   const bool ak = a.a_cs == 1, bk = a.b_cs == 1;
   // 16-byte vector loads: pitches are multiples of 8 elements; a contiguous extent that is not a multiple of 8 is
   // accepted when the pitch covers it rounded up (the caller keeps that padding zero: it is read, never stored).
@@ -682,7 +733,22 @@ int launch_gemm_mfma(const GemmArgs<bf16>& a, hipStream_t s) {
   const bool small = ext_a < (int64_t)0x7fffffff && ext_b < (int64_t)0x7fffffff;   // 32-bit buffer extents and offsets
   const int64_t pitch_c = a.ldc ? a.ldc : a.N;
   const bool ok_c = pitch_c % 8 == 0 && pitch_c >= up8(a.N) && (a.epi != EPI_GRAD || a.N % 8 == 0) && aligned16(a.C) && aligned16(a.R) && aligned16(a.Z) && aligned16(a.bias) && aligned16(a.G) && aligned16(a.Rf) && aligned16(a.Cf);   // vector epilogue
-  if (!ok_a || !ok_b || !ok_c || !small || !aligned16(a.A) || !aligned16(a.B)) return general(a, s);
+  return ok_a && ok_b && ok_c && small && aligned16(a.A) && aligned16(a.B);
+}
+}  // namespace
+
+bool gemm_mfma_takes(const GemmArgs<bf16>& a) {
+  if (a.M <= 0 || a.N <= 0 || a.K <= 0 || !fits_mfma(a)) return false;
+  return a.epi == EPI_GRAD;      // (asked for the weight gradients only: every operand layout of those is instantiated)
+}
+
+int launch_gemm_mfma(const GemmArgs<bf16>& a, hipStream_t s) {
+  if (a.M <= 0 || a.N <= 0 || a.K <= 0) return fail(CEPHALO_EINVAL, "gemm: empty problem %dx%dx%d", a.M, a.N, a.K);
+  const bool ak = a.a_cs == 1, bk = a.b_cs == 1;
+  if (!fits_mfma(a)) {
+    if (a.rowsum) return fail(CEPHALO_EUNSUPPORTED, "gemm: row sums come with the MFMA kernels only");
+    return general(a, s);
+  }
   // Only the layout/epilogue pairs a linear layer produces are instantiated.
   if (ak && bk) {          // forward: Y = X W^T
     switch (a.epi) {

@@ -148,7 +148,17 @@ struct GemmArgs {
   // order: reproducible) and applies scale / accumulate.  part holds splits*M*N floats.
   int splits;
   float* part;
+  // EPI_GRAD, optional: the sums of A's rows over the contracted axis as well (beside a weight gradient dW = dY^T X these
+  // are the column sums of dY, the bias gradient), rowsum[m] = (accumulate ? rowsum[m] : 0) + scale * sum_k A[m][k].
+  // The row fragments pass through the registers anyway; each k-slab of a tile row is summed by exactly one wavefront
+  // among the blocks of that row, with one extra MFMA per fragment, into rowsum_part (gemm_rowsum_part_bytes(M, N)
+  // bytes), and a second pass adds the pieces in a fixed order.  Only the MFMA path takes it: ask gemm_mfma_takes first.
+  float* rowsum;
+  float* rowsum_part;
+  size_t rowsum_part_bytes;
 };
+size_t gemm_rowsum_part_bytes(int M, int N);            // upper bound over tile shapes and splits
+bool gemm_mfma_takes(const GemmArgs<bf16>& a);          // whether launch_gemm_mfma runs this problem on its MFMA kernels
 
 // Number of pieces the weight-gradient GEMM G[M,N] = sum over K tokens would like the token axis cut into (1: none).
 int gemm_grad_splits(int M, int N, int K);

@@ -83,7 +83,7 @@ struct SaveLayout {
 // Backward work area.  dz, dx1 and dqkv (the dY operands of the weight gradients) and the copy of dy in the
 // activation type are kept for `span` samples; the rest is per micro-batch of m samples.
 struct ScratchLayout {
-  size_t dz, dx1, dx1l, dyl, dqkv, du2, dO, du, dvec, wT, wg_part, ln_part, col_part, col_part_bytes, total;
+  size_t dz, dx1, dx1l, dyl, dqkv, du2, dO, du, dvec, wT, wg_part, rs_part, rs_part_bytes, ln_part, col_part, col_part_bytes, total;
   size_t slot_each; // bytes of one slot's du2, dO, du, dvec (slot k's copies lie k * slot_each further on)
   size_t ln_rows;   // rows of each of the four LayerNorm partial arrays (ln2.gamma, ln2.beta, ln1.gamma, ln1.beta)
 };
@@ -139,6 +139,9 @@ ScratchLayout scratch_layout(const cephalo_layer_desc& d, int m, int span, int s
     }
     take(need);
   }
+  // pieces of the bias gradients that the weight-gradient GEMMs of the two bf16-fed projections sum on the way
+  L.rs_part_bytes = (es != 4 && !is_llama(d)) ? std::max(gemm_rowsum_part_bytes((int)(3 * H), (int)H), gemm_rowsum_part_bytes((int)F1, (int)H)) : 0;
+  L.rs_part = take(L.rs_part_bytes);
   L.ln_rows = (size_t)(span / m) * ln_bwd_blocks((int)Tm);
   L.ln_part = take(4 * L.ln_rows * H * sizeof(float));
   const int widest = (int)(3 * H > F1 ? 3 * H : F1);
@@ -222,16 +225,23 @@ GemmArgs<T> linear_wgrad(const T* dY, const T* X, int Tn, int N, int K, float* G
 // Both operands are read as they lie, token-major (the contraction runs over their rows: the GEMM reads such
 // operands with transposing LDS reads at the rate of k-contiguous ones, so no transposed copy is made).
 // `part`: room for the pieces of a split contraction (sized by gemm_grad_splits for the whole token axis), or null.
+// `colsums` (optional): where the column sums of dY, the bias gradient of the same projection, are wanted with the same
+// scale / acc.  The bf16 GEMM sums them beside the products when it can (one piece, operands that fit its MFMA kernels)
+// and then sets colsums->done; otherwise the caller runs the column-sum kernel.
+struct ColsumsBeside { float* g; float* part; size_t part_bytes; bool done; };
 template <typename T>
-int wgrad(const T* dY, const T* X, int Tn, int N, int K, float* G, float scale, int acc, float* part, hipStream_t s, int ldy = 0);
+int wgrad(const T* dY, const T* X, int Tn, int N, int K, float* G, float scale, int acc, float* part, hipStream_t s, int ldy = 0,
+          ColsumsBeside* colsums = nullptr);
 template <>
-int wgrad<float>(const float* dY, const float* X, int Tn, int N, int K, float* G, float scale, int acc, float*, hipStream_t s, int ldy) {
+int wgrad<float>(const float* dY, const float* X, int Tn, int N, int K, float* G, float scale, int acc, float*, hipStream_t s, int ldy,
+                 ColsumsBeside*) {
   GemmArgs<float> a = linear_wgrad<float>(dY, X, Tn, N, K, G, scale, acc);
   if (ldy) a.a_cs = ldy;
   return gemm<float>(a, s);
 }
 template <>
-int wgrad<bf16>(const bf16* dY, const bf16* X, int Tn, int N, int K, float* G, float scale, int acc, float* part, hipStream_t s, int ldy) {
+int wgrad<bf16>(const bf16* dY, const bf16* X, int Tn, int N, int K, float* G, float scale, int acc, float* part, hipStream_t s, int ldy,
+                ColsumsBeside* colsums) {
   if (!ldy) ldy = N;
   // the GEMM addresses its operands through 32-bit buffer descriptors: contract over the tokens in pieces below 2 GiB
   const int64_t widest = ldy > K ? ldy : K;
@@ -244,6 +254,10 @@ int wgrad<bf16>(const bf16* dY, const bf16* X, int Tn, int N, int K, float* G, f
     a.splits = part ? gemm_grad_splits(N, K, tc) : 1;     // `part` was sized with the same rule for the whole token axis
     a.part = part;
     if (tc != Tn) a.splits = 1;
+    if (colsums && tc == Tn && colsums->part && colsums->part_bytes >= gemm_rowsum_part_bytes(N, K) && gemm_mfma_takes(a)) {
+      a.rowsum = colsums->g; a.rowsum_part = colsums->part; a.rowsum_part_bytes = colsums->part_bytes;
+      colsums->done = true;
+    }
     TRY(gemm<bf16>(a, s));
   }
   return CEPHALO_OK;
@@ -276,6 +290,7 @@ template <typename T> struct Work {
   float *ln2_g, *ln2_b, *ln1_g, *ln1_b;   // LayerNorm partial sums, at the row offset of the current micro-batch
   float *col_part; size_t col_part_bytes;
   float *wg_part;
+  float *rs_part; size_t rs_part_bytes;
 };
 template <typename T>
 Work<T> work_at(void* base, const ScratchLayout& W, const cephalo_layer_desc& d, int sample0, int mb_index, int m, int slot = 0) {
@@ -291,6 +306,7 @@ Work<T> work_at(void* base, const ScratchLayout& W, const cephalo_layer_desc& d,
   w.ln2_g = ln + r0; w.ln2_b = ln + arr + r0; w.ln1_g = ln + 2 * arr + r0; w.ln1_b = ln + 3 * arr + r0;
   w.col_part = at<float>(base, W.col_part); w.col_part_bytes = W.col_part_bytes;
   w.wg_part = at<float>(base, W.wg_part);
+  w.rs_part = at<float>(base, W.rs_part); w.rs_part_bytes = W.rs_part_bytes;
   return w;
 }
 
@@ -470,16 +486,25 @@ int layer_bwd_params_t(const cephalo_layer_desc& d, const float* dy, const T* dy
     TRY(launch_reduce_partials(w.ln1_g, ln_chunks, H, G + o.ln1_g, scale, acc, w.col_part, w.col_part_bytes, s2));
     return CEPHALO_OK;
   }
+  // The bias gradients of the two projections into the residual stream are column sums of fp32 gradients and have a
+  // kernel of their own; those of the other two are sums of the very bf16 values their weight-gradient GEMMs read, and
+  // the GEMMs form them on the way.
   if (dy) TRY(launch_colsum<float>(dy, w.col_part, w.col_part_bytes, G + o.b_fc2, scale, acc, tokens, H, s2));   // (null: the caller has summed it already)
   TRY(wgrad<T>(dyl, sv.h, tokens, H, F, G + o.w_fc2, scale, acc, w.wg_part, s));
-  TRY(launch_colsum<T>(w.dz, w.col_part, w.col_part_bytes, G + o.b_fc1, scale, acc, tokens, F, s2));
-  TRY(wgrad<T>(w.dz, sv.u2, tokens, F, H, G + o.w_fc1, scale, acc, w.wg_part, s));
+  {
+    ColsumsBeside cb = {G + o.b_fc1, w.rs_part, w.rs_part_bytes, false};
+    TRY(wgrad<T>(w.dz, sv.u2, tokens, F, H, G + o.w_fc1, scale, acc, w.wg_part, s, 0, &cb));
+    if (!cb.done) TRY(launch_colsum<T>(w.dz, w.col_part, w.col_part_bytes, G + o.b_fc1, scale, acc, tokens, F, s2));
+  }
   TRY(launch_reduce_partials(w.ln2_g, ln_chunks, H, G + o.ln2_g, scale, acc, w.col_part, w.col_part_bytes, s2));
   TRY(launch_reduce_partials(w.ln2_b, ln_chunks, H, G + o.ln2_b, scale, acc, w.col_part, w.col_part_bytes, s2));
   TRY(launch_colsum<float>(w.dx1, w.col_part, w.col_part_bytes, G + o.b_o, scale, acc, tokens, H, s2));
   TRY(wgrad<T>(lowp_of<T>(w.dx1, w.dx1l), sv.O, tokens, H, H, G + o.w_o, scale, acc, w.wg_part, s));
-  TRY(launch_colsum<T>(w.dqkv, w.col_part, w.col_part_bytes, G + o.b_qkv, scale, acc, tokens, 3 * H, s2));
-  TRY(wgrad<T>(w.dqkv, sv.u, tokens, 3 * H, H, G + o.w_qkv, scale, acc, w.wg_part, s));
+  {
+    ColsumsBeside cb = {G + o.b_qkv, w.rs_part, w.rs_part_bytes, false};
+    TRY(wgrad<T>(w.dqkv, sv.u, tokens, 3 * H, H, G + o.w_qkv, scale, acc, w.wg_part, s, 0, &cb));
+    if (!cb.done) TRY(launch_colsum<T>(w.dqkv, w.col_part, w.col_part_bytes, G + o.b_qkv, scale, acc, tokens, 3 * H, s2));
+  }
   TRY(launch_reduce_partials(w.ln1_g, ln_chunks, H, G + o.ln1_g, scale, acc, w.col_part, w.col_part_bytes, s2));
   TRY(launch_reduce_partials(w.ln1_b, ln_chunks, H, G + o.ln1_b, scale, acc, w.col_part, w.col_part_bytes, s2));
   return CEPHALO_OK;

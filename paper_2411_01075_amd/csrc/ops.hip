@@ -105,6 +105,41 @@ extern "C" int cephalo_op_linear_wgrad(int32_t dtype, const void* dY, const void
   return wgrad<bf16>(static_cast<const bf16*>(dY), static_cast<const bf16*>(X), T, N, K, G, scale, accumulate, part, s);
 }
 
+// work area of linear_wgrad_bias: [pieces of a split token axis | pieces of the column sums | the column-sum kernel's partials]
+extern "C" size_t cephalo_op_linear_wgrad_bias_workspace(int32_t dtype, int32_t T, int32_t N, int32_t K) {
+  if (T <= 0 || N <= 0 || K <= 0) return 0;
+  const size_t rs = dtype == CEPHALO_BF16 ? gemm_rowsum_part_bytes(N, K) : 0;
+  return align_up(wgrad_part_bytes(dtype, T, N, K)) + align_up(rs) + colsum_partial_bytes(T, N) + 256;
+}
+
+extern "C" int cephalo_op_linear_wgrad_bias(int32_t dtype, const void* dY, const void* X, int32_t T, int32_t N, int32_t K,
+                                            float* G, float* gb, float scale, int32_t accumulate, void* workspace,
+                                            size_t workspace_bytes, void* stream) {
+  if (T <= 0 || N <= 0 || K <= 0) return fail(CEPHALO_EINVAL, "linear_wgrad_bias: sizes %d x %d x %d must be positive", T, N, K);
+  if (!dY || !X || !G || !gb || !workspace) return fail(CEPHALO_EINVAL, "linear_wgrad_bias: null buffer");
+  if (accumulate != 0 && accumulate != 1) return fail(CEPHALO_EINVAL, "linear_wgrad_bias: accumulate must be 0 or 1");
+  if (dtype != CEPHALO_F32 && dtype != CEPHALO_BF16) return fail(CEPHALO_EINVAL, "linear_wgrad_bias: unknown dtype %d", dtype);
+  if (N % 8 != 0) return fail(CEPHALO_EUNSUPPORTED, "linear_wgrad_bias: the output width %d must be a multiple of 8", N);
+  for (const void* p : {dY, X, (const void*)G, (const void*)gb, (const void*)workspace})
+    if (reinterpret_cast<uintptr_t>(p) % 16 != 0) return fail(CEPHALO_EINVAL, "linear_wgrad_bias: buffers must be 16-byte aligned");
+  if (workspace_bytes < cephalo_op_linear_wgrad_bias_workspace(dtype, T, N, K))
+    return fail(CEPHALO_EWORKSPACE, "linear_wgrad_bias: workspace %zu B < %zu B", workspace_bytes, cephalo_op_linear_wgrad_bias_workspace(dtype, T, N, K));
+  hipStream_t s = static_cast<hipStream_t>(stream);
+  char* w = static_cast<char*>(workspace);
+  const size_t part_bytes = wgrad_part_bytes(dtype, T, N, K), rs_bytes = dtype == CEPHALO_BF16 ? gemm_rowsum_part_bytes(N, K) : 0;
+  float* col_part = reinterpret_cast<float*>(w + align_up(part_bytes) + align_up(rs_bytes));
+  const size_t col_bytes = colsum_partial_bytes(T, N);
+  if (dtype == CEPHALO_F32) {
+    TRY(wgrad<float>(static_cast<const float*>(dY), static_cast<const float*>(X), T, N, K, G, scale, accumulate, nullptr, s));
+    return launch_colsum<float>(static_cast<const float*>(dY), col_part, col_bytes, gb, scale, accumulate, T, N, s);
+  }
+  ColsumsBeside cb = {gb, reinterpret_cast<float*>(w + align_up(part_bytes)), rs_bytes, false};
+  TRY(wgrad<bf16>(static_cast<const bf16*>(dY), static_cast<const bf16*>(X), T, N, K, G, scale, accumulate,
+                  part_bytes ? reinterpret_cast<float*>(w) : nullptr, s, 0, &cb));
+  if (cb.done) return CEPHALO_OK;
+  return launch_colsum<bf16>(static_cast<const bf16*>(dY), col_part, col_bytes, gb, scale, accumulate, T, N, s);
+}
+
 extern "C" int cephalo_op_attention_fwd(const cephalo_layer_desc* d, const void* qkv, void* O, float* lse,
                                         int32_t m, void* stream) {
   int rc = check_attn(d, m);

@@ -151,3 +151,43 @@ def test_linear_weight_gradient_op(T, N, K, bf16):
         small = torch.empty(16, dtype=torch.uint8, device="cuda")
         with pytest.raises(C.CephaloError, match="error -3"):
             C.cephalo_op_linear_wgrad(dt, dev(dY, bf16), dev(X, bf16), T, N, K, G, 1.0, 0, small)
+
+
+@pytest.mark.parametrize("bf16", [False, True])
+@pytest.mark.parametrize("T,N,K", [(4096, 256, 256),      # one tile, the token axis in pieces: one owner per piece and wavefront column
+                                   (4104, 320, 200),      # ragged rows, columns and tokens
+                                   (2048, 1024, 512),     # 256 x 256 tiles
+                                   (1000, 2048, 1024),    # several tile rows and columns: the k-slabs go round 8 owners
+                                   (192, 512, 4096),      # more owners than k-slabs: most pieces stay zero
+                                   (300, 72, 136),        # smaller than a tile in every direction
+                                   (8192, 512, 256)])
+def test_weight_gradient_with_bias_gradient_beside_it(T, N, K, bf16):
+    """Sec. 3.2's accumulated gradient holds, for every projection, dW = dY^T X and db = the column sums of dY.  The
+    bf16 GEMM forms db from the dY tiles that pass through its registers; the weight gradient must not change by a
+    bit, and db is the sum of the very bf16 values, in fp32."""
+    print("wgrad+bias op", T, N, K, bf16, flush=True)
+    rng = np.random.default_rng(T + N * 5 + K)
+    X = rng.standard_normal((T, K)).astype(np.float32)
+    dY = (rng.standard_normal((T, N)) + 0.25).astype(np.float32)      # (a mean: the sums do not cancel to noise)
+    rnd = round_to_bf16 if bf16 else (lambda a: a.astype(np.float64))
+    ref_b = rnd(dY).sum(axis=0)
+    dt = C.BF16 if bf16 else C.F32
+    ws = torch.empty(C.cephalo_op_linear_wgrad_bias_workspace(dt, T, N, K), dtype=torch.uint8, device="cuda")
+    ws.fill_(0xFF)                                                     # NaN patterns: nothing may be read before it is written
+    ws0 = torch.empty(max(16, C.cephalo_op_linear_wgrad_workspace(dt, T, N, K)), dtype=torch.uint8, device="cuda")
+    G = torch.full((N, K), float("nan"), dtype=torch.float32, device="cuda")
+    G0 = torch.full((N, K), float("nan"), dtype=torch.float32, device="cuda")
+    gb = torch.full((N,), float("nan"), dtype=torch.float32, device="cuda")
+    C.cephalo_op_linear_wgrad_bias(dt, dev(dY, bf16), dev(X, bf16), T, N, K, G, gb, 0.5, 0, ws)
+    C.cephalo_op_linear_wgrad(dt, dev(dY, bf16), dev(X, bf16), T, N, K, G0, 0.5, 0, ws0)
+    assert torch.equal(G, G0)
+    assert rel_errors(host(gb), 0.5 * ref_b)[0] < 1e-5
+    first = gb.clone()
+    C.cephalo_op_linear_wgrad_bias(dt, dev(dY, bf16), dev(X, bf16), T, N, K, G, gb, 0.25, 1, ws)
+    assert rel_errors(host(gb), 0.75 * ref_b)[0] < 1e-5
+    gb2 = torch.full((N,), float("nan"), dtype=torch.float32, device="cuda")
+    C.cephalo_op_linear_wgrad_bias(dt, dev(dY, bf16), dev(X, bf16), T, N, K, G0, gb2, 0.5, 0, ws)
+    assert torch.equal(first, gb2)                             # fixed summation order: bit-reproducible
+    small = torch.empty(256, dtype=torch.uint8, device="cuda")
+    with pytest.raises(C.CephaloError, match="error -3"):
+        C.cephalo_op_linear_wgrad_bias(dt, dev(dY, bf16), dev(X, bf16), T, N, K, G, gb, 1.0, 0, small)
