@@ -126,49 +126,132 @@ struct OperandTile {
 
 // Second half of the bf16/fp32-output epilogue: 32 rows x WTN columns of fp32 results staged row-major in LDS (pitch
 // WTN + 4 floats) are read back 8 columns per lane, bias / residual / pre-activation applied, and written as
-// coalesced 16-byte accesses.  mrow0, ncol0: matrix coordinates of the staged block's corner.
+// coalesced 16-byte accesses.  A lane keeps its 8 columns and walks down the rows in PASSES steps.
+//
+// Everything here is straight-line code.  What the epilogue reads from memory is fetched for a whole staged block at
+// once (`fetch`, into a register set), the bias once per tile; then every row's result is formed, then every row is
+// stored.  All accesses go through buffer descriptors over the wavefront's 64 rows, whose range check drops what lies
+// past the matrix (rows past M; columns past N get an out-of-range offset), so no row needs a branch.  Written row by
+// row as load, use, store under a bounds test, every row waited for its loads behind the previous row's stores: one
+// memory round trip per row, 16 in a row per tile, 12 000 to 25 000 clocks of epilogue on a tile whose main loop takes
+// 83 000 at K = 2048.  (The compiler counts memory operations in order and gives up at branches.)
 template <int EPI, int WTN>
-__device__ __forceinline__ void write_staged_rows(const GemmArgs<bf16>& a, const LDS_AS float* stage, int mrow0, int ncol0, int ldc) {
-  constexpr int SP = WTN + 4, LPR = WTN / 8, RPS = 64 / LPR;
-  const int lane = threadIdx.x & 63;
-  const int c = (lane % LPR) * 8;
-  const int n = ncol0 + c;
+struct StagedRows {
+  static constexpr int SP = WTN + 4, LPR = WTN / 8, RPS = 64 / LPR, PASSES = (32 + RPS - 1) / RPS;
+  static constexpr bool BIAS = EPI == EPI_BIAS || EPI == EPI_BIAS_GELU || EPI == EPI_BIAS_GELU_DERIV || EPI == EPI_BIAS_RESID;
+  // 16-byte vectors a row's 8 columns need from memory
+  static constexpr int NX = (EPI == EPI_BIAS_RESID || EPI == EPI_DSWIGLU || EPI == EPI_ROPE) ? 2 : (EPI == EPI_DGELU || EPI == EPI_MUL) ? 1 : 0;
+  typedef bf16 bf16x8 __attribute__((ext_vector_type(8)));
+  typedef f16 f16x8 __attribute__((ext_vector_type(8)));
+  struct Set { f32x4 x0[PASSES], x1[PASSES]; };     // (small arrays of their own: one large one stays in scratch memory)
+  float b8[8];
+  int c, n, r0, ldc, mrow;
+  unsigned col_off;                                  // 0, or the out-of-range mark for a lane whose columns lie past N
+  __amdgpu_buffer_rsrc_t out16, out32, zed, res;     // C, Cf, Z, R or Rf: the wavefront's rows of each
+  unsigned res_es, res_second;                       // residual: bytes per element, offset of its second vector
+
+  // mrow0, ncol0: matrix coordinates of the wavefront tile's corner (64 rows: two staged blocks)
+  __device__ __forceinline__ void init(const GemmArgs<bf16>& a, int mrow0, int ncol0, int ldc_) {
+    mrow0 = __builtin_amdgcn_readfirstlane(mrow0);       // (the same in every lane: the descriptors must be scalars)
+    const int lane = threadIdx.x & 63;
+    c = (lane % LPR) * 8;
+    n = ncol0 + c;
+    r0 = lane / LPR;
+    ldc = ldc_;
+    mrow = mrow0;
+    col_off = n < a.N ? 0u : kOob;
+    const int rows = max(0, min(a.M - mrow0, 64));
+    const int64_t base = (int64_t)mrow0 * ldc;
+    const unsigned elems = (unsigned)rows * (unsigned)ldc;
+    out16 = make_rsrc(a.C ? a.C + base : nullptr, a.C ? elems * 2 : 0);
+    out32 = make_rsrc(a.Cf ? a.Cf + base : nullptr, a.Cf ? elems * 4 : 0);
+    zed = make_rsrc(a.Z ? a.Z + base : nullptr, a.Z ? elems * 2 : 0);       // (bf16 or IEEE half: two bytes either way)
+    res_es = a.Rf ? 4 : 2;
+    res_second = a.Rf ? 16u : kOob;                                          // (a bf16 residual is one vector)
+    const void* rp = a.Rf ? static_cast<const void*>(a.Rf + base) : static_cast<const void*>(a.R ? a.R + base : nullptr);
+    res = make_rsrc(rp, (a.Rf || a.R) ? elems * res_es : 0);
 #pragma unroll
-    for (int r = lane / LPR; r < 32; r += RPS) {
+    for (int t = 0; t < 8; ++t) b8[t] = 0.f;
+    if (BIAS && n < a.N && (EPI != EPI_BIAS_RESID || a.bias)) load_vec<bf16>(a.bias + n, b8);     // (no bias: residual only)
+  }
+  // element offset of this lane's 8 columns in row `r` of staged block `blk`, relative to the wavefront's first row
+  __device__ __forceinline__ unsigned elem(int blk, int r) const { return (unsigned)(blk * 32 + r) * (unsigned)ldc + (unsigned)n; }
+  __device__ static __forceinline__ f32x4 load16(__amdgpu_buffer_rsrc_t rsrc, unsigned off) {
+    return __builtin_bit_cast(f32x4, __builtin_amdgcn_raw_buffer_load_b128(rsrc, (int)off, 0, 0));
+  }
+  __device__ static __forceinline__ void store16(__amdgpu_buffer_rsrc_t rsrc, unsigned off, f32x4 v) {
+    __builtin_amdgcn_raw_buffer_store_b128(__builtin_bit_cast(i32x4, v), rsrc, (int)off, 0, 0);
+  }
+  // the memory operands of staged block `blk` (0 or 1), into register set `set`
+  __device__ __forceinline__ void fetch(const GemmArgs<bf16>& a, Set& set, int blk) {
+    if (NX == 0) return;
+#pragma unroll
+    for (int p = 0; p < PASSES; ++p) {
+      const int r = min(r0 + p * RPS, 31);
+      const unsigned e = elem(blk, r);
+      if (EPI == EPI_BIAS_RESID) {
+        set.x0[p] = load16(res, (e * res_es) | col_off);
+        set.x1[p] = load16(res, (e * res_es + res_second) | col_off);
+      }
+      if (EPI == EPI_DGELU || EPI == EPI_MUL) set.x0[p] = load16(zed, (e * 2) | col_off);
+      if (EPI == EPI_DSWIGLU) {
+        set.x0[p] = load16(zed, (e * 2) | col_off);
+        set.x1[p] = load16(zed, ((e + (unsigned)a.N) * 2) | col_off);
+      }
+      if (EPI == EPI_ROPE) {       // (a small table: plain loads at a row and column kept inside it)
+        const int m = min(mrow + blk * 32 + r, a.M - 1), nr = n < a.rot_cols ? n : 0;
+        const f32x4* cs = reinterpret_cast<const f32x4*>(a.rot + ((int64_t)(m % a.rot_S) * (a.rot_d / 2) + (nr % a.rot_d) / 2) * 2);
+        set.x0[p] = cs[0];
+        set.x1[p] = cs[1];
+      }
+    }
+  }
+  template <typename V> __device__ static __forceinline__ void widen(const f32x4& raw, float (&out)[8]) {
+    const V v = __builtin_bit_cast(V, raw);
+#pragma unroll
+    for (int t = 0; t < 8; ++t) out[t] = (float)v[t];
+  }
+  template <typename V, typename E> __device__ static __forceinline__ f32x4 narrow(const float (&in)[8]) {
+    V v;
+#pragma unroll
+    for (int t = 0; t < 8; ++t) v[t] = (E)in[t];
+    return __builtin_bit_cast(f32x4, v);
+  }
+  // staged block `blk`, with the operands of register set `set`
+  __device__ __forceinline__ void write(const GemmArgs<bf16>& a, const LDS_AS float* stage, const Set& set, int blk) {
+    float out[PASSES][8];
+    f32x4 second[PASSES];         // a second output of 8 two-byte values (pre-activation, saved derivative, the up projection's gradient)
+#pragma unroll
+    for (int p = 0; p < PASSES; ++p) {
+      const int r = min(r0 + p * RPS, 31);
       const f32x4 v0 = *reinterpret_cast<const LDS_AS f32x4*>(stage + r * SP + c);
       const f32x4 v1 = *reinterpret_cast<const LDS_AS f32x4*>(stage + r * SP + c + 4);
-      const int m = mrow0 + r;
-      if (m >= a.M || n >= a.N) continue;
-      const int64_t o = (int64_t)m * ldc + n;
-      float v[8];
+      float (&v)[8] = out[p];
 #pragma unroll
       for (int t = 0; t < 4; ++t) { v[t] = v0[t]; v[4 + t] = v1[t]; }
-      if (EPI == EPI_BIAS || EPI == EPI_BIAS_GELU || EPI == EPI_BIAS_GELU_DERIV || (EPI == EPI_BIAS_RESID && a.bias)) {    // (no bias: residual only)
-        float b8[8];
-        load_vec<bf16>(a.bias + n, b8);
+      if (BIAS) {
 #pragma unroll
         for (int t = 0; t < 8; ++t) v[t] += b8[t];
       }
       if (EPI == EPI_BIAS_RESID) {
-        if (a.Rf) {      // fp32 residual stream
-          const f32x4 r0 = *reinterpret_cast<const f32x4*>(a.Rf + o), r1 = *reinterpret_cast<const f32x4*>(a.Rf + o + 4);
+        if (a.Rf) {
 #pragma unroll
-          for (int t = 0; t < 4; ++t) { v[t] += r0[t]; v[4 + t] += r1[t]; }
+          for (int t = 0; t < 4; ++t) { v[t] += set.x0[p][t]; v[4 + t] += set.x1[p][t]; }
         } else {
           float r8[8];
-          load_vec<bf16>(a.R + o, r8);
+          widen<bf16x8>(set.x0[p], r8);
 #pragma unroll
           for (int t = 0; t < 8; ++t) v[t] += r8[t];
         }
       }
       if (EPI == EPI_BIAS_GELU) {
-        store_vec<bf16>(a.Z + o, v);
+        second[p] = narrow<bf16x8, bf16>(v);
 #pragma unroll
         for (int t = 0; t < 8; ++t) v[t] = gelu_fast(v[t]);
       }
       if (EPI == EPI_DGELU) {
         float z8[8];
-        load_vec<bf16>(a.Z + o, z8);
+        widen<bf16x8>(set.x0[p], z8);
 #pragma unroll
         for (int t = 0; t < 8; ++t) v[t] *= gelu_grad_fast(z8[t]);
       }
@@ -176,19 +259,18 @@ __device__ __forceinline__ void write_staged_rows(const GemmArgs<bf16>& a, const
         float d8[8];
 #pragma unroll
         for (int t = 0; t < 8; ++t) gelu_and_grad_fast(v[t], v[t], d8[t]);
-        store_vec<f16>(reinterpret_cast<f16*>(a.Z) + o, d8);      // a factor, not an operand: IEEE half
+        second[p] = narrow<f16x8, f16>(d8);      // a factor, not an operand: IEEE half
       }
       if (EPI == EPI_MUL) {
         float z8[8];
-        load_vec<f16>(reinterpret_cast<const f16*>(a.Z) + o, z8);
+        widen<f16x8>(set.x0[p], z8);
 #pragma unroll
         for (int t = 0; t < 8; ++t) v[t] *= z8[t];
       }
       if (EPI == EPI_ROPE) {
-        if (n < a.rot_cols) {       // (a group of 8 columns lies wholly inside or outside the rotated part)
-          const f32x4* cs = reinterpret_cast<const f32x4*>(a.rot + ((int64_t)(m % a.rot_S) * (a.rot_d / 2) + (n % a.rot_d) / 2) * 2);
-          const f32x4 r0 = cs[0], r1 = cs[1];
-          const float c4[4] = {r0[0], r0[2], r1[0], r1[2]}, s4[4] = {r0[1], r0[3], r1[1], r1[3]};
+        if (n < a.rot_cols) {
+          const f32x4 r0v = set.x0[p], r1v = set.x1[p];
+          const float c4[4] = {r0v[0], r0v[2], r1v[0], r1v[2]}, s4[4] = {r0v[1], r0v[3], r1v[1], r1v[3]};
 #pragma unroll
           for (int t = 0; t < 4; ++t) {
             const float e = v[2 * t], od = v[2 * t + 1];
@@ -198,26 +280,33 @@ __device__ __forceinline__ void write_staged_rows(const GemmArgs<bf16>& a, const
         }
       }
       if (EPI == EPI_DSWIGLU) {     // two outputs per product: the gate's and the up projection's gradient, N columns apart
-        float g8[8], u8[8], dg[8], du[8];
-        load_vec<bf16>(a.Z + o, g8);
-        load_vec<bf16>(a.Z + o + a.N, u8);
+        float g8[8], u8[8], du[8];
+        widen<bf16x8>(set.x0[p], g8);
+        widen<bf16x8>(set.x1[p], u8);
 #pragma unroll
-        for (int t = 0; t < 8; ++t) swiglu_grad(g8[t], u8[t], v[t], dg[t], du[t]);
-        store_vec<bf16>(a.C + o, dg);
-        store_vec<bf16>(a.C + o + a.N, du);
-        continue;
-      }
-      if (a.Cf) {        // fp32 output (residual stream, or a gradient that an element-wise kernel reads next)
-        f32x4 w0, w1;
-#pragma unroll
-        for (int t = 0; t < 4; ++t) { w0[t] = v[t]; w1[t] = v[4 + t]; }
-        *reinterpret_cast<f32x4*>(a.Cf + o) = w0;
-        *reinterpret_cast<f32x4*>(a.Cf + o + 4) = w1;
-      } else {
-        store_vec<bf16>(a.C + o, v);
+        for (int t = 0; t < 8; ++t) swiglu_grad(g8[t], u8[t], v[t], v[t], du[t]);
+        second[p] = narrow<bf16x8, bf16>(du);
       }
     }
-}
+    if (EPI != EPI_DSWIGLU && a.Cf) {        // fp32 output (residual stream, or a gradient that an element-wise kernel reads next)
+#pragma unroll
+      for (int p = 0; p < PASSES; ++p) {
+        const unsigned e = elem(blk, min(r0 + p * RPS, 31));
+        if (EPI == EPI_BIAS_GELU || EPI == EPI_BIAS_GELU_DERIV) store16(zed, (e * 2) | col_off, second[p]);
+        store16(out32, (e * 4) | col_off, f32x4{out[p][0], out[p][1], out[p][2], out[p][3]});
+        store16(out32, (e * 4 + 16) | col_off, f32x4{out[p][4], out[p][5], out[p][6], out[p][7]});
+      }
+    } else {
+#pragma unroll
+      for (int p = 0; p < PASSES; ++p) {
+        const unsigned e = elem(blk, min(r0 + p * RPS, 31));
+        if (EPI == EPI_BIAS_GELU || EPI == EPI_BIAS_GELU_DERIV) store16(zed, (e * 2) | col_off, second[p]);
+        if (EPI == EPI_DSWIGLU) store16(out16, ((e + (unsigned)a.N) * 2) | col_off, second[p]);
+        store16(out16, (e * 2) | col_off, narrow<bf16x8, bf16>(out[p]));
+      }
+    }
+  }
+};
 
 // s_waitcnt operand that waits for vmcnt(n) only (6-bit counter split over two fields; the other counters at their maxima)
 constexpr int vmcnt_only(int n) { return 0x0F70 | (n & 15) | ((n >> 4) << 14); }
@@ -582,16 +671,30 @@ __global__ void __launch_bounds__(64 * WGM * WGN) gemm_mfma_kernel(GemmArgs<bf16
   static_assert(NW * 32 * SP * 4 <= 160 * 1024, "staging regions must fit in LDS");
   LDS_AS float* stage = (LDS_AS float*)(smem + wave * (32 * SP * 4));
   __builtin_amdgcn_s_waitcnt(vmcnt_only(0) & 0xF0FF);     // the last (unused) slab loads and fragment reads are over,
+  StagedRows<EPI, WTN> rows;
+  rows.init(a, m0 + wm, n0 + wn, ldc);
+  typedef typename StagedRows<EPI, WTN>::Set Operands;
+  Operands set0, set1;                                    // (named, not indexed: a choice of address keeps them out of registers)
+  rows.fetch(a, set0, 0);                                 // (the first block's operands fly across the barrier)
   __syncthreads();                                        // in every wavefront, before the stages are overwritten
-#pragma unroll
-  for (int i2 = 0; i2 < MI / 2; ++i2) {
+  static_assert(MI == 4, "two staged blocks of 32 rows");
+  // The second block's operands are asked for before the first block is written where one 16-byte vector per row is
+  // all (two register sets); with two vectors per row the accumulators still held leave room for one set only, and the
+  // second block's loads follow the first block's stores.
+  constexpr bool TWO_SETS = StagedRows<EPI, WTN>::NX < 2;
+  auto stage_block = [&](int i2) {
 #pragma unroll
     for (int ii = 0; ii < 2; ++ii)
 #pragma unroll
       for (int j = 0; j < NI; ++j)
         *reinterpret_cast<LDS_AS f32x4*>(stage + (16 * ii + (lane & 15)) * SP + 16 * j + 4 * (lane >> 4)) = acc[2 * i2 + ii][j];
-    write_staged_rows<EPI, WTN>(a, stage, m0 + wm + 32 * i2, n0 + wn, ldc);
-  }
+  };
+  if constexpr (TWO_SETS) rows.fetch(a, set1, 1);
+  stage_block(0);
+  rows.write(a, stage, set0, 0);
+  if constexpr (!TWO_SETS) rows.fetch(a, set0, 1);
+  stage_block(1);
+  rows.write(a, stage, TWO_SETS ? set1 : set0, 1);
 }
 
 // G = (accumulate ? G : 0) + scale * (part[0] + part[1] + ... ) in split order, 4 floats per thread
@@ -732,7 +835,8 @@ bool fits_mfma(const GemmArgs<bf16>& a) {
   const int64_t ext_a = 2 * (ak ? (int64_t)a.M * a.a_rs : (int64_t)a.K * a.a_cs), ext_b = 2 * (bk ? (int64_t)a.N * a.b_rs : (int64_t)a.K * a.b_cs);
   const bool small = ext_a < (int64_t)0x7fffffff && ext_b < (int64_t)0x7fffffff;   // 32-bit buffer extents and offsets
   const int64_t pitch_c = a.ldc ? a.ldc : a.N;
-  const bool ok_c = pitch_c % 8 == 0 && pitch_c >= up8(a.N) && (a.epi != EPI_GRAD || a.N % 8 == 0) && aligned16(a.C) && aligned16(a.R) && aligned16(a.Z) && aligned16(a.bias) && aligned16(a.G) && aligned16(a.Rf) && aligned16(a.Cf);   // vector epilogue
+  // (the epilogue addresses a wavefront's 64 rows of the output through a 32-bit buffer extent)
+  const bool ok_c = pitch_c % 8 == 0 && pitch_c >= up8(a.N) && pitch_c * 64 * 4 < (int64_t)0x7fffffff && (a.epi != EPI_GRAD || a.N % 8 == 0) && aligned16(a.C) && aligned16(a.R) && aligned16(a.Z) && aligned16(a.bias) && aligned16(a.G) && aligned16(a.Rf) && aligned16(a.Cf);   // vector epilogue
   return ok_a && ok_b && ok_c && small && aligned16(a.A) && aligned16(a.B);
 }
 }  // namespace
