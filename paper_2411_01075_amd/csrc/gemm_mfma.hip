@@ -7,10 +7,10 @@
 //   weight gradient  dW = dY^T X       tokens are k: one operand is transposed beforehand by the caller, the other
 //                                      is read row-contiguous
 //
-// Matrix instruction: v_mfma_f32_16x16x32_bf16.  On this chip a stream of 16x16x32 products sustains about a fifth
-// more than a stream of 32x32x16 products on the same data (measured with operands held in registers: 2.0 against
-// 1.66 PFLOP/s; the chip is power-limited long before its nominal 2.5), and the LDS bytes per flop depend on the
-// wavefront tile only, not on the MFMA shape.
+// Matrix instruction: v_mfma_f32_16x16x32_bf16.  On this chip a stream of 16x16x32 products sustains an eighth
+// more than a stream of 32x32x16 products on the same data (measured with operands held in registers, the same
+// 64 x 128 wavefront tile either way: 2.06 against 1.82 PFLOP/s; the chip is power-limited long before its nominal
+// 2.5), and the LDS bytes per flop depend on the wavefront tile only, not on the MFMA shape.
 //
 // Data path.  The tile is as large as the accumulators allow (256 x 256 per block of 8 wavefronts, 64 x 128 per
 // wavefront: every byte brought into LDS and every LDS byte read feeds the most MFMAs) and operand slabs of 64
