@@ -103,12 +103,14 @@ constexpr int kLnBwdRowsPerBlock = 8;
 // the row in registers, needed 234 registers at H = 2048 and left two wavefronts per SIMD taking turns between a burst
 // of loads and a burst of stores: 0.50-0.57 of the memory's rate.)  The two row sums go through LDS: one barrier per
 // pair of rows, the slots alternate so that a second one is not needed.
-template <typename T, int MV, bool RMS>
+// SUMS: the block's column sums of `out` go to part_s as well (the bias gradient of a projection that writes into the
+// residual stream is the column sum of the stream's gradient, which is this kernel's result).
+template <typename T, int MV, bool RMS, bool SUMS>
 __global__ void __launch_bounds__(kThreads)
 ln_bwd_kernel(const float* __restrict__ du, const float* __restrict__ x, const float* __restrict__ mean,
               const float* __restrict__ rstd, const T* __restrict__ gamma, const float* __restrict__ resid,
               float* __restrict__ out, T* __restrict__ out_lowp, float* __restrict__ part_g, float* __restrict__ part_b,
-              int rows, int H) {
+              float* __restrict__ part_s, int rows, int H) {
   constexpr int VN = Vec<T>::N;
   constexpr int R = 2;                                   // rows per step
   constexpr int STEPS = kLnBwdRowsPerBlock / R;
@@ -119,7 +121,7 @@ ln_bwd_kernel(const float* __restrict__ du, const float* __restrict__ x, const f
   const float inv_h = 1.0f / (float)H;
   const int row0 = blockIdx.x * kLnBwdRowsPerBlock;
 
-  float gm[MV][VN], dg[MV][VN], db[MV][VN];
+  float gm[MV][VN], dg[MV][VN], db[MV][VN], ds[SUMS ? MV : 1][VN];
 #pragma unroll
   for (int j = 0; j < MV; ++j) {
     const int v = threadIdx.x + kThreads * j;
@@ -131,6 +133,10 @@ ln_bwd_kernel(const float* __restrict__ du, const float* __restrict__ x, const f
     }
 #pragma unroll
     for (int i = 0; i < VN; ++i) { dg[j][i] = 0.f; db[j][i] = 0.f; }
+    if (SUMS) {
+#pragma unroll
+      for (int i = 0; i < VN; ++i) ds[j][i] = 0.f;
+    }
   }
 
   struct Rows { float d[R][MV][VN], xv[R][MV][VN], rr[R][MV][VN]; };
@@ -201,6 +207,10 @@ ln_bwd_kernel(const float* __restrict__ du, const float* __restrict__ x, const f
             float o[VN];
 #pragma unroll
             for (int i = 0; i < VN; ++i) o[i] = b.rr[r][j][i] + rs[r] * (b.d[r][j][i] - c1 - b.xv[r][j][i] * c2);
+            if (SUMS) {
+#pragma unroll
+              for (int i = 0; i < VN; ++i) ds[j][i] += o[i];
+            }
             store_f32<VN>(out + (int64_t)row * H + v * VN, o);
             if (out_lowp) store_vec<T>(out_lowp + (int64_t)row * H + v * VN, o);
           }
@@ -234,6 +244,7 @@ ln_bwd_kernel(const float* __restrict__ du, const float* __restrict__ x, const f
     if (v < nv) {
       store_f32<VN>(pg + v * VN, dg[j]);
       store_f32<VN>(pb + v * VN, db[j]);
+      if (SUMS) store_f32<VN>(part_s + (int64_t)blockIdx.x * H + v * VN, ds[j]);
     }
   }
 }
@@ -357,15 +368,18 @@ int ln_bwd_blocks(int rows) { return (rows + kLnBwdRowsPerBlock - 1) / kLnBwdRow
 
 template <typename T>
 int launch_ln_bwd(const float* du, const float* x, const float* mean, const float* rstd, const T* gamma,
-                  const float* resid, float* out, T* out_lowp, float* part_g, float* part_b, int rows, int H, hipStream_t s, bool rms) {
+                  const float* resid, float* out, T* out_lowp, float* part_g, float* part_b, int rows, int H, hipStream_t s, bool rms,
+                  float* part_s) {
+  if (rms && part_s) return fail(CEPHALO_EINVAL, "norm backward: column sums of the result go with the LayerNorm form only");
   const int nblocks = ln_bwd_blocks(rows);
   const int nv = H / Vec<T>::N;
   int mv = 1;
   while (mv * kThreads < nv) mv *= 2;          // 16-byte column groups per thread
 #define LN_BWD_CASE(MV)                                                                                               \
   case MV:                                                                                                            \
-    if (rms) ln_bwd_kernel<T, MV, true><<<nblocks, kThreads, 0, s>>>(du, x, mean, rstd, gamma, resid, out, out_lowp, part_g, part_b, rows, H); \
-    else ln_bwd_kernel<T, MV, false><<<nblocks, kThreads, 0, s>>>(du, x, mean, rstd, gamma, resid, out, out_lowp, part_g, part_b, rows, H); \
+    if (rms) ln_bwd_kernel<T, MV, true, false><<<nblocks, kThreads, 0, s>>>(du, x, mean, rstd, gamma, resid, out, out_lowp, part_g, part_b, nullptr, rows, H); \
+    else if (part_s) ln_bwd_kernel<T, MV, false, true><<<nblocks, kThreads, 0, s>>>(du, x, mean, rstd, gamma, resid, out, out_lowp, part_g, part_b, part_s, rows, H); \
+    else ln_bwd_kernel<T, MV, false, false><<<nblocks, kThreads, 0, s>>>(du, x, mean, rstd, gamma, resid, out, out_lowp, part_g, part_b, nullptr, rows, H); \
     break;
   switch (mv) {
     LN_BWD_CASE(1) LN_BWD_CASE(2) LN_BWD_CASE(4)
@@ -509,7 +523,7 @@ int launch_swiglu_fwd(const T* gu, T* h, int64_t rows, int F, hipStream_t s) {
 #define INSTANTIATE(T)                                                                                          \
   template int launch_ln_fwd<T>(const float*, const T*, const T*, T*, float*, float*, int, int, float, hipStream_t, bool); \
   template int launch_ln_bwd<T>(const float*, const float*, const float*, const float*, const T*, const float*, float*, \
-                                T*, float*, float*, int, int, hipStream_t, bool);                                 \
+                                T*, float*, float*, int, int, hipStream_t, bool, float*);                         \
   template int launch_rotary<T>(T*, const float*, int, int, int, int, int, hipStream_t);                          \
   template int launch_swiglu_fwd<T>(const T*, T*, int64_t, int, hipStream_t);                                     \
   template int launch_colsum<T>(const T*, float*, size_t, float*, float, int, int, int, hipStream_t);

@@ -188,10 +188,11 @@ int launch_ln_fwd(const float* x, const T* gamma, const T* beta, T* u, float* me
 // of dgamma (du * xhat) and dbeta (du) to part_g / part_b ([ln_bwd_blocks(rows)][H] fp32 each);
 // launch_reduce_partials folds any number of such partial rows into a flat-gradient slice:
 //   g = (accumulate ? g : 0) + scale * sum over chunks.
+// part_s, if not null (LayerNorm form only): the blocks' column sums of `out`, laid out like part_g.
 template <typename T>
 int launch_ln_bwd(const float* du, const float* x, const float* mean, const float* rstd, const T* gamma,
                   const float* resid, float* out, T* out_lowp, float* part_g, float* part_b, int rows, int H, hipStream_t s,
-                  bool rms = false);
+                  bool rms = false, float* part_s = nullptr);
 int ln_bwd_blocks(int rows);
 
 // Rotary position embedding in place on the Q and K thirds of qkv [rows, 3H] (row % S = position, pairs (2i, 2i+1) of

@@ -143,7 +143,7 @@ ScratchLayout scratch_layout(const cephalo_layer_desc& d, int m, int span, int s
   L.rs_part_bytes = (es != 4 && !is_llama(d)) ? std::max(gemm_rowsum_part_bytes((int)(3 * H), (int)H), gemm_rowsum_part_bytes((int)F1, (int)H)) : 0;
   L.rs_part = take(L.rs_part_bytes);
   L.ln_rows = (size_t)(span / m) * ln_bwd_blocks((int)Tm);
-  L.ln_part = take(4 * L.ln_rows * H * sizeof(float));
+  L.ln_part = take(6 * L.ln_rows * H * sizeof(float));      // d gamma and d beta of both norms, and the column sums of the two LayerNorm backwards' results
   const int widest = (int)(3 * H > F1 ? 3 * H : F1);
   L.col_part_bytes = colsum_partial_bytes((int)Ts, widest);
   L.col_part = take(L.col_part_bytes);
@@ -288,6 +288,7 @@ template <typename T> struct Work {
   T *dO, *wT;
   float *du2, *du, *dvec;
   float *ln2_g, *ln2_b, *ln1_g, *ln1_b;   // LayerNorm partial sums, at the row offset of the current micro-batch
+  float *ln2_s, *ln1_s;                   // column sums of dx1 and of dx, block by block like the above (GPT-style layer)
   float *col_part; size_t col_part_bytes;
   float *wg_part;
   float *rs_part; size_t rs_part_bytes;
@@ -304,6 +305,7 @@ Work<T> work_at(void* base, const ScratchLayout& W, const cephalo_layer_desc& d,
   float* ln = at<float>(base, W.ln_part);
   const size_t r0 = (size_t)mb_index * ln_bwd_blocks(m * d.seq) * H, arr = W.ln_rows * H;
   w.ln2_g = ln + r0; w.ln2_b = ln + arr + r0; w.ln1_g = ln + 2 * arr + r0; w.ln1_b = ln + 3 * arr + r0;
+  w.ln2_s = ln + 4 * arr + r0; w.ln1_s = ln + 5 * arr + r0;
   w.col_part = at<float>(base, W.col_part); w.col_part_bytes = W.col_part_bytes;
   w.wg_part = at<float>(base, W.wg_part);
   w.rs_part = at<float>(base, W.rs_part); w.rs_part_bytes = W.rs_part_bytes;
@@ -450,7 +452,7 @@ int layer_bwd_data_t(const cephalo_layer_desc& d, const T* P, const float* x, co
     TRY(gemm<T>(a, s));
   }
   // u2 = LN2(x1); dx1 = dy + LN2-backward(du2)
-  TRY(launch_ln_bwd<T>(w.du2, sv.x1, sv.mean2, sv.rstd2, P + o.ln2_g, dy, w.dx1, lowp_out<T>(w.dx1l), w.ln2_g, w.ln2_b, Tn, H, s));
+  TRY(launch_ln_bwd<T>(w.du2, sv.x1, sv.mean2, sv.rstd2, P + o.ln2_g, dy, w.dx1, lowp_out<T>(w.dx1l), w.ln2_g, w.ln2_b, Tn, H, s, false, w.ln2_s));
   {
     GemmArgs<T> a = dgrad_args<T>(lowp_of<T>(w.dx1, w.dx1l), P, w.wT, o.w_o, Tn, H, H);
     a.epi = EPI_NONE; a.C = w.dO;
@@ -463,17 +465,21 @@ int layer_bwd_data_t(const cephalo_layer_desc& d, const T* P, const float* x, co
     TRY(gemm<T>(a, s));
   }
   // u = LN1(x); dx = dx1 + LN1-backward(du)
-  TRY(launch_ln_bwd<T>(w.du, x, sv.mean1, sv.rstd1, P + o.ln1_g, w.dx1, dx, lowp_out<T>(dxl), w.ln1_g, w.ln1_b, Tn, H, s));
+  TRY(launch_ln_bwd<T>(w.du, x, sv.mean1, sv.rstd1, P + o.ln1_g, w.dx1, dx, lowp_out<T>(dxl), w.ln1_g, w.ln1_b, Tn, H, s, false, w.ln1_s));
   return CEPHALO_OK;
 }
 
 // ---- backward, parameter path over `tokens` tokens (one micro-batch, or the whole share at once) ---------------------
 // G <- (acc ? G : 0) + scale * (gradient summed over those tokens).  Over the whole share the sum over micro-batches
 // happens inside the fp32 MFMA accumulators and each gradient element is written exactly once.  Bias gradients of the
-// two residual-stream projections are column sums of the fp32 gradients.
+// two residual-stream projections are column sums of the fp32 gradients of the stream: of dx1 (out-projection), which
+// the backward of the second LayerNorm has summed block by block as it wrote it, and of dy (second feed-forward
+// projection), summed here unless the caller passes none.  A caller whose dy was the dx of the layer above (a stack)
+// passes null and gives that layer `b_fc2_below` instead: where the sums of its dx go, with the same scale / acc.
 template <typename T>
 int layer_bwd_params_t(const cephalo_layer_desc& d, const float* dy, const T* dyl, int tokens, int ln_chunks,
-                       const Saved<T>& sv, const Work<T>& w, float* G, float scale, int acc, hipStream_t s, hipStream_t s2 = nullptr) {
+                       const Saved<T>& sv, const Work<T>& w, float* G, float scale, int acc, hipStream_t s, hipStream_t s2 = nullptr,
+                       float* b_fc2_below = nullptr) {
   if (!s2) s2 = s;      // s2: where the bandwidth-bound reductions (bias column sums, norm-parameter partials) run, beside the GEMMs on s
   const ParamOffsets o = param_offsets(d);
   const int H = d.hidden, F = d.mlp;
@@ -486,9 +492,9 @@ int layer_bwd_params_t(const cephalo_layer_desc& d, const float* dy, const T* dy
     TRY(launch_reduce_partials(w.ln1_g, ln_chunks, H, G + o.ln1_g, scale, acc, w.col_part, w.col_part_bytes, s2));
     return CEPHALO_OK;
   }
-  // The bias gradients of the two projections into the residual stream are column sums of fp32 gradients and have a
-  // kernel of their own; those of the other two are sums of the very bf16 values their weight-gradient GEMMs read, and
-  // the GEMMs form them on the way.
+  // (the other two bias gradients are sums of the very bf16 values their weight-gradient GEMMs read, and the GEMMs form
+  // them on the way)
+  if (b_fc2_below) TRY(launch_reduce_partials(w.ln1_s, ln_chunks, H, b_fc2_below, scale, acc, w.col_part, w.col_part_bytes, s2));
   if (dy) TRY(launch_colsum<float>(dy, w.col_part, w.col_part_bytes, G + o.b_fc2, scale, acc, tokens, H, s2));   // (null: the caller has summed it already)
   TRY(wgrad<T>(dyl, sv.h, tokens, H, F, G + o.w_fc2, scale, acc, w.wg_part, s));
   {
@@ -498,7 +504,7 @@ int layer_bwd_params_t(const cephalo_layer_desc& d, const float* dy, const T* dy
   }
   TRY(launch_reduce_partials(w.ln2_g, ln_chunks, H, G + o.ln2_g, scale, acc, w.col_part, w.col_part_bytes, s2));
   TRY(launch_reduce_partials(w.ln2_b, ln_chunks, H, G + o.ln2_b, scale, acc, w.col_part, w.col_part_bytes, s2));
-  TRY(launch_colsum<float>(w.dx1, w.col_part, w.col_part_bytes, G + o.b_o, scale, acc, tokens, H, s2));
+  TRY(launch_reduce_partials(w.ln2_s, ln_chunks, H, G + o.b_o, scale, acc, w.col_part, w.col_part_bytes, s2));
   TRY(wgrad<T>(lowp_of<T>(w.dx1, w.dx1l), sv.O, tokens, H, H, G + o.w_o, scale, acc, w.wg_part, s));
   {
     ColsumsBeside cb = {G + o.b_qkv, w.rs_part, w.rs_part_bytes, false};

@@ -435,7 +435,7 @@ StackLayout stack_layout(const cephalo_stack_desc& d, int b, int m) {
   L.wteT = es == 4 ? 0 : take(H * (size_t)L.ldv * es);   // wte^T [H, ldv] for the input gradient of the LM head
   L.loss = take(n * 4);
   L.lnf_rows = (size_t)(b / m) * ln_bwd_blocks((int)Tm);
-  L.lnf_part = take(2 * L.lnf_rows * H * 4);
+  L.lnf_part = take(3 * L.lnf_rows * H * 4);      // d gamma, d beta, and the column sums of the gradient the last layer receives
   L.keys = take((size_t)sort_pad((int)n) * sizeof(u64));      // (id, token index) keys of the embedding gradient's sort
   L.embed_part = take((size_t)embed_segments((int)n) * 2 * H * 4);   // pieces of runs of equal ids that cross a segment boundary
   L.total = p;
@@ -594,7 +594,7 @@ int run_stack(const cephalo_stack_desc& d, const void* Pv, const int* ids, const
   // ---- head: final LN, tied logits (fp32, one micro-batch at a time), cross-entropy and its gradient, back to the last layer's output
   T* uf = at<T>(ws, L.uf); float* logits = at<float>(ws, L.logits); T* dlogits = at<T>(ws, L.dlogits); float* duf = at<float>(ws, L.duf);
   float* meanf = at<float>(ws, L.meanf); float* rstdf = at<float>(ws, L.rstdf);
-  float* lnf_g = at<float>(ws, L.lnf_part); float* lnf_b = lnf_g + L.lnf_rows * H;
+  float* lnf_g = at<float>(ws, L.lnf_part); float* lnf_b = lnf_g + L.lnf_rows * H; float* lnf_s = lnf_b + L.lnf_rows * H;
   float* dx_cur = at<float>(ws, L.dxa); float* dx_nxt = at<float>(ws, L.dxb);
   T* dxl_cur = at<T>(ws, L.dxal); T* dxl_nxt = at<T>(ws, L.dxbl);
   const float coef = scale / (float)n;
@@ -623,7 +623,8 @@ int run_stack(const cephalo_stack_desc& d, const void* Pv, const int* ids, const
     }
     float* dxo = Gx.offload ? Gx.out(NL % 2, j) : dx_cur + t0 * H;
     TRY(launch_ln_bwd<T>(duf_j, xL, meanf + t0, rstdf + t0, P + o_lnf, (const float*)nullptr, dxo,
-                         lowp_out<T>(dxl_cur + t0 * H), lnf_g + (size_t)j * nb * H, lnf_b + (size_t)j * nb * H, Tm, H, sj, rms));
+                         lowp_out<T>(dxl_cur + t0 * H), lnf_g + (size_t)j * nb * H, lnf_b + (size_t)j * nb * H, Tm, H, sj, rms,
+                         rms ? (float*)nullptr : lnf_s + (size_t)j * nb * H));
     Gx.out_done(NL % 2, j);
     X.in_done();
   }
@@ -636,6 +637,10 @@ int run_stack(const cephalo_stack_desc& d, const void* Pv, const int* ids, const
     TRY(wgrad<T>(dlogits, uf, n, V, H, G + o_head, 1.0f, 0, (float*)nullptr, s, L.ldv));       // the head's gradient (tied: the head's part of d wte), whole share
     TRY(launch_reduce_partials(lnf_g, l * nb, H, G + o_lnf, 1.0f, 0, w.col_part, w.col_part_bytes, s));
     if (!rms) TRY(launch_reduce_partials(lnf_b, l * nb, H, G + o_lnf + H, 1.0f, 0, w.col_part, w.col_part_bytes, s));
+    // The bias gradient of a layer's second feed-forward projection is the column sum of the gradient arriving at the
+    // layer's output.  Whoever produces that gradient (the final norm's backward here, the layer above further down)
+    // sums it block by block as it writes it.
+    if (!rms) TRY(launch_reduce_partials(lnf_s, l * nb, H, G + o_layers + (size_t)(NL - 1) * PL + param_offsets(ld).b_fc2, 1.0f, 0, w.col_part, w.col_part_bytes, s));
   }
   // ---- backward through the layers
   for (int li = NL - 1; li >= 0; --li) {
@@ -658,9 +663,6 @@ int run_stack(const cephalo_stack_desc& d, const void* Pv, const int* ids, const
       const float* dyj = Gx.offload ? Gx.in((li + 1) % 2, j, l) : dx_cur + j * act;
       Gx.prefetch((li + 1) % 2, j + 1, l);
       float* dxj = !Gx.offload ? dx_nxt + j * act : (li == 0 ? at<float>(ws, L.dxa) + j * act : Gx.out(li % 2, j));
-      if (Gx.offload && !rms)      // the bias gradient of the second feed-forward projection sums this gradient's columns: now, while it is here
-        TRY(launch_colsum<float>(dyj, work_at<T>(scratch, WL, ld, 0, 0, m).col_part, work_at<T>(scratch, WL, ld, 0, 0, m).col_part_bytes,
-                                 G + o_layers + li * PL + param_offsets(ld).b_fc2, 1.0f, j > 0, Tm, H, st[j % nst]));
       TRY(layer_bwd_data_t<T>(ld, Pl, xi, dyj, dxl_cur + j * act, dxj,
                               dxl_nxt + j * act, m, saved_at<T>(save, SL, ld, j * m), work_at<T>(scratch, WL, ld, j * m, j, m, j % nst), st[j % nst]));
       Gx.in_done();
@@ -670,8 +672,9 @@ int run_stack(const cephalo_stack_desc& d, const void* Pv, const int* ids, const
     J.join();
     hint.now(1);
     J.fork();        // the parameter pass: weight-gradient GEMMs on the main stream, the bandwidth-bound reductions beside them
-    TRY(layer_bwd_params_t<T>(ld, Gx.offload ? (const float*)nullptr : dx_cur, Gx.offload ? dxl_cur : lowp_of<T>(dx_cur, dxl_cur), n, l * nb,
-                              saved_at<T>(save, SL, ld, 0), work_at<T>(scratch, WL, ld, 0, 0, m), G + o_layers + li * PL, 1.0f, 0, s, st[1]));
+    TRY(layer_bwd_params_t<T>(ld, (const float*)nullptr, Gx.offload ? dxl_cur : lowp_of<T>(dx_cur, dxl_cur), n, l * nb,
+                              saved_at<T>(save, SL, ld, 0), work_at<T>(scratch, WL, ld, 0, 0, m), G + o_layers + li * PL, 1.0f, 0, s, st[1],
+                              (!rms && li > 0) ? G + o_layers + (size_t)(li - 1) * PL + param_offsets(ld).b_fc2 : (float*)nullptr));
     J.join();
     { float* t = dx_cur; dx_cur = dx_nxt; dx_nxt = t; }
     { T* t = dxl_cur; dxl_cur = dxl_nxt; dxl_nxt = t; }

@@ -259,9 +259,9 @@ def test_residual_stream_gradients_offloaded_to_host_as_well(case):
     host memory (the supplementary figure's transfers GC^g / CG^g): a micro-batch's gradient leaves when a layer's
     backward has produced it and returns, one micro-batch ahead, when the layer below needs it; the device keeps four
     micro-batch slots instead of a second [b*S, H] buffer.  Same kernels on the same values, so the loss and every
-    gradient element are bit-identical to the resident run, but for the bias gradient of the second feed-forward
-    projection, whose column sum is now formed micro-batch by micro-batch (each micro-batch's fp32 gradient is on the
-    device only then) and agrees to fp32 rounding.  The step is also compared with the oracle on its own, and the
+    gradient element are bit-identical to the resident run (the bias gradient of the second feed-forward projection,
+    the column sum of a gradient that is on the device one micro-batch at a time, included: the norm backward that
+    produces the gradient sums it block by block in both forms).  The step is also compared with the oracle on its own, and the
     host area must end up holding the boundary activations and, behind them, the gradient with respect to the
     embedding output's successor boundaries as the resident run leaves them in its work area."""
     cfg = CASES[case]
@@ -271,10 +271,6 @@ def test_residual_stream_gradients_offloaded_to_host_as_well(case):
     a_loss, a_G, sd_res = run_gpu(cfg, params, ids, tgt, 0.75, checkpoint=True)
     sd = C.stack_desc_from_config(cfg, True, 2)
     P = C.cephalo_stack_param_count(sd)
-    PL = C.cephalo_layer_param_count(sd.layer)
-    offs = dict(zip(C.LAYER_TENSOR_NAMES, C.cephalo_layer_param_offsets(sd.layer)))
-    base = (cfg.vocab + S) * H
-    bias_spans = [(base + li * PL + offs["b_fc2"], base + li * PL + offs["b_fc2"] + H) for li in range(L)]
     n_act = b * S * H
     assert C.cephalo_stack_host_bytes(sd, b, m) == (L + 3) * n_act * 4
     flat32 = torch.from_numpy(C.flatten_stack_params(sd, params)).cuda()
@@ -290,11 +286,7 @@ def test_residual_stream_gradients_offloaded_to_host_as_well(case):
         torch.cuda.current_stream().synchronize()
         Gh = G.cpu().numpy()
         assert float(loss.item()) == a_loss
-        mask = np.ones(P, dtype=bool)
-        for lo, hi in bias_spans:
-            mask[lo:hi] = False
-            assert rel_errors(Gh[lo:hi], a_G[lo:hi])[0] <= 1e-5
-        assert np.array_equal(Gh[mask], a_G[mask])
+        assert np.array_equal(Gh, a_G)
     # less device memory than with the activations alone offloaded, by a [b*S, H] fp32 buffer minus four micro-batch slots
     ws1 = C.cephalo_stack_workspace_bytes(C.stack_desc_from_config(cfg, True, 1), b, m)
     assert ws1 - ws.numel() >= n_act * 4 - 4 * m * S * H * 4 - 4096
