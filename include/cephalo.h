@@ -279,6 +279,11 @@ int cephalo_op_linear_wgrad_static(int32_t dtype, const void* dY, const void* X,
  *   rms: the mean_h(g) term is absent); dx_lowp, if not NULL, receives dx in the activation type as well;
  *   dgamma[h] = sum_r du * xhat, dbeta[h] = sum_r du (rms: dbeta untouched, may be NULL), summed in a fixed order.
  *   workspace: device, cephalo_op_norm_bwd_workspace(rows, H) bytes.
+ * norm_bwd_sums: norm_bwd in the LayerNorm form (no rms) that also returns dx_colsum[h] = sum_r dx[r][h] (fp32, fixed
+ *   order): dx is a gradient of the residual stream, and its column sum is the bias gradient of the projection whose
+ *   output was added to the stream there (Sec. 3.2's accumulated gradient holds it), so the kernel that writes dx sums
+ *   it on the way.  dx, dx_lowp, dgamma, dbeta are bit-identical to norm_bwd's.  workspace:
+ *   cephalo_op_norm_bwd_sums_workspace(rows, H) bytes.
  * colsum: g[n] = (accumulate ? g[n] : 0) + scale * sum_r X[r][n], X [rows, N] in dtype (a bias gradient), fixed order.
  * cross_entropy: for each row of fp32 logits [rows, ld] (V valid columns, ld >= V a multiple of 8):
  *   loss_rows[r] = logsumexp(row) - row[target],  dlogits[r] = coef * (softmax(row) - onehot(target)) in dtype, columns
@@ -290,6 +295,10 @@ size_t cephalo_op_norm_bwd_workspace(int32_t rows, int32_t H);
 int cephalo_op_norm_bwd(int32_t dtype, int32_t rms, const float* du, const float* x, const float* mean, const float* rstd,
                         const void* gamma, const float* resid, float* dx, void* dx_lowp, float* dgamma, float* dbeta,
                         int32_t rows, int32_t H, void* workspace, size_t workspace_bytes, void* stream);
+size_t cephalo_op_norm_bwd_sums_workspace(int32_t rows, int32_t H);
+int cephalo_op_norm_bwd_sums(int32_t dtype, const float* du, const float* x, const float* mean, const float* rstd,
+                             const void* gamma, const float* resid, float* dx, void* dx_lowp, float* dgamma, float* dbeta,
+                             float* dx_colsum, int32_t rows, int32_t H, void* workspace, size_t workspace_bytes, void* stream);
 size_t cephalo_op_colsum_workspace(int32_t rows, int32_t N);
 int cephalo_op_colsum(int32_t dtype, const void* X, int32_t rows, int32_t N, float* g, float scale, int32_t accumulate,
                       void* workspace, size_t workspace_bytes, void* stream);

@@ -99,6 +99,8 @@ SIGNATURES = {
     "cephalo_op_linear_wgrad_static": (ctypes.c_int, [_i32, _vp, _vp, _i32, _i32, _i32, _vp, _f32, _i32, _vp]),
     "cephalo_op_norm_fwd": (ctypes.c_int, [_i32, _i32, _vp, _vp, _vp, _vp, _vp, _vp, _i32, _i32, _f32, _vp]),
     "cephalo_op_norm_bwd_workspace": (_sz, [_i32, _i32]),
+    "cephalo_op_norm_bwd_sums_workspace": (_sz, [_i32, _i32]),
+    "cephalo_op_norm_bwd_sums": (ctypes.c_int, [_i32, _vp, _vp, _vp, _vp, _vp, _vp, _vp, _vp, _vp, _vp, _vp, _i32, _i32, _vp, _sz, _vp]),
     "cephalo_op_norm_bwd": (ctypes.c_int, [_i32, _i32, _vp, _vp, _vp, _vp, _vp, _vp, _vp, _vp, _vp, _vp, _i32, _i32, _vp, _sz, _vp]),
     "cephalo_op_colsum_workspace": (_sz, [_i32, _i32]),
     "cephalo_op_colsum": (ctypes.c_int, [_i32, _vp, _i32, _i32, _vp, _f32, _i32, _vp, _sz, _vp]),
@@ -264,6 +266,16 @@ def cephalo_op_norm_fwd(dtype, rms, x, gamma, beta, u, mean, rstd, rows, H, eps,
 
 def cephalo_op_norm_bwd_workspace(rows, H):
     return int(lib().cephalo_op_norm_bwd_workspace(rows, H))
+
+
+def cephalo_op_norm_bwd_sums_workspace(rows, H):
+    return int(lib().cephalo_op_norm_bwd_sums_workspace(rows, H))
+
+
+def cephalo_op_norm_bwd_sums(dtype, du, x, mean, rstd, gamma, resid, dx, dx_lowp, dgamma, dbeta, dx_colsum, rows, H, workspace, stream=None):
+    _check(lib().cephalo_op_norm_bwd_sums(dtype, _ptr(du), _ptr(x), _ptr(mean), _ptr(rstd), _ptr(gamma), _ptr(resid), _ptr(dx),
+                                          _ptr(dx_lowp), _ptr(dgamma), _ptr(dbeta), _ptr(dx_colsum), rows, H, _ptr(workspace),
+                                          workspace.numel() * workspace.element_size(), _stream(stream)))
 
 
 def cephalo_op_norm_bwd(dtype, rms, du, x, mean, rstd, gamma, resid, dx, dx_lowp, dgamma, dbeta, rows, H, workspace, stream=None):

@@ -61,6 +61,38 @@ extern "C" int cephalo_op_norm_bwd(int32_t dtype, int32_t rms, const float* du, 
   return CEPHALO_OK;
 }
 
+// norm_bwd in the LayerNorm form with the column sums of its result as a third reduction
+extern "C" size_t cephalo_op_norm_bwd_sums_workspace(int32_t rows, int32_t H) {
+  if (rows <= 0 || H <= 0) return 0;
+  return (3 * norm_bwd_part_floats(rows, H)) * sizeof(float) + reduce_tmp_bytes(ln_bwd_blocks(rows), H) + 256;
+}
+
+extern "C" int cephalo_op_norm_bwd_sums(int32_t dtype, const float* du, const float* x, const float* mean, const float* rstd,
+                                        const void* gamma, const float* resid, float* dx, void* dx_lowp, float* dgamma, float* dbeta,
+                                        float* dx_colsum, int32_t rows, int32_t H, void* workspace, size_t workspace_bytes, void* stream) {
+  TRY(check_norm("norm_bwd_sums", dtype, rows, H));
+  if (!du || !x || !mean || !rstd || !gamma || !dx || !dgamma || !dbeta || !dx_colsum || !workspace) return fail(CEPHALO_EINVAL, "norm_bwd_sums: null buffer");
+  if (!all_aligned({du, x, gamma, resid, dx, dx_lowp, dgamma, dbeta, dx_colsum, workspace})) return fail(CEPHALO_EINVAL, "norm_bwd_sums: buffers must be 16-byte aligned");
+  if (workspace_bytes < cephalo_op_norm_bwd_sums_workspace(rows, H))
+    return fail(CEPHALO_EWORKSPACE, "norm_bwd_sums: workspace %zu B < %zu B", workspace_bytes, cephalo_op_norm_bwd_sums_workspace(rows, H));
+  hipStream_t s = static_cast<hipStream_t>(stream);
+  const int nb = ln_bwd_blocks(rows);
+  const size_t each = norm_bwd_part_floats(rows, H);
+  float* part_g = static_cast<float*>(workspace);
+  float* part_b = part_g + each;
+  float* part_s = part_b + each;
+  float* tmp = part_s + each;
+  const size_t tmp_bytes = reduce_tmp_bytes(nb, H);
+  if (dtype == CEPHALO_F32)
+    TRY(launch_ln_bwd<float>(du, x, mean, rstd, static_cast<const float*>(gamma), resid, dx, static_cast<float*>(nullptr), part_g, part_b, rows, H, s, false, part_s));
+  else
+    TRY(launch_ln_bwd<bf16>(du, x, mean, rstd, static_cast<const bf16*>(gamma), resid, dx, static_cast<bf16*>(dx_lowp), part_g, part_b, rows, H, s, false, part_s));
+  TRY(launch_reduce_partials(part_g, nb, H, dgamma, 1.0f, 0, tmp, tmp_bytes, s));
+  TRY(launch_reduce_partials(part_b, nb, H, dbeta, 1.0f, 0, tmp, tmp_bytes, s));
+  TRY(launch_reduce_partials(part_s, nb, H, dx_colsum, 1.0f, 0, tmp, tmp_bytes, s));
+  return CEPHALO_OK;
+}
+
 extern "C" size_t cephalo_op_colsum_workspace(int32_t rows, int32_t N) {
   if (rows <= 0 || N <= 0) return 0;
   return colsum_partial_bytes(rows, N) + 256;

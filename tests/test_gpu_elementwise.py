@@ -74,6 +74,21 @@ def test_norm_forward_and_backward(rows, H, bf16, rms):
         assert rel_errors(db.double().cpu().numpy(), db_ref)[0] <= 1e-4
     if bf16:
         assert torch.equal(dxl, dx.to(torch.bfloat16))            # the operand copy is the rounding of the fp32 result
+    if not rms:
+        # the same with the column sums of dx (the bias gradient of the projection whose output joined the stream there)
+        ws3 = torch.empty(C.cephalo_op_norm_bwd_sums_workspace(rows, H), dtype=torch.uint8, device="cuda")
+        ws3.fill_(0xFF)
+        dx2, dg2, db2 = torch.full_like(dx, float("nan")), torch.full_like(dg, float("nan")), torch.full_like(db, float("nan"))
+        dxl2 = torch.full_like(dxl, float("nan")) if bf16 else None
+        dsum = torch.full((H,), float("nan"), device="cuda")
+        C.cephalo_op_norm_bwd_sums(dt, torch.from_numpy(du).cuda(), dx_, mean, rstd, dgam, torch.from_numpy(resid).cuda(), dx2, dxl2,
+                                   dg2, db2, dsum, rows, H, ws3)
+        torch.cuda.synchronize()
+        assert torch.equal(dx2, dx) and torch.equal(dg2, dg) and torch.equal(db2, db)
+        if bf16:
+            assert torch.equal(dxl2, dxl)
+        assert rel_errors(dsum.double().cpu().numpy(), dx.double().cpu().numpy().sum(axis=0))[0] <= 1e-5   # sums of the very values written
+        assert rel_errors(dsum.double().cpu().numpy(), (dx_ref + resid).sum(axis=0))[0] <= 1e-4
     # without a residual
     C.cephalo_op_norm_bwd(dt, rms, torch.from_numpy(du).cuda(), dx_, mean, rstd, dgam, None, dx, dxl, dg, None if rms else db, rows, H, ws)
     torch.cuda.synchronize()
