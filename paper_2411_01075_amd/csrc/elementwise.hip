@@ -44,46 +44,53 @@ ln_fwd_kernel(const float* __restrict__ x, const T* __restrict__ gamma, const T*
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
   const int nv = H / VN;
   const float inv_h = 1.0f / (float)H;
+  // Straight-line code: a lane whose 16-byte group lies past the row reads the row's first group instead and its
+  // values are replaced by zeros; only the stores are predicated.  (With each group's loads under its own bounds
+  // branch the compiler waited for one group before it asked for the next, and for every group's store before the next
+  // group's gamma and beta: eight memory round trips in a row per row of the matrix.)
+  typedef typename Vec<T>::raw RawT;
   for (int row = blockIdx.x * kWaves + wave; row < rows; row += gridDim.x * kWaves) {
     const float* xr = x + (int64_t)row * H;
     float vals[MAXV][VN];
+    constexpr bool EARLY = MAXV <= 8;      // gamma and beta asked for with the row (the widest rows have no registers for that)
+    RawT gr[MAXV], br[MAXV];
+#pragma unroll
+    for (int j = 0; j < MAXV; ++j) {
+      const int v = lane + 64 * j, vc = v < nv ? v : 0;
+      load_f32<VN>(xr + vc * VN, vals[j]);
+      if (EARLY) {
+        gr[j] = *reinterpret_cast<const RawT*>(gamma + vc * VN);
+        if (!RMS) br[j] = *reinterpret_cast<const RawT*>(beta + vc * VN);
+      }
+    }
     float sum = 0.f;
 #pragma unroll
     for (int j = 0; j < MAXV; ++j) {
-      const int v = lane + 64 * j;
-      if (v < nv) {
-        load_f32<VN>(xr + v * VN, vals[j]);
+      const bool ok = lane + 64 * j < nv;
 #pragma unroll
-        for (int i = 0; i < VN; ++i) sum += vals[j][i];
-      }
+      for (int i = 0; i < VN; ++i) { vals[j][i] = ok ? vals[j][i] : 0.f; sum += vals[j][i]; }
     }
     const float mu = RMS ? 0.f : wave_sum(sum) * inv_h;
     float sq = 0.f;
 #pragma unroll
     for (int j = 0; j < MAXV; ++j) {
-      if (lane + 64 * j < nv) {
+      const bool ok = lane + 64 * j < nv;
 #pragma unroll
-        for (int i = 0; i < VN; ++i) { const float d = vals[j][i] - mu; sq += d * d; }
-      }
+      for (int i = 0; i < VN; ++i) { const float d = ok ? vals[j][i] - mu : 0.f; sq += d * d; }
     }
     const float rs = 1.0f / sqrtf(wave_sum(sq) * inv_h + eps);
     T* ur = u + (int64_t)row * H;
 #pragma unroll
     for (int j = 0; j < MAXV; ++j) {
-      const int v = lane + 64 * j;
-      if (v < nv) {
-        float g[VN], b[VN], o[VN];
-        load_vec<T>(gamma + v * VN, g);
-        if (RMS) {
-#pragma unroll
-          for (int i = 0; i < VN; ++i) b[i] = 0.f;
-        } else {
-          load_vec<T>(beta + v * VN, b);
-        }
-#pragma unroll
-        for (int i = 0; i < VN; ++i) o[i] = g[i] * ((vals[j][i] - mu) * rs) + b[i];
-        store_vec<T>(ur + v * VN, o);
+      const int v = lane + 64 * j, vc = v < nv ? v : 0;
+      if (!EARLY) {
+        gr[j] = *reinterpret_cast<const RawT*>(gamma + vc * VN);
+        if (!RMS) br[j] = *reinterpret_cast<const RawT*>(beta + vc * VN);
       }
+      float o[VN];
+#pragma unroll
+      for (int i = 0; i < VN; ++i) o[i] = (float)gr[j][i] * ((vals[j][i] - mu) * rs) + (RMS ? 0.f : (float)br[j][i]);
+      if (v < nv) store_vec<T>(ur + v * VN, o);
     }
     if (lane == 0) { mean[row] = mu; rstd[row] = rs; }
   }
