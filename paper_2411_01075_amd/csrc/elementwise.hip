@@ -153,20 +153,21 @@ ln_bwd_kernel(const float* __restrict__ du, const float* __restrict__ x, const f
       const int row = row0 + step * R + r;
 #pragma unroll
       for (int j = 0; j < MV; ++j) {
+        // (no branch around the loads: a group past the last row or the row's end reads a valid one instead and is
+        // replaced by zeros -- it contributes nothing and is not stored; with the loads under bounds branches the
+        // compiler waits for all of them at once and the rows asked for ahead do not overlap the arithmetic)
         const int v = threadIdx.x + kThreads * j;
-        if (row < rows && v < nv) {
-          const int64_t o = (int64_t)row * H + v * VN;
-          load_f32<VN>(du + o, b.d[r][j]);
-          load_f32<VN>(x + o, b.xv[r][j]);
-          if (resid) {
-            load_f32<VN>(resid + o, b.rr[r][j]);
-          } else {
+        const bool ok = row < rows && v < nv;
+        const int64_t o = (int64_t)min(row, rows - 1) * H + (v < nv ? v : 0) * VN;
+        load_f32<VN>(du + o, b.d[r][j]);
+        load_f32<VN>(x + o, b.xv[r][j]);
+        load_f32<VN>((resid ? resid : x) + o, b.rr[r][j]);
+        const bool keep = ok && resid != nullptr;
 #pragma unroll
-            for (int i = 0; i < VN; ++i) b.rr[r][j][i] = 0.f;
-          }
-        } else {       // past the last row or the row's end: contributes nothing, is not stored
-#pragma unroll
-          for (int i = 0; i < VN; ++i) { b.d[r][j][i] = 0.f; b.xv[r][j][i] = 0.f; b.rr[r][j][i] = 0.f; }
+        for (int i = 0; i < VN; ++i) {
+          b.d[r][j][i] = ok ? b.d[r][j][i] : 0.f;
+          b.xv[r][j][i] = ok ? b.xv[r][j][i] : 0.f;
+          b.rr[r][j][i] = keep ? b.rr[r][j][i] : 0.f;
         }
       }
     }
