@@ -27,6 +27,9 @@ SHAPES = [  # tokens T, out features N, in features K
     (520, 328, 72),       # ragged in all three, k not a multiple of the 64-slab
     (1024, 3072, 1024),   # the BERT-large-shaped QKV projection
     (64, 64, 64),
+    (1, 8, 8),            # one row, one group of 8 columns
+    (8, 72, 40),          # less than a wavefront's 64 rows, less than a k-slab
+    (72, 2056, 264),      # a last tile column of 8 columns, a second wavefront row of 8 rows
 ]
 
 
