@@ -52,16 +52,11 @@ ln_fwd_kernel(const float* __restrict__ x, const T* __restrict__ gamma, const T*
   for (int row = blockIdx.x * kWaves + wave; row < rows; row += gridDim.x * kWaves) {
     const float* xr = x + (int64_t)row * H;
     float vals[MAXV][VN];
-    constexpr bool EARLY = MAXV <= 8;      // gamma and beta asked for with the row (the widest rows have no registers for that)
     RawT gr[MAXV], br[MAXV];
 #pragma unroll
     for (int j = 0; j < MAXV; ++j) {
       const int v = lane + 64 * j, vc = v < nv ? v : 0;
       load_f32<VN>(xr + vc * VN, vals[j]);
-      if (EARLY) {
-        gr[j] = *reinterpret_cast<const RawT*>(gamma + vc * VN);
-        if (!RMS) br[j] = *reinterpret_cast<const RawT*>(beta + vc * VN);
-      }
     }
     float sum = 0.f;
 #pragma unroll
@@ -71,6 +66,19 @@ ln_fwd_kernel(const float* __restrict__ x, const T* __restrict__ gamma, const T*
       for (int i = 0; i < VN; ++i) { vals[j][i] = ok ? vals[j][i] : 0.f; sum += vals[j][i]; }
     }
     const float mu = RMS ? 0.f : wave_sum(sum) * inv_h;
+    // gamma and beta (in L2: every row reads the same) are asked for here, all at once, and arrive under the second
+    // reduction; asked for with the row they cost 50 registers more and a third of the rows in flight per SIMD
+    constexpr bool EARLY = MAXV <= 8;      // (the widest rows: no registers for that either, they load them group by group)
+    if (EARLY) {
+#pragma unroll
+      for (int j = 0; j < MAXV; ++j) {
+        const int v = lane + 64 * j;
+        int vc = v < nv ? v : 0;
+        asm volatile("" : "+v"(vc));      // (kept here: they do not depend on the row, and the compiler would move them above the row's own loads)
+        gr[j] = *reinterpret_cast<const RawT*>(gamma + vc * VN);
+        if (!RMS) br[j] = *reinterpret_cast<const RawT*>(beta + vc * VN);
+      }
+    }
     float sq = 0.f;
 #pragma unroll
     for (int j = 0; j < MAXV; ++j) {
@@ -112,7 +120,8 @@ constexpr int kLnBwdRowsPerBlock = 8;
 // pair of rows, the slots alternate so that a second one is not needed.
 // SUMS: the block's column sums of `out` go to part_s as well (the bias gradient of a projection that writes into the
 // residual stream is the column sum of the stream's gradient, which is this kernel's result).
-template <typename T, int MV, bool RMS, bool SUMS>
+// RESID: there is a residual to add (otherwise `resid` is not read).
+template <typename T, int MV, bool RMS, bool SUMS, bool RESID>
 __global__ void __launch_bounds__(kThreads)
 ln_bwd_kernel(const float* __restrict__ du, const float* __restrict__ x, const float* __restrict__ mean,
               const float* __restrict__ rstd, const T* __restrict__ gamma, const float* __restrict__ resid,
@@ -161,14 +170,15 @@ ln_bwd_kernel(const float* __restrict__ du, const float* __restrict__ x, const f
         const int64_t o = (int64_t)min(row, rows - 1) * H + (v < nv ? v : 0) * VN;
         load_f32<VN>(du + o, b.d[r][j]);
         load_f32<VN>(x + o, b.xv[r][j]);
-        load_f32<VN>((resid ? resid : x) + o, b.rr[r][j]);
-        const bool keep = ok && resid != nullptr;
+        if (RESID) {
+          load_f32<VN>(resid + o, b.rr[r][j]);
+        } else {
 #pragma unroll
-        for (int i = 0; i < VN; ++i) {
-          b.d[r][j][i] = ok ? b.d[r][j][i] : 0.f;
-          b.xv[r][j][i] = ok ? b.xv[r][j][i] : 0.f;
-          b.rr[r][j][i] = keep ? b.rr[r][j][i] : 0.f;
+          for (int i = 0; i < VN; ++i) b.rr[r][j][i] = 0.f;
         }
+        // a zero gradient is all it takes: every sum below has it as a factor, and the result of such a group is not stored
+#pragma unroll
+        for (int i = 0; i < VN; ++i) b.d[r][j][i] = ok ? b.d[r][j][i] : 0.f;
       }
     }
   };
@@ -383,17 +393,20 @@ int launch_ln_bwd(const float* du, const float* x, const float* mean, const floa
   const int nv = H / Vec<T>::N;
   int mv = 1;
   while (mv * kThreads < nv) mv *= 2;          // 16-byte column groups per thread
+#define LN_BWD_FORMS(MV, RESID)                                                                                      \
+    { if (rms) ln_bwd_kernel<T, MV, true, false, RESID><<<nblocks, kThreads, 0, s>>>(du, x, mean, rstd, gamma, resid, out, out_lowp, part_g, part_b, nullptr, rows, H); \
+      else if (part_s) ln_bwd_kernel<T, MV, false, true, RESID><<<nblocks, kThreads, 0, s>>>(du, x, mean, rstd, gamma, resid, out, out_lowp, part_g, part_b, part_s, rows, H); \
+      else ln_bwd_kernel<T, MV, false, false, RESID><<<nblocks, kThreads, 0, s>>>(du, x, mean, rstd, gamma, resid, out, out_lowp, part_g, part_b, nullptr, rows, H); }
 #define LN_BWD_CASE(MV)                                                                                               \
   case MV:                                                                                                            \
-    if (rms) ln_bwd_kernel<T, MV, true, false><<<nblocks, kThreads, 0, s>>>(du, x, mean, rstd, gamma, resid, out, out_lowp, part_g, part_b, nullptr, rows, H); \
-    else if (part_s) ln_bwd_kernel<T, MV, false, true><<<nblocks, kThreads, 0, s>>>(du, x, mean, rstd, gamma, resid, out, out_lowp, part_g, part_b, part_s, rows, H); \
-    else ln_bwd_kernel<T, MV, false, false><<<nblocks, kThreads, 0, s>>>(du, x, mean, rstd, gamma, resid, out, out_lowp, part_g, part_b, nullptr, rows, H); \
+    if (resid) LN_BWD_FORMS(MV, true) else LN_BWD_FORMS(MV, false)                                                    \
     break;
   switch (mv) {
     LN_BWD_CASE(1) LN_BWD_CASE(2) LN_BWD_CASE(4)
     default: return fail(CEPHALO_EUNSUPPORTED, "layer norm: hidden width %d too large", H);
   }
 #undef LN_BWD_CASE
+#undef LN_BWD_FORMS
   CEPHALO_CHECK_LAUNCH("ln_bwd");
   return CEPHALO_OK;
 }
